@@ -1,0 +1,414 @@
+/*
+ * CPU oracle for the sparse graph-attention layer over an And-Inverter Graph.
+ *
+ * TEST INFRASTRUCTURE ONLY. This file is the slow, plain, double-precision
+ * statement of what the layer computes. Only the tests, the smoke check and
+ * the benchmark's cpu_baseline leg may call it; the GPU library shares no
+ * code with it and never falls back to it.
+ *
+ * What follows the paper, and where:
+ *   - logic level                      : Section 3.2, Eq. 1
+ *   - cone_k(v) and its size bound     : Section 3.2 (partial order <=_k)
+ *   - attention restricted to cone_k(v), realised as virtual edges
+ *                                      : Section 3.5 "GAT-based Sparse Attention"
+ *   - level-ordered sweep, every gate computed once, earlier gates frozen and
+ *     read from the historical store   : Section 3.4, Algorithm 2, Fig. 2
+ *   - a row with a single source has alpha = 1 : Section 3.7
+ *
+ * Readings taken where the paper is silent (it prints no attention formula
+ * and the block diagram is a figure):
+ *   R1  in-degree 0, 1 or 2 accepted; a duplicated (src,dst) pair, a self loop
+ *       or an id out of range is an error.
+ *   R2  the sweep schedule is Eq. 1 unless the caller supplies a levelling
+ *       that is checked to be topological (PI = 0, every edge goes upward).
+ *   R3  nodes inside a level are ordered by ascending id.
+ *   R4  a neighbour row is stored by ascending id, the node itself included.
+ *   R5  inverter flags enter as an additive per-head logit bias indexed by a
+ *       relation code: 0 self, 1 direct fanin, 2 direct inverted fanin,
+ *       3 virtual edge (shortest path of 2 or more hops). The shortest hop wins.
+ *   R6  LEVEL-MAJOR nesting for several layers: a node runs through all layers
+ *       before the next level starts; in every layer its sources are read at
+ *       their FINAL embedding H_u, the node itself at its running state.
+ *   R7  the block is attention + output projection + residual + LayerNorm
+ *       without affine parameters (biased variance, eps inside the root);
+ *       epilogue=0 returns the bare projection instead.
+ *   R8  scores are scaled dot products <q,k>/sqrt(d_head).
+ *   R9  softmax subtracts the row maximum; natural exponential.
+ *   R10 no projection biases.
+ *   R12 arithmetic is double throughout; the only rounding is of H when it is
+ *       stored (to float or to bfloat16), because the storage format of the
+ *       historical embeddings is part of the problem.
+ *
+ * Parity pins live in tests/ (brute-force dense masked attention, closed
+ * forms, hand-worked graphs, invariances). The numeric values of embeddings
+ * are NOT pinned by the paper, which prints none: "parity unpinned" by the
+ * paper, pinned by mathematics only.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { ORC_OK = 0, ORC_EINVAL = -1, ORC_ERANGE = -2, ORC_EFANIN = -3, ORC_ECYCLE = -4,
+       ORC_EHINT = -5, ORC_ENOMEM = -6 };
+
+enum { ORC_STORE_F64 = 0, ORC_STORE_F32 = 1, ORC_STORE_BF16 = 2 };
+
+/* ------------------------------------------------------------------ graph */
+
+/* R1: validate the edge list. */
+int orc_validate(int64_t n, int64_t e, const int32_t* src, const int32_t* dst, const uint8_t* inv)
+{
+    if (n < 0 || e < 0 || (e > 0 && (!src || !dst || !inv))) return ORC_EINVAL;
+    int32_t* first = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    uint8_t* deg = (uint8_t*)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!first || !deg) { free(first); free(deg); return ORC_ENOMEM; }
+    int rc = ORC_OK;
+    for (int64_t i = 0; i < e && rc == ORC_OK; ++i) {
+        int64_t u = src[i], v = dst[i];
+        if (u < 0 || u >= n || v < 0 || v >= n) { rc = ORC_ERANGE; break; }
+        if (inv[i] > 1) { rc = ORC_EINVAL; break; }
+        if (u == v) { rc = ORC_ECYCLE; break; }
+        if (deg[v] == 2) { rc = ORC_EFANIN; break; }
+        if (deg[v] == 1 && first[v] == u) { rc = ORC_EFANIN; break; }
+        if (deg[v] == 0) first[v] = (int32_t)u;
+        ++deg[v];
+    }
+    free(first); free(deg);
+    return rc;
+}
+
+/* Eq. 1 by Kahn's algorithm: a node is finished once all its fanins are. */
+int orc_levels(int64_t n, int64_t e, const int32_t* src, const int32_t* dst, int32_t* level)
+{
+    int64_t* out_ptr = (int64_t*)calloc((size_t)n + 2, sizeof(int64_t));
+    int32_t* out_dst = (int32_t*)malloc(sizeof(int32_t) * (size_t)(e > 0 ? e : 1));
+    int32_t* pending = (int32_t*)calloc((size_t)(n > 0 ? n : 1), sizeof(int32_t));
+    int32_t* queue = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n > 0 ? n : 1));
+    if (!out_ptr || !out_dst || !pending || !queue) {
+        free(out_ptr); free(out_dst); free(pending); free(queue); return ORC_ENOMEM;
+    }
+    for (int64_t i = 0; i < e; ++i) { ++out_ptr[src[i] + 2]; ++pending[dst[i]]; }
+    for (int64_t v = 0; v < n; ++v) out_ptr[v + 2] += out_ptr[v + 1];
+    for (int64_t i = 0; i < e; ++i) out_dst[out_ptr[src[i] + 1]++] = dst[i];
+    /* now out edges of u are out_dst[out_ptr[u] .. out_ptr[u+1]) */
+    int64_t head = 0, tail = 0;
+    for (int64_t v = 0; v < n; ++v) { level[v] = 0; if (pending[v] == 0) queue[tail++] = (int32_t)v; }
+    while (head < tail) {
+        int32_t u = queue[head++];
+        for (int64_t i = out_ptr[u]; i < out_ptr[u + 1]; ++i) {
+            int32_t w = out_dst[i];
+            if (level[u] + 1 > level[w]) level[w] = level[u] + 1;
+            if (--pending[w] == 0) queue[tail++] = w;
+        }
+    }
+    free(out_ptr); free(out_dst); free(pending); free(queue);
+    return tail == n ? ORC_OK : ORC_ECYCLE;
+}
+
+/* R2: a caller-supplied levelling must be topological. */
+int orc_check_hint(int64_t n, int64_t e, const int32_t* src, const int32_t* dst, const int32_t* hint)
+{
+    uint8_t* has_fanin = (uint8_t*)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!has_fanin) return ORC_ENOMEM;
+    int rc = ORC_OK;
+    for (int64_t i = 0; i < e; ++i) {
+        has_fanin[dst[i]] = 1;
+        if (hint[dst[i]] <= hint[src[i]]) rc = ORC_EHINT;
+    }
+    for (int64_t v = 0; v < n; ++v) {
+        if (hint[v] < 0) rc = ORC_EHINT;
+        if (!has_fanin[v] && hint[v] != 0) rc = ORC_EHINT;
+    }
+    free(has_fanin);
+    return rc;
+}
+
+/* R3: order = ids sorted by (level, id); level_ptr[l] = first position of level l,
+ * l = 0..max_level+1 (so max_level+2 entries). */
+void orc_order(int64_t n, const int32_t* level, int32_t max_level, int32_t* order, int64_t* level_ptr)
+{
+    for (int32_t l = 0; l <= max_level + 1; ++l) level_ptr[l] = 0;
+    for (int64_t v = 0; v < n; ++v) ++level_ptr[level[v] + 1];
+    for (int32_t l = 0; l <= max_level; ++l) level_ptr[l + 1] += level_ptr[l];
+    int64_t* cursor = (int64_t*)malloc(sizeof(int64_t) * ((size_t)max_level + 2));
+    memcpy(cursor, level_ptr, sizeof(int64_t) * ((size_t)max_level + 2));
+    for (int64_t v = 0; v < n; ++v) order[cursor[level[v]]++] = (int32_t)v;
+    free(cursor);
+}
+
+/*
+ * cone_k(v): all u with a path u -> v of at most `hops` edges, v included
+ * (Section 3.2). Breadth-first search backwards over fanin edges; the first
+ * time a node is reached fixes its shortest hop, hence its relation code (R5).
+ * nbr_idx / nbr_rel may be NULL to only count. Returns NNZ (or < 0 on error).
+ */
+int64_t orc_cone_csr(int64_t n, int64_t e, const int32_t* src, const int32_t* dst, const uint8_t* inv,
+                     int32_t hops, int64_t* nbr_ptr, int32_t* nbr_idx, uint8_t* nbr_rel)
+{
+    if (hops < 0 || hops > 8) return ORC_EINVAL;
+    /* fanin lists in edge order */
+    int32_t* fin = (int32_t*)malloc(sizeof(int32_t) * 2 * (size_t)(n > 0 ? n : 1));
+    uint8_t* finv = (uint8_t*)malloc(2 * (size_t)(n > 0 ? n : 1));
+    uint8_t* deg = (uint8_t*)calloc((size_t)(n > 0 ? n : 1), 1);
+    if (!fin || !finv || !deg) { free(fin); free(finv); free(deg); return ORC_ENOMEM; }
+    for (int64_t i = 0; i < e; ++i) {
+        int32_t v = dst[i];
+        fin[2 * (int64_t)v + deg[v]] = src[i];
+        finv[2 * (int64_t)v + deg[v]] = inv[i];
+        ++deg[v];
+    }
+    enum { CAP = 1 << 9 };                    /* 2^(8+1)-1 < CAP */
+    int32_t found[CAP]; uint8_t code[CAP]; int32_t hop[CAP];
+    int64_t nnz = 0;
+    for (int64_t v = 0; v < n; ++v) {
+        int cnt = 0;
+        found[cnt] = (int32_t)v; code[cnt] = 0; hop[cnt] = 0; ++cnt;
+        for (int head = 0; head < cnt; ++head) {          /* found[] doubles as the BFS queue */
+            if (hop[head] == hops) continue;
+            int32_t w = found[head];
+            for (int k = 0; k < deg[w]; ++k) {
+                int32_t u = fin[2 * (int64_t)w + k];
+                int seen = 0;
+                for (int j = 0; j < cnt; ++j) if (found[j] == u) { seen = 1; break; }
+                if (seen) continue;
+                found[cnt] = u; hop[cnt] = hop[head] + 1;
+                code[cnt] = hop[cnt] == 1 ? (uint8_t)(1 + finv[2 * (int64_t)w + k]) : 3;
+                ++cnt;
+            }
+        }
+        nbr_ptr[v] = nnz;
+        if (nbr_idx) {
+            /* R4: ascending id (insertion sort of a tiny row) */
+            for (int i = 1; i < cnt; ++i) {
+                int32_t fi = found[i]; uint8_t ci = code[i]; int j = i - 1;
+                while (j >= 0 && found[j] > fi) { found[j + 1] = found[j]; code[j + 1] = code[j]; --j; }
+                found[j + 1] = fi; code[j + 1] = ci;
+            }
+            for (int i = 0; i < cnt; ++i) { nbr_idx[nnz + i] = found[i]; nbr_rel[nnz + i] = code[i]; }
+        }
+        nnz += cnt;
+    }
+    nbr_ptr[n] = nnz;
+    free(fin); free(finv); free(deg);
+    return nnz;
+}
+
+/* ------------------------------------------------------------- arithmetic */
+
+/* nearest bfloat16 (8 significant bits), ties to even, straight from double. */
+static double round_bf16(double x)
+{
+    if (x == 0.0 || !isfinite(x)) return x;
+    int ex;
+    double m = frexp(x, &ex);                 /* |m| in [0.5, 1) */
+    return ldexp(rint(ldexp(m, 8)), ex - 8);  /* rint: current mode = nearest even */
+}
+
+static double round_store(double x, int store)
+{
+    if (store == ORC_STORE_BF16) return round_bf16(x);
+    if (store == ORC_STORE_F32) return (double)(float)x;
+    return x;
+}
+
+/* y[j] = sum_i s[i] * W[i, col0 + j], W row-major with `ld` columns. */
+static void vec_mat(const double* s, int d, const float* W, int ld, int col0, int ncols, double* y)
+{
+    for (int j = 0; j < ncols; ++j) {
+        double acc = 0.0;
+        for (int i = 0; i < d; ++i) acc += s[i] * (double)W[(int64_t)i * ld + col0 + j];
+        y[j] = acc;
+    }
+}
+
+/* Q = S Wq, K = S Wk, V = S Wv with W = [Wq | Wk | Wv] of shape [d, 3d]. */
+void orc_qkv_proj(int64_t rows, int32_t d, const float* S, const float* W, double* Q, double* K, double* V)
+{
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double s[1024];
+        for (int i = 0; i < d; ++i) s[i] = (double)S[r * d + i];
+        vec_mat(s, d, W, 3 * d, 0, d, Q + r * d);
+        vec_mat(s, d, W, 3 * d, d, d, K + r * d);
+        vec_mat(s, d, W, 3 * d, 2 * d, d, V + r * d);
+    }
+}
+
+/*
+ * scores, softmax and aggregation of one destination (R5, R8, R9).
+ * q[d]; k, v: cnt rows of d; rel[cnt]; bias[heads*4]. a[d] out.
+ * alpha (nullable): cnt*heads, alpha[j*heads + h].
+ */
+static void attend(int d, int heads, int cnt, const double* q, const double* k, const double* v,
+                   const uint8_t* rel, const float* bias, double* a, double* alpha)
+{
+    const int dh = d / heads;
+    const double scale = 1.0 / sqrt((double)dh);
+    double sc[1 << 9];
+    for (int h = 0; h < heads; ++h) {
+        double mx = -INFINITY;
+        for (int j = 0; j < cnt; ++j) {
+            double dot = 0.0;
+            for (int c = 0; c < dh; ++c) dot += q[h * dh + c] * k[(int64_t)j * d + h * dh + c];
+            sc[j] = dot * scale + (double)bias[h * 4 + rel[j]];
+            if (sc[j] > mx) mx = sc[j];
+        }
+        double z = 0.0;
+        for (int j = 0; j < cnt; ++j) { sc[j] = exp(sc[j] - mx); z += sc[j]; }
+        for (int c = 0; c < dh; ++c) a[h * dh + c] = 0.0;
+        for (int j = 0; j < cnt; ++j) {
+            double al = sc[j] / z;
+            if (alpha) alpha[j * heads + h] = al;
+            for (int c = 0; c < dh; ++c) a[h * dh + c] += al * v[(int64_t)j * d + h * dh + c];
+        }
+    }
+}
+
+/* Kernel-level oracle: attention on given Q, K, V (rows indexed by node id). */
+void orc_sparse_attn(int64_t n, int32_t d, int32_t heads, int64_t row_begin, int64_t row_end,
+                     const float* Q, const float* K, const float* V, const float* bias,
+                     const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
+                     double* A /* [n,d], rows outside the range untouched */,
+                     double* alpha /* nullable [nnz, heads] */)
+{
+    (void)n;
+#pragma omp parallel for schedule(dynamic, 64)
+    for (int64_t r = row_begin; r < row_end; ++r) {
+        int cnt = (int)(nbr_ptr[r + 1] - nbr_ptr[r]);
+        double* q = (double*)malloc(sizeof(double) * (size_t)d * (2 * (size_t)cnt + 1));
+        double* k = q + d; double* v = k + (size_t)cnt * d;
+        for (int i = 0; i < d; ++i) q[i] = (double)Q[r * d + i];
+        for (int j = 0; j < cnt; ++j) {
+            int64_t u = nbr_idx[nbr_ptr[r] + j];
+            for (int i = 0; i < d; ++i) { k[(int64_t)j * d + i] = (double)K[u * d + i]; v[(int64_t)j * d + i] = (double)V[u * d + i]; }
+        }
+        attend(d, heads, cnt, q, k, v, nbr_rel + nbr_ptr[r], bias, A + r * d,
+               alpha ? alpha + nbr_ptr[r] * heads : NULL);
+        free(q);
+    }
+}
+
+typedef struct {
+    int32_t d, heads, n_layers, store, epilogue;
+    double ln_eps;
+    const float* x;         /* [n, d] */
+    const float* wqkv;      /* [n_layers, d, 3d] */
+    const float* wo;        /* [n_layers, d, d] */
+    const float* bias;      /* [n_layers, heads, 4] */
+    const int64_t* nbr_ptr; const int32_t* nbr_idx; const uint8_t* nbr_rel;
+} orc_layer;
+
+/*
+ * All layers of one node v (R6, R7). Source states come from Hd (double rows)
+ * if non-NULL, else from Hf (float rows). kv_memo (nullable): per layer and
+ * node the already projected [K | V] row of the node's final embedding; it is
+ * a pure function of H_u, so using it changes no value.
+ */
+static void node_step(const orc_layer* L, int64_t v, const double* Hd, const float* Hf,
+                      const double* kv_memo, int64_t n, double* out)
+{
+    const int d = L->d;
+    const int64_t p0 = L->nbr_ptr[v];
+    const int cnt = (int)(L->nbr_ptr[v + 1] - p0);
+    double* buf = (double*)malloc(sizeof(double) * (size_t)d * (2 * (size_t)cnt + 5));
+    double *s = buf, *q = s + d, *a = q + d, *o = a + d, *src = o + d;
+    double *k = src + d, *vv = k + (size_t)cnt * d;
+    for (int i = 0; i < d; ++i) s[i] = (double)L->x[v * d + i];
+    for (int l = 0; l < L->n_layers; ++l) {
+        const float* W = L->wqkv + (int64_t)l * d * 3 * d;
+        vec_mat(s, d, W, 3 * d, 0, d, q);
+        for (int j = 0; j < cnt; ++j) {
+            int64_t u = L->nbr_idx[p0 + j];
+            if (u == v) {
+                vec_mat(s, d, W, 3 * d, d, d, k + (int64_t)j * d);
+                vec_mat(s, d, W, 3 * d, 2 * d, d, vv + (int64_t)j * d);
+            } else if (kv_memo) {
+                const double* m = kv_memo + ((int64_t)l * n + u) * 2 * d;
+                memcpy(k + (int64_t)j * d, m, sizeof(double) * d);
+                memcpy(vv + (int64_t)j * d, m + d, sizeof(double) * d);
+            } else {
+                for (int i = 0; i < d; ++i) src[i] = Hd ? Hd[u * d + i] : (double)Hf[u * d + i];
+                vec_mat(src, d, W, 3 * d, d, d, k + (int64_t)j * d);
+                vec_mat(src, d, W, 3 * d, 2 * d, d, vv + (int64_t)j * d);
+            }
+        }
+        attend(d, L->heads, cnt, q, k, vv, L->nbr_rel + p0, L->bias + (int64_t)l * L->heads * 4, a, NULL);
+        vec_mat(a, d, L->wo + (int64_t)l * d * d, d, 0, d, o);
+        if (L->epilogue) {
+            double mean = 0.0, var = 0.0;
+            for (int i = 0; i < d; ++i) { o[i] += s[i]; mean += o[i]; }
+            mean /= d;
+            for (int i = 0; i < d; ++i) var += (o[i] - mean) * (o[i] - mean);
+            var /= d;
+            double r = 1.0 / sqrt(var + L->ln_eps);
+            for (int i = 0; i < d; ++i) s[i] = (o[i] - mean) * r;
+        } else {
+            for (int i = 0; i < d; ++i) s[i] = o[i];
+        }
+    }
+    for (int i = 0; i < d; ++i) out[i] = round_store(s[i], L->store);
+    free(buf);
+}
+
+/*
+ * The level sweep (Algorithm 2 with every level a root level): levels in
+ * [level_begin, level_end) ascending; inside a level nodes are independent.
+ * H must already hold the embeddings of all levels < level_begin.
+ * memo != 0 caches the projected K/V of finished nodes (same values, less work).
+ */
+int orc_layer_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32_t store,
+                  int32_t epilogue, double ln_eps, int32_t memo,
+                  const float* x, const float* wqkv, const float* wo, const float* bias,
+                  const int32_t* order, const int64_t* level_ptr, int32_t level_begin, int32_t level_end,
+                  const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
+                  double* H)
+{
+    if (d <= 0 || d > 1024 || heads <= 0 || d % heads || n_layers <= 0) return ORC_EINVAL;
+    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, nbr_ptr, nbr_idx, nbr_rel };
+    double* kv = NULL;
+    if (memo) {
+        kv = (double*)malloc(sizeof(double) * (size_t)n_layers * (size_t)n * 2 * (size_t)d);
+        if (!kv) return ORC_ENOMEM;
+        /* nodes finished before level_begin */
+#pragma omp parallel for schedule(static)
+        for (int64_t p = 0; p < level_ptr[level_begin]; ++p) {
+            int64_t u = order[p];
+            for (int l = 0; l < n_layers; ++l)
+                vec_mat(H + u * d, d, wqkv + (int64_t)l * d * 3 * d, 3 * d, d, 2 * d,
+                        kv + ((int64_t)l * n + u) * 2 * d);
+        }
+    }
+    for (int32_t lev = level_begin; lev < level_end; ++lev) {
+#pragma omp parallel for schedule(dynamic, 16)
+        for (int64_t p = level_ptr[lev]; p < level_ptr[lev + 1]; ++p) {
+            int64_t v = order[p];
+            node_step(&L, v, H, NULL, kv, n, H + v * d);
+            if (kv)
+                for (int l = 0; l < n_layers; ++l)
+                    vec_mat(H + v * d, d, wqkv + (int64_t)l * d * 3 * d, 3 * d, d, 2 * d,
+                            kv + ((int64_t)l * n + v) * 2 * d);
+        }
+    }
+    free(kv);
+    return ORC_OK;
+}
+
+/*
+ * One step for listed nodes with the sources' final embeddings GIVEN (Hsrc,
+ * float rows by node id): the single-node definition, used to check sampled
+ * outputs of a large run and for teacher-forced comparison.
+ */
+int orc_layer_nodes(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32_t store,
+                    int32_t epilogue, double ln_eps,
+                    const float* x, const float* wqkv, const float* wo, const float* bias,
+                    const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
+                    const float* Hsrc, const int64_t* nodes, int64_t n_listed, double* out /* [n_listed, d] */)
+{
+    if (d <= 0 || d > 1024 || heads <= 0 || d % heads || n_layers <= 0) return ORC_EINVAL;
+    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, nbr_ptr, nbr_idx, nbr_rel };
+#pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t i = 0; i < n_listed; ++i)
+        node_step(&L, nodes[i], NULL, Hsrc, NULL, n, out + i * d);
+    return ORC_OK;
+}
