@@ -1,0 +1,157 @@
+#!/usr/bin/env python3
+"""Benchmark of the level sweep (dg4_layer_fwd) on one MI355X.
+
+One step = one pass of the whole hot path over the 1M-gate "large" synthetic
+AIG: projections, per-edge scores, segmented softmax, aggregation, output
+projection + LayerNorm, swept level by level (about 1000 levels). Inputs are
+resident in HBM before the timed region; graph analysis (host) and uploads are
+reported separately and excluded. Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0
+
+
+def algorithmic_bytes(g, cfg, levels=None):
+    """Bytes the method has to move for one sweep (per-gate figures of the design notes).
+
+    Per gate and layer: read the state row R, write the new state row R, write the gate's K and V
+    rows 2R, read its packed neighbour row. Per level and layer: read the K and V rows of the
+    DISTINCT sources of the level once (compulsory traffic), 2R each. `gathered` counts every
+    neighbour entry instead (what a cache-less gather moves).
+    """
+    es = 4 if cfg.dtype == "f32" else 2
+    R = cfg.hidden * es
+    level = g.array("level")
+    ptr, idx = g.array("nbr_ptr"), g.array("nbr_idx")
+    n = g.n
+    dst = np.repeat(np.arange(n, dtype=np.int64), np.diff(ptr))
+    keep = idx != dst                                   # sources other than the gate itself
+    dl, src = level[dst[keep]].astype(np.int64), idx[keep].astype(np.int64)
+    if levels is not None:
+        sel = dl < levels
+        dl, src = dl[sel], src[sel]
+        n_rows = int((level < levels).sum())
+    else:
+        n_rows = n
+    distinct = len(np.unique(dl * n + src))
+    ell_row = 4 * (1 << (g.hops + 1))
+    per_gate = (R + R + 2 * R + ell_row) * cfg.n_layers
+    compulsory = n_rows * per_gate + distinct * 2 * R * cfg.n_layers
+    gathered = n_rows * per_gate + len(src) * 2 * R * cfg.n_layers
+    return compulsory, gathered
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="large", help="large (default) | medium | small | tiny | stress")
+    ap.add_argument("--n-and", type=int, default=None, help="override the number of AND gates (debug)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no sharding, no collectives); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import dg4_synth as synth
+    import paper_2502_01681_amd as dg4
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    t0 = time.perf_counter()
+    w = synth.make(args.workload, n_and=args.n_and)
+    c = w.cfg
+    t_gen = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    t_build = time.perf_counter() - t0
+    cfg = dg4.LayerConfig(c.hidden, c.heads, c.hops, c.n_layers, c.dtype)
+    td = torch.float32 if c.dtype == "f32" else torch.bfloat16
+    t0 = time.perf_counter()
+    X = torch.from_numpy(w.x).cuda().to(td).contiguous()
+    W = [(torch.from_numpy(w.wqkv[l]).cuda().to(td).contiguous(), torch.from_numpy(w.wo[l]).cuda().to(td).contiguous(),
+          torch.from_numpy(w.rel_bias[l]).cuda().contiguous()) for l in range(c.n_layers)]
+    g.upload()
+    torch.cuda.synchronize()
+    t_upload = time.perf_counter() - t0
+    H = torch.empty_like(X)
+    ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+
+    for _ in range(args.warmup):
+        dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
+    torch.cuda.synchronize()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for a, b in ev:
+        a.record()
+        dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
+        b.record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    ms_dev = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+    n_gates, nnz = g.n, g.nnz
+    layers = c.n_layers
+    compulsory, gathered = algorithmic_bytes(g, cfg)
+    achieved = compulsory / (ms_dev * 1e-3) / 1e9
+    out = {
+        "metric": "edges/sec per sparse-attn layer fwd (level sweep)",
+        "value": nnz * layers / (ms_step * 1e-3),
+        "unit": "edges/s",
+        "gates_per_s": n_gates * layers / (ms_step * 1e-3),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_step, "ms_per_layer": ms_step / layers,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": c.dtype, "data": "synthetic",
+        "config": {"workload": f"{c.name}: {c.n_pi} PIs + {c.n_and} ANDs, {g.n_levels} levels, "
+                               f"{c.hops}-hop cones, hidden {c.hidden}, {c.heads} heads, {layers} layer(s)",
+                   "gates": n_gates, "neighbour_edges": nnz, "aig_edges": int(len(w.edge_src)),
+                   "levels": g.n_levels},
+        "roofline": {"bound": "hbm", "kernel": "dg4_layer_fwd level sweep (all launches of one step)",
+                     "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "algorithmic_bytes": compulsory, "gathered_bytes": gathered, "ms_device": ms_dev},
+        "setup_s": {"generate": t_gen, "dg4_build_levels": t_build, "upload": t_upload},
+    }
+
+    if not args.no_cpu_baseline:
+        import oracle
+        # bounded sample: the same sweep over the lowest levels holding about --cpu-gates gates
+        lp = g.array("level_ptr")
+        lev_end = int(np.searchsorted(lp, min(args.cpu_gates, n_gates), side="left"))
+        lev_end = max(1, min(lev_end, g.n_levels))
+        og = oracle.build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+        t0 = time.perf_counter()
+        oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype, level_end=lev_end)
+        dt = time.perf_counter() - t0
+        rows = int(lp[lev_end])
+        sample_nnz = int(og.nbr_ptr[og.order[:rows] + 1].sum() - og.nbr_ptr[og.order[:rows]].sum())
+        out["cpu_baseline"] = {"value": sample_nnz * layers / dt, "unit": "edges/s",
+                               "gates_per_s": rows * layers / dt,
+                               "cores": oracle.threads(),
+                               "kind": "oracle", "seconds": dt,
+                               "sample": f"levels [0,{lev_end}) of the same graph: {rows} gates, "
+                                         f"{sample_nnz} neighbour edges, fp64, K/V of finished gates cached"}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

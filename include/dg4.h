@@ -1,0 +1,155 @@
+/*
+ * dg4 - sparse graph-attention layer over And-Inverter Graphs on AMD MI355X.
+ *
+ * C ABI of the data-parallel hot path of DeepGate4 (arXiv 2502.01681): node
+ * features plus an AIG edge list with inverter flags in, gate embeddings out.
+ *
+ * Conventions for every call
+ *   - returns 0 (DG4_OK) or a negative dg4_status; nothing throws or aborts
+ *     across the boundary; on error the outputs are left untouched unless a
+ *     device error (DG4_EHIP) struck after work had been queued.
+ *   - "host" pointers are ordinary process memory; "device" pointers are HIP
+ *     device memory of the current device, owned by the caller. The library
+ *     allocates device memory only inside a dg4_graph (its neighbour tables),
+ *     on the first device call that uses the graph or in dg4_graph_upload.
+ *   - rows of X, H, Q, K, V, A are indexed by ORIGINAL node id, row-major,
+ *     `hidden` elements each, element type cfg->dtype (float or bfloat16).
+ *   - device calls are asynchronous on `stream` (a hipStream_t, may be NULL
+ *     for the default stream) and touch no other stream.
+ *   - a dg4_graph is immutable after construction; concurrent calls may share it.
+ */
+#ifndef DG4_H
+#define DG4_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct dg4_graph dg4_graph;
+
+typedef enum { DG4_F32 = 0, DG4_BF16 = 1 } dg4_dtype;
+
+typedef enum {
+    DG4_OK = 0,
+    DG4_EINVAL = -1,        /* null pointer, negative size, bad flag or bad config field   */
+    DG4_ERANGE = -2,        /* node id outside [0, n_nodes)                                */
+    DG4_EFANIN = -3,        /* in-degree above 2, or the same (src,dst) pair twice         */
+    DG4_ECYCLE = -4,        /* the edge list is not a DAG (self loops included)            */
+    DG4_EHINT = -5,         /* level_hint is not a topological levelling with PIs at 0     */
+    DG4_EUNSUPPORTED = -6,  /* head dim != 32, hidden not 128/256, hops not 1..3, layers>8 */
+    DG4_ENOMEM = -7,        /* host or device allocation failed                            */
+    DG4_EWORKSPACE = -8,    /* workspace missing, misaligned (256 B) or too small          */
+    DG4_EHIP = -9           /* a HIP runtime call failed                                   */
+} dg4_status;
+
+/* cfg->flags */
+#define DG4_NO_EPILOGUE 1u  /* H = A*Wo without residual and LayerNorm (kernel tests)      */
+
+typedef struct {
+    int32_t hidden;         /* d: 128 or 256                                               */
+    int32_t heads;          /* d / 32                                                      */
+    int32_t hops;           /* k of cone_k, must equal the graph's                         */
+    int32_t n_layers;       /* 1..8 stacked layers (dg4_layer_fwd only)                    */
+    int32_t dtype;          /* dg4_dtype of X, H, Q, K, V, A and of the weight matrices    */
+    uint32_t flags;
+    float ln_eps;           /* LayerNorm epsilon, e.g. 1e-5                                */
+} dg4_layer_cfg;
+
+/*
+ * Graph analysis (paper Section 3.2). HOST call, host pointers.
+ *   - node type by in-degree: 0 primary input, 2 AND, 1 NOT/buffer; ids need
+ *     not be topological. edge_inv[e] in {0,1} marks an inverted fanin edge.
+ *   - level(v) by Eq. 1; or, if level_hint (n_nodes entries) is given, the hint
+ *     after checking hint[PI] == 0 and hint[dst] > hint[src] for every edge. The
+ *     level only fixes the sweep schedule; embeddings do not depend on it.
+ *   - order: node ids sorted by (level, id).
+ *   - neighbour rows N(v) = cone_hops(v), v included, at most 2^(hops+1)-1
+ *     entries, ascending id, each with a relation code: 0 self, 1 direct fanin,
+ *     2 direct inverted fanin, 3 ancestor first reached by >= 2 edges (the
+ *     virtual edges of Section 3.5). The shortest path decides the code.
+ * On success *out owns host copies of all tables; free with dg4_graph_free.
+ * Errors: EINVAL, ERANGE, EFANIN, ECYCLE, EHINT, EUNSUPPORTED (hops), ENOMEM.
+ */
+int dg4_build_levels(int64_t n_nodes, int64_t n_edges,
+                     const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,
+                     int32_t hops, const int32_t* level_hint /* nullable */,
+                     dg4_graph** out);
+
+/* Tables of a graph, borrowed host pointers valid until dg4_graph_free. */
+typedef enum {
+    DG4_LEVEL = 0,      /* int32  [n_nodes]                                    */
+    DG4_ORDER = 1,      /* int32  [n_nodes]      ids by (level, id)            */
+    DG4_LEVEL_PTR = 2,  /* int64  [n_levels + 1] first position of each level  */
+    DG4_NBR_PTR = 3,    /* int64  [n_nodes + 1]                                */
+    DG4_NBR_IDX = 4,    /* int32  [nnz]                                        */
+    DG4_NBR_REL = 5     /* uint8  [nnz]                                        */
+} dg4_array;
+
+int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count);
+int dg4_graph_info(const dg4_graph* g, int64_t* n_nodes, int64_t* n_levels, int64_t* nnz, int32_t* hops);
+
+/* Copy the neighbour tables to the current device now (otherwise done lazily
+ * by the first device call). EHIP / ENOMEM on failure. */
+int dg4_graph_upload(dg4_graph* g);
+void dg4_graph_free(dg4_graph* g);
+
+/*
+ * Bytes of device workspace the calls below need (256-byte aligned buffers).
+ * dg4_layer_workspace_bytes covers dg4_layer_fwd: packed weights, the
+ * projected self rows, the per-layer K/V store of finished gates and the
+ * level-sorted copy of H. Negative dg4_status on a bad configuration.
+ */
+int64_t dg4_proj_workspace_bytes(const dg4_layer_cfg* cfg);
+int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4_graph* g);
+
+/*
+ * Q = S Wq, K = S Wk, V = S Wv for rows [row_begin, row_end) of S (the
+ * projection at the head of the attention block, Section 3.5; no biases).
+ *   S [n, hidden] device; Wqkv [hidden, 3*hidden] device, row-major, columns
+ *   Wq | Wk | Wv, same dtype; Q, K, V [n, hidden] device (rows outside the
+ *   range untouched). bf16: bf16 inputs, fp32 accumulation, bf16 outputs.
+ */
+int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                 const void* Wqkv, void* Q, void* K, void* V,
+                 void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
+ * Attention restricted to the cone (Section 3.5), for destination rows
+ * [row_begin, row_end): for each head h of 32 features
+ *   s[u]   = <Q[v,h], K[u,h]> / sqrt(32) + rel_bias[h][rel(v,u)],  u in N(v)
+ *   alpha  = softmax_u s[u]          (fp32; a single-source row has alpha = 1, Section 3.7)
+ *   A[v,h] = sum_u alpha[u] V[u,h]
+ * scores and alpha live in registers only. rel_bias: device float [heads, 4].
+ */
+int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begin, int64_t row_end,
+                        const void* Q, const void* K, const void* V, const float* rel_bias,
+                        void* A, void* stream);
+
+/*
+ * The level sweep of the updating strategy (Section 3.4, Algorithm 2 with
+ * every level a root level): for levels [level_begin, level_end) ascending,
+ * every gate of the level is computed exactly once; its cone sources are read
+ * at their FINAL embedding H (the historical embeddings of Fig. 2), the gate
+ * itself at its running state. Per gate, for layer l = 0..n_layers-1 (all
+ * layers of a gate before the next level):
+ *   s_0 = X[v];  q, k_self, v_self = s_l Wqkv_l;  k_u, v_u = H[u] Wk_l, H[u] Wv_l
+ *   a = attention as in dg4_sparse_attn_fwd;  s_{l+1} = LayerNorm(s_l + a Wo_l)
+ * (no affine, biased variance) and H[v] = s_{n_layers}, stored in cfg->dtype.
+ *   X [n, hidden] device; Hout [n, hidden] device. With level_begin > 0, Hout
+ *   must already hold the rows of all lower levels (resume).
+ *   W: HOST array of 3*n_layers DEVICE pointers: Wqkv_l [hidden,3*hidden],
+ *   Wo_l [hidden,hidden] (cfg->dtype), rel_bias_l float [heads,4].
+ * The workspace contents are scratch; nothing persists between calls.
+ */
+int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const void* const* W,
+                  int32_t level_begin, int32_t level_end, void* Hout,
+                  void* workspace, int64_t workspace_bytes, void* stream);
+
+const char* dg4_strerror(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DG4_H */

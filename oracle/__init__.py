@@ -66,8 +66,15 @@ def _load():
         lib.orc_layer_nodes.restype = ctypes.c_int
         lib.orc_layer_nodes.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64,
                                         _P, _P, _P, _P, _P, _P, _P, _P, _P, _I64, _P]
+        lib.orc_threads.restype = ctypes.c_int
+        lib.orc_threads.argtypes = []
         _lib = lib
     return _lib
+
+
+def threads() -> int:
+    """Threads the oracle's per-level loops use (OpenMP)."""
+    return int(_load().orc_threads())
 
 
 def _c(a, dtype):

@@ -48,11 +48,24 @@
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
 
 enum { ORC_OK = 0, ORC_EINVAL = -1, ORC_ERANGE = -2, ORC_EFANIN = -3, ORC_ECYCLE = -4,
        ORC_EHINT = -5, ORC_ENOMEM = -6 };
 
 enum { ORC_STORE_F64 = 0, ORC_STORE_F32 = 1, ORC_STORE_BF16 = 2 };
+
+/* threads the parallel loops over the nodes of one level will use */
+int orc_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
 
 /* ------------------------------------------------------------------ graph */
 

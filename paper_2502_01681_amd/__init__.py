@@ -1,0 +1,9 @@
+"""dg4: the sparse graph-attention layer of DeepGate4 on MI355X (gfx950).
+
+Thin Python binding over the C ABI in include/dg4.h. Every step of the path
+runs in the HIP library; this package only marshals pointers. PyTorch is used
+for device memory and streams.
+"""
+from .binding import (DG4Error, Graph, LayerConfig, dg4_build_levels, dg4_layer_fwd,  # noqa: F401
+                      dg4_layer_workspace_bytes, dg4_proj_workspace_bytes, dg4_qkv_proj,
+                      dg4_sparse_attn_fwd, lib, library_path)

@@ -1,0 +1,205 @@
+"""ctypes binding of libdg4.so: argument marshalling only."""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+from . import build as _build
+
+_P = ctypes.c_void_p
+_I64 = ctypes.c_int64
+_I32 = ctypes.c_int32
+
+DG4_F32, DG4_BF16 = 0, 1
+DG4_NO_EPILOGUE = 1
+ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
+          "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8)}
+STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
+          -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP"}
+
+
+class DG4Error(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        self.name = STATUS.get(status, str(status))
+        super().__init__(f"{where}: {self.name} ({lib().dg4_strerror(status).decode()})")
+
+
+class _Cfg(ctypes.Structure):
+    _fields_ = [("hidden", _I32), ("heads", _I32), ("hops", _I32), ("n_layers", _I32),
+                ("dtype", _I32), ("flags", ctypes.c_uint32), ("ln_eps", ctypes.c_float)]
+
+
+@dataclass
+class LayerConfig:
+    hidden: int
+    heads: int
+    hops: int
+    n_layers: int = 1
+    dtype: str = "bf16"          # "f32" | "bf16"
+    epilogue: bool = True
+    ln_eps: float = 1e-5
+
+    def c(self) -> _Cfg:
+        return _Cfg(self.hidden, self.heads, self.hops, self.n_layers,
+                    DG4_F32 if self.dtype == "f32" else DG4_BF16,
+                    0 if self.epilogue else DG4_NO_EPILOGUE, self.ln_eps)
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB
+
+
+def lib():
+    """The loaded C library. Built first if absent; a failure to load is fatal by design."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_build.LIB):
+            _build.build()
+        L = ctypes.CDLL(_build.LIB)
+        L.dg4_strerror.restype = ctypes.c_char_p
+        L.dg4_strerror.argtypes = [ctypes.c_int]
+        L.dg4_build_levels.restype = ctypes.c_int
+        L.dg4_build_levels.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, ctypes.POINTER(_P)]
+        L.dg4_graph_array.restype = ctypes.c_int
+        L.dg4_graph_array.argtypes = [_P, ctypes.c_int, ctypes.POINTER(_P), ctypes.POINTER(_I64)]
+        L.dg4_graph_info.restype = ctypes.c_int
+        L.dg4_graph_info.argtypes = [_P, ctypes.POINTER(_I64), ctypes.POINTER(_I64), ctypes.POINTER(_I64),
+                                     ctypes.POINTER(_I32)]
+        L.dg4_graph_upload.restype = ctypes.c_int
+        L.dg4_graph_upload.argtypes = [_P]
+        L.dg4_graph_free.restype = None
+        L.dg4_graph_free.argtypes = [_P]
+        L.dg4_proj_workspace_bytes.restype = _I64
+        L.dg4_proj_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
+        L.dg4_layer_workspace_bytes.restype = _I64
+        L.dg4_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), _P]
+        L.dg4_qkv_proj.restype = ctypes.c_int
+        L.dg4_qkv_proj.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _I64, _P]
+        L.dg4_sparse_attn_fwd.restype = ctypes.c_int
+        L.dg4_sparse_attn_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _P]
+        L.dg4_layer_fwd.restype = ctypes.c_int
+        L.dg4_layer_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(_P), _I32, _I32, _P, _P, _I64, _P]
+        _lib = L
+    return _lib
+
+
+def _check(rc: int, where: str):
+    if rc != 0:
+        raise DG4Error(int(rc), where)
+
+
+class Graph:
+    """Owner of a dg4_graph handle; tables are exposed as numpy copies."""
+
+    def __init__(self, handle: int):
+        self._h = _P(handle)
+        n, nl, nnz, hops = _I64(), _I64(), _I64(), _I32()
+        _check(lib().dg4_graph_info(self._h, n, nl, nnz, hops), "dg4_graph_info")
+        self.n, self.n_levels, self.nnz, self.hops = n.value, nl.value, nnz.value, hops.value
+
+    @property
+    def handle(self):
+        return self._h
+
+    def array(self, name: str) -> np.ndarray:
+        which, dtype = ARRAYS[name]
+        ptr, cnt = _P(), _I64()
+        _check(lib().dg4_graph_array(self._h, which, ptr, cnt), "dg4_graph_array")
+        if cnt.value == 0:
+            return np.empty(0, dtype=dtype)
+        buf = (ctypes.c_char * (cnt.value * np.dtype(dtype).itemsize)).from_address(ptr.value)
+        return np.frombuffer(buf, dtype=dtype).copy()
+
+    def upload(self):
+        _check(lib().dg4_graph_upload(self._h), "dg4_graph_upload")
+
+    def close(self):
+        if self._h:
+            lib().dg4_graph_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def dg4_build_levels(n_nodes, edge_src, edge_dst, edge_inv, hops, level_hint=None) -> Graph:
+    src = np.ascontiguousarray(edge_src, dtype=np.int32)
+    dst = np.ascontiguousarray(edge_dst, dtype=np.int32)
+    inv = np.ascontiguousarray(edge_inv, dtype=np.uint8)
+    if not (len(src) == len(dst) == len(inv)):
+        raise DG4Error(-1, "dg4_build_levels")
+    hint = None if level_hint is None else np.ascontiguousarray(level_hint, dtype=np.int32)
+    if hint is not None and len(hint) != n_nodes:
+        raise DG4Error(-1, "dg4_build_levels")
+    out = _P()
+    rc = lib().dg4_build_levels(n_nodes, len(src), src.ctypes.data, dst.ctypes.data, inv.ctypes.data, hops,
+                                hint.ctypes.data if hint is not None else None, ctypes.byref(out))
+    _check(rc, "dg4_build_levels")
+    return Graph(out.value)
+
+
+def dg4_proj_workspace_bytes(cfg: LayerConfig) -> int:
+    c = cfg.c()
+    r = lib().dg4_proj_workspace_bytes(ctypes.byref(c))
+    if r < 0:
+        raise DG4Error(int(r), "dg4_proj_workspace_bytes")
+    return int(r)
+
+
+def dg4_layer_workspace_bytes(cfg: LayerConfig, g: Graph) -> int:
+    c = cfg.c()
+    r = lib().dg4_layer_workspace_bytes(ctypes.byref(c), g.handle)
+    if r < 0:
+        raise DG4Error(int(r), "dg4_layer_workspace_bytes")
+    return int(r)
+
+
+def _stream():
+    import torch
+    return _P(torch.cuda.current_stream().cuda_stream)
+
+
+def _ws(nbytes: int, like):
+    import torch
+    return torch.empty(max(nbytes, 256), dtype=torch.uint8, device=like.device)
+
+
+def dg4_qkv_proj(cfg: LayerConfig, S, Wqkv, Q, K, V, row_begin=0, row_end=None, workspace=None):
+    """Q, K, V rows [row_begin,row_end) = S rows x [Wq | Wk | Wv] (device tensors, in place)."""
+    row_end = S.shape[0] if row_end is None else row_end
+    ws = _ws(dg4_proj_workspace_bytes(cfg), S) if workspace is None else workspace
+    c = cfg.c()
+    rc = lib().dg4_qkv_proj(ctypes.byref(c), S.data_ptr(), row_begin, row_end, Wqkv.data_ptr(),
+                            Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "dg4_qkv_proj")
+
+
+def dg4_sparse_attn_fwd(cfg: LayerConfig, g: Graph, Q, K, V, rel_bias, A, row_begin=0, row_end=None):
+    row_end = g.n if row_end is None else row_end
+    c = cfg.c()
+    rc = lib().dg4_sparse_attn_fwd(ctypes.byref(c), g.handle, row_begin, row_end, Q.data_ptr(), K.data_ptr(),
+                                   V.data_ptr(), rel_bias.data_ptr(), A.data_ptr(), _stream())
+    _check(rc, "dg4_sparse_attn_fwd")
+
+
+def dg4_layer_fwd(cfg: LayerConfig, g: Graph, X, weights, Hout, level_begin=0, level_end=None, workspace=None):
+    """weights: per layer (Wqkv, Wo, rel_bias) device tensors. Hout is written in place."""
+    level_end = g.n_levels if level_end is None else level_end
+    ws = _ws(dg4_layer_workspace_bytes(cfg, g), X) if workspace is None else workspace
+    flat = [t.data_ptr() for layer in weights for t in layer]
+    arr = (_P * len(flat))(*flat)
+    c = cfg.c()
+    rc = lib().dg4_layer_fwd(ctypes.byref(c), g.handle, X.data_ptr(), arr, level_begin, level_end,
+                             Hout.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "dg4_layer_fwd")
+    return ws

@@ -1,0 +1,262 @@
+// extern "C" entry points: argument checks, workspace layout and the host side
+// of the level sweep (paper Section 3.4, Algorithm 2). All arithmetic is in
+// the device kernels; there is no CPU fallback.
+#include <algorithm>
+#include <cstring>
+
+#include "dg4_internal.h"
+
+namespace {
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline size_t elt_size(int dtype) { return dtype == DG4_F32 ? 4 : 2; }
+
+int check_cfg(const dg4_layer_cfg* c, bool need_layers)
+{
+    if (!c) return DG4_EINVAL;
+    if (c->dtype != DG4_F32 && c->dtype != DG4_BF16) return DG4_EINVAL;
+    if (c->flags & ~(uint32_t)DG4_NO_EPILOGUE) return DG4_EINVAL;
+    if (c->hidden != 128 && c->hidden != 256) return DG4_EUNSUPPORTED;
+    if (c->heads <= 0 || c->heads * 32 != c->hidden) return DG4_EUNSUPPORTED;
+    if (c->hops < 1 || c->hops > 3) return DG4_EUNSUPPORTED;
+    if (need_layers && (c->n_layers < 1 || c->n_layers > DG4_MAX_LAYERS)) return DG4_EUNSUPPORTED;
+    if (!(c->ln_eps >= 0.f)) return DG4_EINVAL;
+    return DG4_OK;
+}
+
+// Workspace of dg4_layer_fwd, in bytes from the (256-byte aligned) base.
+struct LayerPlan {
+    size_t wqkv[DG4_MAX_LAYERS], wo[DG4_MAX_LAYERS];
+    size_t wkv_all;      // packed [d, n_layers*2d]: K|V columns of every layer
+    size_t qkv_self;     // [n, 3d]  Q | K | V of x, level-sorted rows (layer 0)
+    size_t kv;           // [n_layers, n, 2d]  K | V of the final embeddings, level-sorted
+    size_t hpos;         // [n, d]   final embeddings, level-sorted
+    size_t abuf;         // [max_level_rows, d]
+    size_t s0, s1;       // [max_level_rows, d] running state between layers
+    size_t qkv_level;    // [max_level_rows, 3d] (layers >= 1)
+    size_t total;
+    int64_t max_rows;
+};
+
+LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
+{
+    LayerPlan p{};
+    const size_t es = elt_size(c->dtype), d = (size_t)c->hidden, n = (size_t)std::max<int64_t>(g->n, 1);
+    const size_t L = (size_t)c->n_layers;
+    int64_t mr = 1;
+    for (size_t l = 0; l + 1 < g->level_ptr.size(); ++l) mr = std::max(mr, g->level_ptr[l + 1] - g->level_ptr[l]);
+    p.max_rows = mr;
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
+    for (size_t l = 0; l < L; ++l) { p.wqkv[l] = take(d * 3 * d * es); p.wo[l] = take(d * d * es); }
+    p.wkv_all = take(d * 2 * d * L * es);
+    p.qkv_self = take(n * 3 * d * es);
+    p.kv = take(L * n * 2 * d * es);
+    p.hpos = take(n * d * es);
+    p.abuf = take((size_t)mr * d * es);
+    p.s0 = take((size_t)mr * d * es);
+    p.s1 = take((size_t)mr * d * es);
+    p.qkv_level = take(L > 1 ? (size_t)mr * 3 * d * es : 0);
+    p.total = off;
+    return p;
+}
+
+#define HIPCHK(expr) do { if ((expr) != (int)hipSuccess) return DG4_EHIP; } while (0)
+
+}  // namespace
+
+extern "C" const char* dg4_strerror(int status)
+{
+    switch (status) {
+    case DG4_OK: return "ok";
+    case DG4_EINVAL: return "invalid argument";
+    case DG4_ERANGE: return "node id out of range";
+    case DG4_EFANIN: return "in-degree above 2 or duplicated fanin edge";
+    case DG4_ECYCLE: return "edge list is not a DAG";
+    case DG4_EHINT: return "level hint is not a topological levelling";
+    case DG4_EUNSUPPORTED: return "unsupported configuration";
+    case DG4_ENOMEM: return "out of memory";
+    case DG4_EWORKSPACE: return "workspace missing, misaligned or too small";
+    case DG4_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+    }
+}
+
+extern "C" int64_t dg4_proj_workspace_bytes(const dg4_layer_cfg* cfg)
+{
+    const int rc = check_cfg(cfg, false);
+    if (rc != DG4_OK) return rc;
+    return (int64_t)align256((size_t)cfg->hidden * 3 * cfg->hidden * elt_size(cfg->dtype));
+}
+
+extern "C" int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4_graph* g)
+{
+    const int rc = check_cfg(cfg, true);
+    if (rc != DG4_OK) return rc;
+    if (!g) return DG4_EINVAL;
+    if (g->hops != cfg->hops) return DG4_EINVAL;
+    return (int64_t)plan_layer(cfg, g).total;
+}
+
+extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                            const void* Wqkv, void* Q, void* K, void* V,
+                            void* workspace, int64_t workspace_bytes, void* stream)
+{
+    int rc = check_cfg(cfg, false);
+    if (rc != DG4_OK) return rc;
+    if (!S || !Wqkv || !Q || !K || !V || row_begin < 0 || row_end < row_begin) return DG4_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < dg4_proj_workspace_bytes(cfg)) return DG4_EWORKSPACE;
+    if (row_end == row_begin) return DG4_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int d = cfg->hidden;
+    HIPCHK(dg4_launch_pack_w(cfg->dtype, Wqkv, 3 * d, 0, 3 * d, d, workspace, s));
+    dg4_gemm_args a{};
+    a.a = S; a.a_stride = d;
+    a.w_packed = workspace; a.n_cols = 3 * d;
+    a.out[0] = Q; a.out[1] = K; a.out[2] = V; a.out_stride = d;
+    a.row_begin = row_begin; a.row_end = row_end;
+    HIPCHK(dg4_launch_gemm(cfg->dtype, d, a, s));
+    return DG4_OK;
+}
+
+extern "C" int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begin, int64_t row_end,
+                                   const void* Q, const void* K, const void* V, const float* rel_bias,
+                                   void* A, void* stream)
+{
+    int rc = check_cfg(cfg, false);
+    if (rc != DG4_OK) return rc;
+    if (!g || !Q || !K || !V || !rel_bias || !A) return DG4_EINVAL;
+    if (g->hops != cfg->hops || row_begin < 0 || row_end < row_begin || row_end > g->n) return DG4_EINVAL;
+    if (row_end == row_begin) return DG4_OK;
+    rc = dg4_graph_ensure_device(g);
+    if (rc != DG4_OK) return rc;
+    const int d = cfg->hidden;
+    dg4_attn_args a{};
+    a.q = Q; a.q_stride = d;
+    a.k_self = K; a.v_self = V; a.self_stride = d;
+    a.k_src = K; a.v_src = V; a.src_stride = d;
+    a.rel_bias = rel_bias;
+    a.ell = g->d_ell_id; a.ell_w = g->ell_w;
+    a.a = A; a.a_stride = d;
+    a.row_begin = row_begin; a.row_end = row_end;
+    HIPCHK(dg4_launch_attn(cfg->dtype, d, a, (hipStream_t)stream));
+    return DG4_OK;
+}
+
+extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const void* const* W,
+                             int32_t level_begin, int32_t level_end, void* Hout,
+                             void* workspace, int64_t workspace_bytes, void* stream)
+{
+    int rc = check_cfg(cfg, true);
+    if (rc != DG4_OK) return rc;
+    if (!g || !X || !W || !Hout) return DG4_EINVAL;
+    if (g->hops != cfg->hops) return DG4_EINVAL;
+    const int32_t n_levels = g->max_level + 1;
+    if (level_begin < 0 || level_end < level_begin || level_end > n_levels) return DG4_EINVAL;
+    const int L = cfg->n_layers;
+    for (int i = 0; i < 3 * L; ++i) if (!W[i]) return DG4_EINVAL;
+    const LayerPlan pl = plan_layer(cfg, g);
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (int64_t)pl.total) return DG4_EWORKSPACE;
+    if (g->n == 0 || level_begin == level_end) return DG4_OK;
+    rc = dg4_graph_ensure_device(g);
+    if (rc != DG4_OK) return rc;
+
+    hipStream_t s = (hipStream_t)stream;
+    const int d = cfg->hidden, dt = cfg->dtype;
+    const int64_t es = (int64_t)elt_size(dt);
+    const bool epi = !(cfg->flags & DG4_NO_EPILOGUE);
+    char* ws = (char*)workspace;
+    auto at = [&](size_t off) { return (void*)(ws + off); };
+    // base pointer of a per-level buffer such that row p (a position) lands at local row p - p0
+    auto local = [&](size_t off, int64_t p0, int64_t stride) { return (void*)(ws + off - p0 * stride * es); };
+
+    for (int l = 0; l < L; ++l) {
+        HIPCHK(dg4_launch_pack_w(dt, W[3 * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
+        HIPCHK(dg4_launch_pack_w(dt, W[3 * l + 1], d, 0, d, d, at(pl.wo[l]), s));
+        // K | V columns of layer l go to column tiles [l*2d/32, (l+1)*2d/32) of wkv_all
+        HIPCHK(dg4_launch_pack_w(dt, W[3 * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
+    }
+    const int64_t P0 = g->level_ptr[level_begin], P1 = g->level_ptr[level_end];
+
+    auto kv_project = [&](const void* rows, int64_t stride, const int32_t* gather, int64_t r0, int64_t r1) -> int {
+        dg4_gemm_args a{};
+        a.a = rows; a.a_stride = stride; a.a_gather = gather;
+        a.w_packed = at(pl.wkv_all); a.n_cols = 2 * d * L;
+        for (int l = 0; l < L; ++l) {
+            char* base = ws + pl.kv + (size_t)l * (size_t)g->n * 2 * d * es;
+            a.out[2 * l] = base; a.out[2 * l + 1] = base + (size_t)d * es;
+        }
+        a.out_stride = 2 * d;
+        a.row_begin = r0; a.row_end = r1;
+        return dg4_launch_gemm(dt, d, a, s);
+    };
+
+    // K/V of gates finished before this call (resume): from the caller's H
+    if (P0 > 0) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
+
+    // layer 0 projections of x for every gate of the swept levels, in one pass
+    {
+        dg4_gemm_args a{};
+        a.a = X; a.a_stride = d; a.a_gather = g->d_order;
+        a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
+        char* base = ws + pl.qkv_self;
+        a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
+        a.out_stride = 3 * d;
+        a.row_begin = P0; a.row_end = P1;
+        HIPCHK(dg4_launch_gemm(dt, d, a, s));
+    }
+
+    for (int32_t lev = level_begin; lev < level_end; ++lev) {
+        const int64_t p0 = g->level_ptr[lev], p1 = g->level_ptr[lev + 1];
+        if (p1 == p0) continue;
+        for (int l = 0; l < L; ++l) {
+            const bool last = l == L - 1;
+            dg4_attn_args t{};
+            if (l == 0) {
+                char* base = ws + pl.qkv_self;
+                t.q = base; t.k_self = base + (size_t)d * es; t.v_self = base + (size_t)2 * d * es;
+            } else {
+                char* base = (char*)local(pl.qkv_level, p0, 3 * d);
+                t.q = base; t.k_self = base + (size_t)d * es; t.v_self = base + (size_t)2 * d * es;
+            }
+            t.q_stride = 3 * d; t.self_stride = 3 * d;
+            char* kvb = ws + pl.kv + (size_t)l * (size_t)g->n * 2 * d * es;
+            t.k_src = kvb; t.v_src = kvb + (size_t)d * es; t.src_stride = 2 * d;
+            t.rel_bias = (const float*)W[3 * l + 2];
+            t.ell = g->d_ell_pos; t.ell_w = g->ell_w;
+            t.a = local(pl.abuf, p0, d); t.a_stride = d;
+            t.row_begin = p0; t.row_end = p1;
+            HIPCHK(dg4_launch_attn(dt, d, t, s));
+
+            // s_{l+1} = LN(s_l + a Wo_l); the last layer's result is H
+            dg4_gemm_args o{};
+            o.a = local(pl.abuf, p0, d); o.a_stride = d;
+            o.w_packed = at(pl.wo[l]); o.n_cols = d;
+            o.row_begin = p0; o.row_end = p1;
+            o.epilogue = epi ? 1 : 0; o.ln_eps = cfg->ln_eps;
+            if (l == 0) { o.resid = X; o.resid_stride = d; o.resid_gather = g->d_order; }
+            else { o.resid = local((l & 1) ? pl.s1 : pl.s0, p0, d); o.resid_stride = d; }
+            if (last) {
+                o.out[0] = Hout; o.out_stride = d; o.out_scatter = g->d_order;
+                o.out2 = at(pl.hpos); o.out2_stride = d;
+            } else {
+                o.out[0] = local(((l + 1) & 1) ? pl.s1 : pl.s0, p0, d); o.out_stride = d;
+            }
+            HIPCHK(dg4_launch_gemm(dt, d, o, s));
+
+            if (!last) {
+                dg4_gemm_args a{};
+                a.a = local(((l + 1) & 1) ? pl.s1 : pl.s0, p0, d); a.a_stride = d;
+                a.w_packed = at(pl.wqkv[l + 1]); a.n_cols = 3 * d;
+                char* base = (char*)local(pl.qkv_level, p0, 3 * d);
+                a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
+                a.out_stride = 3 * d;
+                a.row_begin = p0; a.row_end = p1;
+                HIPCHK(dg4_launch_gemm(dt, d, a, s));
+            }
+        }
+        // publish K/V of the level's final embeddings for every layer
+        if (lev + 1 < n_levels) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
+    }
+    return DG4_OK;
+}

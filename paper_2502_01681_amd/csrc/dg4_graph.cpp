@@ -1,0 +1,292 @@
+// Host-side graph analysis behind dg4_build_levels (paper Section 3.2):
+// validation, logic levels (Eq. 1), the (level, id) order and the cone_k
+// neighbour rows with relation codes, plus the upload of the device tables.
+#include <algorithm>
+#include <cstring>
+#include <new>
+
+#include "dg4_internal.h"
+
+namespace {
+
+struct Fanins {
+    std::vector<int32_t> src;   // [2n], -1 = absent
+    std::vector<uint8_t> inv;   // [2n]
+};
+
+int collect_fanins(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei, Fanins& f)
+{
+    f.src.assign(2 * (size_t)n, -1);
+    f.inv.assign(2 * (size_t)n, 0);
+    for (int64_t i = 0; i < e; ++i) {
+        const int64_t u = es[i], v = ed[i];
+        if (u < 0 || u >= n || v < 0 || v >= n) return DG4_ERANGE;
+        if (ei[i] > 1) return DG4_EINVAL;
+        if (u == v) return DG4_ECYCLE;
+        int32_t* slot = &f.src[2 * v];
+        if (slot[0] < 0) {
+            slot[0] = (int32_t)u; f.inv[2 * v] = ei[i];
+        } else if (slot[1] < 0) {
+            if (slot[0] == u) return DG4_EFANIN;
+            slot[1] = (int32_t)u; f.inv[2 * v + 1] = ei[i];
+        } else {
+            return DG4_EFANIN;
+        }
+    }
+    return DG4_OK;
+}
+
+// Eq. 1 as a longest-path recursion over fanins, run as an explicit-stack
+// depth-first search; a node met again while still open closes a cycle.
+int longest_path_levels(int64_t n, const Fanins& f, std::vector<int32_t>& level)
+{
+    enum : uint8_t { NEW = 0, OPEN = 1, DONE = 2 };
+    std::vector<uint8_t> state((size_t)n, NEW);
+    std::vector<int32_t> stack;
+    level.assign((size_t)n, 0);
+    for (int64_t root = 0; root < n; ++root) {
+        if (state[root] != NEW) continue;
+        stack.push_back((int32_t)root);
+        while (!stack.empty()) {
+            const int32_t v = stack.back();
+            if (state[v] == DONE) { stack.pop_back(); continue; }
+            state[v] = OPEN;
+            bool ready = true;
+            int32_t best = -1;
+            for (int k = 0; k < 2; ++k) {
+                const int32_t u = f.src[2 * (size_t)v + k];
+                if (u < 0) continue;
+                if (state[u] == DONE) { best = std::max(best, level[u]); continue; }
+                if (state[u] == OPEN) return DG4_ECYCLE;
+                stack.push_back(u);
+                ready = false;
+            }
+            if (ready) { level[v] = best + 1; state[v] = DONE; stack.pop_back(); }
+        }
+    }
+    return DG4_OK;
+}
+
+int check_hint(int64_t n, const Fanins& f, const int32_t* hint)
+{
+    for (int64_t v = 0; v < n; ++v) {
+        if (hint[v] < 0) return DG4_EHINT;
+        const bool pi = f.src[2 * v] < 0;
+        if (pi && hint[v] != 0) return DG4_EHINT;
+        for (int k = 0; k < 2; ++k) {
+            const int32_t u = f.src[2 * v + k];
+            if (u >= 0 && hint[u] >= hint[v]) return DG4_EHINT;
+        }
+    }
+    return DG4_OK;
+}
+
+// cone_j(v) = {v} U cone_{j-1}(fanin0) U cone_{j-1}(fanin1), built hop by hop
+// as sorted merges; every entry carries its smallest hop count and, for hop 1,
+// the inverter flag of the edge. Rows stay sorted by id throughout.
+struct ConeTable {
+    int width = 1;                   // slots per node
+    std::vector<int32_t> id;         // [n*width], unused slots = -1
+    std::vector<uint8_t> hop;        // smallest hop
+    std::vector<uint8_t> inv;        // inverter flag where hop == 1
+    std::vector<uint8_t> cnt;        // [n]
+};
+
+void cone_step(int64_t n, const Fanins& f, const ConeTable& prev, ConeTable& next)
+{
+    next.width = 2 * prev.width + 1;
+    next.id.assign((size_t)n * next.width, -1);
+    next.hop.assign((size_t)n * next.width, 0);
+    next.inv.assign((size_t)n * next.width, 0);
+    next.cnt.assign((size_t)n, 0);
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t* oid = &next.id[(size_t)v * next.width];
+        uint8_t* ohop = &next.hop[(size_t)v * next.width];
+        uint8_t* oinv = &next.inv[(size_t)v * next.width];
+        int cnt = 0;
+        // three sorted streams: {v}, cone(f0) with hops+1, cone(f1) with hops+1
+        const int32_t f0 = f.src[2 * v], f1 = f.src[2 * v + 1];
+        const int32_t* ida = f0 >= 0 ? &prev.id[(size_t)f0 * prev.width] : nullptr;
+        const int32_t* idb = f1 >= 0 ? &prev.id[(size_t)f1 * prev.width] : nullptr;
+        const uint8_t* ha = f0 >= 0 ? &prev.hop[(size_t)f0 * prev.width] : nullptr;
+        const uint8_t* hb = f1 >= 0 ? &prev.hop[(size_t)f1 * prev.width] : nullptr;
+        const int na = f0 >= 0 ? prev.cnt[f0] : 0, nb = f1 >= 0 ? prev.cnt[f1] : 0;
+        int ia = 0, ib = 0;
+        bool self_out = false;
+        while (ia < na || ib < nb || !self_out) {
+            int64_t best = INT64_MAX;
+            if (ia < na) best = std::min<int64_t>(best, ida[ia]);
+            if (ib < nb) best = std::min<int64_t>(best, idb[ib]);
+            if (!self_out) best = std::min<int64_t>(best, v);
+            uint8_t h = 255, iv = 0;
+            if (!self_out && best == v) { h = 0; self_out = true; }
+            if (ia < na && ida[ia] == best) {
+                const uint8_t hh = (uint8_t)(ha[ia] + 1);
+                if (hh < h) { h = hh; iv = hh == 1 ? f.inv[2 * v] : 0; }
+                ++ia;
+            }
+            if (ib < nb && idb[ib] == best) {
+                const uint8_t hh = (uint8_t)(hb[ib] + 1);
+                if (hh < h) { h = hh; iv = hh == 1 ? f.inv[2 * v + 1] : 0; }
+                ++ib;
+            }
+            oid[cnt] = (int32_t)best; ohop[cnt] = h; oinv[cnt] = iv; ++cnt;
+        }
+        next.cnt[v] = (uint8_t)cnt;
+    }
+}
+
+}  // namespace
+
+extern "C" int dg4_build_levels(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
+                                const uint8_t* ei, int32_t hops, const int32_t* level_hint,
+                                dg4_graph** out)
+{
+    if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
+    if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
+    if (n >= (int64_t)0x3FFFFFFF) return DG4_EUNSUPPORTED;     // 30-bit packed indices
+    try {
+        Fanins f;
+        int rc = collect_fanins(n, e, es, ed, ei, f);
+        if (rc != DG4_OK) return rc;
+        dg4_graph* g = new dg4_graph();
+        std::unique_ptr<dg4_graph> guard(g);
+        g->n = n; g->e = e; g->hops = hops;
+        rc = longest_path_levels(n, f, g->level);
+        if (rc != DG4_OK) return rc;
+        if (level_hint) {
+            rc = check_hint(n, f, level_hint);
+            if (rc != DG4_OK) return rc;
+            g->level.assign(level_hint, level_hint + n);
+        }
+        // (level, id) order by a counting sort
+        g->max_level = 0;
+        for (int64_t v = 0; v < n; ++v) g->max_level = std::max(g->max_level, g->level[v]);
+        g->level_ptr.assign((size_t)g->max_level + 2, 0);
+        for (int64_t v = 0; v < n; ++v) ++g->level_ptr[(size_t)g->level[v] + 1];
+        for (int32_t l = 0; l <= g->max_level; ++l) g->level_ptr[l + 1] += g->level_ptr[l];
+        g->order.resize((size_t)n);
+        g->pos.resize((size_t)n);
+        {
+            std::vector<int64_t> cur(g->level_ptr.begin(), g->level_ptr.end() - 1);
+            for (int64_t v = 0; v < n; ++v) {
+                const int64_t p = cur[g->level[v]]++;
+                g->order[p] = (int32_t)v; g->pos[v] = (int32_t)p;
+            }
+        }
+        // cones, hop by hop
+        ConeTable a, b;
+        a.width = 1;
+        a.id.resize((size_t)n); a.hop.assign((size_t)n, 0); a.inv.assign((size_t)n, 0); a.cnt.assign((size_t)n, 1);
+        for (int64_t v = 0; v < n; ++v) a.id[v] = (int32_t)v;
+        for (int h = 0; h < hops; ++h) { cone_step(n, f, a, b); std::swap(a, b); }
+        g->nbr_ptr.resize((size_t)n + 1);
+        int64_t nnz = 0;
+        for (int64_t v = 0; v < n; ++v) { g->nbr_ptr[v] = nnz; nnz += a.cnt[v]; }
+        g->nbr_ptr[n] = nnz; g->nnz = nnz;
+        g->nbr_idx.resize((size_t)nnz);
+        g->nbr_rel.resize((size_t)nnz);
+        for (int64_t v = 0; v < n; ++v) {
+            const size_t base = (size_t)v * a.width;
+            for (int j = 0; j < a.cnt[v]; ++j) {
+                const uint8_t h = a.hop[base + j];
+                g->nbr_idx[g->nbr_ptr[v] + j] = a.id[base + j];
+                g->nbr_rel[g->nbr_ptr[v] + j] = h == 0 ? 0 : h == 1 ? (uint8_t)(1 + a.inv[base + j]) : 3;
+            }
+        }
+        *out = guard.release();
+        return DG4_OK;
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    } catch (...) {
+        return DG4_EINVAL;
+    }
+}
+
+extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count)
+{
+    if (!g || !host_ptr || !count) return DG4_EINVAL;
+    switch (which) {
+    case DG4_LEVEL: *host_ptr = g->level.data(); *count = g->n; break;
+    case DG4_ORDER: *host_ptr = g->order.data(); *count = g->n; break;
+    case DG4_LEVEL_PTR: *host_ptr = g->level_ptr.data(); *count = (int64_t)g->level_ptr.size(); break;
+    case DG4_NBR_PTR: *host_ptr = g->nbr_ptr.data(); *count = g->n + 1; break;
+    case DG4_NBR_IDX: *host_ptr = g->nbr_idx.data(); *count = g->nnz; break;
+    case DG4_NBR_REL: *host_ptr = g->nbr_rel.data(); *count = g->nnz; break;
+    default: return DG4_EINVAL;
+    }
+    return DG4_OK;
+}
+
+extern "C" int dg4_graph_info(const dg4_graph* g, int64_t* n_nodes, int64_t* n_levels, int64_t* nnz, int32_t* hops)
+{
+    if (!g) return DG4_EINVAL;
+    if (n_nodes) *n_nodes = g->n;
+    if (n_levels) *n_levels = (int64_t)g->max_level + 1;
+    if (nnz) *nnz = g->nnz;
+    if (hops) *hops = g->hops;
+    return DG4_OK;
+}
+
+// Device tables: fixed-width packed rows, once by node id (for calls whose
+// tensors are indexed by id) and once by position in the (level, id) order
+// (for the sweep, whose internal buffers are level sorted).
+int dg4_graph_ensure_device(dg4_graph* g)
+{
+    std::lock_guard<std::mutex> lock(g->mu);
+    if (g->on_device) return DG4_OK;
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return DG4_EHIP;
+    const int w = 1 << (g->hops + 1);
+    const size_t rows = (size_t)std::max<int64_t>(g->n, 1);
+    try {
+        std::vector<uint32_t> by_id(rows * w, DG4_ELL_PAD), by_pos(rows * w, DG4_ELL_PAD);
+        for (int64_t v = 0; v < g->n; ++v) {
+            const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
+            uint32_t* rid = &by_id[(size_t)v * w];
+            uint32_t* rpos = &by_pos[(size_t)g->pos[v] * w];
+            for (int64_t j = 0; j < cnt; ++j) {
+                const uint32_t rel = g->nbr_rel[lo + j];
+                rid[j] = (rel << 30) | (uint32_t)g->nbr_idx[lo + j];
+                rpos[j] = (rel << 30) | (uint32_t)g->pos[g->nbr_idx[lo + j]];
+            }
+            // entries stay in ascending-id order in both tables, so the summation
+            // order of a gate's sources does not depend on the schedule
+        }
+        const size_t bytes = rows * w * sizeof(uint32_t);
+        auto fail = [&](int rc) {
+            if (g->d_ell_id) (void)hipFree(g->d_ell_id);
+            if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
+            if (g->d_order) (void)hipFree(g->d_order);
+            g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr;
+            return rc;
+        };
+        if (hipMalloc((void**)&g->d_ell_id, bytes) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&g->d_ell_pos, bytes) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&g->d_order, rows * sizeof(int32_t)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMemcpy(g->d_ell_id, by_id.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        if (hipMemcpy(g->d_ell_pos, by_pos.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        if (g->n > 0 &&
+            hipMemcpy(g->d_order, g->order.data(), (size_t)g->n * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
+            return fail(DG4_EHIP);
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
+    g->ell_w = w; g->device = dev; g->on_device = true;
+    return DG4_OK;
+}
+
+extern "C" int dg4_graph_upload(dg4_graph* g)
+{
+    if (!g) return DG4_EINVAL;
+    return dg4_graph_ensure_device(g);
+}
+
+extern "C" void dg4_graph_free(dg4_graph* g)
+{
+    if (!g) return;
+    if (g->d_ell_id) (void)hipFree(g->d_ell_id);
+    if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
+    if (g->d_order) (void)hipFree(g->d_order);
+    delete g;
+}

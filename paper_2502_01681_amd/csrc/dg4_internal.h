@@ -1,0 +1,72 @@
+// Internal declarations shared by the host graph builder, the entry points and
+// the kernel launchers. Not part of the public ABI.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <memory>
+#include <mutex>
+#include <vector>
+
+#include "dg4.h"
+
+// Neighbour rows on the device: fixed-width rows of packed 32-bit entries
+// (relation code << 30 | index), padded with DG4_ELL_PAD. Width = 2^(hops+1),
+// one more than the largest cone (Section 3.2), so a row always ends in a pad.
+#define DG4_ELL_PAD 0xFFFFFFFFu
+#define DG4_MAX_LAYERS 8
+
+struct dg4_graph {
+    int64_t n = 0, e = 0, nnz = 0;
+    int32_t hops = 0, max_level = 0;
+    std::vector<int32_t> level, order, pos;      // pos[id] = position in `order`
+    std::vector<int64_t> level_ptr, nbr_ptr;
+    std::vector<int32_t> nbr_idx;
+    std::vector<uint8_t> nbr_rel;
+
+    // device mirror (one device), created once under `mu`
+    std::mutex mu;
+    bool on_device = false;
+    int device = -1;
+    int ell_w = 0;
+    uint32_t* d_ell_id = nullptr;    // [n, ell_w] rows and entries by node id
+    uint32_t* d_ell_pos = nullptr;   // [n, ell_w] rows and entries by position
+    int32_t* d_order = nullptr;      // [n]
+};
+
+int dg4_graph_ensure_device(dg4_graph* g);
+
+// ---- kernel launchers (dg4_kernels.hip). All return a hipError_t as int. ----
+
+struct dg4_attn_args {
+    const void* q; int64_t q_stride;        // row r of Q at q + r*q_stride elements
+    const void* k_self; const void* v_self; int64_t self_stride;   // rows by destination row
+    const void* k_src; const void* v_src; int64_t src_stride;      // rows by neighbour index
+    const float* rel_bias;                  // [heads,4]
+    const uint32_t* ell; int ell_w;
+    void* a; int64_t a_stride;
+    int64_t row_begin, row_end;
+};
+int dg4_launch_attn(int dtype, int hidden, const dg4_attn_args& a, hipStream_t s);
+
+// Re-tile columns [col0, col0+n_cols) of a row-major weight with `ld` columns
+// and k_dim rows into MFMA B-operand order (n_cols % 32 == 0).
+int dg4_launch_pack_w(int dtype, const void* w, int ld, int col0, int n_cols, int k_dim, void* packed, hipStream_t s);
+
+struct dg4_gemm_args {
+    const void* a; int64_t a_stride;        // input rows; row r at a + idx(r)*a_stride
+    const int32_t* a_gather;                // nullable: idx(r) = a_gather[r], else r
+    const void* w_packed; int n_cols;       // packed [hidden, n_cols]
+    // output: column block j (of `hidden` columns) of row r goes to
+    // out[j] + oidx(r)*out_stride
+    void* out[2 * DG4_MAX_LAYERS + 3]; int64_t out_stride;
+    const int32_t* out_scatter;             // nullable: oidx(r) = out_scatter[r]
+    int64_t row_begin, row_end;
+    // epilogue (n_cols == hidden only): out = LN(resid + acc)
+    int epilogue;                           // 0 plain, 1 residual + LayerNorm
+    const void* resid; int64_t resid_stride; const int32_t* resid_gather;
+    void* out2; int64_t out2_stride;        // nullable second copy, indexed by r
+    float ln_eps;
+};
+int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s);

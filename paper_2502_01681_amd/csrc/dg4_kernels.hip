@@ -1,0 +1,401 @@
+// Device kernels for gfx950 (MI355X, wave64) and their launchers.
+//
+//  attn_kernel   scores + segmented softmax + aggregation over cone rows
+//                (Section 3.5; single-source rows get alpha = 1, Section 3.7).
+//                HBM-bound gather: lanes split the FEATURE dimension of a row,
+//                the <= 15 neighbours are looped over in registers, so the
+//                softmax needs no cross-lane traffic and no score tensor exists.
+//  pack_w_kernel re-tiles a row-major weight into MFMA B-operand order.
+//  gemm_kernel   rows x packed weight on the matrix cores (the dense
+//                projections), optionally fused with residual + LayerNorm.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dg4_internal.h"
+
+namespace {
+
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+struct bf16_t { uint16_t bits; };   // storage only
+
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+// float -> bfloat16 bits, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return 0x7FC0u;
+    u += 0x7FFFu + ((u >> 16) & 1u);
+    return u >> 16;
+}
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
+{
+    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+}
+
+// Lane exchange inside a group of 4 lanes by data-parallel primitives.
+__device__ __forceinline__ float xor1(float v)   // lane ^ 1
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0xB1, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float xor2(float v)   // lane ^ 2
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), 0x4E, 0xF, 0xF, true));
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+    static constexpr int EPL = 8;                 // elements in a lane's 32 bytes
+    __device__ static void unpack(const uint4& a, const uint4& b, float* f)
+    {
+        f[0] = __uint_as_float(a.x); f[1] = __uint_as_float(a.y); f[2] = __uint_as_float(a.z); f[3] = __uint_as_float(a.w);
+        f[4] = __uint_as_float(b.x); f[5] = __uint_as_float(b.y); f[6] = __uint_as_float(b.z); f[7] = __uint_as_float(b.w);
+    }
+    __device__ static void pack(const float* f, uint4& a, uint4& b)
+    {
+        a = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+        b = make_uint4(__float_as_uint(f[4]), __float_as_uint(f[5]), __float_as_uint(f[6]), __float_as_uint(f[7]));
+    }
+    __device__ static float head_sum(float p) { p += xor1(p); p += xor2(p); return p; }   // 4 lanes per head
+    __device__ static float load1(const void* p, int64_t i) { return ((const float*)p)[i]; }
+    __device__ static void store1(void* p, int64_t i, float v) { ((float*)p)[i] = v; }
+};
+template <> struct Elem<bf16_t> {
+    static constexpr int EPL = 16;
+    __device__ static void unpack(const uint4& a, const uint4& b, float* f)
+    {
+        const uint32_t w[8] = { a.x, a.y, a.z, a.w, b.x, b.y, b.z, b.w };
+#pragma unroll
+        for (int i = 0; i < 8; ++i) { f[2 * i] = bf16_lo(w[i]); f[2 * i + 1] = bf16_hi(w[i]); }
+    }
+    __device__ static void pack(const float* f, uint4& a, uint4& b)
+    {
+        a = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+        b = make_uint4(pack_bf16x2(f[8], f[9]), pack_bf16x2(f[10], f[11]), pack_bf16x2(f[12], f[13]), pack_bf16x2(f[14], f[15]));
+    }
+    __device__ static float head_sum(float p) { p += xor1(p); return p; }                   // 2 lanes per head
+    __device__ static float load1(const void* p, int64_t i) { return bf16_lo(((const uint16_t*)p)[i]); }
+    __device__ static void store1(void* p, int64_t i, float v) { ((uint16_t*)p)[i] = (uint16_t)f32_to_bf16_bits(v); }
+};
+
+// ------------------------------------------------------------------ attention
+
+// One destination row per group of LPR lanes; every lane owns 32 contiguous
+// bytes of each 512-byte (or 256 / 1024-byte) row it touches.
+template <typename T, int D, int W>
+__global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
+{
+    constexpr int EPL = Elem<T>::EPL;
+    constexpr int LPR = D / EPL;              // lanes per row
+    constexpr int RPW = 64 / LPR;             // rows per wave
+    constexpr int CH = W < 8 ? W : 8;         // neighbour rows in flight per pass
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int sub = lane % LPR;
+    const int64_t row = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+    if (row >= p.row_end) return;             // whole lane groups leave together
+
+    const int64_t eoff = (int64_t)sub * EPL;  // element offset of this lane inside a row
+    const int head = (int)(eoff >> 5);
+
+    uint32_t ent[W];
+    {
+        const uint4* e4 = (const uint4*)(p.ell + row * W);
+#pragma unroll
+        for (int i = 0; i < W / 4; ++i) {
+            const uint4 t = e4[i];
+            ent[4 * i] = t.x; ent[4 * i + 1] = t.y; ent[4 * i + 2] = t.z; ent[4 * i + 3] = t.w;
+        }
+    }
+    float q[EPL];
+    {
+        const uint4* qp = (const uint4*)((const T*)p.q + row * p.q_stride + eoff);
+        Elem<T>::unpack(qp[0], qp[1], q);
+    }
+    float bias[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[head * 4 + i];
+
+    auto src_row = [&](const void* self_base, const void* src_base, uint32_t e) -> const uint4* {
+        const uint32_t rel = e >> 30;
+        const int64_t idx = e & 0x3FFFFFFFu;
+        const T* r = rel == 0 ? (const T*)self_base + row * p.self_stride
+                              : (const T*)src_base + idx * p.src_stride;
+        return (const uint4*)(r + eoff);
+    };
+
+    // pass 1: scores
+    float s[W];
+    const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+#pragma unroll
+    for (int c0 = 0; c0 < W; c0 += CH) {
+        uint4 ka[CH], kb[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (ent[c0 + j] != DG4_ELL_PAD) {
+                const uint4* kp = src_row(p.k_self, p.k_src, ent[c0 + j]);
+                ka[j] = kp[0]; kb[j] = kp[1];
+            } else {
+                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            float k[EPL];
+            Elem<T>::unpack(ka[j], kb[j], k);
+            float dot = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
+            dot = Elem<T>::head_sum(dot);
+            const uint32_t rel = ent[c0 + j] >> 30;
+            const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+            s[c0 + j] = ent[c0 + j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
+        }
+    }
+    // softmax over the row, in this lane (all lanes of a head hold the same s)
+    float mx = s[0];
+#pragma unroll
+    for (int j = 1; j < W; ++j) mx = fmaxf(mx, s[j]);
+    float z = 0.f;
+#pragma unroll
+    for (int j = 0; j < W; ++j) { s[j] = __expf(s[j] - mx); z += s[j]; }
+    const float rz = 1.0f / z;
+
+    // pass 2: aggregation
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int c0 = 0; c0 < W; c0 += CH) {
+        uint4 va[CH], vb[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (ent[c0 + j] != DG4_ELL_PAD) {
+                const uint4* vp = src_row(p.v_self, p.v_src, ent[c0 + j]);
+                va[j] = vp[0]; vb[j] = vp[1];
+            } else {
+                va[j] = make_uint4(0, 0, 0, 0); vb[j] = va[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            float v[EPL];
+            Elem<T>::unpack(va[j], vb[j], v);
+            const float al = s[c0 + j] * rz;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(al, v[i], acc[i]);
+        }
+    }
+    uint4 oa, ob;
+    Elem<T>::pack(acc, oa, ob);
+    uint4* op = (uint4*)((T*)p.a + row * p.a_stride + eoff);
+    op[0] = oa; op[1] = ob;
+}
+
+template <typename T, int D>
+int launch_attn_w(const dg4_attn_args& a, hipStream_t s)
+{
+    constexpr int RPB = 4 * (64 / (D / Elem<T>::EPL));     // rows per block
+    const int64_t rows = a.row_end - a.row_begin;
+    if (rows <= 0) return hipSuccess;
+    const unsigned grid = (unsigned)((rows + RPB - 1) / RPB);
+    switch (a.ell_w) {
+    case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), dim3(grid), dim3(256), 0, s, a); break;
+    case 8: hipLaunchKernelGGL((attn_kernel<T, D, 8>), dim3(grid), dim3(256), 0, s, a); break;
+    case 16: hipLaunchKernelGGL((attn_kernel<T, D, 16>), dim3(grid), dim3(256), 0, s, a); break;
+    default: return hipErrorInvalidValue;
+    }
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------- weight packing
+
+// Packed order, in 16-byte units: unit ((nt*KC + c)*64 + lane) holds, for
+// column n = nt*32 + lane%32 and half kg = lane/32, the E consecutive rows
+// k = (2c + kg)*E .. +E-1 (E = 8 bf16 or 4 floats): exactly what one lane
+// feeds to the B operand of a 32x32 MFMA for K-chunk c.
+template <typename T>
+__global__ void pack_w_kernel(const T* w, int ld, int col0, int n_cols, int k_dim, T* packed)
+{
+    constexpr int E = 16 / sizeof(T);
+    const int KC = k_dim / (2 * E);
+    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t units = (int64_t)(n_cols / 32) * KC * 64;
+    if (unit >= units) return;
+    const int lane = (int)(unit & 63);
+    const int c = (int)((unit >> 6) % KC);
+    const int nt = (int)((unit >> 6) / KC);
+    const int n = col0 + nt * 32 + (lane & 31);
+    const int k0 = (2 * c + (lane >> 5)) * E;
+#pragma unroll
+    for (int j = 0; j < E; ++j) packed[unit * E + j] = w[(int64_t)(k0 + j) * ld + n];
+}
+
+// ----------------------------------------------------------------------- GEMM
+
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+    __device__ static void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {
+    __device__ static void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+__device__ __forceinline__ float sum_over_32_lanes(float v)
+{
+    v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8); v += __shfl_xor(v, 16);
+    return v;
+}
+
+// One wave = 32 rows x all output columns. The wave keeps its 32 x D slice of
+// the A operand in registers and streams the packed weight tiles.
+// Accumulator element i of a lane sits at row 8*(i/4) + 4*(lane/32) + i%4,
+// column lane%32 of the 32x32 tile.
+template <typename T, int D, bool LN>
+__global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
+{
+    constexpr int E = 16 / sizeof(T);
+    constexpr int KC = D / (2 * E);
+    constexpr int NT_LN = D / 32;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int m = lane & 31, kg = lane >> 5;
+    const int64_t r0 = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * 32;
+    if (r0 >= p.row_end) return;
+
+    uint4 a[KC];
+    {
+        int64_t r = r0 + m;
+        if (r >= p.row_end) r = p.row_end - 1;          // clamp: loads stay in bounds, stores are masked
+        const int64_t ar = p.a_gather ? (int64_t)p.a_gather[r] : r;
+        const uint4* ap = (const uint4*)((const T*)p.a + ar * p.a_stride);
+#pragma unroll
+        for (int c = 0; c < KC; ++c) a[c] = ap[2 * c + kg];
+    }
+    const uint4* wp = (const uint4*)p.w_packed;
+
+    // rows this lane's accumulator elements belong to
+    int64_t orow[16];
+    bool ok[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t r = r0 + 8 * (i / 4) + 4 * kg + (i % 4);
+        ok[i] = r < p.row_end;
+        orow[i] = ok[i] ? r : p.row_end - 1;
+    }
+
+    if constexpr (!LN) {
+        const int n_tiles = p.n_cols / 32;
+        for (int nt = 0; nt < n_tiles; ++nt) {
+            f32x16 acc;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+#pragma unroll
+            for (int c = 0; c < KC; ++c) {
+                const uint4 b = wp[((int64_t)nt * KC + c) * 64 + lane];
+                Mma<T>::run(a[c], b, acc);
+            }
+            const int col = nt * 32 + m;
+            void* base = p.out[col / D];
+            const int cc = col % D;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                if (!ok[i]) continue;
+                const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
+                Elem<T>::store1(base, orr * p.out_stride + cc, acc[i]);
+                if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col, acc[i]);
+            }
+        }
+    } else {
+        f32x16 acc[NT_LN];
+#pragma unroll
+        for (int nt = 0; nt < NT_LN; ++nt) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+#pragma unroll
+            for (int c = 0; c < KC; ++c) {
+                const uint4 b = wp[((int64_t)nt * KC + c) * 64 + lane];
+                Mma<T>::run(a[c], b, acc[nt]);
+            }
+        }
+        // residual, then LayerNorm over each row (no affine, biased variance)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[orow[i]] : orow[i];
+            float s1 = 0.f;
+#pragma unroll
+            for (int nt = 0; nt < NT_LN; ++nt) {
+                acc[nt][i] += Elem<T>::load1(p.resid, rr * p.resid_stride + nt * 32 + m);
+                s1 += acc[nt][i];
+            }
+            const float mean = sum_over_32_lanes(s1) * (1.0f / D);
+            float s2 = 0.f;
+#pragma unroll
+            for (int nt = 0; nt < NT_LN; ++nt) { const float t = acc[nt][i] - mean; s2 = fmaf(t, t, s2); }
+            const float rstd = rsqrtf(sum_over_32_lanes(s2) * (1.0f / D) + p.ln_eps);
+            if (!ok[i]) continue;
+            const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
+#pragma unroll
+            for (int nt = 0; nt < NT_LN; ++nt) {
+                const float y = (acc[nt][i] - mean) * rstd;
+                Elem<T>::store1(p.out[0], orr * p.out_stride + nt * 32 + m, y);
+                if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + nt * 32 + m, y);
+            }
+        }
+    }
+}
+
+template <typename T, int D>
+int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
+{
+    const int64_t rows = a.row_end - a.row_begin;
+    if (rows <= 0) return hipSuccess;
+    const unsigned grid = (unsigned)((rows + 127) / 128);
+    if (a.epilogue) {
+        if (a.n_cols != D) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemm_kernel<T, D, true>), dim3(grid), dim3(256), 0, s, a);
+    } else {
+        if (a.out2 && a.n_cols != D) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((gemm_kernel<T, D, false>), dim3(grid), dim3(256), 0, s, a);
+    }
+    return hipGetLastError();
+}
+
+}  // namespace
+
+int dg4_launch_attn(int dtype, int hidden, const dg4_attn_args& a, hipStream_t s)
+{
+    if (dtype == DG4_F32) return hidden == 128 ? launch_attn_w<float, 128>(a, s) : launch_attn_w<float, 256>(a, s);
+    return hidden == 128 ? launch_attn_w<bf16_t, 128>(a, s) : launch_attn_w<bf16_t, 256>(a, s);
+}
+
+int dg4_launch_pack_w(int dtype, const void* w, int ld, int col0, int n_cols, int k_dim, void* packed, hipStream_t s)
+{
+    const int e = dtype == DG4_F32 ? 4 : 8;
+    const int64_t units = (int64_t)(n_cols / 32) * (k_dim / (2 * e)) * 64;
+    const unsigned grid = (unsigned)((units + 255) / 256);
+    if (dtype == DG4_F32)
+        hipLaunchKernelGGL(pack_w_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)w, ld, col0, n_cols, k_dim, (float*)packed);
+    else
+        hipLaunchKernelGGL(pack_w_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t*)w, ld, col0, n_cols, k_dim, (uint16_t*)packed);
+    return hipGetLastError();
+}
+
+int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s)
+{
+    if (dtype == DG4_F32) return hidden == 128 ? launch_gemm_t<float, 128>(a, s) : launch_gemm_t<float, 256>(a, s);
+    return hidden == 128 ? launch_gemm_t<bf16_t, 128>(a, s) : launch_gemm_t<bf16_t, 256>(a, s);
+}

@@ -1,0 +1,114 @@
+"""Host side of the C ABI (no GPU): the library loads, exports every declared
+symbol, and dg4_build_levels matches the oracle bit for bit."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import dg4_synth as synth
+import oracle
+import paper_2502_01681_amd as dg4
+from helpers import load_hand_graphs
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    hdr = open(os.path.join(ROOT, "include", "dg4.h")).read()
+    names = set(re.findall(r"^(?:int|int64_t|void|const char\*)\s+(dg4_[a-z_]+)\s*\(", hdr, flags=re.M))
+    assert len(names) == 11
+    assert {"dg4_build_levels", "dg4_qkv_proj", "dg4_sparse_attn_fwd", "dg4_layer_fwd"} <= names
+    L = ctypes.CDLL(dg4.library_path()) if os.path.exists(dg4.library_path()) else dg4.lib()
+    for n in sorted(names):
+        assert hasattr(L, n), n
+
+
+def same_tables(g, og):
+    for a in ("level", "order", "level_ptr", "nbr_ptr", "nbr_idx", "nbr_rel"):
+        mine, ref = g.array(a), getattr(og, a)
+        assert mine.dtype == ref.dtype and mine.shape == ref.shape and (mine == ref).all(), a
+
+
+@pytest.mark.parametrize("gr", load_hand_graphs(), ids=lambda g: g["name"])
+def test_hand_graphs(gr):
+    g = dg4.dg4_build_levels(gr["n"], gr["src"], gr["dst"], gr["inv"], gr["hops"])
+    assert g.array("level").tolist() == gr["level"]
+    ptr, idx, rel = g.array("nbr_ptr"), g.array("nbr_idx"), g.array("nbr_rel")
+    for v, row in gr["rows"].items():
+        assert list(zip(idx[ptr[v]:ptr[v + 1]].tolist(), rel[ptr[v]:ptr[v + 1]].tolist())) == row
+
+
+@pytest.mark.parametrize("name,n_and,hops", [("tiny", None, 1), ("tiny", None, 2), ("tiny", None, 3),
+                                              ("small", None, 2), ("medium", 50_000, 2),
+                                              ("large", 60_000, 2), ("stress", 60_000, 3)])
+def test_tables_bit_exact_against_oracle(name, n_and, hops):
+    w = synth.make(name, n_and=n_and, features=False)
+    n = w.cfg.n_nodes
+    for hint in ([None, w.level_hint] if w.level_hint is not None else [None]):
+        g = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, hint)
+        og = oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, hint)
+        same_tables(g, og)
+        assert g.n == n and g.n_levels == og.n_levels and g.nnz == len(og.nbr_idx)
+
+
+def test_shuffled_edges_and_relabelled_nodes():
+    w = synth.make("small", n_and=5000, features=False)
+    n = w.cfg.n_nodes
+    rng = np.random.default_rng(1)
+    perm, eperm = rng.permutation(n).astype(np.int32), rng.permutation(len(w.edge_src))
+    src, dst, inv = perm[w.edge_src][eperm], perm[w.edge_dst][eperm], w.edge_inv[eperm]
+    same_tables(dg4.dg4_build_levels(n, src, dst, inv, 2), oracle.build_levels(n, src, dst, inv, 2))
+
+
+def test_in_degree_one_nodes():
+    # NOT/buffer nodes of the paper's AIG representation (in-degree 1)
+    src, dst, inv = [0, 1, 2, 3, 3], [2, 2, 3, 4, 5], [0, 1, 1, 0, 1]
+    same_tables(dg4.dg4_build_levels(6, src, dst, inv, 3), oracle.build_levels(6, src, dst, inv, 3))
+
+
+@pytest.mark.parametrize("src,dst,inv,err", [
+    ([0, 1, 2], [3, 3, 3], [0, 0, 0], "EFANIN"),
+    ([0, 0], [3, 3], [0, 1], "EFANIN"),
+    ([0, 5], [3, 3], [0, 0], "ERANGE"),
+    ([0, -1], [3, 3], [0, 0], "ERANGE"),
+    ([0, 1], [3, 3], [0, 2], "EINVAL"),
+    ([3, 1], [3, 3], [0, 0], "ECYCLE"),
+    ([0, 3, 2, 4], [3, 4, 4, 3], [0, 0, 0, 0], "ECYCLE"),
+])
+def test_invalid_graphs_agree_with_oracle(src, dst, inv, err):
+    with pytest.raises(dg4.DG4Error) as e:
+        dg4.dg4_build_levels(5, src, dst, inv, 2)
+    assert e.value.name == err
+    with pytest.raises(oracle.OracleError, match=err):
+        oracle.build_levels(5, src, dst, inv, 2)
+
+
+def test_bad_hint_hops_and_empty():
+    with pytest.raises(dg4.DG4Error) as e:
+        dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2, level_hint=[0, 0, 0])
+    assert e.value.name == "EHINT"
+    with pytest.raises(dg4.DG4Error) as e:
+        dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2, level_hint=[0, 1, 2])
+    assert e.value.name == "EHINT"
+    for hops in (0, 4):
+        with pytest.raises(dg4.DG4Error) as e:
+            dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], hops)
+        assert e.value.name == "EUNSUPPORTED"
+    g = dg4.dg4_build_levels(0, [], [], [], 2)
+    assert g.n == 0 and g.n_levels == 1 and g.array("level_ptr").tolist() == [0, 0]
+    g = dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2, level_hint=[0, 0, 5])
+    assert g.n_levels == 6 and g.array("level_ptr").tolist() == [0, 2, 2, 2, 2, 2, 3]
+
+
+def test_config_errors_without_a_device():
+    g = dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2)
+    for bad in (dict(hidden=64, heads=2), dict(hidden=128, heads=8), dict(hidden=128, heads=4, n_layers=9),
+                dict(hidden=128, heads=4, hops=3)):
+        kw = dict(hidden=128, heads=4, hops=2, n_layers=1, dtype="f32")
+        kw.update(bad)
+        with pytest.raises(dg4.DG4Error):
+            dg4.dg4_layer_workspace_bytes(dg4.LayerConfig(**kw), g)
+    assert dg4.dg4_layer_workspace_bytes(dg4.LayerConfig(128, 4, 2, 1, "f32"), g) > 0
+    assert dg4.dg4_proj_workspace_bytes(dg4.LayerConfig(256, 8, 2, 1, "bf16")) == 256 * 768 * 2
