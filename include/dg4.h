@@ -46,6 +46,8 @@ typedef enum {
 
 /* cfg->flags */
 #define DG4_NO_EPILOGUE 1u  /* H = A*Wo without residual and LayerNorm (kernel tests)      */
+#define DG4_PER_LEVEL   2u  /* dg4_layer_fwd: launch level by level instead of the single  */
+                            /* persistent dataflow kernel (same results; for comparison)   */
 
 typedef struct {
     int32_t hidden;         /* d: 128 or 256                                               */

@@ -15,6 +15,7 @@ _I32 = ctypes.c_int32
 
 DG4_F32, DG4_BF16 = 0, 1
 DG4_NO_EPILOGUE = 1
+DG4_PER_LEVEL = 2
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
           "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8)}
 STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
@@ -42,11 +43,12 @@ class LayerConfig:
     dtype: str = "bf16"          # "f32" | "bf16"
     epilogue: bool = True
     ln_eps: float = 1e-5
+    per_level: bool = False      # launch level by level instead of the persistent sweep kernel
 
     def c(self) -> _Cfg:
         return _Cfg(self.hidden, self.heads, self.hops, self.n_layers,
                     DG4_F32 if self.dtype == "f32" else DG4_BF16,
-                    0 if self.epilogue else DG4_NO_EPILOGUE, self.ln_eps)
+                    (0 if self.epilogue else DG4_NO_EPILOGUE) | (DG4_PER_LEVEL if self.per_level else 0), self.ln_eps)
 
 
 _lib = None

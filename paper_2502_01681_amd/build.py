@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdg4.so")
-SOURCES = ["dg4_graph.cpp", "dg4_api.cpp", "dg4_kernels.hip"]
+SOURCES = ["dg4_graph.cpp", "dg4_api.cpp", "dg4_kernels.hip", "dg4_sweep.hip"]
 
 
 def sources():
@@ -19,7 +19,7 @@ def stale() -> bool:
     if not os.path.exists(LIB):
         return True
     t = os.path.getmtime(LIB)
-    deps = sources() + [os.path.join(CSRC, "dg4_internal.h"), os.path.join(ROOT, "include", "dg4.h")]
+    deps = sources() + [os.path.join(CSRC, "dg4_internal.h"), os.path.join(CSRC, "dg4_device.h"), os.path.join(ROOT, "include", "dg4.h")]
     return any(os.path.getmtime(d) > t for d in deps)
 
 

@@ -2,6 +2,7 @@
 // of the level sweep (paper Section 3.4, Algorithm 2). All arithmetic is in
 // the device kernels; there is no CPU fallback.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 
 #include "dg4_internal.h"
@@ -15,7 +16,7 @@ int check_cfg(const dg4_layer_cfg* c, bool need_layers)
 {
     if (!c) return DG4_EINVAL;
     if (c->dtype != DG4_F32 && c->dtype != DG4_BF16) return DG4_EINVAL;
-    if (c->flags & ~(uint32_t)DG4_NO_EPILOGUE) return DG4_EINVAL;
+    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL)) return DG4_EINVAL;
     if (c->hidden != 128 && c->hidden != 256) return DG4_EUNSUPPORTED;
     if (c->heads <= 0 || c->heads * 32 != c->hidden) return DG4_EUNSUPPORTED;
     if (c->hops < 1 || c->hops > 3) return DG4_EUNSUPPORTED;
@@ -34,6 +35,9 @@ struct LayerPlan {
     size_t abuf;         // [max_level_rows, d]
     size_t s0, s1;       // [max_level_rows, d] running state between layers
     size_t qkv_level;    // [max_level_rows, 3d] (layers >= 1)
+    size_t wo_t, wkv_t;  // persistent sweep: weights in its A-operand order (layer 0)
+    size_t flags;        // [n] uint32 "rows published"
+    size_t ctrl;         // ticket counter, abort flag
     size_t total;
     int64_t max_rows;
 };
@@ -57,8 +61,25 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     p.s0 = take((size_t)mr * d * es);
     p.s1 = take((size_t)mr * d * es);
     p.qkv_level = take(L > 1 ? (size_t)mr * 3 * d * es : 0);
+    p.wo_t = take(d * d * es);
+    p.wkv_t = take(d * 2 * d * es);
+    p.flags = take(n * sizeof(uint32_t));
+    p.ctrl = take(256);
     p.total = off;
     return p;
+}
+
+// Tunables of the persistent sweep, overridable from the environment for experiments.
+uint32_t dg4_sweep_spin_limit()
+{
+    const char* e = getenv("DG4_SWEEP_SPIN_LIMIT");
+    return e ? (uint32_t)strtoul(e, nullptr, 10) : (1u << 22);
+}
+int dg4_sweep_wgs_per_cu()
+{
+    const char* e = getenv("DG4_SWEEP_WGS_PER_CU");
+    const int v = e ? atoi(e) : 2;
+    return v < 1 ? 1 : v > 8 ? 8 : v;
 }
 
 #define HIPCHK(expr) do { if ((expr) != (int)hipSuccess) return DG4_EHIP; } while (0)
@@ -204,6 +225,29 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.out_stride = 3 * d;
         a.row_begin = P0; a.row_end = P1;
         HIPCHK(dg4_launch_gemm(dt, d, a, s));
+    }
+
+    // One persistent dataflow kernel for the whole range of levels
+    if (dt == DG4_BF16 && d == 256 && L == 1 && !(cfg->flags & DG4_PER_LEVEL)) {
+        HIPCHK(dg4_launch_pack_wt(W[1], d, 0, 4, 4, at(pl.wo_t), s));
+        HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, d, 8, 4, at(pl.wkv_t), s));
+        dg4_sweep_args a{};
+        a.tiles = g->d_tiles;
+        a.tile_begin = g->level_tile_ptr[level_begin];
+        a.n_tiles = g->level_tile_ptr[level_end] - a.tile_begin;
+        a.ell = g->d_ell_pos; a.ell_w = g->ell_w;
+        a.order = g->d_order;
+        a.x = (const uint16_t*)X;
+        a.qkv_self = (const uint16_t*)at(pl.qkv_self);
+        a.kv = (uint16_t*)at(pl.kv);
+        a.h_out = (uint16_t*)Hout;
+        a.wo_packed = at(pl.wo_t); a.wkv_packed = at(pl.wkv_t);
+        a.rel_bias = (const float*)W[2];
+        a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
+        a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.publish_kv = 1;
+        a.spin_limit = dg4_sweep_spin_limit();
+        HIPCHK(dg4_launch_sweep(a, g->n, P0, dg4_sweep_wgs_per_cu(), s));
+        return DG4_OK;
     }
 
     for (int32_t lev = level_begin; lev < level_end; ++lev) {

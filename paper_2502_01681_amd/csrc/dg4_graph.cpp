@@ -253,17 +253,30 @@ int dg4_graph_ensure_device(dg4_graph* g)
             // entries stay in ascending-id order in both tables, so the summation
             // order of a gate's sources does not depend on the schedule
         }
+        std::vector<uint2> tiles;
+        g->level_tile_ptr.assign((size_t)g->max_level + 2, 0);
+        for (int32_t l = 0; l <= g->max_level; ++l) {
+            g->level_tile_ptr[l] = (int64_t)tiles.size();
+            for (int64_t p0 = g->level_ptr[l]; p0 < g->level_ptr[l + 1]; p0 += DG4_TILE_ROWS)
+                tiles.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(DG4_TILE_ROWS, g->level_ptr[l + 1] - p0)));
+        }
+        g->level_tile_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
         const size_t bytes = rows * w * sizeof(uint32_t);
         auto fail = [&](int rc) {
             if (g->d_ell_id) (void)hipFree(g->d_ell_id);
             if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
             if (g->d_order) (void)hipFree(g->d_order);
-            g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr;
+            if (g->d_tiles) (void)hipFree(g->d_tiles);
+            g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr;
             return rc;
         };
         if (hipMalloc((void**)&g->d_ell_id, bytes) != hipSuccess) return fail(DG4_ENOMEM);
         if (hipMalloc((void**)&g->d_ell_pos, bytes) != hipSuccess) return fail(DG4_ENOMEM);
         if (hipMalloc((void**)&g->d_order, rows * sizeof(int32_t)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&g->d_tiles, std::max<size_t>(tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (!tiles.empty() &&
+            hipMemcpy(g->d_tiles, tiles.data(), tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess)
+            return fail(DG4_EHIP);
         if (hipMemcpy(g->d_ell_id, by_id.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (hipMemcpy(g->d_ell_pos, by_pos.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (g->n > 0 &&
@@ -288,5 +301,6 @@ extern "C" void dg4_graph_free(dg4_graph* g)
     if (g->d_ell_id) (void)hipFree(g->d_ell_id);
     if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
     if (g->d_order) (void)hipFree(g->d_order);
+    if (g->d_tiles) (void)hipFree(g->d_tiles);
     delete g;
 }

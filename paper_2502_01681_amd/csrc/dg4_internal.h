@@ -16,6 +16,7 @@
 // one more than the largest cone (Section 3.2), so a row always ends in a pad.
 #define DG4_ELL_PAD 0xFFFFFFFFu
 #define DG4_MAX_LAYERS 8
+#define DG4_TILE_ROWS 16          // gates per tile of the persistent sweep
 
 struct dg4_graph {
     int64_t n = 0, e = 0, nnz = 0;
@@ -33,6 +34,9 @@ struct dg4_graph {
     uint32_t* d_ell_id = nullptr;    // [n, ell_w] rows and entries by node id
     uint32_t* d_ell_pos = nullptr;   // [n, ell_w] rows and entries by position
     int32_t* d_order = nullptr;      // [n]
+    // tiles of the persistent sweep: runs of <= DG4_TILE_ROWS positions inside one level
+    std::vector<int64_t> level_tile_ptr;   // [n_levels + 1] first tile of each level
+    uint2* d_tiles = nullptr;        // [n_tiles] (first position, rows)
 };
 
 int dg4_graph_ensure_device(dg4_graph* g);
@@ -70,3 +74,22 @@ struct dg4_gemm_args {
     float ln_eps;
 };
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s);
+
+// ---- persistent sweep (dg4_sweep.hip): bf16, hidden 256, one layer ----
+struct dg4_sweep_args {
+    const uint2* tiles; int64_t tile_begin; int64_t n_tiles;   // tickets 0..n_tiles-1 map to tiles[tile_begin + t]
+    const uint32_t* ell; int ell_w;        // neighbour rows by position
+    const int32_t* order;                  // position -> node id
+    const uint16_t* x;                     // [n, 256] by node id
+    const uint16_t* qkv_self;              // [n, 768] by position: Q | K | V of x
+    uint16_t* kv;                          // [n, 512] by position: K | V of the final embeddings
+    uint16_t* h_out;                       // [n, 256] by node id
+    const void* wo_packed; const void* wkv_packed;   // pack_wt order
+    const float* rel_bias;
+    uint32_t* flags;                       // [n] by position: 1 = rows published
+    uint32_t* ctrl;                        // [0] ticket counter, [1] abort flag
+    float ln_eps; int epilogue; int publish_kv;
+    uint32_t spin_limit;
+};
+int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void* packed, hipStream_t s);
+int dg4_launch_sweep(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, int wgs_per_cu, hipStream_t s);

@@ -89,6 +89,8 @@ def run_layer(w, cfg, g, level_begin=0, level_end=None, H0=None):
     ("tiny", None, {}), ("small", None, {}), ("tiny", None, dict(hops=3)), ("tiny", None, dict(hops=1)),
     ("tiny", None, dict(n_layers=3)), ("tiny", None, dict(epilogue=False)),
     ("medium", 40_000, {}), ("large", 50_000, {}), ("stress", 30_000, {}),
+    ("medium", 40_000, dict(per_level=True)), ("large", 50_000, dict(per_level=True)),
+    ("stress", 30_000, dict(n_layers=1)), ("large", 20_000, dict(hops=1)), ("large", 20_000, dict(epilogue=False)),
     ("stress", 3_000, dict(dtype="f32", hidden=128, heads=4)),
 ])
 def test_layer_fwd_end_to_end(name, n_and, kw):
@@ -97,7 +99,7 @@ def test_layer_fwd_end_to_end(name, n_and, kw):
     over = {k: v for k, v in kw.items() if k in ("hops", "n_layers", "dtype", "hidden", "heads")}
     c = synth.Config(**{**base.__dict__, **over, **({"n_and": n_and} if n_and else {})})
     w = synth.make(c)
-    cfg = cfg_of(c, epilogue=kw.get("epilogue", True))
+    cfg = cfg_of(c, epilogue=kw.get("epilogue", True), per_level=kw.get("per_level", False))
     g, og = graphs(w)
     H = to_np(run_layer(w, cfg, g))
     assert not np.isnan(H).any()                       # every gate written
@@ -132,6 +134,26 @@ def test_layer_fwd_schedule_split_and_determinism():
     assert torch.isnan(H1[lev >= mid].float()).all() and not torch.isnan(H1[lev < mid].float()).any()
     H2 = run_layer(w, cfg, g_hint, mid, None, H0=H1)
     assert torch.equal(H2, Hh)                          # resumed sweep = whole sweep
+
+
+def test_workspace_reuse_with_new_inputs():
+    # the same workspace and output buffer, different features: nothing stale may be read
+    print("layer_fwd workspace reuse", flush=True)
+    w = synth.make("large", n_and=30_000)
+    c = w.cfg
+    cfg = cfg_of(c)
+    g, og = graphs(w)
+    X1 = to_dev(w.x, c.dtype)
+    x2 = synth.normal(c.seed + 99, 4, w.x.shape, 1.0, True)
+    X2 = to_dev(x2, c.dtype)
+    W = device_weights(w, c.dtype)
+    H = torch.empty_like(X1)
+    ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+    for X, x in ((X1, w.x), (X2, x2), (X1, w.x)):
+        dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
+        torch.cuda.synchronize()
+        ref = oracle.layer_fwd(og, x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
+        assert row_rel_err(to_np(H), ref).max() <= TOL[c.dtype]
 
 
 def test_device_call_errors():
