@@ -149,6 +149,18 @@ int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const v
                   int32_t level_begin, int32_t level_end, void* Hout,
                   void* workspace, int64_t workspace_bytes, void* stream);
 
+/*
+ * Tracing aid for the persistent sweep kernel of dg4_layer_fwd. Synchronous:
+ * copies from `workspace` (as left by the last dg4_layer_fwd with the same cfg
+ * and graph, after the caller synchronised the stream) the abort flag of the
+ * kernel's bounded dependency wait (0 = the sweep ran to completion) and, if
+ * the environment variable DG4_SWEEP_PROFILE was set during that call, eight
+ * per-phase timers in 10 ns ticks summed over workgroups: ticket, dependency
+ * wait, attention, output projection, LayerNorm, K|V projection, publish, 0.
+ */
+int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace,
+                      uint64_t* ticks8, uint32_t* aborted);
+
 const char* dg4_strerror(int status);
 
 #ifdef __cplusplus

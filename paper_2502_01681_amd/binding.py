@@ -88,6 +88,9 @@ def lib():
         L.dg4_sparse_attn_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _P]
         L.dg4_layer_fwd.restype = ctypes.c_int
         L.dg4_layer_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(_P), _I32, _I32, _P, _P, _I64, _P]
+        L.dg4_layer_profile.restype = ctypes.c_int
+        L.dg4_layer_profile.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(ctypes.c_uint64),
+                                        ctypes.POINTER(ctypes.c_uint32)]
         _lib = L
     return _lib
 
@@ -205,3 +208,13 @@ def dg4_layer_fwd(cfg: LayerConfig, g: Graph, X, weights, Hout, level_begin=0, l
                              Hout.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "dg4_layer_fwd")
     return ws
+
+
+def dg4_layer_profile(cfg: LayerConfig, g: Graph, workspace):
+    """(aborted, ticks[8]) left in `workspace` by the last persistent sweep (synchronise first)."""
+    ticks = (ctypes.c_uint64 * 8)()
+    aborted = ctypes.c_uint32()
+    c = cfg.c()
+    _check(lib().dg4_layer_profile(ctypes.byref(c), g.handle, workspace.data_ptr(), ticks, ctypes.byref(aborted)),
+           "dg4_layer_profile")
+    return int(aborted.value), [int(t) for t in ticks]

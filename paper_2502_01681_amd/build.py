@@ -32,6 +32,9 @@ def build(force: bool = True) -> str:
            "-x", "hip",
            # packed fp32 VALU forms are switched off for every kernel of this library
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # MFMA accumulators in VGPRs: leaves the AGPR half of the register file to the
+           # weights that the persistent sweep kernel keeps resident
+           "-mllvm", "-amdgpu-mfma-vgpr-form=1",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC,
            "-Wall", "-Wno-unused-function",
            "-o", LIB] + sources()

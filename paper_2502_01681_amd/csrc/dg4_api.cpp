@@ -130,6 +130,16 @@ extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row
     if (row_end == row_begin) return DG4_OK;
     hipStream_t s = (hipStream_t)stream;
     const int d = cfg->hidden;
+    if (cfg->dtype == DG4_BF16 && d == 256) {
+        HIPCHK(dg4_launch_pack_w32(Wqkv, 3 * d, 0, 3 * d, workspace, s));
+        dg4_bulk_args b{};
+        b.src = (const uint16_t*)S;
+        b.w_packed = workspace; b.n_cols = 3 * d;
+        b.out[0] = (uint16_t*)Q; b.out[1] = (uint16_t*)K; b.out[2] = (uint16_t*)V; b.out_stride = d;
+        b.row_begin = row_begin; b.row_end = row_end;
+        HIPCHK(dg4_launch_bulk_proj(b, s));
+        return DG4_OK;
+    }
     HIPCHK(dg4_launch_pack_w(cfg->dtype, Wqkv, 3 * d, 0, 3 * d, d, workspace, s));
     dg4_gemm_args a{};
     a.a = S; a.a_stride = d;
@@ -215,20 +225,18 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // K/V of gates finished before this call (resume): from the caller's H
     if (P0 > 0) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
-    // layer 0 projections of x for every gate of the swept levels, in one pass
-    {
-        dg4_gemm_args a{};
-        a.a = X; a.a_stride = d; a.a_gather = g->d_order;
-        a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
-        char* base = ws + pl.qkv_self;
-        a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
-        a.out_stride = 3 * d;
-        a.row_begin = P0; a.row_end = P1;
-        HIPCHK(dg4_launch_gemm(dt, d, a, s));
-    }
-
     // One persistent dataflow kernel for the whole range of levels
     if (dt == DG4_BF16 && d == 256 && L == 1 && !(cfg->flags & DG4_PER_LEVEL)) {
+        {   // Q | K | V of x for every gate of the swept levels, level-sorted rows
+            HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, 0, 3 * d, at(pl.wqkv[0]), s));
+            dg4_bulk_args b{};
+            b.src = (const uint16_t*)X; b.gather = g->d_order;
+            b.w_packed = at(pl.wqkv[0]); b.n_cols = 3 * d;
+            uint16_t* base = (uint16_t*)at(pl.qkv_self);
+            b.out[0] = base; b.out[1] = base + d; b.out[2] = base + 2 * d; b.out_stride = 3 * d;
+            b.row_begin = P0; b.row_end = P1;
+            HIPCHK(dg4_launch_bulk_proj(b, s));
+        }
         HIPCHK(dg4_launch_pack_wt(W[1], d, 0, 4, 4, at(pl.wo_t), s));
         HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, d, 8, 4, at(pl.wkv_t), s));
         dg4_sweep_args a{};
@@ -246,8 +254,21 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
         a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.publish_kv = 1;
         a.spin_limit = dg4_sweep_spin_limit();
+        a.prof = getenv("DG4_SWEEP_PROFILE") ? (uint64_t*)((char*)at(pl.ctrl) + 64) : nullptr;
         HIPCHK(dg4_launch_sweep(a, g->n, P0, dg4_sweep_wgs_per_cu(), s));
         return DG4_OK;
+    }
+
+    // layer 0 projections of x for every gate of the swept levels, in one pass
+    {
+        dg4_gemm_args a{};
+        a.a = X; a.a_stride = d; a.a_gather = g->d_order;
+        a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
+        char* base = ws + pl.qkv_self;
+        a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
+        a.out_stride = 3 * d;
+        a.row_begin = P0; a.row_end = P1;
+        HIPCHK(dg4_launch_gemm(dt, d, a, s));
     }
 
     for (int32_t lev = level_begin; lev < level_end; ++lev) {
@@ -302,5 +323,19 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         // publish K/V of the level's final embeddings for every layer
         if (lev + 1 < n_levels) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
     }
+    return DG4_OK;
+}
+
+extern "C" int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace,
+                                 uint64_t* ticks8, uint32_t* aborted)
+{
+    const int rc = check_cfg(cfg, true);
+    if (rc != DG4_OK) return rc;
+    if (!g || !workspace || !ticks8 || !aborted) return DG4_EINVAL;
+    const LayerPlan pl = plan_layer(cfg, g);
+    uint32_t ctrl[64];
+    if (hipMemcpy(ctrl, (const char*)workspace + pl.ctrl, sizeof(ctrl), hipMemcpyDeviceToHost) != hipSuccess) return DG4_EHIP;
+    memcpy(ticks8, ctrl + 16, 8 * sizeof(uint64_t));
+    *aborted = ctrl[1];
     return DG4_OK;
 }

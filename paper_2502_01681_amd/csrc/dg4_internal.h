@@ -88,8 +88,21 @@ struct dg4_sweep_args {
     const float* rel_bias;
     uint32_t* flags;                       // [n] by position: 1 = rows published
     uint32_t* ctrl;                        // [0] ticket counter, [1] abort flag
+    uint64_t* prof;                        // nullable: 8 phase timers (100 MHz ticks, summed over workgroups)
     float ln_eps; int epilogue; int publish_kv;
     uint32_t spin_limit;
 };
 int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void* packed, hipStream_t s);
 int dg4_launch_sweep(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, int wgs_per_cu, hipStream_t s);
+
+// ---- bulk projection on the matrix cores (dg4_sweep.hip): bf16, hidden 256 ----
+struct dg4_bulk_args {
+    const uint16_t* src;                   // [*, 256] input rows
+    const int32_t* gather;                 // nullable: input row of output row r is gather[r]
+    const void* w_packed; int n_cols;      // pack_w32 order, n_cols % 64 == 0
+    uint16_t* out[2 * DG4_MAX_LAYERS + 3]; // column block j (256 columns) of row r at out[j] + r*out_stride
+    int64_t out_stride;
+    int64_t row_begin, row_end;
+};
+int dg4_launch_pack_w32(const void* w, int ld, int col0, int n_cols, void* packed, hipStream_t s);
+int dg4_launch_bulk_proj(const dg4_bulk_args& a, hipStream_t s);
