@@ -240,6 +240,28 @@ int dg4_graph_ensure_device(dg4_graph* g)
     const int w = 1 << (g->hops + 1);
     const size_t rows = (size_t)std::max<int64_t>(g->n, 1);
     try {
+        // Processing order of the device kernels. Levels stay in order; INSIDE a level the gates
+        // are sorted by the position of their latest-finished source, so that gates whose sources
+        // are old share tiles and only the last tiles of a level wait on the levels just before.
+        // (The published `order` table keeps (level, id); results do not depend on this.)
+        std::vector<int32_t> sweep((size_t)g->n);
+        {
+            std::vector<int64_t> key((size_t)g->n, -1);
+            for (int32_t l = 0; l <= g->max_level; ++l) {
+                const int64_t lo = g->level_ptr[l], hi = g->level_ptr[l + 1];
+                for (int64_t q = lo; q < hi; ++q) {
+                    const int32_t v = g->order[q];
+                    int64_t latest = -1;
+                    for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                        if (g->nbr_idx[j] != v) latest = std::max<int64_t>(latest, g->pos[g->nbr_idx[j]]);
+                    key[v] = latest;
+                    sweep[q] = v;
+                }
+                std::stable_sort(sweep.begin() + lo, sweep.begin() + hi,
+                                 [&](int32_t a, int32_t b) { return key[a] < key[b]; });
+                for (int64_t q = lo; q < hi; ++q) g->pos[sweep[q]] = (int32_t)q;   // sources of higher levels see these
+            }
+        }
         std::vector<uint32_t> by_id(rows * w, DG4_ELL_PAD), by_pos(rows * w, DG4_ELL_PAD);
         for (int64_t v = 0; v < g->n; ++v) {
             const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
@@ -280,7 +302,7 @@ int dg4_graph_ensure_device(dg4_graph* g)
         if (hipMemcpy(g->d_ell_id, by_id.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (hipMemcpy(g->d_ell_pos, by_pos.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (g->n > 0 &&
-            hipMemcpy(g->d_order, g->order.data(), (size_t)g->n * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
+            hipMemcpy(g->d_order, sweep.data(), (size_t)g->n * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
             return fail(DG4_EHIP);
     } catch (const std::bad_alloc&) {
         return DG4_ENOMEM;

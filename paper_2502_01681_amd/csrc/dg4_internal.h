@@ -21,7 +21,8 @@
 struct dg4_graph {
     int64_t n = 0, e = 0, nnz = 0;
     int32_t hops = 0, max_level = 0;
-    std::vector<int32_t> level, order, pos;      // pos[id] = position in `order`
+    std::vector<int32_t> level, order;           // order: ids by (level, id)
+    std::vector<int32_t> pos;                    // pos[id] = position in the device processing order (set at upload)
     std::vector<int64_t> level_ptr, nbr_ptr;
     std::vector<int32_t> nbr_idx;
     std::vector<uint8_t> nbr_rel;
@@ -33,7 +34,7 @@ struct dg4_graph {
     int ell_w = 0;
     uint32_t* d_ell_id = nullptr;    // [n, ell_w] rows and entries by node id
     uint32_t* d_ell_pos = nullptr;   // [n, ell_w] rows and entries by position
-    int32_t* d_order = nullptr;      // [n]
+    int32_t* d_order = nullptr;      // [n] position -> node id in the device processing order
     // tiles of the persistent sweep: runs of <= DG4_TILE_ROWS positions inside one level
     std::vector<int64_t> level_tile_ptr;   // [n_levels + 1] first tile of each level
     uint2* d_tiles = nullptr;        // [n_tiles] (first position, rows)

@@ -23,7 +23,7 @@
 #include "dg4_internal.h"
 
 #ifndef DG4_SWEEP_RESIDENT_TILES
-#define DG4_SWEEP_RESIDENT_TILES 5
+#define DG4_SWEEP_RESIDENT_TILES 6
 #endif
 
 namespace {
@@ -118,7 +118,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int grp = lane >> 4, sub = lane & 15;
-    constexpr int CH = W < 8 ? W : 8;         // sources whose K and V rows are in flight together
+    constexpr bool EARLY_K = W <= 8;          // gather the next tile's K rows during this tile's projections
     const int64_t eoff = (int64_t)sub * 16;   // attention role: this lane's 16 features of gate 4*wave+grp
     const int c0 = 64 * wave + 16 * grp;      // projection role: this lane's 16 columns of gate `sub`
 
@@ -151,145 +151,141 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             for (int i = 0; i < 8; ++i) atomicAdd((unsigned long long*)&p.prof[i], (unsigned long long)prof[i]);
     };
 
-    // What a tile needs that does not depend on other tiles, fetched one tile ahead: the
-    // neighbour row and the projected self rows of "my" gate (attention role), the residual
-    // row and node id of gate `sub` (projection role).
-    struct Ahead {
-        int64_t p0; int rows;
-        uint32_t ent[W];
-        uint4 q0, q1, ks0, ks1, vs0, vs1;
-        uint4 x0, x1;
-        int64_t orig;
-    };
-    auto fetch = [&](int64_t ticket, Ahead& a) {
-        const uint2 ti = p.tiles[p.tile_begin + ticket];
-        a.p0 = ti.x; a.rows = (int)ti.y;
+    // Inputs of a tile that do not depend on other tiles travel ahead of it: the descriptor and
+    // the neighbour row of "my" gate (attention role: gate 4*wave + grp) two tiles ahead, the
+    // projected self rows of that gate and the residual row of gate `sub` (projection role) one
+    // tile ahead.
+    struct Desc { int64_t p0; int rows; uint32_t ent[W]; };
+    struct Self { uint4 q0, q1, x0, x1; int64_t orig; };
+    auto fetch_desc = [&](int64_t t, Desc& d) __attribute__((always_inline)) {
+        const uint2 ti = p.tiles[p.tile_begin + t];
+        d.p0 = ti.x; d.rows = (int)ti.y;
         const int r = 4 * wave + grp;
-        const int64_t row = a.p0 + (r < a.rows ? r : 0);
-        const uint4* e4 = (const uint4*)(p.ell + row * W);
+        const uint4* e4 = (const uint4*)(p.ell + (d.p0 + (r < d.rows ? r : 0)) * W);
 #pragma unroll
         for (int i = 0; i < W / 4; ++i) {
-            const uint4 t = e4[i];
-            a.ent[4 * i] = t.x; a.ent[4 * i + 1] = t.y; a.ent[4 * i + 2] = t.z; a.ent[4 * i + 3] = t.w;
+            const uint4 v = e4[i];
+            d.ent[4 * i] = v.x; d.ent[4 * i + 1] = v.y; d.ent[4 * i + 2] = v.z; d.ent[4 * i + 3] = v.w;
         }
-        const uint4* sp = (const uint4*)(p.qkv_self + row * (3 * D) + eoff);
-        a.q0 = sp[0]; a.q1 = sp[1];
-        a.ks0 = sp[D / 8]; a.ks1 = sp[D / 8 + 1];
-        a.vs0 = sp[2 * D / 8]; a.vs1 = sp[2 * D / 8 + 1];
-        a.orig = p.order[a.p0 + (sub < a.rows ? sub : 0)];
-        const uint4* xp = (const uint4*)(p.x + a.orig * D + c0);
-        a.x0 = xp[0]; a.x1 = xp[1];
+    };
+    auto fetch_self = [&](const Desc& d, Self& f) __attribute__((always_inline)) {
+        const int r = 4 * wave + grp;
+        const uint4* sp = (const uint4*)(p.qkv_self + (d.p0 + (r < d.rows ? r : 0)) * (3 * D) + eoff);
+        f.q0 = sp[0]; f.q1 = sp[1];
+        f.orig = p.order[d.p0 + (sub < d.rows ? sub : 0)];
+        const uint4* xp = (const uint4*)(p.x + f.orig * D + c0);
+        f.x0 = xp[0]; f.x1 = xp[1];
+    };
+    // One look at the flags of my gate's sources (lane `sub` watches entry `sub`): true if some
+    // source of one of this wave's four gates is not published yet.
+    auto pending = [&](const Desc& d) __attribute__((always_inline)) -> bool {
+        uint32_t mine = DG4_ELL_PAD;
+#pragma unroll
+        for (int i = 0; i < W; ++i) if (sub == i) mine = d.ent[i];
+        const bool need = 4 * wave + grp < d.rows && mine != DG4_ELL_PAD && (mine >> 30) != 0;
+        const bool wait = need && __hip_atomic_load(p.flags + (mine & 0x3FFFFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
+        const bool any = __any(wait);
+        // No cache invalidation is needed once a flag is seen: a K|V row is written once per
+        // sweep, through to device memory, before its flag; nobody reads it earlier, so no cache
+        // of this compute unit or its L2 can hold an older copy. The fence only keeps the
+        // compiler from moving row loads above the flag loads.
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        return any;
+    };
+    // K (which = 0) or V (1) rows of my gate's sources. The gate itself reads the projection of
+    // its own x; padding slots read that row too (their weight is zero) so every lane always
+    // loads from a valid address.
+    auto gather = [&](const Desc& d, int which, uint4 (&ra)[W], uint4 (&rb)[W]) __attribute__((always_inline)) {
+        const int r = 4 * wave + grp;
+        const uint16_t* self = p.qkv_self + (d.p0 + (r < d.rows ? r : 0)) * (3 * D) + (1 + which) * D + eoff;
+#pragma unroll
+        for (int j = 0; j < W; ++j) {
+            const uint32_t e = d.ent[j];
+            const bool src = r < d.rows && e != DG4_ELL_PAD && (e >> 30) != 0;
+            const uint4* rp = (const uint4*)(src ? p.kv + (int64_t)(e & 0x3FFFFFFFu) * (2 * D) + which * D + eoff : self);
+            ra[j] = rp[0]; rb[j] = rp[1];
+        }
     };
 
     // Tiles are dealt round-robin: workgroup b owns tiles b, b + G, b + 2G, ... (G = grid size,
     // one workgroup per compute unit, so all of them are resident together). A tile waits only
     // for lower-numbered tiles, each owned by a workgroup that is running.
+    const int64_t G = gridDim.x;
     int64_t ticket = blockIdx.x;
     if (ticket >= p.n_tiles) return;
-    Ahead cur, nxt;
-    fetch(ticket, cur);
-    __syncthreads();                             // sWo, sAbort
+    Desc cur, nxt;
+    Self cself, nself;
+    // (tickets past the end are clamped: the fetch is harmless and its result unused)
+    const int64_t last = p.n_tiles - 1;
+    fetch_desc(ticket, cur);
+    fetch_desc(ticket + G < last ? ticket + G : last, nxt);
+    fetch_self(cur, cself);
+    uint4 ka[W], kb[W];                           // K rows of the tile about to be attended
+    bool k_ready = false;                         // ... already gathered (early, during the previous tile)
+    __syncthreads();                              // sWo, sAbort
 
     for (;;) {
         const int64_t p0 = cur.p0;
         const int rows = cur.rows;
-        const int64_t next_ticket = ticket + gridDim.x;
-        const bool has_next = next_ticket < p.n_tiles;
+        const bool has_next = ticket + G < p.n_tiles;
 
         // ---------------- attention: gate (4*wave + grp), lane owns 16 features
         {
             const int r = 4 * wave + grp;
             const bool valid = r < rows;
-            // wait until every source of this gate is published: lane `sub` watches entry `sub`
-            {
-                uint32_t mine = DG4_ELL_PAD;
-#pragma unroll
-                for (int i = 0; i < W; ++i) if (sub == i) mine = cur.ent[i];
-                bool need = valid && mine != DG4_ELL_PAD && (mine >> 30) != 0;
-                const uint32_t* f = p.flags + (mine & 0x3FFFFFFFu);
+            if (!k_ready) {
+                // wait until every source of this wave's gates is published
                 uint32_t spins = 0;
-                bool gave_up = false;
-                for (;;) {
-                    if (need && __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) need = false;
-                    if (!__any(need)) break;
+                while (pending(cur)) {
                     __builtin_amdgcn_s_sleep(1);
                     if (++spins > p.spin_limit ||
                         ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-                        gave_up = true;
+                        if (lane == 0) {
+                            __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                            sAbort = 1;
+                        }
                         break;
                     }
                 }
-                if (gave_up && lane == 0) {
-                    __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    sAbort = 1;
-                }
-                // No cache invalidation is needed after the wait: a K|V row is written once per
-                // sweep, through to device memory, before its flag; nobody reads it earlier, so
-                // no cache of this compute unit or its L2 can hold an older copy. The fence below
-                // only keeps the compiler from moving the row loads above the flag loads.
-                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                gather(cur, 0, ka, kb);
             }
             if (p.prof) __syncthreads();      // timers only: charge every wave's wait to phase 1
             lap(1);
+            uint4 va[W], vb[W];
+            gather(cur, 1, va, vb);
 
             float q[16];
-            Elem<bf16_t>::unpack(cur.q0, cur.q1, q);
+            Elem<bf16_t>::unpack(cself.q0, cself.q1, q);
             const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+            float s[W];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                float k[16];
+                Elem<bf16_t>::unpack(ka[j], kb[j], k);
+                float dot = 0.f;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) dot = fmaf(q[i], k[i], dot);
+                dot = Elem<bf16_t>::head_sum(dot);
+                const uint32_t rel = cur.ent[j] >> 30;
+                const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+                s[j] = cur.ent[j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
+                mx = fmaxf(mx, s[j]);
+            }
+            float z = 0.f;
+#pragma unroll
+            for (int j = 0; j < W; ++j) { s[j] = __expf(s[j] - mx); z += s[j]; }
+            const float rz = 1.0f / z;
             float acc[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-            float mx = -INFINITY, z = 0.f;
 #pragma unroll
-            for (int cb = 0; cb < W; cb += CH) {
-                // K and V rows of up to CH sources in flight together
-                uint4 ka[CH], kb[CH], va[CH], vb[CH];
+            for (int j = 0; j < W; ++j) {
+                float v[16];
+                Elem<bf16_t>::unpack(va[j], vb[j], v);
+                const float al = s[j] * rz;
 #pragma unroll
-                for (int j = 0; j < CH; ++j) {
-                    const uint32_t e = cur.ent[cb + j];
-                    if (valid && e != DG4_ELL_PAD && (e >> 30) != 0) {
-                        const uint4* kp = (const uint4*)(p.kv + (int64_t)(e & 0x3FFFFFFFu) * (2 * D) + eoff);
-                        ka[j] = kp[0]; kb[j] = kp[1]; va[j] = kp[D / 8]; vb[j] = kp[D / 8 + 1];
-                    } else {                  // the gate itself (its rows came with the prefetch) or padding
-                        ka[j] = cur.ks0; kb[j] = cur.ks1; va[j] = cur.vs0; vb[j] = cur.vs1;
-                    }
-                }
-                float s[CH];
-                float cmx = mx;
-#pragma unroll
-                for (int j = 0; j < CH; ++j) {
-                    float k[16];
-                    Elem<bf16_t>::unpack(ka[j], kb[j], k);
-                    float dot = 0.f;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) dot = fmaf(q[i], k[i], dot);
-                    dot = Elem<bf16_t>::head_sum(dot);
-                    const uint32_t rel = cur.ent[cb + j] >> 30;
-                    const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
-                    s[j] = cur.ent[cb + j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
-                    cmx = fmaxf(cmx, s[j]);
-                }
-                // online softmax: rescale what was accumulated under the old maximum
-                const float corr = __expf(mx - cmx);       // first chunk: exp(-inf) = 0
-                mx = cmx;
-                z *= corr;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] *= corr;
-#pragma unroll
-                for (int j = 0; j < CH; ++j) {
-                    float v[16];
-                    Elem<bf16_t>::unpack(va[j], vb[j], v);
-                    const float e = __expf(s[j] - mx);
-                    z += e;
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[i] = fmaf(e, v[i], acc[i]);
-                }
-                // keep the next chunk's loads below this point (register budget)
-                if (cb + CH < W) __builtin_amdgcn_sched_barrier(0);
-            }
-            {
-                const float rz = 1.0f / z;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] *= rz;
+                for (int i = 0; i < 16; ++i) acc[i] = fmaf(al, v[i], acc[i]);
             }
             uint4 oa, ob;
             if (valid) Elem<bf16_t>::pack(acc, oa, ob);
@@ -297,15 +293,20 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             uint4* dst = (uint4*)&sA[r][eoff];
             dst[0] = oa; dst[1] = ob;
         }
-        // the next tile's independent inputs and the non-resident weight tiles travel while this
-        // tile goes through the output projection
+        // ---------------- while this tile goes through its projections: the non-resident weight
+        // tiles, the next tile's self rows, a first look at its flags and, if they are all up,
+        // its K rows (gathered early, they overlap with the matrix work below)
         __builtin_amdgcn_sched_barrier(0);
         uint4 wkv_s[8 - RES][8];
 #pragma unroll
         for (int nt = RES; nt < 8; ++nt)
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) wkv_s[nt - RES][ks] = wkv[(nt * 8 + ks) * 64];
-        if (has_next) fetch(next_ticket, nxt);
+        fetch_self(nxt, nself);
+        k_ready = EARLY_K && has_next && !pending(nxt);
+        if (k_ready) gather(nxt, 0, ka, kb);
+        Desc nn;
+        fetch_desc(ticket + 2 * G < last ? ticket + 2 * G : last, nn);
         __syncthreads();
         if (sAbort) { flush(); return; }
         lap(2);
@@ -320,7 +321,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             for (int nt = 0; nt < 4; ++nt) acc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
             tile_gemm_lds<4>(sWo + wave * 4 * 8 * 64 + lane, &sA[n][8 * grp], acc);
             float x[16];
-            Elem<bf16_t>::unpack(cur.x0, cur.x1, x);
+            Elem<bf16_t>::unpack(cself.x0, cself.x1, x);
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
@@ -348,7 +349,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             uint4 ha, hb;
             Elem<bf16_t>::pack(t, ha, hb);
             if (nvalid) {
-                uint4* hp = (uint4*)(p.h_out + cur.orig * D + c0);
+                uint4* hp = (uint4*)(p.h_out + cself.orig * D + c0);
                 hp[0] = ha; hp[1] = hb;
             }
             uint4* hs = (uint4*)&sH[n][c0];
@@ -401,8 +402,12 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         lap(6);
 
         if (!has_next) { flush(); return; }
-        ticket = next_ticket;
-        cur = nxt;
+        ticket += G;
+        cur.p0 = nxt.p0; cur.rows = nxt.rows; nxt.p0 = nn.p0; nxt.rows = nn.rows;
+#pragma unroll
+        for (int i = 0; i < W; ++i) { cur.ent[i] = nxt.ent[i]; nxt.ent[i] = nn.ent[i]; }
+        cself.q0 = nself.q0; cself.q1 = nself.q1; cself.x0 = nself.x0; cself.x1 = nself.x1;
+        cself.orig = nself.orig;
     }
 }
 
