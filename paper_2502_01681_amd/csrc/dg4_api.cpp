@@ -226,7 +226,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     if (P0 > 0) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
     // One persistent dataflow kernel for the whole range of levels
-    if (dt == DG4_BF16 && d == 256 && L == 1 && !(cfg->flags & DG4_PER_LEVEL)) {
+    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & DG4_PER_LEVEL)) {
         {   // Q | K | V of x for every gate of the swept levels, level-sorted rows
             HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, 0, 3 * d, at(pl.wqkv[0]), s));
             dg4_bulk_args b{};

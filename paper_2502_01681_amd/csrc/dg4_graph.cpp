@@ -238,13 +238,14 @@ int dg4_graph_ensure_device(dg4_graph* g)
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return DG4_EHIP;
     const int w = 1 << (g->hops + 1);
-    const size_t rows = (size_t)std::max<int64_t>(g->n, 1);
+    // one tile of padding: the sweep kernel fetches descriptors of 16 positions at a time
+    const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
     try {
         // Processing order of the device kernels. Levels stay in order; INSIDE a level the gates
         // are sorted by the position of their latest-finished source, so that gates whose sources
         // are old share tiles and only the last tiles of a level wait on the levels just before.
         // (The published `order` table keeps (level, id); results do not depend on this.)
-        std::vector<int32_t> sweep((size_t)g->n);
+        std::vector<int32_t> sweep(rows, 0);
         {
             std::vector<int64_t> key((size_t)g->n, -1);
             for (int32_t l = 0; l <= g->max_level; ++l) {
@@ -302,7 +303,7 @@ int dg4_graph_ensure_device(dg4_graph* g)
         if (hipMemcpy(g->d_ell_id, by_id.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (hipMemcpy(g->d_ell_pos, by_pos.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (g->n > 0 &&
-            hipMemcpy(g->d_order, sweep.data(), (size_t)g->n * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
+            hipMemcpy(g->d_order, sweep.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
             return fail(DG4_EHIP);
     } catch (const std::bad_alloc&) {
         return DG4_ENOMEM;

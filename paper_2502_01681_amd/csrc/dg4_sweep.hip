@@ -22,53 +22,45 @@
 #include "dg4_device.h"
 #include "dg4_internal.h"
 
-#ifndef DG4_SWEEP_RESIDENT_TILES
-#define DG4_SWEEP_RESIDENT_TILES 6
-#endif
-
 namespace {
 
 typedef __bf16 bf16x8s __attribute__((ext_vector_type(8)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 constexpr int TILE = DG4_TILE_ROWS;   // 16
 constexpr int D = 256;
 constexpr int LDS_STRIDE = D + 8;     // bf16 elements per LDS row (16 bytes of padding)
 constexpr int KV_STRIDE = 2 * D + 8;
-constexpr int RES = DG4_SWEEP_RESIDENT_TILES;   // column tiles of Wk|Wv (of 8 per wave) kept in registers
-constexpr int SMEM_WO = D * D * 2;                                  // 128 KB
-constexpr int SMEM_TILE = 3 * TILE * LDS_STRIDE * 2;                // sA, sX (spare), sH; sKV overlays sA + sX
+// LDS map (bytes): three row buffers (sKV overlays the first two), LayerNorm partial sums, for
+// this tile and the next the packed neighbour rows followed by the node ids (one contiguous
+// block per parity, filled by a single gather), the abort word, timers, then the landing zone:
+// per gate 8 KB = six source slots of K|V (1 KB each), the gate's own Q|K|V rows (1.5 KB) and
+// its residual row (512 B).
+constexpr int SMEM_TILE = 3 * TILE * LDS_STRIDE * 2;                // sA, sX (spare), sH
 static_assert(TILE * KV_STRIDE * 2 <= 2 * TILE * LDS_STRIDE * 2, "sKV must fit over sA and sX");
-constexpr int SMEM_BYTES = SMEM_WO + SMEM_TILE + TILE * 4 * 2 * 4 + 16;
+constexpr int SMEM_RED = SMEM_TILE;
+constexpr int SMEM_DESC = SMEM_RED + TILE * 4 * 2 * 4;              // [2 parities][ent 16 x 8 words | ids 16 words]
+constexpr int DESC_BYTES = TILE * 8 * 4 + TILE * 4;                 // 576
+constexpr int SMEM_ABORT = SMEM_DESC + 2 * DESC_BYTES;
+constexpr int SMEM_PROF = SMEM_ABORT + 16;
+constexpr int SMEM_BIAS = SMEM_PROF + 64;                          // rel_bias [8 heads][4]
+constexpr int SMEM_WOF = SMEM_BIAS + 128;                           // one Wo fragment per wave (4 x 1 KB)
+constexpr int SMEM_LAND = SMEM_WOF + 4096;
+constexpr int LAND_GATE = 8192, LAND_SELF = 6144, LAND_X = 7680;
+constexpr int SMEM_BYTES = SMEM_LAND + TILE * LAND_GATE;
+static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+static_assert(SMEM_LAND % 16 == 0 && SMEM_DESC % 16 == 0 && DESC_BYTES % 16 == 0, "alignment");
+
+typedef __bf16 bf16x2s __attribute__((ext_vector_type(2)));
+// sum += a.lo*b.lo + a.hi*b.hi on packed bf16 pairs, fp32 accumulation
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float sum)
+{
+    return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2s, a), __builtin_bit_cast(bf16x2s, b), sum, false);
+}
 
 __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, f32x4 c)
 {
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8s, a), __builtin_bit_cast(bf16x8s, b), c, 0, 0, 0);
-}
-
-// acc[nt] += W_tile(nt) x tile, for the NT column tiles of one wave. The weight fragments
-// (A operand) live in REGISTERS for the whole kernel: a workgroup of four waves holds the
-// complete Wo (128 registers per lane) and Wk|Wv (256 per lane), so a tile costs no weight
-// traffic at all. The gate rows (B operand) come from LDS.
-template <int NT>
-__device__ __forceinline__ void tile_gemm(const uint4 (&w)[NT][8], const uint16_t* __restrict__ brow, f32x4 (&acc)[NT])
-{
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const uint4 b = *(const uint4*)(brow + ks * 32);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma16(w[nt][ks], b, acc[nt]);
-    }
-}
-// Same with the weight fragments in LDS (`w` already offset to this wave and lane).
-template <int NT>
-__device__ __forceinline__ void tile_gemm_lds(const uint4* __restrict__ w, const uint16_t* __restrict__ brow, f32x4 (&acc)[NT])
-{
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        const uint4 b = *(const uint4*)(brow + ks * 32);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) acc[nt] = mfma16(w[(nt * 8 + ks) * 64], b, acc[nt]);
-    }
 }
 
 // Packed order for weights used as the A operand of a 16x16x32 MFMA, in
@@ -101,110 +93,150 @@ __global__ void sweep_init_kernel(uint32_t* flags, int64_t n, int64_t done_below
     if (i < 64) ctrl[i] = 0u;                     // [0] ticket, [1] abort, [16..31] phase timers
 }
 
-template <int W>
+template <int W, bool TIMERS>
 __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 {
-    // LDS: Wo in A-operand order (128 KB), then three row buffers. sKV (the tile's K|V rows on
-    // their way out) overlays sA and sX, both dead by then; sH stays separate so that the K|V
-    // projection can read it while sKV is being written.
+    static_assert(W == 8, "the landing zone is laid out for cones of two hops");
+    constexpr int NS = W - 2;                 // most sources a gate can have besides itself (6)
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    uint4* sWo = (uint4*)smem;                                                       // [4*4*8*64]
-    uint16_t (*sA)[LDS_STRIDE] = (uint16_t (*)[LDS_STRIDE])(smem + SMEM_WO);         // attention output, bf16
+    uint16_t (*sA)[LDS_STRIDE] = (uint16_t (*)[LDS_STRIDE])smem;                     // attention output, bf16
     uint16_t (*sH)[LDS_STRIDE] = sA + 2 * TILE;                                      // new embeddings, bf16
-    uint16_t (*sKV)[KV_STRIDE] = (uint16_t (*)[KV_STRIDE])(smem + SMEM_WO);          // K|V rows, bf16
-    float (*sRed)[4][2] = (float (*)[4][2])(smem + SMEM_WO + SMEM_TILE);
-    int& sAbort = *(int*)(smem + SMEM_WO + SMEM_TILE + TILE * 4 * 2 * sizeof(float));
+    uint16_t (*sKV)[KV_STRIDE] = (uint16_t (*)[KV_STRIDE])smem;                      // K|V rows on their way out
+    float (*sRed)[4][2] = (float (*)[4][2])(smem + SMEM_RED);
+    int& sAbort = *(int*)(smem + SMEM_ABORT);
+    unsigned char* sLand = smem + SMEM_LAND;
+    // neighbour rows [gate][entry] and node ids [gate] of the tile with the given parity
+    auto ent_of = [&](int parity) __attribute__((always_inline)) { return (const uint32_t (*)[8])(smem + SMEM_DESC + parity * DESC_BYTES); };
+    auto ids_of = [&](int parity) __attribute__((always_inline)) { return (const int32_t*)(smem + SMEM_DESC + parity * DESC_BYTES + TILE * 8 * 4); };
 
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int grp = lane >> 4, sub = lane & 15;
-    constexpr bool EARLY_K = W <= 8;          // gather the next tile's K rows during this tile's projections
-    const int64_t eoff = (int64_t)sub * 16;   // attention role: this lane's 16 features of gate 4*wave+grp
-    const int c0 = 64 * wave + 16 * grp;      // projection role: this lane's 16 columns of gate `sub`
+    const int my = 4 * wave + grp;            // attention role: this lane holds 16 features of gate `my`
+    const int c0 = 64 * wave + 16 * grp;      // projection role: this lane holds 16 columns of gate `sub`
 
-    // weights, loaded once: Wo into LDS; of this wave's 8 column tiles of Wk|Wv, RES stay in
-    // registers for the whole kernel, the other 8-RES are re-read from L2 once per tile (after
-    // the attention phase has released its registers).
-    const uint4* wkv = (const uint4*)p.wkv_packed + (int64_t)wave * 8 * 8 * 64 + lane;
-    uint4 wkv_r[RES][8];
+    // The weights of this wave stay in registers for the whole kernel: its 4 column tiles of Wo
+    // (128 vector registers) and its 8 column tiles of Wk|Wv (all 256 accumulation registers,
+    // which the matrix cores read directly). Everything else below is written to need few
+    // registers: every row a tile needs is gathered into LDS, not into registers.
+    u32x4 wo_r[4][8];
+    u32x4 wkv_r[8][8];
     {
-        const uint4* wo = (const uint4*)p.wo_packed;
-        for (int i = threadIdx.x; i < 4 * 4 * 8 * 64; i += 256) sWo[i] = wo[i];
+        const uint4* wo = (const uint4*)p.wo_packed + (int64_t)wave * 4 * 8 * 64 + lane;
+        const uint4* wkv = (const uint4*)p.wkv_packed + (int64_t)wave * 8 * 8 * 64 + lane;
 #pragma unroll
-        for (int nt = 0; nt < RES; ++nt)
+        for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) wkv_r[nt][ks] = wkv[(nt * 8 + ks) * 64];
+            for (int ks = 0; ks < 8; ++ks) wo_r[nt][ks] = __builtin_bit_cast(u32x4, wo[(nt * 8 + ks) * 64]);
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) wkv_r[nt][ks] = __builtin_bit_cast(u32x4, wkv[(nt * 8 + ks) * 64]);
     }
-    float bias[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[(sub >> 1) * 4 + i];
+    // (the last fragment of Wo and the bias table sit in LDS: the register file is full)
+    const float* sBias = (const float*)(smem + SMEM_BIAS) + (sub >> 1) * 4;          // this lane's head
+    const uint4* sWoF = (const uint4*)(smem + SMEM_WOF) + wave * 64 + lane;
+    if (threadIdx.x < 32) ((float*)(smem + SMEM_BIAS))[threadIdx.x] = p.rel_bias[threadIdx.x];
+    ((uint4*)(smem + SMEM_WOF))[wave * 64 + lane] = __builtin_bit_cast(uint4, wo_r[3][7]);
     if (threadIdx.x == 0) sAbort = 0;
 
     // optional phase timers (thread 0, constant-rate clock): -, wait, attention, Wo, LN, KV, publish
-    uint64_t prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};
-    uint64_t tick = p.prof ? wall_clock64() : 0;
-    auto lap = [&](int phase) {
-        if (p.prof && threadIdx.x == 0) { const uint64_t now = wall_clock64(); prof[phase] += now - tick; tick = now; }
+    // (accumulated in LDS so that the timed build needs no more registers than the plain one)
+    uint64_t* sProf = (uint64_t*)(smem + SMEM_PROF);
+    uint64_t tick = 0;
+    if (TIMERS && threadIdx.x == 0) {
+        for (int i = 0; i < 8; ++i) sProf[i] = 0;
+        tick = wall_clock64();
+    }
+    auto lap = [&](int phase) __attribute__((always_inline)) {
+        if (TIMERS && threadIdx.x == 0) { const uint64_t now = wall_clock64(); sProf[phase] += now - tick; tick = now; }
     };
-    auto flush = [&]() {
-        if (p.prof && threadIdx.x == 0)
-            for (int i = 0; i < 8; ++i) atomicAdd((unsigned long long*)&p.prof[i], (unsigned long long)prof[i]);
+    auto flush = [&]() __attribute__((always_inline)) {
+        if (TIMERS && threadIdx.x == 0)
+            for (int i = 0; i < 8; ++i) atomicAdd((unsigned long long*)&p.prof[i], (unsigned long long)sProf[i]);
     };
 
-    // Inputs of a tile that do not depend on other tiles travel ahead of it: the descriptor and
-    // the neighbour row of "my" gate (attention role: gate 4*wave + grp) two tiles ahead, the
-    // projected self rows of that gate and the residual row of gate `sub` (projection role) one
-    // tile ahead.
-    struct Desc { int64_t p0; int rows; uint32_t ent[W]; };
-    struct Self { uint4 q0, q1, x0, x1; int64_t orig; };
-    auto fetch_desc = [&](int64_t t, Desc& d) __attribute__((always_inline)) {
-        const uint2 ti = p.tiles[p.tile_begin + t];
-        d.p0 = ti.x; d.rows = (int)ti.y;
-        const int r = 4 * wave + grp;
-        const uint4* e4 = (const uint4*)(p.ell + (d.p0 + (r < d.rows ? r : 0)) * W);
-#pragma unroll
-        for (int i = 0; i < W / 4; ++i) {
-            const uint4 v = e4[i];
-            d.ent[4 * i] = v.x; d.ent[4 * i + 1] = v.y; d.ent[4 * i + 2] = v.z; d.ent[4 * i + 3] = v.w;
+    // All gathers go straight from global memory into LDS, 16 bytes per lane, no registers.
+    // (1) what describes a tile: the packed neighbour rows of its 16 positions (512 B) and
+    //     their node ids (64 B), one instruction, issued by wave 0. Both tables are padded by
+    //     one tile on the host, so a ragged last tile reads valid memory.
+    auto gather_desc = [&](int64_t p0, int parity) __attribute__((always_inline)) {
+        if (wave == 0 && lane < 36) {
+            const void* src = lane < 32 ? (const void*)(p.ell + p0 * W + lane * 4) : (const void*)(p.order + p0 + (lane - 32) * 4);
+            __builtin_amdgcn_global_load_lds(src, (uint32_t*)(smem + SMEM_DESC + parity * DESC_BYTES), 16, 0, 0);
         }
     };
-    auto fetch_self = [&](const Desc& d, Self& f) __attribute__((always_inline)) {
-        const int r = 4 * wave + grp;
-        const uint4* sp = (const uint4*)(p.qkv_self + (d.p0 + (r < d.rows ? r : 0)) * (3 * D) + eoff);
-        f.q0 = sp[0]; f.q1 = sp[1];
-        f.orig = p.order[d.p0 + (sub < d.rows ? sub : 0)];
-        const uint4* xp = (const uint4*)(p.x + f.orig * D + c0);
-        f.x0 = xp[0]; f.x1 = xp[1];
-    };
-    // One look at the flags of my gate's sources (lane `sub` watches entry `sub`): true if some
-    // source of one of this wave's four gates is not published yet.
-    auto pending = [&](const Desc& d) __attribute__((always_inline)) -> bool {
-        uint32_t mine = DG4_ELL_PAD;
+    // (2) rows that depend on nobody else: a gate's own Q|K|V (1.5 KB) and its residual row
+    auto gather_own = [&](int64_t p0, int rows, int parity) __attribute__((always_inline)) {
 #pragma unroll
-        for (int i = 0; i < W; ++i) if (sub == i) mine = d.ent[i];
-        const bool need = 4 * wave + grp < d.rows && mine != DG4_ELL_PAD && (mine >> 30) != 0;
-        const bool wait = need && __hip_atomic_load(p.flags + (mine & 0x3FFFFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u;
-        const bool any = __any(wait);
+        for (int gq = 0; gq < 4; ++gq) {
+            const int g = 4 * wave + gq;
+            if (g >= rows) continue;
+            const int64_t orig = __builtin_amdgcn_readfirstlane(ids_of(parity)[g]);
+            const uint16_t* self = p.qkv_self + (p0 + g) * (3 * D);
+            unsigned char* dst = sLand + g * LAND_GATE + LAND_SELF;
+            __builtin_amdgcn_global_load_lds(self + lane * 8, (uint32_t*)dst, 16, 0, 0);                       // Q | K
+            const uint16_t* tail = lane < 32 ? self + 2 * D + lane * 8 : p.x + orig * D + (lane - 32) * 8;   // V | x
+            __builtin_amdgcn_global_load_lds(tail, (uint32_t*)(dst + 1024), 16, 0, 0);
+        }
+    };
+    // (3) the K|V kilobyte of a source: one instruction per (gate, source). `take` has bit
+    //     16*gq + j set for entry j of this wave's gate gq if that source is to be fetched now;
+    //     `need` marks all entries that are sources. Slot s of a gate holds its s-th source.
+    //     `e_mine` is entry `sub` of gate `my` as held by each lane.
+    auto gather_src = [&](uint32_t e_mine, uint64_t take, uint64_t need) __attribute__((always_inline)) {
+        const uint16_t* lane_base = p.kv + lane * 8;
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const int g = 4 * wave + gq;
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                if ((take >> (16 * gq + j)) & 1) {
+                    const int slot = __builtin_popcountll(need & (((1ull << j) - 1) << (16 * gq)));
+                    const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)e_mine, 16 * gq + j);
+                    if (slot < NS)
+                        __builtin_amdgcn_global_load_lds(lane_base + (int64_t)(e & 0x3FFFFFFFu) * (2 * D),
+                                                         (uint32_t*)(sLand + g * LAND_GATE + slot * 1024), 16, 0, 0);
+                }
+            }
+        }
+    };
+    // The sources of this wave's gates: lane (grp, sub) watches entry `sub` of gate `my`.
+    // Returns the ballot of lanes whose entry is a source; `*up` gets those whose flag is raised.
+    auto look = [&](int parity, int rows, uint64_t* up, uint32_t* e_mine) __attribute__((always_inline)) -> uint64_t {
+        const uint32_t e = sub < W ? ent_of(parity)[my][sub] : DG4_ELL_PAD;
+        *e_mine = e;
+        const bool need = my < rows && e != DG4_ELL_PAD && (e >> 30) != 0;
+        const bool ok = need && __hip_atomic_load(p.flags + (e & 0x3FFFFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
+        *up = __ballot(ok);
         // No cache invalidation is needed once a flag is seen: a K|V row is written once per
         // sweep, through to device memory, before its flag; nobody reads it earlier, so no cache
         // of this compute unit or its L2 can hold an older copy. The fence only keeps the
         // compiler from moving row loads above the flag loads.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        return any;
+        return __ballot(need);
     };
-    // K (which = 0) or V (1) rows of my gate's sources. The gate itself reads the projection of
-    // its own x; padding slots read that row too (their weight is zero) so every lane always
-    // loads from a valid address.
-    auto gather = [&](const Desc& d, int which, uint4 (&ra)[W], uint4 (&rb)[W]) __attribute__((always_inline)) {
-        const int r = 4 * wave + grp;
-        const uint16_t* self = p.qkv_self + (d.p0 + (r < d.rows ? r : 0)) * (3 * D) + (1 + which) * D + eoff;
-#pragma unroll
-        for (int j = 0; j < W; ++j) {
-            const uint32_t e = d.ent[j];
-            const bool src = r < d.rows && e != DG4_ELL_PAD && (e >> 30) != 0;
-            const uint4* rp = (const uint4*)(src ? p.kv + (int64_t)(e & 0x3FFFFFFFu) * (2 * D) + which * D + eoff : self);
-            ra[j] = rp[0]; rb[j] = rp[1];
+    // Block until the sources in `late` are published, then fetch them.
+    auto wait_and_gather = [&](int parity, int rows, uint64_t late, uint64_t need) __attribute__((always_inline)) {
+        uint32_t spins = 0;
+        uint32_t e_mine = DG4_ELL_PAD;
+        for (;;) {
+            uint64_t up;
+            (void)look(parity, rows, &up, &e_mine);
+            if ((late & ~up) == 0) break;
+            __builtin_amdgcn_s_sleep(1);
+            if (++spins > p.spin_limit ||
+                ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                if (lane == 0) {
+                    __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    sAbort = 1;
+                }
+                break;
+            }
         }
+        gather_src(e_mine, late, need);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __asm__ volatile("" ::: "memory");
     };
 
     // Tiles are dealt round-robin: workgroup b owns tiles b, b + G, b + 2G, ... (G = grid size,
@@ -213,120 +245,164 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     const int64_t G = gridDim.x;
     int64_t ticket = blockIdx.x;
     if (ticket >= p.n_tiles) return;
-    Desc cur, nxt;
-    Self cself, nself;
     // (tickets past the end are clamped: the fetch is harmless and its result unused)
     const int64_t last = p.n_tiles - 1;
-    fetch_desc(ticket, cur);
-    fetch_desc(ticket + G < last ? ticket + G : last, nxt);
-    fetch_self(cur, cself);
-    uint4 ka[W], kb[W];                           // K rows of the tile about to be attended
-    bool k_ready = false;                         // ... already gathered (early, during the previous tile)
-    __syncthreads();                              // sWo, sAbort
+    int parity = 0;
+    uint2 cur = p.tiles[p.tile_begin + ticket];                                      // first position, rows
+    uint2 nxt = p.tiles[p.tile_begin + (ticket + G < last ? ticket + G : last)];
+    uint64_t late = 0, need_cur = 0;              // sources of the current tile not gathered yet / all of them
+    {
+        gather_desc(cur.x, 0);
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        __syncthreads();                          // sAbort, descriptor of the first tile
+        gather_own(cur.x, (int)cur.y, 0);
+        uint64_t up;
+        uint32_t e0;
+        need_cur = look(0, (int)cur.y, &up, &e0);
+        late = need_cur;                          // the first tile fetches all its sources at the top of the loop
+    }
+    int64_t pub_p0 = 0;                           // rows 4*wave .. of the previous tile still to be published
+    int pub_rows = 0;
 
     for (;;) {
-        const int64_t p0 = cur.p0;
-        const int rows = cur.rows;
+        // keep the Wk|Wv tiles in the accumulation registers
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) __asm__ volatile("" : "+a"(wkv_r[nt][ks]));
+
+        const int64_t p0 = cur.x;
+        const int rows = (int)cur.y;
         const bool has_next = ticket + G < p.n_tiles;
 
-        // ---------------- attention: gate (4*wave + grp), lane owns 16 features
-        {
-            const int r = 4 * wave + grp;
-            const bool valid = r < rows;
-            if (!k_ready) {
-                // wait until every source of this wave's gates is published
-                uint32_t spins = 0;
-                while (pending(cur)) {
-                    __builtin_amdgcn_s_sleep(1);
-                    if (++spins > p.spin_limit ||
-                        ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-                        if (lane == 0) {
-                            __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                            sAbort = 1;
-                        }
-                        break;
-                    }
-                }
-                gather(cur, 0, ka, kb);
-            }
-            if (p.prof) __syncthreads();      // timers only: charge every wave's wait to phase 1
-            lap(1);
-            uint4 va[W], vb[W];
-            gather(cur, 1, va, vb);
+        // ---------------- publish the previous tile. Loads and stores of a wave complete in order,
+        // so one wait covers both the K|V row stores of the previous tile (complete = written
+        // through, visible to every compute unit) and the gathers of this tile issued behind
+        // them. Each wave raises the flags of the four rows it stored itself. This happens
+        // before any blocking wait below: other workgroups may be waiting for these rows.
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
+        __asm__ volatile("" ::: "memory");
+        if (lane < 4 && 4 * wave + lane < pub_rows)
+            __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lap(6);
+        // sources that were not published yet when this tile's gathers went out
+        if (late) wait_and_gather(parity, rows, late, need_cur);
+        if (TIMERS) __syncthreads();          // timers only: charge every wave's wait to phase 1
+        lap(1);
+        // the next tile's descriptor travels during the attention below
+        gather_desc(nxt.x, parity ^ 1);
+        const uint2 nn = p.tiles[p.tile_begin + (ticket + 2 * G < last ? ticket + 2 * G : last)];
 
-            float q[16];
-            Elem<bf16_t>::unpack(cself.q0, cself.q1, q);
-            const float scale = 0.17677669529663687f;     // 1/sqrt(32)
-            float s[W];
-            float mx = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < W; ++j) {
-                float k[16];
-                Elem<bf16_t>::unpack(ka[j], kb[j], k);
-                float dot = 0.f;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) dot = fmaf(q[i], k[i], dot);
-                dot = Elem<bf16_t>::head_sum(dot);
-                const uint32_t rel = cur.ent[j] >> 30;
-                const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
-                s[j] = cur.ent[j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
-                mx = fmaxf(mx, s[j]);
+        // ---------------- attention: gate `my`, lane owns 16 features. Two entries per round so
+        // that their LDS reads overlap; softmax kept online (running maximum, rescaled sums).
+        {
+            const bool valid = my < rows;
+            const unsigned char* land = sLand + my * LAND_GATE + sub * 32;
+            uint32_t q[8];
+            {
+                const uint4* qp = (const uint4*)(land + LAND_SELF);
+                const uint4 a = qp[0], b = qp[1];
+                q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
             }
-            float z = 0.f;
-#pragma unroll
-            for (int j = 0; j < W; ++j) { s[j] = __expf(s[j] - mx); z += s[j]; }
-            const float rz = 1.0f / z;
+            const float scale = 0.17677669529663687f;     // 1/sqrt(32)
             float acc[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            float mx = -INFINITY, z = 0.f;
+            int slot = 0;
+#pragma unroll 1
+            for (int j = 0; j < W; j += 2) {
+                const uint2 e2 = *(const uint2*)&ent_of(parity)[my][j];
+                const uint32_t ea = e2.x, eb = e2.y;
+                if (ea == DG4_ELL_PAD) break;             // entries are packed from slot 0
+                const bool sa = (ea >> 30) != 0 && slot < NS;
+                const uint4* ka = (const uint4*)(land + (sa ? slot * 1024 : LAND_SELF + 512));    // V sits 512 bytes after K
+                if (sa) ++slot;
+                const bool sb = eb != DG4_ELL_PAD && (eb >> 30) != 0 && slot < NS;
+                const uint4* kb = (const uint4*)(land + (sb ? slot * 1024 : LAND_SELF + 512));
+                if (sb) ++slot;
+                const uint4 ka0 = ka[0], ka1 = ka[1], va0 = ka[32], va1 = ka[33];
+                const uint4 kb0 = kb[0], kb1 = kb[1], vb0 = kb[32], vb1 = kb[33];
+                float da = 0.f, db = 0.f;
+                da = dot2_bf16(q[0], ka0.x, da); db = dot2_bf16(q[0], kb0.x, db);
+                da = dot2_bf16(q[1], ka0.y, da); db = dot2_bf16(q[1], kb0.y, db);
+                da = dot2_bf16(q[2], ka0.z, da); db = dot2_bf16(q[2], kb0.z, db);
+                da = dot2_bf16(q[3], ka0.w, da); db = dot2_bf16(q[3], kb0.w, db);
+                da = dot2_bf16(q[4], ka1.x, da); db = dot2_bf16(q[4], kb1.x, db);
+                da = dot2_bf16(q[5], ka1.y, da); db = dot2_bf16(q[5], kb1.y, db);
+                da = dot2_bf16(q[6], ka1.z, da); db = dot2_bf16(q[6], kb1.z, db);
+                da = dot2_bf16(q[7], ka1.w, da); db = dot2_bf16(q[7], kb1.w, db);
+                da = Elem<bf16_t>::head_sum(da); db = Elem<bf16_t>::head_sum(db);
+                const uint32_t ra = ea >> 30, rb = eb >> 30;
+                const float ba = sBias[ra], bb = sBias[rb];
+                const float sca = fmaf(da, scale, ba);
+                const float scb = eb != DG4_ELL_PAD ? fmaf(db, scale, bb) : -INFINITY;   // padding: weight exp(-inf) = 0
+                const float nm = fmaxf(mx, fmaxf(sca, scb));
+                const float corr = __expf(mx - nm);       // first round: exp(-inf) = 0
+                const float pa = __expf(sca - nm), pb = __expf(scb - nm);
+                mx = nm;
+                z = fmaf(z, corr, pa + pb);
+                float va[16], vb[16];
+                Elem<bf16_t>::unpack(va0, va1, va);
+                Elem<bf16_t>::unpack(vb0, vb1, vb);
 #pragma unroll
-            for (int j = 0; j < W; ++j) {
-                float v[16];
-                Elem<bf16_t>::unpack(va[j], vb[j], v);
-                const float al = s[j] * rz;
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = fmaf(al, v[i], acc[i]);
+                for (int i = 0; i < 16; ++i) acc[i] = fmaf(acc[i], corr, fmaf(pa, va[i], pb * vb[i]));
             }
+            const float rz = 1.0f / z;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[i] *= rz;
             uint4 oa, ob;
             if (valid) Elem<bf16_t>::pack(acc, oa, ob);
             else { oa = make_uint4(0, 0, 0, 0); ob = oa; }
-            uint4* dst = (uint4*)&sA[r][eoff];
+            uint4* dst = (uint4*)&sA[my][sub * 16];
             dst[0] = oa; dst[1] = ob;
         }
-        // ---------------- while this tile goes through its projections: the non-resident weight
-        // tiles, the next tile's self rows, a first look at its flags and, if they are all up,
-        // its K rows (gathered early, they overlap with the matrix work below)
-        __builtin_amdgcn_sched_barrier(0);
-        uint4 wkv_s[8 - RES][8];
-#pragma unroll
-        for (int nt = RES; nt < 8; ++nt)
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) wkv_s[nt - RES][ks] = wkv[(nt * 8 + ks) * 64];
-        fetch_self(nxt, nself);
-        k_ready = EARLY_K && has_next && !pending(nxt);
-        if (k_ready) gather(nxt, 0, ka, kb);
-        Desc nn;
-        fetch_desc(ticket + 2 * G < last ? ticket + 2 * G : last, nn);
-        __syncthreads();
+        if (wave == 0) { __builtin_amdgcn_s_waitcnt(0x0F70); __asm__ volatile("" ::: "memory"); }   // next descriptor has landed
+        __syncthreads();                      // sA and the next descriptor complete; every wave is done with its source slots
         if (sAbort) { flush(); return; }
         lap(2);
+        // a first look at the next tile's flags, answered while the matrix cores work below
+        bool nneed = false;
+        uint32_t nflag = 0, nent = DG4_ELL_PAD;
+        if (has_next) {
+            nent = sub < W ? ent_of(parity ^ 1)[my][sub] : DG4_ELL_PAD;
+            nneed = my < (int)nxt.y && nent != DG4_ELL_PAD && (nent >> 30) != 0;
+            if (nneed) nflag = __hip_atomic_load(p.flags + (nent & 0x3FFFFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
 
         // ---------------- output projection; lane (n = sub, g = grp) owns columns 64*wave + 16*g .. +15 of gate n
         const int n = sub;
         const bool nvalid = n < rows;
         float t[16];
+        uint64_t need_nxt, up_nxt;
         {
             f32x4 acc[4];
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt) acc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            tile_gemm_lds<4>(sWo + wave * 4 * 8 * 64 + lane, &sA[n][8 * grp], acc);
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+                const uint4 b = *(const uint4*)&sA[n][8 * grp + ks * 32];
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    acc[nt] = mfma16(nt == 3 && ks == 7 ? *sWoF : __builtin_bit_cast(uint4, wo_r[nt][ks]), b, acc[nt]);
+            }
+            // the next tile's published sources start to travel now and overlap the rest of this
+            // tile (issued here so that the address arithmetic runs while the matrix cores work)
+            need_nxt = __ballot(nneed); up_nxt = __ballot(nneed && nflag != 0u);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");     // row gathers stay below the flag loads
+            if (has_next) gather_src(nent, up_nxt, need_nxt);
+            if (TIMERS && threadIdx.x == 0 && (need_nxt & ~up_nxt)) sProf[0] += 1;   // tiles with a late source
             float x[16];
-            Elem<bf16_t>::unpack(cself.x0, cself.x1, x);
+            {
+                const uint4* xp = (const uint4*)(sLand + n * LAND_GATE + LAND_X + c0 * 2);
+                Elem<bf16_t>::unpack(xp[0], xp[1], x);
+            }
 #pragma unroll
             for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) t[nt * 4 + i] = acc[nt][i] + (p.epilogue ? x[nt * 4 + i] : 0.f);
         }
+        const int64_t orig_n = ids_of(parity)[nvalid ? n : 0];
         lap(3);
         if (p.epilogue) {
             float s1 = 0.f, s2 = 0.f;
@@ -349,14 +425,16 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             uint4 ha, hb;
             Elem<bf16_t>::pack(t, ha, hb);
             if (nvalid) {
-                uint4* hp = (uint4*)(p.h_out + cself.orig * D + c0);
+                uint4* hp = (uint4*)(p.h_out + orig_n * D + c0);
                 hp[0] = ha; hp[1] = hb;
             }
             uint4* hs = (uint4*)&sH[n][c0];
             hs[0] = ha; hs[1] = hb;
         }
-        __syncthreads();
+        __syncthreads();                      // sH complete; every wave has read its residual rows
         lap(4);
+        // the landing zone of the gates' own rows is free now: the next tile's may come in
+        if (has_next) gather_own(nxt.x, (int)nxt.y, parity ^ 1);
 
         // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
         {
@@ -367,9 +445,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             for (int ks = 0; ks < 8; ++ks) {
                 const uint4 b = *(const uint4*)&sH[n][8 * grp + ks * 32];
 #pragma unroll
-                for (int nt = 0; nt < RES; ++nt) acc[nt] = mfma16(wkv_r[nt][ks], b, acc[nt]);
-#pragma unroll
-                for (int nt = RES; nt < 8; ++nt) acc[nt] = mfma16(wkv_s[nt - RES][ks], b, acc[nt]);
+                for (int nt = 0; nt < 8; ++nt) acc[nt] = mfma16(__builtin_bit_cast(uint4, wkv_r[nt][ks]), b, acc[nt]);
             }
             uint4* dst = (uint4*)&sKV[n][128 * wave + 32 * grp];
 #pragma unroll
@@ -379,8 +455,9 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                                     pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3]));
             }
             __syncthreads();
-            // wave w writes rows 4w..4w+3, 512 contiguous bytes per instruction. Device-scope
-            // stores: written through the L2 of this XCD; complete = visible to every compute unit.
+            // wave w writes rows 4w..4w+3, 512 contiguous bytes per instruction, as device-scope
+            // stores (written through the L2 of this XCD). Their flags follow at the top of the
+            // next round, once the stores have completed.
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = 4 * wave + rr;
@@ -392,22 +469,22 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 }
             }
         }
-        // ---------------- publish: every wave first waits until its own row stores have completed
-        // (vmcnt(0); the barrier alone does not wait for global stores), then the flags go out
-        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
-        __syncthreads();
+        __syncthreads();                      // sKV has been read; sA may be written again
         lap(5);
-        if (wave == 0 && lane < rows)
-            __hip_atomic_store(&p.flags[p0 + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        lap(6);
+        pub_p0 = p0; pub_rows = rows;
 
-        if (!has_next) { flush(); return; }
+        if (!has_next) {
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __asm__ volatile("" ::: "memory");
+            if (lane < 4 && 4 * wave + lane < pub_rows)
+                __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            flush();
+            return;
+        }
         ticket += G;
-        cur.p0 = nxt.p0; cur.rows = nxt.rows; nxt.p0 = nn.p0; nxt.rows = nn.rows;
-#pragma unroll
-        for (int i = 0; i < W; ++i) { cur.ent[i] = nxt.ent[i]; nxt.ent[i] = nn.ent[i]; }
-        cself.q0 = nself.q0; cself.q1 = nself.q1; cself.x0 = nself.x0; cself.x1 = nself.x1;
-        cself.orig = nself.orig;
+        parity ^= 1;
+        cur = nxt; nxt = nn;
+        need_cur = need_nxt; late = need_nxt & ~up_nxt;
     }
 }
 
@@ -432,8 +509,8 @@ int dg4_launch_sweep(const dg4_sweep_args& a, int64_t n_flags, int64_t done_belo
     (void)wgs_per_cu;                  // one workgroup per compute unit: its registers and LDS hold the weights
     int64_t grid = cus;
     if (grid > a.n_tiles) grid = a.n_tiles;
-    void (*kern)(dg4_sweep_args) = a.ell_w == 8 ? sweep_kernel<8> : a.ell_w == 16 ? sweep_kernel<16>
-                                  : a.ell_w == 4 ? sweep_kernel<4> : nullptr;
+    void (*kern)(dg4_sweep_args) = nullptr;            // the LDS landing zone is laid out for cones of two hops
+    if (a.ell_w == 8) kern = a.prof ? sweep_kernel<8, true> : sweep_kernel<8, false>;
     if (!kern) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
     if (e != hipSuccess) return e;
