@@ -161,6 +161,14 @@ int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const v
 int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace,
                       uint64_t* ticks8, uint32_t* aborted);
 
+/*
+ * Tracing aid: device time in milliseconds of the persistent sweep kernel of the most recent
+ * dg4_layer_fwd that ran it while the environment variable DG4_SWEEP_EVENTS was set (two
+ * events recorded on the caller's stream around that one kernel). Waits for the kernel.
+ * EINVAL if no such call has been made.
+ */
+int dg4_sweep_elapsed_ms(float* ms);
+
 const char* dg4_strerror(int status);
 
 #ifdef __cplusplus

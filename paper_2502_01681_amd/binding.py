@@ -88,6 +88,8 @@ def lib():
         L.dg4_sparse_attn_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _P]
         L.dg4_layer_fwd.restype = ctypes.c_int
         L.dg4_layer_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(_P), _I32, _I32, _P, _P, _I64, _P]
+        L.dg4_sweep_elapsed_ms.restype = ctypes.c_int
+        L.dg4_sweep_elapsed_ms.argtypes = [ctypes.POINTER(ctypes.c_float)]
         L.dg4_layer_profile.restype = ctypes.c_int
         L.dg4_layer_profile.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(ctypes.c_uint64),
                                         ctypes.POINTER(ctypes.c_uint32)]
@@ -218,3 +220,10 @@ def dg4_layer_profile(cfg: LayerConfig, g: Graph, workspace):
     _check(lib().dg4_layer_profile(ctypes.byref(c), g.handle, workspace.data_ptr(), ticks, ctypes.byref(aborted)),
            "dg4_layer_profile")
     return int(aborted.value), [int(t) for t in ticks]
+
+
+def dg4_sweep_elapsed_ms() -> float:
+    """Device time of the last persistent sweep kernel launched with DG4_SWEEP_EVENTS set."""
+    ms = ctypes.c_float()
+    _check(lib().dg4_sweep_elapsed_ms(ctypes.byref(ms)), "dg4_sweep_elapsed_ms")
+    return float(ms.value)

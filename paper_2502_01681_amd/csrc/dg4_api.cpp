@@ -75,12 +75,10 @@ uint32_t dg4_sweep_spin_limit()
     const char* e = getenv("DG4_SWEEP_SPIN_LIMIT");
     return e ? (uint32_t)strtoul(e, nullptr, 10) : (1u << 22);
 }
-int dg4_sweep_wgs_per_cu()
-{
-    const char* e = getenv("DG4_SWEEP_WGS_PER_CU");
-    const int v = e ? atoi(e) : 2;
-    return v < 1 ? 1 : v > 8 ? 8 : v;
-}
+// Optional timing of the persistent sweep kernel alone (tracing aid): two events on the
+// caller's stream around its launch, read back by dg4_sweep_elapsed_ms.
+struct SweepEvents { hipEvent_t a = nullptr, b = nullptr; bool armed = false; };
+SweepEvents& sweep_events() { static SweepEvents e; return e; }
 
 #define HIPCHK(expr) do { if ((expr) != (int)hipSuccess) return DG4_EHIP; } while (0)
 
@@ -255,7 +253,15 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.publish_kv = 1;
         a.spin_limit = dg4_sweep_spin_limit();
         a.prof = getenv("DG4_SWEEP_PROFILE") ? (uint64_t*)((char*)at(pl.ctrl) + 64) : nullptr;
-        HIPCHK(dg4_launch_sweep(a, g->n, P0, dg4_sweep_wgs_per_cu(), s));
+        SweepEvents& ev = sweep_events();
+        const bool timed = getenv("DG4_SWEEP_EVENTS") != nullptr;
+        if (timed && !ev.a) {
+            if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return DG4_EHIP;
+        }
+        HIPCHK(dg4_launch_sweep_init(a, g->n, P0, s));
+        if (timed) HIPCHK(hipEventRecord(ev.a, s));
+        HIPCHK(dg4_launch_sweep(a, s));
+        if (timed) { HIPCHK(hipEventRecord(ev.b, s)); ev.armed = true; }
         return DG4_OK;
     }
 
@@ -337,5 +343,15 @@ extern "C" int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, c
     if (hipMemcpy(ctrl, (const char*)workspace + pl.ctrl, sizeof(ctrl), hipMemcpyDeviceToHost) != hipSuccess) return DG4_EHIP;
     memcpy(ticks8, ctrl + 16, 8 * sizeof(uint64_t));
     *aborted = ctrl[1];
+    return DG4_OK;
+}
+
+extern "C" int dg4_sweep_elapsed_ms(float* ms)
+{
+    SweepEvents& ev = sweep_events();
+    if (!ms) return DG4_EINVAL;
+    if (!ev.armed) return DG4_EINVAL;
+    if (hipEventSynchronize(ev.b) != hipSuccess) return DG4_EHIP;
+    if (hipEventElapsedTime(ms, ev.a, ev.b) != hipSuccess) return DG4_EHIP;
     return DG4_OK;
 }

@@ -94,7 +94,8 @@ struct dg4_sweep_args {
     uint32_t spin_limit;
 };
 int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void* packed, hipStream_t s);
-int dg4_launch_sweep(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, int wgs_per_cu, hipStream_t s);
+int dg4_launch_sweep_init(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, hipStream_t s);
+int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s);
 
 // ---- bulk projection on the matrix cores (dg4_sweep.hip): bf16, hidden 256 ----
 struct dg4_bulk_args {

@@ -498,16 +498,20 @@ int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void
     return hipGetLastError();
 }
 
-int dg4_launch_sweep(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, int wgs_per_cu, hipStream_t s)
+int dg4_launch_sweep_init(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, hipStream_t s)
 {
-    if (a.n_tiles <= 0) return hipSuccess;
     hipLaunchKernelGGL(sweep_init_kernel, dim3((unsigned)((std::max<int64_t>(n_flags, 64) + 255) / 256)), dim3(256), 0, s,
                        a.flags, n_flags, done_below, a.ctrl);
+    return hipGetLastError();
+}
+
+int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
+{
+    if (a.n_tiles <= 0) return hipSuccess;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
-    (void)wgs_per_cu;                  // one workgroup per compute unit: its registers and LDS hold the weights
-    int64_t grid = cus;
+    int64_t grid = cus;                // one workgroup per compute unit: its registers and LDS hold the weights
     if (grid > a.n_tiles) grid = a.n_tiles;
     void (*kern)(dg4_sweep_args) = nullptr;            // the LDS landing zone is laid out for cones of two hops
     if (a.ell_w == 8) kern = a.prof ? sweep_kernel<8, true> : sweep_kernel<8, false>;
