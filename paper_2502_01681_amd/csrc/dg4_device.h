@@ -24,9 +24,14 @@ __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);
     return u >> 16;
 }
+// two floats -> packed bfloat16 pair, round to nearest even, in one instruction
+// (v_cvt_pk_bf16_f32 on gfx950)
 __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
 {
-    return f32_to_bf16_bits(lo) | (f32_to_bf16_bits(hi) << 16);
+    typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+    typedef float f32x2_t __attribute__((ext_vector_type(2)));
+    const f32x2_t v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
 }
 
 // Lane exchange inside a group of 4 lanes by data-parallel primitives.

@@ -242,11 +242,19 @@ int dg4_graph_ensure_device(dg4_graph* g)
     const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
     try {
         // Processing order of the device kernels. Levels stay in order; INSIDE a level the gates
-        // are sorted by the position of their latest-finished source, so that gates whose sources
-        // are old share tiles and only the last tiles of a level wait on the levels just before.
-        // (The published `order` table keeps (level, id); results do not depend on this.)
+        // that some gate at most two levels up reads come first (they are published early), and
+        // within both groups gates are sorted by the position of their latest-finished source, so
+        // that gates whose sources are old share tiles and only the last tiles of a level wait on
+        // the levels just before. (The published `order` table keeps (level, id); results do not
+        // depend on this.)
         std::vector<int32_t> sweep(rows, 0);
         {
+            std::vector<int32_t> min_reader((size_t)g->n, INT32_MAX);
+            for (int64_t v = 0; v < g->n; ++v)
+                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j) {
+                    const int32_t u = g->nbr_idx[j];
+                    if (u != v) min_reader[u] = std::min(min_reader[u], g->level[v]);
+                }
             std::vector<int64_t> key((size_t)g->n, -1);
             for (int32_t l = 0; l <= g->max_level; ++l) {
                 const int64_t lo = g->level_ptr[l], hi = g->level_ptr[l + 1];
@@ -255,7 +263,8 @@ int dg4_graph_ensure_device(dg4_graph* g)
                     int64_t latest = -1;
                     for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
                         if (g->nbr_idx[j] != v) latest = std::max<int64_t>(latest, g->pos[g->nbr_idx[j]]);
-                    key[v] = latest;
+                    const int64_t far = (int64_t)min_reader[v] - l > 2 ? 1 : 0;
+                    key[v] = (far << 40) + latest + 1;
                     sweep[q] = v;
                 }
                 std::stable_sort(sweep.begin() + lo, sweep.begin() + hi,

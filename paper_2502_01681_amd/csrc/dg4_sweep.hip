@@ -63,6 +63,22 @@ __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, f32x4 c)
     return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8s, a), __builtin_bit_cast(bf16x8s, b), c, 0, 0, 0);
 }
 
+// Global memory -> LDS without passing through registers: every lane moves 16 bytes from its own
+// global address to LDS address lds_base + 16*lane (lds_base wave-uniform). Issued as assembly
+// so that the waits stay under this file's control: the compiler would otherwise drain every
+// outstanding transfer before ANY later LDS read, whatever its address. The transfers count in
+// vmcnt like loads and complete in issue order; a reader waits with s_waitcnt (plus a barrier if
+// another wave issued the transfer).
+__device__ __forceinline__ void dma16(const void* src, uint32_t lds_base)
+{
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_base) : "memory");
+}
+// same with a wave-uniform 64-bit base and a per-lane 32-bit byte offset
+__device__ __forceinline__ void dma16_row(const void* base, uint32_t lane_off, uint32_t lds_base)
+{
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+}
+
 // Packed order for weights used as the A operand of a 16x16x32 MFMA, in
 // 16-byte units: unit (((wave*NTW + nt)*8 + ks)*64 + lane) holds rows
 // k = ks*32 + 8*(lane/16) .. +7 of output column
@@ -105,12 +121,21 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     float (*sRed)[4][2] = (float (*)[4][2])(smem + SMEM_RED);
     int& sAbort = *(int*)(smem + SMEM_ABORT);
     unsigned char* sLand = smem + SMEM_LAND;
+    // LDS byte address of smem[0] for the transfers above
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
+    // the tile table is read-only for the whole kernel: fetched through the constant address space
+    // (wave-uniform index, so the loads are scalar and do not count in vmcnt)
+    const __attribute__((address_space(4))) uint64_t* tiles64 = (const __attribute__((address_space(4))) uint64_t*)p.tiles;
+    auto tile_at = [&](int64_t i) __attribute__((always_inline)) -> uint2 {
+        const uint64_t t = tiles64[p.tile_begin + i];
+        return make_uint2((uint32_t)t, (uint32_t)(t >> 32));                          // first position, rows
+    };
     // neighbour rows [gate][entry] and node ids [gate] of the tile with the given parity
     auto ent_of = [&](int parity) __attribute__((always_inline)) { return (const uint32_t (*)[8])(smem + SMEM_DESC + parity * DESC_BYTES); };
     auto ids_of = [&](int parity) __attribute__((always_inline)) { return (const int32_t*)(smem + SMEM_DESC + parity * DESC_BYTES + TILE * 8 * 4); };
 
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform, and known to be
     const int grp = lane >> 4, sub = lane & 15;
     const int my = 4 * wave + grp;            // attention role: this lane holds 16 features of gate `my`
     const int c0 = 64 * wave + 16 * grp;      // projection role: this lane holds 16 columns of gate `sub`
@@ -163,7 +188,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     auto gather_desc = [&](int64_t p0, int parity) __attribute__((always_inline)) {
         if (wave == 0 && lane < 36) {
             const void* src = lane < 32 ? (const void*)(p.ell + p0 * W + lane * 4) : (const void*)(p.order + p0 + (lane - 32) * 4);
-            __builtin_amdgcn_global_load_lds(src, (uint32_t*)(smem + SMEM_DESC + parity * DESC_BYTES), 16, 0, 0);
+            dma16(src, lds0 + (uint32_t)(SMEM_DESC + parity * DESC_BYTES));
         }
     };
     // (2) rows that depend on nobody else: a gate's own Q|K|V (1.5 KB) and its residual row
@@ -174,32 +199,33 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             if (g >= rows) continue;
             const int64_t orig = __builtin_amdgcn_readfirstlane(ids_of(parity)[g]);
             const uint16_t* self = p.qkv_self + (p0 + g) * (3 * D);
-            unsigned char* dst = sLand + g * LAND_GATE + LAND_SELF;
-            __builtin_amdgcn_global_load_lds(self + lane * 8, (uint32_t*)dst, 16, 0, 0);                       // Q | K
+            const uint32_t dst = lds0 + (uint32_t)(SMEM_LAND + g * LAND_GATE + LAND_SELF);
+            dma16_row(self, (uint32_t)lane * 16u, dst);                                                      // Q | K
             const uint16_t* tail = lane < 32 ? self + 2 * D + lane * 8 : p.x + orig * D + (lane - 32) * 8;   // V | x
-            __builtin_amdgcn_global_load_lds(tail, (uint32_t*)(dst + 1024), 16, 0, 0);
+            dma16(tail, dst + 1024u);
         }
     };
-    // (3) the K|V kilobyte of a source: one instruction per (gate, source). `take` has bit
-    //     16*gq + j set for entry j of this wave's gate gq if that source is to be fetched now;
-    //     `need` marks all entries that are sources. Slot s of a gate holds its s-th source.
-    //     `e_mine` is entry `sub` of gate `my` as held by each lane.
-    auto gather_src = [&](uint32_t e_mine, uint64_t take, uint64_t need) __attribute__((always_inline)) {
-        const uint16_t* lane_base = p.kv + lane * 8;
-#pragma unroll
-        for (int gq = 0; gq < 4; ++gq) {
-            const int g = 4 * wave + gq;
-#pragma unroll
-            for (int j = 0; j < W; ++j) {
-                if ((take >> (16 * gq + j)) & 1) {
-                    const int slot = __builtin_popcountll(need & (((1ull << j) - 1) << (16 * gq)));
-                    const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)e_mine, 16 * gq + j);
-                    if (slot < NS)
-                        __builtin_amdgcn_global_load_lds(lane_base + (int64_t)(e & 0x3FFFFFFFu) * (2 * D),
-                                                         (uint32_t*)(sLand + g * LAND_GATE + slot * 1024), 16, 0, 0);
-                }
-            }
+    // (3) the K|V kilobyte of a source: one instruction per (gate, source), in a loop over the
+    //     set bits of `take` (bit 16*gq + j = entry j of this wave's gate gq). Each lane holds
+    //     "its" entry (entry `sub` of gate `my`) and the slot it lands in; slot s of a gate holds
+    //     its s-th source. Row base addresses are wave-uniform (scalar arithmetic); the only
+    //     per-lane part is the fixed 16-byte stride.
+    auto gather_src = [&](uint32_t e_mine, uint32_t slot_mine, uint64_t take) __attribute__((always_inline)) {
+        while (take) {
+            const int b = __builtin_ctzll(take);
+            take &= take - 1;
+            const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)e_mine, b);
+            const uint32_t slot = (uint32_t)__builtin_amdgcn_readlane((int)slot_mine, b);
+            const int g = 4 * wave + (b >> 4);
+            if (slot < (uint32_t)NS)
+                dma16_row((const unsigned char*)p.kv + (uint64_t)(e & 0x3FFFFFFFu) * (2 * D * 2), (uint32_t)lane * 16u,
+                          lds0 + (uint32_t)(SMEM_LAND + g * LAND_GATE) + slot * 1024u);
         }
+    };
+    // slot of "my" entry: how many sources of my gate come before it in the row
+    auto slot_of = [&](uint64_t need) __attribute__((always_inline)) -> uint32_t {
+        const uint32_t gate_bits = (uint32_t)(need >> (16 * grp)) & 0xFFFFu;
+        return (uint32_t)__builtin_popcount(gate_bits & ((1u << sub) - 1u));
     };
     // The sources of this wave's gates: lane (grp, sub) watches entry `sub` of gate `my`.
     // Returns the ballot of lanes whose entry is a source; `*up` gets those whose flag is raised.
@@ -234,7 +260,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 break;
             }
         }
-        gather_src(e_mine, late, need);
+        gather_src(e_mine, slot_of(need), late);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __asm__ volatile("" ::: "memory");
     };
@@ -248,8 +274,8 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     // (tickets past the end are clamped: the fetch is harmless and its result unused)
     const int64_t last = p.n_tiles - 1;
     int parity = 0;
-    uint2 cur = p.tiles[p.tile_begin + ticket];                                      // first position, rows
-    uint2 nxt = p.tiles[p.tile_begin + (ticket + G < last ? ticket + G : last)];
+    uint2 cur = tile_at(ticket);                                      // first position, rows
+    uint2 nxt = tile_at(ticket + G < last ? ticket + G : last);
     uint64_t late = 0, need_cur = 0;              // sources of the current tile not gathered yet / all of them
     {
         gather_desc(cur.x, 0);
@@ -291,7 +317,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         lap(1);
         // the next tile's descriptor travels during the attention below
         gather_desc(nxt.x, parity ^ 1);
-        const uint2 nn = p.tiles[p.tile_begin + (ticket + 2 * G < last ? ticket + 2 * G : last)];
+        const uint2 nn = tile_at(ticket + 2 * G < last ? ticket + 2 * G : last);
 
         // ---------------- attention: gate `my`, lane owns 16 features. Two entries per round so
         // that their LDS reads overlap; softmax kept online (running maximum, rescaled sums).
@@ -367,8 +393,9 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (has_next) {
             nent = sub < W ? ent_of(parity ^ 1)[my][sub] : DG4_ELL_PAD;
             nneed = my < (int)nxt.y && nent != DG4_ELL_PAD && (nent >> 30) != 0;
-            if (nneed) nflag = __hip_atomic_load(p.flags + (nent & 0x3FFFFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
+        // (loaded by every lane, needed or not, and looked at only after the matrix products)
+        nflag = __hip_atomic_load(p.flags + (nneed ? (nent & 0x3FFFFFFFu) : 0u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---------------- output projection; lane (n = sub, g = grp) owns columns 64*wave + 16*g .. +15 of gate n
         const int n = sub;
@@ -388,9 +415,11 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             }
             // the next tile's published sources start to travel now and overlap the rest of this
             // tile (issued here so that the address arithmetic runs while the matrix cores work)
+            __builtin_amdgcn_sched_barrier(0);
+            __asm__ volatile("" : "+v"(nflag));
             need_nxt = __ballot(nneed); up_nxt = __ballot(nneed && nflag != 0u);
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");     // row gathers stay below the flag loads
-            if (has_next) gather_src(nent, up_nxt, need_nxt);
+            if (has_next) gather_src(nent, slot_of(need_nxt), up_nxt);
             if (TIMERS && threadIdx.x == 0 && (need_nxt & ~up_nxt)) sProf[0] += 1;   // tiles with a late source
             float x[16];
             {
