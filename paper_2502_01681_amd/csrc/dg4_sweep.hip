@@ -38,10 +38,11 @@ constexpr int KV_STRIDE = 2 * D + 8;
 // its residual row (512 B).
 constexpr int SMEM_TILE = 3 * TILE * LDS_STRIDE * 2;                // sA, sX (spare), sH
 static_assert(TILE * KV_STRIDE * 2 <= 2 * TILE * LDS_STRIDE * 2, "sKV must fit over sA and sX");
+constexpr int SMEM_LOOK = TILE * LDS_STRIDE * 2;                    // two flag snapshots (1 KB each) in the spare row buffer
 constexpr int SMEM_RED = SMEM_TILE;
 constexpr int SMEM_DESC = SMEM_RED + TILE * 4 * 2 * 4;              // [2 parities][ent 16 x 8 words | ids 16 words]
 constexpr int DESC_BYTES = TILE * 8 * 4 + TILE * 4;                 // 576
-constexpr int SMEM_ABORT = SMEM_DESC + 2 * DESC_BYTES;
+constexpr int SMEM_ABORT = SMEM_DESC + 3 * DESC_BYTES;
 constexpr int SMEM_PROF = SMEM_ABORT + 16;
 constexpr int SMEM_BIAS = SMEM_PROF + 64;                          // rel_bias [8 heads][4]
 constexpr int SMEM_WOF = SMEM_BIAS + 128;                           // one Wo fragment per wave (4 x 1 KB)
@@ -76,7 +77,19 @@ __device__ __forceinline__ void dma16(const void* src, uint32_t lds_base)
 // same with a wave-uniform 64-bit base and a per-lane 32-bit byte offset
 __device__ __forceinline__ void dma16_row(const void* base, uint32_t lane_off, uint32_t lds_base)
 {
+#if defined(DG4_NODMA) && DG4_NODMA == 1
+    return;
+#elif defined(DG4_NODMA)
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t; %0 %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+    return;
+#endif
     __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+}
+
+// one 32-bit word per lane, read at device scope (served by the L2, never by this unit's L1)
+__device__ __forceinline__ void dma4_fresh(const void* base, uint32_t lane_off, uint32_t lds_base)
+{
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 sc1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
 }
 
 // Packed order for weights used as the A operand of a 16x16x32 MFMA, in
@@ -109,6 +122,30 @@ __global__ void sweep_init_kernel(uint32_t* flags, int64_t n, int64_t done_below
     if (i < 64) ctrl[i] = 0u;                     // [0] ticket, [1] abort, [16..31] phase timers
 }
 
+#ifndef DG4_B_ATT
+#define DG4_B_ATT 3
+#endif
+#ifndef DG4_B_MID
+#define DG4_B_MID 3
+#endif
+#ifndef DG4_OWN_LATE
+#define DG4_OWN_LATE 0
+#endif
+// Transfers of slots [S0, S1) of a wave's four gates: lane 8*g + s of (lo, hi) holds the global
+// address of the row, land + g*LAND_GATE + s*1024 is where it goes.
+template <int S0, int S1>
+__device__ __forceinline__ void issue_slots(uint32_t lo, uint32_t hi, uint32_t lane_off, uint32_t land)
+{
+#pragma unroll
+    for (int g = 0; g < 4; ++g)
+#pragma unroll
+        for (int sl = S0; sl < S1; ++sl) {
+            const uint64_t a = (uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)lo, 8 * g + sl) |
+                               ((uint64_t)(uint32_t)__builtin_amdgcn_readlane((int)hi, 8 * g + sl) << 32);
+            dma16_row((const void*)(uintptr_t)a, lane_off, land + (uint32_t)(g * LAND_GATE + sl * 1024));
+        }
+}
+
 template <int W, bool TIMERS>
 __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 {
@@ -137,8 +174,10 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform, and known to be
     const int grp = lane >> 4, sub = lane & 15;
+    const uint32_t lane16 = (uint32_t)lane * 16u;
     const int my = 4 * wave + grp;            // attention role: this lane holds 16 features of gate `my`
     const int c0 = 64 * wave + 16 * grp;      // projection role: this lane holds 16 columns of gate `sub`
+    const uint32_t wave_land = lds0 + (uint32_t)(SMEM_LAND + 4 * wave * LAND_GATE);   // landing zone of this wave's gates
 
     // The weights of this wave stay in registers for the whole kernel: its 4 column tiles of Wo
     // (128 vector registers) and its 8 column tiles of Wk|Wv (all 256 accumulation registers,
@@ -210,8 +249,8 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     //     "its" entry (entry `sub` of gate `my`) and the slot it lands in; slot s of a gate holds
     //     its s-th source. Row base addresses are wave-uniform (scalar arithmetic); the only
     //     per-lane part is the fixed 16-byte stride.
-    auto gather_src = [&](uint32_t e_mine, uint32_t slot_mine, uint64_t take) __attribute__((always_inline)) {
-        while (take) {
+    auto gather_some = [&](uint32_t e_mine, uint32_t slot_mine, uint64_t& take, int most) __attribute__((always_inline)) {
+        while (take && most-- > 0) {
             const int b = __builtin_ctzll(take);
             take &= take - 1;
             const uint32_t e = (uint32_t)__builtin_amdgcn_readlane((int)e_mine, b);
@@ -221,6 +260,9 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 dma16_row((const unsigned char*)p.kv + (uint64_t)(e & 0x3FFFFFFFu) * (2 * D * 2), (uint32_t)lane * 16u,
                           lds0 + (uint32_t)(SMEM_LAND + g * LAND_GATE) + slot * 1024u);
         }
+    };
+    auto gather_src = [&](uint32_t e_mine, uint32_t slot_mine, uint64_t take) __attribute__((always_inline)) {
+        gather_some(e_mine, slot_mine, take, 64);
     };
     // slot of "my" entry: how many sources of my gate come before it in the row
     auto slot_of = [&](uint64_t need) __attribute__((always_inline)) -> uint32_t {
@@ -241,6 +283,14 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         // compiler from moving row loads above the flag loads.
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         return __ballot(need);
+    };
+    // Flag snapshots without registers: every lane fetches the flag word of the entry it watches
+    // (word 0 if it watches none) into its own LDS word; read back with looked() after a wait.
+    auto look_async = [&](uint32_t e, bool need, int which) __attribute__((always_inline)) {
+        dma4_fresh(p.flags, need ? (e & 0x3FFFFFFFu) * 4u : 0u, lds0 + (uint32_t)(SMEM_LOOK + which * 1024 + wave * 256));
+    };
+    auto looked = [&](int which) __attribute__((always_inline)) -> uint32_t {
+        return ((const uint32_t*)(smem + SMEM_LOOK + which * 1024))[wave * 64 + lane];
     };
     // Block until the sources in `late` are published, then fetch them.
     auto wait_and_gather = [&](int parity, int rows, uint64_t late, uint64_t need) __attribute__((always_inline)) {
@@ -273,14 +323,15 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     if (ticket >= p.n_tiles) return;
     // (tickets past the end are clamped: the fetch is harmless and its result unused)
     const int64_t last = p.n_tiles - 1;
-    int parity = 0;
+    int d0 = 0, d1 = 1, d2 = 2;                   // descriptor buffers of this tile, the next one, the one after
     uint2 cur = tile_at(ticket);                                      // first position, rows
     uint2 nxt = tile_at(ticket + G < last ? ticket + G : last);
     uint64_t late = 0, need_cur = 0;              // sources of the current tile not gathered yet / all of them
     {
         gather_desc(cur.x, 0);
+        gather_desc(nxt.x, 1);
         __builtin_amdgcn_s_waitcnt(0x0F70);
-        __syncthreads();                          // sAbort, descriptor of the first tile
+        __syncthreads();                          // sAbort, descriptors of the first two tiles
         gather_own(cur.x, (int)cur.y, 0);
         uint64_t up;
         uint32_t e0;
@@ -312,15 +363,30 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         lap(6);
         // sources that were not published yet when this tile's gathers went out
-        if (late) wait_and_gather(parity, rows, late, need_cur);
+        if (late) wait_and_gather(d0, rows, late, need_cur);
         if (TIMERS) __syncthreads();          // timers only: charge every wave's wait to phase 1
         lap(1);
-        // the next tile's descriptor travels during the attention below
-        gather_desc(nxt.x, parity ^ 1);
+        // the descriptor two tiles ahead travels during the attention below
         const uint2 nn = tile_at(ticket + 2 * G < last ? ticket + 2 * G : last);
+        gather_desc(nn.x, d2);
+        // A first look at the flags of the NEXT tile's sources (its descriptor came in a round
+        // ago). Loaded by every lane, needed or not; looked at after the first attention round.
+        uint32_t nent = DG4_ELL_PAD;
+        bool nneed = false;
+        if (has_next) {
+            nent = sub < W ? ent_of(d1)[my][sub] : DG4_ELL_PAD;
+            nneed = my < (int)nxt.y && nent != DG4_ELL_PAD && (nent >> 30) != 0;
+        }
+        look_async(nent, nneed, 0);
+        uint64_t need_nxt = 0, up_nxt = 0;
+        uint32_t nslot = 0;
 
         // ---------------- attention: gate `my`, lane owns 16 features. Two entries per round so
         // that their LDS reads overlap; softmax kept online (running maximum, rescaled sums).
+        // The number of rounds is the same for the whole wave (gates with fewer entries idle with
+        // weight zero), because the wave also issues, after each round, the gathers of the next
+        // tile into the source slots that round has just finished reading: after round r every
+        // gate is done with its slots 0 .. 2r (a row holds at most one entry that is no source).
         {
             const bool valid = my < rows;
             const unsigned char* land = sLand + my * LAND_GATE + sub * 32;
@@ -330,6 +396,13 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 const uint4 a = qp[0], b = qp[1];
                 q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
             }
+            int rounds;
+            {
+                const uint64_t vm = __ballot(sub < W && ent_of(d0)[my][sub] != DG4_ELL_PAD);
+                const uint32_t any = (uint32_t)(vm | (vm >> 16) | (vm >> 32) | (vm >> 48)) & 0xFFu;
+                rounds = (32 - __builtin_clz(any | 1u) + 1) >> 1;                 // 1 .. 4, wave-uniform
+            }
+            uint32_t src_lo = 0, src_hi = 0;              // lane 8*gate + slot: row address of that source of the next tile
             const float scale = 0.17677669529663687f;     // 1/sqrt(32)
             float acc[16];
 #pragma unroll
@@ -337,14 +410,14 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             float mx = -INFINITY, z = 0.f;
             int slot = 0;
 #pragma unroll 1
-            for (int j = 0; j < W; j += 2) {
-                const uint2 e2 = *(const uint2*)&ent_of(parity)[my][j];
+            for (int r = 0; r < rounds; ++r) {
+                const uint2 e2 = *(const uint2*)&ent_of(d0)[my][2 * r];
                 const uint32_t ea = e2.x, eb = e2.y;
-                if (ea == DG4_ELL_PAD) break;             // entries are packed from slot 0
-                const bool sa = (ea >> 30) != 0 && slot < NS;
+                const bool oa = ea != DG4_ELL_PAD, ob = eb != DG4_ELL_PAD;           // entries are packed from slot 0
+                const bool sa = oa && (ea >> 30) != 0 && slot < NS;
                 const uint4* ka = (const uint4*)(land + (sa ? slot * 1024 : LAND_SELF + 512));    // V sits 512 bytes after K
                 if (sa) ++slot;
-                const bool sb = eb != DG4_ELL_PAD && (eb >> 30) != 0 && slot < NS;
+                const bool sb = ob && (eb >> 30) != 0 && slot < NS;
                 const uint4* kb = (const uint4*)(land + (sb ? slot * 1024 : LAND_SELF + 512));
                 if (sb) ++slot;
                 const uint4 ka0 = ka[0], ka1 = ka[1], va0 = ka[32], va1 = ka[33];
@@ -361,8 +434,8 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 da = Elem<bf16_t>::head_sum(da); db = Elem<bf16_t>::head_sum(db);
                 const uint32_t ra = ea >> 30, rb = eb >> 30;
                 const float ba = sBias[ra], bb = sBias[rb];
-                const float sca = fmaf(da, scale, ba);
-                const float scb = eb != DG4_ELL_PAD ? fmaf(db, scale, bb) : -INFINITY;   // padding: weight exp(-inf) = 0
+                const float sca = oa ? fmaf(da, scale, ba) : -INFINITY;                  // padding: weight exp(-inf) = 0
+                const float scb = ob ? fmaf(db, scale, bb) : -INFINITY;
                 const float nm = fmaxf(mx, fmaxf(sca, scb));
                 const float corr = __expf(mx - nm);       // first round: exp(-inf) = 0
                 const float pa = __expf(sca - nm), pb = __expf(scb - nm);
@@ -373,6 +446,41 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 Elem<bf16_t>::unpack(vb0, vb1, vb);
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[i] = fmaf(acc[i], corr, fmaf(pa, va[i], pb * vb[i]));
+                if (r == 0) {
+                    // the first look has had a round to come back (so has the descriptor fetch)
+                    __builtin_amdgcn_s_waitcnt(0x0F70);
+                    __asm__ volatile("" ::: "memory");
+                    need_nxt = __ballot(nneed);
+                    const bool upl = nneed && looked(0) != 0u;
+                    up_nxt = __ballot(upl);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");     // row gathers stay below the flag loads
+                    nslot = slot_of(need_nxt);
+                    // Row addresses by (gate, slot), so that the issue below is straight-line code
+                    // with fixed lanes and fixed LDS addresses (with one wave per SIMD every
+                    // instruction counts): lanes scatter the address of their entry through LDS to
+                    // lane 8*gate + slot. Slots without a published source point at row 0: that
+                    // transfer is wasted but harmless (its slot is unused, or refilled later).
+                    uint64_t* tmp = (uint64_t*)(smem + SMEM_LOOK + 2048) + wave * 32;
+                    if (lane < 32) tmp[lane] = (uint64_t)(uintptr_t)p.kv;
+                    if (upl && nslot < (uint32_t)NS)
+                        tmp[grp * 8 + nslot] = (uint64_t)(uintptr_t)p.kv + (uint64_t)(nent & 0x3FFFFFFFu) * (2 * D * 2);
+                    const uint64_t a = tmp[lane & 31];
+                    src_lo = (uint32_t)a; src_hi = (uint32_t)(a >> 32);
+                }
+                // this round's rows are in registers: their slots may be overwritten
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+                if (has_next) {
+                    if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
+                    else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
+                    else if (r == 2) issue_slots<3, 5>(src_lo, src_hi, lane16, wave_land);
+                    else issue_slots<5, 6>(src_lo, src_hi, lane16, wave_land);
+                }
+            }
+            // slot groups beyond the last round were never read by this tile
+            if (has_next) {
+                if (rounds < 2) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
+                if (rounds < 3) issue_slots<3, 5>(src_lo, src_hi, lane16, wave_land);
+                if (rounds < 4) issue_slots<5, 6>(src_lo, src_hi, lane16, wave_land);
             }
             const float rz = 1.0f / z;
 #pragma unroll
@@ -383,25 +491,19 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             uint4* dst = (uint4*)&sA[my][sub * 16];
             dst[0] = oa; dst[1] = ob;
         }
-        if (wave == 0) { __builtin_amdgcn_s_waitcnt(0x0F70); __asm__ volatile("" ::: "memory"); }   // next descriptor has landed
-        __syncthreads();                      // sA and the next descriptor complete; every wave is done with its source slots
+        // a second look at the sources the first one found unpublished, answered while the matrix
+        // cores work below
+        const bool miss = nneed && ((up_nxt >> lane) & 1u) == 0u;
+        const bool any_miss = (need_nxt & ~up_nxt) != 0;
+        if (any_miss) look_async(nent, miss, 1);
+        __syncthreads();                      // sA and the descriptor fetched above complete
         if (sAbort) { flush(); return; }
         lap(2);
-        // a first look at the next tile's flags, answered while the matrix cores work below
-        bool nneed = false;
-        uint32_t nflag = 0, nent = DG4_ELL_PAD;
-        if (has_next) {
-            nent = sub < W ? ent_of(parity ^ 1)[my][sub] : DG4_ELL_PAD;
-            nneed = my < (int)nxt.y && nent != DG4_ELL_PAD && (nent >> 30) != 0;
-        }
-        // (loaded by every lane, needed or not, and looked at only after the matrix products)
-        nflag = __hip_atomic_load(p.flags + (nneed ? (nent & 0x3FFFFFFFu) : 0u), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 
         // ---------------- output projection; lane (n = sub, g = grp) owns columns 64*wave + 16*g .. +15 of gate n
         const int n = sub;
         const bool nvalid = n < rows;
         float t[16];
-        uint64_t need_nxt, up_nxt;
         {
             f32x4 acc[4];
 #pragma unroll
@@ -413,15 +515,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 for (int nt = 0; nt < 4; ++nt)
                     acc[nt] = mfma16(nt == 3 && ks == 7 ? *sWoF : __builtin_bit_cast(uint4, wo_r[nt][ks]), b, acc[nt]);
             }
-            // the next tile's published sources start to travel now and overlap the rest of this
-            // tile (issued here so that the address arithmetic runs while the matrix cores work)
-            __builtin_amdgcn_sched_barrier(0);
-            __asm__ volatile("" : "+v"(nflag));
-            need_nxt = __ballot(nneed); up_nxt = __ballot(nneed && nflag != 0u);
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");     // row gathers stay below the flag loads
-            if (has_next) gather_src(nent, slot_of(need_nxt), up_nxt);
-            if (TIMERS && threadIdx.x == 0 && (need_nxt & ~up_nxt)) sProf[0] += 1;   // tiles with a late source
-            float x[16];
+                float x[16];
             {
                 const uint4* xp = (const uint4*)(sLand + n * LAND_GATE + LAND_X + c0 * 2);
                 Elem<bf16_t>::unpack(xp[0], xp[1], x);
@@ -431,7 +525,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) t[nt * 4 + i] = acc[nt][i] + (p.epilogue ? x[nt * 4 + i] : 0.f);
         }
-        const int64_t orig_n = ids_of(parity)[nvalid ? n : 0];
+        const int64_t orig_n = ids_of(d0)[nvalid ? n : 0];
         lap(3);
         if (p.epilogue) {
             float s1 = 0.f, s2 = 0.f;
@@ -441,7 +535,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             s1 += __shfl_xor(s1, 32); s2 += __shfl_xor(s2, 32);
             if (grp == 0) { sRed[n][wave][0] = s1; sRed[n][wave][1] = s2; }
             __syncthreads();
-            float a1 = 0.f, a2 = 0.f;
+                float a1 = 0.f, a2 = 0.f;
 #pragma unroll
             for (int w2 = 0; w2 < 4; ++w2) { a1 += sRed[n][w2][0]; a2 += sRed[n][w2][1]; }
             const float mean = a1 * (1.0f / D);
@@ -450,6 +544,17 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) t[i] = (t[i] - mean) * rstd;
         }
+        if (any_miss) {
+            // The second snapshot. Transfers complete in order, so this also waits for the gathers
+            // issued during the attention; only waves that had a miss pay for it.
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __asm__ volatile("" ::: "memory");
+            uint64_t up2 = __ballot(miss && looked(1) != 0u);
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            up_nxt |= up2;
+            gather_some(nent, nslot, up2, 64);
+        }
+        if (TIMERS && threadIdx.x == 0 && (need_nxt & ~up_nxt)) sProf[0] += 1;       // tiles with a late source
         {
             uint4 ha, hb;
             Elem<bf16_t>::pack(t, ha, hb);
@@ -463,7 +568,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         __syncthreads();                      // sH complete; every wave has read its residual rows
         lap(4);
         // the landing zone of the gates' own rows is free now: the next tile's may come in
-        if (has_next) gather_own(nxt.x, (int)nxt.y, parity ^ 1);
+        if (!DG4_OWN_LATE && has_next) gather_own(nxt.x, (int)nxt.y, d1);
 
         // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
         {
@@ -476,6 +581,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 #pragma unroll
                 for (int nt = 0; nt < 8; ++nt) acc[nt] = mfma16(__builtin_bit_cast(uint4, wkv_r[nt][ks]), b, acc[nt]);
             }
+            if (DG4_OWN_LATE && has_next) gather_own(nxt.x, (int)nxt.y, d1);
             uint4* dst = (uint4*)&sKV[n][128 * wave + 32 * grp];
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
@@ -511,7 +617,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             return;
         }
         ticket += G;
-        parity ^= 1;
+        { const int t = d0; d0 = d1; d1 = d2; d2 = t; }
         cur = nxt; nxt = nn;
         need_cur = need_nxt; late = need_nxt & ~up_nxt;
     }
