@@ -225,10 +225,13 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
 
     // One persistent dataflow kernel for the whole range of levels
     if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & DG4_PER_LEVEL)) {
-        {   // Q | K | V of x for every gate of the swept levels, level-sorted rows
+        // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
+        // level by level; rows of the internal buffers are positions in the order in use.
+        const bool whole = level_begin == 0 && level_end == (int32_t)g->max_level + 1 && !getenv("DG4_SWEEP_LEVEL_ORDER");
+        {   // Q | K | V of x for every gate of the swept levels, rows in processing order
             HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, 0, 3 * d, at(pl.wqkv[0]), s));
             dg4_bulk_args b{};
-            b.src = (const uint16_t*)X; b.gather = g->d_order;
+            b.src = (const uint16_t*)X; b.gather = whole ? g->d_flow_order : g->d_order;
             b.w_packed = at(pl.wqkv[0]); b.n_cols = 3 * d;
             uint16_t* base = (uint16_t*)at(pl.qkv_self);
             b.out[0] = base; b.out[1] = base + d; b.out[2] = base + 2 * d; b.out_stride = 3 * d;
@@ -238,11 +241,11 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         HIPCHK(dg4_launch_pack_wt(W[1], d, 0, 4, 4, at(pl.wo_t), s));
         HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, d, 8, 4, at(pl.wkv_t), s));
         dg4_sweep_args a{};
-        a.tiles = g->d_tiles;
-        a.tile_begin = g->level_tile_ptr[level_begin];
-        a.n_tiles = g->level_tile_ptr[level_end] - a.tile_begin;
-        a.ell = g->d_ell_pos; a.ell_w = g->ell_w;
-        a.order = g->d_order;
+        a.tiles = whole ? g->d_flow_tiles : g->d_tiles;
+        a.tile_begin = whole ? 0 : g->level_tile_ptr[level_begin];
+        a.n_tiles = whole ? g->n_flow_tiles : g->level_tile_ptr[level_end] - a.tile_begin;
+        a.ell = whole ? g->d_flow_ell : g->d_ell_pos; a.ell_w = g->ell_w;
+        a.order = whole ? g->d_flow_order : g->d_order;
         a.x = (const uint16_t*)X;
         a.qkv_self = (const uint16_t*)at(pl.qkv_self);
         a.kv = (uint16_t*)at(pl.kv);

@@ -4,6 +4,7 @@
 #include <algorithm>
 #include <cstring>
 #include <new>
+#include <queue>
 
 #include "dg4_internal.h"
 
@@ -293,12 +294,88 @@ int dg4_graph_ensure_device(dg4_graph* g)
                 tiles.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(DG4_TILE_ROWS, g->level_ptr[l + 1] - p0)));
         }
         g->level_tile_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
+        // Dataflow order for whole-graph sweeps. A tile takes the (up to) 16 gates whose direct
+        // fanins all sit in EARLIER tiles and whose latest cone source is oldest; ties go to the
+        // lower level, then the lower id. `slack` tiles between a source and its reader let the
+        // source be published before the reader looks for it (tiles are dealt round-robin to one
+        // workgroup per compute unit, so `cus` tiles are in flight at once).
+        std::vector<int32_t> flow(rows, 0);
+        std::vector<uint2> flow_tiles;
+        std::vector<uint32_t> by_flow(rows * w, DG4_ELL_PAD);
+        {
+            int cus = 0;
+            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
+            const int64_t slack = (int64_t)cus * 5 / 2;
+            std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
+            std::vector<int32_t> remaining((size_t)g->n, 0);
+            for (int64_t v = 0; v < g->n; ++v)
+                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                    if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) { ++fo_ptr[(size_t)g->nbr_idx[j] + 1]; ++remaining[v]; }
+            for (int64_t v = 0; v < g->n; ++v) fo_ptr[v + 1] += fo_ptr[v];
+            std::vector<int32_t> fo((size_t)fo_ptr[g->n]);
+            {
+                std::vector<int64_t> fill(fo_ptr.begin(), fo_ptr.end() - 1);
+                for (int64_t v = 0; v < g->n; ++v)
+                    for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                        if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fo[(size_t)fill[g->nbr_idx[j]]++] = (int32_t)v;
+            }
+            struct Item { int64_t due; int32_t level; int32_t v; };
+            auto later = [](const Item& a, const Item& b) {
+                if (a.due != b.due) return a.due > b.due;
+                if (a.level != b.level) return a.level > b.level;
+                return a.v > b.v;
+            };
+            std::priority_queue<Item, std::vector<Item>, decltype(later)> ready(later);
+            for (int64_t v = 0; v < g->n; ++v)
+                if (remaining[v] == 0) ready.push(Item{0, g->level[v], (int32_t)v});
+            std::vector<int32_t> tile_of((size_t)g->n, -1), fpos((size_t)g->n, -1);
+            std::vector<Item> fresh;
+            int64_t q = 0;
+            while (!ready.empty()) {
+                const int64_t t = (int64_t)flow_tiles.size();
+                const int64_t first = q;
+                for (int k = 0; k < DG4_TILE_ROWS && !ready.empty(); ++k) {
+                    const int32_t v = ready.top().v;
+                    ready.pop();
+                    tile_of[v] = (int32_t)t; fpos[v] = (int32_t)q; flow[(size_t)q++] = v;
+                }
+                flow_tiles.push_back(make_uint2((uint32_t)first, (uint32_t)(q - first)));
+                fresh.clear();
+                for (int64_t p = first; p < q; ++p) {
+                    const int32_t v = flow[(size_t)p];
+                    for (int64_t j = fo_ptr[v]; j < fo_ptr[v + 1]; ++j) {
+                        const int32_t u = fo[(size_t)j];
+                        if (--remaining[u] != 0) continue;
+                        int64_t newest = -1;      // every cone source is scheduled: it precedes a direct fanin
+                        for (int64_t i = g->nbr_ptr[u]; i < g->nbr_ptr[u + 1]; ++i)
+                            if (g->nbr_idx[i] != u) newest = std::max<int64_t>(newest, tile_of[g->nbr_idx[i]]);
+                        fresh.push_back(Item{newest + slack, g->level[u], u});
+                    }
+                }
+                for (const Item& it : fresh) ready.push(it);     // eligible from the next tile on
+            }
+            if (q != g->n) return DG4_ECYCLE;                      // cannot happen for a validated DAG
+            for (int64_t v = 0; v < g->n; ++v) {
+                const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
+                uint32_t* r = &by_flow[(size_t)fpos[v] * w];
+                for (int64_t j = 0; j < cnt; ++j)
+                    r[j] = ((uint32_t)g->nbr_rel[lo + j] << 30) | (uint32_t)fpos[g->nbr_idx[lo + j]];
+            }
+            g->n_flow_tiles = (int64_t)flow_tiles.size();
+        }
         const size_t bytes = rows * w * sizeof(uint32_t);
         auto fail = [&](int rc) {
+            if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
+            if (g->d_flow_order) (void)hipFree(g->d_flow_order);
+            if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
+            g->d_flow_ell = nullptr; g->d_flow_order = nullptr; g->d_flow_tiles = nullptr;
             if (g->d_ell_id) (void)hipFree(g->d_ell_id);
             if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
             if (g->d_order) (void)hipFree(g->d_order);
             if (g->d_tiles) (void)hipFree(g->d_tiles);
+    if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
+    if (g->d_flow_order) (void)hipFree(g->d_flow_order);
+    if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
             g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr;
             return rc;
         };
@@ -314,6 +391,14 @@ int dg4_graph_ensure_device(dg4_graph* g)
         if (g->n > 0 &&
             hipMemcpy(g->d_order, sweep.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
             return fail(DG4_EHIP);
+        if (hipMalloc((void**)&g->d_flow_ell, bytes) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&g->d_flow_order, rows * sizeof(int32_t)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&g->d_flow_tiles, std::max<size_t>(flow_tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (!flow_tiles.empty() &&
+            hipMemcpy(g->d_flow_tiles, flow_tiles.data(), flow_tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess)
+            return fail(DG4_EHIP);
+        if (hipMemcpy(g->d_flow_ell, by_flow.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        if (hipMemcpy(g->d_flow_order, flow.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
     } catch (const std::bad_alloc&) {
         return DG4_ENOMEM;
     }
@@ -334,5 +419,8 @@ extern "C" void dg4_graph_free(dg4_graph* g)
     if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
     if (g->d_order) (void)hipFree(g->d_order);
     if (g->d_tiles) (void)hipFree(g->d_tiles);
+    if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
+    if (g->d_flow_order) (void)hipFree(g->d_flow_order);
+    if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
     delete g;
 }

@@ -38,6 +38,13 @@ struct dg4_graph {
     // tiles of the persistent sweep: runs of <= DG4_TILE_ROWS positions inside one level
     std::vector<int64_t> level_tile_ptr;   // [n_levels + 1] first tile of each level
     uint2* d_tiles = nullptr;        // [n_tiles] (first position, rows)
+    // A second processing order for sweeps over ALL levels: tiles filled by list scheduling over
+    // the real dependencies (a gate goes as early as its sources allow, sources long finished
+    // first), not level by level. Same layout as the three tables above.
+    uint32_t* d_flow_ell = nullptr;
+    int32_t* d_flow_order = nullptr;
+    uint2* d_flow_tiles = nullptr;
+    int64_t n_flow_tiles = 0;
 };
 
 int dg4_graph_ensure_device(dg4_graph* g);
