@@ -200,7 +200,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     // (the last fragment of Wo and the bias table sit in LDS: the register file is full)
     const float* sBias = (const float*)(smem + SMEM_BIAS) + (sub >> 1) * 4;          // this lane's head
     const uint4* sWoF = (const uint4*)(smem + SMEM_WOF) + wave * 64 + lane;
-    if (threadIdx.x < 32) ((float*)(smem + SMEM_BIAS))[threadIdx.x] = p.rel_bias[threadIdx.x];
+    if (threadIdx.x < 32) ((float*)(smem + SMEM_BIAS))[threadIdx.x] = p.rel_bias[threadIdx.x] * 1.4426950408889634f;   // in units of log 2
     ((uint4*)(smem + SMEM_WOF))[wave * 64 + lane] = __builtin_bit_cast(uint4, wo_r[3][7]);
     if (threadIdx.x == 0) sAbort = 0;
 
@@ -381,12 +381,13 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         uint64_t need_nxt = 0, up_nxt = 0;
         uint32_t nslot = 0;
 
-        // ---------------- attention: gate `my`, lane owns 16 features. Two entries per round so
-        // that their LDS reads overlap; softmax kept online (running maximum, rescaled sums).
-        // The number of rounds is the same for the whole wave (gates with fewer entries idle with
-        // weight zero), because the wave also issues, after each round, the gathers of the next
-        // tile into the source slots that round has just finished reading: after round r every
-        // gate is done with its slots 0 .. 2r (a row holds at most one entry that is no source).
+        // ---------------- attention: gate `my`, lane owns 16 features (two lanes per head). Two
+        // passes over the row: scores of all entries from the K halves, softmax over them in
+        // registers, then the weighted sum over the V halves. Entries are handled in pairs; how
+        // many pairs is the same for the whole wave (gates with fewer entries idle with weight
+        // zero), because the wave also issues, after each pair of the second pass, the gathers of
+        // the next tile into the source slots that pair has just finished reading: after pair r
+        // every gate is done with its slots 0 .. 2r (a row holds at most one entry that is no source).
         {
             const bool valid = my < rows;
             const unsigned char* land = sLand + my * LAND_GATE + sub * 32;
@@ -396,79 +397,98 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 const uint4 a = qp[0], b = qp[1];
                 q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
             }
+            uint32_t e[8];
+            {
+                const uint4* ep = (const uint4*)&ent_of(d0)[my][0];
+                const uint4 a = ep[0], b = ep[1];
+                e[0] = a.x; e[1] = a.y; e[2] = a.z; e[3] = a.w; e[4] = b.x; e[5] = b.y; e[6] = b.z; e[7] = b.w;
+            }
             int rounds;
             {
                 const uint64_t vm = __ballot(sub < W && ent_of(d0)[my][sub] != DG4_ELL_PAD);
                 const uint32_t any = (uint32_t)(vm | (vm >> 16) | (vm >> 32) | (vm >> 48)) & 0xFFu;
                 rounds = (32 - __builtin_clz(any | 1u) + 1) >> 1;                 // 1 .. 4, wave-uniform
             }
+            // first pass: scores, in units of log 2 (scale and bias table carry the factor log2 e)
+            const float scale = 0.17677669529663687f * 1.4426950408889634f;           // log2(e) / sqrt(32)
+            float sc[8];
+            uint32_t koff[8];                             // where the entry's K half sits in the landing zone
+            {
+                uint32_t slot = 0;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) {
+                    const bool src = e[j] != DG4_ELL_PAD && (e[j] >> 30) != 0 && slot < (uint32_t)NS;   // entries are packed from 0
+                    koff[j] = src ? slot * 1024u : (uint32_t)(LAND_SELF + 512);                         // V sits 512 bytes after K
+                    slot += src ? 1u : 0u;
+                }
+            }
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                if (r < rounds) {
+#pragma unroll
+                    for (int j = 2 * r; j < 2 * r + 2; ++j) {
+                        const uint4* kp = (const uint4*)(land + koff[j]);
+                        const uint4 k0 = kp[0], k1 = kp[1];
+                        float d = 0.f;
+                        d = dot2_bf16(q[0], k0.x, d); d = dot2_bf16(q[1], k0.y, d); d = dot2_bf16(q[2], k0.z, d); d = dot2_bf16(q[3], k0.w, d);
+                        d = dot2_bf16(q[4], k1.x, d); d = dot2_bf16(q[5], k1.y, d); d = dot2_bf16(q[6], k1.z, d); d = dot2_bf16(q[7], k1.w, d);
+                        d = Elem<bf16_t>::head_sum(d);
+                        sc[j] = e[j] != DG4_ELL_PAD ? fmaf(d, scale, sBias[e[j] >> 30]) : -INFINITY;   // padding: weight 2^-inf = 0
+                    }
+                } else {
+                    sc[2 * r] = -INFINITY; sc[2 * r + 1] = -INFINITY;
+                }
+            }
+            {
+                const float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+                float z = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { sc[j] = __builtin_amdgcn_exp2f(sc[j] - mx); z += sc[j]; }
+                const float rz = 1.0f / z;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) sc[j] *= rz;
+            }
+            // the first look has had the first pass to come back (so has the descriptor fetch)
             uint32_t src_lo = 0, src_hi = 0;              // lane 8*gate + slot: row address of that source of the next tile
-            const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+            {
+                __builtin_amdgcn_s_waitcnt(0x0F70);
+                __asm__ volatile("" ::: "memory");
+                need_nxt = __ballot(nneed);
+                const bool upl = nneed && looked(0) != 0u;
+                up_nxt = __ballot(upl);
+                __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");     // row gathers stay below the flag loads
+                nslot = slot_of(need_nxt);
+                // Row addresses by (gate, slot), so that the issue below is straight-line code
+                // with fixed lanes and fixed LDS addresses (with one wave per SIMD every
+                // instruction counts): lanes scatter the address of their entry through LDS to
+                // lane 8*gate + slot. Slots without a published source point at row 0: that
+                // transfer is wasted but harmless (its slot is unused, or refilled later).
+                uint64_t* tmp = (uint64_t*)(smem + SMEM_LOOK + 2048) + wave * 32;
+                if (lane < 32) tmp[lane] = (uint64_t)(uintptr_t)p.kv;
+                if (upl && nslot < (uint32_t)NS)
+                    tmp[grp * 8 + nslot] = (uint64_t)(uintptr_t)p.kv + (uint64_t)(nent & 0x3FFFFFFFu) * (2 * D * 2);
+                const uint64_t a = tmp[lane & 31];
+                src_lo = (uint32_t)a; src_hi = (uint32_t)(a >> 32);
+            }
+            // second pass: weighted sum of the V halves
             float acc[16];
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-            float mx = -INFINITY, z = 0.f;
-            int slot = 0;
-#pragma unroll 1
-            for (int r = 0; r < rounds; ++r) {
-                const uint2 e2 = *(const uint2*)&ent_of(d0)[my][2 * r];
-                const uint32_t ea = e2.x, eb = e2.y;
-                const bool oa = ea != DG4_ELL_PAD, ob = eb != DG4_ELL_PAD;           // entries are packed from slot 0
-                const bool sa = oa && (ea >> 30) != 0 && slot < NS;
-                const uint4* ka = (const uint4*)(land + (sa ? slot * 1024 : LAND_SELF + 512));    // V sits 512 bytes after K
-                if (sa) ++slot;
-                const bool sb = ob && (eb >> 30) != 0 && slot < NS;
-                const uint4* kb = (const uint4*)(land + (sb ? slot * 1024 : LAND_SELF + 512));
-                if (sb) ++slot;
-                const uint4 ka0 = ka[0], ka1 = ka[1], va0 = ka[32], va1 = ka[33];
-                const uint4 kb0 = kb[0], kb1 = kb[1], vb0 = kb[32], vb1 = kb[33];
-                float da = 0.f, db = 0.f;
-                da = dot2_bf16(q[0], ka0.x, da); db = dot2_bf16(q[0], kb0.x, db);
-                da = dot2_bf16(q[1], ka0.y, da); db = dot2_bf16(q[1], kb0.y, db);
-                da = dot2_bf16(q[2], ka0.z, da); db = dot2_bf16(q[2], kb0.z, db);
-                da = dot2_bf16(q[3], ka0.w, da); db = dot2_bf16(q[3], kb0.w, db);
-                da = dot2_bf16(q[4], ka1.x, da); db = dot2_bf16(q[4], kb1.x, db);
-                da = dot2_bf16(q[5], ka1.y, da); db = dot2_bf16(q[5], kb1.y, db);
-                da = dot2_bf16(q[6], ka1.z, da); db = dot2_bf16(q[6], kb1.z, db);
-                da = dot2_bf16(q[7], ka1.w, da); db = dot2_bf16(q[7], kb1.w, db);
-                da = Elem<bf16_t>::head_sum(da); db = Elem<bf16_t>::head_sum(db);
-                const uint32_t ra = ea >> 30, rb = eb >> 30;
-                const float ba = sBias[ra], bb = sBias[rb];
-                const float sca = oa ? fmaf(da, scale, ba) : -INFINITY;                  // padding: weight exp(-inf) = 0
-                const float scb = ob ? fmaf(db, scale, bb) : -INFINITY;
-                const float nm = fmaxf(mx, fmaxf(sca, scb));
-                const float corr = __expf(mx - nm);       // first round: exp(-inf) = 0
-                const float pa = __expf(sca - nm), pb = __expf(scb - nm);
-                mx = nm;
-                z = fmaf(z, corr, pa + pb);
-                float va[16], vb[16];
-                Elem<bf16_t>::unpack(va0, va1, va);
-                Elem<bf16_t>::unpack(vb0, vb1, vb);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = fmaf(acc[i], corr, fmaf(pa, va[i], pb * vb[i]));
-                if (r == 0) {
-                    // the first look has had a round to come back (so has the descriptor fetch)
-                    __builtin_amdgcn_s_waitcnt(0x0F70);
-                    __asm__ volatile("" ::: "memory");
-                    need_nxt = __ballot(nneed);
-                    const bool upl = nneed && looked(0) != 0u;
-                    up_nxt = __ballot(upl);
-                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");     // row gathers stay below the flag loads
-                    nslot = slot_of(need_nxt);
-                    // Row addresses by (gate, slot), so that the issue below is straight-line code
-                    // with fixed lanes and fixed LDS addresses (with one wave per SIMD every
-                    // instruction counts): lanes scatter the address of their entry through LDS to
-                    // lane 8*gate + slot. Slots without a published source point at row 0: that
-                    // transfer is wasted but harmless (its slot is unused, or refilled later).
-                    uint64_t* tmp = (uint64_t*)(smem + SMEM_LOOK + 2048) + wave * 32;
-                    if (lane < 32) tmp[lane] = (uint64_t)(uintptr_t)p.kv;
-                    if (upl && nslot < (uint32_t)NS)
-                        tmp[grp * 8 + nslot] = (uint64_t)(uintptr_t)p.kv + (uint64_t)(nent & 0x3FFFFFFFu) * (2 * D * 2);
-                    const uint64_t a = tmp[lane & 31];
-                    src_lo = (uint32_t)a; src_hi = (uint32_t)(a >> 32);
+            for (int r = 0; r < 4; ++r) {
+                if (r < rounds) {
+#pragma unroll
+                    for (int j = 2 * r; j < 2 * r + 2; ++j) {
+                        const uint4* vp = (const uint4*)(land + koff[j]) + 32;
+                        const uint4 v0 = vp[0], v1 = vp[1];
+                        float v[16];
+                        Elem<bf16_t>::unpack(v0, v1, v);
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) acc[i] = fmaf(sc[j], v[i], acc[i]);
+                    }
+                    // this pair's rows are in registers: their slots may be overwritten
+                    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
                 }
-                // this round's rows are in registers: their slots may be overwritten
-                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
                 if (has_next) {
                     if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
                     else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
@@ -476,15 +496,6 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                     else issue_slots<5, 6>(src_lo, src_hi, lane16, wave_land);
                 }
             }
-            // slot groups beyond the last round were never read by this tile
-            if (has_next) {
-                if (rounds < 2) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
-                if (rounds < 3) issue_slots<3, 5>(src_lo, src_hi, lane16, wave_land);
-                if (rounds < 4) issue_slots<5, 6>(src_lo, src_hi, lane16, wave_land);
-            }
-            const float rz = 1.0f / z;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] *= rz;
             uint4 oa, ob;
             if (valid) Elem<bf16_t>::pack(acc, oa, ob);
             else { oa = make_uint4(0, 0, 0, 0); ob = oa; }
