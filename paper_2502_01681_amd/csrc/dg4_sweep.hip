@@ -34,8 +34,8 @@ constexpr int KV_STRIDE = 2 * D + 8;
 // LDS map (bytes): three row buffers (sKV overlays the first two), LayerNorm partial sums, for
 // this tile and the next the packed neighbour rows followed by the node ids (one contiguous
 // block per parity, filled by a single gather), the abort word, timers, then the landing zone:
-// per gate 8 KB = six source slots of K|V (1 KB each), the gate's own Q|K|V rows (1.5 KB) and
-// its residual row (512 B).
+// per gate 8 KB = six source slots of K|V (1 KB each), the gate's own K|V as a seventh slot, its
+// own Q row (512 B) and its residual row (512 B).
 constexpr int SMEM_TILE = 3 * TILE * LDS_STRIDE * 2;                // sA, sX (spare), sH
 static_assert(TILE * KV_STRIDE * 2 <= 2 * TILE * LDS_STRIDE * 2, "sKV must fit over sA and sX");
 constexpr int SMEM_LOOK = TILE * LDS_STRIDE * 2;                    // two flag snapshots (1 KB each) in the spare row buffer
@@ -47,7 +47,7 @@ constexpr int SMEM_PROF = SMEM_ABORT + 16;
 constexpr int SMEM_BIAS = SMEM_PROF + 64;                          // rel_bias [8 heads][4]
 constexpr int SMEM_WOF = SMEM_BIAS + 128;                           // one Wo fragment per wave (4 x 1 KB)
 constexpr int SMEM_LAND = SMEM_WOF + 4096;
-constexpr int LAND_GATE = 8192, LAND_SELF = 6144, LAND_X = 7680;
+constexpr int LAND_GATE = 8192, LAND_SELF = 6144, LAND_Q = 7168, LAND_X = 7680;
 constexpr int SMEM_BYTES = SMEM_LAND + TILE * LAND_GATE;
 static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
 static_assert(SMEM_LAND % 16 == 0 && SMEM_DESC % 16 == 0 && DESC_BYTES % 16 == 0, "alignment");
@@ -122,6 +122,9 @@ __global__ void sweep_init_kernel(uint32_t* flags, int64_t n, int64_t done_below
     if (i < 64) ctrl[i] = 0u;                     // [0] ticket, [1] abort, [16..31] phase timers
 }
 
+#ifndef DG4_ISSUE_MODE
+#define DG4_ISSUE_MODE 2
+#endif
 #ifndef DG4_B_ATT
 #define DG4_B_ATT 3
 #endif
@@ -171,12 +174,26 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     auto ent_of = [&](int parity) __attribute__((always_inline)) { return (const uint32_t (*)[8])(smem + SMEM_DESC + parity * DESC_BYTES); };
     auto ids_of = [&](int parity) __attribute__((always_inline)) { return (const int32_t*)(smem + SMEM_DESC + parity * DESC_BYTES + TILE * 8 * 4); };
 
-    const int lane = threadIdx.x & 63;
+    const int lane0 = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // wave-uniform, and known to be
-    const int grp = lane >> 4, sub = lane & 15;
-    const uint32_t lane16 = (uint32_t)lane * 16u;
-    const int my = 4 * wave + grp;            // attention role: this lane holds 16 features of gate `my`
-    const int c0 = 64 * wave + 16 * grp;      // projection role: this lane holds 16 columns of gate `sub`
+    // Everything derived from the lane number (roles, LDS addresses) is recomputed at the start of
+    // each phase from a copy the compiler cannot see through. Otherwise dozens of such values are
+    // kept in registers across the whole loop, and the weights held there leave no room for that.
+    int lane, grp, sub, my, c0;
+    uint32_t lane16;
+    const float* sBias;
+    const uint4* sWoF;
+    auto roles = [&]() __attribute__((always_inline)) {
+        int t = lane0;
+        __asm__ volatile("" : "+v"(t));
+        lane = t; grp = t >> 4; sub = t & 15;
+        lane16 = (uint32_t)t * 16u;
+        my = 4 * wave + grp;              // attention role: this lane holds 16 features of gate `my`
+        c0 = 64 * wave + 16 * grp;        // projection role: this lane holds 16 columns of gate `sub`
+        sBias = (const float*)(smem + SMEM_BIAS) + (sub >> 1) * 4;          // this lane's head
+        sWoF = (const uint4*)(smem + SMEM_WOF) + wave * 64 + lane;
+    };
+    roles();
     const uint32_t wave_land = lds0 + (uint32_t)(SMEM_LAND + 4 * wave * LAND_GATE);   // landing zone of this wave's gates
 
     // The weights of this wave stay in registers for the whole kernel: its 4 column tiles of Wo
@@ -198,8 +215,6 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             for (int ks = 0; ks < 8; ++ks) wkv_r[nt][ks] = __builtin_bit_cast(u32x4, wkv[(nt * 8 + ks) * 64]);
     }
     // (the last fragment of Wo and the bias table sit in LDS: the register file is full)
-    const float* sBias = (const float*)(smem + SMEM_BIAS) + (sub >> 1) * 4;          // this lane's head
-    const uint4* sWoF = (const uint4*)(smem + SMEM_WOF) + wave * 64 + lane;
     if (threadIdx.x < 32) ((float*)(smem + SMEM_BIAS))[threadIdx.x] = p.rel_bias[threadIdx.x] * 1.4426950408889634f;   // in units of log 2
     ((uint4*)(smem + SMEM_WOF))[wave * 64 + lane] = __builtin_bit_cast(uint4, wo_r[3][7]);
     if (threadIdx.x == 0) sAbort = 0;
@@ -239,8 +254,8 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             const int64_t orig = __builtin_amdgcn_readfirstlane(ids_of(parity)[g]);
             const uint16_t* self = p.qkv_self + (p0 + g) * (3 * D);
             const uint32_t dst = lds0 + (uint32_t)(SMEM_LAND + g * LAND_GATE + LAND_SELF);
-            dma16_row(self, (uint32_t)lane * 16u, dst);                                                      // Q | K
-            const uint16_t* tail = lane < 32 ? self + 2 * D + lane * 8 : p.x + orig * D + (lane - 32) * 8;   // V | x
+            dma16_row(self + D, lane16, dst);                                                                // K | V
+            const uint16_t* tail = lane < 32 ? self + lane * 8 : p.x + orig * D + (lane - 32) * 8;          // Q | x
             dma16(tail, dst + 1024u);
         }
     };
@@ -351,6 +366,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         const int64_t p0 = cur.x;
         const int rows = (int)cur.y;
         const bool has_next = ticket + G < p.n_tiles;
+        roles();
 
         // ---------------- publish the previous tile. Loads and stores of a wave complete in order,
         // so one wait covers both the K|V row stores of the previous tile (complete = written
@@ -380,6 +396,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         look_async(nent, nneed, 0);
         uint64_t need_nxt = 0, up_nxt = 0;
         uint32_t nslot = 0;
+        uint32_t keep_lo = 0, keep_hi = 0;
 
         // ---------------- attention: gate `my`, lane owns 16 features (two lanes per head). Two
         // passes over the row: scores of all entries from the K halves, softmax over them in
@@ -389,11 +406,12 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         // the next tile into the source slots that pair has just finished reading: after pair r
         // every gate is done with its slots 0 .. 2r (a row holds at most one entry that is no source).
         {
+            roles();
             const bool valid = my < rows;
             const unsigned char* land = sLand + my * LAND_GATE + sub * 32;
             uint32_t q[8];
             {
-                const uint4* qp = (const uint4*)(land + LAND_SELF);
+                const uint4* qp = (const uint4*)(land + LAND_Q);
                 const uint4 a = qp[0], b = qp[1];
                 q[0] = a.x; q[1] = a.y; q[2] = a.z; q[3] = a.w; q[4] = b.x; q[5] = b.y; q[6] = b.z; q[7] = b.w;
             }
@@ -403,50 +421,52 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 const uint4 a = ep[0], b = ep[1];
                 e[0] = a.x; e[1] = a.y; e[2] = a.z; e[3] = a.w; e[4] = b.x; e[5] = b.y; e[6] = b.z; e[7] = b.w;
             }
-            int rounds;
-            {
-                const uint64_t vm = __ballot(sub < W && ent_of(d0)[my][sub] != DG4_ELL_PAD);
-                const uint32_t any = (uint32_t)(vm | (vm >> 16) | (vm >> 32) | (vm >> 48)) & 0xFFu;
-                rounds = (32 - __builtin_clz(any | 1u) + 1) >> 1;                 // 1 .. 4, wave-uniform
-            }
-            // first pass: scores, in units of log 2 (scale and bias table carry the factor log2 e)
+            // first pass: scores, in units of log 2 (scale and bias table carry the factor log2 e).
+            // All eight entries of the row are processed, padding included (it reads the gate's
+            // own rows and gets weight zero): no branches, so the loads of several entries are
+            // in flight together.
             const float scale = 0.17677669529663687f * 1.4426950408889634f;           // log2(e) / sqrt(32)
             float sc[8];
-            uint32_t koff[8];                             // where the entry's K half sits in the landing zone
+            // per entry, 4 bits each: where its K|V sits (source slot 0..5, 6 = the gate's own rows)
+            // and its relation code with a "present" bit (the register file is full: two registers
+            // instead of sixteen)
+            uint32_t where = 0, what = 0;
             {
                 uint32_t slot = 0;
 #pragma unroll
                 for (int j = 0; j < 8; ++j) {
-                    const bool src = e[j] != DG4_ELL_PAD && (e[j] >> 30) != 0 && slot < (uint32_t)NS;   // entries are packed from 0
-                    koff[j] = src ? slot * 1024u : (uint32_t)(LAND_SELF + 512);                         // V sits 512 bytes after K
+                    const bool present = e[j] != DG4_ELL_PAD;                                   // entries are packed from 0
+                    const bool src = present && (e[j] >> 30) != 0 && slot < (uint32_t)NS;
+                    where |= (src ? slot : 6u) << (4 * j);
+                    what |= (present ? 4u | (e[j] >> 30) : 3u) << (4 * j);
                     slot += src ? 1u : 0u;
                 }
             }
+            auto k_of = [&](int j) __attribute__((always_inline)) {                             // V sits 512 bytes after K
+                return (const uint4*)(land + (((where >> (4 * j)) & 7u) << 10));
+            };
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                if (r < rounds) {
+            for (int h = 0; h < 4; ++h) {
+                uint4 k0[2], k1[2];
+                float bias[2];
 #pragma unroll
-                    for (int j = 2 * r; j < 2 * r + 2; ++j) {
-                        const uint4* kp = (const uint4*)(land + koff[j]);
-                        const uint4 k0 = kp[0], k1 = kp[1];
-                        float d = 0.f;
-                        d = dot2_bf16(q[0], k0.x, d); d = dot2_bf16(q[1], k0.y, d); d = dot2_bf16(q[2], k0.z, d); d = dot2_bf16(q[3], k0.w, d);
-                        d = dot2_bf16(q[4], k1.x, d); d = dot2_bf16(q[5], k1.y, d); d = dot2_bf16(q[6], k1.z, d); d = dot2_bf16(q[7], k1.w, d);
-                        d = Elem<bf16_t>::head_sum(d);
-                        sc[j] = e[j] != DG4_ELL_PAD ? fmaf(d, scale, sBias[e[j] >> 30]) : -INFINITY;   // padding: weight 2^-inf = 0
-                    }
-                } else {
-                    sc[2 * r] = -INFINITY; sc[2 * r + 1] = -INFINITY;
+                for (int j = 0; j < 2; ++j) {
+                    const uint4* kp = k_of(2 * h + j);
+                    k0[j] = kp[0]; k1[j] = kp[1];
+                    bias[j] = sBias[(what >> (4 * (2 * h + j))) & 3u];          // padding reads entry 3 of the table, unused
                 }
-            }
-            {
-                const float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-                float z = 0.f;
 #pragma unroll
-                for (int j = 0; j < 8; ++j) { sc[j] = __builtin_amdgcn_exp2f(sc[j] - mx); z += sc[j]; }
-                const float rz = 1.0f / z;
-#pragma unroll
-                for (int j = 0; j < 8; ++j) sc[j] *= rz;
+                for (int j = 0; j < 2; ++j) {
+                    float d0 = 0.f, d1 = 0.f;                     // two chains: the dot products issue back to back
+                    d0 = dot2_bf16(q[0], k0[j].x, d0); d1 = dot2_bf16(q[1], k0[j].y, d1);
+                    d0 = dot2_bf16(q[2], k0[j].z, d0); d1 = dot2_bf16(q[3], k0[j].w, d1);
+                    d0 = dot2_bf16(q[4], k1[j].x, d0); d1 = dot2_bf16(q[5], k1[j].y, d1);
+                    d0 = dot2_bf16(q[6], k1[j].z, d0); d1 = dot2_bf16(q[7], k1[j].w, d1);
+                    const float d = Elem<bf16_t>::head_sum(d0 + d1);
+                    const float t = fmaf(d, scale, bias[j]);
+                    sc[2 * h + j] = (what >> (4 * (2 * h + j)) & 4u) ? t : -INFINITY;   // padding: weight 2^-inf = 0
+                }
+                __builtin_amdgcn_sched_barrier(0);            // one pair's rows in registers at a time: the register file is full
             }
             // the first look has had the first pass to come back (so has the descriptor fetch)
             uint32_t src_lo = 0, src_hi = 0;              // lane 8*gate + slot: row address of that source of the next tile
@@ -470,32 +490,52 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 const uint64_t a = tmp[lane & 31];
                 src_lo = (uint32_t)a; src_hi = (uint32_t)(a >> 32);
             }
-            // second pass: weighted sum of the V halves
+            {
+                const float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+                float z = 0.f;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) { sc[j] = __builtin_amdgcn_exp2f(sc[j] - mx); z += sc[j]; }
+                const float rz = 1.0f / z;
+#pragma unroll
+                for (int j = 0; j < 8; ++j) sc[j] *= rz;
+            }
+            // second pass: weighted sum of the V halves, two entries at a time. After pair r every
+            // gate is done with its slots 0 .. 2r (a row holds at most one entry that is no
+            // source), so the next tile's sources for those slots can start to travel.
             float acc[16];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
             for (int r = 0; r < 4; ++r) {
-                if (r < rounds) {
+                const uint4* va = k_of(2 * r) + 32;
+                const uint4* vb = k_of(2 * r + 1) + 32;
+                const uint4 a0 = va[0], a1 = va[1], b0 = vb[0], b1 = vb[1];
+                {
+                    float f[16];
+                    Elem<bf16_t>::unpack(a0, a1, f);
 #pragma unroll
-                    for (int j = 2 * r; j < 2 * r + 2; ++j) {
-                        const uint4* vp = (const uint4*)(land + koff[j]) + 32;
-                        const uint4 v0 = vp[0], v1 = vp[1];
-                        float v[16];
-                        Elem<bf16_t>::unpack(v0, v1, v);
-#pragma unroll
-                        for (int i = 0; i < 16; ++i) acc[i] = fmaf(sc[j], v[i], acc[i]);
-                    }
-                    // this pair's rows are in registers: their slots may be overwritten
-                    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+                    for (int i = 0; i < 16; ++i) acc[i] = r == 0 ? sc[0] * f[i] : fmaf(sc[2 * r], f[i], acc[i]);
                 }
-                if (has_next) {
+                __builtin_amdgcn_sched_barrier(0);
+                {
+                    float f[16];
+                    Elem<bf16_t>::unpack(b0, b1, f);
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[i] = fmaf(sc[2 * r + 1], f[i], acc[i]);
+                }
+                // this pair's rows are in registers: their slots may be overwritten
+                __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
+                if (has_next && DG4_ISSUE_MODE == 0) {
                     if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
                     else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
                     else if (r == 2) issue_slots<3, 5>(src_lo, src_hi, lane16, wave_land);
                     else issue_slots<5, 6>(src_lo, src_hi, lane16, wave_land);
                 }
+                if (has_next && DG4_ISSUE_MODE == 2) {
+                    if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
+                    else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
+                }
             }
+            if (has_next && DG4_ISSUE_MODE == 1) issue_slots<0, 6>(src_lo, src_hi, lane16, wave_land);
+            keep_lo = src_lo; keep_hi = src_hi;
             uint4 oa, ob;
             if (valid) Elem<bf16_t>::pack(acc, oa, ob);
             else { oa = make_uint4(0, 0, 0, 0); ob = oa; }
@@ -510,23 +550,27 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         __syncthreads();                      // sA and the descriptor fetched above complete
         if (sAbort) { flush(); return; }
         lap(2);
+        if (has_next && DG4_ISSUE_MODE == 2) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
 
         // ---------------- output projection; lane (n = sub, g = grp) owns columns 64*wave + 16*g .. +15 of gate n
+        roles();
         const int n = sub;
         const bool nvalid = n < rows;
         float t[16];
         {
+            // (accumulators start from a literal zero operand: zero-filled registers would be kept
+            // alive across the whole loop)
             f32x4 acc[4];
-#pragma unroll
-            for (int nt = 0; nt < 4; ++nt) acc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 const uint4 b = *(const uint4*)&sA[n][8 * grp + ks * 32];
 #pragma unroll
                 for (int nt = 0; nt < 4; ++nt)
-                    acc[nt] = mfma16(nt == 3 && ks == 7 ? *sWoF : __builtin_bit_cast(uint4, wo_r[nt][ks]), b, acc[nt]);
+                    acc[nt] = mfma16(nt == 3 && ks == 7 ? *sWoF : __builtin_bit_cast(uint4, wo_r[nt][ks]), b,
+                                     ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[nt]);
             }
-                float x[16];
+                if (has_next && DG4_ISSUE_MODE == 2) issue_slots<5, 6>(keep_lo, keep_hi, lane16, wave_land);
+            float x[16];
             {
                 const uint4* xp = (const uint4*)(sLand + n * LAND_GATE + LAND_X + c0 * 2);
                 Elem<bf16_t>::unpack(xp[0], xp[1], x);
@@ -578,6 +622,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         }
         __syncthreads();                      // sH complete; every wave has read its residual rows
         lap(4);
+        roles();
         // the landing zone of the gates' own rows is free now: the next tile's may come in
         if (!DG4_OWN_LATE && has_next) gather_own(nxt.x, (int)nxt.y, d1);
 
@@ -585,12 +630,11 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         {
             f32x4 acc[8];
 #pragma unroll
-            for (int nt = 0; nt < 8; ++nt) acc[nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-#pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
                 const uint4 b = *(const uint4*)&sH[n][8 * grp + ks * 32];
 #pragma unroll
-                for (int nt = 0; nt < 8; ++nt) acc[nt] = mfma16(__builtin_bit_cast(uint4, wkv_r[nt][ks]), b, acc[nt]);
+                for (int nt = 0; nt < 8; ++nt)
+                    acc[nt] = mfma16(__builtin_bit_cast(uint4, wkv_r[nt][ks]), b, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[nt]);
             }
             if (DG4_OWN_LATE && has_next) gather_own(nxt.x, (int)nxt.y, d1);
             uint4* dst = (uint4*)&sKV[n][128 * wave + 32 * grp];
