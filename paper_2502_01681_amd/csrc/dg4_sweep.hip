@@ -70,9 +70,17 @@ __device__ __forceinline__ f32x4 mfma16(const uint4& a, const uint4& b, f32x4 c)
 // outstanding transfer before ANY later LDS read, whatever its address. The transfers count in
 // vmcnt like loads and complete in issue order; a reader waits with s_waitcnt (plus a barrier if
 // another wave issued the transfer).
+// (the scalar operands go through readfirstlane: the compiler does not do that by itself for a
+// value it keeps in a vector register, and folds it away for one it knows to be uniform)
+__device__ __forceinline__ uint32_t uniform32(uint32_t v) { return (uint32_t)__builtin_amdgcn_readfirstlane((int)v); }
+__device__ __forceinline__ const void* uniform_ptr(const void* q)
+{
+    const uint64_t a = (uint64_t)(uintptr_t)q;
+    return (const void*)(uintptr_t)((uint64_t)uniform32((uint32_t)a) | ((uint64_t)uniform32((uint32_t)(a >> 32)) << 32));
+}
 __device__ __forceinline__ void dma16(const void* src, uint32_t lds_base)
 {
-    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_base) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform32(lds_base)) : "memory");
 }
 // same with a wave-uniform 64-bit base and a per-lane 32-bit byte offset
 __device__ __forceinline__ void dma16_row(const void* base, uint32_t lane_off, uint32_t lds_base)
@@ -83,13 +91,12 @@ __device__ __forceinline__ void dma16_row(const void* base, uint32_t lane_off, u
     __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t; %0 %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
     return;
 #endif
-    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory");
 }
-
 // one 32-bit word per lane, read at device scope (served by the L2, never by this unit's L1)
 __device__ __forceinline__ void dma4_fresh(const void* base, uint32_t lane_off, uint32_t lds_base)
 {
-    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 sc1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 sc1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory");
 }
 
 // Packed order for weights used as the A operand of a 16x16x32 MFMA, in
@@ -713,115 +720,158 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
 }
 
 // --------------------------------------------------------------------------------------------
-// Bulk projection (bf16, hidden 256): out[r, :] = S[idx(r), :] x W for many rows at once, e.g.
+// Bulk projection (bf16, hidden 256): out[r, 0..767] = S[idx(r), :] x Wqkv for many rows at once:
 // Q | K | V of x for every gate before the sweep, or dg4_qkv_proj. HBM-bound (512 B in, 1.5 KB
-// out per row), so the aim is full-width rows in and out with the matrix cores kept fed:
-// a wave owns 64 rows (two 32-row B operands held in registers for all of K = 256) and walks
-// over the output columns two 32-column tiles at a time; the weight tiles (A operand) stream
-// from L2 and are each used for both row blocks. With the rows as B operand a lane ends up with
-// 32 CONTIGUOUS output columns of one row per tile pair (64-byte stores).
+// out per row). One persistent workgroup per compute unit keeps ALL of Wq|Wk|Wv in its
+// registers (each wave 192 output columns: 96 fragments, 256 accumulation + 128 vector
+// registers) and streams 16-row tiles past them: the rows of the next tile travel straight into
+// LDS while this one is multiplied, results are transposed through LDS and leave as whole rows.
 namespace {
 
-typedef float f32x16s __attribute__((ext_vector_type(16)));
+constexpr int PS_XSTRIDE = 264;                          // bf16 per input row in LDS (16 bytes of padding)
+constexpr int PS_OSTRIDE = 776;                          // bf16 per staged output row
+constexpr int PS_OUT = 2 * TILE * PS_XSTRIDE * 2;        // two input tiles first
+constexpr int PS_BYTES = PS_OUT + TILE * PS_OSTRIDE * 2;
+constexpr int PS_NT = 12;                                // column tiles of 16 per wave
 
-__device__ __forceinline__ f32x16s mfma32(const uint4& a, const uint4& b, f32x16s c)
+__global__ __launch_bounds__(256, 1) void proj768_kernel(dg4_bulk_args p)
 {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a), __builtin_bit_cast(bf16x8s, b), c, 0, 0, 0);
-}
-
-// Packed order, 16-byte units: unit ((tile*16 + ks)*64 + lane) holds rows k = ks*16 + 8*(lane/32) .. +7
-// of column  col0 + (tile/2)*64 + g*32 + (tile%2)*16 + a*4 + b,  where m = lane%32 = 8a + 4g + b.
-__global__ void pack_w32_kernel(const uint16_t* w, int ld, int col0, int n_cols, uint16_t* packed)
-{
-    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    const int64_t units = (int64_t)(n_cols / 32) * 16 * 64;
-    if (unit >= units) return;
-    const int lane = (int)(unit & 63);
-    const int ks = (int)((unit >> 6) & 15);
-    const int tile = (int)(unit >> 10);
-    const int m = lane & 31;
-    const int a = m >> 3, g = (m >> 2) & 1, b = m & 3;
-    const int col = col0 + (tile >> 1) * 64 + g * 32 + (tile & 1) * 16 + a * 4 + b;
-    const int k0 = ks * 16 + 8 * (lane >> 5);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) packed[unit * 8 + j] = w[(int64_t)(k0 + j) * ld + col];
-}
-
-__global__ __launch_bounds__(256, 2) void bulk_proj_kernel(dg4_bulk_args p)
-{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int n = lane & 31, g = lane >> 5;
-    const int64_t r0 = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * 64;
-    if (r0 >= p.row_end) return;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int n = lane & 15, g = lane >> 4;
+    const __attribute__((address_space(4))) int32_t* gat = (const __attribute__((address_space(4))) int32_t*)p.gather;
 
-    // the two 32-row blocks of this wave as B operands for all 16 k-steps
-    uint4 act[2][16];
-    int64_t orow[2];
-    bool ok[2];
+    u32x4 wa[8][8], wb[PS_NT - 8][8];
+    {
+        const uint4* w = (const uint4*)p.w_packed + (int64_t)wave * PS_NT * 8 * 64 + lane;
 #pragma unroll
-    for (int rb = 0; rb < 2; ++rb) {
-        int64_t r = r0 + rb * 32 + n;
-        ok[rb] = r < p.row_end;
-        if (!ok[rb]) r = p.row_end - 1;                  // clamp: loads stay in bounds, stores are masked
-        orow[rb] = r;
-        const int64_t sr = p.gather ? (int64_t)p.gather[r] : r;
-        const uint4* sp = (const uint4*)(p.src + sr * D);
+        for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
-        for (int ks = 0; ks < 16; ++ks) act[rb][ks] = sp[ks * 2 + g];
+            for (int ks = 0; ks < 8; ++ks) wa[nt][ks] = __builtin_bit_cast(u32x4, w[(nt * 8 + ks) * 64]);
+#pragma unroll
+        for (int nt = 8; nt < PS_NT; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) wb[nt - 8][ks] = __builtin_bit_cast(u32x4, w[(nt * 8 + ks) * 64]);
     }
-    const uint4* wp = (const uint4*)p.w_packed + lane;
-    const int n_pairs = p.n_cols / 64;
-    for (int pr = 0; pr < n_pairs; ++pr) {
-        f32x16s acc[2][2];
+    const int64_t n_rows = p.row_end - p.row_begin;
+    const int64_t n_tiles = (n_rows + TILE - 1) / TILE;
+    const int64_t G = gridDim.x;
+    int64_t t = blockIdx.x;
+    if (t >= n_tiles) return;
+
+    // wave w fetches rows 4w .. 4w+3 of a tile, one 512-byte transfer each (lanes 0..31); rows
+    // past the end are clamped to the last one (their results are not stored)
+    auto rows_of = [&](int64_t tile, int64_t* sr) __attribute__((always_inline)) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb)
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int i = 0; i < 16; ++i) acc[rb][t][i] = 0.f;
-#pragma unroll
-        for (int ks = 0; ks < 16; ++ks) {
-            const uint4 w0 = wp[((int64_t)(2 * pr) * 16 + ks) * 64];
-            const uint4 w1 = wp[((int64_t)(2 * pr + 1) * 16 + ks) * 64];
-#pragma unroll
-            for (int rb = 0; rb < 2; ++rb) {
-                acc[rb][0] = mfma32(w0, act[rb][ks], acc[rb][0]);
-                acc[rb][1] = mfma32(w1, act[rb][ks], acc[rb][1]);
-            }
+        for (int q = 0; q < 4; ++q) {
+            int64_t r = p.row_begin + tile * TILE + 4 * wave + q;
+            if (r >= p.row_end) r = p.row_end - 1;
+            sr[q] = gat ? (int64_t)gat[r] : r;
         }
-        // lane (n, g): columns pr*64 + g*32 + t*16 + a*4 + b  <-  acc[rb][t][4a + b]
-        const int col = pr * 64 + g * 32;
-        uint16_t* base = p.out[col / D] + (col % D);
+    };
+    auto fetch = [&](const int64_t* sr, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int rb = 0; rb < 2; ++rb) {
-            if (!ok[rb]) continue;
-            uint4* op = (uint4*)(base + orow[rb] * p.out_stride);
+        for (int q = 0; q < 4; ++q)
+            if (lane < 32)
+                dma16_row((const unsigned char*)p.src + sr[q] * (D * 2), (uint32_t)lane * 16u,
+                          lds0 + (uint32_t)(buf * TILE * PS_XSTRIDE * 2 + (4 * wave + q) * PS_XSTRIDE * 2));
+    };
+    // this lane's three 16-byte pieces of a pair of output rows (3072 bytes = three 1 KB stores):
+    // which row of the pair, where in the staged row, where in the caller's tensors
+    uint32_t st_lds[3];
+    int st_row[3];
+    unsigned char* st_ptr[3];
 #pragma unroll
-            for (int t = 0; t < 2; ++t) {
-                const f32x16s c = acc[rb][t];
-                op[2 * t] = make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]), pack_bf16x2(c[4], c[5]), pack_bf16x2(c[6], c[7]));
-                op[2 * t + 1] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]), pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
+    for (int i = 0; i < 3; ++i) {
+        const int o = i * 1024 + lane * 16;
+        st_row[i] = o >= 3 * D * 2 ? 1 : 0;
+        const int cb = o - st_row[i] * 3 * D * 2;            // byte within the 1536-byte row
+        st_lds[i] = (uint32_t)(PS_OUT + st_row[i] * PS_OSTRIDE * 2 + cb);
+        st_ptr[i] = (unsigned char*)p.out[cb / (D * 2)] + cb % (D * 2);
+    }
+
+    {
+        int64_t sr[4];
+        rows_of(t, sr);
+        fetch(sr, 0);
+    }
+    int buf = 0;
+    bool first = true;
+    for (;;) {
+#pragma unroll
+        for (int nt = 0; nt < 8; ++nt)
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) __asm__ volatile("" : "+a"(wa[nt][ks]));
+        const bool has_next = t + G < n_tiles;
+        const int64_t r0 = p.row_begin + t * TILE;
+        // Transfers and stores complete in issue order: this tile's rows were requested before
+        // the six stores of the previous tile, which need not be waited for.
+        if (first) __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+        else __builtin_amdgcn_s_waitcnt(0x0F76);             // vmcnt(6)
+        __asm__ volatile("" ::: "memory");
+        first = false;
+        __syncthreads();          // every wave's rows have landed; the staging rows have been read
+        int64_t next_rows[4];                   // (row numbers now, the transfers once the matrix cores are busy)
+        if (has_next) rows_of(t + G, next_rows);
+
+        const uint16_t (*sX)[PS_XSTRIDE] = (const uint16_t (*)[PS_XSTRIDE])(smem + buf * TILE * PS_XSTRIDE * 2);
+        uint16_t (*sO)[PS_OSTRIDE] = (uint16_t (*)[PS_OSTRIDE])(smem + PS_OUT);
+        uint4 b[8];                             // the tile as B operand, read once for all 12 column tiles
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) b[ks] = *(const uint4*)&sX[n][8 * g + ks * 32];
+#pragma unroll
+        for (int cg = 0; cg < 3; ++cg) {
+            f32x4 acc[4];
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) {
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int nt = cg * 4 + j;
+                    const uint4 a = nt < 8 ? __builtin_bit_cast(uint4, wa[nt < 8 ? nt : 0][ks]) : __builtin_bit_cast(uint4, wb[nt < 8 ? 0 : nt - 8][ks]);
+                    acc[j] = mfma16(a, b[ks], ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[j]);
+                }
             }
+            if (cg == 0 && has_next) fetch(next_rows, buf ^ 1);
+            // lane (n, g) owns columns 192*wave + 48*g + 16*cg .. +15 of row n
+            uint4* dst = (uint4*)&sO[n][192 * wave + 48 * g + 16 * cg];
+            dst[0] = make_uint4(pack_bf16x2(acc[0][0], acc[0][1]), pack_bf16x2(acc[0][2], acc[0][3]),
+                                pack_bf16x2(acc[1][0], acc[1][1]), pack_bf16x2(acc[1][2], acc[1][3]));
+            dst[1] = make_uint4(pack_bf16x2(acc[2][0], acc[2][1]), pack_bf16x2(acc[2][2], acc[2][3]),
+                                pack_bf16x2(acc[3][0], acc[3][1]), pack_bf16x2(acc[3][2], acc[3][3]));
         }
+        __syncthreads();          // staged rows complete
+        // wave w stores rows 4w .. 4w+3, two at a time
+#pragma unroll
+        for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+            for (int i = 0; i < 3; ++i) {
+                const int row = 4 * wave + 2 * pr + st_row[i];
+                const uint4 v = *(const uint4*)(smem + st_lds[i] + (4 * wave + 2 * pr) * PS_OSTRIDE * 2);
+#ifdef PS_NOSTORE
+                if (v.x == 0x12345u && r0 + row < p.row_end) *(uint4*)(st_ptr[i] + (r0 + row) * p.out_stride * 2) = v;
+#else
+                if (r0 + row < p.row_end) *(uint4*)(st_ptr[i] + (r0 + row) * p.out_stride * 2) = v;
+#endif
+            }
+        if (!has_next) return;
+        t += G;
+        buf ^= 1;
     }
 }
 
 }  // namespace
 
-int dg4_launch_pack_w32(const void* w, int ld, int col0, int n_cols, void* packed, hipStream_t s)
-{
-    const int64_t units = (int64_t)(n_cols / 32) * 16 * 64;
-    hipLaunchKernelGGL(pack_w32_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
-                       (const uint16_t*)w, ld, col0, n_cols, (uint16_t*)packed);
-    return hipGetLastError();
-}
-
 int dg4_launch_bulk_proj(const dg4_bulk_args& a, hipStream_t s)
 {
     const int64_t rows = a.row_end - a.row_begin;
     if (rows <= 0) return hipSuccess;
-    if (a.n_cols % 64) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(bulk_proj_kernel, dim3((unsigned)((rows + 255) / 256)), dim3(256), 0, s, a);
+    if (a.n_cols != 3 * D) return hipErrorInvalidValue;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
+    const int64_t tiles = (rows + TILE - 1) / TILE;
+    hipLaunchKernelGGL(proj768_kernel, dim3((unsigned)std::min<int64_t>(cus, tiles)), dim3(256), PS_BYTES, s, a);
     return hipGetLastError();
 }
