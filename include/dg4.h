@@ -65,7 +65,8 @@ typedef struct {
  *     not be topological. edge_inv[e] in {0,1} marks an inverted fanin edge.
  *   - level(v) by Eq. 1; or, if level_hint (n_nodes entries) is given, the hint
  *     after checking hint[PI] == 0 and hint[dst] > hint[src] for every edge. The
- *     level only fixes the sweep schedule; embeddings do not depend on it.
+ *     level only names the ranges a sweep can be cut into (level_begin, level_end of
+ *     dg4_layer_fwd) and orders the work of a partial sweep; embeddings do not depend on it.
  *   - order: node ids sorted by (level, id).
  *   - neighbour rows N(v) = cone_hops(v), v included, at most 2^(hops+1)-1
  *     entries, ascending id, each with a relation code: 0 self, 1 direct fanin,
@@ -86,7 +87,13 @@ typedef enum {
     DG4_LEVEL_PTR = 2,  /* int64  [n_levels + 1] first position of each level  */
     DG4_NBR_PTR = 3,    /* int64  [n_nodes + 1]                                */
     DG4_NBR_IDX = 4,    /* int32  [nnz]                                        */
-    DG4_NBR_REL = 5     /* uint8  [nnz]                                        */
+    DG4_NBR_REL = 5,    /* uint8  [nnz]                                        */
+    /* The order in which a sweep over ALL levels processes the gates on the device: tiles of at
+     * most 16 gates, each gate after every gate of its neighbour row (list scheduling over the
+     * real dependencies; the level only breaks ties). For inspection and tests; the embeddings do
+     * not depend on it. Built on first request. */
+    DG4_FLOW_ORDER = 6,     /* int32 [n_nodes]     node ids in processing order          */
+    DG4_FLOW_TILE_PTR = 7   /* int64 [n_tiles + 1] first position of each tile           */
 } dg4_array;
 
 int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count);

@@ -17,7 +17,8 @@ DG4_F32, DG4_BF16 = 0, 1
 DG4_NO_EPILOGUE = 1
 DG4_PER_LEVEL = 2
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
-          "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8)}
+          "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8),
+          "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64)}
 STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
           -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP"}
 

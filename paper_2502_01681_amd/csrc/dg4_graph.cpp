@@ -214,6 +214,18 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
     case DG4_NBR_PTR: *host_ptr = g->nbr_ptr.data(); *count = g->n + 1; break;
     case DG4_NBR_IDX: *host_ptr = g->nbr_idx.data(); *count = g->nnz; break;
     case DG4_NBR_REL: *host_ptr = g->nbr_rel.data(); *count = g->nnz; break;
+    case DG4_FLOW_ORDER:
+    case DG4_FLOW_TILE_PTR: {
+        dg4_graph* m = const_cast<dg4_graph*>(g);            // the schedule is built on first use, under the lock
+        std::lock_guard<std::mutex> lock(m->mu);
+        if (m->flow_tile_ptr.empty()) {
+            const int rc = dg4_flow_schedule(m, 640);
+            if (rc != DG4_OK) return rc;
+        }
+        if (which == DG4_FLOW_ORDER) { *host_ptr = g->flow_order.data(); *count = g->n; }
+        else { *host_ptr = g->flow_tile_ptr.data(); *count = (int64_t)g->flow_tile_ptr.size(); }
+        break;
+    }
     default: return DG4_EINVAL;
     }
     return DG4_OK;
@@ -226,6 +238,75 @@ extern "C" int dg4_graph_info(const dg4_graph* g, int64_t* n_nodes, int64_t* n_l
     if (n_levels) *n_levels = (int64_t)g->max_level + 1;
     if (nnz) *nnz = g->nnz;
     if (hops) *hops = g->hops;
+    return DG4_OK;
+}
+
+// Dataflow order for whole-graph sweeps: list scheduling over the real dependencies. A tile takes
+// the (up to) 16 gates whose direct fanins all sit in EARLIER tiles and whose latest cone source
+// is oldest (`due` = tile of that source + slack); ties go to the lower level, then the lower id.
+// `slack` tiles between a source and its reader let the source be published before the reader looks
+// for it. Results do not depend on the order; it only decides who waits for whom.
+int dg4_flow_schedule(dg4_graph* g, int64_t slack)
+{
+    if (!g->flow_tile_ptr.empty()) return DG4_OK;          // built once: pointers into it may have been handed out
+    try {
+        std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
+        std::vector<int32_t> remaining((size_t)g->n, 0);
+        for (int64_t v = 0; v < g->n; ++v)
+            for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) { ++fo_ptr[(size_t)g->nbr_idx[j] + 1]; ++remaining[v]; }
+        for (int64_t v = 0; v < g->n; ++v) fo_ptr[v + 1] += fo_ptr[v];
+        std::vector<int32_t> fo((size_t)fo_ptr[g->n]);
+        {
+            std::vector<int64_t> fill(fo_ptr.begin(), fo_ptr.end() - 1);
+            for (int64_t v = 0; v < g->n; ++v)
+                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                    if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fo[(size_t)fill[g->nbr_idx[j]]++] = (int32_t)v;
+        }
+        struct Item { int64_t due; int32_t level; int32_t v; };
+        auto later = [](const Item& a, const Item& b) {
+            if (a.due != b.due) return a.due > b.due;
+            if (a.level != b.level) return a.level > b.level;
+            return a.v > b.v;
+        };
+        std::priority_queue<Item, std::vector<Item>, decltype(later)> ready(later);
+        for (int64_t v = 0; v < g->n; ++v)
+            if (remaining[v] == 0) ready.push(Item{0, g->level[v], (int32_t)v});
+        std::vector<int32_t> tile_of((size_t)g->n, -1);
+        std::vector<int32_t> flow((size_t)g->n, 0);
+        std::vector<int64_t> tile_ptr(1, 0);
+        std::vector<Item> fresh;
+        int64_t q = 0;
+        while (!ready.empty()) {
+            const int64_t t = (int64_t)tile_ptr.size() - 1;
+            const int64_t first = q;
+            for (int k = 0; k < DG4_TILE_ROWS && !ready.empty(); ++k) {
+                const int32_t v = ready.top().v;
+                ready.pop();
+                tile_of[v] = (int32_t)t; flow[(size_t)q++] = v;
+            }
+            tile_ptr.push_back(q);
+            fresh.clear();
+            for (int64_t p = first; p < q; ++p) {
+                const int32_t v = flow[(size_t)p];
+                for (int64_t j = fo_ptr[v]; j < fo_ptr[v + 1]; ++j) {
+                    const int32_t u = fo[(size_t)j];
+                    if (--remaining[u] != 0) continue;
+                    int64_t newest = -1;      // every cone source is scheduled: it precedes a direct fanin
+                    for (int64_t i = g->nbr_ptr[u]; i < g->nbr_ptr[u + 1]; ++i)
+                        if (g->nbr_idx[i] != u) newest = std::max<int64_t>(newest, tile_of[g->nbr_idx[i]]);
+                    fresh.push_back(Item{newest + slack, g->level[u], u});
+                }
+            }
+            for (const Item& it : fresh) ready.push(it);     // eligible from the next tile on
+        }
+        if (q != g->n) return DG4_ECYCLE;                      // cannot happen for a validated DAG
+        g->flow_order.swap(flow);
+        g->flow_tile_ptr.swap(tile_ptr);
+        g->flow_slack = slack;
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
     return DG4_OK;
 }
 
@@ -294,67 +375,23 @@ int dg4_graph_ensure_device(dg4_graph* g)
                 tiles.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(DG4_TILE_ROWS, g->level_ptr[l + 1] - p0)));
         }
         g->level_tile_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
-        // Dataflow order for whole-graph sweeps. A tile takes the (up to) 16 gates whose direct
-        // fanins all sit in EARLIER tiles and whose latest cone source is oldest; ties go to the
-        // lower level, then the lower id. `slack` tiles between a source and its reader let the
-        // source be published before the reader looks for it (tiles are dealt round-robin to one
-        // workgroup per compute unit, so `cus` tiles are in flight at once).
-        std::vector<int32_t> flow(rows, 0);
-        std::vector<uint2> flow_tiles;
-        std::vector<uint32_t> by_flow(rows * w, DG4_ELL_PAD);
+        // Dataflow order for whole-graph sweeps (dg4_flow_schedule), with room between a source and
+        // its readers for as many tiles as are in flight at once (one workgroup per compute unit).
         {
             int cus = 0;
             if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-            const int64_t slack = (int64_t)cus * 5 / 2;
-            std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
-            std::vector<int32_t> remaining((size_t)g->n, 0);
-            for (int64_t v = 0; v < g->n; ++v)
-                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
-                    if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) { ++fo_ptr[(size_t)g->nbr_idx[j] + 1]; ++remaining[v]; }
-            for (int64_t v = 0; v < g->n; ++v) fo_ptr[v + 1] += fo_ptr[v];
-            std::vector<int32_t> fo((size_t)fo_ptr[g->n]);
-            {
-                std::vector<int64_t> fill(fo_ptr.begin(), fo_ptr.end() - 1);
-                for (int64_t v = 0; v < g->n; ++v)
-                    for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
-                        if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fo[(size_t)fill[g->nbr_idx[j]]++] = (int32_t)v;
-            }
-            struct Item { int64_t due; int32_t level; int32_t v; };
-            auto later = [](const Item& a, const Item& b) {
-                if (a.due != b.due) return a.due > b.due;
-                if (a.level != b.level) return a.level > b.level;
-                return a.v > b.v;
-            };
-            std::priority_queue<Item, std::vector<Item>, decltype(later)> ready(later);
-            for (int64_t v = 0; v < g->n; ++v)
-                if (remaining[v] == 0) ready.push(Item{0, g->level[v], (int32_t)v});
-            std::vector<int32_t> tile_of((size_t)g->n, -1), fpos((size_t)g->n, -1);
-            std::vector<Item> fresh;
-            int64_t q = 0;
-            while (!ready.empty()) {
-                const int64_t t = (int64_t)flow_tiles.size();
-                const int64_t first = q;
-                for (int k = 0; k < DG4_TILE_ROWS && !ready.empty(); ++k) {
-                    const int32_t v = ready.top().v;
-                    ready.pop();
-                    tile_of[v] = (int32_t)t; fpos[v] = (int32_t)q; flow[(size_t)q++] = v;
-                }
-                flow_tiles.push_back(make_uint2((uint32_t)first, (uint32_t)(q - first)));
-                fresh.clear();
-                for (int64_t p = first; p < q; ++p) {
-                    const int32_t v = flow[(size_t)p];
-                    for (int64_t j = fo_ptr[v]; j < fo_ptr[v + 1]; ++j) {
-                        const int32_t u = fo[(size_t)j];
-                        if (--remaining[u] != 0) continue;
-                        int64_t newest = -1;      // every cone source is scheduled: it precedes a direct fanin
-                        for (int64_t i = g->nbr_ptr[u]; i < g->nbr_ptr[u + 1]; ++i)
-                            if (g->nbr_idx[i] != u) newest = std::max<int64_t>(newest, tile_of[g->nbr_idx[i]]);
-                        fresh.push_back(Item{newest + slack, g->level[u], u});
-                    }
-                }
-                for (const Item& it : fresh) ready.push(it);     // eligible from the next tile on
-            }
-            if (q != g->n) return DG4_ECYCLE;                      // cannot happen for a validated DAG
+            const int rc = dg4_flow_schedule(g, (int64_t)cus * 5 / 2);
+            if (rc != DG4_OK) return rc;
+        }
+        std::vector<int32_t> flow(rows, 0);
+        std::copy(g->flow_order.begin(), g->flow_order.end(), flow.begin());
+        std::vector<uint2> flow_tiles(g->flow_tile_ptr.size() - 1);
+        for (size_t t = 0; t + 1 < g->flow_tile_ptr.size(); ++t)
+            flow_tiles[t] = make_uint2((uint32_t)g->flow_tile_ptr[t], (uint32_t)(g->flow_tile_ptr[t + 1] - g->flow_tile_ptr[t]));
+        std::vector<uint32_t> by_flow(rows * w, DG4_ELL_PAD);
+        {
+            std::vector<int32_t> fpos((size_t)g->n, -1);
+            for (int64_t q = 0; q < g->n; ++q) fpos[(size_t)g->flow_order[(size_t)q]] = (int32_t)q;
             for (int64_t v = 0; v < g->n; ++v) {
                 const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
                 uint32_t* r = &by_flow[(size_t)fpos[v] * w];

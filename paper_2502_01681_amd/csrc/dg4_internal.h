@@ -40,7 +40,11 @@ struct dg4_graph {
     uint2* d_tiles = nullptr;        // [n_tiles] (first position, rows)
     // A second processing order for sweeps over ALL levels: tiles filled by list scheduling over
     // the real dependencies (a gate goes as early as its sources allow, sources long finished
-    // first), not level by level. Same layout as the three tables above.
+    // first), not level by level. Host copy (node ids in processing order, first position of
+    // each tile), then device tables with the layout of the three above.
+    std::vector<int32_t> flow_order;
+    std::vector<int64_t> flow_tile_ptr;
+    int64_t flow_slack = -1;
     uint32_t* d_flow_ell = nullptr;
     int32_t* d_flow_order = nullptr;
     uint2* d_flow_tiles = nullptr;
@@ -48,6 +52,7 @@ struct dg4_graph {
 };
 
 int dg4_graph_ensure_device(dg4_graph* g);
+int dg4_flow_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
 
 // ---- kernel launchers (dg4_kernels.hip). All return a hipError_t as int. ----
 

@@ -1,21 +1,31 @@
-// The level sweep as ONE persistent dataflow kernel (bf16, hidden 256, one layer).
+// The level sweep as ONE persistent dataflow kernel (bf16, hidden 256, one layer, two-hop cones).
 //
 // The updating strategy (paper Section 3.4, Algorithm 2) orders the work level
 // by level; what it requires is that a gate reads the FINAL embeddings of its
-// cone sources and is itself computed once. Work is cut into tiles of 16
-// level-sorted gates (never across a level boundary). Resident workgroups draw
-// tiles from a global ticket counter in (level, id) order; a tile spins only on
-// the "finished" flags of ITS sources, so several levels are in flight at once
-// while every gate still sees exactly the values the level-by-level sweep
-// would give it. A workgroup waits only for lower tickets, and those are held
-// by workgroups that are already running, so the wait always ends; a bounded
-// spin count turns any violation into an abort flag instead of a hang.
+// cone sources and is itself computed once. Work is cut into tiles of at most 16
+// gates, in an order in which every source of a gate sits in an earlier tile:
+// level by level, or (whole-graph sweeps) list-scheduled over the dependencies.
+// One workgroup per compute unit; workgroup b owns tiles b, b + G, b + 2G, ...
+// A tile waits only on the "published" flags of ITS sources, so many levels are
+// in flight at once while every gate still sees exactly the values the
+// level-by-level sweep would give it. A tile waits only for lower-numbered
+// tiles, and those belong to workgroups that are running, so the wait always
+// ends; a bounded spin count turns any violation into an abort flag instead of
+// a hang.
+//
+// With the weights resident in registers (Wo in vector registers, Wk|Wv in the
+// accumulation registers) there is ONE wave per SIMD: nothing hides latency for
+// free, and every instruction costs four cycles of issue. Hence the shape of
+// the code: rows travel from global memory straight into LDS (no registers, no
+// waits in between), the next tile's sources are requested while this tile's
+// attention runs, and the per-row bookkeeping is vectorised across lanes.
 //
 // Per tile: attention over the cone rows (lanes split the feature dimension,
-// softmax in registers), output projection on the matrix cores with the tile
-// as the B operand (so a lane ends up owning CONTIGUOUS output columns of one
-// gate), residual + LayerNorm in registers, K|V projection of the new
-// embeddings, publication of the rows and of the flags.
+// scores and softmax in registers), output projection on the matrix cores with
+// the tile as the B operand (so a lane ends up owning CONTIGUOUS output columns
+// of one gate), residual + LayerNorm in registers, K|V projection of the new
+// embeddings, publication of the rows and, once they are written through, of
+// the flags.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 

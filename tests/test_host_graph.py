@@ -53,6 +53,34 @@ def test_tables_bit_exact_against_oracle(name, n_and, hops):
         assert g.n == n and g.n_levels == og.n_levels and g.nnz == len(og.nbr_idx)
 
 
+@pytest.mark.parametrize("name,n_and,hops,hint", [("tiny", None, 2, False), ("small", None, 2, False),
+                                                   ("large", 60_000, 2, True), ("large", 60_000, 2, False),
+                                                   ("stress", 40_000, 3, True)])
+def test_dataflow_order_is_a_valid_schedule(name, n_and, hops, hint):
+    # the order of whole-graph sweeps on the device: every gate once, in tiles of at most 16, and
+    # every gate of a neighbour row in a strictly earlier tile than the row's own gate
+    w = synth.make(name, n_and=n_and, features=False)
+    n = w.cfg.n_nodes
+    g = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint if hint else None)
+    order, tp = g.array("flow_order"), g.array("flow_tile_ptr")
+    assert sorted(order.tolist()) == list(range(n))
+    assert tp[0] == 0 and tp[-1] == n
+    rows = np.diff(tp)
+    assert rows.min() >= 1 and rows.max() <= 16
+    tile_of = np.empty(n, dtype=np.int64)
+    tile_of[order] = np.repeat(np.arange(len(rows)), rows)
+    ptr, idx = g.array("nbr_ptr"), g.array("nbr_idx")
+    dst = np.repeat(np.arange(n), np.diff(ptr))
+    other = idx != dst
+    assert (tile_of[idx[other]] < tile_of[dst[other]]).all()
+    # a primary input has no source: all of them fit into the leading tiles, which are full
+    n_pi = int((np.diff(ptr) == 1).sum())
+    assert (rows[: n_pi // 16] == 16).all()
+    # the same graph gives the same order again
+    g2 = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint if hint else None)
+    assert (g2.array("flow_order") == order).all()
+
+
 def test_shuffled_edges_and_relabelled_nodes():
     w = synth.make("small", n_and=5000, features=False)
     n = w.cfg.n_nodes
