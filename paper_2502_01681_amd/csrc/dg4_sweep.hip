@@ -166,6 +166,17 @@ __device__ __forceinline__ void issue_slots(uint32_t lo, uint32_t hi, uint32_t l
         }
 }
 
+// x summed over the four 16-lane rows of a wave (lanes with equal lane % 16), in every lane:
+// two row exchanges on the vector ALU instead of four trips through the LDS crossbar
+__device__ __forceinline__ float sum_rows(float x)
+{
+    const uint32_t u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);      // rows (0,1) and (2,3) exchanged
+    const uint32_t v = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);      // halves exchanged
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
 template <int W, bool TIMERS>
 __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 {
@@ -385,15 +396,29 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         const bool has_next = ticket + G < p.n_tiles;
         roles();
 
-        // ---------------- publish the previous tile. Loads and stores of a wave complete in order,
-        // so one wait covers both the K|V row stores of the previous tile (complete = written
-        // through, visible to every compute unit) and the gathers of this tile issued behind
-        // them. Each wave raises the flags of the four rows it stored itself. This happens
-        // before any blocking wait below: other workgroups may be waiting for these rows.
-        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
-        __asm__ volatile("" ::: "memory");
-        if (lane < 4 && 4 * wave + lane < pub_rows)
-            __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        // ---------------- the previous tile's rows and this tile's gathers. Loads and stores of a
+        // wave complete in order, and the last things it issued were the eight K|V row stores
+        // of the previous tile: once at most eight operations are outstanding, every gather of
+        // this tile has landed, and the attention can start while the stores are still on
+        // their way. The flags of those rows (each wave raises the four it stored itself)
+        // follow further down, once the stores have completed (= are written through, visible
+        // to every compute unit). Only a wave that has to wait for late sources, or whose
+        // previous tile was ragged (fewer stores), waits for everything here: the flags must
+        // be up before any blocking wait, other workgroups may be waiting for them.
+        auto publish = [&]() __attribute__((always_inline)) {
+            if (lane < 4 && 4 * wave + lane < pub_rows)
+                __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        };
+        bool published = false;
+        if (TIMERS || late || pub_rows != TILE) {     // (the timed build has a barrier right below: flags first)
+            __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
+            __asm__ volatile("" ::: "memory");
+            publish();
+            published = true;
+        } else {
+            __builtin_amdgcn_s_waitcnt(0x0F78);       // vmcnt(8)
+            __asm__ volatile("" ::: "memory");
+        }
         lap(6);
         // sources that were not published yet when this tile's gathers went out
         if (late) wait_and_gather(d0, rows, late, need_cur);
@@ -490,6 +515,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             {
                 __builtin_amdgcn_s_waitcnt(0x0F70);
                 __asm__ volatile("" ::: "memory");
+                if (!published) publish();        // the previous tile's row stores have completed too
                 need_nxt = __ballot(nneed);
                 const bool upl = nneed && looked(0) != 0u;
                 up_nxt = __ballot(upl);
@@ -603,8 +629,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             float s1 = 0.f, s2 = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) { s1 += t[i]; s2 = fmaf(t[i], t[i], s2); }
-            s1 += __shfl_xor(s1, 16); s2 += __shfl_xor(s2, 16);
-            s1 += __shfl_xor(s1, 32); s2 += __shfl_xor(s2, 32);
+            s1 = sum_rows(s1); s2 = sum_rows(s2);
             if (grp == 0) { sRed[n][wave][0] = s1; sRed[n][wave][1] = s2; }
             __syncthreads();
                 float a1 = 0.f, a2 = 0.f;
