@@ -129,7 +129,7 @@ extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row
     hipStream_t s = (hipStream_t)stream;
     const int d = cfg->hidden;
     if (cfg->dtype == DG4_BF16 && d == 256) {
-        HIPCHK(dg4_launch_pack_wt(Wqkv, 3 * d, 0, 12, 4, workspace, s));
+        HIPCHK(dg4_launch_pack_w32(Wqkv, 3 * d, workspace, s));
         dg4_bulk_args b{};
         b.src = (const uint16_t*)S;
         b.w_packed = workspace; b.n_cols = 3 * d;
@@ -229,7 +229,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         // level by level; rows of the internal buffers are positions in the order in use.
         const bool whole = level_begin == 0 && level_end == (int32_t)g->max_level + 1 && !getenv("DG4_SWEEP_LEVEL_ORDER");
         {   // Q | K | V of x for every gate of the swept levels, rows in processing order
-            HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, 0, 12, 4, at(pl.wqkv[0]), s));
+            HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, at(pl.wqkv[0]), s));
             dg4_bulk_args b{};
             b.src = (const uint16_t*)X; b.gather = whole ? g->d_flow_order : g->d_order;
             b.w_packed = at(pl.wqkv[0]); b.n_cols = 3 * d;

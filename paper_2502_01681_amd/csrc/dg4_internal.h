@@ -113,9 +113,10 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s);
 struct dg4_bulk_args {
     const uint16_t* src;                   // [*, 256] input rows
     const int32_t* gather;                 // nullable: input row of output row r is gather[r]
-    const void* w_packed; int n_cols;      // pack_wt order (12 column tiles per wave, 4 waves); n_cols == 768
+    const void* w_packed; int n_cols;      // pack_w32 order; n_cols == 768
     uint16_t* out[2 * DG4_MAX_LAYERS + 3]; // column block j (256 columns) of row r at out[j] + r*out_stride
     int64_t out_stride;
     int64_t row_begin, row_end;
 };
+int dg4_launch_pack_w32(const void* w, int ld, void* packed, hipStream_t s);   // [256, 768] weights, row stride ld
 int dg4_launch_bulk_proj(const dg4_bulk_args& a, hipStream_t s);

@@ -758,16 +758,46 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
 // Bulk projection (bf16, hidden 256): out[r, 0..767] = S[idx(r), :] x Wqkv for many rows at once:
 // Q | K | V of x for every gate before the sweep, or dg4_qkv_proj. HBM-bound (512 B in, 1.5 KB
 // out per row). One persistent workgroup per compute unit keeps ALL of Wq|Wk|Wv in its
-// registers (each wave 192 output columns: 96 fragments, 256 accumulation + 128 vector
-// registers) and streams 16-row tiles past them: the rows of the next tile travel straight into
-// LDS while this one is multiplied, results are transposed through LDS and leave as whole rows.
+// registers (each wave 192 output columns: 96 fragments of a 32x32x16 product, 256 accumulation
+// + 128 vector registers) and streams 32-row tiles past them: the rows of the next two tiles
+// travel straight into LDS while this one is multiplied, results are transposed through LDS and
+// leave as whole rows.
 namespace {
 
+typedef float f32x16s __attribute__((ext_vector_type(16)));
+
+__device__ __forceinline__ f32x16s mfma32(const uint4& a, const uint4& b, f32x16s c)
+{
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8s, a), __builtin_bit_cast(bf16x8s, b), c, 0, 0, 0);
+}
+
+constexpr int PS_ROWS = 32;                              // rows per tile
 constexpr int PS_XSTRIDE = 264;                          // bf16 per input row in LDS (16 bytes of padding)
 constexpr int PS_OSTRIDE = 776;                          // bf16 per staged output row
-constexpr int PS_OUT = 2 * TILE * PS_XSTRIDE * 2;        // two input tiles first
-constexpr int PS_BYTES = PS_OUT + TILE * PS_OSTRIDE * 2;
-constexpr int PS_NT = 12;                                // column tiles of 16 per wave
+constexpr int PS_OUT = 3 * PS_ROWS * PS_XSTRIDE * 2;     // a ring of three input tiles first
+constexpr int PS_BYTES = PS_OUT + PS_ROWS * PS_OSTRIDE * 2;
+constexpr int PS_NT = 6;                                 // column tiles of 32 per wave
+
+// Weights as the A operand of a 32x32x16 product, 16-byte units: unit (((wave*6 + tile)*16 + ks)*64
+// + lane) holds rows k = ks*16 + 8*(lane/32) .. +7 of column 192*wave + 96*hi + 16*tile + 4*a + b,
+// where lane%32 = 8*a + 4*hi + b. With the rows of the tile as B operand, accumulator register
+// 4*a + b of lane (n = lane%32, hi = lane/32) is then row n, column 192*wave + 96*hi + 16*tile +
+// 4*a + b: every lane owns 96 contiguous columns of one row.
+__global__ void pack_w32_kernel(const uint16_t* w, int ld, uint16_t* packed)
+{
+    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (unit >= 4 * PS_NT * 16 * 64) return;
+    const int lane = (int)(unit & 63);
+    const int ks = (int)((unit >> 6) & 15);
+    const int t = (int)(unit >> 10);                   // wave*6 + tile
+    const int tile = t % PS_NT, wave = t / PS_NT;
+    const int m = lane & 31;
+    const int a = m >> 3, hi = (m >> 2) & 1, b = m & 3;
+    const int col = 192 * wave + 96 * hi + 16 * tile + 4 * a + b;
+    const int k0 = ks * 16 + 8 * (lane >> 5);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) packed[unit * 8 + j] = w[(int64_t)(k0 + j) * ld + col];
+}
 
 __global__ __launch_bounds__(256, 1) void proj768_kernel(dg4_bulk_args p)
 {
@@ -775,43 +805,50 @@ __global__ __launch_bounds__(256, 1) void proj768_kernel(dg4_bulk_args p)
     const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)smem;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int n = lane & 15, g = lane >> 4;
+    const int n = lane & 31, hi = lane >> 5;
     const __attribute__((address_space(4))) int32_t* gat = (const __attribute__((address_space(4))) int32_t*)p.gather;
 
-    u32x4 wa[8][8], wb[PS_NT - 8][8];
+    u32x4 wa[4][16], wb[PS_NT - 4][16];
     {
-        const uint4* w = (const uint4*)p.w_packed + (int64_t)wave * PS_NT * 8 * 64 + lane;
+        const uint4* w = (const uint4*)p.w_packed + (int64_t)wave * PS_NT * 16 * 64 + lane;
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt)
+        for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) wa[nt][ks] = __builtin_bit_cast(u32x4, w[(nt * 8 + ks) * 64]);
+            for (int ks = 0; ks < 16; ++ks) wa[nt][ks] = __builtin_bit_cast(u32x4, w[(nt * 16 + ks) * 64]);
 #pragma unroll
-        for (int nt = 8; nt < PS_NT; ++nt)
+        for (int nt = 4; nt < PS_NT; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) wb[nt - 8][ks] = __builtin_bit_cast(u32x4, w[(nt * 8 + ks) * 64]);
+            for (int ks = 0; ks < 16; ++ks) wb[nt - 4][ks] = __builtin_bit_cast(u32x4, w[(nt * 16 + ks) * 64]);
     }
     const int64_t n_rows = p.row_end - p.row_begin;
-    const int64_t n_tiles = (n_rows + TILE - 1) / TILE;
+    const int64_t n_tiles = (n_rows + PS_ROWS - 1) / PS_ROWS;
     const int64_t G = gridDim.x;
     int64_t t = blockIdx.x;
     if (t >= n_tiles) return;
 
-    // wave w fetches rows 4w .. 4w+3 of a tile, one 512-byte transfer each (lanes 0..31); rows
+    // wave w fetches rows 8w .. 8w+7 of a tile, one 512-byte transfer each (lanes 0..31); rows
     // past the end are clamped to the last one (their results are not stored)
     auto rows_of = [&](int64_t tile, int64_t* sr) __attribute__((always_inline)) {
+        int64_t r[8];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-            int64_t r = p.row_begin + tile * TILE + 4 * wave + q;
-            if (r >= p.row_end) r = p.row_end - 1;
-            sr[q] = gat ? (int64_t)gat[r] : r;
+        for (int q = 0; q < 8; ++q) {
+            r[q] = p.row_begin + tile * PS_ROWS + 8 * wave + q;
+            if (r[q] >= p.row_end) r[q] = p.row_end - 1;
+        }
+        if (gat) {                               // (one branch, so that the eight index loads go out together)
+#pragma unroll
+            for (int q = 0; q < 8; ++q) sr[q] = (int64_t)gat[r[q]];
+        } else {
+#pragma unroll
+            for (int q = 0; q < 8; ++q) sr[q] = r[q];
         }
     };
     auto fetch = [&](const int64_t* sr, int buf) __attribute__((always_inline)) {
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
+        for (int q = 0; q < 8; ++q)
             if (lane < 32)
                 dma16_row((const unsigned char*)p.src + sr[q] * (D * 2), (uint32_t)lane * 16u,
-                          lds0 + (uint32_t)(buf * TILE * PS_XSTRIDE * 2 + (4 * wave + q) * PS_XSTRIDE * 2));
+                          lds0 + (uint32_t)(buf * PS_ROWS * PS_XSTRIDE * 2 + (8 * wave + q) * PS_XSTRIDE * 2));
     };
     // this lane's three 16-byte pieces of a pair of output rows (3072 bytes = three 1 KB stores):
     // which row of the pair, where in the staged row, where in the caller's tensors
@@ -828,75 +865,105 @@ __global__ __launch_bounds__(256, 1) void proj768_kernel(dg4_bulk_args p)
     }
 
     {
-        int64_t sr[4];
+        int64_t sr[8];
         rows_of(t, sr);
         fetch(sr, 0);
+        if (t + G < n_tiles) { rows_of(t + G, sr); fetch(sr, 1); }
     }
-    int buf = 0;
-    bool first = true;
+    int buf = 0;                  // ring slot of this tile; the tile two rounds ahead goes into slot buf + 2
+    int round = 0;
     for (;;) {
 #pragma unroll
-        for (int nt = 0; nt < 8; ++nt)
+        for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) __asm__ volatile("" : "+a"(wa[nt][ks]));
-        const bool has_next = t + G < n_tiles;
-        const int64_t r0 = p.row_begin + t * TILE;
-        // Transfers and stores complete in issue order: this tile's rows were requested before
-        // the six stores of the previous tile, which need not be waited for.
-        if (first) __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
-        else __builtin_amdgcn_s_waitcnt(0x0F76);             // vmcnt(6)
+            for (int ks = 0; ks < 16; ++ks) __asm__ volatile("" : "+a"(wa[nt][ks]));
+        const bool has_next = t + G < n_tiles, has_next2 = t + 2 * G < n_tiles;
+        const int64_t r0 = p.row_begin + t * PS_ROWS;
+        int64_t next_rows[8];                   // (row numbers now, the transfers once the matrix cores are busy)
+        if (has_next2) rows_of(t + 2 * G, next_rows);
+        // Transfers and stores complete in issue order, so "this tile's rows have landed" is
+        // "at most as many operations outstanding as were issued after them": the eight
+        // transfers of the next tile (if there is one) and the twelve row stores of each of
+        // the last two rounds. Nothing younger has to be waited for.
+        if (round == 0) { if (has_next) __builtin_amdgcn_s_waitcnt(0x0F78); else __builtin_amdgcn_s_waitcnt(0x0F70); }        // 8 | 0
+        else if (round == 1) { if (has_next) __builtin_amdgcn_s_waitcnt(0x4F74); else __builtin_amdgcn_s_waitcnt(0x0F7C); }   // 20 | 12
+        else { if (has_next) __builtin_amdgcn_s_waitcnt(0x8F70); else __builtin_amdgcn_s_waitcnt(0x4F78); }                   // 32 | 24
         __asm__ volatile("" ::: "memory");
-        first = false;
         __syncthreads();          // every wave's rows have landed; the staging rows have been read
-        int64_t next_rows[4];                   // (row numbers now, the transfers once the matrix cores are busy)
-        if (has_next) rows_of(t + G, next_rows);
 
-        const uint16_t (*sX)[PS_XSTRIDE] = (const uint16_t (*)[PS_XSTRIDE])(smem + buf * TILE * PS_XSTRIDE * 2);
+        const uint16_t (*sX)[PS_XSTRIDE] = (const uint16_t (*)[PS_XSTRIDE])(smem + buf * PS_ROWS * PS_XSTRIDE * 2);
         uint16_t (*sO)[PS_OSTRIDE] = (uint16_t (*)[PS_OSTRIDE])(smem + PS_OUT);
-        uint4 b[8];                             // the tile as B operand, read once for all 12 column tiles
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) b[ks] = *(const uint4*)&sX[n][8 * g + ks * 32];
+        for (int cg = 0; cg < 3; ++cg) {        // two column tiles at a time
+            f32x16s acc[2];
+            // the tile as B operand, 16 k-steps, read through a window of four fragments: each
+            // is requested three steps before its two products (one wave per SIMD: nothing else
+            // hides the LDS latency)
+            uint4 bw[4];
 #pragma unroll
-        for (int cg = 0; cg < 3; ++cg) {
-            f32x4 acc[4];
+            for (int ks = 0; ks < 3; ++ks) bw[ks] = *(const uint4*)&sX[n][8 * hi + ks * 16];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) {
+            for (int ks = 0; ks < 16; ++ks) {
+                if (ks + 3 < 16) bw[(ks + 3) & 3] = *(const uint4*)&sX[n][8 * hi + (ks + 3) * 16];
+                const uint4 b = bw[ks & 3];
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int nt = cg * 4 + j;
-                    const uint4 a = nt < 8 ? __builtin_bit_cast(uint4, wa[nt < 8 ? nt : 0][ks]) : __builtin_bit_cast(uint4, wb[nt < 8 ? 0 : nt - 8][ks]);
-                    acc[j] = mfma16(a, b[ks], ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[j]);
+                for (int j = 0; j < 2; ++j) {
+                    const int nt = cg * 2 + j;
+                    const uint4 a = nt < 4 ? __builtin_bit_cast(uint4, wa[nt < 4 ? nt : 0][ks]) : __builtin_bit_cast(uint4, wb[nt < 4 ? 0 : nt - 4][ks]);
+                    if (ks == 0) {
+                        f32x16s z;
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) z[i] = 0.f;
+                        acc[j] = mfma32(a, b, z);
+                    } else {
+                        acc[j] = mfma32(a, b, acc[j]);
+                    }
                 }
+                __builtin_amdgcn_sched_barrier(0);
             }
-            if (cg == 0 && has_next) fetch(next_rows, buf ^ 1);
-            // lane (n, g) owns columns 192*wave + 48*g + 16*cg .. +15 of row n
-            uint4* dst = (uint4*)&sO[n][192 * wave + 48 * g + 16 * cg];
-            dst[0] = make_uint4(pack_bf16x2(acc[0][0], acc[0][1]), pack_bf16x2(acc[0][2], acc[0][3]),
-                                pack_bf16x2(acc[1][0], acc[1][1]), pack_bf16x2(acc[1][2], acc[1][3]));
-            dst[1] = make_uint4(pack_bf16x2(acc[2][0], acc[2][1]), pack_bf16x2(acc[2][2], acc[2][3]),
-                                pack_bf16x2(acc[3][0], acc[3][1]), pack_bf16x2(acc[3][2], acc[3][3]));
+            if (cg == 0 && has_next2) fetch(next_rows, buf >= 1 ? buf - 1 : 2);
+            // lane (n, hi) owns columns 192*wave + 96*hi + 32*cg .. +31 of row n
+            uint4* dst = (uint4*)&sO[n][192 * wave + 96 * hi + 32 * cg];
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const f32x16s c = acc[j];
+                dst[2 * j] = make_uint4(pack_bf16x2(c[0], c[1]), pack_bf16x2(c[2], c[3]), pack_bf16x2(c[4], c[5]), pack_bf16x2(c[6], c[7]));
+                dst[2 * j + 1] = make_uint4(pack_bf16x2(c[8], c[9]), pack_bf16x2(c[10], c[11]), pack_bf16x2(c[12], c[13]), pack_bf16x2(c[14], c[15]));
+            }
         }
         __syncthreads();          // staged rows complete
-        // wave w stores rows 4w .. 4w+3, two at a time
+        // wave w stores rows 8w .. 8w+7, two at a time
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int pr = 0; pr < 2; ++pr)
+        for (int half = 0; half < 2; ++half) {
+            uint4 piece[6];
 #pragma unroll
-            for (int i = 0; i < 3; ++i) {
-                const int row = 4 * wave + 2 * pr + st_row[i];
-                const uint4 v = *(const uint4*)(smem + st_lds[i] + (4 * wave + 2 * pr) * PS_OSTRIDE * 2);
-#ifdef PS_NOSTORE
-                if (v.x == 0x12345u && r0 + row < p.row_end) *(uint4*)(st_ptr[i] + (r0 + row) * p.out_stride * 2) = v;
-#else
-                if (r0 + row < p.row_end) *(uint4*)(st_ptr[i] + (r0 + row) * p.out_stride * 2) = v;
-#endif
-            }
+            for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+                for (int i = 0; i < 3; ++i)
+                    piece[3 * pr + i] = *(const uint4*)(smem + st_lds[i] + (8 * wave + 4 * half + 2 * pr) * PS_OSTRIDE * 2);
+#pragma unroll
+            for (int pr = 0; pr < 2; ++pr)
+#pragma unroll
+                for (int i = 0; i < 3; ++i) {
+                    const int row = 8 * wave + 4 * half + 2 * pr + st_row[i];
+                    if (r0 + row < p.row_end) *(uint4*)(st_ptr[i] + (r0 + row) * p.out_stride * 2) = piece[3 * pr + i];
+                }
+        }
         if (!has_next) return;
         t += G;
-        buf ^= 1;
+        buf = buf == 2 ? 0 : buf + 1;
+        ++round;
     }
 }
 
 }  // namespace
+
+int dg4_launch_pack_w32(const void* w, int ld, void* packed, hipStream_t s)
+{
+    hipLaunchKernelGGL(pack_w32_kernel, dim3(4 * PS_NT * 16 * 64 / 256), dim3(256), 0, s, (const uint16_t*)w, ld, (uint16_t*)packed);
+    return hipGetLastError();
+}
 
 int dg4_launch_bulk_proj(const dg4_bulk_args& a, hipStream_t s)
 {
@@ -906,7 +973,9 @@ int dg4_launch_bulk_proj(const dg4_bulk_args& a, hipStream_t s)
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
-    const int64_t tiles = (rows + TILE - 1) / TILE;
+    const int64_t tiles = (rows + PS_ROWS - 1) / PS_ROWS;
+    hipError_t e = hipFuncSetAttribute((const void*)proj768_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, PS_BYTES);
+    if (e != hipSuccess) return e;
     hipLaunchKernelGGL(proj768_kernel, dim3((unsigned)std::min<int64_t>(cus, tiles)), dim3(256), PS_BYTES, s, a);
     return hipGetLastError();
 }
