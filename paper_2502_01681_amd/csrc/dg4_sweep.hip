@@ -487,28 +487,35 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             auto k_of = [&](int j) __attribute__((always_inline)) {                             // V sits 512 bytes after K
                 return (const uint4*)(land + (((where >> (4 * j)) & 7u) << 10));
             };
-#pragma unroll
-            for (int h = 0; h < 4; ++h) {
-                uint4 k0[2], k1[2];
-                float bias[2];
+            // (the rows of pair h+1 are requested before pair h is used: with one wave per SIMD
+            // nothing else hides the LDS latency)
+            uint4 kr[2][4];                               // [buffer][entry of the pair: two 16-byte halves each]
+            float br[2][2];
+            auto load_k = [&](int h, int bufi) __attribute__((always_inline)) {
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
                     const uint4* kp = k_of(2 * h + j);
-                    k0[j] = kp[0]; k1[j] = kp[1];
-                    bias[j] = sBias[(what >> (4 * (2 * h + j))) & 3u];          // padding reads entry 3 of the table, unused
+                    kr[bufi][2 * j] = kp[0]; kr[bufi][2 * j + 1] = kp[1];
+                    br[bufi][j] = sBias[(what >> (4 * (2 * h + j))) & 3u];          // padding reads entry 3 of the table, unused
                 }
+            };
+            load_k(0, 0);
+#pragma unroll
+            for (int h = 0; h < 4; ++h) {
+                if (h + 1 < 4) load_k(h + 1, (h + 1) & 1);
 #pragma unroll
                 for (int j = 0; j < 2; ++j) {
+                    const uint4 k0 = kr[h & 1][2 * j], k1 = kr[h & 1][2 * j + 1];
                     float d0 = 0.f, d1 = 0.f;                     // two chains: the dot products issue back to back
-                    d0 = dot2_bf16(q[0], k0[j].x, d0); d1 = dot2_bf16(q[1], k0[j].y, d1);
-                    d0 = dot2_bf16(q[2], k0[j].z, d0); d1 = dot2_bf16(q[3], k0[j].w, d1);
-                    d0 = dot2_bf16(q[4], k1[j].x, d0); d1 = dot2_bf16(q[5], k1[j].y, d1);
-                    d0 = dot2_bf16(q[6], k1[j].z, d0); d1 = dot2_bf16(q[7], k1[j].w, d1);
+                    d0 = dot2_bf16(q[0], k0.x, d0); d1 = dot2_bf16(q[1], k0.y, d1);
+                    d0 = dot2_bf16(q[2], k0.z, d0); d1 = dot2_bf16(q[3], k0.w, d1);
+                    d0 = dot2_bf16(q[4], k1.x, d0); d1 = dot2_bf16(q[5], k1.y, d1);
+                    d0 = dot2_bf16(q[6], k1.z, d0); d1 = dot2_bf16(q[7], k1.w, d1);
                     const float d = Elem<bf16_t>::head_sum(d0 + d1);
-                    const float t = fmaf(d, scale, bias[j]);
+                    const float t = fmaf(d, scale, br[h & 1][j]);
                     sc[2 * h + j] = (what >> (4 * (2 * h + j)) & 4u) ? t : -INFINITY;   // padding: weight 2^-inf = 0
                 }
-                __builtin_amdgcn_sched_barrier(0);            // one pair's rows in registers at a time: the register file is full
+                __builtin_amdgcn_sched_barrier(0);            // no further hoisting: the register file is full
             }
             // the first look has had the first pass to come back (so has the descriptor fetch)
             uint32_t src_lo = 0, src_hi = 0;              // lane 8*gate + slot: row address of that source of the next tile
@@ -546,25 +553,28 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             // gate is done with its slots 0 .. 2r (a row holds at most one entry that is no
             // source), so the next tile's sources for those slots can start to travel.
             float acc[16];
+            uint4 vr[2][4];
+            auto load_v = [&](int r, int bufi) __attribute__((always_inline)) {
+#pragma unroll
+                for (int j = 0; j < 2; ++j) {
+                    const uint4* vp = k_of(2 * r + j) + 32;
+                    vr[bufi][2 * j] = vp[0]; vr[bufi][2 * j + 1] = vp[1];
+                }
+            };
+            load_v(0, 0);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const uint4* va = k_of(2 * r) + 32;
-                const uint4* vb = k_of(2 * r + 1) + 32;
-                const uint4 a0 = va[0], a1 = va[1], b0 = vb[0], b1 = vb[1];
-                {
-                    float f[16];
-                    Elem<bf16_t>::unpack(a0, a1, f);
+                if (r + 1 < 4) load_v(r + 1, (r + 1) & 1);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[i] = r == 0 ? sc[0] * f[i] : fmaf(sc[2 * r], f[i], acc[i]);
-                }
-                __builtin_amdgcn_sched_barrier(0);
-                {
+                for (int j = 0; j < 2; ++j) {
                     float f[16];
-                    Elem<bf16_t>::unpack(b0, b1, f);
+                    Elem<bf16_t>::unpack(vr[r & 1][2 * j], vr[r & 1][2 * j + 1], f);
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[i] = fmaf(sc[2 * r + 1], f[i], acc[i]);
+                    for (int i = 0; i < 16; ++i) acc[i] = (r == 0 && j == 0) ? sc[0] * f[i] : fmaf(sc[2 * r + j], f[i], acc[i]);
+                    __builtin_amdgcn_sched_barrier(0);
                 }
-                // this pair's rows are in registers: their slots may be overwritten
+                // this pair's rows are in registers (so are the next pair's, which sit in higher
+                // slots): its slots may be overwritten
                 __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
                 if (has_next && DG4_ISSUE_MODE == 0) {
                     if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
