@@ -23,7 +23,7 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0
 # HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE,
 # calibrated against a plain copy (see profiles/); None until measured for a workload.
-TRAFFIC_BYTES = {"large": 9.94e9}     # sweep_kernel: 8.39 GB fetched + 1.55 GB written (profiles/large_sweep_rocprofv3.txt)
+TRAFFIC_BYTES = {"large": 8.60e9}     # sweep_kernel: 7.05 GB fetched + 1.55 GB written (profiles/large_sweep_rocprofv3.txt)
 
 
 def algorithmic_bytes(g, cfg, levels=None):
@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--workload", default="large", help="large (default) | medium | small | tiny | stress")
     ap.add_argument("--n-and", type=int, default=None, help="override the number of AND gates (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-level-order", action="store_true",
+                    help="skip the extra run with level-ordered tiles (for profiles of the default path only)")
     ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
@@ -162,7 +164,7 @@ def main():
 
     # For information: the same step with the tiles dealt strictly level by level (the order of the
     # level hint) instead of the library's default dependency-driven order. Same results, bit for bit.
-    if len(sweep_ms) == args.steps:
+    if len(sweep_ms) == args.steps and not args.no_level_order:
         os.environ["DG4_SWEEP_LEVEL_ORDER"] = "1"
         for _ in range(args.warmup):
             dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
