@@ -48,6 +48,12 @@ typedef enum {
 #define DG4_NO_EPILOGUE 1u  /* H = A*Wo without residual and LayerNorm (kernel tests)      */
 #define DG4_PER_LEVEL   2u  /* dg4_layer_fwd: launch level by level instead of the single  */
                             /* persistent dataflow kernel (same results; for comparison)   */
+#define DG4_BOUNDED_KV  4u  /* dg4_layer_fwd: keep no K|V store of finished gates. The K|V  */
+                            /* rows of a level's distinct sources are projected from Hout   */
+                            /* when the level is processed, so the workspace holds one      */
+                            /* level's frontier only (Section 3.4: memory that does not     */
+                            /* grow with the graph). Level-by-level launches; same results  */
+                            /* bit for bit; the projection work is repeated per reader level */
 
 typedef struct {
     int32_t hidden;         /* d: 128 or 256                                               */

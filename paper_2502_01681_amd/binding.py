@@ -16,6 +16,7 @@ _I32 = ctypes.c_int32
 DG4_F32, DG4_BF16 = 0, 1
 DG4_NO_EPILOGUE = 1
 DG4_PER_LEVEL = 2
+DG4_BOUNDED_KV = 4
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
           "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8),
           "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64)}
@@ -45,11 +46,13 @@ class LayerConfig:
     epilogue: bool = True
     ln_eps: float = 1e-5
     per_level: bool = False      # launch level by level instead of the persistent sweep kernel
+    bounded_kv: bool = False     # no K|V store: one level's frontier is projected when the level is processed
 
     def c(self) -> _Cfg:
         return _Cfg(self.hidden, self.heads, self.hops, self.n_layers,
                     DG4_F32 if self.dtype == "f32" else DG4_BF16,
-                    (0 if self.epilogue else DG4_NO_EPILOGUE) | (DG4_PER_LEVEL if self.per_level else 0), self.ln_eps)
+                    (0 if self.epilogue else DG4_NO_EPILOGUE) | (DG4_PER_LEVEL if self.per_level else 0) |
+                    (DG4_BOUNDED_KV if self.bounded_kv else 0), self.ln_eps)
 
 
 _lib = None

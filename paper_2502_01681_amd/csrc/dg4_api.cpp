@@ -16,7 +16,7 @@ int check_cfg(const dg4_layer_cfg* c, bool need_layers)
 {
     if (!c) return DG4_EINVAL;
     if (c->dtype != DG4_F32 && c->dtype != DG4_BF16) return DG4_EINVAL;
-    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL)) return DG4_EINVAL;
+    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL | DG4_BOUNDED_KV)) return DG4_EINVAL;
     if (c->hidden != 128 && c->hidden != 256) return DG4_EUNSUPPORTED;
     if (c->heads <= 0 || c->heads * 32 != c->hidden) return DG4_EUNSUPPORTED;
     if (c->hops < 1 || c->hops > 3) return DG4_EUNSUPPORTED;
@@ -30,7 +30,8 @@ struct LayerPlan {
     size_t wqkv[DG4_MAX_LAYERS], wo[DG4_MAX_LAYERS];
     size_t wkv_all;      // packed [d, n_layers*2d]: K|V columns of every layer
     size_t qkv_self;     // [n, 3d]  Q | K | V of x, level-sorted rows (layer 0)
-    size_t kv;           // [n_layers, n, 2d]  K | V of the final embeddings, level-sorted
+    size_t kv;           // [n_layers, kv_rows, 2d]  K | V of the final embeddings, level-sorted
+    size_t kv_rows;
     size_t hpos;         // [n, d]   final embeddings, level-sorted
     size_t abuf;         // [max_level_rows, d]
     size_t s0, s1;       // [max_level_rows, d] running state between layers
@@ -54,13 +55,16 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
     for (size_t l = 0; l < L; ++l) { p.wqkv[l] = take(d * 3 * d * es); p.wo[l] = take(d * d * es); }
     p.wkv_all = take(d * 2 * d * L * es);
-    p.qkv_self = take(n * 3 * d * es);
-    p.kv = take(L * n * 2 * d * es);
-    p.hpos = take(n * d * es);
+    p.qkv_self = take((c->flags & DG4_BOUNDED_KV) ? 0 : n * 3 * d * es);
+    // K | V rows: of every finished gate, or (DG4_BOUNDED_KV) of one level's frontier only
+    const bool bounded = (c->flags & DG4_BOUNDED_KV) != 0;
+    p.kv_rows = bounded ? (size_t)std::max<int64_t>(g->front_max, 1) : n;
+    p.kv = take(L * p.kv_rows * 2 * d * es);
+    p.hpos = take(bounded ? 0 : n * d * es);
     p.abuf = take((size_t)mr * d * es);
     p.s0 = take((size_t)mr * d * es);
     p.s1 = take((size_t)mr * d * es);
-    p.qkv_level = take(L > 1 ? (size_t)mr * 3 * d * es : 0);
+    p.qkv_level = take(L > 1 || bounded ? (size_t)mr * 3 * d * es : 0);
     p.wo_t = take(d * d * es);
     p.wkv_t = take(d * 2 * d * es);
     p.flags = take(n * sizeof(uint32_t));
@@ -114,6 +118,12 @@ extern "C" int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4
     if (rc != DG4_OK) return rc;
     if (!g) return DG4_EINVAL;
     if (g->hops != cfg->hops) return DG4_EINVAL;
+    if (cfg->flags & DG4_BOUNDED_KV) {       // the size depends on the largest frontier: tables first
+        dg4_graph* m = const_cast<dg4_graph*>(g);
+        int rc2 = dg4_graph_ensure_device(m);
+        if (rc2 == DG4_OK) rc2 = dg4_graph_ensure_frontier(m);
+        if (rc2 != DG4_OK) return rc2;
+    }
     return (int64_t)plan_layer(cfg, g).total;
 }
 
@@ -184,6 +194,12 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     if (level_begin < 0 || level_end < level_begin || level_end > n_levels) return DG4_EINVAL;
     const int L = cfg->n_layers;
     for (int i = 0; i < 3 * L; ++i) if (!W[i]) return DG4_EINVAL;
+    const bool bounded = (cfg->flags & DG4_BOUNDED_KV) != 0;
+    if (bounded) {
+        rc = dg4_graph_ensure_device(g);
+        if (rc == DG4_OK) rc = dg4_graph_ensure_frontier(g);
+        if (rc != DG4_OK) return rc;
+    }
     const LayerPlan pl = plan_layer(cfg, g);
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < (int64_t)pl.total) return DG4_EWORKSPACE;
     if (g->n == 0 || level_begin == level_end) return DG4_OK;
@@ -212,7 +228,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.a = rows; a.a_stride = stride; a.a_gather = gather;
         a.w_packed = at(pl.wkv_all); a.n_cols = 2 * d * L;
         for (int l = 0; l < L; ++l) {
-            char* base = ws + pl.kv + (size_t)l * (size_t)g->n * 2 * d * es;
+            char* base = ws + pl.kv + (size_t)l * pl.kv_rows * 2 * d * es;
             a.out[2 * l] = base; a.out[2 * l + 1] = base + (size_t)d * es;
         }
         a.out_stride = 2 * d;
@@ -221,10 +237,10 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     };
 
     // K/V of gates finished before this call (resume): from the caller's H
-    if (P0 > 0) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
+    if (P0 > 0 && !bounded) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
     // One persistent dataflow kernel for the whole range of levels
-    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & DG4_PER_LEVEL)) {
+    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV))) {
         // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
         // level by level; rows of the internal buffers are positions in the order in use.
         const bool whole = level_begin == 0 && level_end == (int32_t)g->max_level + 1 && !getenv("DG4_SWEEP_LEVEL_ORDER");
@@ -268,8 +284,9 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         return DG4_OK;
     }
 
-    // layer 0 projections of x for every gate of the swept levels, in one pass
-    {
+    // layer 0 projections of x for every gate of the swept levels, in one pass (level by level
+    // further down if nothing of the size of the graph may be kept)
+    if (!bounded) {
         dg4_gemm_args a{};
         a.a = X; a.a_stride = d; a.a_gather = g->d_order;
         a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
@@ -283,10 +300,25 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     for (int32_t lev = level_begin; lev < level_end; ++lev) {
         const int64_t p0 = g->level_ptr[lev], p1 = g->level_ptr[lev + 1];
         if (p1 == p0) continue;
+        if (bounded) {
+            // K | V (every layer) of this level's distinct sources, from their final embeddings
+            const int64_t f0 = g->front_ptr[lev], f1 = g->front_ptr[lev + 1];
+            if (f1 > f0) HIPCHK(kv_project(Hout, d, g->d_front_id + f0, 0, f1 - f0));
+        }
+        if (bounded) {
+            dg4_gemm_args a{};
+            a.a = X; a.a_stride = d; a.a_gather = g->d_order;
+            a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
+            char* base = (char*)local(pl.qkv_level, p0, 3 * d);
+            a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
+            a.out_stride = 3 * d;
+            a.row_begin = p0; a.row_end = p1;
+            HIPCHK(dg4_launch_gemm(dt, d, a, s));
+        }
         for (int l = 0; l < L; ++l) {
             const bool last = l == L - 1;
             dg4_attn_args t{};
-            if (l == 0) {
+            if (l == 0 && !bounded) {
                 char* base = ws + pl.qkv_self;
                 t.q = base; t.k_self = base + (size_t)d * es; t.v_self = base + (size_t)2 * d * es;
             } else {
@@ -294,10 +326,10 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
                 t.q = base; t.k_self = base + (size_t)d * es; t.v_self = base + (size_t)2 * d * es;
             }
             t.q_stride = 3 * d; t.self_stride = 3 * d;
-            char* kvb = ws + pl.kv + (size_t)l * (size_t)g->n * 2 * d * es;
+            char* kvb = ws + pl.kv + (size_t)l * pl.kv_rows * 2 * d * es;
             t.k_src = kvb; t.v_src = kvb + (size_t)d * es; t.src_stride = 2 * d;
             t.rel_bias = (const float*)W[3 * l + 2];
-            t.ell = g->d_ell_pos; t.ell_w = g->ell_w;
+            t.ell = bounded ? g->d_ell_front : g->d_ell_pos; t.ell_w = g->ell_w;
             t.a = local(pl.abuf, p0, d); t.a_stride = d;
             t.row_begin = p0; t.row_end = p1;
             HIPCHK(dg4_launch_attn(dt, d, t, s));
@@ -312,7 +344,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             else { o.resid = local((l & 1) ? pl.s1 : pl.s0, p0, d); o.resid_stride = d; }
             if (last) {
                 o.out[0] = Hout; o.out_stride = d; o.out_scatter = g->d_order;
-                o.out2 = at(pl.hpos); o.out2_stride = d;
+                if (!bounded) { o.out2 = at(pl.hpos); o.out2_stride = d; }
             } else {
                 o.out[0] = local(((l + 1) & 1) ? pl.s1 : pl.s0, p0, d); o.out_stride = d;
             }
@@ -330,7 +362,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             }
         }
         // publish K/V of the level's final embeddings for every layer
-        if (lev + 1 < n_levels) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
+        if (lev + 1 < n_levels && !bounded) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
     }
     return DG4_OK;
 }

@@ -354,6 +354,7 @@ int dg4_graph_ensure_device(dg4_graph* g)
                 for (int64_t q = lo; q < hi; ++q) g->pos[sweep[q]] = (int32_t)q;   // sources of higher levels see these
             }
         }
+        g->sweep_order.assign(sweep.begin(), sweep.begin() + g->n);
         std::vector<uint32_t> by_id(rows * w, DG4_ELL_PAD), by_pos(rows * w, DG4_ELL_PAD);
         for (int64_t v = 0; v < g->n; ++v) {
             const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
@@ -413,6 +414,8 @@ int dg4_graph_ensure_device(dg4_graph* g)
     if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
     if (g->d_flow_order) (void)hipFree(g->d_flow_order);
     if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
+    if (g->d_front_id) (void)hipFree(g->d_front_id);
+    if (g->d_ell_front) (void)hipFree(g->d_ell_front);
             g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr;
             return rc;
         };
@@ -440,6 +443,67 @@ int dg4_graph_ensure_device(dg4_graph* g)
         return DG4_ENOMEM;
     }
     g->ell_w = w; g->device = dev; g->on_device = true;
+    return DG4_OK;
+}
+
+// Tables for sweeps that keep no K|V store: the frontier of a level is the set of distinct sources
+// of its gates (Section 3.4: what has to be pulled from the historical embeddings for one level).
+int dg4_graph_ensure_frontier(dg4_graph* g)
+{
+    std::lock_guard<std::mutex> lock(g->mu);
+    if (g->has_frontier) return DG4_OK;
+    if (!g->on_device) return DG4_EINVAL;
+    const int w = g->ell_w;
+    const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
+    try {
+        const int32_t n_levels = g->max_level + 1;
+        std::vector<int64_t> ptr((size_t)n_levels + 1, 0);
+        std::vector<int32_t> ids;
+        std::vector<uint32_t> ell(rows * w, DG4_ELL_PAD);
+        std::vector<int32_t> local((size_t)g->n, -1), seen;
+        int64_t largest = 0;
+        for (int32_t l = 0; l < n_levels; ++l) {
+            seen.clear();
+            for (int64_t q = g->level_ptr[l]; q < g->level_ptr[l + 1]; ++q) {
+                const int32_t v = g->sweep_order[(size_t)q];
+                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j) {
+                    const int32_t u = g->nbr_idx[j];
+                    if (u != v && local[u] < 0) { local[u] = 0; seen.push_back(g->pos[u]); }
+                }
+            }
+            std::sort(seen.begin(), seen.end());                    // positions: sources of a level sit close together
+            // (sweep order position -> node id through the level-ordered table the device uses)
+            for (size_t i = 0; i < seen.size(); ++i) local[g->sweep_order[(size_t)seen[i]]] = (int32_t)i;
+            for (int64_t q = g->level_ptr[l]; q < g->level_ptr[l + 1]; ++q) {
+                const int32_t v = g->sweep_order[(size_t)q];
+                uint32_t* r = &ell[(size_t)q * w];
+                const int64_t lo = g->nbr_ptr[v];
+                for (int64_t j = lo; j < g->nbr_ptr[v + 1]; ++j) {
+                    const int32_t u = g->nbr_idx[j];
+                    r[j - lo] = ((uint32_t)g->nbr_rel[j] << 30) | (uint32_t)(u == v ? 0 : local[u]);
+                }
+            }
+            for (int32_t pos : seen) { const int32_t u = g->sweep_order[(size_t)pos]; ids.push_back(u); local[u] = -1; }
+            ptr[(size_t)l + 1] = (int64_t)ids.size();
+            largest = std::max<int64_t>(largest, (int64_t)seen.size());
+        }
+        if (hipMalloc((void**)&g->d_front_id, std::max<size_t>(ids.size(), 1) * sizeof(int32_t)) != hipSuccess) return DG4_ENOMEM;
+        if (hipMalloc((void**)&g->d_ell_front, rows * w * sizeof(uint32_t)) != hipSuccess) {
+            (void)hipFree(g->d_front_id); g->d_front_id = nullptr;
+            return DG4_ENOMEM;
+        }
+        if ((!ids.empty() && hipMemcpy(g->d_front_id, ids.data(), ids.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) ||
+            hipMemcpy(g->d_ell_front, ell.data(), rows * w * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(g->d_front_id); (void)hipFree(g->d_ell_front);
+            g->d_front_id = nullptr; g->d_ell_front = nullptr;
+            return DG4_EHIP;
+        }
+        g->front_ptr.swap(ptr);
+        g->front_max = largest;
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
+    g->has_frontier = true;
     return DG4_OK;
 }
 

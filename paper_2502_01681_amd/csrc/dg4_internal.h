@@ -22,7 +22,8 @@ struct dg4_graph {
     int64_t n = 0, e = 0, nnz = 0;
     int32_t hops = 0, max_level = 0;
     std::vector<int32_t> level, order;           // order: ids by (level, id)
-    std::vector<int32_t> pos;                    // pos[id] = position in the device processing order (set at upload)
+    std::vector<int32_t> pos;                    // pos[id] = position in the level-ordered device processing order (set at upload)
+    std::vector<int32_t> sweep_order;            // its inverse: position -> id
     std::vector<int64_t> level_ptr, nbr_ptr;
     std::vector<int32_t> nbr_idx;
     std::vector<uint8_t> nbr_rel;
@@ -42,6 +43,14 @@ struct dg4_graph {
     // the real dependencies (a gate goes as early as its sources allow, sources long finished
     // first), not level by level. Host copy (node ids in processing order, first position of
     // each tile), then device tables with the layout of the three above.
+    // Frontier tables for sweeps without a K|V store (DG4_BOUNDED_KV), built on first use: per level
+    // the distinct sources of its gates (node ids, ascending position), and neighbour rows whose
+    // entries index that list.
+    bool has_frontier = false;
+    std::vector<int64_t> front_ptr;      // [n_levels + 1]
+    int64_t front_max = 0;               // largest frontier of a level
+    int32_t* d_front_id = nullptr;       // [front_ptr.back()] node ids
+    uint32_t* d_ell_front = nullptr;     // [n, ell_w] by position, entries rel << 30 | index in the level's frontier
     std::vector<int32_t> flow_order;
     std::vector<int64_t> flow_tile_ptr;
     int64_t flow_slack = -1;
@@ -53,6 +62,7 @@ struct dg4_graph {
 
 int dg4_graph_ensure_device(dg4_graph* g);
 int dg4_flow_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
+int dg4_graph_ensure_frontier(dg4_graph* g);           // after dg4_graph_ensure_device
 
 // ---- kernel launchers (dg4_kernels.hip). All return a hipError_t as int. ----
 

@@ -57,6 +57,34 @@ def test_full_size_sampled(name, samples):
     assert torch.equal(H, H2)
 
 
+def test_stress_full_size_with_bounded_kv():
+    # the stress configuration as it is defined: 4 layers, 3-hop cones, and no K|V store, only one
+    # level's frontier (the store of the default path would be 16 GB for this graph)
+    print("full size stress, bounded K|V: generating", flush=True)
+    w = synth.make("stress")
+    c = w.cfg
+    cfg = cfg_of(c, bounded_kv=True)
+    g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    X, W = to_dev(w.x, c.dtype), device_weights(w, c.dtype)
+    H = torch.full((c.n_nodes, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+    need = dg4.dg4_layer_workspace_bytes(cfg, g)
+    full = dg4.dg4_layer_workspace_bytes(cfg_of(c), g)
+    print(f"  workspace {need / 1e9:.2f} GB bounded, {full / 1e9:.2f} GB with the store", flush=True)
+    assert need < 1e9 < full
+    dg4.dg4_layer_fwd(cfg, g, X, W, H)
+    torch.cuda.synchronize()
+    print("  sweep done", flush=True)
+    Hn = to_np(H)
+    assert not np.isnan(Hn).any()
+    og = oracle.build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    nodes = np.unique(np.concatenate([np.random.default_rng(3).choice(c.n_nodes, size=1200, replace=False),
+                                      og.order[-100:]]))
+    ref = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, Hn, nodes, store=c.dtype)
+    err = row_rel_err(Hn[nodes], ref)
+    print(f"  sampled {len(nodes)} gates: max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype]
+
+
 def test_bounded_wait_aborts_instead_of_hanging(monkeypatch):
     # A spin limit of zero makes the kernel give up on the first unpublished source: it must
     # return (abort flag set or not, depending on timing) and a normal run afterwards is correct.

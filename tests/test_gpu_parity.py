@@ -136,6 +136,49 @@ def test_layer_fwd_schedule_split_and_determinism():
     assert torch.equal(H2, Hh)                          # resumed sweep = whole sweep
 
 
+def test_dataflow_and_level_ordered_tiles_agree(monkeypatch):
+    # a whole-graph sweep runs in the dependency-driven tile order; the same sweep with the tiles
+    # dealt level by level must not change a bit (nor does the per-level launch path change more
+    # than rounding)
+    print("layer_fwd dataflow order vs level order", flush=True)
+    w = synth.make("large", n_and=60_000)
+    cfg = cfg_of(w.cfg)
+    g, _ = graphs(w, hint=True)
+    H_flow = run_layer(w, cfg, g)
+    monkeypatch.setenv("DG4_SWEEP_LEVEL_ORDER", "1")
+    H_level = run_layer(w, cfg, g)
+    monkeypatch.delenv("DG4_SWEEP_LEVEL_ORDER")
+    assert torch.equal(H_flow, H_level)
+    assert not torch.isnan(H_flow.float()).any()
+
+
+@pytest.mark.parametrize("name,n_and,kw", [("stress", 30_000, {}), ("large", 30_000, {}),
+                                           ("tiny", None, dict(n_layers=2)), ("small", None, {})])
+def test_bounded_kv_sweep(name, n_and, kw):
+    # no K|V store: the K|V rows of a level's frontier are projected when the level is processed.
+    # Same bits as the sweep with the store, a much smaller workspace, and a resumed sweep works.
+    print(f"layer_fwd bounded K|V {name} {kw}", flush=True)
+    base = synth.CONFIGS[name]
+    c = synth.Config(**{**base.__dict__, **kw, **({"n_and": n_and} if n_and else {})})
+    w = synth.make(c)
+    g, og = graphs(w)
+    cfg_store = cfg_of(c, per_level=True)
+    cfg_bound = cfg_of(c, bounded_kv=True)
+    H_store = run_layer(w, cfg_store, g)
+    H_bound = run_layer(w, cfg_bound, g)
+    assert not torch.isnan(H_bound.float()).any()
+    assert torch.equal(H_store, H_bound)
+    ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
+    assert row_rel_err(to_np(H_bound), ref).max() <= TOL[c.dtype]
+    big, small = dg4.dg4_layer_workspace_bytes(cfg_store, g), dg4.dg4_layer_workspace_bytes(cfg_bound, g)
+    print(f"  workspace {big / 1e6:.1f} MB with the store, {small / 1e6:.1f} MB bounded", flush=True)
+    assert small < big
+    mid = g.n_levels // 2
+    H1 = run_layer(w, cfg_bound, g, 0, mid)
+    H2 = run_layer(w, cfg_bound, g, mid, None, H0=H1)
+    assert torch.equal(H2, H_bound)
+
+
 def test_workspace_reuse_with_new_inputs():
     # the same workspace and output buffer, different features: nothing stale may be read
     print("layer_fwd workspace reuse", flush=True)
