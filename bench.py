@@ -64,6 +64,8 @@ def main():
     ap.add_argument("--workload", default="large", help="large (default) | medium | small | tiny | stress")
     ap.add_argument("--n-and", type=int, default=None, help="override the number of AND gates (debug)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-points", action="store_true",
+                    help="skip the stand-alone timings of dg4_qkv_proj and dg4_sparse_attn_fwd over all rows")
     ap.add_argument("--no-level-order", action="store_true",
                     help="skip the extra run with level-ordered tiles (for profiles of the default path only)")
     ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
@@ -183,6 +185,40 @@ def main():
         out["level_order_tiles"] = {"step_ms_device": float(np.mean(lo_ms)), "kernel_ms": k,
                                     "roofline_frac": compulsory / (k * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                     "edges_per_s": nnz * layers / (float(np.mean(lo_ms)) * 1e-3)}
+
+    # The two non-recurrent calls over all rows at once, as pure-kernel roofline points
+    # (bf16 MFMA peak 2.5 PFLOP/s dense; both are HBM-bound at this size).
+    if not args.no_kernel_points:
+        def timed(fn, reps=5):
+            for _ in range(2):
+                fn()
+            torch.cuda.synchronize()
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            for _ in range(reps):
+                fn()
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        es = 4 if c.dtype == "f32" else 2
+        R = c.hidden * es
+        Q, K, V, A = (torch.empty_like(X) for _ in range(4))
+        pws = torch.empty(dg4.dg4_proj_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+        ms_p = timed(lambda: dg4.dg4_qkv_proj(cfg, X, W[0][0], Q, K, V, workspace=pws))
+        flop_p = 2.0 * n_gates * c.hidden * 3 * c.hidden
+        ms_a = timed(lambda: dg4.dg4_sparse_attn_fwd(cfg, g, Q, K, V, W[0][2], A))
+        bytes_a = n_gates * 2 * R + (nnz - n_gates) * 2 * R + n_gates * 4 * (1 << (c.hops + 1))
+        peak_flops = 2.5e15 if c.dtype == "bf16" else 157.3e12
+        out["kernel_points"] = {
+            "dg4_qkv_proj": {"ms": ms_p, "GB/s": n_gates * 4 * R / (ms_p * 1e-3) / 1e9,
+                             "TFLOP/s": flop_p / (ms_p * 1e-3) / 1e12,
+                             "mfma_frac": flop_p / (ms_p * 1e-3) / peak_flops, "hbm_frac": n_gates * 4 * R / (ms_p * 1e-3) / 1e9 / HBM_PEAK_GBPS},
+            # compulsory: every Q, K, V row read once, every A row written once, the neighbour rows
+            "dg4_sparse_attn_fwd": {"ms": ms_a, "GB/s_gathered": bytes_a / (ms_a * 1e-3) / 1e9,
+                                    "GB/s_compulsory": n_gates * (4 * R + 4 * (1 << (c.hops + 1))) / (ms_a * 1e-3) / 1e9,
+                                    "hbm_frac_compulsory": n_gates * (4 * R + 4 * (1 << (c.hops + 1))) / (ms_a * 1e-3) / 1e9 / HBM_PEAK_GBPS,
+                                    "edges_per_s": nnz / (ms_a * 1e-3)}}
+        del Q, K, V, A
 
     if not args.no_cpu_baseline:
         import oracle
