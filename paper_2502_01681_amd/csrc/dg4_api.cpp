@@ -38,7 +38,7 @@ struct LayerPlan {
     size_t qkv_level;    // [max_level_rows, 3d] (layers >= 1)
     size_t wo_t, wkv_t;  // persistent sweep: weights in its A-operand order (layer 0)
     size_t flags;        // [n] uint32 "rows published"
-    size_t ctrl;         // ticket counter, abort flag
+    size_t ctrl;         // abort flag, phase timers
     size_t total;
     int64_t max_rows;
 };

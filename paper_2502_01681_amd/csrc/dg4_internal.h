@@ -100,7 +100,7 @@ int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s
 
 // ---- persistent sweep (dg4_sweep.hip): bf16, hidden 256, one layer ----
 struct dg4_sweep_args {
-    const uint2* tiles; int64_t tile_begin; int64_t n_tiles;   // tickets 0..n_tiles-1 map to tiles[tile_begin + t]
+    const uint2* tiles; int64_t tile_begin; int64_t n_tiles;   // tile t of the sweep is tiles[tile_begin + t]
     const uint32_t* ell; int ell_w;        // neighbour rows by position
     const int32_t* order;                  // position -> node id
     const uint16_t* x;                     // [n, 256] by node id
@@ -110,7 +110,7 @@ struct dg4_sweep_args {
     const void* wo_packed; const void* wkv_packed;   // pack_wt order
     const float* rel_bias;
     uint32_t* flags;                       // [n] by position: 1 = rows published
-    uint32_t* ctrl;                        // [0] ticket counter, [1] abort flag
+    uint32_t* ctrl;                        // [1] abort flag, [16..31] phase timers
     uint64_t* prof;                        // nullable: 8 phase timers (100 MHz ticks, summed over workgroups)
     float ln_eps; int epilogue; int publish_kv;
     uint32_t spin_limit;

@@ -43,7 +43,7 @@ constexpr int LDS_STRIDE = D + 8;     // bf16 elements per LDS row (16 bytes of 
 constexpr int KV_STRIDE = 2 * D + 8;
 // LDS map (bytes): three row buffers (sKV overlays the first two), LayerNorm partial sums, for
 // this tile and the next the packed neighbour rows followed by the node ids (one contiguous
-// block per parity, filled by a single gather), the abort word, timers, then the landing zone:
+// block per tile in flight, filled by a single gather), the abort word, timers, then the landing zone:
 // per gate 8 KB = six source slots of K|V (1 KB each), the gate's own K|V as a seventh slot, its
 // own Q row (512 B) and its residual row (512 B).
 constexpr int SMEM_TILE = 3 * TILE * LDS_STRIDE * 2;                // sA, sX (spare), sH
@@ -95,12 +95,6 @@ __device__ __forceinline__ void dma16(const void* src, uint32_t lds_base)
 // same with a wave-uniform 64-bit base and a per-lane 32-bit byte offset
 __device__ __forceinline__ void dma16_row(const void* base, uint32_t lane_off, uint32_t lds_base)
 {
-#if defined(DG4_NODMA) && DG4_NODMA == 1
-    return;
-#elif defined(DG4_NODMA)
-    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\t; %0 %1" : : "v"(lane_off), "s"(base), "s"(lds_base) : "memory");
-    return;
-#endif
     __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory");
 }
 // one 32-bit word per lane, read at device scope (served by the L2, never by this unit's L1)
@@ -136,21 +130,9 @@ __global__ void sweep_init_kernel(uint32_t* flags, int64_t n, int64_t done_below
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i < n) flags[i] = i < done_below ? 1u : 0u;
-    if (i < 64) ctrl[i] = 0u;                     // [0] ticket, [1] abort, [16..31] phase timers
+    if (i < 64) ctrl[i] = 0u;                     // [1] abort flag, [16..31] phase timers
 }
 
-#ifndef DG4_ISSUE_MODE
-#define DG4_ISSUE_MODE 2
-#endif
-#ifndef DG4_B_ATT
-#define DG4_B_ATT 3
-#endif
-#ifndef DG4_B_MID
-#define DG4_B_MID 3
-#endif
-#ifndef DG4_OWN_LATE
-#define DG4_OWN_LATE 0
-#endif
 // Transfers of slots [S0, S1) of a wave's four gates: lane 8*g + s of (lo, hi) holds the global
 // address of the row, land + g*LAND_GATE + s*1024 is where it goes.
 template <int S0, int S1>
@@ -198,7 +180,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         const uint64_t t = tiles64[p.tile_begin + i];
         return make_uint2((uint32_t)t, (uint32_t)(t >> 32));                          // first position, rows
     };
-    // neighbour rows [gate][entry] and node ids [gate] of the tile with the given parity
+    // neighbour rows [gate][entry] and node ids [gate] of the tile in descriptor buffer `parity` (0..2)
     auto ent_of = [&](int parity) __attribute__((always_inline)) { return (const uint32_t (*)[8])(smem + SMEM_DESC + parity * DESC_BYTES); };
     auto ids_of = [&](int parity) __attribute__((always_inline)) { return (const int32_t*)(smem + SMEM_DESC + parity * DESC_BYTES + TILE * 8 * 4); };
 
@@ -304,9 +286,6 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                           lds0 + (uint32_t)(SMEM_LAND + g * LAND_GATE) + slot * 1024u);
         }
     };
-    auto gather_src = [&](uint32_t e_mine, uint32_t slot_mine, uint64_t take) __attribute__((always_inline)) {
-        gather_some(e_mine, slot_mine, take, 64);
-    };
     // slot of "my" entry: how many sources of my gate come before it in the row
     auto slot_of = [&](uint64_t need) __attribute__((always_inline)) -> uint32_t {
         const uint32_t gate_bits = (uint32_t)(need >> (16 * grp)) & 0xFFFFu;
@@ -353,7 +332,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 break;
             }
         }
-        gather_src(e_mine, slot_of(need), late);
+        gather_some(e_mine, slot_of(need), late, 64);
         __builtin_amdgcn_s_waitcnt(0x0F70);
         __asm__ volatile("" ::: "memory");
     };
@@ -576,18 +555,14 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 // this pair's rows are in registers (so are the next pair's, which sit in higher
                 // slots): its slots may be overwritten
                 __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0)
-                if (has_next && DG4_ISSUE_MODE == 0) {
-                    if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
-                    else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
-                    else if (r == 2) issue_slots<3, 5>(src_lo, src_hi, lane16, wave_land);
-                    else issue_slots<5, 6>(src_lo, src_hi, lane16, wave_land);
-                }
-                if (has_next && DG4_ISSUE_MODE == 2) {
+                // (the gathers are spread out: a wave that issues more transfers than the memory
+                // pipeline takes stalls until they have drained. Slots 0 .. 2 go here, 3 .. 5 below,
+                // around the output projection)
+                if (has_next) {
                     if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
                     else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
                 }
             }
-            if (has_next && DG4_ISSUE_MODE == 1) issue_slots<0, 6>(src_lo, src_hi, lane16, wave_land);
             keep_lo = src_lo; keep_hi = src_hi;
             uint4 oa, ob;
             if (valid) Elem<bf16_t>::pack(acc, oa, ob);
@@ -603,7 +578,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         __syncthreads();                      // sA and the descriptor fetched above complete
         if (sAbort) { flush(); return; }
         lap(2);
-        if (has_next && DG4_ISSUE_MODE == 2) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
+        if (has_next) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
 
         // ---------------- output projection; lane (n = sub, g = grp) owns columns 64*wave + 16*g .. +15 of gate n
         roles();
@@ -622,7 +597,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                     acc[nt] = mfma16(nt == 3 && ks == 7 ? *sWoF : __builtin_bit_cast(uint4, wo_r[nt][ks]), b,
                                      ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[nt]);
             }
-                if (has_next && DG4_ISSUE_MODE == 2) issue_slots<5, 6>(keep_lo, keep_hi, lane16, wave_land);
+                if (has_next) issue_slots<5, 6>(keep_lo, keep_hi, lane16, wave_land);
             float x[16];
             {
                 const uint4* xp = (const uint4*)(sLand + n * LAND_GATE + LAND_X + c0 * 2);
@@ -676,7 +651,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         lap(4);
         roles();
         // the landing zone of the gates' own rows is free now: the next tile's may come in
-        if (!DG4_OWN_LATE && has_next) gather_own(nxt.x, (int)nxt.y, d1);
+        if (has_next) gather_own(nxt.x, (int)nxt.y, d1);
 
         // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
         {
@@ -688,7 +663,6 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 for (int nt = 0; nt < 8; ++nt)
                     acc[nt] = mfma16(__builtin_bit_cast(uint4, wkv_r[nt][ks]), b, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[nt]);
             }
-            if (DG4_OWN_LATE && has_next) gather_own(nxt.x, (int)nxt.y, d1);
             uint4* dst = (uint4*)&sKV[n][128 * wave + 32 * grp];
 #pragma unroll
             for (int h = 0; h < 4; ++h) {
