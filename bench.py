@@ -209,6 +209,11 @@ def main():
         ms_a = timed(lambda: dg4.dg4_sparse_attn_fwd(cfg, g, Q, K, V, W[0][2], A))
         bytes_a = n_gates * 2 * R + (nnz - n_gates) * 2 * R + n_gates * 4 * (1 << (c.hops + 1))
         peak_flops = 2.5e15 if c.dtype == "bf16" else 157.3e12
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        ms_c = timed(lambda: dst.copy_(src))
+        out["roofline"]["measured_copy_GBps"] = 2 * (1 << 30) / (ms_c * 1e-3) / 1e9     # 1 GiB read + 1 GiB written
+        del src, dst
         out["kernel_points"] = {
             "dg4_qkv_proj": {"ms": ms_p, "GB/s": n_gates * 4 * R / (ms_p * 1e-3) / 1e9,
                              "TFLOP/s": flop_p / (ms_p * 1e-3) / 1e12,
