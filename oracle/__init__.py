@@ -66,6 +66,10 @@ def _load():
         lib.orc_layer_nodes.restype = ctypes.c_int
         lib.orc_layer_nodes.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64,
                                         _P, _P, _P, _P, _P, _P, _P, _P, _P, _I64, _P]
+        lib.orc_out_degrees.restype = None
+        lib.orc_out_degrees.argtypes = [_I64, _I64, _P, _P, _P, _P, _P]
+        lib.orc_struct_encode.restype = None
+        lib.orc_struct_encode.argtypes = [_I64, _I32, _P, _P, _P, _P, _P, _I32, _P]
         lib.orc_threads.restype = ctypes.c_int
         lib.orc_threads.argtypes = []
         _lib = lib
@@ -205,4 +209,23 @@ def layer_nodes(g: Graph, x, wqkv, wo, rel_bias, heads, Hsrc, nodes, *, store="f
                                  _ptr(Hsrc), _ptr(nodes), len(nodes), _ptr(out))
     if rc:
         raise OracleError(rc)
+    return out
+
+
+def out_degrees(n, src, dst, inv):
+    """OutAND(v), OutNOT(v) of Eq. 2: AND / NOT gates among the direct fanouts (reading R15)."""
+    src, dst, inv = _c(src, np.int32), _c(dst, np.int32), _c(inv, np.uint8)
+    out_and, out_not = np.empty(n, dtype=np.int32), np.empty(n, dtype=np.int32)
+    _load().orc_out_degrees(n, len(src), _ptr(src), _ptr(dst), _ptr(inv), _ptr(out_and), _ptr(out_not))
+    return out_and, out_not
+
+
+def struct_encode(x, level, out_and, out_not, emb, store="f64"):
+    """x + SE (Eq. 2); emb [6, d] = w_l, b_l, w_and, b_and, w_not, b_not. Returns float64 [N, d]."""
+    x, emb = _c(x, np.float32), _c(emb, np.float32)
+    n, d = x.shape
+    assert emb.shape == (6, d)
+    level, out_and, out_not = _c(level, np.int32), _c(out_and, np.int32), _c(out_not, np.int32)
+    out = np.empty((n, d), dtype=np.float64)
+    _load().orc_struct_encode(n, d, _ptr(x), _ptr(level), _ptr(out_and), _ptr(out_not), _ptr(emb), STORE[store], _ptr(out))
     return out

@@ -38,6 +38,14 @@
  *   R12 arithmetic is double throughout; the only rounding is of H when it is
  *       stored (to float or to bfloat16), because the storage format of the
  *       historical embeddings is part of the problem.
+ *   R15 structural encoding (Section 3.5, Eq. 2) on a graph whose inverters are edge
+ *       flags: a fanout node with in-degree 1 is a NOT/buffer gate; all inverted
+ *       edges leaving v into AND gates stand for ONE inverter fed by v (structural
+ *       hashing keeps one NOT per signal), and the ANDs behind it are fanouts of that
+ *       inverter, not of v. So OutNOT(v) = #fanouts with in-degree 1 + [v has an
+ *       inverted edge into an AND], OutAND(v) = #non-inverted edges into ANDs. Each
+ *       Emb is a linear layer on a scalar, s*w + b; the encoding is added to the
+ *       initial embedding.
  *
  * Parity pins live in tests/ (brute-force dense masked attention, closed
  * forms, hand-worked graphs, invariances). The numeric values of embeddings
@@ -424,4 +432,40 @@ int orc_layer_nodes(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32
     for (int64_t i = 0; i < n_listed; ++i)
         node_step(&L, nodes[i], NULL, Hsrc, NULL, n, out + i * d);
     return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Structural encoding, Section 3.5 Eq. 2:
+ *   SE(v) = Emb_l(level(v)) + Emb_and(OutAND(v)) + Emb_not(OutNOT(v)),  x'(v) = x(v) + SE(v)
+ * with OutAND / OutNOT the numbers of AND / NOT gates among the direct fanouts of v (R15).
+ */
+void orc_out_degrees(int64_t n, int64_t e, const int32_t* src, const int32_t* dst, const uint8_t* inv,
+                     int32_t* out_and, int32_t* out_not)
+{
+    int32_t* indeg = (int32_t*)calloc((size_t)(n > 0 ? n : 1), sizeof(int32_t));
+    uint8_t* has_inverter = (uint8_t*)calloc((size_t)(n > 0 ? n : 1), 1);
+    for (int64_t i = 0; i < e; ++i) indeg[dst[i]]++;
+    for (int64_t v = 0; v < n; ++v) { out_and[v] = 0; out_not[v] = 0; }
+    for (int64_t i = 0; i < e; ++i) {
+        const int32_t v = src[i], u = dst[i];
+        if (indeg[u] == 1) out_not[v]++;                 /* u is a NOT / buffer gate              */
+        else if (inv[i]) has_inverter[v] = 1;            /* the one inverter behind v             */
+        else out_and[v]++;                               /* u is an AND fed by v directly         */
+    }
+    for (int64_t v = 0; v < n; ++v) out_not[v] += has_inverter[v];
+    free(indeg); free(has_inverter);
+}
+
+/* emb: [6][d] = w_l, b_l, w_and, b_and, w_not, b_not; out rounded as stored (store as above) */
+void orc_struct_encode(int64_t n, int32_t d, const float* x, const int32_t* level,
+                       const int32_t* out_and, const int32_t* out_not, const float* emb,
+                       int32_t store, double* out)
+{
+    for (int64_t v = 0; v < n; ++v)
+        for (int32_t c = 0; c < d; ++c) {
+            const double se = ((double)level[v] * emb[0 * d + c] + emb[1 * d + c])
+                            + ((double)out_and[v] * emb[2 * d + c] + emb[3 * d + c])
+                            + ((double)out_not[v] * emb[4 * d + c] + emb[5 * d + c]);
+            out[v * d + c] = round_store((double)x[v * d + c] + se, store);
+        }
 }
