@@ -223,6 +223,11 @@ def main():
                                     "GB/s_compulsory": n_gates * (4 * R + 4 * (1 << (c.hops + 1))) / (ms_a * 1e-3) / 1e9,
                                     "hbm_frac_compulsory": n_gates * (4 * R + 4 * (1 << (c.hops + 1))) / (ms_a * 1e-3) / 1e9 / HBM_PEAK_GBPS,
                                     "edges_per_s": nnz / (ms_a * 1e-3)}}
+        emb = torch.from_numpy(synth.normal(c.seed + 7, 9, (6, c.hidden), 0.25, False)).cuda()
+        ms_s = timed(lambda: dg4.dg4_struct_encode(cfg, g, X, emb, A))
+        bytes_s = n_gates * (2 * R + 12)                       # a row in, a row out, three integers
+        out["kernel_points"]["dg4_struct_encode"] = {"ms": ms_s, "GB/s": bytes_s / (ms_s * 1e-3) / 1e9,
+                                                     "hbm_frac": bytes_s / (ms_s * 1e-3) / 1e9 / HBM_PEAK_GBPS}
         del Q, K, V, A
 
     if not args.no_cpu_baseline:

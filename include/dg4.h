@@ -99,7 +99,10 @@ typedef enum {
      * real dependencies; the level only breaks ties). For inspection and tests; the embeddings do
      * not depend on it. Built on first request. */
     DG4_FLOW_ORDER = 6,     /* int32 [n_nodes]     node ids in processing order          */
-    DG4_FLOW_TILE_PTR = 7   /* int64 [n_tiles + 1] first position of each tile           */
+    DG4_FLOW_TILE_PTR = 7,  /* int64 [n_tiles + 1] first position of each tile           */
+    /* Fanout counts of the structural encoding (Section 3.5, Eq. 2), see dg4_struct_encode. */
+    DG4_OUT_AND = 8,        /* int32 [n_nodes]                                           */
+    DG4_OUT_NOT = 9         /* int32 [n_nodes]                                           */
 } dg4_array;
 
 int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count);
@@ -118,6 +121,19 @@ void dg4_graph_free(dg4_graph* g);
  */
 int64_t dg4_proj_workspace_bytes(const dg4_layer_cfg* cfg);
 int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4_graph* g);
+
+/*
+ * Structural encoding (Section 3.5, Eq. 2), added to the initial embeddings:
+ *   Xout[v] = X[v] + Emb_l(level(v)) + Emb_and(OutAND(v)) + Emb_not(OutNOT(v)),  Emb(s) = s*w + b,
+ * OutAND(v) / OutNOT(v) = numbers of AND / NOT gates among the direct fanouts of v. With inverters
+ * as edge flags: a fanout with in-degree 1 is a NOT/buffer gate; all inverted edges from v into AND
+ * gates stand for the ONE inverter of v (counted once), plain edges into AND gates count one each.
+ * level(v) is the graph's level (Eq. 1 or the hint). fp32 arithmetic, one rounding to cfg->dtype.
+ *   X, Xout [n, hidden] device (may be the same buffer); emb: device float [6, hidden] = w_l, b_l,
+ *   w_and, b_and, w_not, b_not. cfg: hidden, heads, dtype are used.
+ */
+int dg4_struct_encode(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const float* emb,
+                      void* Xout, void* stream);
 
 /*
  * Q = S Wq, K = S Wk, V = S Wv for rows [row_begin, row_end) of S (the

@@ -19,7 +19,8 @@ DG4_PER_LEVEL = 2
 DG4_BOUNDED_KV = 4
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
           "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8),
-          "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64)}
+          "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64),
+          "out_and": (8, np.int32), "out_not": (9, np.int32)}
 STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
           -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP"}
 
@@ -88,6 +89,8 @@ def lib():
         L.dg4_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), _P]
         L.dg4_qkv_proj.restype = ctypes.c_int
         L.dg4_qkv_proj.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _I64, _P]
+        L.dg4_struct_encode.restype = ctypes.c_int
+        L.dg4_struct_encode.argtypes = [ctypes.POINTER(_Cfg), _P, _P, _P, _P, _P]
         L.dg4_sparse_attn_fwd.restype = ctypes.c_int
         L.dg4_sparse_attn_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _P]
         L.dg4_layer_fwd.restype = ctypes.c_int
@@ -193,6 +196,13 @@ def dg4_qkv_proj(cfg: LayerConfig, S, Wqkv, Q, K, V, row_begin=0, row_end=None, 
     rc = lib().dg4_qkv_proj(ctypes.byref(c), S.data_ptr(), row_begin, row_end, Wqkv.data_ptr(),
                             Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "dg4_qkv_proj")
+
+
+def dg4_struct_encode(cfg: LayerConfig, g: Graph, X, emb, Xout):
+    """Xout = X + structural encoding (level, OutAND, OutNOT through three linear layers); emb float [6, hidden]."""
+    c = cfg.c()
+    rc = lib().dg4_struct_encode(ctypes.byref(c), g.handle, X.data_ptr(), emb.data_ptr(), Xout.data_ptr(), _stream())
+    _check(rc, "dg4_struct_encode")
 
 
 def dg4_sparse_attn_fwd(cfg: LayerConfig, g: Graph, Q, K, V, rel_bias, A, row_begin=0, row_end=None):

@@ -158,6 +158,19 @@ extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row
     return DG4_OK;
 }
 
+extern "C" int dg4_struct_encode(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const float* emb,
+                                 void* Xout, void* stream)
+{
+    int rc = check_cfg(cfg, false);
+    if (rc != DG4_OK) return rc;
+    if (!g || !X || !emb || !Xout) return DG4_EINVAL;
+    if (g->n == 0) return DG4_OK;
+    rc = dg4_graph_ensure_struct(g);
+    if (rc != DG4_OK) return rc;
+    HIPCHK(dg4_launch_struct_encode(cfg->dtype, cfg->hidden, X, g->d_struct, emb, Xout, g->n, (hipStream_t)stream));
+    return DG4_OK;
+}
+
 extern "C" int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begin, int64_t row_end,
                                    const void* Q, const void* K, const void* V, const float* rel_bias,
                                    void* A, void* stream)

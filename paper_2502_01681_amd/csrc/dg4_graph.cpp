@@ -195,6 +195,24 @@ extern "C" int dg4_build_levels(int64_t n, int64_t e, const int32_t* es, const i
                 g->nbr_rel[g->nbr_ptr[v] + j] = h == 0 ? 0 : h == 1 ? (uint8_t)(1 + a.inv[base + j]) : 3;
             }
         }
+        // Fanout counts of the structural encoding (Section 3.5, Eq. 2), gathered from the fanin
+        // table: a reader with one fanin is a NOT/buffer gate; inverted uses by AND gates share the
+        // one inverter of the signal; plain uses by AND gates count one by one.
+        g->out_and.assign((size_t)n, 0);
+        g->out_not.assign((size_t)n, 0);
+        {
+            std::vector<uint8_t> inverter((size_t)n, 0);
+            for (int64_t v = 0; v < n; ++v) {
+                const int32_t a0 = f.src[2 * (size_t)v], a1 = f.src[2 * (size_t)v + 1];
+                if (a0 < 0) continue;                                   // primary input
+                if (a1 < 0) { ++g->out_not[a0]; continue; }             // v is a NOT / buffer gate
+                for (int k = 0; k < 2; ++k) {
+                    const int32_t u = f.src[2 * (size_t)v + k];
+                    if (f.inv[2 * (size_t)v + k]) inverter[u] = 1; else ++g->out_and[u];
+                }
+            }
+            for (int64_t v = 0; v < n; ++v) g->out_not[v] += inverter[v];
+        }
         *out = guard.release();
         return DG4_OK;
     } catch (const std::bad_alloc&) {
@@ -214,6 +232,8 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
     case DG4_NBR_PTR: *host_ptr = g->nbr_ptr.data(); *count = g->n + 1; break;
     case DG4_NBR_IDX: *host_ptr = g->nbr_idx.data(); *count = g->nnz; break;
     case DG4_NBR_REL: *host_ptr = g->nbr_rel.data(); *count = g->nnz; break;
+    case DG4_OUT_AND: *host_ptr = g->out_and.data(); *count = g->n; break;
+    case DG4_OUT_NOT: *host_ptr = g->out_not.data(); *count = g->n; break;
     case DG4_FLOW_ORDER:
     case DG4_FLOW_TILE_PTR: {
         dg4_graph* m = const_cast<dg4_graph*>(g);            // the schedule is built on first use, under the lock
@@ -414,6 +434,7 @@ int dg4_graph_ensure_device(dg4_graph* g)
     if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
     if (g->d_flow_order) (void)hipFree(g->d_flow_order);
     if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
+    if (g->d_struct) (void)hipFree(g->d_struct);
     if (g->d_front_id) (void)hipFree(g->d_front_id);
     if (g->d_ell_front) (void)hipFree(g->d_ell_front);
             g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr;
@@ -443,6 +464,27 @@ int dg4_graph_ensure_device(dg4_graph* g)
         return DG4_ENOMEM;
     }
     g->ell_w = w; g->device = dev; g->on_device = true;
+    return DG4_OK;
+}
+
+// level, OutAND, OutNOT of every node as one device table [n][3] for dg4_struct_encode
+int dg4_graph_ensure_struct(dg4_graph* g)
+{
+    std::lock_guard<std::mutex> lock(g->mu);
+    if (g->d_struct) return DG4_OK;
+    try {
+        std::vector<int32_t> t((size_t)std::max<int64_t>(g->n, 1) * 3, 0);
+        for (int64_t v = 0; v < g->n; ++v) {
+            t[3 * (size_t)v] = g->level[v]; t[3 * (size_t)v + 1] = g->out_and[v]; t[3 * (size_t)v + 2] = g->out_not[v];
+        }
+        if (hipMalloc((void**)&g->d_struct, t.size() * sizeof(int32_t)) != hipSuccess) return DG4_ENOMEM;
+        if (hipMemcpy(g->d_struct, t.data(), t.size() * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(g->d_struct); g->d_struct = nullptr;
+            return DG4_EHIP;
+        }
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
     return DG4_OK;
 }
 

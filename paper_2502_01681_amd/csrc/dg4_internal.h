@@ -25,6 +25,8 @@ struct dg4_graph {
     std::vector<int32_t> pos;                    // pos[id] = position in the level-ordered device processing order (set at upload)
     std::vector<int32_t> sweep_order;            // its inverse: position -> id
     std::vector<int64_t> level_ptr, nbr_ptr;
+    std::vector<int32_t> out_and, out_not;       // fanout counts of the structural encoding (Eq. 2)
+    int32_t* d_struct = nullptr;                 // device [n][3]: level, OutAND, OutNOT (on first dg4_struct_encode)
     std::vector<int32_t> nbr_idx;
     std::vector<uint8_t> nbr_rel;
 
@@ -63,6 +65,11 @@ struct dg4_graph {
 int dg4_graph_ensure_device(dg4_graph* g);
 int dg4_flow_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
 int dg4_graph_ensure_frontier(dg4_graph* g);           // after dg4_graph_ensure_device
+int dg4_graph_ensure_struct(dg4_graph* g);
+
+// ---- structural encoding (dg4_kernels.hip) ----
+int dg4_launch_struct_encode(int dtype, int hidden, const void* x, const int32_t* feat, const float* emb, void* out,
+                             int64_t n, hipStream_t s);
 
 // ---- kernel launchers (dg4_kernels.hip). All return a hipError_t as int. ----
 

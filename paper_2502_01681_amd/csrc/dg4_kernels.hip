@@ -309,7 +309,67 @@ int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
     return hipGetLastError();
 }
 
+// Structural encoding (paper Section 3.5, Eq. 2): out[v] = x[v] + (level*w_l + b_l) + (OutAND*w_and +
+// b_and) + (OutNOT*w_not + b_not). Elementwise and HBM-bound (a row in, a row out, 12 bytes of
+// integer features): one thread per 16 bytes of a row, the [6, d] embedding table comes from cache.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void struct_encode_kernel(const T* x, const int32_t* feat, const float* emb, T* out, int64_t n)
+{
+    constexpr int E = 16 / (int)sizeof(T);           // elements per thread
+    constexpr int U = D / E;                         // threads per row
+    constexpr int RPB = 256 / U;                     // rows per block and step
+    const int c0 = (int)(threadIdx.x % U) * E;
+    // this thread's slice of the six embedding rows stays in registers while it walks down the rows
+    float wl[E], bl[E], wa[E], ba[E], wn[E], bn[E];
+#pragma unroll
+    for (int i = 0; i < E; ++i) {
+        wl[i] = emb[c0 + i]; bl[i] = emb[D + c0 + i]; wa[i] = emb[2 * D + c0 + i];
+        ba[i] = emb[3 * D + c0 + i]; wn[i] = emb[4 * D + c0 + i]; bn[i] = emb[5 * D + c0 + i];
+    }
+    for (int64_t v = (int64_t)blockIdx.x * RPB + threadIdx.x / U; v < n; v += (int64_t)gridDim.x * RPB) {
+        const float lev = (float)feat[3 * v], oa = (float)feat[3 * v + 1], on = (float)feat[3 * v + 2];
+        const uint4 raw = *(const uint4*)(x + v * D + c0);
+        float f[8];
+        if (sizeof(T) == 4) {
+            f[0] = __uint_as_float(raw.x); f[1] = __uint_as_float(raw.y); f[2] = __uint_as_float(raw.z); f[3] = __uint_as_float(raw.w);
+        } else {
+            const uint32_t w4[4] = { raw.x, raw.y, raw.z, raw.w };
+#pragma unroll
+            for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(w4[i]); f[2 * i + 1] = bf16_hi(w4[i]); }
+        }
+        // the three linear layers, summed in the order of Eq. 2, then added to the feature
+#pragma unroll
+        for (int i = 0; i < E; ++i) f[i] += fmaf(lev, wl[i], bl[i]) + fmaf(oa, wa[i], ba[i]) + fmaf(on, wn[i], bn[i]);
+        uint4 o;
+        if (sizeof(T) == 4) {
+            o = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+        } else {
+            o = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+        }
+        *(uint4*)(out + v * D + c0) = o;
+    }
+}
+
+template <typename T, int D>
+int launch_struct_encode_t(const void* x, const int32_t* feat, const float* emb, void* out, int64_t n, hipStream_t s)
+{
+    constexpr int RPB = 256 / (D / (16 / (int)sizeof(T)));
+    const int64_t blocks = std::min<int64_t>((n + RPB - 1) / RPB, 256 * 16);      // 16 workgroups per compute unit
+    hipLaunchKernelGGL((struct_encode_kernel<T, D>), dim3((unsigned)blocks), dim3(256), 0, s,
+                       (const T*)x, feat, emb, (T*)out, n);
+    return hipGetLastError();
+}
+
 }  // namespace
+
+int dg4_launch_struct_encode(int dtype, int hidden, const void* x, const int32_t* feat, const float* emb, void* out,
+                             int64_t n, hipStream_t s)
+{
+    if (n <= 0) return hipSuccess;
+    if (dtype == DG4_F32)
+        return hidden == 128 ? launch_struct_encode_t<float, 128>(x, feat, emb, out, n, s) : launch_struct_encode_t<float, 256>(x, feat, emb, out, n, s);
+    return hidden == 128 ? launch_struct_encode_t<uint16_t, 128>(x, feat, emb, out, n, s) : launch_struct_encode_t<uint16_t, 256>(x, feat, emb, out, n, s);
+}
 
 int dg4_launch_attn(int dtype, int hidden, const dg4_attn_args& a, hipStream_t s)
 {

@@ -179,6 +179,41 @@ def test_bounded_kv_sweep(name, n_and, kw):
     assert torch.equal(H2, H_bound)
 
 
+@pytest.mark.parametrize("name,n_and,dtype,hidden", [("tiny", None, "f32", 128), ("small", None, "f32", 256),
+                                                     ("large", 70_001, "bf16", 256), ("medium", 30_000, "bf16", 128)])
+def test_struct_encode(name, n_and, dtype, hidden):
+    # Eq. 2 of Section 3.5 against the oracle, element by element; in place as well
+    print(f"struct_encode {name} {dtype} d={hidden}", flush=True)
+    base = synth.CONFIGS[name]
+    c = synth.Config(**{**base.__dict__, "dtype": dtype, "hidden": hidden, "heads": hidden // 32,
+                        **({"n_and": n_and} if n_and else {})})
+    w = synth.make(c)
+    g, og = graphs(w)
+    emb = synth.normal(c.seed + 7, 9, (6, hidden), 0.25, False)
+    oa, on = oracle.out_degrees(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv)
+    ref = oracle.struct_encode(w.x, og.level, oa, on, emb, store=dtype)
+    cfg = cfg_of(c)
+    X = to_dev(w.x, dtype)
+    E = to_dev(emb, "f32")
+    out = torch.full_like(X, float("nan"))
+    dg4.dg4_struct_encode(cfg, g, X, E, out)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    assert not np.isnan(got).any()
+    # fp32 arithmetic against fp64: a few fp32 roundings of the terms' magnitudes, plus the one
+    # rounding to the stored format
+    F = np.stack([og.level, np.ones(c.n_nodes), oa, np.ones(c.n_nodes), on, np.ones(c.n_nodes)], axis=1)
+    mag = np.abs(w.x).astype(np.float64) + np.abs(F) @ np.abs(emb).astype(np.float64)
+    store_ulp = 2.0 ** -23 if dtype == "f32" else 2.0 ** -7     # a different rounding decision next to a tie
+    assert (np.abs(got - ref) <= 8 * 2.0 ** -24 * mag + store_ulp * np.abs(ref)).all()
+    assert row_rel_err(got, ref).max() <= TOL[dtype]
+    if dtype == "bf16":
+        assert (got == ref).mean() > 0.999            # bf16: the same rounding decision almost everywhere
+    dg4.dg4_struct_encode(cfg, g, X, E, X)             # in place
+    torch.cuda.synchronize()
+    assert torch.equal(X, out)
+
+
 def test_workspace_reuse_with_new_inputs():
     # the same workspace and output buffer, different features: nothing stale may be read
     print("layer_fwd workspace reuse", flush=True)

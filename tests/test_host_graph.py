@@ -18,8 +18,8 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "dg4.h")).read()
     names = set(re.findall(r"^(?:int|int64_t|void|const char\*)\s+(dg4_[a-z_]+)\s*\(", hdr, flags=re.M))
-    assert len(names) == 13
-    assert {"dg4_build_levels", "dg4_qkv_proj", "dg4_sparse_attn_fwd", "dg4_layer_fwd"} <= names
+    assert len(names) == 14
+    assert {"dg4_build_levels", "dg4_qkv_proj", "dg4_sparse_attn_fwd", "dg4_layer_fwd", "dg4_struct_encode"} <= names
     L = ctypes.CDLL(dg4.library_path()) if os.path.exists(dg4.library_path()) else dg4.lib()
     for n in sorted(names):
         assert hasattr(L, n), n
@@ -79,6 +79,24 @@ def test_dataflow_order_is_a_valid_schedule(name, n_and, hops, hint):
     # the same graph gives the same order again
     g2 = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint if hint else None)
     assert (g2.array("flow_order") == order).all()
+
+
+@pytest.mark.parametrize("name,n_and", [("tiny", None), ("small", None), ("large", 40_000)])
+def test_fanout_counts_of_the_structural_encoding(name, n_and):
+    # OutAND / OutNOT of Eq. 2, bit for bit against the oracle; also on a graph with in-degree-1 nodes
+    w = synth.make(name, n_and=n_and, features=False)
+    n = w.cfg.n_nodes
+    g = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, 2, w.level_hint)
+    oa, on = oracle.out_degrees(n, w.edge_src, w.edge_dst, w.edge_inv)
+    assert (g.array("out_and") == oa).all() and (g.array("out_not") == on).all()
+    # drop the second fanin of every third AND: those gates become NOT/buffer nodes
+    keep = np.ones(len(w.edge_src), dtype=bool)
+    keep[np.arange(1, len(w.edge_src), 6)] = False
+    src, dst, inv = w.edge_src[keep], w.edge_dst[keep], w.edge_inv[keep]
+    g = dg4.dg4_build_levels(n, src, dst, inv, 2)
+    oa, on = oracle.out_degrees(n, src, dst, inv)
+    assert (g.array("out_and") == oa).all() and (g.array("out_not") == on).all()
+    assert on.max() >= 2                                       # a NOT node and the signal's own inverter
 
 
 def test_shuffled_edges_and_relabelled_nodes():
