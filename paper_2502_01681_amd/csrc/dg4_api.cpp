@@ -282,7 +282,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.wo_packed = at(pl.wo_t); a.wkv_packed = at(pl.wkv_t);
         a.rel_bias = (const float*)W[2];
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
-        a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.publish_kv = 1;
+        a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.eager_publish = whole ? 0 : 1;
         a.spin_limit = dg4_sweep_spin_limit();
         a.prof = getenv("DG4_SWEEP_PROFILE") ? (uint64_t*)((char*)at(pl.ctrl) + 64) : nullptr;
         SweepEvents& ev = sweep_events();

@@ -119,7 +119,8 @@ struct dg4_sweep_args {
     uint32_t* flags;                       // [n] by position: 1 = rows published
     uint32_t* ctrl;                        // [1] abort flag, [16..31] phase timers
     uint64_t* prof;                        // nullable: 8 phase timers (100 MHz ticks, summed over workgroups)
-    float ln_eps; int epilogue; int publish_kv;
+    float ln_eps; int epilogue;
+    int eager_publish;                     // raise a tile's flags as soon as its rows are written (level-ordered tiles: readers are close)
     uint32_t spin_limit;
 };
 int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void* packed, hipStream_t s);

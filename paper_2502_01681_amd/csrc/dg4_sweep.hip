@@ -383,13 +383,14 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         // follow further down, once the stores have completed (= are written through, visible
         // to every compute unit). Only a wave that has to wait for late sources, or whose
         // previous tile was ragged (fewer stores), waits for everything here: the flags must
-        // be up before any blocking wait, other workgroups may be waiting for them.
+        // be up before any blocking wait, other workgroups may be waiting for them. (So does
+        // every wave when the tiles are dealt level by level: there the readers follow closely.)
         auto publish = [&]() __attribute__((always_inline)) {
             if (lane < 4 && 4 * wave + lane < pub_rows)
                 __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         };
         bool published = false;
-        if (TIMERS || late || pub_rows != TILE) {     // (the timed build has a barrier right below: flags first)
+        if (TIMERS || p.eager_publish || late || pub_rows != TILE) {     // (the timed build has a barrier right below: flags first)
             __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
             __asm__ volatile("" ::: "memory");
             publish();
