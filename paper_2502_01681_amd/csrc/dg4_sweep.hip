@@ -269,6 +269,22 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             dma16(tail, dst + 1024u);
         }
     };
+    //     The same for a full tile (nearly all are), with few instructions: one scalar base walked
+    //     from gate to gate for the K|V halves; for the second transfer (Q in lanes 0..31, the
+    //     residual row in lanes 32..63) a per-lane base plus 512 * (3*gq | node id).
+    auto gather_own_full = [&](int64_t p0, int parity) __attribute__((always_inline)) {
+        const unsigned char* kv_row = (const unsigned char*)p.qkv_self + (p0 + 4 * wave) * (3 * D * 2) + D * 2;
+        const bool lo = lane < 32;
+        const uint64_t base = lo ? (uint64_t)(uintptr_t)p.qkv_self + (uint64_t)(p0 + 4 * wave) * (3 * D * 2) + lane16
+                                 : (uint64_t)(uintptr_t)p.x + (lane16 - 512u);
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+            const uint32_t dst = wave_land + (uint32_t)(gq * LAND_GATE + LAND_SELF);
+            dma16_row(kv_row + gq * (3 * D * 2), lane16, dst);                                              // K | V
+            const uint32_t sel = lo ? 3u * gq : (uint32_t)ids_of(parity)[4 * wave + gq];
+            dma16((const void*)(uintptr_t)(base + (uint64_t)sel * (D * 2)), dst + 1024u);                    // Q | x
+        }
+    };
     // (3) the K|V kilobyte of a source: one instruction per (gate, source), in a loop over the
     //     set bits of `take` (bit 16*gq + j = entry j of this wave's gate gq). Each lane holds
     //     "its" entry (entry `sub` of gate `my`) and the slot it lands in; slot s of a gate holds
@@ -652,7 +668,10 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         lap(4);
         roles();
         // the landing zone of the gates' own rows is free now: the next tile's may come in
-        if (has_next) gather_own(nxt.x, (int)nxt.y, d1);
+        if (has_next) {
+            if ((int)nxt.y == TILE) gather_own_full(nxt.x, d1);
+            else gather_own(nxt.x, (int)nxt.y, d1);
+        }
 
         // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
         {
