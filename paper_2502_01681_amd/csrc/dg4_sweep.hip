@@ -357,6 +357,9 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     // one workgroup per compute unit, so all of them are resident together). A tile waits only
     // for lower-numbered tiles, each owned by a workgroup that is running.
     const int64_t G = gridDim.x;
+    // (Dealing runs of consecutive tiles to one XCD, so that gates sharing a source share an L2, was
+    // measured and is not worth it: 80 % of a tile's source rows are distinct already inside the
+    // tile, 71 % inside 32 consecutive tiles.)
     int64_t ticket = blockIdx.x;
     if (ticket >= p.n_tiles) return;
     // (tickets past the end are clamped: the fetch is harmless and its result unused)
