@@ -41,16 +41,17 @@ constexpr int TILE = DG4_TILE_ROWS;   // 16
 constexpr int D = 256;
 constexpr int LDS_STRIDE = D + 8;     // bf16 elements per LDS row (16 bytes of padding)
 constexpr int KV_STRIDE = 2 * D + 8;
-// LDS map (bytes): three row buffers (sKV overlays the first two), LayerNorm partial sums, for
-// this tile and the next the packed neighbour rows followed by the node ids (one contiguous
-// block per tile in flight, filled by a single gather), the abort word, timers, then the landing zone:
-// per gate 8 KB = six source slots of K|V (1 KB each), the gate's own K|V as a seventh slot, its
-// own Q row (512 B) and its residual row (512 B).
+// LDS map (bytes): three row buffers (sKV overlays the first two; the second, spare one also
+// holds the flag snapshots and the address scatter of the attention phase), LayerNorm partial
+// sums, for this tile and the next two the packed neighbour rows followed by the node ids (one
+// contiguous block per tile, filled by a single gather), the abort word, timers, the bias table,
+// one Wo fragment per wave, then the landing zone: per gate 8 KB = six source slots of K|V (1 KB
+// each), the gate's own K|V as a seventh slot, its own Q row (512 B) and its residual row (512 B).
 constexpr int SMEM_TILE = 3 * TILE * LDS_STRIDE * 2;                // sA, sX (spare), sH
 static_assert(TILE * KV_STRIDE * 2 <= 2 * TILE * LDS_STRIDE * 2, "sKV must fit over sA and sX");
-constexpr int SMEM_LOOK = TILE * LDS_STRIDE * 2;                    // two flag snapshots (1 KB each) in the spare row buffer
+constexpr int SMEM_LOOK = TILE * LDS_STRIDE * 2;                    // two flag snapshots and the address scatter (1 KB each) in the spare row buffer
 constexpr int SMEM_RED = SMEM_TILE;
-constexpr int SMEM_DESC = SMEM_RED + TILE * 4 * 2 * 4;              // [2 parities][ent 16 x 8 words | ids 16 words]
+constexpr int SMEM_DESC = SMEM_RED + TILE * 4 * 2 * 4;              // [3 tiles][ent 16 x 8 words | ids 16 words]
 constexpr int DESC_BYTES = TILE * 8 * 4 + TILE * 4;                 // 576
 constexpr int SMEM_ABORT = SMEM_DESC + 3 * DESC_BYTES;
 constexpr int SMEM_PROF = SMEM_ABORT + 16;
