@@ -62,10 +62,10 @@ def _load():
         lib.orc_sparse_attn.argtypes = [_I64, _I32, _I32, _I64, _I64, _P, _P, _P, _P, _P, _P, _P, _P, _P]
         lib.orc_layer_fwd.restype = ctypes.c_int
         lib.orc_layer_fwd.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64, _I32,
-                                      _P, _P, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P]
+                                      _P, _P, _P, _P, _P, _P, _P, _P, _I32, _I32, _P, _P, _P, _P]
         lib.orc_layer_nodes.restype = ctypes.c_int
         lib.orc_layer_nodes.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64,
-                                        _P, _P, _P, _P, _P, _P, _P, _P, _P, _I64, _P]
+                                        _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _I64, _P]
         lib.orc_out_degrees.restype = None
         lib.orc_out_degrees.argtypes = [_I64, _I64, _P, _P, _P, _P, _P]
         lib.orc_struct_encode.restype = None
@@ -177,17 +177,26 @@ def _stack(ws, shape):
     return a
 
 
+def _ffn(w1, w2, nl, d):
+    if w1 is None and w2 is None:
+        return None, None
+    assert w1 is not None and w2 is not None and len(w1) == nl and len(w2) == nl
+    return _stack(w1, (d, 4 * d)), _stack(w2, (4 * d, d))
+
+
 def layer_fwd(g: Graph, x, wqkv, wo, rel_bias, heads, *, store="f64", epilogue=True, ln_eps=1e-5,
-              memo=True, level_begin=0, level_end=None, H_init=None):
-    """The full level sweep. wqkv / wo / rel_bias are per-layer lists. Returns H [N,d] float64."""
+              memo=True, level_begin=0, level_end=None, H_init=None, w1=None, w2=None):
+    """The full level sweep. wqkv / wo / rel_bias (and w1 / w2 of the feed-forward sub-block,
+    if any) are per-layer lists. Returns H [N,d] float64."""
     x = _c(x, np.float32)
     n, d = x.shape
     nl = len(wqkv)
     Wqkv, Wo, B = _stack(wqkv, (d, 3 * d)), _stack(wo, (d, d)), _stack(rel_bias, (heads, 4))
+    W1, W2 = _ffn(w1, w2, nl, d)
     level_end = g.n_levels if level_end is None else level_end
     H = np.zeros((n, d), dtype=np.float64) if H_init is None else np.array(H_init, dtype=np.float64, order="C")
     rc = _load().orc_layer_fwd(n, d, heads, nl, STORE[store], int(epilogue), float(ln_eps), int(memo),
-                               _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B), _ptr(g.order), _ptr(g.level_ptr),
+                               _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B), _ptr(W1), _ptr(W2), _ptr(g.order), _ptr(g.level_ptr),
                                level_begin, level_end, _ptr(g.nbr_ptr), _ptr(g.nbr_idx), _ptr(g.nbr_rel), _ptr(H))
     if rc:
         raise OracleError(rc)
@@ -195,16 +204,17 @@ def layer_fwd(g: Graph, x, wqkv, wo, rel_bias, heads, *, store="f64", epilogue=T
 
 
 def layer_nodes(g: Graph, x, wqkv, wo, rel_bias, heads, Hsrc, nodes, *, store="f64", epilogue=True,
-                ln_eps=1e-5):
+                ln_eps=1e-5, w1=None, w2=None):
     """One step for the listed nodes, sources' final embeddings given in Hsrc [N,d] float32."""
     x, Hsrc = _c(x, np.float32), _c(Hsrc, np.float32)
     n, d = x.shape
     nl = len(wqkv)
     Wqkv, Wo, B = _stack(wqkv, (d, 3 * d)), _stack(wo, (d, d)), _stack(rel_bias, (heads, 4))
+    W1, W2 = _ffn(w1, w2, nl, d)
     nodes = _c(nodes, np.int64)
     out = np.empty((len(nodes), d), dtype=np.float64)
     rc = _load().orc_layer_nodes(n, d, heads, nl, STORE[store], int(epilogue), float(ln_eps),
-                                 _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B),
+                                 _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B), _ptr(W1), _ptr(W2),
                                  _ptr(g.nbr_ptr), _ptr(g.nbr_idx), _ptr(g.nbr_rel),
                                  _ptr(Hsrc), _ptr(nodes), len(nodes), _ptr(out))
     if rc:

@@ -46,6 +46,11 @@
  *       inverted edge into an AND], OutAND(v) = #non-inverted edges into ANDs. Each
  *       Emb is a linear layer on a scalar, s*w + b; the encoding is added to the
  *       initial embedding.
+ *   R16 "the original transformer structure" (Section 3.5) read as the post-norm encoder
+ *       block: after the attention sub-block h = LN(s + a Wo) comes the position-wise
+ *       feed-forward sub-block s' = LN(h + max(h W1, 0) W2), W1 [d, 4d], W2 [4d, d],
+ *       rectifier, no biases (R10), LayerNorm as in R7. Optional: a layer without
+ *       W1 / W2 is the attention sub-block alone.
  *
  * Parity pins live in tests/ (brute-force dense masked attention, closed
  * forms, hand-worked graphs, invariances). The numeric values of embeddings
@@ -317,11 +322,25 @@ typedef struct {
     const float* wqkv;      /* [n_layers, d, 3d] */
     const float* wo;        /* [n_layers, d, d] */
     const float* bias;      /* [n_layers, heads, 4] */
+    const float* w1;        /* [n_layers, d, 4d] or NULL: no feed-forward sub-block (R16) */
+    const float* w2;        /* [n_layers, 4d, d] */
     const int64_t* nbr_ptr; const int32_t* nbr_idx; const uint8_t* nbr_rel;
 } orc_layer;
 
+/* t <- LayerNorm(t): no affine parameters, biased variance, eps inside the root (R7) */
+static void layer_norm(double* t, int d, double eps)
+{
+    double mean = 0.0, var = 0.0;
+    for (int i = 0; i < d; ++i) mean += t[i];
+    mean /= d;
+    for (int i = 0; i < d; ++i) var += (t[i] - mean) * (t[i] - mean);
+    var /= d;
+    double r = 1.0 / sqrt(var + eps);
+    for (int i = 0; i < d; ++i) t[i] = (t[i] - mean) * r;
+}
+
 /*
- * All layers of one node v (R6, R7). Source states come from Hd (double rows)
+ * All layers of one node v (R6, R7, R16). Source states come from Hd (double rows)
  * if non-NULL, else from Hf (float rows). kv_memo (nullable): per layer and
  * node the already projected [K | V] row of the node's final embedding; it is
  * a pure function of H_u, so using it changes no value.
@@ -332,9 +351,9 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
     const int d = L->d;
     const int64_t p0 = L->nbr_ptr[v];
     const int cnt = (int)(L->nbr_ptr[v + 1] - p0);
-    double* buf = (double*)malloc(sizeof(double) * (size_t)d * (2 * (size_t)cnt + 5));
+    double* buf = (double*)malloc(sizeof(double) * (size_t)d * (2 * (size_t)cnt + 9));
     double *s = buf, *q = s + d, *a = q + d, *o = a + d, *src = o + d;
-    double *k = src + d, *vv = k + (size_t)cnt * d;
+    double *k = src + d, *vv = k + (size_t)cnt * d, *u = vv + (size_t)cnt * d;   /* u: 4d */
     for (int i = 0; i < d; ++i) s[i] = (double)L->x[v * d + i];
     for (int l = 0; l < L->n_layers; ++l) {
         const float* W = L->wqkv + (int64_t)l * d * 3 * d;
@@ -357,15 +376,17 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
         attend(d, L->heads, cnt, q, k, vv, L->nbr_rel + p0, L->bias + (int64_t)l * L->heads * 4, a, NULL);
         vec_mat(a, d, L->wo + (int64_t)l * d * d, d, 0, d, o);
         if (L->epilogue) {
-            double mean = 0.0, var = 0.0;
-            for (int i = 0; i < d; ++i) { o[i] += s[i]; mean += o[i]; }
-            mean /= d;
-            for (int i = 0; i < d; ++i) var += (o[i] - mean) * (o[i] - mean);
-            var /= d;
-            double r = 1.0 / sqrt(var + L->ln_eps);
-            for (int i = 0; i < d; ++i) s[i] = (o[i] - mean) * r;
+            for (int i = 0; i < d; ++i) s[i] += o[i];
+            layer_norm(s, d, L->ln_eps);
         } else {
             for (int i = 0; i < d; ++i) s[i] = o[i];
+        }
+        if (L->w1) {                                      /* R16: s <- LN(s + max(s W1, 0) W2) */
+            vec_mat(s, d, L->w1 + (int64_t)l * d * 4 * d, 4 * d, 0, 4 * d, u);
+            for (int i = 0; i < 4 * d; ++i) if (u[i] < 0.0) u[i] = 0.0;
+            vec_mat(u, 4 * d, L->w2 + (int64_t)l * 4 * d * d, d, 0, d, o);
+            for (int i = 0; i < d; ++i) s[i] += o[i];
+            layer_norm(s, d, L->ln_eps);
         }
     }
     for (int i = 0; i < d; ++i) out[i] = round_store(s[i], L->store);
@@ -381,12 +402,14 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
 int orc_layer_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32_t store,
                   int32_t epilogue, double ln_eps, int32_t memo,
                   const float* x, const float* wqkv, const float* wo, const float* bias,
+                  const float* w1 /* nullable */, const float* w2 /* nullable with w1 */,
                   const int32_t* order, const int64_t* level_ptr, int32_t level_begin, int32_t level_end,
                   const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
                   double* H)
 {
     if (d <= 0 || d > 1024 || heads <= 0 || d % heads || n_layers <= 0) return ORC_EINVAL;
-    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, nbr_ptr, nbr_idx, nbr_rel };
+    if ((w1 == NULL) != (w2 == NULL) || (w1 && !epilogue)) return ORC_EINVAL;
+    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, w1, w2, nbr_ptr, nbr_idx, nbr_rel };
     double* kv = NULL;
     if (memo) {
         kv = (double*)malloc(sizeof(double) * (size_t)n_layers * (size_t)n * 2 * (size_t)d);
@@ -423,11 +446,13 @@ int orc_layer_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32_t
 int orc_layer_nodes(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32_t store,
                     int32_t epilogue, double ln_eps,
                     const float* x, const float* wqkv, const float* wo, const float* bias,
+                    const float* w1 /* nullable */, const float* w2 /* nullable with w1 */,
                     const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
                     const float* Hsrc, const int64_t* nodes, int64_t n_listed, double* out /* [n_listed, d] */)
 {
     if (d <= 0 || d > 1024 || heads <= 0 || d % heads || n_layers <= 0) return ORC_EINVAL;
-    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, nbr_ptr, nbr_idx, nbr_rel };
+    if ((w1 == NULL) != (w2 == NULL) || (w1 && !epilogue)) return ORC_EINVAL;
+    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, w1, w2, nbr_ptr, nbr_idx, nbr_rel };
 #pragma omp parallel for schedule(dynamic, 16)
     for (int64_t i = 0; i < n_listed; ++i)
         node_step(&L, nodes[i], NULL, Hsrc, NULL, n, out + i * d);

@@ -80,11 +80,12 @@ def layer_norm(t, eps):
     return (t - mu) / np.sqrt(var + eps)
 
 
-def dense_layer(n, src, dst, inv, hops, x, wqkv, wo, rel_bias, heads, eps=1e-5, epilogue=True):
+def dense_layer(n, src, dst, inv, hops, x, wqkv, wo, rel_bias, heads, eps=1e-5, epilogue=True, w1=None, w2=None):
     """Brute-force dense masked attention, float64, one node at a time.
 
     Multi-layer nesting: a node finishes all its layers before any fanout starts;
-    sources are read at their final embedding in every layer.
+    sources are read at their final embedding in every layer. With w1 / w2 (per-layer
+    lists) every layer ends with the feed-forward sub-block LN(h + relu(h W1) W2).
     """
     x = np.asarray(x, dtype=np.float64)
     d = x.shape[1]
@@ -93,7 +94,7 @@ def dense_layer(n, src, dst, inv, hops, x, wqkv, wo, rel_bias, heads, eps=1e-5, 
     H = np.full((n, d), np.nan)
     for v in dfs_topological(n, A):
         s = x[v].copy()
-        for W, Wo, B in zip(wqkv, wo, rel_bias):
+        for l, (W, Wo, B) in enumerate(zip(wqkv, wo, rel_bias)):
             W, Wo, B = (np.asarray(t, dtype=np.float64) for t in (W, Wo, B))
             Wq, Wk, Wv = W[:, :d], W[:, d:2 * d], W[:, 2 * d:]
             state = H.copy()
@@ -112,5 +113,8 @@ def dense_layer(n, src, dst, inv, hops, x, wqkv, wo, rel_bias, heads, eps=1e-5, 
                 a[sl] = p @ V[:, sl]
             o = a @ Wo
             s = layer_norm(s + o, eps) if epilogue else o
+            if w1 is not None:
+                hid = np.maximum(s @ np.asarray(w1[l], dtype=np.float64), 0.0)
+                s = layer_norm(s + hid @ np.asarray(w2[l], dtype=np.float64), eps)
         H[v] = s
     return H
