@@ -66,6 +66,8 @@ def _load():
         lib.orc_layer_nodes.restype = ctypes.c_int
         lib.orc_layer_nodes.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64,
                                         _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _P, _I64, _P]
+        lib.orc_ffn.restype = ctypes.c_int
+        lib.orc_ffn.argtypes = [_I64, _I32, _P, _P, _P, _F64, _I32, _P]
         lib.orc_out_degrees.restype = None
         lib.orc_out_degrees.argtypes = [_I64, _I64, _P, _P, _P, _P, _P]
         lib.orc_struct_encode.restype = None
@@ -217,6 +219,18 @@ def layer_nodes(g: Graph, x, wqkv, wo, rel_bias, heads, Hsrc, nodes, *, store="f
                                  _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B), _ptr(W1), _ptr(W2),
                                  _ptr(g.nbr_ptr), _ptr(g.nbr_idx), _ptr(g.nbr_rel),
                                  _ptr(Hsrc), _ptr(nodes), len(nodes), _ptr(out))
+    if rc:
+        raise OracleError(rc)
+    return out
+
+
+def ffn(S, w1, w2, *, ln_eps=1e-5, store="f64"):
+    """LayerNorm(S + relu(S W1) W2) row by row (reading R16). Returns float64 [rows, d]."""
+    S, w1, w2 = _c(S, np.float32), _c(w1, np.float32), _c(w2, np.float32)
+    rows, d = S.shape
+    assert w1.shape == (d, 4 * d) and w2.shape == (4 * d, d)
+    out = np.empty((rows, d), dtype=np.float64)
+    rc = _load().orc_ffn(rows, d, _ptr(S), _ptr(w1), _ptr(w2), float(ln_eps), STORE[store], _ptr(out))
     if rc:
         raise OracleError(rc)
     return out

@@ -339,6 +339,31 @@ static void layer_norm(double* t, int d, double eps)
     for (int i = 0; i < d; ++i) t[i] = (t[i] - mean) * r;
 }
 
+/* R16: s <- LN(s + max(s W1, 0) W2), W1 [d, 4d], W2 [4d, d]; u (4d) and o (d) are scratch */
+static void ffn_block(double* s, int d, const float* W1, const float* W2, double eps, double* u, double* o)
+{
+    vec_mat(s, d, W1, 4 * d, 0, 4 * d, u);
+    for (int i = 0; i < 4 * d; ++i) if (u[i] < 0.0) u[i] = 0.0;
+    vec_mat(u, 4 * d, W2, d, 0, d, o);
+    for (int i = 0; i < d; ++i) s[i] += o[i];
+    layer_norm(s, d, eps);
+}
+
+/* Kernel-level oracle of the feed-forward sub-block on given rows S [rows, d]. */
+int orc_ffn(int64_t rows, int32_t d, const float* S, const float* W1, const float* W2, double ln_eps,
+            int32_t store, double* out)
+{
+    if (d <= 0 || d > 1024) return ORC_EINVAL;
+#pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < rows; ++r) {
+        double s[1024], o[1024], u[4096];
+        for (int i = 0; i < d; ++i) s[i] = (double)S[r * d + i];
+        ffn_block(s, d, W1, W2, ln_eps, u, o);
+        for (int i = 0; i < d; ++i) out[r * d + i] = round_store(s[i], store);
+    }
+    return ORC_OK;
+}
+
 /*
  * All layers of one node v (R6, R7, R16). Source states come from Hd (double rows)
  * if non-NULL, else from Hf (float rows). kv_memo (nullable): per layer and
@@ -381,13 +406,8 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
         } else {
             for (int i = 0; i < d; ++i) s[i] = o[i];
         }
-        if (L->w1) {                                      /* R16: s <- LN(s + max(s W1, 0) W2) */
-            vec_mat(s, d, L->w1 + (int64_t)l * d * 4 * d, 4 * d, 0, 4 * d, u);
-            for (int i = 0; i < 4 * d; ++i) if (u[i] < 0.0) u[i] = 0.0;
-            vec_mat(u, 4 * d, L->w2 + (int64_t)l * 4 * d * d, d, 0, d, o);
-            for (int i = 0; i < d; ++i) s[i] += o[i];
-            layer_norm(s, d, L->ln_eps);
-        }
+        if (L->w1)
+            ffn_block(s, d, L->w1 + (int64_t)l * d * 4 * d, L->w2 + (int64_t)l * 4 * d * d, L->ln_eps, u, o);
     }
     for (int i = 0; i < d; ++i) out[i] = round_store(s[i], L->store);
     free(buf);

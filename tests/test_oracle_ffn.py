@@ -97,6 +97,30 @@ def test_zero_second_weight_leaves_a_second_layernorm():
     assert np.abs(H - want).max() < 1e-12
 
 
+def test_row_oracle_is_two_library_products_between_layernorms():
+    rng = np.random.default_rng(8)
+    d = 24
+    S = rng.standard_normal((19, d)).astype(np.float32)
+    W1 = (rng.standard_normal((d, 4 * d)) / 5).astype(np.float32)
+    W2 = (rng.standard_normal((4 * d, d)) / 10).astype(np.float32)
+    got = oracle.ffn(S, W1, W2, ln_eps=1e-3)
+    S64 = S.astype(np.float64)
+    t = S64 + np.maximum(S64 @ W1.astype(np.float64), 0.0) @ W2.astype(np.float64)
+    mu = t.mean(axis=1, keepdims=True)
+    want = (t - mu) / np.sqrt(((t - mu) ** 2).mean(axis=1, keepdims=True) + 1e-3)
+    assert np.abs(got - want).max() < 1e-12
+    # eps sits inside the root, the variance is the biased one
+    assert np.abs(got - (t - mu) / (t.std(axis=1, ddof=1, keepdims=True))).max() > 1e-3
+    # and the layer applies the same function after its attention sub-block
+    n, src, dst, inv, x, wqkv, wo, rb, g = small_problem()
+    w1, w2 = ffn_weights(x.shape[1], 1)
+    h = oracle.layer_fwd(g, x, wqkv, wo, rb, 2)
+    pis = np.nonzero(g.level == 0)[0]
+    H = oracle.layer_fwd(g, x, wqkv, wo, rb, 2, w1=w1, w2=w2)
+    # float32 rows in, so agreement to float32 rounding of h only
+    assert np.abs(oracle.ffn(h[pis], w1[0], w2[0]) - H[pis]).max() < 1e-5
+
+
 def test_ffn_needs_the_epilogue_and_both_weights():
     n, src, dst, inv, x, wqkv, wo, rb, g = small_problem()
     w1, w2 = ffn_weights(x.shape[1], 1)
