@@ -40,6 +40,14 @@ def stream_bias(layer: int) -> int:
     return 102 + 3 * layer
 
 
+def stream_w1(layer: int) -> int:
+    return 200 + 2 * layer
+
+
+def stream_w2(layer: int) -> int:
+    return 201 + 2 * layer
+
+
 @dataclass(frozen=True)
 class Config:
     name: str
@@ -149,6 +157,16 @@ def weights(cfg: Config, seed: int | None = None):
     wo = [normal(seed, stream_wo(l), (d, d), s, bf) for l in range(cfg.n_layers)]
     rb = [normal(seed, stream_bias(l), (cfg.heads, 4), 1.0, False) for l in range(cfg.n_layers)]
     return wqkv, wo, rb
+
+
+def ffn_weights(cfg: Config, seed: int | None = None):
+    """Per layer W1 [d, 4d] ~ N(0, 1/d) and W2 [4d, d] ~ N(0, 1/(4d)) of the feed-forward sub-block."""
+    seed = cfg.seed if seed is None else seed
+    bf = cfg.dtype == "bf16"
+    d = cfg.hidden
+    w1 = [normal(seed, stream_w1(l), (d, 4 * d), d ** -0.5, bf) for l in range(cfg.n_layers)]
+    w2 = [normal(seed, stream_w2(l), (4 * d, d), (4 * d) ** -0.5, bf) for l in range(cfg.n_layers)]
+    return w1, w2
 
 
 def make(cfg: Config | str, *, n_and: int | None = None, features: bool = True) -> Workload:

@@ -54,6 +54,11 @@ typedef enum {
                             /* level's frontier only (Section 3.4: memory that does not     */
                             /* grow with the graph). Level-by-level launches; same results  */
                             /* bit for bit; the projection work is repeated per reader level */
+#define DG4_FFN         8u  /* dg4_layer_fwd: every layer ends with the position-wise feed-  */
+                            /* forward sub-block of the transformer (Section 3.5 keeps the   */
+                            /* transformer structure around the attention):                  */
+                            /* s <- LayerNorm(s + max(s W1, 0) W2). Level-by-level launches.  */
+                            /* Not together with DG4_NO_EPILOGUE                             */
 
 typedef struct {
     int32_t hidden;         /* d: 128 or 256                                               */
@@ -120,6 +125,7 @@ void dg4_graph_free(dg4_graph* g);
  * level-sorted copy of H. Negative dg4_status on a bad configuration.
  */
 int64_t dg4_proj_workspace_bytes(const dg4_layer_cfg* cfg);
+int64_t dg4_ffn_workspace_bytes(const dg4_layer_cfg* cfg);
 int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4_graph* g);
 
 /*
@@ -147,6 +153,20 @@ int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int
                  void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * The position-wise feed-forward sub-block that follows the attention sub-block in the
+ * transformer layer (Section 3.5: the attention module is replaced, the rest of the transformer
+ * structure is kept), for rows [row_begin, row_end) of S:
+ *   Out[r] = LayerNorm(S[r] + max(S[r] W1, 0) W2)      (no biases, no affine, biased variance)
+ *   S, Out [n, hidden] device (rows outside the range untouched; Out may not alias S);
+ *   W1 [hidden, 4*hidden], W2 [4*hidden, hidden] device, row-major, cfg->dtype.
+ * bf16: bf16 inputs and hidden activations, fp32 accumulation and LayerNorm, bf16 output.
+ * workspace: dg4_ffn_workspace_bytes (the two weights in matrix-core operand order).
+ */
+int dg4_ffn_fwd(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                const void* W1, const void* W2, void* Out,
+                void* workspace, int64_t workspace_bytes, void* stream);
+
+/*
  * Attention restricted to the cone (Section 3.5), for destination rows
  * [row_begin, row_end): for each head h of 32 features
  *   s[u]   = <Q[v,h], K[u,h]> / sqrt(32) + rel_bias[h][rel(v,u)],  u in N(v)
@@ -172,6 +192,10 @@ int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begi
  *   must already hold the rows of all lower levels (resume).
  *   W: HOST array of 3*n_layers DEVICE pointers: Wqkv_l [hidden,3*hidden],
  *   Wo_l [hidden,hidden] (cfg->dtype), rel_bias_l float [heads,4].
+ * With DG4_FFN the layer is the whole transformer block: after the LayerNorm above,
+ *   s_{l+1} <- LayerNorm(s_{l+1} + max(s_{l+1} W1_l, 0) W2_l)   (as in dg4_ffn_fwd),
+ * and W holds 5*n_layers pointers: Wqkv_l, Wo_l, rel_bias_l, W1_l [hidden,4*hidden],
+ * W2_l [4*hidden,hidden].
  * The workspace contents are scratch; nothing persists between calls.
  */
 int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const void* const* W,

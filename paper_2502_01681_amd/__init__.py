@@ -7,4 +7,5 @@ for device memory and streams.
 from .binding import (DG4Error, Graph, LayerConfig, dg4_build_levels, dg4_layer_fwd,  # noqa: F401
                       dg4_layer_profile, dg4_sweep_elapsed_ms,
                       dg4_layer_workspace_bytes, dg4_proj_workspace_bytes, dg4_qkv_proj,
+                      dg4_ffn_fwd, dg4_ffn_workspace_bytes,
                       dg4_sparse_attn_fwd, dg4_struct_encode, lib, library_path)

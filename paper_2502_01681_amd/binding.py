@@ -17,6 +17,7 @@ DG4_F32, DG4_BF16 = 0, 1
 DG4_NO_EPILOGUE = 1
 DG4_PER_LEVEL = 2
 DG4_BOUNDED_KV = 4
+DG4_FFN = 8
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
           "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8),
           "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64),
@@ -48,12 +49,13 @@ class LayerConfig:
     ln_eps: float = 1e-5
     per_level: bool = False      # launch level by level instead of the persistent sweep kernel
     bounded_kv: bool = False     # no K|V store: one level's frontier is projected when the level is processed
+    ffn: bool = False            # every layer ends with the feed-forward sub-block (weights W1, W2 per layer)
 
     def c(self) -> _Cfg:
         return _Cfg(self.hidden, self.heads, self.hops, self.n_layers,
                     DG4_F32 if self.dtype == "f32" else DG4_BF16,
                     (0 if self.epilogue else DG4_NO_EPILOGUE) | (DG4_PER_LEVEL if self.per_level else 0) |
-                    (DG4_BOUNDED_KV if self.bounded_kv else 0), self.ln_eps)
+                    (DG4_BOUNDED_KV if self.bounded_kv else 0) | (DG4_FFN if self.ffn else 0), self.ln_eps)
 
 
 _lib = None
@@ -86,6 +88,10 @@ def lib():
         L.dg4_proj_workspace_bytes.restype = _I64
         L.dg4_proj_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
         L.dg4_layer_workspace_bytes.restype = _I64
+        L.dg4_ffn_workspace_bytes.restype = _I64
+        L.dg4_ffn_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg)]
+        L.dg4_ffn_fwd.restype = ctypes.c_int
+        L.dg4_ffn_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _I64, _P]
         L.dg4_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), _P]
         L.dg4_qkv_proj.restype = ctypes.c_int
         L.dg4_qkv_proj.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _I64, _P]
@@ -170,6 +176,14 @@ def dg4_proj_workspace_bytes(cfg: LayerConfig) -> int:
     return int(r)
 
 
+def dg4_ffn_workspace_bytes(cfg: LayerConfig) -> int:
+    c = cfg.c()
+    r = lib().dg4_ffn_workspace_bytes(ctypes.byref(c))
+    if r < 0:
+        raise DG4Error(int(r), "dg4_ffn_workspace_bytes")
+    return int(r)
+
+
 def dg4_layer_workspace_bytes(cfg: LayerConfig, g: Graph) -> int:
     c = cfg.c()
     r = lib().dg4_layer_workspace_bytes(ctypes.byref(c), g.handle)
@@ -198,6 +212,16 @@ def dg4_qkv_proj(cfg: LayerConfig, S, Wqkv, Q, K, V, row_begin=0, row_end=None, 
     _check(rc, "dg4_qkv_proj")
 
 
+def dg4_ffn_fwd(cfg: LayerConfig, S, W1, W2, Out, row_begin=0, row_end=None, workspace=None):
+    """Out rows [row_begin,row_end) = LayerNorm(S + relu(S W1) W2) (device tensors, Out in place)."""
+    row_end = S.shape[0] if row_end is None else row_end
+    ws = _ws(dg4_ffn_workspace_bytes(cfg), S) if workspace is None else workspace
+    c = cfg.c()
+    rc = lib().dg4_ffn_fwd(ctypes.byref(c), S.data_ptr(), row_begin, row_end, W1.data_ptr(), W2.data_ptr(),
+                           Out.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
+    _check(rc, "dg4_ffn_fwd")
+
+
 def dg4_struct_encode(cfg: LayerConfig, g: Graph, X, emb, Xout):
     """Xout = X + structural encoding (level, OutAND, OutNOT through three linear layers); emb float [6, hidden]."""
     c = cfg.c()
@@ -214,7 +238,9 @@ def dg4_sparse_attn_fwd(cfg: LayerConfig, g: Graph, Q, K, V, rel_bias, A, row_be
 
 
 def dg4_layer_fwd(cfg: LayerConfig, g: Graph, X, weights, Hout, level_begin=0, level_end=None, workspace=None):
-    """weights: per layer (Wqkv, Wo, rel_bias) device tensors. Hout is written in place."""
+    """weights: per layer (Wqkv, Wo, rel_bias) device tensors, or (Wqkv, Wo, rel_bias, W1, W2) with
+    cfg.ffn. Hout is written in place."""
+    assert all(len(layer) == (5 if cfg.ffn else 3) for layer in weights) and len(weights) == cfg.n_layers
     level_end = g.n_levels if level_end is None else level_end
     ws = _ws(dg4_layer_workspace_bytes(cfg, g), X) if workspace is None else workspace
     flat = [t.data_ptr() for layer in weights for t in layer]

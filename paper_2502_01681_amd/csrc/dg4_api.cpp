@@ -16,7 +16,8 @@ int check_cfg(const dg4_layer_cfg* c, bool need_layers)
 {
     if (!c) return DG4_EINVAL;
     if (c->dtype != DG4_F32 && c->dtype != DG4_BF16) return DG4_EINVAL;
-    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL | DG4_BOUNDED_KV)) return DG4_EINVAL;
+    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL | DG4_BOUNDED_KV | DG4_FFN)) return DG4_EINVAL;
+    if ((c->flags & DG4_FFN) && (c->flags & DG4_NO_EPILOGUE)) return DG4_EINVAL;
     if (c->hidden != 128 && c->hidden != 256) return DG4_EUNSUPPORTED;
     if (c->heads <= 0 || c->heads * 32 != c->hidden) return DG4_EUNSUPPORTED;
     if (c->hops < 1 || c->hops > 3) return DG4_EUNSUPPORTED;
@@ -28,6 +29,8 @@ int check_cfg(const dg4_layer_cfg* c, bool need_layers)
 // Workspace of dg4_layer_fwd, in bytes from the (256-byte aligned) base.
 struct LayerPlan {
     size_t wqkv[DG4_MAX_LAYERS], wo[DG4_MAX_LAYERS];
+    size_t w1[DG4_MAX_LAYERS], w2[DG4_MAX_LAYERS];   // feed-forward weights, packed (DG4_FFN)
+    size_t h1;           // [max_level_rows, d] state after the attention sub-block (DG4_FFN)
     size_t wkv_all;      // packed [d, n_layers*2d]: K|V columns of every layer
     size_t qkv_self;     // [n, 3d]  Q | K | V of x, level-sorted rows (layer 0)
     size_t kv;           // [n_layers, kv_rows, 2d]  K | V of the final embeddings, level-sorted
@@ -54,6 +57,8 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
     for (size_t l = 0; l < L; ++l) { p.wqkv[l] = take(d * 3 * d * es); p.wo[l] = take(d * d * es); }
+    const bool ffn = (c->flags & DG4_FFN) != 0;
+    for (size_t l = 0; l < L; ++l) { p.w1[l] = take(ffn ? d * 4 * d * es : 0); p.w2[l] = take(ffn ? 4 * d * d * es : 0); }
     p.wkv_all = take(d * 2 * d * L * es);
     p.qkv_self = take((c->flags & DG4_BOUNDED_KV) ? 0 : n * 3 * d * es);
     // K | V rows: of every finished gate, or (DG4_BOUNDED_KV) of one level's frontier only
@@ -64,6 +69,7 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     p.abuf = take((size_t)mr * d * es);
     p.s0 = take((size_t)mr * d * es);
     p.s1 = take((size_t)mr * d * es);
+    p.h1 = take(ffn ? (size_t)mr * d * es : 0);
     p.qkv_level = take(L > 1 || bounded ? (size_t)mr * 3 * d * es : 0);
     p.wo_t = take(d * d * es);
     p.wkv_t = take(d * 2 * d * es);
@@ -112,6 +118,13 @@ extern "C" int64_t dg4_proj_workspace_bytes(const dg4_layer_cfg* cfg)
     return (int64_t)align256((size_t)cfg->hidden * 3 * cfg->hidden * elt_size(cfg->dtype));
 }
 
+extern "C" int64_t dg4_ffn_workspace_bytes(const dg4_layer_cfg* cfg)
+{
+    const int rc = check_cfg(cfg, false);
+    if (rc != DG4_OK) return rc;
+    return (int64_t)(2 * align256((size_t)cfg->hidden * 4 * cfg->hidden * elt_size(cfg->dtype)));
+}
+
 extern "C" int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4_graph* g)
 {
     const int rc = check_cfg(cfg, true);
@@ -155,6 +168,31 @@ extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row
     a.out[0] = Q; a.out[1] = K; a.out[2] = V; a.out_stride = d;
     a.row_begin = row_begin; a.row_end = row_end;
     HIPCHK(dg4_launch_gemm(cfg->dtype, d, a, s));
+    return DG4_OK;
+}
+
+extern "C" int dg4_ffn_fwd(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                           const void* W1, const void* W2, void* Out,
+                           void* workspace, int64_t workspace_bytes, void* stream)
+{
+    int rc = check_cfg(cfg, false);
+    if (rc != DG4_OK) return rc;
+    if (!S || !W1 || !W2 || !Out || row_begin < 0 || row_end < row_begin) return DG4_EINVAL;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < dg4_ffn_workspace_bytes(cfg)) return DG4_EWORKSPACE;
+    if (row_end == row_begin) return DG4_OK;
+    hipStream_t s = (hipStream_t)stream;
+    const int d = cfg->hidden;
+    char* w1p = (char*)workspace;
+    char* w2p = w1p + align256((size_t)d * 4 * d * elt_size(cfg->dtype));
+    HIPCHK(dg4_launch_pack_w(cfg->dtype, W1, 4 * d, 0, 4 * d, d, w1p, s));
+    HIPCHK(dg4_launch_pack_w2(cfg->dtype, W2, d, w2p, s));
+    dg4_ffn_args f{};
+    f.h = S; f.h_stride = d;
+    f.w1_packed = w1p; f.w2_packed = w2p;
+    f.out = Out; f.out_stride = d;
+    f.row_begin = row_begin; f.row_end = row_end;
+    f.ln_eps = cfg->ln_eps;
+    HIPCHK(dg4_launch_ffn(cfg->dtype, d, f, s));
     return DG4_OK;
 }
 
@@ -206,7 +244,9 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     const int32_t n_levels = g->max_level + 1;
     if (level_begin < 0 || level_end < level_begin || level_end > n_levels) return DG4_EINVAL;
     const int L = cfg->n_layers;
-    for (int i = 0; i < 3 * L; ++i) if (!W[i]) return DG4_EINVAL;
+    const bool ffn = (cfg->flags & DG4_FFN) != 0;
+    const int WS = ffn ? 5 : 3;                      // weight pointers per layer
+    for (int i = 0; i < WS * L; ++i) if (!W[i]) return DG4_EINVAL;
     const bool bounded = (cfg->flags & DG4_BOUNDED_KV) != 0;
     if (bounded) {
         rc = dg4_graph_ensure_device(g);
@@ -229,10 +269,14 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     auto local = [&](size_t off, int64_t p0, int64_t stride) { return (void*)(ws + off - p0 * stride * es); };
 
     for (int l = 0; l < L; ++l) {
-        HIPCHK(dg4_launch_pack_w(dt, W[3 * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
-        HIPCHK(dg4_launch_pack_w(dt, W[3 * l + 1], d, 0, d, d, at(pl.wo[l]), s));
+        HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
+        HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 1], d, 0, d, d, at(pl.wo[l]), s));
         // K | V columns of layer l go to column tiles [l*2d/32, (l+1)*2d/32) of wkv_all
-        HIPCHK(dg4_launch_pack_w(dt, W[3 * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
+        HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
+        if (ffn) {
+            HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 3], 4 * d, 0, 4 * d, d, at(pl.w1[l]), s));
+            HIPCHK(dg4_launch_pack_w2(dt, W[WS * l + 4], d, at(pl.w2[l]), s));
+        }
     }
     const int64_t P0 = g->level_ptr[level_begin], P1 = g->level_ptr[level_end];
 
@@ -253,7 +297,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     if (P0 > 0 && !bounded) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
     // One persistent dataflow kernel for the whole range of levels
-    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV))) {
+    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV | DG4_FFN))) {
         // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
         // level by level; rows of the internal buffers are positions in the order in use.
         const bool whole = level_begin == 0 && level_end == (int32_t)g->max_level + 1 && !getenv("DG4_SWEEP_LEVEL_ORDER");
@@ -341,13 +385,14 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             t.q_stride = 3 * d; t.self_stride = 3 * d;
             char* kvb = ws + pl.kv + (size_t)l * pl.kv_rows * 2 * d * es;
             t.k_src = kvb; t.v_src = kvb + (size_t)d * es; t.src_stride = 2 * d;
-            t.rel_bias = (const float*)W[3 * l + 2];
+            t.rel_bias = (const float*)W[WS * l + 2];
             t.ell = bounded ? g->d_ell_front : g->d_ell_pos; t.ell_w = g->ell_w;
             t.a = local(pl.abuf, p0, d); t.a_stride = d;
             t.row_begin = p0; t.row_end = p1;
             HIPCHK(dg4_launch_attn(dt, d, t, s));
 
-            // s_{l+1} = LN(s_l + a Wo_l); the last layer's result is H
+            // s_{l+1} = LN(s_l + a Wo_l), then (DG4_FFN) s_{l+1} <- LN(s_{l+1} + relu(s_{l+1} W1_l) W2_l);
+            // the last layer's result is H
             dg4_gemm_args o{};
             o.a = local(pl.abuf, p0, d); o.a_stride = d;
             o.w_packed = at(pl.wo[l]); o.n_cols = d;
@@ -355,13 +400,29 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             o.epilogue = epi ? 1 : 0; o.ln_eps = cfg->ln_eps;
             if (l == 0) { o.resid = X; o.resid_stride = d; o.resid_gather = g->d_order; }
             else { o.resid = local((l & 1) ? pl.s1 : pl.s0, p0, d); o.resid_stride = d; }
-            if (last) {
+            void* next = local(((l + 1) & 1) ? pl.s1 : pl.s0, p0, d);
+            if (ffn) {
+                o.out[0] = local(pl.h1, p0, d); o.out_stride = d;
+            } else if (last) {
                 o.out[0] = Hout; o.out_stride = d; o.out_scatter = g->d_order;
                 if (!bounded) { o.out2 = at(pl.hpos); o.out2_stride = d; }
             } else {
-                o.out[0] = local(((l + 1) & 1) ? pl.s1 : pl.s0, p0, d); o.out_stride = d;
+                o.out[0] = next; o.out_stride = d;
             }
             HIPCHK(dg4_launch_gemm(dt, d, o, s));
+            if (ffn) {
+                dg4_ffn_args f{};
+                f.h = local(pl.h1, p0, d); f.h_stride = d;
+                f.w1_packed = at(pl.w1[l]); f.w2_packed = at(pl.w2[l]);
+                f.row_begin = p0; f.row_end = p1; f.ln_eps = cfg->ln_eps;
+                if (last) {
+                    f.out = Hout; f.out_stride = d; f.out_scatter = g->d_order;
+                    if (!bounded) { f.out2 = at(pl.hpos); f.out2_stride = d; }
+                } else {
+                    f.out = next; f.out_stride = d;
+                }
+                HIPCHK(dg4_launch_ffn(dt, d, f, s));
+            }
 
             if (!last) {
                 dg4_gemm_args a{};

@@ -105,6 +105,20 @@ struct dg4_gemm_args {
 };
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s);
 
+// Feed-forward sub-block: out = LN(h + max(h W1, 0) W2) for rows [row_begin, row_end).
+struct dg4_ffn_args {
+    const void* h; int64_t h_stride;        // input rows, row r at h + r*h_stride
+    const void* w1_packed;                  // W1 [hidden, 4*hidden] in dg4_launch_pack_w order
+    const void* w2_packed;                  // W2 [4*hidden, hidden] in dg4_launch_pack_w2 order
+    void* out; int64_t out_stride;          // row r goes to out + oidx(r)*out_stride
+    const int32_t* out_scatter;             // nullable: oidx(r) = out_scatter[r], else r
+    void* out2; int64_t out2_stride;        // nullable second copy, indexed by r
+    int64_t row_begin, row_end;
+    float ln_eps;
+};
+int dg4_launch_pack_w2(int dtype, const void* w2, int hidden, void* packed, hipStream_t s);
+int dg4_launch_ffn(int dtype, int hidden, const dg4_ffn_args& a, hipStream_t s);
+
 // ---- persistent sweep (dg4_sweep.hip): bf16, hidden 256, one layer ----
 struct dg4_sweep_args {
     const uint2* tiles; int64_t tile_begin; int64_t n_tiles;   // tile t of the sweep is tiles[tile_begin + t]

@@ -8,6 +8,10 @@
 //  pack_w_kernel re-tiles a row-major weight into MFMA B-operand order.
 //  gemm_kernel   rows x packed weight on the matrix cores (the dense
 //                projections), optionally fused with residual + LayerNorm.
+//  ffn_kernel    the position-wise feed-forward sub-block of the transformer
+//                layer (Section 3.5), both products, rectifier, residual and
+//                LayerNorm in one pass; the 4d hidden activations never leave
+//                the registers.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -309,6 +313,170 @@ int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
     return hipGetLastError();
 }
 
+// ------------------------------------------------------------ feed-forward
+
+// W2 [4d, d] in the order the second product of ffn_kernel consumes it. The first product
+// leaves, in accumulator element i of lane (m, kg), the activation of hidden unit
+// 32*hc + 8*(i/4) + 4*kg + i%4 for row m; E consecutive elements (i = q*E .. q*E+E-1) form one
+// A operand. 16-byte unit (((hc*G + q)*NT + nt)*64 + lane) holds the E matching rows of W2 for
+// column nt*32 + lane%32, G = 16/E groups per 32 hidden units.
+template <typename T>
+__global__ void pack_w2_kernel(const T* w2, int d, T* packed)
+{
+    constexpr int E = 16 / sizeof(T);
+    constexpr int G = 16 / E;
+    const int NT = d / 32;
+    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t units = (int64_t)(4 * d / 32) * G * NT * 64;
+    if (unit >= units) return;
+    const int lane = (int)(unit & 63);
+    int64_t t = unit >> 6;
+    const int nt = (int)(t % NT); t /= NT;
+    const int q = (int)(t % G);
+    const int hc = (int)(t / G);
+    const int n = nt * 32 + (lane & 31), kg = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+        const int i = q * E + j;
+        const int hidden = 32 * hc + 8 * (i / 4) + 4 * kg + (i % 4);
+        packed[unit * E + j] = w2[(int64_t)hidden * d + n];
+    }
+}
+
+template <typename T> struct Act;
+template <> struct Act<bf16_t> {      // 16 activations -> two bf16 A operands
+    __device__ static void pack(const f32x16& u, uint4* a)
+    {
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            a[q] = make_uint4(pack_bf16x2(u[8 * q], u[8 * q + 1]), pack_bf16x2(u[8 * q + 2], u[8 * q + 3]),
+                              pack_bf16x2(u[8 * q + 4], u[8 * q + 5]), pack_bf16x2(u[8 * q + 6], u[8 * q + 7]));
+    }
+};
+template <> struct Act<float> {       // 16 activations -> four groups of four fp32 A operands
+    __device__ static void pack(const f32x16& u, uint4* a)
+    {
+#pragma unroll
+        for (int q = 0; q < 4; ++q)
+            a[q] = make_uint4(__float_as_uint(u[4 * q]), __float_as_uint(u[4 * q + 1]),
+                              __float_as_uint(u[4 * q + 2]), __float_as_uint(u[4 * q + 3]));
+    }
+};
+
+// out = LN(h + max(h W1, 0) W2) for 32 rows per workgroup. The four waves split the 4d hidden
+// units; each computes its slice of the activations TRANSPOSED (W1 tile as the A operand, the
+// rows of h as B), so that the accumulator of the first product is, element for element, the A
+// operand of the second (with W2 packed to match) and nothing moves between lanes. The four
+// partial results are summed through LDS in a fixed order: (w0 + w2) + (w1 + w3).
+template <typename T, int D>
+__global__ __launch_bounds__(256) void ffn_kernel(dg4_ffn_args p)
+{
+    constexpr int E = 16 / sizeof(T);
+    constexpr int KC = D / (2 * E);
+    constexpr int NT = D / 32;
+    constexpr int G = 16 / E;
+    constexpr int CPW = D / 32;                 // chunks of 32 hidden units per wave (4d / 32 / 4)
+    __shared__ float red[2][NT * 16 * 64];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int m = lane & 31, kg = lane >> 5;
+    const int64_t r0 = p.row_begin + (int64_t)blockIdx.x * 32;
+
+    uint4 a[KC];
+    {
+        int64_t r = r0 + m;
+        if (r >= p.row_end) r = p.row_end - 1;          // clamp: loads stay in bounds, stores are masked
+        const uint4* ap = (const uint4*)((const T*)p.h + r * p.h_stride);
+#pragma unroll
+        for (int c = 0; c < KC; ++c) a[c] = ap[2 * c + kg];
+    }
+    f32x16 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+
+    const uint4* w1p = (const uint4*)p.w1_packed + lane;
+    const uint4* w2p = (const uint4*)p.w2_packed + lane;
+#pragma unroll 2
+    for (int ch = 0; ch < CPW; ++ch) {
+        const int64_t hc = wave * CPW + ch;
+        f32x16 u;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) u[i] = 0.f;
+#pragma unroll
+        for (int c = 0; c < KC; ++c) Mma<T>::run(w1p[(hc * KC + c) * 64], a[c], u);
+#pragma unroll
+        for (int i = 0; i < 16; ++i) u[i] = fmaxf(u[i], 0.f);
+        uint4 ua[G];
+        Act<T>::pack(u, ua);
+#pragma unroll
+        for (int q = 0; q < G; ++q)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) Mma<T>::run(ua[q], w2p[((hc * G + q) * NT + nt) * 64], acc[nt]);
+    }
+
+    if (wave >= 2) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[wave - 2][(nt * 16 + i) * 64 + lane] = acc[nt][i];
+    }
+    __syncthreads();
+    if (wave < 2) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[nt][i] += red[wave][(nt * 16 + i) * 64 + lane];
+    }
+    __syncthreads();
+    if (wave == 1) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) red[0][(nt * 16 + i) * 64 + lane] = acc[nt][i];
+    }
+    __syncthreads();
+    if (wave != 0) return;
+
+    // wave 0: total, residual, LayerNorm (no affine, biased variance), store
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        int64_t r = r0 + 8 * (i / 4) + 4 * kg + (i % 4);
+        const bool ok = r < p.row_end;
+        if (!ok) r = p.row_end - 1;
+        float s1 = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            acc[nt][i] += red[0][(nt * 16 + i) * 64 + lane];
+            acc[nt][i] += Elem<T>::load1(p.h, r * p.h_stride + nt * 32 + m);
+            s1 += acc[nt][i];
+        }
+        const float mean = sum_over_32_lanes(s1) * (1.0f / D);
+        float s2 = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) { const float t = acc[nt][i] - mean; s2 = fmaf(t, t, s2); }
+        const float rstd = rsqrtf(sum_over_32_lanes(s2) * (1.0f / D) + p.ln_eps);
+        if (!ok) continue;
+        const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[r] : r;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const float y = (acc[nt][i] - mean) * rstd;
+            Elem<T>::store1(p.out, orr * p.out_stride + nt * 32 + m, y);
+            if (p.out2) Elem<T>::store1(p.out2, r * p.out2_stride + nt * 32 + m, y);
+        }
+    }
+}
+
+template <typename T, int D>
+int launch_ffn_t(const dg4_ffn_args& a, hipStream_t s)
+{
+    const int64_t rows = a.row_end - a.row_begin;
+    if (rows <= 0) return hipSuccess;
+    hipLaunchKernelGGL((ffn_kernel<T, D>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
+    return hipGetLastError();
+}
+
 // Structural encoding (paper Section 3.5, Eq. 2): out[v] = x[v] + (level*w_l + b_l) + (OutAND*w_and +
 // b_and) + (OutNOT*w_not + b_not). Elementwise and HBM-bound (a row in, a row out, 12 bytes of
 // integer features): one thread per 16 bytes of a row, the [6, d] embedding table comes from cache.
@@ -387,6 +555,24 @@ int dg4_launch_pack_w(int dtype, const void* w, int ld, int col0, int n_cols, in
     else
         hipLaunchKernelGGL(pack_w_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t*)w, ld, col0, n_cols, k_dim, (uint16_t*)packed);
     return hipGetLastError();
+}
+
+int dg4_launch_pack_w2(int dtype, const void* w2, int hidden, void* packed, hipStream_t s)
+{
+    const int e = dtype == DG4_F32 ? 4 : 8;
+    const int64_t units = (int64_t)(4 * hidden / 32) * (16 / e) * (hidden / 32) * 64;
+    const unsigned grid = (unsigned)((units + 255) / 256);
+    if (dtype == DG4_F32)
+        hipLaunchKernelGGL(pack_w2_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)w2, hidden, (float*)packed);
+    else
+        hipLaunchKernelGGL(pack_w2_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t*)w2, hidden, (uint16_t*)packed);
+    return hipGetLastError();
+}
+
+int dg4_launch_ffn(int dtype, int hidden, const dg4_ffn_args& a, hipStream_t s)
+{
+    if (dtype == DG4_F32) return hidden == 128 ? launch_ffn_t<float, 128>(a, s) : launch_ffn_t<float, 256>(a, s);
+    return hidden == 128 ? launch_ffn_t<bf16_t, 128>(a, s) : launch_ffn_t<bf16_t, 256>(a, s);
 }
 
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s)

@@ -214,6 +214,65 @@ def test_struct_encode(name, n_and, dtype, hidden):
     assert torch.equal(X, out)
 
 
+@pytest.mark.parametrize("dtype,d,rows,lo,hi", [
+    ("f32", 128, 500, 0, 500), ("f32", 128, 77, 3, 70), ("f32", 256, 65, 0, 65),
+    ("bf16", 256, 1000, 0, 1000), ("bf16", 256, 257, 1, 256), ("bf16", 128, 95, 0, 95),
+    ("bf16", 256, 31, 0, 31), ("bf16", 256, 40, 10, 10),
+])
+def test_ffn_fwd(dtype, d, rows, lo, hi):
+    print(f"ffn_fwd {dtype} d={d} rows={rows} [{lo},{hi})", flush=True)
+    bf = dtype == "bf16"
+    S = synth.normal(23, 4, (rows, d), 1.0, bf)
+    W1 = synth.normal(23, 200, (d, 4 * d), d ** -0.5, bf)
+    W2 = synth.normal(23, 201, (4 * d, d), (4 * d) ** -0.5, bf)
+    cfg = dg4.LayerConfig(d, d // 32, 2, 1, dtype)
+    out = torch.full((rows, d), 7.0, dtype=tdtype(dtype), device="cuda")
+    dg4.dg4_ffn_fwd(cfg, to_dev(S, dtype), to_dev(W1, dtype), to_dev(W2, dtype), out, row_begin=lo, row_end=hi)
+    torch.cuda.synchronize()
+    got = to_np(out)
+    assert (got[:lo] == 7.0).all() and (got[hi:] == 7.0).all()          # rows outside the range untouched
+    if hi > lo:
+        ref = oracle.ffn(S, W1, W2, store=dtype)
+        err = row_rel_err(got[lo:hi], ref[lo:hi])
+        print(f"  max rel err {err.max():.3e}", flush=True)
+        assert err.max() <= TOL[dtype], err.max()
+
+
+@pytest.mark.parametrize("name,n_and,kw", [
+    ("tiny", None, {}), ("small", None, {}), ("tiny", None, dict(n_layers=3, hops=3)),
+    ("large", 30_000, {}), ("stress", 20_000, {}), ("stress", 20_000, dict(bounded_kv=True)),
+    ("medium", 20_000, dict(dtype="f32")),
+])
+def test_layer_fwd_with_feed_forward(name, n_and, kw):
+    """The whole transformer block per layer: attention sub-block, then LN(h + relu(h W1) W2)."""
+    print(f"layer_fwd ffn {name} n_and={n_and} {kw}", flush=True)
+    base = synth.CONFIGS[name]
+    over = {k: v for k, v in kw.items() if k in ("hops", "n_layers", "dtype")}
+    c = synth.Config(**{**base.__dict__, **over, **({"n_and": n_and} if n_and else {})})
+    w = synth.make(c)
+    w1, w2 = synth.ffn_weights(c)
+    cfg = cfg_of(c, ffn=True, bounded_kv=kw.get("bounded_kv", False))
+    g, og = graphs(w)
+    X = to_dev(w.x, c.dtype)
+    W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(device_weights(w, c.dtype))]
+    Hd = torch.full((c.n_nodes, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+    dg4.dg4_layer_fwd(cfg, g, X, W, Hd)
+    torch.cuda.synchronize()
+    H = to_np(Hd)
+    assert not np.isnan(H).any()
+    ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype, w1=w1, w2=w2)
+    err = row_rel_err(H, ref)
+    print(f"  max rel err {err.max():.3e}  p99.9 {np.quantile(err, 0.999):.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype], err.max()
+    rng = np.random.default_rng(0)
+    nodes = rng.choice(c.n_nodes, size=min(c.n_nodes, 2000), replace=False)
+    step = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, H, nodes, store=c.dtype, w1=w1, w2=w2)
+    assert row_rel_err(H[nodes], step).max() <= TOL[c.dtype]
+    # and it is not the layer without the sub-block
+    plain = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, H, nodes[:50], store=c.dtype)
+    assert row_rel_err(H[nodes[:50]], plain).min() > 10 * TOL[c.dtype]
+
+
 def test_workspace_reuse_with_new_inputs():
     # the same workspace and output buffer, different features: nothing stale may be read
     print("layer_fwd workspace reuse", flush=True)
