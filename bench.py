@@ -228,7 +228,24 @@ def main():
         bytes_s = n_gates * (2 * R + 12)                       # a row in, a row out, three integers
         out["kernel_points"]["dg4_struct_encode"] = {"ms": ms_s, "GB/s": bytes_s / (ms_s * 1e-3) / 1e9,
                                                      "hbm_frac": bytes_s / (ms_s * 1e-3) / 1e9 / HBM_PEAK_GBPS}
-        del Q, K, V, A
+        # the feed-forward sub-block over all rows: 16 d^2 flop per row against 2 rows of traffic, MFMA-bound
+        fws = torch.empty(dg4.dg4_ffn_workspace_bytes(cfg), dtype=torch.uint8, device="cuda")
+        W1, W2 = (torch.from_numpy(t[0]).cuda().to(td).contiguous() for t in synth.ffn_weights(c))
+        ms_f = timed(lambda: dg4.dg4_ffn_fwd(cfg, X, W1, W2, A, workspace=fws))
+        flop_f = 16.0 * n_gates * c.hidden * c.hidden
+        out["kernel_points"]["dg4_ffn_fwd"] = {"ms": ms_f, "TFLOP/s": flop_f / (ms_f * 1e-3) / 1e12,
+                                               "mfma_frac": flop_f / (ms_f * 1e-3) / peak_flops,
+                                               "GB/s": n_gates * 2 * R / (ms_f * 1e-3) / 1e9}
+        # the layer with the feed-forward sub-block after the attention sub-block (level-by-level launches)
+        fcfg = dg4.LayerConfig(c.hidden, c.heads, c.hops, c.n_layers, c.dtype, ffn=True)
+        fw1, fw2 = synth.ffn_weights(c)
+        FW = [W[l] + (torch.from_numpy(fw1[l]).cuda().to(td).contiguous(), torch.from_numpy(fw2[l]).cuda().to(td).contiguous())
+              for l in range(c.n_layers)]
+        fwsl = torch.empty(dg4.dg4_layer_workspace_bytes(fcfg, g), dtype=torch.uint8, device="cuda")
+        ms_l = timed(lambda: dg4.dg4_layer_fwd(fcfg, g, X, FW, A, workspace=fwsl), reps=3)
+        out["ffn_layer"] = {"step_ms_device": ms_l, "edges_per_s": nnz * layers / (ms_l * 1e-3),
+                            "gates_per_s": n_gates * layers / (ms_l * 1e-3)}
+        del Q, K, V, A, fwsl
 
     if not args.no_cpu_baseline:
         import oracle

@@ -57,7 +57,7 @@ typedef enum {
 #define DG4_FFN         8u  /* dg4_layer_fwd: every layer ends with the position-wise feed-  */
                             /* forward sub-block of the transformer (Section 3.5 keeps the   */
                             /* transformer structure around the attention):                  */
-                            /* s <- LayerNorm(s + max(s W1, 0) W2). Level-by-level launches.  */
+                            /* s <- LayerNorm(s + max(s W1, 0) W2).                          */
                             /* Not together with DG4_NO_EPILOGUE                             */
 
 typedef struct {

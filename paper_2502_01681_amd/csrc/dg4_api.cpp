@@ -40,6 +40,7 @@ struct LayerPlan {
     size_t s0, s1;       // [max_level_rows, d] running state between layers
     size_t qkv_level;    // [max_level_rows, 3d] (layers >= 1)
     size_t wo_t, wkv_t;  // persistent sweep: weights in its A-operand order (layer 0)
+    size_t ffn_t;        // persistent sweep: W1 | W2 in its streaming order (DG4_FFN)
     size_t flags;        // [n] uint32 "rows published"
     size_t ctrl;         // abort flag, phase timers
     size_t total;
@@ -73,6 +74,7 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     p.qkv_level = take(L > 1 || bounded ? (size_t)mr * 3 * d * es : 0);
     p.wo_t = take(d * d * es);
     p.wkv_t = take(d * 2 * d * es);
+    p.ffn_t = take(ffn ? 2 * d * 4 * d * es : 0);
     p.flags = take(n * sizeof(uint32_t));
     p.ctrl = take(256);
     p.total = off;
@@ -297,7 +299,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     if (P0 > 0 && !bounded) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
     // One persistent dataflow kernel for the whole range of levels
-    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV | DG4_FFN))) {
+    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV))) {
         // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
         // level by level; rows of the internal buffers are positions in the order in use.
         const bool whole = level_begin == 0 && level_end == (int32_t)g->max_level + 1 && !getenv("DG4_SWEEP_LEVEL_ORDER");
@@ -325,6 +327,10 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.h_out = (uint16_t*)Hout;
         a.wo_packed = at(pl.wo_t); a.wkv_packed = at(pl.wkv_t);
         a.rel_bias = (const float*)W[2];
+        if (ffn) {
+            HIPCHK(dg4_launch_pack_ffn(W[3], W[4], at(pl.ffn_t), s));
+            a.ffn_packed = at(pl.ffn_t);
+        }
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
         a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.eager_publish = whole ? 0 : 1;
         a.spin_limit = dg4_sweep_spin_limit();

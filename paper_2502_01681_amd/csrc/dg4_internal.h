@@ -129,6 +129,7 @@ struct dg4_sweep_args {
     uint16_t* kv;                          // [n, 512] by position: K | V of the final embeddings
     uint16_t* h_out;                       // [n, 256] by node id
     const void* wo_packed; const void* wkv_packed;   // pack_wt order
+    const void* ffn_packed;                // nullable: W1 | W2 of the feed-forward sub-block, dg4_launch_pack_ffn order (1 MB)
     const float* rel_bias;
     uint32_t* flags;                       // [n] by position: 1 = rows published
     uint32_t* ctrl;                        // [1] abort flag, [16..31] phase timers
@@ -138,6 +139,7 @@ struct dg4_sweep_args {
     uint32_t spin_limit;
 };
 int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void* packed, hipStream_t s);
+int dg4_launch_pack_ffn(const void* w1, const void* w2, void* packed, hipStream_t s);   // [256,1024], [1024,256] bf16
 int dg4_launch_sweep_init(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, hipStream_t s);
 int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s);
 

@@ -29,6 +29,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "dg4_device.h"
 #include "dg4_internal.h"
 
@@ -127,6 +129,50 @@ __global__ void pack_wt_kernel(const uint16_t* w, int ld, int col0, int ntw, int
     for (int j = 0; j < 8; ++j) packed[unit * 8 + j] = w[(int64_t)(k0 + j) * ld + col];
 }
 
+// The feed-forward weights in the order the sweep streams them (16-byte units). A tile's
+// sub-block runs in FFN_PASSES passes of 256 hidden units; in a pass wave w first forms the
+// activations of its 64 hidden units (A operand: a 16 x 32 piece of W1 transposed, hidden unit
+// 256*pass + 64*w + 16*ht + m against inputs 32*ks + 8*g .. +7; fragment 4*ks + ht), then adds
+// the pass's contribution to its 64 output columns (A operand: a piece of W2 transposed, output
+// column 64*w + 16*(m/4) + 4*ct + m%4, the same column ownership as the output projection,
+// against hidden units 256*pass + 32*kk + 8*g .. +7; fragment 32 + 4*kk + ct). Unit
+// (((w*FFN_PASSES + pass)*64 + fragment)*64 + lane), lane = 16*g + m: one contiguous stream per wave.
+constexpr int FFN_PASSES = 4;
+constexpr int FFN_FRAGS = 64;         // fragments (1 KB each) per wave and pass
+__global__ void pack_ffn_kernel(const uint16_t* w1, const uint16_t* w2, uint16_t* packed)
+{
+    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (unit >= 4 * FFN_PASSES * FFN_FRAGS * 64) return;
+    const int lane = (int)(unit & 63);
+    const int j = (int)((unit >> 6) % FFN_FRAGS);
+    const int pass = (int)((unit >> 12) % FFN_PASSES);
+    const int w = (int)(unit >> 14);
+    const int m = lane & 15, g = lane >> 4;
+    if (j < 32) {
+        const int ks = j >> 2, ht = j & 3;
+        const int hidden = 256 * pass + 64 * w + 16 * ht + m;
+        const int k0 = 32 * ks + 8 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) packed[unit * 8 + e] = w1[(int64_t)(k0 + e) * (4 * D) + hidden];
+    } else {
+        const int kk = (j - 32) >> 2, ct = (j - 32) & 3;
+        const int col = 64 * w + 16 * (m >> 2) + 4 * ct + (m & 3);
+        const int h0 = 256 * pass + 32 * kk + 8 * g;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) packed[unit * 8 + e] = w2[(int64_t)(h0 + e) * D + col];
+    }
+}
+
+// compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1
+template <int I, int N, typename F>
+__device__ __forceinline__ void static_for(F&& f)
+{
+    if constexpr (I < N) {
+        f(std::integral_constant<int, I>{});
+        static_for<I + 1, N>(f);
+    }
+}
+
 __global__ void sweep_init_kernel(uint32_t* flags, int64_t n, int64_t done_below, uint32_t* ctrl)
 {
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -160,7 +206,7 @@ __device__ __forceinline__ float sum_rows(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-template <int W, bool TIMERS>
+template <int W, bool TIMERS, bool FFN>
 __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 {
     static_assert(W == 8, "the landing zone is laid out for cones of two hops");
@@ -531,10 +577,13 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 // Row addresses by (gate, slot), so that the issue below is straight-line code
                 // with fixed lanes and fixed LDS addresses (with one wave per SIMD every
                 // instruction counts): lanes scatter the address of their entry through LDS to
-                // lane 8*gate + slot. Slots without a published source point at row 0: that
-                // transfer is wasted but harmless (its slot is unused, or refilled later).
+                // lane 8*gate + slot. Slots without a published source point at the first kilobyte
+                // of the projected self rows: that transfer is wasted but harmless (its slot is
+                // unused, or refilled later). It must not touch the K|V store: a row of it read
+                // before it is written would leave a stale copy in this XCD's L2 for the gates
+                // that read it as a source later.
                 uint64_t* tmp = (uint64_t*)(smem + SMEM_LOOK + 2048) + wave * 32;
-                if (lane < 32) tmp[lane] = (uint64_t)(uintptr_t)p.kv;
+                if (lane < 32) tmp[lane] = (uint64_t)(uintptr_t)p.qkv_self;
                 if (upl && nslot < (uint32_t)NS)
                     tmp[grp * 8 + nslot] = (uint64_t)(uintptr_t)p.kv + (uint64_t)(nent & 0x3FFFFFFFu) * (2 * D * 2);
                 const uint64_t a = tmp[lane & 31];
@@ -661,7 +710,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         {
             uint4 ha, hb;
             Elem<bf16_t>::pack(t, ha, hb);
-            if (nvalid) {
+            if (!FFN && nvalid) {
                 uint4* hp = (uint4*)(p.h_out + orig_n * D + c0);
                 hp[0] = ha; hp[1] = hb;
             }
@@ -675,6 +724,95 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (has_next) {
             if ((int)nxt.y == TILE) gather_own_full(nxt.x, d1);
             else gather_own(nxt.x, (int)nxt.y, d1);
+        }
+
+        // ---------------- feed-forward sub-block (Section 3.5 keeps the transformer structure around
+        // the attention): h <- LN(h + max(h W1, 0) W2), h = the rows in sH. The megabyte of W1 | W2
+        // fits neither the registers nor LDS next to everything else, so it is streamed from the
+        // L2 cache, every wave its own contiguous stream, through a ring of RING fragments that
+        // are requested RING steps before the matrix cores need them. Per pass of 256 hidden units:
+        // every wave forms 64 of the activations (transposed, so that a lane ends up with four
+        // consecutive hidden units of one gate), they are exchanged through the idle attention
+        // buffer, and every wave adds the pass's part of its own 64 output columns.
+        if constexpr (FFN) {
+            constexpr int RING = 16;
+            static_assert(FFN_FRAGS % RING == 0, "ring slots repeat from pass to pass");
+            const uint4* wp = (const uint4*)p.ffn_packed + (int64_t)wave * (FFN_PASSES * FFN_FRAGS * 64) + lane;
+            u32x4 ring[RING];
+            static_for<0, RING>([&](auto I) __attribute__((always_inline)) { ring[I.value] = __builtin_bit_cast(u32x4, wp[I.value * 64]); });
+            f32x4 out[4];
+            uint16_t (*sU)[LDS_STRIDE] = sA;
+#pragma unroll 1
+            for (int pass = 0; pass < FFN_PASSES; ++pass) {
+                const uint4* wq = wp + (int64_t)pass * (FFN_FRAGS * 64);
+                const bool more = pass + 1 < FFN_PASSES;
+                f32x4 u[4];
+                // activations of hidden units 256*pass + 64*wave .. +63, transposed
+                static_for<0, 32>([&](auto J) __attribute__((always_inline)) {
+                    constexpr int j = J.value, ks = j >> 2, ht = j & 3, slot = j % RING;
+                    const uint4 b = *(const uint4*)&sH[n][8 * grp + ks * 32];
+                    u[ht] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : u[ht]);
+                    ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+                if (pass) {                       // the previous pass has been read by every wave
+                    __builtin_amdgcn_s_waitcnt(0xC07F);
+                    __asm__ volatile("" ::: "memory");
+                    __builtin_amdgcn_s_barrier();
+                    __asm__ volatile("" ::: "memory");
+                }
+#pragma unroll
+                for (int ht = 0; ht < 4; ++ht)
+                    *(uint2*)&sU[n][64 * wave + 16 * ht + 4 * grp] =
+                        make_uint2(pack_bf16x2(fmaxf(u[ht][0], 0.f), fmaxf(u[ht][1], 0.f)), pack_bf16x2(fmaxf(u[ht][2], 0.f), fmaxf(u[ht][3], 0.f)));
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __asm__ volatile("" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                __asm__ volatile("" ::: "memory");
+                // this pass's part of output columns 64*wave + 16*grp .. +15
+                static_for<32, 64>([&](auto J) __attribute__((always_inline)) {
+                    constexpr int j = J.value, kk = (j - 32) >> 2, ct = j & 3, slot = j % RING;
+                    const uint4 b = *(const uint4*)&sU[n][8 * grp + kk * 32];
+                    out[ct] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b, (pass == 0 && kk == 0) ? (f32x4){0.f, 0.f, 0.f, 0.f} : out[ct]);
+                    if (j + RING < FFN_FRAGS || more)         // (past the end of this pass: the first fragments of the next)
+                        ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
+                    __builtin_amdgcn_sched_barrier(0);
+                });
+            }
+            // residual (the rows in sH, this lane's own 16 columns), LayerNorm, the new rows
+            {
+                float h1[16];
+                const uint4* hp = (const uint4*)&sH[n][c0];
+                Elem<bf16_t>::unpack(hp[0], hp[1], h1);
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) t[ct * 4 + i] = out[ct][i] + h1[ct * 4 + i];
+            }
+            float s1 = 0.f, s2 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { s1 += t[i]; s2 = fmaf(t[i], t[i], s2); }
+            s1 = sum_rows(s1); s2 = sum_rows(s2);
+            __syncthreads();                  // every wave is done with the activations and with sH as an operand
+            if (grp == 0) { sRed[n][wave][0] = s1; sRed[n][wave][1] = s2; }
+            __syncthreads();
+            float a1 = 0.f, a2 = 0.f;
+#pragma unroll
+            for (int w2 = 0; w2 < 4; ++w2) { a1 += sRed[n][w2][0]; a2 += sRed[n][w2][1]; }
+            const float mean = a1 * (1.0f / D);
+            const float var = fmaxf(a2 * (1.0f / D) - mean * mean, 0.f);
+            const float rstd = rsqrtf(var + p.ln_eps);
+#pragma unroll
+            for (int i = 0; i < 16; ++i) t[i] = (t[i] - mean) * rstd;
+            uint4 ha, hb;
+            Elem<bf16_t>::pack(t, ha, hb);
+            if (nvalid) {
+                uint4* hp = (uint4*)(p.h_out + orig_n * D + c0);
+                hp[0] = ha; hp[1] = hb;
+            }
+            uint4* hs = (uint4*)&sH[n][c0];
+            hs[0] = ha; hs[1] = hb;
+            __syncthreads();                  // sH holds the final embeddings
         }
 
         // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
@@ -738,6 +876,14 @@ int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void
     return hipGetLastError();
 }
 
+int dg4_launch_pack_ffn(const void* w1, const void* w2, void* packed, hipStream_t s)
+{
+    const int64_t units = 4 * FFN_PASSES * FFN_FRAGS * 64;
+    hipLaunchKernelGGL(pack_ffn_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
+                       (const uint16_t*)w1, (const uint16_t*)w2, (uint16_t*)packed);
+    return hipGetLastError();
+}
+
 int dg4_launch_sweep_init(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, hipStream_t s)
 {
     hipLaunchKernelGGL(sweep_init_kernel, dim3((unsigned)((std::max<int64_t>(n_flags, 64) + 255) / 256)), dim3(256), 0, s,
@@ -754,7 +900,10 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
     int64_t grid = cus;                // one workgroup per compute unit: its registers and LDS hold the weights
     if (grid > a.n_tiles) grid = a.n_tiles;
     void (*kern)(dg4_sweep_args) = nullptr;            // the LDS landing zone is laid out for cones of two hops
-    if (a.ell_w == 8) kern = a.prof ? sweep_kernel<8, true> : sweep_kernel<8, false>;
+    if (a.ell_w == 8) {
+        if (a.ffn_packed) kern = a.prof ? sweep_kernel<8, true, true> : sweep_kernel<8, false, true>;
+        else kern = a.prof ? sweep_kernel<8, true, false> : sweep_kernel<8, false, false>;
+    }
     if (!kern) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
     if (e != hipSuccess) return e;

@@ -240,7 +240,8 @@ def test_ffn_fwd(dtype, d, rows, lo, hi):
 
 @pytest.mark.parametrize("name,n_and,kw", [
     ("tiny", None, {}), ("small", None, {}), ("tiny", None, dict(n_layers=3, hops=3)),
-    ("large", 30_000, {}), ("stress", 20_000, {}), ("stress", 20_000, dict(bounded_kv=True)),
+    ("large", 30_000, {}), ("large", 30_000, dict(per_level=True)), ("medium", 20_000, {}),
+    ("stress", 20_000, {}), ("stress", 20_000, dict(bounded_kv=True)),
     ("medium", 20_000, dict(dtype="f32")),
 ])
 def test_layer_fwd_with_feed_forward(name, n_and, kw):
@@ -251,7 +252,7 @@ def test_layer_fwd_with_feed_forward(name, n_and, kw):
     c = synth.Config(**{**base.__dict__, **over, **({"n_and": n_and} if n_and else {})})
     w = synth.make(c)
     w1, w2 = synth.ffn_weights(c)
-    cfg = cfg_of(c, ffn=True, bounded_kv=kw.get("bounded_kv", False))
+    cfg = cfg_of(c, ffn=True, bounded_kv=kw.get("bounded_kv", False), per_level=kw.get("per_level", False))
     g, og = graphs(w)
     X = to_dev(w.x, c.dtype)
     W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(device_weights(w, c.dtype))]
@@ -271,6 +272,34 @@ def test_layer_fwd_with_feed_forward(name, n_and, kw):
     # and it is not the layer without the sub-block
     plain = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, H, nodes[:50], store=c.dtype)
     assert row_rel_err(H[nodes[:50]], plain).min() > 10 * TOL[c.dtype]
+
+
+@pytest.mark.parametrize("ffn", [False, True])
+def test_sweep_reads_no_row_before_it_is_written(ffn):
+    """Workspace filled with NaN patterns before every run: a K|V row fetched before its gate has
+    written it (or a stale cached copy of it) would surface as NaN or as a wrong embedding."""
+    print(f"poisoned workspace ffn={ffn}", flush=True)
+    w = synth.make("large", n_and=30_000)
+    c = w.cfg
+    cfg = cfg_of(c, ffn=ffn)
+    g, og = graphs(w)
+    X = to_dev(w.x, c.dtype)
+    W = device_weights(w, c.dtype)
+    w1 = w2 = None
+    if ffn:
+        w1, w2 = synth.ffn_weights(c)
+        W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(W)]
+    ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+    nodes = np.arange(c.n_nodes)
+    for _ in range(3):
+        ws.fill_(0xFF)
+        Hd = torch.full((c.n_nodes, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+        dg4.dg4_layer_fwd(cfg, g, X, W, Hd, workspace=ws)
+        torch.cuda.synchronize()
+        H = to_np(Hd)
+        assert not np.isnan(H).any()
+        step = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, H, nodes, store=c.dtype, w1=w1, w2=w2)
+        assert row_rel_err(H, step).max() <= TOL[c.dtype]
 
 
 def test_workspace_reuse_with_new_inputs():
