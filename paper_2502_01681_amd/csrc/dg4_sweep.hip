@@ -730,12 +730,15 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         // the attention): h <- LN(h + max(h W1, 0) W2), h = the rows in sH. The megabyte of W1 | W2
         // fits neither the registers nor LDS next to everything else, so it is streamed from the
         // L2 cache, every wave its own contiguous stream, through a ring of RING fragments that
-        // are requested RING steps before the matrix cores need them. Per pass of 256 hidden units:
+        // are requested RING products before the matrix cores need them. Per pass of 256 hidden units:
         // every wave forms 64 of the activations (transposed, so that a lane ends up with four
         // consecutive hidden units of one gate), they are exchanged through the idle attention
         // buffer, and every wave adds the pass's part of its own 64 output columns.
         if constexpr (FFN) {
-            constexpr int RING = 16;
+            // (Measured on the 1M-gate workload: the stream runs at about 78 GB/s per compute unit,
+            // 19 TB/s over the chip, nearly all L2 hits, and is what bounds the phase: with the
+            // loads taken out the phase costs a third. A deeper ring changes nothing but spills.)
+            constexpr int RING = 8;
             static_assert(FFN_FRAGS % RING == 0, "ring slots repeat from pass to pass");
             const uint4* wp = (const uint4*)p.ffn_packed + (int64_t)wave * (FFN_PASSES * FFN_FRAGS * 64) + lane;
             u32x4 ring[RING];
@@ -748,13 +751,24 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 const bool more = pass + 1 < FFN_PASSES;
                 f32x4 u[4];
                 // activations of hidden units 256*pass + 64*wave .. +63, transposed
-                static_for<0, 32>([&](auto J) __attribute__((always_inline)) {
-                    constexpr int j = J.value, ks = j >> 2, ht = j & 3, slot = j % RING;
-                    const uint4 b = *(const uint4*)&sH[n][8 * grp + ks * 32];
-                    u[ht] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : u[ht]);
-                    ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
-                    __builtin_amdgcn_sched_barrier(0);
-                });
+                // (the tile's operand of the next group of four products is read from LDS while
+                // this group runs: with one wave per SIMD nothing else hides that latency)
+                {
+                    uint4 b_cur = *(const uint4*)&sH[n][8 * grp];
+                    static_for<0, 8>([&](auto KS) __attribute__((always_inline)) {
+                        constexpr int ks = KS.value;
+                        uint4 b_nxt = b_cur;
+                        if (ks + 1 < 8) b_nxt = *(const uint4*)&sH[n][8 * grp + (ks + 1) * 32];
+#pragma unroll
+                        for (int ht = 0; ht < 4; ++ht) {
+                            const int j = 4 * ks + ht, slot = j % RING;
+                            u[ht] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : u[ht]);
+                            ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        b_cur = b_nxt;
+                    });
+                }
                 if (pass) {                       // the previous pass has been read by every wave
                     __builtin_amdgcn_s_waitcnt(0xC07F);
                     __asm__ volatile("" ::: "memory");
@@ -770,14 +784,23 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 __builtin_amdgcn_s_barrier();
                 __asm__ volatile("" ::: "memory");
                 // this pass's part of output columns 64*wave + 16*grp .. +15
-                static_for<32, 64>([&](auto J) __attribute__((always_inline)) {
-                    constexpr int j = J.value, kk = (j - 32) >> 2, ct = j & 3, slot = j % RING;
-                    const uint4 b = *(const uint4*)&sU[n][8 * grp + kk * 32];
-                    out[ct] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b, (pass == 0 && kk == 0) ? (f32x4){0.f, 0.f, 0.f, 0.f} : out[ct]);
-                    if (j + RING < FFN_FRAGS || more)         // (past the end of this pass: the first fragments of the next)
-                        ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
-                    __builtin_amdgcn_sched_barrier(0);
-                });
+                {
+                    uint4 b_cur = *(const uint4*)&sU[n][8 * grp];
+                    static_for<0, 8>([&](auto KK) __attribute__((always_inline)) {
+                        constexpr int kk = KK.value;
+                        uint4 b_nxt = b_cur;
+                        if (kk + 1 < 8) b_nxt = *(const uint4*)&sU[n][8 * grp + (kk + 1) * 32];
+#pragma unroll
+                        for (int ct = 0; ct < 4; ++ct) {
+                            const int j = 32 + 4 * kk + ct, slot = j % RING;
+                            out[ct] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b_cur, (pass == 0 && kk == 0) ? (f32x4){0.f, 0.f, 0.f, 0.f} : out[ct]);
+                            if (j + RING < FFN_FRAGS || more)         // (past the end of this pass: the first fragments of the next)
+                                ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        b_cur = b_nxt;
+                    });
+                }
             }
             // residual (the rows in sH, this lane's own 16 columns), LayerNorm, the new rows
             {
