@@ -68,6 +68,9 @@ def main():
                     help="skip the stand-alone timings of dg4_qkv_proj and dg4_sparse_attn_fwd over all rows")
     ap.add_argument("--no-level-order", action="store_true",
                     help="skip the extra run with level-ordered tiles (for profiles of the default path only)")
+    ap.add_argument("--ffn", action="store_true",
+                    help="time the layer WITH its feed-forward sub-block (not the headline configuration; "
+                         "the roofline object then prices the step's matrix products against the MFMA peak)")
     ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
@@ -101,12 +104,16 @@ def main():
     t0 = time.perf_counter()
     g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
     t_build = time.perf_counter() - t0
-    cfg = dg4.LayerConfig(c.hidden, c.heads, c.hops, c.n_layers, c.dtype)
+    cfg = dg4.LayerConfig(c.hidden, c.heads, c.hops, c.n_layers, c.dtype, ffn=args.ffn)
     td = torch.float32 if c.dtype == "f32" else torch.bfloat16
     t0 = time.perf_counter()
     X = torch.from_numpy(w.x).cuda().to(td).contiguous()
     W = [(torch.from_numpy(w.wqkv[l]).cuda().to(td).contiguous(), torch.from_numpy(w.wo[l]).cuda().to(td).contiguous(),
           torch.from_numpy(w.rel_bias[l]).cuda().contiguous()) for l in range(c.n_layers)]
+    if args.ffn:
+        fw1, fw2 = synth.ffn_weights(c)
+        W = [W[l] + (torch.from_numpy(fw1[l]).cuda().to(td).contiguous(), torch.from_numpy(fw2[l]).cuda().to(td).contiguous())
+             for l in range(c.n_layers)]
     g.upload()
     torch.cuda.synchronize()
     t_upload = time.perf_counter() - t0
@@ -163,10 +170,23 @@ def main():
                      "step_achieved": compulsory / (ms_dev * 1e-3) / 1e9},
         "setup_s": {"generate": t_gen, "dg4_build_levels": t_build, "upload": t_upload},
     }
+    if args.ffn:
+        # With the feed-forward sub-block the step is bound by its matrix products and by the weight
+        # stream that feeds them, not by HBM: per gate and layer 2*d*3d (Q|K|V of x) + 2*d*d (Wo) +
+        # 2*d*2d (K|V of H) + 16*d*d (feed-forward) flop.
+        d = c.hidden
+        flop = float(n_gates) * layers * (6 * d * d + 2 * d * d + 4 * d * d + 16 * d * d)
+        peak = 2500.0 if c.dtype == "bf16" else 157.3
+        out["config"]["workload"] += " + feed-forward sub-block (4x hidden)"
+        hbm = out["roofline"]
+        out["roofline"] = {"bound": "mfma", "kernel": hbm["kernel"], "achieved": flop / (ms_dev * 1e-3) / 1e12,
+                           "peak": peak, "unit": "TFLOP/s", "frac": flop / (ms_dev * 1e-3) / 1e12 / peak,
+                           "traffic": None, "flop": flop, "kernel_ms": ms_kernel, "step_ms_device": ms_dev,
+                           "hbm_algorithmic_bytes": compulsory, "hbm_frac": hbm["frac"]}
 
     # For information: the same step with the tiles dealt strictly level by level (the order of the
     # level hint) instead of the library's default dependency-driven order. Same results, bit for bit.
-    if len(sweep_ms) == args.steps and not args.no_level_order:
+    if len(sweep_ms) == args.steps and not args.no_level_order and not args.ffn:
         os.environ["DG4_SWEEP_LEVEL_ORDER"] = "1"
         for _ in range(args.warmup):
             dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
@@ -188,7 +208,7 @@ def main():
 
     # The two non-recurrent calls over all rows at once, as pure-kernel roofline points
     # (bf16 MFMA peak 2.5 PFLOP/s dense; both are HBM-bound at this size).
-    if not args.no_kernel_points:
+    if not args.no_kernel_points and not args.ffn:
         def timed(fn, reps=5):
             for _ in range(2):
                 fn()
@@ -255,7 +275,8 @@ def main():
         lev_end = max(1, min(lev_end, g.n_levels))
         og = oracle.build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
         t0 = time.perf_counter()
-        oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype, level_end=lev_end)
+        ffn_kw = dict(zip(("w1", "w2"), synth.ffn_weights(c))) if args.ffn else {}
+        oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype, level_end=lev_end, **ffn_kw)
         dt = time.perf_counter() - t0
         rows = int(lp[lev_end])
         sample_nnz = int(og.nbr_ptr[og.order[:rows] + 1].sum() - og.nbr_ptr[og.order[:rows]].sum())

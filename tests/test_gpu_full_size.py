@@ -57,6 +57,41 @@ def test_full_size_sampled(name, samples):
     assert torch.equal(H, H2)
 
 
+@pytest.mark.parametrize("name", ["medium", "large"])
+def test_full_size_with_feed_forward(name):
+    """The layer with its feed-forward sub-block (Section 3.5) at full size, in the persistent kernel."""
+    print(f"full size {name} with feed-forward: generating", flush=True)
+    w = synth.make(name)
+    c = w.cfg
+    w1, w2 = synth.ffn_weights(c)
+    cfg = cfg_of(c, ffn=True)
+    g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    X = to_dev(w.x, c.dtype)
+    W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(device_weights(w, c.dtype))]
+    H = torch.full((c.n_nodes, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+    ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)                                              # NaN patterns: nothing may be read before it is written
+    dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
+    torch.cuda.synchronize()
+    print("  sweep done", flush=True)
+    aborted, _ = dg4.dg4_layer_profile(cfg, g, ws)
+    assert aborted == 0
+    Hn = to_np(H)
+    assert not np.isnan(Hn).any()
+    assert np.abs(Hn.mean(axis=1)).max() < 2e-2 and np.abs(Hn.var(axis=1) - 1).max() < 5e-2
+    og = oracle.build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    rng = np.random.default_rng(4)
+    nodes = np.unique(np.concatenate([rng.choice(c.n_nodes, size=3000, replace=False), og.order[-200:], og.order[:100]]))
+    ref = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, Hn, nodes, store=c.dtype, w1=w1, w2=w2)
+    err = row_rel_err(Hn[nodes], ref)
+    print(f"  sampled {len(nodes)} gates: max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype]
+    H2 = torch.empty_like(H)
+    dg4.dg4_layer_fwd(cfg, g, X, W, H2, workspace=ws)
+    torch.cuda.synchronize()
+    assert torch.equal(H, H2)
+
+
 def test_stress_full_size_with_bounded_kv():
     # the stress configuration as it is defined: 4 layers, 3-hop cones, and no K|V store, only one
     # level's frontier (the store of the default path would be 16 GB for this graph)
