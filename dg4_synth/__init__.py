@@ -135,6 +135,26 @@ def aig(seed: int, n_pi: int, n_and: int, window: int, p_window: float = 1.0, le
     return src, dst, inv, hint
 
 
+def not_as_nodes(n: int, src, dst, inv):
+    """The same circuit with inverters as NODES, the paper's own AIG form (Section 3.2: in-degree 1
+    = NOT gate): every signal that some AND reads inverted gets ONE NOT node (structural hashing),
+    id n + its rank among such signals, fed by a plain edge; the inverted edges into ANDs are
+    re-attached to it as plain edges. Edges into in-degree-1 nodes are left alone.
+    Returns (n2, src2, dst2, inv2, not_node) with not_node[v] = id of v's NOT node or -1."""
+    src, dst, inv = (np.asarray(a) for a in (src, dst, inv))
+    indeg = np.bincount(dst, minlength=n)
+    moved = (inv == 1) & (indeg[dst] == 2)
+    signals = np.unique(src[moved])
+    not_node = np.full(n, -1, dtype=np.int32)
+    not_node[signals] = n + np.arange(len(signals), dtype=np.int32)
+    src2 = np.where(moved, not_node[src], src).astype(np.int32)
+    inv2 = np.where(moved, 0, inv).astype(np.uint8)
+    src2 = np.concatenate([src2, signals.astype(np.int32)])
+    dst2 = np.concatenate([dst.astype(np.int32), not_node[signals]])
+    inv2 = np.concatenate([inv2, np.zeros(len(signals), dtype=np.uint8)])
+    return n + len(signals), src2, dst2, inv2, not_node
+
+
 @dataclass
 class Workload:
     cfg: Config
