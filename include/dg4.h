@@ -91,6 +91,23 @@ int dg4_build_levels(int64_t n_nodes, int64_t n_edges,
                      int32_t hops, const int32_t* level_hint /* nullable */,
                      dg4_graph** out);
 
+/*
+ * The same analysis (Section 3.2: levels by Eq. 1, cone rows; and the fanout counts of Eq. 2) run on
+ * the GPU, for an edge list that is already in DEVICE memory: edge_src, edge_dst, edge_inv and
+ * level_hint (nullable) are device pointers. Levels are found in rounds over the fanin table (a gate
+ * is finished one round after its fanins), the (level, id) order by a stable sort, each cone row by a
+ * backward search from its gate. Every table of the resulting graph equals the host call's bit for
+ * bit. Synchronous: waits on `stream`; temporary device memory (about 130 bytes per node) is
+ * allocated and released inside the call, and the tables are copied to host memory, where the graph
+ * object keeps them. Errors as dg4_build_levels; if an edge list has defects of several kinds, the
+ * kind reported may differ from the host call's (which reports the first in edge order), and an
+ * invalid hint on a cyclic graph gives EHINT. Also EHIP.
+ */
+int dg4_build_levels_device(int64_t n_nodes, int64_t n_edges,
+                            const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,
+                            int32_t hops, const int32_t* level_hint /* nullable */,
+                            void* stream, dg4_graph** out);
+
 /* Tables of a graph, borrowed host pointers valid until dg4_graph_free. */
 typedef enum {
     DG4_LEVEL = 0,      /* int32  [n_nodes]                                    */

@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdg4.so")
-SOURCES = ["dg4_graph.cpp", "dg4_api.cpp", "dg4_kernels.hip", "dg4_sweep.hip"]
+SOURCES = ["dg4_graph.cpp", "dg4_graph_gpu.hip", "dg4_api.cpp", "dg4_kernels.hip", "dg4_sweep.hip"]
 
 
 def sources():

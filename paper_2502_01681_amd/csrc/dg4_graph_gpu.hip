@@ -1,0 +1,322 @@
+// Graph analysis of paper Section 3.2 on the device, behind dg4_build_levels_device: validation,
+// fanin table, logic levels (Eq. 1) by rounds over the fanin table, the (level, id) order by a
+// stable radix sort, cone_k rows with relation codes by a per-gate backward search, and the fanout
+// counts of Eq. 2. Integer work throughout: every table equals the host builder's bit for bit
+// (nothing here depends on the order in which atomics land: the fanin slot a source takes is not
+// observable in any output).
+#include <hip/hip_runtime.h>
+#include <hipcub/hipcub.hpp>
+#include <stdint.h>
+
+#include <algorithm>
+#include <memory>
+#include <new>
+#include <vector>
+
+#include "dg4_internal.h"
+
+namespace {
+
+constexpr int MAXW = 15;            // 2^(3+1) - 1: the largest cone for hops <= 3
+
+// status word: the most negative status any thread reports wins (deterministic for a list with
+// one kind of defect; for several kinds the host call reports the first in edge order instead)
+__device__ __forceinline__ void report(int* status, int code) { atomicMin(status, code); }
+
+__global__ void fanin_kernel(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei,
+                             int32_t* fin, uint8_t* finv, int32_t* deg, int* status)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i >= e) return;
+    const int64_t u = es[i], v = ed[i];
+    if (u < 0 || u >= n || v < 0 || v >= n) { report(status, DG4_ERANGE); return; }
+    if (ei[i] > 1) { report(status, DG4_EINVAL); return; }
+    if (u == v) { report(status, DG4_ECYCLE); return; }
+    const int slot = atomicAdd(&deg[v], 1);
+    if (slot >= 2) { report(status, DG4_EFANIN); return; }
+    fin[2 * v + slot] = (int32_t)u;
+    finv[2 * v + slot] = ei[i];
+}
+
+// duplicated fanin pair; primary inputs start at level 0 and are done
+__global__ void fanin_check_kernel(int64_t n, const int32_t* fin, const int32_t* deg, int32_t* level, uint8_t* done, int* status)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    if (deg[v] == 2 && fin[2 * v] == fin[2 * v + 1]) report(status, DG4_EFANIN);
+    level[v] = 0;
+    done[v] = deg[v] == 0;
+}
+
+// One round of Eq. 1: a gate whose fanins were all done BEFORE this round gets max + 1. Two flag
+// arrays alternate so that a round reads only the previous round's state (level[] of a fanin is
+// final once its flag is set). progress[0] counts the gates finished so far.
+__global__ void level_round_kernel(int64_t n, const int32_t* fin, const int32_t* deg, const uint8_t* done_in,
+                                   uint8_t* done_out, int32_t* level, unsigned long long* progress)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    if (done_in[v]) { done_out[v] = 1; return; }
+    const int d = deg[v];
+    int32_t best = -1;
+    bool ready = true;
+    for (int k = 0; k < d; ++k) {
+        const int32_t u = fin[2 * v + k];
+        if (done_in[u]) best = max(best, level[u]); else ready = false;
+    }
+    if (ready) { level[v] = best + 1; atomicAdd(progress, 1ull); }
+    done_out[v] = ready;
+}
+
+__global__ void count_done_kernel(int64_t n, const uint8_t* done, unsigned long long* progress)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n && done[v]) atomicAdd(progress, 1ull);
+}
+
+// a caller's levelling: non-negative, 0 exactly on primary inputs' side of the rule, strictly
+// increasing along every edge (which also rules out cycles)
+__global__ void hint_check_kernel(int64_t n, const int32_t* fin, const int32_t* deg, const int32_t* hint, int32_t* level, int* status)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    const int32_t h = hint[v];
+    bool ok = h >= 0 && !(deg[v] == 0 && h != 0);
+    for (int k = 0; k < deg[v]; ++k) ok = ok && hint[fin[2 * v + k]] < h;
+    if (!ok) report(status, DG4_EHINT);
+    level[v] = h;
+}
+
+__global__ void iota_max_kernel(int64_t n, const int32_t* level, int32_t* ids, int32_t* max_level)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    ids[v] = (int32_t)v;
+    atomicMax(max_level, level[v]);
+}
+
+// level_ptr[l] = first position whose level is >= l, l = 0 .. max_level + 1 (binary search in the sorted keys)
+__global__ void level_ptr_kernel(int64_t n, const int32_t* sorted_level, int32_t n_ptr, int64_t* level_ptr)
+{
+    const int32_t l = blockIdx.x * blockDim.x + threadIdx.x;
+    if (l >= n_ptr) return;
+    int64_t lo = 0, hi = n;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        if (sorted_level[mid] < l) lo = mid + 1; else hi = mid;
+    }
+    level_ptr[l] = lo;
+}
+
+// cone_k(v) by a backward breadth-first search over the fanin table: the first visit fixes the
+// smallest hop count, hence the relation code (0 self, 1 / 2 direct fanin plain / inverted,
+// 3 reached by two or more edges); the row is then sorted by id. Fixed-width rows; counts in cnt.
+__global__ void cone_kernel(int64_t n, int hops, const int32_t* fin, const uint8_t* finv, const int32_t* deg,
+                            int32_t* row_id, uint8_t* row_rel, int64_t* cnt)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    int32_t id[MAXW];
+    uint8_t rel[MAXW], hop[MAXW];
+    int c = 0;
+    id[0] = (int32_t)v; rel[0] = 0; hop[0] = 0; c = 1;
+    for (int head = 0; head < c; ++head) {
+        if (hop[head] == hops) continue;
+        const int32_t w = id[head];
+        const int d = deg[w];
+        for (int k = 0; k < d; ++k) {
+            const int32_t u = fin[2 * (int64_t)w + k];
+            bool seen = false;
+            for (int j = 0; j < c; ++j) seen = seen || id[j] == u;
+            if (seen) continue;
+            id[c] = u; hop[c] = (uint8_t)(hop[head] + 1);
+            rel[c] = hop[c] == 1 ? (uint8_t)(1 + finv[2 * (int64_t)w + k]) : (uint8_t)3;
+            ++c;
+        }
+    }
+    for (int i = 1; i < c; ++i) {                       // insertion sort by id
+        const int32_t ti = id[i]; const uint8_t tr = rel[i];
+        int j = i - 1;
+        while (j >= 0 && id[j] > ti) { id[j + 1] = id[j]; rel[j + 1] = rel[j]; --j; }
+        id[j + 1] = ti; rel[j + 1] = tr;
+    }
+    for (int i = 0; i < c; ++i) { row_id[v * MAXW + i] = id[i]; row_rel[v * MAXW + i] = rel[i]; }
+    cnt[v] = c;
+}
+
+__global__ void compact_kernel(int64_t n, const int32_t* row_id, const uint8_t* row_rel, const int64_t* nbr_ptr,
+                               int32_t* nbr_idx, uint8_t* nbr_rel)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    const int64_t p0 = nbr_ptr[v];
+    const int c = (int)(nbr_ptr[v + 1] - p0);
+    for (int i = 0; i < c; ++i) { nbr_idx[p0 + i] = row_id[v * MAXW + i]; nbr_rel[p0 + i] = row_rel[v * MAXW + i]; }
+}
+
+// Fanout counts of Eq. 2 from the fanin table (integer atomics: the sums do not depend on order)
+__global__ void fanout_kernel(int64_t n, const int32_t* fin, const uint8_t* finv, const int32_t* deg,
+                              int32_t* out_and, int32_t* out_not, uint8_t* inverter)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    const int d = deg[v];
+    if (d == 1) { atomicAdd(&out_not[fin[2 * v]], 1); return; }        // v is a NOT / buffer gate
+    for (int k = 0; k < d; ++k) {
+        const int32_t u = fin[2 * v + k];
+        if (finv[2 * v + k]) inverter[u] = 1; else atomicAdd(&out_and[u], 1);
+    }
+}
+__global__ void add_inverter_kernel(int64_t n, int32_t* out_not, const uint8_t* inverter)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n) out_not[v] += inverter[v];
+}
+
+// device allocations of one call, released when it returns
+struct Arena {
+    std::vector<void*> blocks;
+    ~Arena() { for (void* p : blocks) (void)hipFree(p); }
+    template <typename T> T* get(size_t count, bool zero, hipStream_t s)
+    {
+        void* p = nullptr;
+        if (hipMalloc(&p, std::max<size_t>(count, 1) * sizeof(T)) != hipSuccess) return nullptr;
+        blocks.push_back(p);
+        if (zero && hipMemsetAsync(p, 0, std::max<size_t>(count, 1) * sizeof(T), s) != hipSuccess) return nullptr;
+        return (T*)p;
+    }
+};
+
+inline unsigned blocks_for(int64_t items) { return (unsigned)((items + 255) / 256); }
+
+#define GPU_CHECK(expr) do { if ((expr) != hipSuccess) return DG4_EHIP; } while (0)
+#define GPU_ALLOC(var, T, count, zero) T* var = arena.get<T>((count), (zero), s); if (!var) return DG4_ENOMEM
+
+}  // namespace
+
+extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
+                                       const uint8_t* ei, int32_t hops, const int32_t* level_hint,
+                                       void* stream, dg4_graph** out)
+{
+    if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
+    if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
+    if (n >= (int64_t)0x3FFFFFFF) return DG4_EUNSUPPORTED;
+    hipStream_t s = (hipStream_t)stream;
+    try {
+        std::unique_ptr<dg4_graph> g(new dg4_graph());
+        g->n = n; g->e = e; g->hops = hops;
+        if (n == 0) {
+            g->level_ptr.assign(2, 0); g->nbr_ptr.assign(1, 0);
+            *out = g.release();
+            return DG4_OK;
+        }
+        Arena arena;
+        GPU_ALLOC(fin, int32_t, 2 * (size_t)n, false);
+        GPU_ALLOC(finv, uint8_t, 2 * (size_t)n, true);
+        GPU_ALLOC(deg, int32_t, (size_t)n, true);
+        GPU_ALLOC(level, int32_t, (size_t)n, false);
+        GPU_ALLOC(done_a, uint8_t, (size_t)n, false);
+        GPU_ALLOC(done_b, uint8_t, (size_t)n, false);
+        GPU_ALLOC(status, int, 1, true);
+        GPU_ALLOC(progress, unsigned long long, 1, true);
+        GPU_ALLOC(max_level, int32_t, 1, true);
+        const unsigned nb = blocks_for(n);
+
+        if (e > 0) hipLaunchKernelGGL(fanin_kernel, dim3(blocks_for(e)), dim3(256), 0, s, n, e, es, ed, ei, fin, finv, deg, status);
+        hipLaunchKernelGGL(fanin_check_kernel, dim3(nb), dim3(256), 0, s, n, fin, deg, level, done_a, status);
+        int st = 0;
+        GPU_CHECK(hipMemcpyAsync(&st, status, sizeof(int), hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipStreamSynchronize(s));
+        if (st != DG4_OK) return st;
+
+        if (level_hint) {
+            hipLaunchKernelGGL(hint_check_kernel, dim3(nb), dim3(256), 0, s, n, fin, deg, level_hint, level, status);
+            GPU_CHECK(hipMemcpyAsync(&st, status, sizeof(int), hipMemcpyDeviceToHost, s));
+            GPU_CHECK(hipStreamSynchronize(s));
+            if (st != DG4_OK) return st;
+        } else {
+            // rounds of Eq. 1, a batch at a time; no progress in a batch with gates left = a cycle
+            hipLaunchKernelGGL(count_done_kernel, dim3(nb), dim3(256), 0, s, n, done_a, progress);
+            unsigned long long finished = 0, before = ~0ull;
+            uint8_t* cur = done_a; uint8_t* nxt = done_b;
+            for (;;) {
+                GPU_CHECK(hipMemcpyAsync(&finished, progress, sizeof(finished), hipMemcpyDeviceToHost, s));
+                GPU_CHECK(hipStreamSynchronize(s));
+                if (finished == (unsigned long long)n) break;
+                if (finished == before) return DG4_ECYCLE;
+                before = finished;
+                for (int r = 0; r < 32; ++r) {
+                    hipLaunchKernelGGL(level_round_kernel, dim3(nb), dim3(256), 0, s, n, fin, deg, cur, nxt, level, progress);
+                    std::swap(cur, nxt);
+                }
+            }
+        }
+
+        // (level, id) order: stable sort of the ids by level
+        GPU_ALLOC(ids, int32_t, (size_t)n, false);
+        GPU_ALLOC(sorted_level, int32_t, (size_t)n, false);
+        GPU_ALLOC(order, int32_t, (size_t)n, false);
+        hipLaunchKernelGGL(iota_max_kernel, dim3(nb), dim3(256), 0, s, n, level, ids, max_level);
+        int32_t h_max = 0;
+        GPU_CHECK(hipMemcpyAsync(&h_max, max_level, sizeof(int32_t), hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipStreamSynchronize(s));
+        g->max_level = h_max;
+        int bits = 1;
+        while (bits < 31 && (h_max >> bits) != 0) ++bits;
+        size_t sort_bytes = 0;
+        GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, level, sorted_level, ids, order, (int)n, 0, bits, s));
+        GPU_ALLOC(sort_tmp, unsigned char, sort_bytes, false);
+        GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, level, sorted_level, ids, order, (int)n, 0, bits, s));
+        const int32_t n_ptr = h_max + 2;
+        GPU_ALLOC(level_ptr, int64_t, (size_t)n_ptr, false);
+        hipLaunchKernelGGL(level_ptr_kernel, dim3(blocks_for(n_ptr)), dim3(256), 0, s, n, sorted_level, n_ptr, level_ptr);
+
+        // cones
+        GPU_ALLOC(row_id, int32_t, (size_t)n * MAXW, false);
+        GPU_ALLOC(row_rel, uint8_t, (size_t)n * MAXW, false);
+        GPU_ALLOC(cnt, int64_t, (size_t)n + 1, true);
+        GPU_ALLOC(nbr_ptr, int64_t, (size_t)n + 1, false);
+        hipLaunchKernelGGL(cone_kernel, dim3(nb), dim3(256), 0, s, n, (int)hops, fin, finv, deg, row_id, row_rel, cnt);
+        size_t scan_bytes = 0;
+        GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(nullptr, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
+        GPU_ALLOC(scan_tmp, unsigned char, scan_bytes, false);
+        GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
+        int64_t nnz = 0;
+        GPU_CHECK(hipMemcpyAsync(&nnz, nbr_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipStreamSynchronize(s));
+        g->nnz = nnz;
+        GPU_ALLOC(nbr_idx, int32_t, (size_t)nnz, false);
+        GPU_ALLOC(nbr_rel, uint8_t, (size_t)nnz, false);
+        hipLaunchKernelGGL(compact_kernel, dim3(nb), dim3(256), 0, s, n, row_id, row_rel, nbr_ptr, nbr_idx, nbr_rel);
+
+        // fanout counts of the structural encoding
+        GPU_ALLOC(out_and, int32_t, (size_t)n, true);
+        GPU_ALLOC(out_not, int32_t, (size_t)n, true);
+        GPU_ALLOC(inverter, uint8_t, (size_t)n, true);
+        hipLaunchKernelGGL(fanout_kernel, dim3(nb), dim3(256), 0, s, n, fin, finv, deg, out_and, out_not, inverter);
+        hipLaunchKernelGGL(add_inverter_kernel, dim3(nb), dim3(256), 0, s, n, out_not, inverter);
+        GPU_CHECK(hipGetLastError());
+
+        // host copies: the graph object hands them out and derives its device tables from them
+        g->level.resize((size_t)n); g->order.resize((size_t)n); g->pos.resize((size_t)n);
+        g->level_ptr.resize((size_t)n_ptr); g->nbr_ptr.resize((size_t)n + 1);
+        g->nbr_idx.resize((size_t)nnz); g->nbr_rel.resize((size_t)nnz);
+        g->out_and.resize((size_t)n); g->out_not.resize((size_t)n);
+        GPU_CHECK(hipMemcpyAsync(g->level.data(), level, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->order.data(), order, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->level_ptr.data(), level_ptr, (size_t)n_ptr * 8, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->nbr_ptr.data(), nbr_ptr, ((size_t)n + 1) * 8, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->nbr_idx.data(), nbr_idx, (size_t)nnz * 4, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->nbr_rel.data(), nbr_rel, (size_t)nnz, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->out_and.data(), out_and, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipMemcpyAsync(g->out_not.data(), out_not, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        GPU_CHECK(hipStreamSynchronize(s));
+        for (int64_t p = 0; p < n; ++p) g->pos[(size_t)g->order[(size_t)p]] = (int32_t)p;
+        *out = g.release();
+        return DG4_OK;
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    } catch (...) {
+        return DG4_EINVAL;
+    }
+}

@@ -1,0 +1,126 @@
+"""dg4_build_levels_device: the graph analysis of Section 3.2 on the GPU, bit for bit against the
+oracle (levels by Eq. 1 or a checked hint, (level, id) order, cone rows and relation codes) and
+against the host call (the fanout counts of Eq. 2, the processing order derived from the tables)."""
+import numpy as np
+import pytest
+import torch
+
+import dg4_synth as synth
+import oracle
+import paper_2502_01681_amd as dg4
+
+pytestmark = pytest.mark.gpu
+
+TABLES = ("level", "order", "level_ptr", "nbr_ptr", "nbr_idx", "nbr_rel")
+
+
+def dev(a, dtype):
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=dtype)).cuda()
+
+
+def build_on_gpu(n, src, dst, inv, hops, hint=None):
+    return dg4.dg4_build_levels_device(n, dev(src, np.int32), dev(dst, np.int32), dev(inv, np.uint8), hops,
+                                       None if hint is None else dev(hint, np.int32))
+
+
+def same_as_oracle(g, og):
+    assert g.n == og.n and g.n_levels == og.n_levels and g.nnz == len(og.nbr_idx)
+    for a in TABLES:
+        assert np.array_equal(g.array(a), getattr(og, a)), a
+
+
+@pytest.mark.parametrize("name,n_and,hops,hint", [
+    ("tiny", None, 2, False), ("tiny", None, 1, False), ("tiny", None, 3, False), ("small", None, 2, False),
+    ("medium", 50_000, 2, False), ("large", 60_000, 2, True), ("large", 60_000, 2, False), ("stress", 40_000, 3, True),
+])
+def test_tables_match_the_oracle(name, n_and, hops, hint):
+    print(f"device graph build {name} n_and={n_and} hops={hops} hint={hint}", flush=True)
+    w = synth.make(name, n_and=n_and, features=False)
+    n = w.cfg.n_nodes
+    h = w.level_hint if hint else None
+    g = build_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, hops, h)
+    same_as_oracle(g, oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, h))
+    oa, on = oracle.out_degrees(n, w.edge_src, w.edge_dst, w.edge_inv)
+    assert np.array_equal(g.array("out_and"), oa) and np.array_equal(g.array("out_not"), on)
+    # what the library derives from the tables is the same as for a host-built graph
+    gh = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, h)
+    assert np.array_equal(g.array("flow_order"), gh.array("flow_order"))
+    assert np.array_equal(g.array("flow_tile_ptr"), gh.array("flow_tile_ptr"))
+
+
+def test_shuffled_edges_relabelled_nodes_and_not_nodes():
+    w = synth.make("small", n_and=8000, features=False)
+    n = w.cfg.n_nodes
+    rng = np.random.default_rng(2)
+    perm, eperm = rng.permutation(n).astype(np.int32), rng.permutation(len(w.edge_src))
+    src, dst, inv = perm[w.edge_src][eperm], perm[w.edge_dst][eperm], w.edge_inv[eperm]
+    same_as_oracle(build_on_gpu(n, src, dst, inv, 2), oracle.build_levels(n, src, dst, inv, 2))
+    n2, s2, d2, i2, _ = synth.not_as_nodes(n, w.edge_src, w.edge_dst, w.edge_inv)
+    g = build_on_gpu(n2, s2, d2, i2, 3)
+    same_as_oracle(g, oracle.build_levels(n2, s2, d2, i2, 3))
+    oa, on = oracle.out_degrees(n2, s2, d2, i2)
+    assert np.array_equal(g.array("out_and"), oa) and np.array_equal(g.array("out_not"), on)
+
+
+def test_deep_chain_and_hand_graph():
+    # a chain of 3000 buffers: 3001 levels, one gate each (many rounds of Eq. 1)
+    n = 3001
+    src, dst = np.arange(n - 1), np.arange(1, n)
+    inv = (np.arange(n - 1) % 2).astype(np.uint8)
+    g = build_on_gpu(n, src, dst, inv, 3)
+    same_as_oracle(g, oracle.build_levels(n, src, dst, inv, 3))
+    assert g.n_levels == n
+    src, dst, inv = [0, 1, 2, 3, 3], [2, 2, 3, 4, 5], [0, 1, 1, 0, 1]
+    same_as_oracle(build_on_gpu(6, src, dst, inv, 3), oracle.build_levels(6, src, dst, inv, 3))
+    g0 = build_on_gpu(4, [], [], [], 2)                # primary inputs only
+    same_as_oracle(g0, oracle.build_levels(4, [], [], [], 2))
+
+
+@pytest.mark.parametrize("src,dst,inv,err", [
+    ([0, 1, 2], [3, 3, 3], [0, 0, 0], "EFANIN"),
+    ([0, 0], [3, 3], [0, 1], "EFANIN"),
+    ([0, 5], [3, 3], [0, 0], "ERANGE"),
+    ([0, -1], [3, 3], [0, 0], "ERANGE"),
+    ([0, 1], [3, 3], [0, 2], "EINVAL"),
+    ([3, 1], [3, 3], [0, 0], "ECYCLE"),
+    ([0, 3, 2, 4], [3, 4, 4, 3], [0, 0, 0, 0], "ECYCLE"),
+])
+def test_invalid_graphs(src, dst, inv, err):
+    with pytest.raises(dg4.DG4Error) as e:
+        build_on_gpu(5, src, dst, inv, 2)
+    assert e.value.name == err
+    with pytest.raises(oracle.OracleError, match=err):
+        oracle.build_levels(5, src, dst, inv, 2)
+
+
+def test_hint_is_checked():
+    w = synth.make("large", n_and=5000, features=False)
+    n = w.cfg.n_nodes
+    bad = w.level_hint.copy()
+    v = int(w.edge_dst[100])
+    bad[v] = bad[w.edge_src[100]]                      # an edge that does not go upward
+    with pytest.raises(dg4.DG4Error) as e:
+        build_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, 2, bad)
+    assert e.value.name == "EHINT"
+    bad = w.level_hint.copy(); bad[0] = 1              # a primary input above level 0
+    with pytest.raises(dg4.DG4Error) as e:
+        build_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, 2, bad)
+    assert e.value.name == "EHINT"
+
+
+def test_full_size_and_the_sweep_on_a_device_built_graph():
+    print("device graph build, full size large", flush=True)
+    w = synth.make("large")
+    c = w.cfg
+    n = c.n_nodes
+    g = build_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    same_as_oracle(g, oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint))
+    from gpu_utils import cfg_of, device_weights, to_dev
+    cfg = cfg_of(c)
+    gh = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    X, W = to_dev(w.x, c.dtype), device_weights(w, c.dtype)
+    H1, H2 = torch.empty_like(X), torch.empty_like(X)
+    dg4.dg4_layer_fwd(cfg, g, X, W, H1)
+    dg4.dg4_layer_fwd(cfg, gh, X, W, H2)
+    torch.cuda.synchronize()
+    assert torch.equal(H1, H2)
