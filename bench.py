@@ -104,6 +104,18 @@ def main():
     t0 = time.perf_counter()
     g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
     t_build = time.perf_counter() - t0
+    # the same analysis on the GPU, edge list resident in device memory (second call timed: the first pays
+    # for module loading)
+    e_dev = [torch.from_numpy(a).cuda() for a in (w.edge_src, w.edge_dst, w.edge_inv)]
+    h_dev = torch.from_numpy(w.level_hint).cuda() if w.level_hint is not None else None
+    t_build_dev = None
+    for _ in range(2):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        g_dev = dg4.dg4_build_levels_device(c.n_nodes, *e_dev, c.hops, h_dev)
+        t_build_dev = time.perf_counter() - t0
+        del g_dev
+    del e_dev, h_dev
     cfg = dg4.LayerConfig(c.hidden, c.heads, c.hops, c.n_layers, c.dtype, ffn=args.ffn)
     td = torch.float32 if c.dtype == "f32" else torch.bfloat16
     t0 = time.perf_counter()
@@ -168,7 +180,8 @@ def main():
                      "algorithmic_bytes": compulsory, "gathered_bytes": gathered,
                      "kernel_ms": ms_kernel, "step_ms_device": ms_dev,
                      "step_achieved": compulsory / (ms_dev * 1e-3) / 1e9},
-        "setup_s": {"generate": t_gen, "dg4_build_levels": t_build, "upload": t_upload},
+        "setup_s": {"generate": t_gen, "dg4_build_levels": t_build, "dg4_build_levels_device": t_build_dev,
+                    "upload": t_upload},
     }
     if args.ffn:
         # With the feed-forward sub-block the step is bound by its matrix products and by the weight

@@ -124,7 +124,12 @@ typedef enum {
     DG4_FLOW_TILE_PTR = 7,  /* int64 [n_tiles + 1] first position of each tile           */
     /* Fanout counts of the structural encoding (Section 3.5, Eq. 2), see dg4_struct_encode. */
     DG4_OUT_AND = 8,        /* int32 [n_nodes]                                           */
-    DG4_OUT_NOT = 9         /* int32 [n_nodes]                                           */
+    DG4_OUT_NOT = 9,        /* int32 [n_nodes]                                           */
+    /* The processing order of sweeps with DG4_FFN: tiles 2k and 2k+1 form a pair without
+     * dependencies between them (the second may be empty). Built on first request. For inspection
+     * and tests. */
+    DG4_PAIR_ORDER = 10,    /* int32 [n_nodes]                                           */
+    DG4_PAIR_TILE_PTR = 11  /* int64 [n_tiles + 1], n_tiles even                         */
 } dg4_array;
 
 int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count);

@@ -21,7 +21,8 @@ DG4_FFN = 8
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
           "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8),
           "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64),
-          "out_and": (8, np.int32), "out_not": (9, np.int32)}
+          "out_and": (8, np.int32), "out_not": (9, np.int32),
+          "pair_order": (10, np.int32), "pair_tile_ptr": (11, np.int64)}
 STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
           -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP"}
 

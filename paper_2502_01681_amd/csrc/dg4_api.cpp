@@ -41,6 +41,7 @@ struct LayerPlan {
     size_t qkv_level;    // [max_level_rows, 3d] (layers >= 1)
     size_t wo_t, wkv_t;  // persistent sweep: weights in its A-operand order (layer 0)
     size_t ffn_t;        // persistent sweep: W1 | W2 in its streaming order (DG4_FFN)
+    size_t park;         // persistent sweep: rows parked between the two tiles of a pair (DG4_FFN)
     size_t flags;        // [n] uint32 "rows published"
     size_t ctrl;         // abort flag, phase timers
     size_t total;
@@ -75,6 +76,7 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     p.wo_t = take(d * d * es);
     p.wkv_t = take(d * 2 * d * es);
     p.ffn_t = take(ffn ? 2 * d * 4 * d * es : 0);
+    p.park = take(ffn ? (size_t)DG4_MAX_SWEEP_GROUPS * DG4_TILE_ROWS * d * es : 0);
     p.flags = take(n * sizeof(uint32_t));
     p.ctrl = take(256);
     p.total = off;
@@ -298,15 +300,23 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // K/V of gates finished before this call (resume): from the caller's H
     if (P0 > 0 && !bounded) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
-    // One persistent dataflow kernel for the whole range of levels
-    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV))) {
+    // One persistent dataflow kernel for the whole range of levels (with the feed-forward sub-block:
+    // whole-graph sweeps only, partial ones run level by level)
+    const bool whole_range = level_begin == 0 && level_end == (int32_t)g->max_level + 1;
+    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) &&
+        (!ffn || whole_range)) {
         // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
         // level by level; rows of the internal buffers are positions in the order in use.
-        const bool whole = level_begin == 0 && level_end == (int32_t)g->max_level + 1 && !getenv("DG4_SWEEP_LEVEL_ORDER");
+        const bool whole = whole_range && (ffn || !getenv("DG4_SWEEP_LEVEL_ORDER"));
+        if (ffn) {
+            rc = dg4_graph_ensure_pairs(g);
+            if (rc != DG4_OK) return rc;
+        }
+        const int32_t* order_in_use = ffn ? g->d_pair_order : whole ? g->d_flow_order : g->d_order;
         {   // Q | K | V of x for every gate of the swept levels, rows in processing order
             HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, at(pl.wqkv[0]), s));
             dg4_bulk_args b{};
-            b.src = (const uint16_t*)X; b.gather = whole ? g->d_flow_order : g->d_order;
+            b.src = (const uint16_t*)X; b.gather = order_in_use;
             b.w_packed = at(pl.wqkv[0]); b.n_cols = 3 * d;
             uint16_t* base = (uint16_t*)at(pl.qkv_self);
             b.out[0] = base; b.out[1] = base + d; b.out[2] = base + 2 * d; b.out_stride = 3 * d;
@@ -316,11 +326,11 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         HIPCHK(dg4_launch_pack_wt(W[1], d, 0, 4, 4, at(pl.wo_t), s));
         HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, d, 8, 4, at(pl.wkv_t), s));
         dg4_sweep_args a{};
-        a.tiles = whole ? g->d_flow_tiles : g->d_tiles;
+        a.tiles = ffn ? g->d_pair_tiles : whole ? g->d_flow_tiles : g->d_tiles;
         a.tile_begin = whole ? 0 : g->level_tile_ptr[level_begin];
-        a.n_tiles = whole ? g->n_flow_tiles : g->level_tile_ptr[level_end] - a.tile_begin;
-        a.ell = whole ? g->d_flow_ell : g->d_ell_pos; a.ell_w = g->ell_w;
-        a.order = whole ? g->d_flow_order : g->d_order;
+        a.n_tiles = ffn ? g->n_pair_tiles : whole ? g->n_flow_tiles : g->level_tile_ptr[level_end] - a.tile_begin;
+        a.ell = ffn ? g->d_pair_ell : whole ? g->d_flow_ell : g->d_ell_pos; a.ell_w = g->ell_w;
+        a.order = order_in_use;
         a.x = (const uint16_t*)X;
         a.qkv_self = (const uint16_t*)at(pl.qkv_self);
         a.kv = (uint16_t*)at(pl.kv);
@@ -330,6 +340,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         if (ffn) {
             HIPCHK(dg4_launch_pack_ffn(W[3], W[4], at(pl.ffn_t), s));
             a.ffn_packed = at(pl.ffn_t);
+            a.park = (uint16_t*)at(pl.park);
         }
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
         a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.eager_publish = whole ? 0 : 1;

@@ -246,6 +246,18 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
         else { *host_ptr = g->flow_tile_ptr.data(); *count = (int64_t)g->flow_tile_ptr.size(); }
         break;
     }
+    case DG4_PAIR_ORDER:
+    case DG4_PAIR_TILE_PTR: {
+        dg4_graph* m = const_cast<dg4_graph*>(g);
+        std::lock_guard<std::mutex> lock(m->mu);
+        if (m->pair_tile_ptr.empty()) {
+            const int rc = dg4_pair_schedule(m, 1280);
+            if (rc != DG4_OK) return rc;
+        }
+        if (which == DG4_PAIR_ORDER) { *host_ptr = g->pair_order.data(); *count = g->n; }
+        else { *host_ptr = g->pair_tile_ptr.data(); *count = (int64_t)g->pair_tile_ptr.size(); }
+        break;
+    }
     default: return DG4_EINVAL;
     }
     return DG4_OK;
@@ -266,9 +278,11 @@ extern "C" int dg4_graph_info(const dg4_graph* g, int64_t* n_nodes, int64_t* n_l
 // is oldest (`due` = tile of that source + slack); ties go to the lower level, then the lower id.
 // `slack` tiles between a source and its reader let the source be published before the reader looks
 // for it. Results do not depend on the order; it only decides who waits for whom.
-int dg4_flow_schedule(dg4_graph* g, int64_t slack)
+// `pairs`: tiles come two at a time (2k and 2k+1, the second possibly empty) with no dependency
+// between the two, and count as published together (at the second one): the unit of the sweep
+// with the feed-forward sub-block, which runs two tiles through one pass over its weights.
+static int flow_schedule(const dg4_graph* g, int64_t slack, bool pairs, std::vector<int32_t>& out_order, std::vector<int64_t>& out_tile_ptr)
 {
-    if (!g->flow_tile_ptr.empty()) return DG4_OK;          // built once: pointers into it may have been handed out
     try {
         std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
         std::vector<int32_t> remaining((size_t)g->n, 0);
@@ -298,13 +312,15 @@ int dg4_flow_schedule(dg4_graph* g, int64_t slack)
         std::vector<Item> fresh;
         int64_t q = 0;
         while (!ready.empty()) {
-            const int64_t t = (int64_t)tile_ptr.size() - 1;
             const int64_t first = q;
-            for (int k = 0; k < DG4_TILE_ROWS && !ready.empty(); ++k) {
+            // the tile whose completion publishes these gates
+            const int64_t t = (int64_t)tile_ptr.size() - 1 + (pairs ? 1 : 0);
+            for (int k = 0; k < (pairs ? 2 : 1) * DG4_TILE_ROWS && !ready.empty(); ++k) {
                 const int32_t v = ready.top().v;
                 ready.pop();
                 tile_of[v] = (int32_t)t; flow[(size_t)q++] = v;
             }
+            if (pairs) tile_ptr.push_back(std::min<int64_t>(first + DG4_TILE_ROWS, q));
             tile_ptr.push_back(q);
             fresh.clear();
             for (int64_t p = first; p < q; ++p) {
@@ -321,9 +337,72 @@ int dg4_flow_schedule(dg4_graph* g, int64_t slack)
             for (const Item& it : fresh) ready.push(it);     // eligible from the next tile on
         }
         if (q != g->n) return DG4_ECYCLE;                      // cannot happen for a validated DAG
-        g->flow_order.swap(flow);
-        g->flow_tile_ptr.swap(tile_ptr);
-        g->flow_slack = slack;
+        out_order.swap(flow);
+        out_tile_ptr.swap(tile_ptr);
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
+    return DG4_OK;
+}
+
+int dg4_flow_schedule(dg4_graph* g, int64_t slack)
+{
+    if (!g->flow_tile_ptr.empty()) return DG4_OK;          // built once: pointers into it may have been handed out
+    const int rc = flow_schedule(g, slack, false, g->flow_order, g->flow_tile_ptr);
+    if (rc == DG4_OK) g->flow_slack = slack;
+    return rc;
+}
+
+int dg4_pair_schedule(dg4_graph* g, int64_t slack)
+{
+    if (!g->pair_tile_ptr.empty()) return DG4_OK;          // built once: pointers into it may have been handed out
+    return flow_schedule(g, slack, true, g->pair_order, g->pair_tile_ptr);
+}
+
+// Device tables of the pair schedule (sweeps with the feed-forward sub-block), built on first use.
+int dg4_graph_ensure_pairs(dg4_graph* g)
+{
+    std::lock_guard<std::mutex> lock(g->mu);
+    if (g->d_pair_tiles) return DG4_OK;
+    if (!g->on_device) return DG4_EINVAL;
+    const int w = g->ell_w;
+    const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
+    try {
+        int cus = 0;
+        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, g->device) != hipSuccess || cus <= 0) cus = 256;
+        const int rc = dg4_pair_schedule(g, (int64_t)cus * 5);      // 2.5 pairs per unit in flight
+        if (rc != DG4_OK) return rc;
+        const std::vector<int32_t>& order = g->pair_order;
+        const std::vector<int64_t>& tile_ptr = g->pair_tile_ptr;
+        std::vector<int32_t> padded(rows, 0);
+        std::copy(order.begin(), order.end(), padded.begin());
+        std::vector<uint2> tiles(tile_ptr.size() - 1);
+        for (size_t t = 0; t + 1 < tile_ptr.size(); ++t)
+            tiles[t] = make_uint2((uint32_t)tile_ptr[t], (uint32_t)(tile_ptr[t + 1] - tile_ptr[t]));
+        std::vector<uint32_t> ell(rows * w, DG4_ELL_PAD);
+        std::vector<int32_t> fpos((size_t)g->n, -1);
+        for (int64_t q = 0; q < g->n; ++q) fpos[(size_t)order[(size_t)q]] = (int32_t)q;
+        for (int64_t v = 0; v < g->n; ++v) {
+            const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
+            uint32_t* r = &ell[(size_t)fpos[v] * w];
+            for (int64_t j = 0; j < cnt; ++j)
+                r[j] = ((uint32_t)g->nbr_rel[lo + j] << 30) | (uint32_t)fpos[g->nbr_idx[lo + j]];
+        }
+        uint32_t* d_ell = nullptr; int32_t* d_order = nullptr; uint2* d_tiles = nullptr;
+        auto fail = [&](int code) {
+            if (d_ell) (void)hipFree(d_ell);
+            if (d_order) (void)hipFree(d_order);
+            if (d_tiles) (void)hipFree(d_tiles);
+            return code;
+        };
+        if (hipMalloc((void**)&d_ell, rows * w * sizeof(uint32_t)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&d_order, rows * sizeof(int32_t)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMalloc((void**)&d_tiles, std::max<size_t>(tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (hipMemcpy(d_ell, ell.data(), rows * w * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        if (hipMemcpy(d_order, padded.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        if (!tiles.empty() && hipMemcpy(d_tiles, tiles.data(), tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        g->d_pair_ell = d_ell; g->d_pair_order = d_order; g->d_pair_tiles = d_tiles;
+        g->n_pair_tiles = (int64_t)tiles.size();
     } catch (const std::bad_alloc&) {
         return DG4_ENOMEM;
     }
@@ -431,12 +510,6 @@ int dg4_graph_ensure_device(dg4_graph* g)
             if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
             if (g->d_order) (void)hipFree(g->d_order);
             if (g->d_tiles) (void)hipFree(g->d_tiles);
-    if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
-    if (g->d_flow_order) (void)hipFree(g->d_flow_order);
-    if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
-    if (g->d_struct) (void)hipFree(g->d_struct);
-    if (g->d_front_id) (void)hipFree(g->d_front_id);
-    if (g->d_ell_front) (void)hipFree(g->d_ell_front);
             g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr;
             return rc;
         };
@@ -565,5 +638,11 @@ extern "C" void dg4_graph_free(dg4_graph* g)
     if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
     if (g->d_flow_order) (void)hipFree(g->d_flow_order);
     if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);
+    if (g->d_struct) (void)hipFree(g->d_struct);
+    if (g->d_front_id) (void)hipFree(g->d_front_id);
+    if (g->d_ell_front) (void)hipFree(g->d_ell_front);
+    if (g->d_pair_ell) (void)hipFree(g->d_pair_ell);
+    if (g->d_pair_order) (void)hipFree(g->d_pair_order);
+    if (g->d_pair_tiles) (void)hipFree(g->d_pair_tiles);
     delete g;
 }

@@ -17,6 +17,7 @@
 #define DG4_ELL_PAD 0xFFFFFFFFu
 #define DG4_MAX_LAYERS 8
 #define DG4_TILE_ROWS 16          // gates per tile of the persistent sweep
+#define DG4_MAX_SWEEP_GROUPS 1024 // most workgroups the persistent sweep is launched with (one per compute unit)
 
 struct dg4_graph {
     int64_t n = 0, e = 0, nnz = 0;
@@ -60,12 +61,22 @@ struct dg4_graph {
     int32_t* d_flow_order = nullptr;
     uint2* d_flow_tiles = nullptr;
     int64_t n_flow_tiles = 0;
+    // The same kind of order with tiles in independent PAIRS (2k, 2k+1; the second may be empty),
+    // for sweeps with the feed-forward sub-block; built on first use.
+    std::vector<int32_t> pair_order;
+    std::vector<int64_t> pair_tile_ptr;
+    uint32_t* d_pair_ell = nullptr;
+    int32_t* d_pair_order = nullptr;
+    uint2* d_pair_tiles = nullptr;
+    int64_t n_pair_tiles = 0;
 };
 
 int dg4_graph_ensure_device(dg4_graph* g);
 int dg4_flow_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
+int dg4_pair_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
 int dg4_graph_ensure_frontier(dg4_graph* g);           // after dg4_graph_ensure_device
 int dg4_graph_ensure_struct(dg4_graph* g);
+int dg4_graph_ensure_pairs(dg4_graph* g);              // after dg4_graph_ensure_device
 
 // ---- structural encoding (dg4_kernels.hip) ----
 int dg4_launch_struct_encode(int dtype, int hidden, const void* x, const int32_t* feat, const float* emb, void* out,
@@ -129,7 +140,9 @@ struct dg4_sweep_args {
     uint16_t* kv;                          // [n, 512] by position: K | V of the final embeddings
     uint16_t* h_out;                       // [n, 256] by node id
     const void* wo_packed; const void* wkv_packed;   // pack_wt order
-    const void* ffn_packed;                // nullable: W1 | W2 of the feed-forward sub-block, dg4_launch_pack_ffn order (1 MB)
+    const void* ffn_packed;                // nullable: W1 | W2 of the feed-forward sub-block, dg4_launch_pack_ffn order (1 MB);
+                                           // the tile table then lists PAIRS (2k, 2k+1) of mutually independent tiles
+    uint16_t* park;                        // with ffn_packed: [workgroups, 16, 256] rows parked between the tiles of a pair
     const float* rel_bias;
     uint32_t* flags;                       // [n] by position: 1 = rows published
     uint32_t* ctrl;                        // [1] abort flag, [16..31] phase timers

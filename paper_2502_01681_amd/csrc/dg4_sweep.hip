@@ -29,6 +29,7 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <cstdlib>
 #include <type_traits>
 
 #include "dg4_device.h"
@@ -62,7 +63,7 @@ constexpr int SMEM_WOF = SMEM_BIAS + 128;                           // one Wo fr
 constexpr int SMEM_LAND = SMEM_WOF + 4096;
 constexpr int LAND_GATE = 8192, LAND_SELF = 6144, LAND_Q = 7168, LAND_X = 7680;
 constexpr int SMEM_BYTES = SMEM_LAND + TILE * LAND_GATE;
-static_assert(SMEM_BYTES <= 160 * 1024, "LDS budget");
+static_assert(SMEM_BYTES + 512 <= 160 * 1024, "LDS budget");
 static_assert(SMEM_LAND % 16 == 0 && SMEM_DESC % 16 == 0 && DESC_BYTES % 16 == 0, "alignment");
 
 typedef __bf16 bf16x2s __attribute__((ext_vector_type(2)));
@@ -127,6 +128,13 @@ __global__ void pack_wt_kernel(const uint16_t* w, int ld, int col0, int ntw, int
     const int k0 = ks * 32 + 8 * g;
 #pragma unroll
     for (int j = 0; j < 8; ++j) packed[unit * 8 + j] = w[(int64_t)(k0 + j) * ld + col];
+}
+
+// 16 bytes per lane from the lane's own global address, read at device scope (rows this compute
+// unit wrote earlier in the kernel: never served from a line its L1 may still hold)
+__device__ __forceinline__ void dma16_fresh(const void* src, uint32_t lds_base)
+{
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc1" : : "v"(src), "s"(uniform32(lds_base)) : "memory");
 }
 
 // The feed-forward weights in the order the sweep streams them (16-byte units). A tile's
@@ -407,13 +415,18 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     // (Dealing runs of consecutive tiles to one XCD, so that gates sharing a source share an L2, was
     // measured and is not worth it: 80 % of a tile's source rows are distinct already inside the
     // tile, 71 % inside 32 consecutive tiles.)
-    int64_t ticket = blockIdx.x;
+    // With the feed-forward sub-block tiles come in pairs (2k, 2k+1) that one workgroup runs back
+    // to back: workgroup b owns pairs b, b + G, ...; the table then holds an even number of tiles.
+    auto next_of = [&](int64_t t) __attribute__((always_inline)) -> int64_t {
+        return FFN ? ((t & 1) ? t + 2 * G - 1 : t + 1) : t + G;
+    };
+    int64_t ticket = FFN ? 2 * (int64_t)blockIdx.x : (int64_t)blockIdx.x;
     if (ticket >= p.n_tiles) return;
     // (tickets past the end are clamped: the fetch is harmless and its result unused)
     const int64_t last = p.n_tiles - 1;
     int d0 = 0, d1 = 1, d2 = 2;                   // descriptor buffers of this tile, the next one, the one after
     uint2 cur = tile_at(ticket);                                      // first position, rows
-    uint2 nxt = tile_at(ticket + G < last ? ticket + G : last);
+    uint2 nxt = tile_at(next_of(ticket) < last ? next_of(ticket) : last);
     uint64_t late = 0, need_cur = 0;              // sources of the current tile not gathered yet / all of them
     {
         gather_desc(cur.x, 0);
@@ -428,6 +441,11 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     }
     int64_t pub_p0 = 0;                           // rows 4*wave .. of the previous tile still to be published
     int pub_rows = 0;
+    int64_t pairA_p0 = 0;                         // feed-forward pairs: the first tile of the pair in progress ...
+    int pairA_rows = 0;
+    int64_t pairA_orig = 0;                       // ... and the node id of its gate `sub` (this lane's output row)
+    int64_t pubA_p0 = 0;                          // and of the finished pair, still to be published
+    int pubA_rows = 0;
 
     for (;;) {
         // keep the Wk|Wv tiles in the accumulation registers
@@ -438,7 +456,9 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 
         const int64_t p0 = cur.x;
         const int rows = (int)cur.y;
-        const bool has_next = ticket + G < p.n_tiles;
+        const bool has_next = next_of(ticket) < p.n_tiles;
+        const bool second = FFN && (ticket & 1) != 0;         // second tile of a feed-forward pair
+        const bool first = FFN && !second;
         roles();
 
         // ---------------- the previous tile's rows and this tile's gathers. Loads and stores of a
@@ -454,9 +474,11 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         auto publish = [&]() __attribute__((always_inline)) {
             if (lane < 4 && 4 * wave + lane < pub_rows)
                 __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (FFN && lane < 4 && 4 * wave + lane < pubA_rows)
+                __hip_atomic_store(&p.flags[pubA_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         };
         bool published = false;
-        if (TIMERS || p.eager_publish || late || pub_rows != TILE) {     // (the timed build has a barrier right below: flags first)
+        if (TIMERS || FFN || p.eager_publish || late || pub_rows != TILE) {     // (the timed build has a barrier right below: flags first)
             __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
             __asm__ volatile("" ::: "memory");
             publish();
@@ -471,7 +493,8 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (TIMERS) __syncthreads();          // timers only: charge every wave's wait to phase 1
         lap(1);
         // the descriptor two tiles ahead travels during the attention below
-        const uint2 nn = tile_at(ticket + 2 * G < last ? ticket + 2 * G : last);
+        const int64_t after_next = next_of(next_of(ticket));
+        const uint2 nn = tile_at(after_next < last ? after_next : last);
         gather_desc(nn.x, d2);
         // A first look at the flags of the NEXT tile's sources (its descriptor came in a round
         // ago). Loaded by every lane, needed or not; looked at after the first attention round.
@@ -649,6 +672,19 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (sAbort) { flush(); return; }
         lap(2);
         if (has_next) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
+        if (second) {
+            // the rows the first tile of the pair parked in global memory come back into the places
+            // of the gates' own K|V, which the attention has finished with (512 bytes a gate, each
+            // row shifted by 16 bytes against its neighbour's so that lanes of different gates hit
+            // different banks)
+#pragma unroll
+            for (int gq = 0; gq < 4; ++gq) {
+                const int g = 4 * wave + gq;
+                if (lane < 32)
+                    dma16_fresh(p.park + ((int64_t)blockIdx.x * TILE + g) * D + lane * 8,
+                                lds0 + (uint32_t)(SMEM_LAND + g * LAND_GATE + LAND_SELF + g * 16));
+            }
+        }
 
         // ---------------- output projection; lane (n = sub, g = grp) owns columns 64*wave + 16*g .. +15 of gate n
         roles();
@@ -714,132 +750,32 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 uint4* hp = (uint4*)(p.h_out + orig_n * D + c0);
                 hp[0] = ha; hp[1] = hb;
             }
+            if (first) {                      // parked until the second tile of the pair has come this far
+                uint4* pp = (uint4*)(p.park + ((int64_t)blockIdx.x * TILE + n) * D + c0);
+                pp[0] = ha; pp[1] = hb;
+            }
             uint4* hs = (uint4*)&sH[n][c0];
             hs[0] = ha; hs[1] = hb;
+        }
+        if (second) {                         // the parked rows have arrived (so have the next tile's sources so far)
+            __builtin_amdgcn_s_waitcnt(0x0F70);
+            __asm__ volatile("" ::: "memory");
         }
         __syncthreads();                      // sH complete; every wave has read its residual rows
         lap(4);
         roles();
-        // the landing zone of the gates' own rows is free now: the next tile's may come in
-        if (has_next) {
-            if ((int)nxt.y == TILE) gather_own_full(nxt.x, d1);
-            else gather_own(nxt.x, (int)nxt.y, d1);
-        }
+        // the landing zone of the gates' own rows is free now: the next tile's may come in (the
+        // second tile of a feed-forward pair still needs the space: see below)
+        auto gather_next_own = [&]() __attribute__((always_inline)) {
+            if (has_next) {
+                if ((int)nxt.y == TILE) gather_own_full(nxt.x, d1);
+                else gather_own(nxt.x, (int)nxt.y, d1);
+            }
+        };
+        if (!second) gather_next_own();
 
-        // ---------------- feed-forward sub-block (Section 3.5 keeps the transformer structure around
-        // the attention): h <- LN(h + max(h W1, 0) W2), h = the rows in sH. The megabyte of W1 | W2
-        // fits neither the registers nor LDS next to everything else, so it is streamed from the
-        // L2 cache, every wave its own contiguous stream, through a ring of RING fragments that
-        // are requested RING products before the matrix cores need them. Per pass of 256 hidden units:
-        // every wave forms 64 of the activations (transposed, so that a lane ends up with four
-        // consecutive hidden units of one gate), they are exchanged through the idle attention
-        // buffer, and every wave adds the pass's part of its own 64 output columns.
-        if constexpr (FFN) {
-            // (Measured on the 1M-gate workload: the stream runs at about 78 GB/s per compute unit,
-            // 19 TB/s over the chip, nearly all L2 hits, and is what bounds the phase: with the
-            // loads taken out the phase costs a third. A deeper ring changes nothing but spills.)
-            constexpr int RING = 8;
-            static_assert(FFN_FRAGS % RING == 0, "ring slots repeat from pass to pass");
-            const uint4* wp = (const uint4*)p.ffn_packed + (int64_t)wave * (FFN_PASSES * FFN_FRAGS * 64) + lane;
-            u32x4 ring[RING];
-            static_for<0, RING>([&](auto I) __attribute__((always_inline)) { ring[I.value] = __builtin_bit_cast(u32x4, wp[I.value * 64]); });
-            f32x4 out[4];
-            uint16_t (*sU)[LDS_STRIDE] = sA;
-#pragma unroll 1
-            for (int pass = 0; pass < FFN_PASSES; ++pass) {
-                const uint4* wq = wp + (int64_t)pass * (FFN_FRAGS * 64);
-                const bool more = pass + 1 < FFN_PASSES;
-                f32x4 u[4];
-                // activations of hidden units 256*pass + 64*wave .. +63, transposed
-                // (the tile's operand of the next group of four products is read from LDS while
-                // this group runs: with one wave per SIMD nothing else hides that latency)
-                {
-                    uint4 b_cur = *(const uint4*)&sH[n][8 * grp];
-                    static_for<0, 8>([&](auto KS) __attribute__((always_inline)) {
-                        constexpr int ks = KS.value;
-                        uint4 b_nxt = b_cur;
-                        if (ks + 1 < 8) b_nxt = *(const uint4*)&sH[n][8 * grp + (ks + 1) * 32];
-#pragma unroll
-                        for (int ht = 0; ht < 4; ++ht) {
-                            const int j = 4 * ks + ht, slot = j % RING;
-                            u[ht] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : u[ht]);
-                            ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        b_cur = b_nxt;
-                    });
-                }
-                if (pass) {                       // the previous pass has been read by every wave
-                    __builtin_amdgcn_s_waitcnt(0xC07F);
-                    __asm__ volatile("" ::: "memory");
-                    __builtin_amdgcn_s_barrier();
-                    __asm__ volatile("" ::: "memory");
-                }
-#pragma unroll
-                for (int ht = 0; ht < 4; ++ht)
-                    *(uint2*)&sU[n][64 * wave + 16 * ht + 4 * grp] =
-                        make_uint2(pack_bf16x2(fmaxf(u[ht][0], 0.f), fmaxf(u[ht][1], 0.f)), pack_bf16x2(fmaxf(u[ht][2], 0.f), fmaxf(u[ht][3], 0.f)));
-                __builtin_amdgcn_s_waitcnt(0xC07F);
-                __asm__ volatile("" ::: "memory");
-                __builtin_amdgcn_s_barrier();
-                __asm__ volatile("" ::: "memory");
-                // this pass's part of output columns 64*wave + 16*grp .. +15
-                {
-                    uint4 b_cur = *(const uint4*)&sU[n][8 * grp];
-                    static_for<0, 8>([&](auto KK) __attribute__((always_inline)) {
-                        constexpr int kk = KK.value;
-                        uint4 b_nxt = b_cur;
-                        if (kk + 1 < 8) b_nxt = *(const uint4*)&sU[n][8 * grp + (kk + 1) * 32];
-#pragma unroll
-                        for (int ct = 0; ct < 4; ++ct) {
-                            const int j = 32 + 4 * kk + ct, slot = j % RING;
-                            out[ct] = mfma16(__builtin_bit_cast(uint4, ring[slot]), b_cur, (pass == 0 && kk == 0) ? (f32x4){0.f, 0.f, 0.f, 0.f} : out[ct]);
-                            if (j + RING < FFN_FRAGS || more)         // (past the end of this pass: the first fragments of the next)
-                                ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                        b_cur = b_nxt;
-                    });
-                }
-            }
-            // residual (the rows in sH, this lane's own 16 columns), LayerNorm, the new rows
-            {
-                float h1[16];
-                const uint4* hp = (const uint4*)&sH[n][c0];
-                Elem<bf16_t>::unpack(hp[0], hp[1], h1);
-#pragma unroll
-                for (int ct = 0; ct < 4; ++ct)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) t[ct * 4 + i] = out[ct][i] + h1[ct * 4 + i];
-            }
-            float s1 = 0.f, s2 = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { s1 += t[i]; s2 = fmaf(t[i], t[i], s2); }
-            s1 = sum_rows(s1); s2 = sum_rows(s2);
-            __syncthreads();                  // every wave is done with the activations and with sH as an operand
-            if (grp == 0) { sRed[n][wave][0] = s1; sRed[n][wave][1] = s2; }
-            __syncthreads();
-            float a1 = 0.f, a2 = 0.f;
-#pragma unroll
-            for (int w2 = 0; w2 < 4; ++w2) { a1 += sRed[n][w2][0]; a2 += sRed[n][w2][1]; }
-            const float mean = a1 * (1.0f / D);
-            const float var = fmaxf(a2 * (1.0f / D) - mean * mean, 0.f);
-            const float rstd = rsqrtf(var + p.ln_eps);
-#pragma unroll
-            for (int i = 0; i < 16; ++i) t[i] = (t[i] - mean) * rstd;
-            uint4 ha, hb;
-            Elem<bf16_t>::pack(t, ha, hb);
-            if (nvalid) {
-                uint4* hp = (uint4*)(p.h_out + orig_n * D + c0);
-                hp[0] = ha; hp[1] = hb;
-            }
-            uint4* hs = (uint4*)&sH[n][c0];
-            hs[0] = ha; hs[1] = hb;
-            __syncthreads();                  // sH holds the final embeddings
-        }
-
-        // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
-        {
+        // K|V projection of the rows in sH, out through LDS as 512-byte device-scope stores
+        auto kv_out = [&](int64_t q0, int nrows) __attribute__((always_inline)) {
             f32x4 acc[8];
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) {
@@ -862,27 +798,197 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = 4 * wave + rr;
-                if (r < rows) {
-                    uint64_t* gp = (uint64_t*)(p.kv + (p0 + r) * (2 * D));
+                if (r < nrows) {
+                    uint64_t* gp = (uint64_t*)(p.kv + (q0 + r) * (2 * D));
                     const uint64_t* lp = (const uint64_t*)&sKV[r][0];
                     __hip_atomic_store(gp + lane, lp[lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     __hip_atomic_store(gp + 64 + lane, lp[64 + lane], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
+            __syncthreads();                  // sKV has been read; sA and sH may be written again
+        };
+
+        if constexpr (!FFN) {
+            // ---------------- K|V projection of the new embeddings: lane owns columns 128*wave + 32*g .. +31
+            kv_out(p0, rows);
+            lap(5);
+            pub_p0 = p0; pub_rows = rows;
+        } else if (first) {
+            // first tile of a pair: its rows are parked, the rest of its work happens with the second tile
+            pairA_p0 = p0; pairA_rows = rows; pairA_orig = orig_n;
+            pub_rows = 0; pubA_rows = 0;
+        } else {
+            // ---------------- feed-forward sub-block (Section 3.5 keeps the transformer structure around
+            // the attention): h <- LN(h + max(h W1, 0) W2) for the 32 gates of the pair, tile A's rows
+            // in the landing zone (own-K|V places), tile B's in sH. The megabyte of W1 | W2 fits
+            // neither the registers nor LDS next to everything else, so it is streamed from the L2
+            // cache, every wave its own contiguous stream, through a ring of RING fragments that
+            // are requested RING products before the matrix cores need them; running two tiles
+            // through one pass halves that stream, which is what bounds the phase (about 75 GB/s
+            // per compute unit, whatever the depth of the ring). Per pass of 256 hidden units:
+            // every wave forms 64 of the activations of both tiles (transposed, so that a lane ends
+            // up with four consecutive hidden units of one gate), they are exchanged through LDS
+            // (tile B: the idle attention buffer, tile A: the idle own-Q / residual places of the
+            // landing zone), and every wave adds the pass's part of its own 64 output columns.
+            constexpr int RING = 8;
+            static_assert(FFN_FRAGS % RING == 0, "ring slots repeat from pass to pass");
+            const uint4* wp = (const uint4*)p.ffn_packed + (int64_t)wave * (FFN_PASSES * FFN_FRAGS * 64) + lane;
+            u32x4 ring[RING];
+            static_for<0, RING>([&](auto I) __attribute__((always_inline)) { ring[I.value] = __builtin_bit_cast(u32x4, wp[I.value * 64]); });
+            uint16_t (*sU)[LDS_STRIDE] = sA;
+            const unsigned char* hA = sLand + n * (LAND_GATE + 16) + LAND_SELF;       // tile A: input rows
+            unsigned char* uAp = sLand + n * (LAND_GATE + 16) + LAND_Q;               // tile A: activations of a pass
+            f32x4 outA[4], outB[4];
+#pragma unroll 1
+            for (int pass = 0; pass < FFN_PASSES; ++pass) {
+                const uint4* wq = wp + (int64_t)pass * (FFN_FRAGS * 64);
+                const bool more = pass + 1 < FFN_PASSES;
+                f32x4 uA[4], uB[4];
+                // activations of hidden units 256*pass + 64*wave .. +63, transposed
+                // (the tiles' operands of the next group of products are read from LDS while
+                // this group runs: with one wave per SIMD nothing else hides that latency)
+                {
+                    uint4 a_cur = *(const uint4*)(hA + 16 * grp);
+                    uint4 b_cur = *(const uint4*)&sH[n][8 * grp];
+                    static_for<0, 8>([&](auto KS) __attribute__((always_inline)) {
+                        constexpr int ks = KS.value;
+                        uint4 a_nxt = a_cur, b_nxt = b_cur;
+                        if (ks + 1 < 8) {
+                            a_nxt = *(const uint4*)(hA + 16 * grp + (ks + 1) * 64);
+                            b_nxt = *(const uint4*)&sH[n][8 * grp + (ks + 1) * 32];
+                        }
+#pragma unroll
+                        for (int ht = 0; ht < 4; ++ht) {
+                            const int j = 4 * ks + ht, slot = j % RING;
+                            const uint4 frag = __builtin_bit_cast(uint4, ring[slot]);
+                            uA[ht] = mfma16(frag, a_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : uA[ht]);
+                            uB[ht] = mfma16(frag, b_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : uB[ht]);
+                            ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        a_cur = a_nxt; b_cur = b_nxt;
+                    });
+                }
+                if (pass) {                       // the previous pass has been read by every wave
+                    __asm__ volatile("" ::: "memory");
+                    __builtin_amdgcn_s_waitcnt(0xC07F);
+                    __builtin_amdgcn_s_barrier();
+                    __asm__ volatile("" ::: "memory");
+                }
+#pragma unroll
+                for (int ht = 0; ht < 4; ++ht) {
+                    *(uint2*)(uAp + (64 * wave + 16 * ht + 4 * grp) * 2) =
+                        make_uint2(pack_bf16x2(fmaxf(uA[ht][0], 0.f), fmaxf(uA[ht][1], 0.f)), pack_bf16x2(fmaxf(uA[ht][2], 0.f), fmaxf(uA[ht][3], 0.f)));
+                    *(uint2*)&sU[n][64 * wave + 16 * ht + 4 * grp] =
+                        make_uint2(pack_bf16x2(fmaxf(uB[ht][0], 0.f), fmaxf(uB[ht][1], 0.f)), pack_bf16x2(fmaxf(uB[ht][2], 0.f), fmaxf(uB[ht][3], 0.f)));
+                }
+                __asm__ volatile("" ::: "memory");
+                __builtin_amdgcn_s_waitcnt(0xC07F);
+                __builtin_amdgcn_s_barrier();
+                __asm__ volatile("" ::: "memory");
+                // this pass's part of output columns 64*wave + 16*grp .. +15
+                {
+                    uint4 a_cur = *(const uint4*)(uAp + 16 * grp);
+                    uint4 b_cur = *(const uint4*)&sU[n][8 * grp];
+                    static_for<0, 8>([&](auto KK) __attribute__((always_inline)) {
+                        constexpr int kk = KK.value;
+                        uint4 a_nxt = a_cur, b_nxt = b_cur;
+                        if (kk + 1 < 8) {
+                            a_nxt = *(const uint4*)(uAp + 16 * grp + (kk + 1) * 64);
+                            b_nxt = *(const uint4*)&sU[n][8 * grp + (kk + 1) * 32];
+                        }
+#pragma unroll
+                        for (int ct = 0; ct < 4; ++ct) {
+                            const int j = 32 + 4 * kk + ct, slot = j % RING;
+                            const uint4 frag = __builtin_bit_cast(uint4, ring[slot]);
+                            outA[ct] = mfma16(frag, a_cur, (pass == 0 && kk == 0) ? (f32x4){0.f, 0.f, 0.f, 0.f} : outA[ct]);
+                            outB[ct] = mfma16(frag, b_cur, (pass == 0 && kk == 0) ? (f32x4){0.f, 0.f, 0.f, 0.f} : outB[ct]);
+                            if (j + RING < FFN_FRAGS || more)         // (past the end of this pass: the first fragments of the next)
+                                ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+                        a_cur = a_nxt; b_cur = b_nxt;
+                    });
+                }
+            }
+            // residual (this lane's own 16 columns of its gate), LayerNorm, the new rows: both tiles
+            float tA[16];
+            {
+                float h1[16];
+                const uint4* hp = (const uint4*)&sH[n][c0];
+                Elem<bf16_t>::unpack(hp[0], hp[1], h1);
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) t[ct * 4 + i] = outB[ct][i] + h1[ct * 4 + i];
+                const uint4* ap = (const uint4*)(hA + c0 * 2);
+                Elem<bf16_t>::unpack(ap[0], ap[1], h1);
+#pragma unroll
+                for (int ct = 0; ct < 4; ++ct)
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) tA[ct * 4 + i] = outA[ct][i] + h1[ct * 4 + i];
+            }
+            float s1 = 0.f, s2 = 0.f, r1 = 0.f, r2 = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { s1 += t[i]; s2 = fmaf(t[i], t[i], s2); r1 += tA[i]; r2 = fmaf(tA[i], tA[i], r2); }
+            s1 = sum_rows(s1); s2 = sum_rows(s2); r1 = sum_rows(r1); r2 = sum_rows(r2);
+            float (*sRedA)[4][2] = (float (*)[4][2])(smem + SMEM_BYTES);
+            __syncthreads();                  // every wave is done with the activations and with the input rows as operands
+            if (grp == 0) { sRed[n][wave][0] = s1; sRed[n][wave][1] = s2; sRedA[n][wave][0] = r1; sRedA[n][wave][1] = r2; }
+            __syncthreads();
+            // the landing zone is free for good now
+            gather_next_own();
+            uint4 hB0, hB1;
+            {
+                float a1 = 0.f, a2 = 0.f, b1 = 0.f, b2 = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < 4; ++w2) { a1 += sRed[n][w2][0]; a2 += sRed[n][w2][1]; b1 += sRedA[n][w2][0]; b2 += sRedA[n][w2][1]; }
+                float mean = a1 * (1.0f / D);
+                float rstd = rsqrtf(fmaxf(a2 * (1.0f / D) - mean * mean, 0.f) + p.ln_eps);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) t[i] = (t[i] - mean) * rstd;
+                Elem<bf16_t>::pack(t, hB0, hB1);
+                if (nvalid) {
+                    uint4* hp = (uint4*)(p.h_out + orig_n * D + c0);
+                    hp[0] = hB0; hp[1] = hB1;
+                }
+                mean = b1 * (1.0f / D);
+                rstd = rsqrtf(fmaxf(b2 * (1.0f / D) - mean * mean, 0.f) + p.ln_eps);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) tA[i] = (tA[i] - mean) * rstd;
+                uint4 hA0, hA1;
+                Elem<bf16_t>::pack(tA, hA0, hA1);
+                if (n < pairA_rows) {
+                    uint4* hp = (uint4*)(p.h_out + pairA_orig * D + c0);
+                    hp[0] = hA0; hp[1] = hA1;
+                }
+                uint4* hs = (uint4*)&sH[n][c0];
+                hs[0] = hA0; hs[1] = hA1;
+            }
+            __syncthreads();                  // sH holds the final embeddings of tile A
+            kv_out(pairA_p0, pairA_rows);
+            {
+                uint4* hs = (uint4*)&sH[n][c0];
+                hs[0] = hB0; hs[1] = hB1;
+            }
+            __syncthreads();                  // ... of tile B
+            kv_out(p0, rows);
+            lap(5);
+            pub_p0 = p0; pub_rows = rows;
+            pubA_p0 = pairA_p0; pubA_rows = pairA_rows;
         }
-        __syncthreads();                      // sKV has been read; sA may be written again
-        lap(5);
-        pub_p0 = p0; pub_rows = rows;
 
         if (!has_next) {
             __builtin_amdgcn_s_waitcnt(0x0F70);
             __asm__ volatile("" ::: "memory");
             if (lane < 4 && 4 * wave + lane < pub_rows)
                 __hip_atomic_store(&p.flags[pub_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (FFN && lane < 4 && 4 * wave + lane < pubA_rows)
+                __hip_atomic_store(&p.flags[pubA_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             flush();
             return;
         }
-        ticket += G;
+        ticket = next_of(ticket);
         { const int t = d0; d0 = d1; d1 = d2; d2 = t; }
         cur = nxt; nxt = nn;
         need_cur = need_nxt; late = need_nxt & ~up_nxt;
@@ -920,7 +1026,12 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
-    int64_t grid = cus;                // one workgroup per compute unit: its registers and LDS hold the weights
+    int64_t grid = std::min<int64_t>(cus, DG4_MAX_SWEEP_GROUPS);   // one workgroup per compute unit: its registers and LDS hold the weights
+    if (const char* e = getenv("DG4_SWEEP_GRID")) grid = std::min<int64_t>(grid, std::max<int64_t>(1, atoll(e)));
+    if (a.ffn_packed) {
+        if ((a.n_tiles & 1) || !a.park) return hipErrorInvalidValue;      // whole pairs only
+        if (grid > a.n_tiles / 2) grid = a.n_tiles / 2;
+    }
     if (grid > a.n_tiles) grid = a.n_tiles;
     void (*kern)(dg4_sweep_args) = nullptr;            // the LDS landing zone is laid out for cones of two hops
     if (a.ell_w == 8) {
@@ -928,9 +1039,10 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
         else kern = a.prof ? sweep_kernel<8, true, false> : sweep_kernel<8, false, false>;
     }
     if (!kern) return hipErrorInvalidValue;
-    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, SMEM_BYTES);
+    const int smem = SMEM_BYTES + (a.ffn_packed ? 512 : 0);      // pairs: a second LayerNorm exchange area
+    hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), SMEM_BYTES, s, a);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), smem, s, a);
     return hipGetLastError();
 }
 

@@ -81,6 +81,28 @@ def test_dataflow_order_is_a_valid_schedule(name, n_and, hops, hint):
     assert (g2.array("flow_order") == order).all()
 
 
+@pytest.mark.parametrize("name,n_and,hint", [("tiny", None, False), ("medium", 30_000, False), ("large", 40_000, True)])
+def test_pair_order_is_a_valid_schedule(name, n_and, hint):
+    # the order of sweeps with the feed-forward sub-block: tiles in pairs (2k, 2k+1), at most 16 gates
+    # each, the second possibly empty; every gate of a neighbour row in a strictly earlier PAIR
+    w = synth.make(name, n_and=n_and, features=False)
+    n = w.cfg.n_nodes
+    g = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, 2, w.level_hint if hint else None)
+    order, tp = g.array("pair_order"), g.array("pair_tile_ptr")
+    assert sorted(order.tolist()) == list(range(n))
+    assert tp[0] == 0 and tp[-1] == n and (len(tp) - 1) % 2 == 0
+    rows = np.diff(tp)
+    assert rows.min() >= 0 and rows.max() <= 16
+    assert (rows[0::2] >= 1).all()                         # only a second tile may be empty ...
+    assert (rows[1::2][rows[0::2] < 16] == 0).all()        # ... and is, unless the first one is full
+    pair_of = np.empty(n, dtype=np.int64)
+    pair_of[order] = np.repeat(np.arange(len(rows)), rows) // 2
+    ptr, idx = g.array("nbr_ptr"), g.array("nbr_idx")
+    dst = np.repeat(np.arange(n), np.diff(ptr))
+    other = idx != dst
+    assert (pair_of[idx[other]] < pair_of[dst[other]]).all()
+
+
 @pytest.mark.parametrize("name,n_and", [("tiny", None), ("small", None), ("large", 40_000)])
 def test_fanout_counts_of_the_structural_encoding(name, n_and):
     # OutAND / OutNOT of Eq. 2, bit for bit against the oracle; also on a graph with in-degree-1 nodes
