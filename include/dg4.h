@@ -231,7 +231,7 @@ int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const v
  * kernel's bounded dependency wait (0 = the sweep ran to completion) and, if
  * the environment variable DG4_SWEEP_PROFILE was set during that call, eight
  * per-phase timers in 10 ns ticks summed over workgroups: tiles with a late source (a count), dependency
- * wait, attention, output projection, LayerNorm, K|V projection, publish, 0.
+ * wait, attention, output projection, LayerNorm, K|V projection, publish, feed-forward sub-block.
  */
 int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace,
                       uint64_t* ticks8, uint32_t* aborted);

@@ -140,7 +140,8 @@ __device__ __forceinline__ void dma16_fresh(const void* src, uint32_t lds_base)
 // The feed-forward weights in the order the sweep streams them (16-byte units). A tile's
 // sub-block runs in FFN_PASSES passes of 256 hidden units; in a pass wave w first forms the
 // activations of its 64 hidden units (A operand: a 16 x 32 piece of W1 transposed, hidden unit
-// 256*pass + 64*w + 16*ht + m against inputs 32*ks + 8*g .. +7; fragment 4*ks + ht), then adds
+// 256*pass + 64*w + 16*ht + m against inputs 32*ks + 8*g .. +7; fragment 16*(ht/2) + 2*ks + ht%2:
+// the wave works through its 64 units in two halves of 32), then adds
 // the pass's contribution to its 64 output columns (A operand: a piece of W2 transposed, output
 // column 64*w + 16*(m/4) + 4*ct + m%4, the same column ownership as the output projection,
 // against hidden units 256*pass + 32*kk + 8*g .. +7; fragment 32 + 4*kk + ct). Unit
@@ -157,7 +158,7 @@ __global__ void pack_ffn_kernel(const uint16_t* w1, const uint16_t* w2, uint16_t
     const int w = (int)(unit >> 14);
     const int m = lane & 15, g = lane >> 4;
     if (j < 32) {
-        const int ks = j >> 2, ht = j & 3;
+        const int ks = (j & 15) >> 1, ht = 2 * (j >> 4) + (j & 1);
         const int hidden = 256 * pass + 64 * w + 16 * ht + m;
         const int k0 = 32 * ks + 8 * g;
 #pragma unroll
@@ -270,10 +271,14 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     {
         const uint4* wo = (const uint4*)p.wo_packed + (int64_t)wave * 4 * 8 * 64 + lane;
         const uint4* wkv = (const uint4*)p.wkv_packed + (int64_t)wave * 8 * 8 * 64 + lane;
+        // (with the feed-forward sub-block Wo is fetched anew for every tile, at the end of the
+        // attention: the sub-block needs the registers; only its last fragment, which sits in LDS, is
+        // read here)
 #pragma unroll
         for (int nt = 0; nt < 4; ++nt)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) wo_r[nt][ks] = __builtin_bit_cast(u32x4, wo[(nt * 8 + ks) * 64]);
+            for (int ks = 0; ks < 8; ++ks)
+                if (!FFN || (nt == 3 && ks == 7)) wo_r[nt][ks] = __builtin_bit_cast(u32x4, wo[(nt * 8 + ks) * 64]);
 #pragma unroll
         for (int nt = 0; nt < 8; ++nt)
 #pragma unroll
@@ -478,11 +483,18 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 __hip_atomic_store(&p.flags[pubA_p0 + 4 * wave + lane], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         };
         bool published = false;
-        if (TIMERS || FFN || p.eager_publish || late || pub_rows != TILE) {     // (the timed build has a barrier right below: flags first)
+        // (a finished pair leaves sixteen row stores behind; the second tile of a pair has nothing
+        // to publish but must see its own rows, which were requested last)
+        const bool may_defer = !TIMERS && !p.eager_publish && !late &&
+                               (FFN ? first && pub_rows == TILE && pubA_rows == TILE : pub_rows == TILE);
+        if (!may_defer) {                     // (the timed build has a barrier right below: flags first)
             __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0), expcnt and lgkmcnt untouched
             __asm__ volatile("" ::: "memory");
             publish();
             published = true;
+        } else if (FFN) {
+            __builtin_amdgcn_s_waitcnt(0x4F70);       // vmcnt(16)
+            __asm__ volatile("" ::: "memory");
         } else {
             __builtin_amdgcn_s_waitcnt(0x0F78);       // vmcnt(8)
             __asm__ volatile("" ::: "memory");
@@ -505,6 +517,23 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             nneed = my < (int)nxt.y && nent != DG4_ELL_PAD && (nent >> 30) != 0;
         }
         look_async(nent, nneed, 0);
+        if constexpr (FFN) {
+            // Wo for this tile's output projection (the feed-forward sub-block needs its registers
+            // in between, so it is not kept). Requested here, before any of the tile's transfers:
+            // the loads are complete at the wait after the first attention pass, which the compiler
+            // sees, and nothing further down waits on vector memory because of them. (The address
+            // goes through an opaque copy: the loads must stay inside the loop; and it is typed as
+            // global memory again, or the loads would be flat ones.)
+            uint64_t wa = (uint64_t)(uintptr_t)((const uint4*)p.wo_packed + (int64_t)wave * 4 * 8 * 64 + lane);
+            __asm__ volatile("" : "+v"(wa));
+            const __attribute__((address_space(1))) u32x4* wl = (const __attribute__((address_space(1))) u32x4*)wa;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+                for (int nt = 0; nt < 4; ++nt)
+                    if (!(nt == 3 && ks == 7)) wo_r[nt][ks] = wl[(nt * 8 + ks) * 64];
+            __builtin_amdgcn_sched_barrier(0);
+        }
         uint64_t need_nxt = 0, up_nxt = 0;
         uint32_t nslot = 0;
         uint32_t keep_lo = 0, keep_hi = 0;
@@ -843,11 +872,18 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             for (int pass = 0; pass < FFN_PASSES; ++pass) {
                 const uint4* wq = wp + (int64_t)pass * (FFN_FRAGS * 64);
                 const bool more = pass + 1 < FFN_PASSES;
-                f32x4 uA[4], uB[4];
-                // activations of hidden units 256*pass + 64*wave .. +63, transposed
-                // (the tiles' operands of the next group of products are read from LDS while
-                // this group runs: with one wave per SIMD nothing else hides that latency)
-                {
+                // Activations of hidden units 256*pass + 64*wave .. +63, transposed, 32 units at a time
+                // (registers). The tiles' operands of the next group of products are read from LDS
+                // while this group runs: with one wave per SIMD nothing else hides that latency.
+                if (pass) {                       // the previous pass's activations have been read by every wave
+                    __asm__ volatile("" ::: "memory");
+                    __builtin_amdgcn_s_waitcnt(0xC07F);
+                    __builtin_amdgcn_s_barrier();
+                    __asm__ volatile("" ::: "memory");
+                }
+                static_for<0, 2>([&](auto HALF) __attribute__((always_inline)) {
+                    constexpr int half = HALF.value;
+                    f32x4 uA[2], uB[2];
                     uint4 a_cur = *(const uint4*)(hA + 16 * grp);
                     uint4 b_cur = *(const uint4*)&sH[n][8 * grp];
                     static_for<0, 8>([&](auto KS) __attribute__((always_inline)) {
@@ -858,30 +894,25 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                             b_nxt = *(const uint4*)&sH[n][8 * grp + (ks + 1) * 32];
                         }
 #pragma unroll
-                        for (int ht = 0; ht < 4; ++ht) {
-                            const int j = 4 * ks + ht, slot = j % RING;
+                        for (int h2 = 0; h2 < 2; ++h2) {
+                            const int j = 16 * half + 2 * ks + h2, slot = j % RING;
                             const uint4 frag = __builtin_bit_cast(uint4, ring[slot]);
-                            uA[ht] = mfma16(frag, a_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : uA[ht]);
-                            uB[ht] = mfma16(frag, b_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : uB[ht]);
+                            uA[h2] = mfma16(frag, a_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : uA[h2]);
+                            uB[h2] = mfma16(frag, b_cur, ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : uB[h2]);
                             ring[slot] = __builtin_bit_cast(u32x4, wq[(j + RING) * 64]);
                         }
                         __builtin_amdgcn_sched_barrier(0);
                         a_cur = a_nxt; b_cur = b_nxt;
                     });
-                }
-                if (pass) {                       // the previous pass has been read by every wave
-                    __asm__ volatile("" ::: "memory");
-                    __builtin_amdgcn_s_waitcnt(0xC07F);
-                    __builtin_amdgcn_s_barrier();
-                    __asm__ volatile("" ::: "memory");
-                }
 #pragma unroll
-                for (int ht = 0; ht < 4; ++ht) {
-                    *(uint2*)(uAp + (64 * wave + 16 * ht + 4 * grp) * 2) =
-                        make_uint2(pack_bf16x2(fmaxf(uA[ht][0], 0.f), fmaxf(uA[ht][1], 0.f)), pack_bf16x2(fmaxf(uA[ht][2], 0.f), fmaxf(uA[ht][3], 0.f)));
-                    *(uint2*)&sU[n][64 * wave + 16 * ht + 4 * grp] =
-                        make_uint2(pack_bf16x2(fmaxf(uB[ht][0], 0.f), fmaxf(uB[ht][1], 0.f)), pack_bf16x2(fmaxf(uB[ht][2], 0.f), fmaxf(uB[ht][3], 0.f)));
-                }
+                    for (int h2 = 0; h2 < 2; ++h2) {
+                        const int col = 64 * wave + 32 * half + 16 * h2 + 4 * grp;
+                        *(uint2*)(uAp + col * 2) =
+                            make_uint2(pack_bf16x2(fmaxf(uA[h2][0], 0.f), fmaxf(uA[h2][1], 0.f)), pack_bf16x2(fmaxf(uA[h2][2], 0.f), fmaxf(uA[h2][3], 0.f)));
+                        *(uint2*)&sU[n][col] =
+                            make_uint2(pack_bf16x2(fmaxf(uB[h2][0], 0.f), fmaxf(uB[h2][1], 0.f)), pack_bf16x2(fmaxf(uB[h2][2], 0.f), fmaxf(uB[h2][3], 0.f)));
+                    }
+                });
                 __asm__ volatile("" ::: "memory");
                 __builtin_amdgcn_s_waitcnt(0xC07F);
                 __builtin_amdgcn_s_barrier();
@@ -966,6 +997,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 hs[0] = hA0; hs[1] = hA1;
             }
             __syncthreads();                  // sH holds the final embeddings of tile A
+            lap(7);
             kv_out(pairA_p0, pairA_rows);
             {
                 uint4* hs = (uint4*)&sH[n][c0];
