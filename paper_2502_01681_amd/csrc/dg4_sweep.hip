@@ -859,7 +859,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             // up with four consecutive hidden units of one gate), they are exchanged through LDS
             // (tile B: the idle attention buffer, tile A: the idle own-Q / residual places of the
             // landing zone), and every wave adds the pass's part of its own 64 output columns.
-            constexpr int RING = 8;
+            constexpr int RING = 16;
             static_assert(FFN_FRAGS % RING == 0, "ring slots repeat from pass to pass");
             const uint4* wp = (const uint4*)p.ffn_packed + (int64_t)wave * (FFN_PASSES * FFN_FRAGS * 64) + lane;
             u32x4 ring[RING];
