@@ -97,7 +97,7 @@ int dg4_build_levels(int64_t n_nodes, int64_t n_edges,
  * level_hint (nullable) are device pointers. Levels are found in rounds over the fanin table (a gate
  * is finished one round after its fanins), the (level, id) order by a stable sort, each cone row by a
  * backward search from its gate. Every table of the resulting graph equals the host call's bit for
- * bit. Synchronous: waits on `stream`; temporary device memory (about 130 bytes per node) is
+ * bit. Synchronous: waits on `stream`; temporary device memory (about 160 bytes per node and 5 per neighbour entry) is
  * allocated and released inside the call, and the tables are copied to host memory, where the graph
  * object keeps them. Errors as dg4_build_levels; if an edge list has defects of several kinds, the
  * kind reported may differ from the host call's (which reports the first in edge order), and an

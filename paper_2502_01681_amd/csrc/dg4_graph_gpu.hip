@@ -90,9 +90,10 @@ __global__ void hint_check_kernel(int64_t n, const int32_t* fin, const int32_t* 
 __global__ void iota_max_kernel(int64_t n, const int32_t* level, int32_t* ids, int32_t* max_level)
 {
     const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v >= n) return;
-    ids[v] = (int32_t)v;
-    atomicMax(max_level, level[v]);
+    int32_t m = 0;
+    if (v < n) { ids[v] = (int32_t)v; m = level[v]; }
+    for (int off = 32; off > 0; off >>= 1) m = max(m, __shfl_xor(m, off));     // one atomic per wave
+    if ((threadIdx.x & 63) == 0) atomicMax(max_level, m);
 }
 
 // level_ptr[l] = first position whose level is >= l, l = 0 .. max_level + 1 (binary search in the sorted keys)
@@ -173,17 +174,29 @@ __global__ void add_inverter_kernel(int64_t n, int32_t* out_not, const uint8_t* 
     if (v < n) out_not[v] += inverter[v];
 }
 
-// device allocations of one call, released when it returns
+// Device memory of one call: carved out of at most two allocations (the tables sized by the node
+// count, then those sized by the number of neighbour entries), released when the call returns.
 struct Arena {
     std::vector<void*> blocks;
+    char* cur = nullptr;
+    size_t left = 0;
     ~Arena() { for (void* p : blocks) (void)hipFree(p); }
-    template <typename T> T* get(size_t count, bool zero, hipStream_t s)
+    bool reserve(size_t bytes)
     {
         void* p = nullptr;
-        if (hipMalloc(&p, std::max<size_t>(count, 1) * sizeof(T)) != hipSuccess) return nullptr;
+        if (hipMalloc(&p, bytes + 256) != hipSuccess) return false;
         blocks.push_back(p);
-        if (zero && hipMemsetAsync(p, 0, std::max<size_t>(count, 1) * sizeof(T), s) != hipSuccess) return nullptr;
-        return (T*)p;
+        cur = (char*)p; left = bytes + 256;
+        return true;
+    }
+    template <typename T> T* get(size_t count, bool zero, hipStream_t s)
+    {
+        const size_t bytes = (std::max<size_t>(count, 1) * sizeof(T) + 255) & ~(size_t)255;
+        if (bytes > left && !reserve(bytes)) return nullptr;
+        T* p = (T*)cur;
+        cur += bytes; left -= bytes;
+        if (zero && hipMemsetAsync(p, 0, bytes, s) != hipSuccess) return nullptr;
+        return p;
     }
 };
 
@@ -211,6 +224,9 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
             return DG4_OK;
         }
         Arena arena;
+        // everything sized by the node count in one allocation (about 140 bytes a node, plus the
+        // sort's and the scan's own scratch, which are small)
+        if (!arena.reserve((size_t)n * 160 + (16u << 20))) return DG4_ENOMEM;
         GPU_ALLOC(fin, int32_t, 2 * (size_t)n, false);
         GPU_ALLOC(finv, uint8_t, 2 * (size_t)n, true);
         GPU_ALLOC(deg, int32_t, (size_t)n, true);
@@ -285,6 +301,7 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
         GPU_CHECK(hipMemcpyAsync(&nnz, nbr_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
         GPU_CHECK(hipStreamSynchronize(s));
         g->nnz = nnz;
+        if (!arena.reserve((size_t)nnz * 5 + 1024)) return DG4_ENOMEM;
         GPU_ALLOC(nbr_idx, int32_t, (size_t)nnz, false);
         GPU_ALLOC(nbr_rel, uint8_t, (size_t)nnz, false);
         hipLaunchKernelGGL(compact_kernel, dim3(nb), dim3(256), 0, s, n, row_id, row_rel, nbr_ptr, nbr_idx, nbr_rel);
