@@ -236,38 +236,59 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
         orow[i] = ok[i] ? r : p.row_end - 1;
     }
 
+    // The packed weight is one linear stream of 16-byte-per-lane fragments (tile nt, chunk c at
+    // nt*KC + c). It is read through a ring of RING fragments requested RING products ahead:
+    // with 32 rows per wave a level's kernel has few waves, and each would otherwise wait out
+    // the full memory latency once per fragment. Fragments are handled in groups of GROUP (a
+    // multiple of both RING and KC), so that every register index below is a compile-time constant.
+    constexpr int RING = 16;
+    constexpr int GROUP = KC > RING ? KC : RING;
+    constexpr int TPG = GROUP / KC;               // column tiles per group
+    uint4 ring[RING];
+    const int64_t total = (int64_t)(p.n_cols / 32) * KC;          // a multiple of GROUP (checked by the launcher)
+#pragma unroll
+    for (int j = 0; j < RING; ++j) ring[j] = wp[(int64_t)j * 64 + lane];
+
     if constexpr (!LN) {
-        const int n_tiles = p.n_cols / 32;
-        for (int nt = 0; nt < n_tiles; ++nt) {
+        for (int64_t f0 = 0; f0 < total; f0 += GROUP) {
             f32x16 acc;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+            for (int j = 0; j < GROUP; ++j) {
+                const int c = j % KC;
+                if (c == 0) {
 #pragma unroll
-            for (int c = 0; c < KC; ++c) {
-                const uint4 b = wp[((int64_t)nt * KC + c) * 64 + lane];
-                Mma<T>::run(a[c], b, acc);
-            }
-            const int col = nt * 32 + m;
-            void* base = p.out[col / D];
-            const int cc = col % D;
+                    for (int i = 0; i < 16; ++i) acc[i] = 0.f;
+                }
+                Mma<T>::run(a[c], ring[j % RING], acc);
+                if (f0 + j + RING < total) ring[j % RING] = wp[(f0 + j + RING) * 64 + lane];
+                if (c == KC - 1) {
+                    const int col = (int)(f0 / KC + j / KC) * 32 + m;
+                    void* base = p.out[col / D];
+                    const int cc = col % D;
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                if (!ok[i]) continue;
-                const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
-                Elem<T>::store1(base, orr * p.out_stride + cc, acc[i]);
-                if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col, acc[i]);
+                    for (int i = 0; i < 16; ++i) {
+                        if (!ok[i]) continue;
+                        const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
+                        Elem<T>::store1(base, orr * p.out_stride + cc, acc[i]);
+                        if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col, acc[i]);
+                    }
+                }
             }
         }
     } else {
         f32x16 acc[NT_LN];
+        static_assert(NT_LN % TPG == 0, "whole groups");
 #pragma unroll
-        for (int nt = 0; nt < NT_LN; ++nt) {
+        for (int g = 0; g < NT_LN / TPG; ++g) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+            for (int j = 0; j < GROUP; ++j) {
+                const int c = j % KC, nt = g * TPG + j / KC;
+                if (c == 0) {
 #pragma unroll
-            for (int c = 0; c < KC; ++c) {
-                const uint4 b = wp[((int64_t)nt * KC + c) * 64 + lane];
-                Mma<T>::run(a[c], b, acc[nt]);
+                    for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+                }
+                Mma<T>::run(a[c], ring[j % RING], acc[nt]);
+                if (g * GROUP + j + RING < NT_LN * KC) ring[j % RING] = wp[(int64_t)(g * GROUP + j + RING) * 64 + lane];
             }
         }
         // residual, then LayerNorm over each row (no affine, biased variance)
@@ -303,6 +324,11 @@ int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
     const int64_t rows = a.row_end - a.row_begin;
     if (rows <= 0) return hipSuccess;
     const unsigned grid = (unsigned)((rows + 127) / 128);
+    {   // the kernel reads the weight stream in whole groups of fragments
+        constexpr int KC = D / (2 * (16 / (int)sizeof(T)));
+        constexpr int GROUP = KC > 16 ? KC : 16;
+        if (a.n_cols % 32 != 0 || ((int64_t)(a.n_cols / 32) * KC) % GROUP != 0) return hipErrorInvalidValue;
+    }
     if (a.epilogue) {
         if (a.n_cols != D) return hipErrorInvalidValue;
         hipLaunchKernelGGL((gemm_kernel<T, D, true>), dim3(grid), dim3(256), 0, s, a);
