@@ -113,6 +113,7 @@ struct dg4_gemm_args {
     const void* resid; int64_t resid_stride; const int32_t* resid_gather;
     void* out2; int64_t out2_stride;        // nullable second copy, indexed by r
     float ln_eps;
+    int split;                              // set by the launcher: waves of a workgroup share rows and split the columns
 };
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s);
 

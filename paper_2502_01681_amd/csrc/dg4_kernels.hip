@@ -212,7 +212,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int m = lane & 31, kg = lane >> 5;
-    const int64_t r0 = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * 32;
+    // Either every wave takes its own 32 rows and all columns, or (split: wide outputs, few rows,
+    // as in a level of the sweep) the four waves of a workgroup share 32 rows and take a quarter
+    // of the columns each, which puts four times as many compute units to work.
+    const bool split = !LN && p.split != 0;
+    const int64_t r0 = p.row_begin + (split ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave) * 32;
     if (r0 >= p.row_end) return;
 
     uint4 a[KC];
@@ -245,12 +249,15 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
     constexpr int GROUP = KC > RING ? KC : RING;
     constexpr int TPG = GROUP / KC;               // column tiles per group
     uint4 ring[RING];
-    const int64_t total = (int64_t)(p.n_cols / 32) * KC;          // a multiple of GROUP (checked by the launcher)
+    const int64_t all = (int64_t)(p.n_cols / 32) * KC;
+    // this wave's part of the stream: a multiple of GROUP fragments (checked by the launcher)
+    const int64_t first = split ? wave * (all / 4) : 0;
+    const int64_t total = split ? first + all / 4 : all;
 #pragma unroll
-    for (int j = 0; j < RING; ++j) ring[j] = wp[(int64_t)j * 64 + lane];
+    for (int j = 0; j < RING; ++j) ring[j] = wp[(first + j) * 64 + lane];
 
     if constexpr (!LN) {
-        for (int64_t f0 = 0; f0 < total; f0 += GROUP) {
+        for (int64_t f0 = first; f0 < total; f0 += GROUP) {
             f32x16 acc;
 #pragma unroll
             for (int j = 0; j < GROUP; ++j) {
@@ -318,23 +325,124 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
     }
 }
 
+// gemm_kernel<.., LN = true> for launches with few rows: the four waves of a workgroup share 32 rows
+// and take a quarter of the D output columns each (four times as many compute units at work, a
+// quarter of the weight stream per wave); the LayerNorm sums are completed through LDS.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
+{
+    constexpr int E = 16 / sizeof(T);
+    constexpr int KC = D / (2 * E);
+    constexpr int NTW = D / 32 / 4;               // column tiles per wave
+    constexpr int RING = 16;
+    constexpr int GROUP = KC > RING ? KC : RING;
+    static_assert((NTW * KC) % GROUP == 0, "whole groups per wave");
+    __shared__ float part[2][4][32];
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int m = lane & 31, kg = lane >> 5;
+    const int64_t r0 = p.row_begin + (int64_t)blockIdx.x * 32;
+
+    uint4 a[KC];
+    {
+        int64_t r = r0 + m;
+        if (r >= p.row_end) r = p.row_end - 1;          // clamp: loads stay in bounds, stores are masked
+        const int64_t ar = p.a_gather ? (int64_t)p.a_gather[r] : r;
+        const uint4* ap = (const uint4*)((const T*)p.a + ar * p.a_stride);
+#pragma unroll
+        for (int c = 0; c < KC; ++c) a[c] = ap[2 * c + kg];
+    }
+    const uint4* wp = (const uint4*)p.w_packed + (int64_t)wave * NTW * KC * 64 + lane;
+    uint4 ring[RING];
+#pragma unroll
+    for (int j = 0; j < RING; ++j) ring[j] = wp[j * 64];
+    f32x16 acc[NTW];
+#pragma unroll
+    for (int j = 0; j < NTW * KC; ++j) {
+        const int c = j % KC, nt = j / KC;
+        if (c == 0) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[nt][i] = 0.f;
+        }
+        Mma<T>::run(a[c], ring[j % RING], acc[nt]);
+        if (j + RING < NTW * KC) ring[j % RING] = wp[(j + RING) * 64];
+    }
+    // residual, then LayerNorm over each row (no affine, biased variance), in two passes
+    const int col0 = wave * NTW * 32 + m;
+    int64_t orow[16];
+    bool ok[16];
+    float mean[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = 8 * (i / 4) + 4 * kg + (i % 4);
+        const int64_t r = r0 + row;
+        ok[i] = r < p.row_end;
+        orow[i] = ok[i] ? r : p.row_end - 1;
+        const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[orow[i]] : orow[i];
+        float s1 = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            acc[nt][i] += Elem<T>::load1(p.resid, rr * p.resid_stride + col0 + nt * 32);
+            s1 += acc[nt][i];
+        }
+        s1 = sum_over_32_lanes(s1);
+        if (m == 0) part[0][wave][row] = s1;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = 8 * (i / 4) + 4 * kg + (i % 4);
+        mean[i] = (part[0][0][row] + part[0][1][row] + part[0][2][row] + part[0][3][row]) * (1.0f / D);
+        float s2 = 0.f;
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) { const float t = acc[nt][i] - mean[i]; s2 = fmaf(t, t, s2); }
+        s2 = sum_over_32_lanes(s2);
+        if (m == 0) part[1][wave][row] = s2;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        if (!ok[i]) continue;
+        const int row = 8 * (i / 4) + 4 * kg + (i % 4);
+        const float rstd = rsqrtf((part[1][0][row] + part[1][1][row] + part[1][2][row] + part[1][3][row]) * (1.0f / D) + p.ln_eps);
+        const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) {
+            const float y = (acc[nt][i] - mean[i]) * rstd;
+            Elem<T>::store1(p.out[0], orr * p.out_stride + col0 + nt * 32, y);
+            if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col0 + nt * 32, y);
+        }
+    }
+}
+
 template <typename T, int D>
 int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
 {
     const int64_t rows = a.row_end - a.row_begin;
     if (rows <= 0) return hipSuccess;
-    const unsigned grid = (unsigned)((rows + 127) / 128);
-    {   // the kernel reads the weight stream in whole groups of fragments
-        constexpr int KC = D / (2 * (16 / (int)sizeof(T)));
-        constexpr int GROUP = KC > 16 ? KC : 16;
-        if (a.n_cols % 32 != 0 || ((int64_t)(a.n_cols / 32) * KC) % GROUP != 0) return hipErrorInvalidValue;
-    }
+    unsigned grid = (unsigned)((rows + 127) / 128);
+    // the kernel reads the weight stream in whole groups of fragments
+    constexpr int KC = D / (2 * (16 / (int)sizeof(T)));
+    constexpr int GROUP = KC > 16 ? KC : 16;
+    const int64_t frags = (int64_t)(a.n_cols / 32) * KC;
+    if (a.n_cols % 32 != 0 || frags % GROUP != 0) return hipErrorInvalidValue;
     if (a.epilogue) {
         if (a.n_cols != D) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((gemm_kernel<T, D, true>), dim3(grid), dim3(256), 0, s, a);
+        constexpr bool can_split = ((D / 32 / 4) * KC) % GROUP == 0 && (D / 32) % 4 == 0;
+        // (always the same kernel for a given shape, whatever the number of rows: the two sum the
+        // LayerNorm statistics in different orders, and the embeddings must not depend on how the
+        // rows were cut into launches)
+        if constexpr (can_split)
+            hipLaunchKernelGGL((gemm_ln_split_kernel<T, D>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((gemm_kernel<T, D, true>), dim3(grid), dim3(256), 0, s, a);
     } else {
         if (a.out2 && a.n_cols != D) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((gemm_kernel<T, D, false>), dim3(grid), dim3(256), 0, s, a);
+        dg4_gemm_args b = a;
+        // few rows (less than two workgroups per compute unit the plain way): split the columns over the waves
+        b.split = (a.n_cols / 32) % 4 == 0 && (frags / 4) % GROUP == 0 && rows < 128 * 512 ? 1 : 0;
+        if (b.split) grid = (unsigned)((rows + 31) / 32);
+        hipLaunchKernelGGL((gemm_kernel<T, D, false>), dim3(grid), dim3(256), 0, s, b);
     }
     return hipGetLastError();
 }
