@@ -5,7 +5,8 @@ One step = one pass of the whole hot path over the 1M-gate "large" synthetic
 AIG: projections, per-edge scores, segmented softmax, aggregation, output
 projection + LayerNorm, swept over all of its about 1000 levels. Inputs are
 resident in HBM before the timed region; graph analysis (host) and uploads are
-reported separately and excluded. Prints ONE JSON line.
+reported separately and excluded. Prints ONE JSON line. `--ffn` times the layer with its
+feed-forward sub-block instead (not the headline configuration).
 """
 from __future__ import annotations
 

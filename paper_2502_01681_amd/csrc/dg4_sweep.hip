@@ -29,7 +29,6 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
-#include <cstdlib>
 #include <type_traits>
 
 #include "dg4_device.h"
@@ -1059,7 +1058,6 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s)
     if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
     int64_t grid = std::min<int64_t>(cus, DG4_MAX_SWEEP_GROUPS);   // one workgroup per compute unit: its registers and LDS hold the weights
-    if (const char* e = getenv("DG4_SWEEP_GRID")) grid = std::min<int64_t>(grid, std::max<int64_t>(1, atoll(e)));
     if (a.ffn_packed) {
         if ((a.n_tiles & 1) || !a.park) return hipErrorInvalidValue;      // whole pairs only
         if (grid > a.n_tiles / 2) grid = a.n_tiles / 2;
