@@ -302,6 +302,41 @@ def test_sweep_reads_no_row_before_it_is_written(ffn):
         assert row_rel_err(H, step).max() <= TOL[c.dtype]
 
 
+@pytest.mark.parametrize("ffn", [False, True])
+@pytest.mark.parametrize("n_pi,n_and", [(3, 0), (2, 1), (32, 5), (7, 17), (32, 40), (16, 500)])
+def test_small_graphs_through_the_persistent_kernel(n_pi, n_and, ffn):
+    """Ragged and empty tiles, fewer tiles than compute units, primary inputs only: bf16, hidden 256,
+    two hops, the configuration the persistent kernel serves."""
+    print(f"small graph n_pi={n_pi} n_and={n_and} ffn={ffn}", flush=True)
+    c = synth.Config("t", 9, n_pi, n_and, 8, 1.0, 0, 256, 8, 2, 1, "bf16")
+    n = c.n_nodes
+    if n_and:
+        src, dst, inv, _ = synth.aig(c.seed, n_pi, n_and, c.window)
+    else:
+        src = dst = np.zeros(0, dtype=np.int32); inv = np.zeros(0, dtype=np.uint8)
+    x = synth.normal(c.seed, synth.STREAM_X, (n, c.hidden), 1.0, True)
+    wqkv, wo, rb = synth.weights(c)
+    w1 = w2 = None
+    g = dg4.dg4_build_levels(n, src, dst, inv, 2)
+    og = oracle.build_levels(n, src, dst, inv, 2)
+    W = [(to_dev(wqkv[0], "bf16"), to_dev(wo[0], "bf16"), to_dev(rb[0], "f32"))]
+    if ffn:
+        w1, w2 = synth.ffn_weights(c)
+        W = [W[0] + (to_dev(w1[0], "bf16"), to_dev(w2[0], "bf16"))]
+    cfg = cfg_of(c, ffn=ffn)
+    ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+    ws.fill_(0xFF)
+    Hd = torch.full((n, c.hidden), float("nan"), dtype=torch.bfloat16, device="cuda")
+    dg4.dg4_layer_fwd(cfg, g, to_dev(x, "bf16"), W, Hd, workspace=ws)
+    torch.cuda.synchronize()
+    aborted, _ = dg4.dg4_layer_profile(cfg, g, ws)
+    assert aborted == 0
+    H = to_np(Hd)
+    assert not np.isnan(H).any()
+    ref = oracle.layer_fwd(og, x, wqkv, wo, rb, c.heads, store="bf16", w1=w1, w2=w2)
+    assert row_rel_err(H, ref).max() <= TOL["bf16"]
+
+
 def test_workspace_reuse_with_new_inputs():
     # the same workspace and output buffer, different features: nothing stale may be read
     print("layer_fwd workspace reuse", flush=True)
