@@ -239,7 +239,7 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
         dg4_graph* m = const_cast<dg4_graph*>(g);            // the schedule is built on first use, under the lock
         std::lock_guard<std::mutex> lock(m->mu);
         if (m->flow_tile_ptr.empty()) {
-            const int rc = dg4_flow_schedule(m, 640);
+            const int rc = dg4_flow_schedule(m);
             if (rc != DG4_OK) return rc;
         }
         if (which == DG4_FLOW_ORDER) { *host_ptr = g->flow_order.data(); *count = g->n; }
@@ -251,7 +251,7 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
         dg4_graph* m = const_cast<dg4_graph*>(g);
         std::lock_guard<std::mutex> lock(m->mu);
         if (m->pair_tile_ptr.empty()) {
-            const int rc = dg4_pair_schedule(m, 1280);
+            const int rc = dg4_pair_schedule(m);
             if (rc != DG4_OK) return rc;
         }
         if (which == DG4_PAIR_ORDER) { *host_ptr = g->pair_order.data(); *count = g->n; }
@@ -274,14 +274,16 @@ extern "C" int dg4_graph_info(const dg4_graph* g, int64_t* n_nodes, int64_t* n_l
 }
 
 // Dataflow order for whole-graph sweeps: list scheduling over the real dependencies. A tile takes
-// the (up to) 16 gates whose direct fanins all sit in EARLIER tiles and whose latest cone source
-// is oldest (`due` = tile of that source + slack); ties go to the lower level, then the lower id.
-// `slack` tiles between a source and its reader let the source be published before the reader looks
-// for it. Results do not depend on the order; it only decides who waits for whom.
+// the (up to) 16 gates that have been ready longest; a gate becomes ready when the tile holding its
+// last direct fanin has been filled (every other cone source then sits in an earlier tile too), and
+// may go into any later tile; gates that became ready together go by lower level, then lower id.
+// Oldest-first keeps as many tiles as possible between a source and its readers, so that the
+// source is published before the reader looks for it. Results do not depend on the order; it only
+// decides who waits for whom.
 // `pairs`: tiles come two at a time (2k and 2k+1, the second possibly empty) with no dependency
 // between the two, and count as published together (at the second one): the unit of the sweep
 // with the feed-forward sub-block, which runs two tiles through one pass over its weights.
-static int flow_schedule(const dg4_graph* g, int64_t slack, bool pairs, std::vector<int32_t>& out_order, std::vector<int64_t>& out_tile_ptr)
+static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& out_order, std::vector<int64_t>& out_tile_ptr)
 {
     try {
         std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
@@ -297,44 +299,31 @@ static int flow_schedule(const dg4_graph* g, int64_t slack, bool pairs, std::vec
                 for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
                     if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fo[(size_t)fill[g->nbr_idx[j]]++] = (int32_t)v;
         }
-        struct Item { int64_t due; int32_t level; int32_t v; };
-        auto later = [](const Item& a, const Item& b) {
-            if (a.due != b.due) return a.due > b.due;
-            if (a.level != b.level) return a.level > b.level;
-            return a.v > b.v;
-        };
-        std::priority_queue<Item, std::vector<Item>, decltype(later)> ready(later);
+        // the ready list is a queue of batches, one per tile, each sorted by (level, id)
+        auto before = [&](int32_t a, int32_t b) { return g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };
+        std::vector<int32_t> ready;                 // the queue: taken from `head`, appended at the end
+        ready.reserve((size_t)g->n);
         for (int64_t v = 0; v < g->n; ++v)
-            if (remaining[v] == 0) ready.push(Item{0, g->level[v], (int32_t)v});
-        std::vector<int32_t> tile_of((size_t)g->n, -1);
+            if (remaining[v] == 0) ready.push_back((int32_t)v);
+        std::sort(ready.begin(), ready.end(), before);
+        size_t head = 0;
         std::vector<int32_t> flow((size_t)g->n, 0);
         std::vector<int64_t> tile_ptr(1, 0);
-        std::vector<Item> fresh;
         int64_t q = 0;
-        while (!ready.empty()) {
+        while (head < ready.size()) {
             const int64_t first = q;
-            // the tile whose completion publishes these gates
-            const int64_t t = (int64_t)tile_ptr.size() - 1 + (pairs ? 1 : 0);
-            for (int k = 0; k < (pairs ? 2 : 1) * DG4_TILE_ROWS && !ready.empty(); ++k) {
-                const int32_t v = ready.top().v;
-                ready.pop();
-                tile_of[v] = (int32_t)t; flow[(size_t)q++] = v;
-            }
+            for (int k = 0; k < (pairs ? 2 : 1) * DG4_TILE_ROWS && head < ready.size(); ++k) flow[(size_t)q++] = ready[head++];
             if (pairs) tile_ptr.push_back(std::min<int64_t>(first + DG4_TILE_ROWS, q));
             tile_ptr.push_back(q);
-            fresh.clear();
+            const size_t fresh = ready.size();      // eligible from the next tile on
             for (int64_t p = first; p < q; ++p) {
                 const int32_t v = flow[(size_t)p];
                 for (int64_t j = fo_ptr[v]; j < fo_ptr[v + 1]; ++j) {
                     const int32_t u = fo[(size_t)j];
-                    if (--remaining[u] != 0) continue;
-                    int64_t newest = -1;      // every cone source is scheduled: it precedes a direct fanin
-                    for (int64_t i = g->nbr_ptr[u]; i < g->nbr_ptr[u + 1]; ++i)
-                        if (g->nbr_idx[i] != u) newest = std::max<int64_t>(newest, tile_of[g->nbr_idx[i]]);
-                    fresh.push_back(Item{newest + slack, g->level[u], u});
+                    if (--remaining[u] == 0) ready.push_back(u);
                 }
             }
-            for (const Item& it : fresh) ready.push(it);     // eligible from the next tile on
+            std::sort(ready.begin() + fresh, ready.end(), before);
         }
         if (q != g->n) return DG4_ECYCLE;                      // cannot happen for a validated DAG
         out_order.swap(flow);
@@ -345,18 +334,16 @@ static int flow_schedule(const dg4_graph* g, int64_t slack, bool pairs, std::vec
     return DG4_OK;
 }
 
-int dg4_flow_schedule(dg4_graph* g, int64_t slack)
+int dg4_flow_schedule(dg4_graph* g)
 {
     if (!g->flow_tile_ptr.empty()) return DG4_OK;          // built once: pointers into it may have been handed out
-    const int rc = flow_schedule(g, slack, false, g->flow_order, g->flow_tile_ptr);
-    if (rc == DG4_OK) g->flow_slack = slack;
-    return rc;
+    return flow_schedule(g, false, g->flow_order, g->flow_tile_ptr);
 }
 
-int dg4_pair_schedule(dg4_graph* g, int64_t slack)
+int dg4_pair_schedule(dg4_graph* g)
 {
     if (!g->pair_tile_ptr.empty()) return DG4_OK;          // built once: pointers into it may have been handed out
-    return flow_schedule(g, slack, true, g->pair_order, g->pair_tile_ptr);
+    return flow_schedule(g, true, g->pair_order, g->pair_tile_ptr);
 }
 
 // Device tables of the pair schedule (sweeps with the feed-forward sub-block), built on first use.
@@ -368,9 +355,7 @@ int dg4_graph_ensure_pairs(dg4_graph* g)
     const int w = g->ell_w;
     const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
     try {
-        int cus = 0;
-        if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, g->device) != hipSuccess || cus <= 0) cus = 256;
-        const int rc = dg4_pair_schedule(g, (int64_t)cus * 5);      // 2.5 pairs per unit in flight
+        const int rc = dg4_pair_schedule(g);
         if (rc != DG4_OK) return rc;
         const std::vector<int32_t>& order = g->pair_order;
         const std::vector<int64_t>& tile_ptr = g->pair_tile_ptr;
@@ -475,12 +460,9 @@ int dg4_graph_ensure_device(dg4_graph* g)
                 tiles.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(DG4_TILE_ROWS, g->level_ptr[l + 1] - p0)));
         }
         g->level_tile_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
-        // Dataflow order for whole-graph sweeps (dg4_flow_schedule), with room between a source and
-        // its readers for as many tiles as are in flight at once (one workgroup per compute unit).
+        // Dataflow order for whole-graph sweeps (dg4_flow_schedule)
         {
-            int cus = 0;
-            if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) cus = 256;
-            const int rc = dg4_flow_schedule(g, (int64_t)cus * 5 / 2);
+            const int rc = dg4_flow_schedule(g);
             if (rc != DG4_OK) return rc;
         }
         std::vector<int32_t> flow(rows, 0);

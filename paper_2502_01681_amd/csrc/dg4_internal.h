@@ -56,7 +56,6 @@ struct dg4_graph {
     uint32_t* d_ell_front = nullptr;     // [n, ell_w] by position, entries rel << 30 | index in the level's frontier
     std::vector<int32_t> flow_order;
     std::vector<int64_t> flow_tile_ptr;
-    int64_t flow_slack = -1;
     uint32_t* d_flow_ell = nullptr;
     int32_t* d_flow_order = nullptr;
     uint2* d_flow_tiles = nullptr;
@@ -72,8 +71,8 @@ struct dg4_graph {
 };
 
 int dg4_graph_ensure_device(dg4_graph* g);
-int dg4_flow_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
-int dg4_pair_schedule(dg4_graph* g, int64_t slack);   // caller holds g->mu
+int dg4_flow_schedule(dg4_graph* g);   // caller holds g->mu
+int dg4_pair_schedule(dg4_graph* g);   // caller holds g->mu
 int dg4_graph_ensure_frontier(dg4_graph* g);           // after dg4_graph_ensure_device
 int dg4_graph_ensure_struct(dg4_graph* g);
 int dg4_graph_ensure_pairs(dg4_graph* g);              // after dg4_graph_ensure_device
