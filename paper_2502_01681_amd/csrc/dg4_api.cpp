@@ -303,7 +303,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // One persistent dataflow kernel for the whole range of levels (with the feed-forward sub-block:
     // whole-graph sweeps only, partial ones run level by level)
     const bool whole_range = level_begin == 0 && level_end == (int32_t)g->max_level + 1;
-    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops == 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) &&
+    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops <= 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) &&
         (!ffn || whole_range)) {
         // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
         // level by level; rows of the internal buffers are positions in the order in use.

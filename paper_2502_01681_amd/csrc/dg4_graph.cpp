@@ -403,7 +403,8 @@ int dg4_graph_ensure_device(dg4_graph* g)
     if (g->on_device) return DG4_OK;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return DG4_EHIP;
-    const int w = 1 << (g->hops + 1);
+    // (one-hop cones get rows of 8 as well: the persistent sweep is laid out for that width)
+    const int w = std::max(8, 1 << (g->hops + 1));
     // one tile of padding: the sweep kernel fetches descriptors of 16 positions at a time
     const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
     try {

@@ -12,7 +12,7 @@
 #include "dg4.h"
 
 // Neighbour rows on the device: fixed-width rows of packed 32-bit entries
-// (relation code << 30 | index), padded with DG4_ELL_PAD. Width = 2^(hops+1),
+// (relation code << 30 | index), padded with DG4_ELL_PAD. Width = 2^(hops+1), at least 8:
 // one more than the largest cone (Section 3.2), so a row always ends in a pad.
 #define DG4_ELL_PAD 0xFFFFFFFFu
 #define DG4_MAX_LAYERS 8
