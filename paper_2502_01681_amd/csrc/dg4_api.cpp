@@ -188,6 +188,19 @@ extern "C" int dg4_ffn_fwd(const dg4_layer_cfg* cfg, const void* S, int64_t row_
     const int d = cfg->hidden;
     char* w1p = (char*)workspace;
     char* w2p = w1p + align256((size_t)d * 4 * d * elt_size(cfg->dtype));
+    if (cfg->dtype == DG4_BF16 && d == 256) {
+        // this shape always takes the kernel for many rows (one kernel per shape: the result of a
+        // row does not depend on the range it was asked for in)
+        HIPCHK(dg4_launch_pack_ffn_bulk(W1, W2, w1p, s));
+        dg4_ffn_args f{};
+        f.h = S; f.h_stride = d;
+        f.w1_packed = w1p;
+        f.out = Out; f.out_stride = d;
+        f.row_begin = row_begin; f.row_end = row_end;
+        f.ln_eps = cfg->ln_eps;
+        HIPCHK(dg4_launch_ffn_bulk(f, s));
+        return DG4_OK;
+    }
     HIPCHK(dg4_launch_pack_w(cfg->dtype, W1, 4 * d, 0, 4 * d, d, w1p, s));
     HIPCHK(dg4_launch_pack_w2(cfg->dtype, W2, d, w2p, s));
     dg4_ffn_args f{};

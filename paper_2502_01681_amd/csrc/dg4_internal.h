@@ -129,6 +129,9 @@ struct dg4_ffn_args {
 };
 int dg4_launch_pack_w2(int dtype, const void* w2, int hidden, void* packed, hipStream_t s);
 int dg4_launch_ffn(int dtype, int hidden, const dg4_ffn_args& a, hipStream_t s);
+// bf16, hidden 256, many rows: W1 | W2 as ONE stream in w1_packed (dg4_launch_pack_ffn_bulk order), w2_packed unused
+int dg4_launch_pack_ffn_bulk(const void* w1, const void* w2, void* packed, hipStream_t s);
+int dg4_launch_ffn_bulk(const dg4_ffn_args& a, hipStream_t s);
 
 // ---- persistent sweep (dg4_sweep.hip): bf16, hidden 256, one layer ----
 struct dg4_sweep_args {

@@ -602,6 +602,211 @@ __global__ __launch_bounds__(256) void ffn_kernel(dg4_ffn_args p)
     }
 }
 
+// ------------------------------------------------- feed-forward, many rows at once (bf16, d = 256)
+//
+// dg4_ffn_fwd over a whole matrix is bound by how often the megabyte of W1 | W2 has to come from
+// the L2 cache: ffn_kernel above reads it once per 32 rows. Here a workgroup takes 96 rows, keeps
+// them in LDS, and streams the weights once for all of them: one contiguous stream per wave, in
+// four passes of 256 hidden units. Per pass a wave forms the activations of its 64 hidden units
+// for all 96 rows (transposed, W1 piece as the A operand), rectifies and writes them to LDS,
+// and after a barrier adds the pass's part of ITS 64 output columns for all rows (the output
+// accumulators, 96 registers, stay put over the passes). Residual + LayerNorm from registers with
+// the row sums completed through LDS; the result leaves through LDS as whole 16-byte pieces.
+constexpr int FB_ROWS = 96, FB_RT = 3, FB_STRIDE = 264, FB_PASSES = 4, FB_FRAGS = 64, FB_RING = 16;
+constexpr int FB_SMEM = 2 * FB_ROWS * FB_STRIDE * 2 + 2 * 4 * FB_ROWS * 4;
+
+// Stream order, 16-byte units: (((w*4 + pass)*64 + j)*64 + lane), lane = 32*kg + m.
+//  j < 32 : first product, hidden tile t = j/16, k-step ks = j%16:
+//           W1[16*ks + 8*kg + e][256*pass + 64*w + 32*t + m], e = 0..7
+//  j >= 32: second product, k-step ks = (j-32)/2, column tile ct = (j-32)%2:
+//           W2[256*pass + 16*ks + 8*kg + e][64*w + 32*ct + m]
+__global__ void pack_ffn_bulk_kernel(const uint16_t* w1, const uint16_t* w2, uint16_t* packed)
+{
+    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (unit >= 4 * FB_PASSES * FB_FRAGS * 64) return;
+    const int lane = (int)(unit & 63);
+    const int j = (int)((unit >> 6) % FB_FRAGS);
+    const int pass = (int)((unit >> 12) % FB_PASSES);
+    const int w = (int)(unit >> 14);
+    const int m = lane & 31, kg = lane >> 5;
+    if (j < 32) {
+        const int t = j >> 4, ks = j & 15;
+        const int hidden = 256 * pass + 64 * w + 32 * t + m;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) packed[unit * 8 + e] = w1[(int64_t)(16 * ks + 8 * kg + e) * 1024 + hidden];
+    } else {
+        const int ks = (j - 32) >> 1, ct = (j - 32) & 1;
+        const int col = 64 * w + 32 * ct + m;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) packed[unit * 8 + e] = w2[(int64_t)(256 * pass + 16 * ks + 8 * kg + e) * 256 + col];
+    }
+}
+
+__device__ __forceinline__ void lds_barrier()      // LDS traffic only: the weight loads in flight are not drained
+{
+    __asm__ volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xC07F);            // lgkmcnt(0)
+    __builtin_amdgcn_s_barrier();
+    __asm__ volatile("" ::: "memory");
+}
+
+__global__ __launch_bounds__(256) void ffn_bulk_kernel(dg4_ffn_args p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char fb_smem[];
+    uint16_t (*sH)[FB_STRIDE] = (uint16_t (*)[FB_STRIDE])fb_smem;
+    uint16_t (*sU)[FB_STRIDE] = sH + FB_ROWS;
+    float (*sPart)[4][FB_ROWS] = (float (*)[4][FB_ROWS])(fb_smem + 2 * FB_ROWS * FB_STRIDE * 2);
+    const int tid = threadIdx.x;
+    const int lane = tid & 63, wave = tid >> 6;
+    const int m = lane & 31, kg = lane >> 5;
+    const int64_t r0 = p.row_begin + (int64_t)blockIdx.x * FB_ROWS;
+    const uint16_t* h = (const uint16_t*)p.h;
+
+    // the rows of this workgroup (past the end: the last row again; never stored)
+#pragma unroll
+    for (int i = 0; i < FB_ROWS * 32 / 256; ++i) {
+        const int chunk = tid + 256 * i, row = chunk >> 5, c16 = chunk & 31;
+        int64_t r = r0 + row;
+        if (r >= p.row_end) r = p.row_end - 1;
+        *(uint4*)&sH[row][c16 * 8] = *(const uint4*)(h + r * p.h_stride + c16 * 8);
+    }
+    const uint4* wp = (const uint4*)p.w1_packed + (int64_t)wave * (FB_PASSES * FB_FRAGS * 64) + lane;
+    uint4 ring[FB_RING];
+#pragma unroll
+    for (int j = 0; j < FB_RING; ++j) ring[j] = wp[j * 64];
+    __syncthreads();
+
+    f32x16 out[2][FB_RT];
+#pragma unroll 1
+    for (int pass = 0; pass < FB_PASSES; ++pass) {
+        const uint4* wq = wp + (int64_t)pass * (FB_FRAGS * 64);
+        const bool more = pass + 1 < FB_PASSES;
+        if (pass) lds_barrier();                  // the previous pass's activations have been read by every wave
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            f32x16 u[FB_RT];
+            // (the rows' operands of the next step are read from LDS while this step's products run)
+            uint4 bc[FB_RT], bn[FB_RT];
+#pragma unroll
+            for (int rt = 0; rt < FB_RT; ++rt) bc[rt] = *(const uint4*)&sH[32 * rt + m][8 * kg];
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks) {
+                const int j = 16 * t + ks;
+#pragma unroll
+                for (int rt = 0; rt < FB_RT; ++rt) bn[rt] = ks + 1 < 16 ? *(const uint4*)&sH[32 * rt + m][16 * (ks + 1) + 8 * kg] : bc[rt];
+#pragma unroll
+                for (int rt = 0; rt < FB_RT; ++rt) {
+                    if (ks == 0) {
+#pragma unroll
+                        for (int i = 0; i < 16; ++i) u[rt][i] = 0.f;
+                    }
+                    Mma<bf16_t>::run(ring[j % FB_RING], bc[rt], u[rt]);
+                }
+                ring[j % FB_RING] = wq[(j + FB_RING) * 64];
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int rt = 0; rt < FB_RT; ++rt) bc[rt] = bn[rt];
+            }
+            // rectified, to LDS by row: element i of the accumulator is hidden unit 8*(i/4) + 4*kg + i%4 of the tile
+#pragma unroll
+            for (int rt = 0; rt < FB_RT; ++rt)
+#pragma unroll
+                for (int q = 0; q < 4; ++q)
+                    *(uint2*)&sU[32 * rt + m][64 * wave + 32 * t + 8 * q + 4 * kg] =
+                        make_uint2(pack_bf16x2(fmaxf(u[rt][4 * q], 0.f), fmaxf(u[rt][4 * q + 1], 0.f)),
+                                   pack_bf16x2(fmaxf(u[rt][4 * q + 2], 0.f), fmaxf(u[rt][4 * q + 3], 0.f)));
+        }
+        lds_barrier();
+        {
+            uint4 bc[FB_RT], bn[FB_RT];
+#pragma unroll
+            for (int rt = 0; rt < FB_RT; ++rt) bc[rt] = *(const uint4*)&sU[32 * rt + m][8 * kg];
+#pragma unroll
+            for (int ks = 0; ks < 16; ++ks) {
+#pragma unroll
+                for (int rt = 0; rt < FB_RT; ++rt) bn[rt] = ks + 1 < 16 ? *(const uint4*)&sU[32 * rt + m][16 * (ks + 1) + 8 * kg] : bc[rt];
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct) {
+                    const int j = 32 + 2 * ks + ct;
+#pragma unroll
+                    for (int rt = 0; rt < FB_RT; ++rt) {
+                        if (pass == 0 && ks == 0) {
+#pragma unroll
+                            for (int i = 0; i < 16; ++i) out[ct][rt][i] = 0.f;
+                        }
+                        Mma<bf16_t>::run(ring[j % FB_RING], bc[rt], out[ct][rt]);
+                    }
+                    if (j + FB_RING < FB_FRAGS || more) ring[j % FB_RING] = wq[(j + FB_RING) * 64];
+                }
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int rt = 0; rt < FB_RT; ++rt) bc[rt] = bn[rt];
+            }
+        }
+    }
+
+    // residual and LayerNorm (no affine, biased variance, two passes). Lane (m, kg) holds, of row
+    // 32*rt + m, the columns 64*wave + 32*ct + 8*q + 4*kg + r (accumulator element 4*q + r).
+    float mean[FB_RT];
+#pragma unroll
+    for (int rt = 0; rt < FB_RT; ++rt) {
+        float s1 = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const uint2 hv = *(const uint2*)&sH[32 * rt + m][64 * wave + 32 * ct + 8 * q + 4 * kg];
+                out[ct][rt][4 * q] += bf16_lo(hv.x); out[ct][rt][4 * q + 1] += bf16_hi(hv.x);
+                out[ct][rt][4 * q + 2] += bf16_lo(hv.y); out[ct][rt][4 * q + 3] += bf16_hi(hv.y);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) s1 += out[ct][rt][4 * q + r];
+            }
+        s1 += __shfl_xor(s1, 32);
+        if (kg == 0) sPart[0][wave][32 * rt + m] = s1;
+    }
+    __syncthreads();                              // also: every wave is done with the activations in sU
+#pragma unroll
+    for (int rt = 0; rt < FB_RT; ++rt) {
+        const int row = 32 * rt + m;
+        mean[rt] = (sPart[0][0][row] + sPart[0][1][row] + sPart[0][2][row] + sPart[0][3][row]) * (1.0f / 256);
+        float s2 = 0.f;
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) { const float d = out[ct][rt][i] - mean[rt]; s2 = fmaf(d, d, s2); }
+        s2 += __shfl_xor(s2, 32);
+        if (kg == 0) sPart[1][wave][row] = s2;
+    }
+    __syncthreads();
+#pragma unroll
+    for (int rt = 0; rt < FB_RT; ++rt) {
+        const int row = 32 * rt + m;
+        const float rstd = rsqrtf((sPart[1][0][row] + sPart[1][1][row] + sPart[1][2][row] + sPart[1][3][row]) * (1.0f / 256) + p.ln_eps);
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                float y[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) y[r] = (out[ct][rt][4 * q + r] - mean[rt]) * rstd;
+                *(uint2*)&sU[row][64 * wave + 32 * ct + 8 * q + 4 * kg] = make_uint2(pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3]));
+            }
+    }
+    __syncthreads();
+    uint16_t* o = (uint16_t*)p.out;
+    uint16_t* o2 = (uint16_t*)p.out2;
+#pragma unroll
+    for (int i = 0; i < FB_ROWS * 32 / 256; ++i) {
+        const int chunk = tid + 256 * i, row = chunk >> 5, c16 = chunk & 31;
+        const int64_t r = r0 + row;
+        if (r >= p.row_end) continue;
+        const uint4 v = *(const uint4*)&sU[row][c16 * 8];
+        const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[r] : r;
+        *(uint4*)(o + orr * p.out_stride + c16 * 8) = v;
+        if (o2) *(uint4*)(o2 + r * p.out2_stride + c16 * 8) = v;
+    }
+}
+
 template <typename T, int D>
 int launch_ffn_t(const dg4_ffn_args& a, hipStream_t s)
 {
@@ -700,6 +905,24 @@ int dg4_launch_pack_w2(int dtype, const void* w2, int hidden, void* packed, hipS
         hipLaunchKernelGGL(pack_w2_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)w2, hidden, (float*)packed);
     else
         hipLaunchKernelGGL(pack_w2_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t*)w2, hidden, (uint16_t*)packed);
+    return hipGetLastError();
+}
+
+int dg4_launch_pack_ffn_bulk(const void* w1, const void* w2, void* packed, hipStream_t s)
+{
+    const int64_t units = 4 * FB_PASSES * FB_FRAGS * 64;
+    hipLaunchKernelGGL(pack_ffn_bulk_kernel, dim3((unsigned)((units + 255) / 256)), dim3(256), 0, s,
+                       (const uint16_t*)w1, (const uint16_t*)w2, (uint16_t*)packed);
+    return hipGetLastError();
+}
+
+int dg4_launch_ffn_bulk(const dg4_ffn_args& a, hipStream_t s)
+{
+    const int64_t rows = a.row_end - a.row_begin;
+    if (rows <= 0) return hipSuccess;
+    hipError_t e = hipFuncSetAttribute((const void*)ffn_bulk_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, FB_SMEM);
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(ffn_bulk_kernel, dim3((unsigned)((rows + FB_ROWS - 1) / FB_ROWS)), dim3(256), FB_SMEM, s, a);
     return hipGetLastError();
 }
 
