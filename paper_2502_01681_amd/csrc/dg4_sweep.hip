@@ -1,4 +1,4 @@
-// The level sweep as ONE persistent dataflow kernel (bf16, hidden 256, one layer, two-hop cones).
+// The level sweep as ONE persistent dataflow kernel (bf16, hidden 256, one layer, cones of at most two hops).
 //
 // The updating strategy (paper Section 3.4, Algorithm 2) orders the work level
 // by level; what it requires is that a gate reads the FINAL embeddings of its
