@@ -74,6 +74,20 @@ def _load():
         lib.orc_struct_encode.argtypes = [_I64, _I32, _P, _P, _P, _P, _P, _I32, _P]
         lib.orc_threads.restype = ctypes.c_int
         lib.orc_threads.argtypes = []
+        lib.orc_partition.restype = ctypes.c_void_p
+        lib.orc_partition.argtypes = [_I64, _I64, _P, _P, _I32, _I32, _P, _P]
+        lib.orc_cones_sizes.restype = None
+        lib.orc_cones_sizes.argtypes = [_P, _P, _P, _P]
+        lib.orc_cones_copy.restype = None
+        lib.orc_cones_copy.argtypes = [_P, _P, _P, _P, _P, _P]
+        lib.orc_cones_free.restype = None
+        lib.orc_cones_free.argtypes = [_P]
+        lib.orc_partitioned_fwd.restype = ctypes.c_int
+        lib.orc_partitioned_fwd.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64,
+                                            _P, _P, _P, _P, _P, _P,
+                                            _P, _P, _P, _P,
+                                            _I64, _P, _P, _P, _I32, _I32,
+                                            _P, _P, _P, _P]
         _lib = lib
     return _lib
 
@@ -101,6 +115,7 @@ class Graph:
     nbr_ptr: np.ndarray      # int64 [N + 1]
     nbr_idx: np.ndarray      # int32 [NNZ] ascending id inside a row
     nbr_rel: np.ndarray      # uint8 [NNZ] 0 self, 1 fanin, 2 inverted fanin, 3 virtual
+    hops: int = -1           # cone depth k the rows were built with
 
     @property
     def n_levels(self) -> int:
@@ -147,7 +162,7 @@ def build_levels(n, src, dst, inv, hops, level_hint=None) -> Graph:
     nbr_idx = np.empty(nnz, dtype=np.int32)
     nbr_rel = np.empty(nnz, dtype=np.uint8)
     lib.orc_cone_csr(n, e, _ptr(src), _ptr(dst), _ptr(inv), hops, _ptr(nbr_ptr), _ptr(nbr_idx), _ptr(nbr_rel))
-    return Graph(n, lev, order, level_ptr, nbr_ptr, nbr_idx, nbr_rel)
+    return Graph(n, lev, order, level_ptr, nbr_ptr, nbr_idx, nbr_rel, int(hops))
 
 
 def qkv_proj(S, W):
@@ -253,3 +268,73 @@ def struct_encode(x, level, out_and, out_not, emb, store="f64"):
     out = np.empty((n, d), dtype=np.float64)
     _load().orc_struct_encode(n, d, _ptr(x), _ptr(level), _ptr(out_and), _ptr(out_not), _ptr(emb), STORE[store], _ptr(out))
     return out
+
+
+@dataclass
+class Cones:
+    """Algorithm 1's result: the lists cones^l by ascending l, each a run of cones."""
+    group_level: np.ndarray   # int32 [G]      level l of each list
+    group_ptr: np.ndarray     # int64 [G + 1]  first cone of each list
+    cone_root: np.ndarray     # int32 [C]
+    cone_ptr: np.ndarray      # int64 [C + 1]  into cone_node
+    cone_node: np.ndarray     # int32          gates of each cone, ascending id
+
+    def cone(self, c):
+        return self.cone_node[self.cone_ptr[c]:self.cone_ptr[c + 1]]
+
+
+def partition(g: Graph, src, delta) -> Cones:
+    """Algorithm 1 (reading R17) with k = the hops the graph's cone rows were built with."""
+    lib = _load()
+    src = _c(src, np.int32)
+    k = _hops_of(g)
+    h = lib.orc_partition(g.n, len(src), _ptr(src), _ptr(g.level), k, int(delta), _ptr(g.nbr_ptr), _ptr(g.nbr_idx))
+    if not h:
+        raise OracleError(-1)
+    try:
+        sizes = [ctypes.c_int64() for _ in range(3)]
+        lib.orc_cones_sizes(h, *[ctypes.addressof(t) for t in sizes])
+        G, C, E = (int(t.value) for t in sizes)
+        out = Cones(np.empty(G, np.int32), np.empty(G + 1, np.int64), np.empty(C, np.int32),
+                    np.empty(C + 1, np.int64), np.empty(E, np.int32))
+        lib.orc_cones_copy(h, _ptr(out.group_level), _ptr(out.group_ptr), _ptr(out.cone_root),
+                           _ptr(out.cone_ptr), _ptr(out.cone_node))
+    finally:
+        lib.orc_cones_free(h)
+    return out
+
+
+def _hops_of(g: Graph) -> int:
+    if g.hops < 1:
+        raise ValueError("the graph does not say which cone depth its rows were built with")
+    return int(g.hops)
+
+
+def partitioned_fwd(g: Graph, cones: Cones, batch, x, wqkv, wo, rel_bias, heads, *, mark=True, store="f64",
+                    epilogue=True, ln_eps=1e-5, w1=None, w2=None):
+    """Algorithm 2 at inference over Algorithm 1's lists (reading R17).
+
+    Returns (H [N,d] float64, rows, stage_of, n_computed): rows = (ptr, idx, rel) of the
+    neighbourhood each gate was (last) computed with, stage_of the running number of the
+    mini-batch that did it, n_computed the number of gate computations."""
+    x = _c(x, np.float32)
+    n, d = x.shape
+    nl = len(wqkv)
+    Wqkv, Wo, B = _stack(wqkv, (d, 3 * d)), _stack(wo, (d, d)), _stack(rel_bias, (heads, 4))
+    W1, W2 = _ffn(w1, w2, nl, d)
+    H = np.full((n, d), np.nan, dtype=np.float64)
+    kept = np.zeros(len(g.nbr_idx), dtype=np.uint8)
+    stage_of = np.full(n, -1, dtype=np.int32)
+    n_computed = ctypes.c_int64()
+    rc = _load().orc_partitioned_fwd(n, d, heads, nl, STORE[store], int(epilogue), float(ln_eps),
+                                     _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B), _ptr(W1), _ptr(W2),
+                                     _ptr(g.level), _ptr(g.nbr_ptr), _ptr(g.nbr_idx), _ptr(g.nbr_rel),
+                                     len(cones.group_level), _ptr(cones.group_ptr), _ptr(cones.cone_ptr),
+                                     _ptr(cones.cone_node), int(batch), int(mark),
+                                     _ptr(H), _ptr(kept), _ptr(stage_of), ctypes.addressof(n_computed))
+    if rc:
+        raise OracleError(rc)
+    sel = kept.astype(bool)
+    cnt = np.add.reduceat(kept.astype(np.int64), g.nbr_ptr[:-1]) if n else np.zeros(0, np.int64)
+    ptr = np.concatenate([[0], np.cumsum(cnt)]).astype(np.int64)
+    return H, (ptr, g.nbr_idx[sel], g.nbr_rel[sel]), stage_of, int(n_computed.value)

@@ -51,6 +51,21 @@
  *       feed-forward sub-block s' = LN(h + max(h W1, 0) W2), W1 [d, 4d], W2 [4d, d],
  *       rectifier, no biases (R10), LayerNorm as in R7. Optional: a layer without
  *       W1 / W2 is the attention sub-block alone.
+ *   R17 general partition and updating strategy (Section 3.3, Algorithm 1; Section 3.4,
+ *       Algorithm 2) at inference. The gates of a level are visited by ascending id; a
+ *       cone is named by its root, so an out-degree-0 gate that already roots a cone of
+ *       its level is not added twice; a gate that after both loops lies in no cone roots
+ *       one of its own in the list of its level, as the out-degree-0 gates do (the
+ *       partition is stated to cover the whole circuit). Lists are taken by ascending
+ *       level, mini-batches are consecutive runs of B cones of a list (the last one may
+ *       be short). In a mini-batch the cones are merged into one graph: a gate lying in
+ *       several of its cones is computed once, over the union of its per-cone
+ *       neighbourhoods {u in cone_i : u <=_k v}. Inside a mini-batch gates go by
+ *       ascending level and read their sources at the sources' final embeddings (R6),
+ *       from the historical store if marked, else as computed earlier in the batch.
+ *       Without marks (the ablation of Section 4.4) every gate of every mini-batch is
+ *       recomputed from its initial features inside that mini-batch and the last
+ *       result stands.
  *
  * Parity pins live in tests/ (brute-force dense masked attention, closed
  * forms, hand-worked graphs, invariances). The numeric values of embeddings
@@ -370,12 +385,10 @@ int orc_ffn(int64_t rows, int32_t d, const float* S, const float* W1, const floa
  * node the already projected [K | V] row of the node's final embedding; it is
  * a pure function of H_u, so using it changes no value.
  */
-static void node_step(const orc_layer* L, int64_t v, const double* Hd, const float* Hf,
-                      const double* kv_memo, int64_t n, double* out)
+static void node_step_row(const orc_layer* L, int64_t v, const int32_t* row_idx, const uint8_t* row_rel, int cnt,
+                          const double* Hd, const float* Hf, const double* kv_memo, int64_t n, double* out)
 {
     const int d = L->d;
-    const int64_t p0 = L->nbr_ptr[v];
-    const int cnt = (int)(L->nbr_ptr[v + 1] - p0);
     double* buf = (double*)malloc(sizeof(double) * (size_t)d * (2 * (size_t)cnt + 9));
     double *s = buf, *q = s + d, *a = q + d, *o = a + d, *src = o + d;
     double *k = src + d, *vv = k + (size_t)cnt * d, *u = vv + (size_t)cnt * d;   /* u: 4d */
@@ -384,7 +397,7 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
         const float* W = L->wqkv + (int64_t)l * d * 3 * d;
         vec_mat(s, d, W, 3 * d, 0, d, q);
         for (int j = 0; j < cnt; ++j) {
-            int64_t u = L->nbr_idx[p0 + j];
+            int64_t u = row_idx[j];
             if (u == v) {
                 vec_mat(s, d, W, 3 * d, d, d, k + (int64_t)j * d);
                 vec_mat(s, d, W, 3 * d, 2 * d, d, vv + (int64_t)j * d);
@@ -398,7 +411,7 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
                 vec_mat(src, d, W, 3 * d, 2 * d, d, vv + (int64_t)j * d);
             }
         }
-        attend(d, L->heads, cnt, q, k, vv, L->nbr_rel + p0, L->bias + (int64_t)l * L->heads * 4, a, NULL);
+        attend(d, L->heads, cnt, q, k, vv, row_rel, L->bias + (int64_t)l * L->heads * 4, a, NULL);
         vec_mat(a, d, L->wo + (int64_t)l * d * d, d, 0, d, o);
         if (L->epilogue) {
             for (int i = 0; i < d; ++i) s[i] += o[i];
@@ -411,6 +424,14 @@ static void node_step(const orc_layer* L, int64_t v, const double* Hd, const flo
     }
     for (int i = 0; i < d; ++i) out[i] = round_store(s[i], L->store);
     free(buf);
+}
+
+/* the same with the node's row of the layer's neighbour table */
+static void node_step(const orc_layer* L, int64_t v, const double* Hd, const float* Hf,
+                      const double* kv_memo, int64_t n, double* out)
+{
+    const int64_t p0 = L->nbr_ptr[v];
+    node_step_row(L, v, L->nbr_idx + p0, L->nbr_rel + p0, (int)(L->nbr_ptr[v + 1] - p0), Hd, Hf, kv_memo, n, out);
 }
 
 /*
@@ -476,6 +497,210 @@ int orc_layer_nodes(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32
 #pragma omp parallel for schedule(dynamic, 16)
     for (int64_t i = 0; i < n_listed; ++i)
         node_step(&L, nodes[i], NULL, Hsrc, NULL, n, out + i * d);
+    return ORC_OK;
+}
+
+/* ------------------------------------------------------------------------------------------
+ * Graph partition (Section 3.3, Algorithm 1) and updating strategy (Section 3.4, Algorithm 2),
+ * reading R17. cone_k(v) is passed in as the rows of orc_cone_csr (ascending id).
+ */
+typedef struct {
+    int64_t n_groups, n_cones, n_entries;
+    int32_t* group_level;   /* [n_groups]     level l of the list cones^l, ascending          */
+    int64_t* group_ptr;     /* [n_groups + 1] first cone of each list                         */
+    int32_t* cone_root;     /* [n_cones]      root of each cone, lists in order of insertion  */
+    int64_t* cone_ptr;      /* [n_cones + 1]  into cone_node                                  */
+    int32_t* cone_node;     /* [n_entries]    the gates of each cone, ascending id            */
+} orc_cones;
+
+void orc_cones_free(orc_cones* c)
+{
+    if (!c) return;
+    free(c->group_level); free(c->group_ptr); free(c->cone_root); free(c->cone_ptr); free(c->cone_node);
+    free(c);
+}
+
+/* Algorithm 1. Returns NULL on bad arguments or lack of memory. */
+orc_cones* orc_partition(int64_t n, int64_t e, const int32_t* src, const int32_t* level,
+                         int32_t k, int32_t delta, const int64_t* nbr_ptr, const int32_t* nbr_idx)
+{
+    if (n < 0 || k < 1 || delta < 1 || delta >= k) return NULL;
+    const size_t n1 = (size_t)(n > 0 ? n : 1);
+    int32_t* app_root = (int32_t*)malloc(sizeof(int32_t) * n1);     /* roots in order of insertion */
+    uint8_t* is_root = (uint8_t*)calloc(n1, 1);
+    uint8_t* in_cone = (uint8_t*)calloc(n1, 1);
+    uint8_t* has_out = (uint8_t*)calloc(n1, 1);
+    orc_cones* c = (orc_cones*)calloc(1, sizeof(orc_cones));
+    if (!app_root || !is_root || !in_cone || !has_out || !c) goto fail;
+    int64_t n_app = 0;
+    int32_t L = 0;
+    for (int64_t v = 0; v < n; ++v) if (level[v] > L) L = level[v];
+    for (int64_t i = 0; i < e; ++i) has_out[src[i]] = 1;
+    /* the cones that end at levels k, k + delta, ... */
+    for (int32_t l = k; l <= L; l += delta)
+        for (int64_t v = 0; v < n; ++v)
+            if (level[v] == l) {
+                app_root[n_app++] = (int32_t)v; is_root[v] = 1;
+                for (int64_t j = nbr_ptr[v]; j < nbr_ptr[v + 1]; ++j) in_cone[nbr_idx[j]] = 1;
+            }
+    /* the cones of the gates nothing reads */
+    for (int64_t v = 0; v < n; ++v)
+        if (!has_out[v] && !is_root[v]) {
+            app_root[n_app++] = (int32_t)v; is_root[v] = 1;
+            for (int64_t j = nbr_ptr[v]; j < nbr_ptr[v + 1]; ++j) in_cone[nbr_idx[j]] = 1;
+        }
+    /* R17: what is still in no cone (decided here, before any of these cones is added) */
+    for (int64_t v = 0; v < n; ++v)
+        if (!in_cone[v]) { app_root[n_app++] = (int32_t)v; is_root[v] = 1; }
+    /* the lists by ascending level, each in order of insertion */
+    int64_t* per_level = (int64_t*)calloc((size_t)L + 2, sizeof(int64_t));
+    if (!per_level) goto fail;
+    for (int64_t i = 0; i < n_app; ++i) ++per_level[level[app_root[i]] + 1];
+    int64_t groups = 0;
+    for (int32_t l = 0; l <= L; ++l) if (per_level[l + 1]) ++groups;
+    c->n_groups = groups; c->n_cones = n_app;
+    c->group_level = (int32_t*)malloc(sizeof(int32_t) * (size_t)(groups + 1));
+    c->group_ptr = (int64_t*)malloc(sizeof(int64_t) * (size_t)(groups + 1));
+    c->cone_root = (int32_t*)malloc(sizeof(int32_t) * (size_t)(n_app + 1));
+    c->cone_ptr = (int64_t*)malloc(sizeof(int64_t) * (size_t)(n_app + 1));
+    if (!c->group_level || !c->group_ptr || !c->cone_root || !c->cone_ptr) { free(per_level); goto fail; }
+    {
+        int64_t gi = 0, at = 0;
+        for (int32_t l = 0; l <= L; ++l) {
+            const int64_t cnt = per_level[l + 1];
+            per_level[l + 1] = at;                     /* from here on: where level l's list starts */
+            if (cnt) { c->group_level[gi] = l; c->group_ptr[gi] = at; ++gi; }
+            at += cnt;
+        }
+        c->group_ptr[groups] = at;
+    }
+    for (int64_t i = 0; i < n_app; ++i) c->cone_root[per_level[level[app_root[i]] + 1]++] = app_root[i];
+    free(per_level);
+    {
+        int64_t tot = 0;
+        for (int64_t i = 0; i < n_app; ++i) { const int32_t r = c->cone_root[i]; c->cone_ptr[i] = tot; tot += nbr_ptr[r + 1] - nbr_ptr[r]; }
+        c->cone_ptr[n_app] = tot; c->n_entries = tot;
+        c->cone_node = (int32_t*)malloc(sizeof(int32_t) * (size_t)(tot + 1));
+        if (!c->cone_node) goto fail;
+        for (int64_t i = 0; i < n_app; ++i) {
+            const int32_t r = c->cone_root[i];
+            memcpy(c->cone_node + c->cone_ptr[i], nbr_idx + nbr_ptr[r], sizeof(int32_t) * (size_t)(nbr_ptr[r + 1] - nbr_ptr[r]));
+        }
+    }
+    free(app_root); free(is_root); free(in_cone); free(has_out);
+    return c;
+fail:
+    free(app_root); free(is_root); free(in_cone); free(has_out);
+    orc_cones_free(c);
+    return NULL;
+}
+
+void orc_cones_sizes(const orc_cones* c, int64_t* n_groups, int64_t* n_cones, int64_t* n_entries)
+{
+    *n_groups = c->n_groups; *n_cones = c->n_cones; *n_entries = c->n_entries;
+}
+
+void orc_cones_copy(const orc_cones* c, int32_t* group_level, int64_t* group_ptr, int32_t* cone_root,
+                    int64_t* cone_ptr, int32_t* cone_node)
+{
+    memcpy(group_level, c->group_level, sizeof(int32_t) * (size_t)c->n_groups);
+    memcpy(group_ptr, c->group_ptr, sizeof(int64_t) * (size_t)(c->n_groups + 1));
+    memcpy(cone_root, c->cone_root, sizeof(int32_t) * (size_t)c->n_cones);
+    memcpy(cone_ptr, c->cone_ptr, sizeof(int64_t) * (size_t)(c->n_cones + 1));
+    memcpy(cone_node, c->cone_node, sizeof(int32_t) * (size_t)c->n_entries);
+}
+
+static const int32_t* sort_level;
+static int by_level_then_id(const void* a, const void* b)
+{
+    const int32_t x = *(const int32_t*)a, y = *(const int32_t*)b;
+    if (sort_level[x] != sort_level[y]) return sort_level[x] < sort_level[y] ? -1 : 1;
+    return x < y ? -1 : x > y;
+}
+
+/*
+ * Algorithm 2 at inference: the lists by ascending level (inter-level updating is what the
+ * marks left by earlier lists do), each list in mini-batches of `batch` cones (intra-level
+ * updating). nbr_* are the rows of cone_k (the relation <=_k with its codes, R5).
+ * mark = 0 is the ablation without marks. Outputs: H [n, d]; kept[j] (nullable) = 1 where
+ * entry j of cone_k(v) was in the neighbourhood v was (last) computed with; stage_of[v]
+ * (nullable) = running number of the mini-batch that (last) computed v; *n_computed
+ * (nullable) = gate computations in total.
+ */
+int orc_partitioned_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, int32_t store,
+                        int32_t epilogue, double ln_eps,
+                        const float* x, const float* wqkv, const float* wo, const float* bias,
+                        const float* w1 /* nullable */, const float* w2 /* nullable with w1 */,
+                        const int32_t* level, const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
+                        int64_t n_groups, const int64_t* group_ptr, const int64_t* cone_ptr, const int32_t* cone_node,
+                        int32_t batch, int32_t mark,
+                        double* H, uint8_t* kept, int32_t* stage_of, int64_t* n_computed)
+{
+    if (d <= 0 || d > 1024 || heads <= 0 || d % heads || n_layers <= 0 || batch < 1) return ORC_EINVAL;
+    if ((w1 == NULL) != (w2 == NULL) || (w1 && !epilogue)) return ORC_EINVAL;
+    orc_layer L = { d, heads, n_layers, store, epilogue, ln_eps, x, wqkv, wo, bias, w1, w2, nbr_ptr, nbr_idx, nbr_rel };
+    const size_t n1 = (size_t)(n > 0 ? n : 1);
+    const int64_t nnz = nbr_ptr[n];
+    uint8_t* updated = (uint8_t*)calloc(n1, 1);                 /* the marks */
+    uint8_t* keep = (uint8_t*)calloc((size_t)(nnz > 0 ? nnz : 1), 1);
+    int64_t* seen_in = (int64_t*)malloc(sizeof(int64_t) * n1);   /* last mini-batch a gate was met in */
+    int64_t* in_cone = (int64_t*)malloc(sizeof(int64_t) * n1);   /* last cone a gate was stamped for  */
+    int32_t* todo = (int32_t*)malloc(sizeof(int32_t) * n1);
+    int32_t* members = (int32_t*)malloc(sizeof(int32_t) * n1);
+    if (!updated || !keep || !seen_in || !in_cone || !todo || !members) {
+        free(updated); free(keep); free(seen_in); free(in_cone); free(todo); free(members);
+        return ORC_ENOMEM;
+    }
+    for (int64_t v = 0; v < n; ++v) { seen_in[v] = -1; in_cone[v] = -1; }
+    int64_t stage = 0, computed = 0;
+    for (int64_t g = 0; g < n_groups; ++g) {
+        for (int64_t b0 = group_ptr[g]; b0 < group_ptr[g + 1]; b0 += batch, ++stage) {
+            const int64_t b1 = b0 + batch < group_ptr[g + 1] ? b0 + batch : group_ptr[g + 1];
+            int64_t n_todo = 0, n_members = 0;
+            for (int64_t c = b0; c < b1; ++c) {
+                for (int64_t i = cone_ptr[c]; i < cone_ptr[c + 1]; ++i) in_cone[cone_node[i]] = c;
+                for (int64_t i = cone_ptr[c]; i < cone_ptr[c + 1]; ++i) {
+                    const int32_t v = cone_node[i];
+                    if (seen_in[v] != stage) {
+                        seen_in[v] = stage; members[n_members++] = v;
+                        if (!(mark && updated[v])) {
+                            todo[n_todo++] = v;
+                            memset(keep + nbr_ptr[v], 0, (size_t)(nbr_ptr[v + 1] - nbr_ptr[v]));
+                        }
+                    }
+                    if (mark && updated[v]) continue;       /* retrieved from the store, its in-edges dropped */
+                    /* the virtual edges of this cone into v: u <=_k v with u in the cone */
+                    for (int64_t j = nbr_ptr[v]; j < nbr_ptr[v + 1]; ++j)
+                        if (in_cone[nbr_idx[j]] == c) keep[j] = 1;
+                }
+            }
+            sort_level = level;
+            qsort(todo, (size_t)n_todo, sizeof(int32_t), by_level_then_id);
+            for (int64_t a = 0; a < n_todo;) {
+                int64_t z = a;
+                while (z < n_todo && level[todo[z]] == level[todo[a]]) ++z;
+#pragma omp parallel for schedule(dynamic, 8)
+                for (int64_t t = a; t < z; ++t) {
+                    const int32_t v = todo[t];
+                    int32_t idx[1 << 9]; uint8_t rel[1 << 9];
+                    int cnt = 0;
+                    for (int64_t j = nbr_ptr[v]; j < nbr_ptr[v + 1]; ++j)
+                        if (keep[j]) { idx[cnt] = nbr_idx[j]; rel[cnt] = nbr_rel[j]; ++cnt; }
+                    node_step_row(&L, v, idx, rel, cnt, H, NULL, NULL, n, H + (int64_t)v * d);
+                }
+                a = z;
+            }
+            computed += n_todo;
+            for (int64_t t = 0; t < n_todo; ++t) {
+                const int32_t v = todo[t];
+                if (stage_of) stage_of[v] = (int32_t)stage;
+                if (kept) memcpy(kept + nbr_ptr[v], keep + nbr_ptr[v], (size_t)(nbr_ptr[v + 1] - nbr_ptr[v]));
+            }
+            for (int64_t t = 0; t < n_members; ++t) updated[members[t]] = 1;
+        }
+    }
+    if (n_computed) *n_computed = computed;
+    free(updated); free(keep); free(seen_in); free(in_cone); free(todo); free(members);
     return ORC_OK;
 }
 

@@ -80,6 +80,37 @@ def layer_norm(t, eps):
     return (t - mu) / np.sqrt(var + eps)
 
 
+def dense_node(v, mask, relrow, x, H, wqkv, wo, rel_bias, heads, eps=1e-5, epilogue=True, w1=None, w2=None):
+    """All layers of node v over the sources selected by the boolean row `mask` (v included),
+    sources at their final embeddings in H: dense masked attention in float64."""
+    d = x.shape[1]
+    dh = d // heads
+    s = x[v].copy()
+    for l, (W, Wo, B) in enumerate(zip(wqkv, wo, rel_bias)):
+        W, Wo, B = (np.asarray(t, dtype=np.float64) for t in (W, Wo, B))
+        Wq, Wk, Wv = W[:, :d], W[:, d:2 * d], W[:, 2 * d:]
+        state = H.copy()
+        state[v] = s
+        state[~mask] = 0.0                           # never read; avoid NaN * 0
+        q = s @ Wq
+        K = state @ Wk
+        V = state @ Wv
+        a = np.zeros(d)
+        for h in range(heads):
+            sl = slice(h * dh, (h + 1) * dh)
+            sc = K[:, sl] @ q[sl] / np.sqrt(dh) + B[h][relrow]
+            sc = np.where(mask, sc, -np.inf)
+            p = np.exp(sc - sc.max())
+            p /= p.sum()
+            a[sl] = p @ V[:, sl]
+        o = a @ Wo
+        s = layer_norm(s + o, eps) if epilogue else o
+        if w1 is not None:
+            hid = np.maximum(s @ np.asarray(w1[l], dtype=np.float64), 0.0)
+            s = layer_norm(s + hid @ np.asarray(w2[l], dtype=np.float64), eps)
+    return s
+
+
 def dense_layer(n, src, dst, inv, hops, x, wqkv, wo, rel_bias, heads, eps=1e-5, epilogue=True, w1=None, w2=None):
     """Brute-force dense masked attention, float64, one node at a time.
 
@@ -89,32 +120,63 @@ def dense_layer(n, src, dst, inv, hops, x, wqkv, wo, rel_bias, heads, eps=1e-5, 
     """
     x = np.asarray(x, dtype=np.float64)
     d = x.shape[1]
-    dh = d // heads
     A, reach, rel = dense_masks(n, src, dst, inv, hops)
     H = np.full((n, d), np.nan)
     for v in dfs_topological(n, A):
-        s = x[v].copy()
-        for l, (W, Wo, B) in enumerate(zip(wqkv, wo, rel_bias)):
-            W, Wo, B = (np.asarray(t, dtype=np.float64) for t in (W, Wo, B))
-            Wq, Wk, Wv = W[:, :d], W[:, d:2 * d], W[:, 2 * d:]
-            state = H.copy()
-            state[v] = s
-            state[~reach[v]] = 0.0                       # never read; avoid NaN * 0
-            q = s @ Wq
-            K = state @ Wk
-            V = state @ Wv
-            a = np.zeros(d)
-            for h in range(heads):
-                sl = slice(h * dh, (h + 1) * dh)
-                sc = K[:, sl] @ q[sl] / np.sqrt(dh) + B[h][rel[v]]
-                sc = np.where(reach[v], sc, -np.inf)
-                p = np.exp(sc - sc.max())
-                p /= p.sum()
-                a[sl] = p @ V[:, sl]
-            o = a @ Wo
-            s = layer_norm(s + o, eps) if epilogue else o
-            if w1 is not None:
-                hid = np.maximum(s @ np.asarray(w1[l], dtype=np.float64), 0.0)
-                s = layer_norm(s + hid @ np.asarray(w2[l], dtype=np.float64), eps)
-        H[v] = s
+        H[v] = dense_node(v, reach[v], rel[v], x, H, wqkv, wo, rel_bias, heads, eps, epilogue, w1, w2)
     return H
+
+
+def set_partition(n, src, level, reach, k, delta):
+    """Algorithm 1 with Python sets over the dense k-hop reachability: {level: [roots]}.
+    Roots of the stride loop by ascending id, then the gates nothing reads, then (one
+    decision for all of them) the gates that lie in no cone so far."""
+    lists = {}
+    top = max(level) if n else 0
+    l = k
+    while l <= top:
+        lists[l] = [v for v in range(n) if level[v] == l]
+        l += delta
+    read = set(int(s) for s in src)
+    for v in range(n):
+        if v not in read and v not in lists.get(level[v], []):
+            lists.setdefault(level[v], []).append(v)
+    covered = np.zeros(n, dtype=bool)
+    for roots in lists.values():
+        for r in roots:
+            covered |= reach[r]
+    for v in range(n):
+        if not covered[v]:
+            lists.setdefault(level[v], []).append(v)
+    return {l: r for l, r in lists.items() if r}
+
+
+def dense_partitioned(n, src, dst, inv, level, k, delta, batch, x, wqkv, wo, rel_bias, heads, mark=True,
+                      eps=1e-5, w1=None, w2=None):
+    """Algorithm 2 at inference by brute force: per mini-batch a dense N x N mask (the union
+    over the batch's cones of "both ends in the cone, and u within k hops of v"), members
+    computed in a depth-first topological order. Returns (H, masks, computations) with
+    masks[v] the mask row v was last computed with."""
+    x = np.asarray(x, dtype=np.float64)
+    A, reach, rel = dense_masks(n, src, dst, inv, k)
+    lists = set_partition(n, src, level, reach, k, delta)
+    topo = dfs_topological(n, A)
+    H = np.full((n, x.shape[1]), np.nan)
+    masks = np.zeros((n, n), dtype=bool)
+    updated = np.zeros(n, dtype=bool)
+    work = 0
+    for l in sorted(lists):
+        roots = lists[l]
+        for b in range(0, len(roots), batch):
+            M = np.zeros((n, n), dtype=bool)
+            members = np.zeros(n, dtype=bool)
+            for r in roots[b:b + batch]:
+                M |= np.outer(reach[r], reach[r]) & reach
+                members |= reach[r]
+            for v in topo:
+                if members[v] and not (mark and updated[v]):
+                    H[v] = dense_node(v, M[v], rel[v], x, H, wqkv, wo, rel_bias, heads, eps, True, w1, w2)
+                    masks[v] = M[v]
+                    work += 1
+            updated |= members
+    return H, masks, work
