@@ -108,6 +108,28 @@ int dg4_build_levels_device(int64_t n_nodes, int64_t n_edges,
                             int32_t hops, const int32_t* level_hint /* nullable */,
                             void* stream, dg4_graph** out);
 
+/*
+ * Graph analysis under the general partition and updating strategy (Section 3.3, Algorithm 1;
+ * Section 3.4, Algorithm 2, at inference): cones of depth k = hops are collected at levels k,
+ * k + stride, ... (stride < hops), then for every gate that nothing reads, then for every gate that
+ * is still in no cone (the partition covers the whole circuit); the cones of a level form a list, in
+ * that order, each part by ascending id, and are processed in mini-batches of batch_cones consecutive
+ * cones, lists by ascending level. A gate is computed once, by the first mini-batch that holds it,
+ * and marked; its neighbour row is what that mini-batch shows of its cone: the union, over the
+ * mini-batch's cones c that hold v, of { u in c : u in cone_hops(v) }. Later mini-batches read it
+ * from the historical embeddings. Since a marked gate never changes and every source of a gate lies
+ * below it, the embeddings are those of one sweep in level order over these rows: the returned graph
+ * is used with every other call exactly like one from dg4_build_levels (rows are subsets of that
+ * call's rows, same order and codes), and its nnz counts the kept entries.
+ * HOST call, host pointers. Errors as dg4_build_levels; EINVAL if stride < 1, stride >= hops or
+ * batch_cones < 1.
+ */
+int dg4_build_partitioned(int64_t n_nodes, int64_t n_edges,
+                          const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,
+                          int32_t hops, const int32_t* level_hint /* nullable */,
+                          int32_t stride, int32_t batch_cones,
+                          dg4_graph** out);
+
 /* Tables of a graph, borrowed host pointers valid until dg4_graph_free. */
 typedef enum {
     DG4_LEVEL = 0,      /* int32  [n_nodes]                                    */
@@ -129,7 +151,13 @@ typedef enum {
      * dependencies between them (the second may be empty). Built on first request. For inspection
      * and tests. */
     DG4_PAIR_ORDER = 10,    /* int32 [n_nodes]                                           */
-    DG4_PAIR_TILE_PTR = 11  /* int64 [n_tiles + 1], n_tiles even                         */
+    DG4_PAIR_TILE_PTR = 11, /* int64 [n_tiles + 1], n_tiles even                         */
+    /* Graphs from dg4_build_partitioned only (EINVAL otherwise): Algorithm 1's lists and the
+     * running number of the mini-batch that computes each gate. */
+    DG4_CONE_ROOT = 12,        /* int32 [n_cones]      roots, list after list                */
+    DG4_CONE_GROUP_LEVEL = 13, /* int32 [n_lists]      level of each list, ascending         */
+    DG4_CONE_GROUP_PTR = 14,   /* int64 [n_lists + 1]  first cone of each list               */
+    DG4_STAGE = 15             /* int32 [n_nodes]                                            */
 } dg4_array;
 
 int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count);

@@ -137,11 +137,109 @@ void cone_step(int64_t n, const Fanins& f, const ConeTable& prev, ConeTable& nex
     }
 }
 
+// Graph partition and updating strategy (Section 3.3, Algorithm 1; Section 3.4, Algorithm 2) turned
+// into neighbour rows. Every root gets the running number of its mini-batch (lists by ascending
+// level, inside a list the roots of the stride loop, then the unread gates, then the gates left in
+// no cone, each part by ascending id); a gate is computed by the smallest number among the cones
+// that hold it, and keeps the entries of its cone row that lie in one of that mini-batch's cones
+// together with it. Rows of g hold cone_hops(v), ascending id, on entry.
+void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, int32_t batch)
+{
+    const int64_t n = g->n;
+    const int32_t k = g->hops;
+    enum : uint8_t { STRIDE = 0, UNREAD = 1, LEFT = 2, NONE = 255 };
+    std::vector<uint8_t> kind((size_t)n, NONE), read((size_t)n, 0), covered((size_t)n, 0);
+    for (int64_t v = 0; v < n; ++v)
+        for (int i = 0; i < 2; ++i)
+            if (f.src[2 * (size_t)v + i] >= 0) read[(size_t)f.src[2 * (size_t)v + i]] = 1;
+    for (int64_t v = 0; v < n; ++v) {
+        const int32_t l = g->level[v];
+        if (l >= k && (l - k) % stride == 0) kind[v] = STRIDE;
+        else if (!read[v]) kind[v] = UNREAD;
+        if (kind[v] != NONE)
+            for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j) covered[(size_t)g->nbr_idx[j]] = 1;
+    }
+    for (int64_t v = 0; v < n; ++v)
+        if (!covered[v]) kind[v] = LEFT;
+    // the lists, and the mini-batch number of every root
+    std::vector<int32_t> root_stage((size_t)n, -1);
+    int32_t stage = 0;
+    for (int32_t l = 0; l <= g->max_level; ++l) {
+        const size_t first_cone = g->cone_root.size();
+        for (uint8_t part = STRIDE; part <= LEFT; ++part)
+            for (int64_t q = g->level_ptr[l]; q < g->level_ptr[l + 1]; ++q)
+                if (kind[(size_t)g->order[q]] == part) g->cone_root.push_back(g->order[q]);
+        const size_t cones = g->cone_root.size() - first_cone;
+        if (!cones) continue;
+        g->cone_group_level.push_back(l);
+        g->cone_group_ptr.push_back((int64_t)first_cone);
+        for (size_t c = 0; c < cones; ++c) root_stage[(size_t)g->cone_root[first_cone + c]] = stage + (int32_t)(c / (size_t)batch);
+        stage += (int32_t)((cones + (size_t)batch - 1) / (size_t)batch);
+    }
+    g->cone_group_ptr.push_back((int64_t)g->cone_root.size());
+    // the mini-batch that computes a gate: the first one that holds it
+    g->stage.assign((size_t)n, INT32_MAX);
+    for (const int32_t r : g->cone_root)
+        for (int64_t j = g->nbr_ptr[r]; j < g->nbr_ptr[r + 1]; ++j) {
+            int32_t& s = g->stage[(size_t)g->nbr_idx[j]];
+            s = std::min(s, root_stage[(size_t)r]);
+        }
+    // entries kept: u in cone(v) and in cone(r), for the roots r of that mini-batch with v in cone(r)
+    std::vector<uint8_t> keep((size_t)g->nnz, 0);
+    for (const int32_t r : g->cone_root) {
+        const int64_t r0 = g->nbr_ptr[r], r1 = g->nbr_ptr[r + 1];
+        for (int64_t j = r0; j < r1; ++j) {
+            const int32_t v = g->nbr_idx[j];
+            if (g->stage[(size_t)v] != root_stage[(size_t)r]) continue;
+            int64_t a = g->nbr_ptr[v], b = r0;                // two ascending rows
+            const int64_t a1 = g->nbr_ptr[v + 1];
+            while (a < a1 && b < r1) {
+                const int32_t x = g->nbr_idx[a], y = g->nbr_idx[b];
+                if (x == y) { keep[(size_t)a] = 1; ++a; ++b; }
+                else if (x < y) ++a;
+                else ++b;
+            }
+        }
+    }
+    int64_t out = 0;
+    for (int64_t v = 0; v < n; ++v) {
+        const int64_t lo = g->nbr_ptr[v], hi = g->nbr_ptr[v + 1];
+        g->nbr_ptr[v] = out;
+        for (int64_t j = lo; j < hi; ++j)
+            if (keep[(size_t)j]) { g->nbr_idx[(size_t)out] = g->nbr_idx[(size_t)j]; g->nbr_rel[(size_t)out] = g->nbr_rel[(size_t)j]; ++out; }
+    }
+    g->nbr_ptr[n] = out; g->nnz = out;
+    g->nbr_idx.resize((size_t)out); g->nbr_rel.resize((size_t)out);
+    g->fanin = f.src;
+    g->stride = stride; g->batch_cones = batch;
+}
+
+int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei, int32_t hops,
+                const int32_t* level_hint, int32_t stride, int32_t batch, dg4_graph** out);
+
 }  // namespace
 
 extern "C" int dg4_build_levels(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
                                 const uint8_t* ei, int32_t hops, const int32_t* level_hint,
                                 dg4_graph** out)
+{
+    return build_graph(n, e, es, ed, ei, hops, level_hint, 0, 0, out);
+}
+
+extern "C" int dg4_build_partitioned(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
+                                     const uint8_t* ei, int32_t hops, const int32_t* level_hint,
+                                     int32_t stride, int32_t batch_cones, dg4_graph** out)
+{
+    if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
+    if (stride < 1 || stride >= hops || batch_cones < 1) return DG4_EINVAL;
+    return build_graph(n, e, es, ed, ei, hops, level_hint, stride, batch_cones, out);
+}
+
+namespace {
+
+// stride == 0: plain cone rows; else the rows of the partitioned update
+int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei, int32_t hops,
+                const int32_t* level_hint, int32_t stride, int32_t batch, dg4_graph** out)
 {
     if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
     if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
@@ -213,6 +311,7 @@ extern "C" int dg4_build_levels(int64_t n, int64_t e, const int32_t* es, const i
             }
             for (int64_t v = 0; v < n; ++v) g->out_not[v] += inverter[v];
         }
+        if (stride > 0) restrict_rows_to_partition(g, f, stride, batch);
         *out = guard.release();
         return DG4_OK;
     } catch (const std::bad_alloc&) {
@@ -221,6 +320,8 @@ extern "C" int dg4_build_levels(int64_t n, int64_t e, const int32_t* es, const i
         return DG4_EINVAL;
     }
 }
+
+}  // namespace
 
 extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count)
 {
@@ -258,6 +359,16 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
         else { *host_ptr = g->pair_tile_ptr.data(); *count = (int64_t)g->pair_tile_ptr.size(); }
         break;
     }
+    case DG4_CONE_ROOT:
+    case DG4_CONE_GROUP_LEVEL:
+    case DG4_CONE_GROUP_PTR:
+    case DG4_STAGE:
+        if (g->stride == 0) return DG4_EINVAL;
+        if (which == DG4_CONE_ROOT) { *host_ptr = g->cone_root.data(); *count = (int64_t)g->cone_root.size(); }
+        else if (which == DG4_CONE_GROUP_LEVEL) { *host_ptr = g->cone_group_level.data(); *count = (int64_t)g->cone_group_level.size(); }
+        else if (which == DG4_CONE_GROUP_PTR) { *host_ptr = g->cone_group_ptr.data(); *count = (int64_t)g->cone_group_ptr.size(); }
+        else { *host_ptr = g->stage.data(); *count = g->n; }
+        break;
     default: return DG4_EINVAL;
     }
     return DG4_OK;
@@ -288,16 +399,26 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
     try {
         std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
         std::vector<int32_t> remaining((size_t)g->n, 0);
+        // direct fanins: the entries with codes 1 and 2 of a whole cone row; a row cut by the
+        // partition may lack one (while keeping a source behind it), so those graphs carry the
+        // fanin table itself
+        auto for_each_fanin = [&](int64_t v, auto&& fn) {
+            if (!g->fanin.empty()) {
+                for (int i = 0; i < 2; ++i)
+                    if (g->fanin[2 * (size_t)v + i] >= 0) fn(g->fanin[2 * (size_t)v + i]);
+            } else {
+                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                    if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fn(g->nbr_idx[j]);
+            }
+        };
         for (int64_t v = 0; v < g->n; ++v)
-            for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
-                if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) { ++fo_ptr[(size_t)g->nbr_idx[j] + 1]; ++remaining[v]; }
+            for_each_fanin(v, [&](int32_t u) { ++fo_ptr[(size_t)u + 1]; ++remaining[v]; });
         for (int64_t v = 0; v < g->n; ++v) fo_ptr[v + 1] += fo_ptr[v];
         std::vector<int32_t> fo((size_t)fo_ptr[g->n]);
         {
             std::vector<int64_t> fill(fo_ptr.begin(), fo_ptr.end() - 1);
             for (int64_t v = 0; v < g->n; ++v)
-                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
-                    if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fo[(size_t)fill[g->nbr_idx[j]]++] = (int32_t)v;
+                for_each_fanin(v, [&](int32_t u) { fo[(size_t)fill[u]++] = (int32_t)v; });
         }
         // the ready list is a queue of batches, one per tile, each sorted by (level, id)
         auto before = [&](int32_t a, int32_t b) { return g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };

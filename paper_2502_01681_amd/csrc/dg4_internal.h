@@ -30,6 +30,12 @@ struct dg4_graph {
     int32_t* d_struct = nullptr;                 // device [n][3]: level, OutAND, OutNOT (on first dg4_struct_encode)
     std::vector<int32_t> nbr_idx;
     std::vector<uint8_t> nbr_rel;
+    // Partitioned graphs (dg4_build_partitioned): rows may lack a direct fanin, so the fanin table
+    // is kept for the schedulers ([2n], -1 = none); Algorithm 1's lists; the mini-batch of each gate.
+    int32_t stride = 0, batch_cones = 0;
+    std::vector<int32_t> fanin;
+    std::vector<int32_t> cone_root, cone_group_level, stage;
+    std::vector<int64_t> cone_group_ptr;
 
     // device mirror (one device), created once under `mu`
     std::mutex mu;

@@ -1,0 +1,112 @@
+"""Host side of dg4_build_partitioned (no GPU): Algorithm 1's lists, the mini-batch of every gate
+and the neighbour rows equal, bit for bit, what the oracle's literal run of Algorithms 1 and 2
+uses (Sections 3.3 and 3.4); the processing orders built from such rows stay valid schedules."""
+import numpy as np
+import pytest
+
+import dg4_synth as synth
+import oracle
+import paper_2502_01681_amd as dg4
+from test_oracle_partition import irregular, layered, load_partition_cases, problem
+
+
+def oracle_run(n, src, dst, inv, k, delta, batch, hint=None):
+    og = oracle.build_levels(n, src, dst, inv, k, level_hint=hint)
+    cones = oracle.partition(og, src, delta)
+    x, wqkv, wo, rb = problem(n, d=4, heads=1)
+    _, rows, stage, work = oracle.partitioned_fwd(og, cones, batch, x, wqkv, wo, rb, 1)
+    assert work == n
+    return og, cones, rows, stage
+
+
+def same_partition(g, og, cones, rows, stage):
+    assert (g.array("level") == og.level).all() and (g.array("order") == og.order).all()
+    assert (g.array("cone_root") == cones.cone_root).all()
+    assert (g.array("cone_group_level") == cones.group_level).all()
+    assert (g.array("cone_group_ptr") == cones.group_ptr).all()
+    assert (g.array("stage") == stage).all()
+    for name, ref in zip(("nbr_ptr", "nbr_idx", "nbr_rel"), rows):
+        mine = g.array(name)
+        assert mine.dtype == ref.dtype and mine.shape == ref.shape and (mine == ref).all(), name
+    assert g.nnz == len(rows[1])
+
+
+@pytest.mark.parametrize("case", load_partition_cases(), ids=lambda c: c["name"])
+def test_hand_worked_cases(case):
+    g = dg4.dg4_build_partitioned(case["n"], case["src"], case["dst"], case["inv"], case["k"], case["delta"],
+                                  case["batch"], level_hint=case["hint"])
+    ptr, idx, rel = g.array("nbr_ptr"), g.array("nbr_idx"), g.array("nbr_rel")
+    for v, row in case["rows"].items():
+        assert list(zip(idx[ptr[v]:ptr[v + 1]].tolist(), rel[ptr[v]:ptr[v + 1]].tolist())) == row
+    assert g.array("stage").tolist() == case["stage"]
+    assert g.array("cone_root").tolist() == [r for _, roots in case["groups"] for r in roots]
+    assert g.array("cone_group_level").tolist() == [l for l, _ in case["groups"]]
+
+
+@pytest.mark.parametrize("seed,k,delta,batch,cap", [
+    (1, 3, 2, 1, 0), (2, 3, 2, 4, 0), (3, 3, 1, 3, 0), (4, 2, 1, 128, 0), (7, 3, 2, 3, 30), (9, 3, 2, 2, -1),
+    (10, 3, 2, 128, -1), (11, 3, 1, 5, -1),
+])
+def test_small_graphs_bit_for_bit(seed, k, delta, batch, cap):
+    n, src, dst, inv, hint = irregular(seed, n_and=300, window=24, cap=cap)
+    g = dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch, level_hint=hint)
+    same_partition(g, *oracle_run(n, src, dst, inv, k, delta, batch, hint))
+
+
+@pytest.mark.parametrize("cfg,k,delta,batch", [("tiny", 3, 2, 128), ("small", 3, 2, 128), ("medium", 2, 1, 16)])
+def test_configs_bit_for_bit(cfg, k, delta, batch):
+    w = synth.make(cfg, n_and=20000 if cfg != "tiny" else None, features=False)
+    n, src, dst, inv = w.cfg.n_nodes, w.edge_src, w.edge_dst, w.edge_inv
+    g = dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch, level_hint=w.level_hint)
+    og, cones, rows, stage = oracle_run(n, src, dst, inv, k, delta, batch, w.level_hint)
+    same_partition(g, og, cones, rows, stage)
+    full = dg4.dg4_build_levels(n, src, dst, inv, k, level_hint=w.level_hint)
+    assert g.nnz <= full.nnz
+
+
+def test_layered_circuit():
+    n, src, dst, inv = layered(31, 6, 10)
+    g = dg4.dg4_build_partitioned(n, src, dst, inv, 3, 2, 4)
+    same_partition(g, *oracle_run(n, src, dst, inv, 3, 2, 4))
+
+
+def test_arguments():
+    n, src, dst, inv, _ = irregular(1)
+    for k, delta, batch in [(3, 3, 1), (3, 0, 1), (2, 2, 8), (3, 2, 0), (1, 1, 1)]:
+        with pytest.raises(dg4.DG4Error) as e:
+            dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch)
+        assert e.value.name == "EINVAL"
+    with pytest.raises(dg4.DG4Error) as e:
+        dg4.dg4_build_partitioned(n, src, dst, inv, 4, 2, 8)
+    assert e.value.name == "EUNSUPPORTED"
+    plain = dg4.dg4_build_levels(n, src, dst, inv, 3)
+    with pytest.raises(dg4.DG4Error):
+        plain.array("stage")
+    empty = dg4.dg4_build_partitioned(0, [], [], [], 3, 2, 8)
+    assert empty.array("cone_root").size == 0 and empty.array("cone_group_ptr").tolist() == [0]
+
+
+@pytest.mark.parametrize("which", ["flow", "pair"])
+def test_processing_orders_put_every_source_in_an_earlier_tile(which):
+    """Rows cut by the partition may keep a distant source while losing the fanin in between: the
+    orders must still come from the circuit's real edges."""
+    n, src, dst, inv, hint = irregular(9, n_and=3000, window=48, cap=-1)
+    g = dg4.dg4_build_partitioned(n, src, dst, inv, 3, 2, 8, level_hint=hint)
+    order, tile_ptr = g.array(which + "_order"), g.array(which + "_tile_ptr")
+    assert sorted(order.tolist()) == list(range(n))
+    tile_of = np.empty(n, dtype=np.int64)
+    for t in range(len(tile_ptr) - 1):
+        tile_of[order[tile_ptr[t]:tile_ptr[t + 1]]] = t // 2 if which == "pair" else t
+    ptr, idx, rel = g.array("nbr_ptr"), g.array("nbr_idx"), g.array("nbr_rel")
+    fanins = {}
+    for s, t in zip(src.tolist(), dst.tolist()):
+        fanins.setdefault(t, []).append(s)
+    lost = 0
+    for v in range(n):
+        row = idx[ptr[v]:ptr[v + 1]]
+        for u in row:
+            assert u == v or tile_of[u] < tile_of[v]
+        lost += any(u not in row for u in fanins.get(v, [])) and (rel[ptr[v]:ptr[v + 1]] == 3).any()
+    assert lost > 20            # the case this test is about does occur
+    for s, t in zip(src.tolist(), dst.tolist()):
+        assert tile_of[s] < tile_of[t]
