@@ -29,6 +29,8 @@ extern "C" {
 
 typedef struct dg4_graph dg4_graph;
 
+#define DG4_MAX_HOPS 8      /* deepest cone (the paper's k = 8): rows of at most 2^9 - 1 entries */
+
 typedef enum { DG4_F32 = 0, DG4_BF16 = 1 } dg4_dtype;
 
 typedef enum {
@@ -38,7 +40,7 @@ typedef enum {
     DG4_EFANIN = -3,        /* in-degree above 2, or the same (src,dst) pair twice         */
     DG4_ECYCLE = -4,        /* the edge list is not a DAG (self loops included)            */
     DG4_EHINT = -5,         /* level_hint is not a topological levelling with PIs at 0     */
-    DG4_EUNSUPPORTED = -6,  /* head dim != 32, hidden not 128/256, hops not 1..3, layers>8 */
+    DG4_EUNSUPPORTED = -6,  /* head dim != 32, hidden not 128/256, hops not 1..8, layers>8 */
     DG4_ENOMEM = -7,        /* host or device allocation failed                            */
     DG4_EWORKSPACE = -8,    /* workspace missing, misaligned (256 B) or too small          */
     DG4_EHIP = -9           /* a HIP runtime call failed                                   */
@@ -79,8 +81,8 @@ typedef struct {
  *     level only names the ranges a sweep can be cut into (level_begin, level_end of
  *     dg4_layer_fwd) and orders the work of a partial sweep; embeddings do not depend on it.
  *   - order: node ids sorted by (level, id).
- *   - neighbour rows N(v) = cone_hops(v), v included, at most 2^(hops+1)-1
- *     entries, ascending id, each with a relation code: 0 self, 1 direct fanin,
+ *   - neighbour rows N(v) = cone_hops(v), v included, hops in 1..DG4_MAX_HOPS, at most
+ *     2^(hops+1)-1 entries, ascending id, each with a relation code: 0 self, 1 direct fanin,
  *     2 direct inverted fanin, 3 ancestor first reached by >= 2 edges (the
  *     virtual edges of Section 3.5). The shortest path decides the code.
  * On success *out owns host copies of all tables; free with dg4_graph_free.
@@ -101,7 +103,7 @@ int dg4_build_levels(int64_t n_nodes, int64_t n_edges,
  * allocated and released inside the call, and the tables are copied to host memory, where the graph
  * object keeps them. Errors as dg4_build_levels; if an edge list has defects of several kinds, the
  * kind reported may differ from the host call's (which reports the first in edge order), and an
- * invalid hint on a cyclic graph gives EHINT. Also EHIP.
+ * invalid hint on a cyclic graph gives EHINT. Also EHIP. hops above 3: EUNSUPPORTED (host call only).
  */
 int dg4_build_levels_device(int64_t n_nodes, int64_t n_edges,
                             const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,

@@ -86,7 +86,7 @@ def _load():
         lib.orc_partitioned_fwd.argtypes = [_I64, _I32, _I32, _I32, _I32, _I32, _F64,
                                             _P, _P, _P, _P, _P, _P,
                                             _P, _P, _P, _P,
-                                            _I64, _P, _P, _P, _I32, _I32,
+                                            _I64, _P, _P, _P, _I32, _I32, _I32,
                                             _P, _P, _P, _P]
         _lib = lib
     return _lib
@@ -311,7 +311,7 @@ def _hops_of(g: Graph) -> int:
 
 
 def partitioned_fwd(g: Graph, cones: Cones, batch, x, wqkv, wo, rel_bias, heads, *, mark=True, store="f64",
-                    epilogue=True, ln_eps=1e-5, w1=None, w2=None):
+                    epilogue=True, ln_eps=1e-5, w1=None, w2=None, memo=True):
     """Algorithm 2 at inference over Algorithm 1's lists (reading R17).
 
     Returns (H [N,d] float64, rows, stage_of, n_computed): rows = (ptr, idx, rel) of the
@@ -330,7 +330,7 @@ def partitioned_fwd(g: Graph, cones: Cones, batch, x, wqkv, wo, rel_bias, heads,
                                      _ptr(x), _ptr(Wqkv), _ptr(Wo), _ptr(B), _ptr(W1), _ptr(W2),
                                      _ptr(g.level), _ptr(g.nbr_ptr), _ptr(g.nbr_idx), _ptr(g.nbr_rel),
                                      len(cones.group_level), _ptr(cones.group_ptr), _ptr(cones.cone_ptr),
-                                     _ptr(cones.cone_node), int(batch), int(mark),
+                                     _ptr(cones.cone_node), int(batch), int(mark), int(memo),
                                      _ptr(H), _ptr(kept), _ptr(stage_of), ctypes.addressof(n_computed))
     if rc:
         raise OracleError(rc)

@@ -622,7 +622,8 @@ static int by_level_then_id(const void* a, const void* b)
  * Algorithm 2 at inference: the lists by ascending level (inter-level updating is what the
  * marks left by earlier lists do), each list in mini-batches of `batch` cones (intra-level
  * updating). nbr_* are the rows of cone_k (the relation <=_k with its codes, R5).
- * mark = 0 is the ablation without marks. Outputs: H [n, d]; kept[j] (nullable) = 1 where
+ * mark = 0 is the ablation without marks. memo != 0 keeps the projected K | V of every gate's
+ * current embedding (a pure function of that embedding: same values, less work). Outputs: H [n, d]; kept[j] (nullable) = 1 where
  * entry j of cone_k(v) was in the neighbourhood v was (last) computed with; stage_of[v]
  * (nullable) = running number of the mini-batch that (last) computed v; *n_computed
  * (nullable) = gate computations in total.
@@ -633,7 +634,7 @@ int orc_partitioned_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, i
                         const float* w1 /* nullable */, const float* w2 /* nullable with w1 */,
                         const int32_t* level, const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel,
                         int64_t n_groups, const int64_t* group_ptr, const int64_t* cone_ptr, const int32_t* cone_node,
-                        int32_t batch, int32_t mark,
+                        int32_t batch, int32_t mark, int32_t memo,
                         double* H, uint8_t* kept, int32_t* stage_of, int64_t* n_computed)
 {
     if (d <= 0 || d > 1024 || heads <= 0 || d % heads || n_layers <= 0 || batch < 1) return ORC_EINVAL;
@@ -647,8 +648,9 @@ int orc_partitioned_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, i
     int64_t* in_cone = (int64_t*)malloc(sizeof(int64_t) * n1);   /* last cone a gate was stamped for  */
     int32_t* todo = (int32_t*)malloc(sizeof(int32_t) * n1);
     int32_t* members = (int32_t*)malloc(sizeof(int32_t) * n1);
-    if (!updated || !keep || !seen_in || !in_cone || !todo || !members) {
-        free(updated); free(keep); free(seen_in); free(in_cone); free(todo); free(members);
+    double* kv = memo ? (double*)malloc(sizeof(double) * (size_t)n_layers * n1 * 2 * (size_t)d) : NULL;
+    if (!updated || !keep || !seen_in || !in_cone || !todo || !members || (memo && !kv)) {
+        free(updated); free(keep); free(seen_in); free(in_cone); free(todo); free(members); free(kv);
         return ORC_ENOMEM;
     }
     for (int64_t v = 0; v < n; ++v) { seen_in[v] = -1; in_cone[v] = -1; }
@@ -686,8 +688,14 @@ int orc_partitioned_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, i
                     int cnt = 0;
                     for (int64_t j = nbr_ptr[v]; j < nbr_ptr[v + 1]; ++j)
                         if (keep[j]) { idx[cnt] = nbr_idx[j]; rel[cnt] = nbr_rel[j]; ++cnt; }
-                    node_step_row(&L, v, idx, rel, cnt, H, NULL, NULL, n, H + (int64_t)v * d);
+                    node_step_row(&L, v, idx, rel, cnt, H, NULL, kv, n, H + (int64_t)v * d);
                 }
+                if (kv)                     /* after the level: no gate of it reads another */
+#pragma omp parallel for schedule(static)
+                    for (int64_t t = a; t < z; ++t)
+                        for (int l = 0; l < n_layers; ++l)
+                            vec_mat(H + (int64_t)todo[t] * d, d, wqkv + (int64_t)l * d * 3 * d, 3 * d, d, 2 * d,
+                                    kv + ((int64_t)l * n + todo[t]) * 2 * d);
                 a = z;
             }
             computed += n_todo;
@@ -700,7 +708,7 @@ int orc_partitioned_fwd(int64_t n, int32_t d, int32_t heads, int32_t n_layers, i
         }
     }
     if (n_computed) *n_computed = computed;
-    free(updated); free(keep); free(seen_in); free(in_cone); free(todo); free(members);
+    free(updated); free(keep); free(seen_in); free(in_cone); free(todo); free(members); free(kv);
     return ORC_OK;
 }
 

@@ -20,7 +20,7 @@ int check_cfg(const dg4_layer_cfg* c, bool need_layers)
     if ((c->flags & DG4_FFN) && (c->flags & DG4_NO_EPILOGUE)) return DG4_EINVAL;
     if (c->hidden != 128 && c->hidden != 256) return DG4_EUNSUPPORTED;
     if (c->heads <= 0 || c->heads * 32 != c->hidden) return DG4_EUNSUPPORTED;
-    if (c->hops < 1 || c->hops > 3) return DG4_EUNSUPPORTED;
+    if (c->hops < 1 || c->hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
     if (need_layers && (c->n_layers < 1 || c->n_layers > DG4_MAX_LAYERS)) return DG4_EUNSUPPORTED;
     if (!(c->ln_eps >= 0.f)) return DG4_EINVAL;
     return DG4_OK;

@@ -137,6 +137,41 @@ void cone_step(int64_t n, const Fanins& f, const ConeTable& prev, ConeTable& nex
     }
 }
 
+// Cones deeper than three hops (up to 2^(k+1)-1 gates, usually far fewer): one backward search per
+// gate over the fanin table, frontier by frontier, so that the first visit fixes the shortest hop;
+// a per-gate stamp marks what has been reached. Rows are then sorted by id.
+void deep_cones(dg4_graph* g, const Fanins& f)
+{
+    const int64_t n = g->n;
+    std::vector<int32_t> seen((size_t)n, -1);
+    std::vector<std::pair<int32_t, uint8_t>> row;       // (id, code)
+    std::vector<int32_t> frontier, next;
+    g->nbr_ptr.assign((size_t)n + 1, 0);
+    g->nbr_idx.clear(); g->nbr_rel.clear();
+    for (int64_t v = 0; v < n; ++v) {
+        row.clear(); frontier.clear();
+        row.emplace_back((int32_t)v, (uint8_t)0);
+        seen[v] = (int32_t)v;
+        frontier.push_back((int32_t)v);
+        for (int hop = 1; hop <= g->hops && !frontier.empty(); ++hop) {
+            next.clear();
+            for (const int32_t w : frontier)
+                for (int i = 0; i < 2; ++i) {
+                    const int32_t u = f.src[2 * (size_t)w + i];
+                    if (u < 0 || seen[u] == (int32_t)v) continue;
+                    seen[u] = (int32_t)v;
+                    row.emplace_back(u, hop == 1 ? (uint8_t)(1 + f.inv[2 * (size_t)w + i]) : (uint8_t)3);
+                    next.push_back(u);
+                }
+            frontier.swap(next);
+        }
+        std::sort(row.begin(), row.end());
+        for (const auto& r : row) { g->nbr_idx.push_back(r.first); g->nbr_rel.push_back(r.second); }
+        g->nbr_ptr[v + 1] = (int64_t)g->nbr_idx.size();
+    }
+    g->nnz = (int64_t)g->nbr_idx.size();
+}
+
 // Graph partition and updating strategy (Section 3.3, Algorithm 1; Section 3.4, Algorithm 2) turned
 // into neighbour rows. Every root gets the running number of its mini-batch (lists by ascending
 // level, inside a list the roots of the stride loop, then the unread gates, then the gates left in
@@ -230,7 +265,7 @@ extern "C" int dg4_build_partitioned(int64_t n, int64_t e, const int32_t* es, co
                                      const uint8_t* ei, int32_t hops, const int32_t* level_hint,
                                      int32_t stride, int32_t batch_cones, dg4_graph** out)
 {
-    if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
+    if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
     if (stride < 1 || stride >= hops || batch_cones < 1) return DG4_EINVAL;
     return build_graph(n, e, es, ed, ei, hops, level_hint, stride, batch_cones, out);
 }
@@ -242,7 +277,7 @@ int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, cons
                 const int32_t* level_hint, int32_t stride, int32_t batch, dg4_graph** out)
 {
     if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
-    if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
+    if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
     if (n >= (int64_t)0x3FFFFFFF) return DG4_EUNSUPPORTED;     // 30-bit packed indices
     try {
         Fanins f;
@@ -273,6 +308,9 @@ int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, cons
                 g->order[p] = (int32_t)v; g->pos[v] = (int32_t)p;
             }
         }
+        if (hops > 3) {
+            deep_cones(g, f);
+        } else {
         // cones, hop by hop
         ConeTable a, b;
         a.width = 1;
@@ -292,6 +330,7 @@ int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, cons
                 g->nbr_idx[g->nbr_ptr[v] + j] = a.id[base + j];
                 g->nbr_rel[g->nbr_ptr[v] + j] = h == 0 ? 0 : h == 1 ? (uint8_t)(1 + a.inv[base + j]) : 3;
             }
+        }
         }
         // Fanout counts of the structural encoding (Section 3.5, Eq. 2), gathered from the fanin
         // table: a reader with one fanin is a NOT/buffer gate; inverted uses by AND gates share the
@@ -524,8 +563,15 @@ int dg4_graph_ensure_device(dg4_graph* g)
     if (g->on_device) return DG4_OK;
     int dev = 0;
     if (hipGetDevice(&dev) != hipSuccess) return DG4_EHIP;
-    // (one-hop cones get rows of 8 as well: the persistent sweep is laid out for that width)
-    const int w = std::max(8, 1 << (g->hops + 1));
+    // (one-hop cones get rows of 8 as well: the persistent sweep is laid out for that width; cones
+    // deeper than three hops get the longest row, rounded up to four entries)
+    int w = std::max(8, 1 << (std::min(g->hops, 3) + 1));
+    if (g->hops > 3) {
+        int64_t longest = 0;
+        for (int64_t v = 0; v < g->n; ++v) longest = std::max(longest, g->nbr_ptr[v + 1] - g->nbr_ptr[v]);
+        w = std::max(w, (int)((longest + 3) / 4 * 4));
+    }
+    const bool with_flow = g->hops <= 2;       // the persistent sweep's tables
     // one tile of padding: the sweep kernel fetches descriptors of 16 positions at a time
     const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
     try {
@@ -583,17 +629,18 @@ int dg4_graph_ensure_device(dg4_graph* g)
         }
         g->level_tile_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
         // Dataflow order for whole-graph sweeps (dg4_flow_schedule)
-        {
+        std::vector<int32_t> flow;
+        std::vector<uint2> flow_tiles;
+        std::vector<uint32_t> by_flow;
+        if (with_flow) {
             const int rc = dg4_flow_schedule(g);
             if (rc != DG4_OK) return rc;
-        }
-        std::vector<int32_t> flow(rows, 0);
-        std::copy(g->flow_order.begin(), g->flow_order.end(), flow.begin());
-        std::vector<uint2> flow_tiles(g->flow_tile_ptr.size() - 1);
-        for (size_t t = 0; t + 1 < g->flow_tile_ptr.size(); ++t)
-            flow_tiles[t] = make_uint2((uint32_t)g->flow_tile_ptr[t], (uint32_t)(g->flow_tile_ptr[t + 1] - g->flow_tile_ptr[t]));
-        std::vector<uint32_t> by_flow(rows * w, DG4_ELL_PAD);
-        {
+            flow.assign(rows, 0);
+            std::copy(g->flow_order.begin(), g->flow_order.end(), flow.begin());
+            flow_tiles.resize(g->flow_tile_ptr.size() - 1);
+            for (size_t t = 0; t + 1 < g->flow_tile_ptr.size(); ++t)
+                flow_tiles[t] = make_uint2((uint32_t)g->flow_tile_ptr[t], (uint32_t)(g->flow_tile_ptr[t + 1] - g->flow_tile_ptr[t]));
+            by_flow.assign(rows * w, DG4_ELL_PAD);
             std::vector<int32_t> fpos((size_t)g->n, -1);
             for (int64_t q = 0; q < g->n; ++q) fpos[(size_t)g->flow_order[(size_t)q]] = (int32_t)q;
             for (int64_t v = 0; v < g->n; ++v) {
@@ -629,14 +676,16 @@ int dg4_graph_ensure_device(dg4_graph* g)
         if (g->n > 0 &&
             hipMemcpy(g->d_order, sweep.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess)
             return fail(DG4_EHIP);
-        if (hipMalloc((void**)&g->d_flow_ell, bytes) != hipSuccess) return fail(DG4_ENOMEM);
-        if (hipMalloc((void**)&g->d_flow_order, rows * sizeof(int32_t)) != hipSuccess) return fail(DG4_ENOMEM);
-        if (hipMalloc((void**)&g->d_flow_tiles, std::max<size_t>(flow_tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
-        if (!flow_tiles.empty() &&
-            hipMemcpy(g->d_flow_tiles, flow_tiles.data(), flow_tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess)
-            return fail(DG4_EHIP);
-        if (hipMemcpy(g->d_flow_ell, by_flow.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
-        if (hipMemcpy(g->d_flow_order, flow.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        if (with_flow) {
+            if (hipMalloc((void**)&g->d_flow_ell, bytes) != hipSuccess) return fail(DG4_ENOMEM);
+            if (hipMalloc((void**)&g->d_flow_order, rows * sizeof(int32_t)) != hipSuccess) return fail(DG4_ENOMEM);
+            if (hipMalloc((void**)&g->d_flow_tiles, std::max<size_t>(flow_tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
+            if (!flow_tiles.empty() &&
+                hipMemcpy(g->d_flow_tiles, flow_tiles.data(), flow_tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess)
+                return fail(DG4_EHIP);
+            if (hipMemcpy(g->d_flow_ell, by_flow.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+            if (hipMemcpy(g->d_flow_order, flow.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
+        }
     } catch (const std::bad_alloc&) {
         return DG4_ENOMEM;
     }

@@ -134,6 +134,97 @@ __global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
     op[0] = oa; op[1] = ob;
 }
 
+// The same for rows of any width (cones deeper than three hops, up to 2^(k+1)-1 sources): the row is
+// walked four entries at a time with a running maximum, denominator and weighted sum (the softmax is
+// unchanged by the rescaling). Rows are padded at the end only, to a multiple of four entries.
+template <typename T, int D>
+__global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
+{
+    constexpr int EPL = Elem<T>::EPL;
+    constexpr int LPR = D / EPL;
+    constexpr int RPW = 64 / LPR;
+    constexpr int CH = 4;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int sub = lane % LPR;
+    const int64_t row = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+    if (row >= p.row_end) return;             // whole lane groups leave together
+
+    const int64_t eoff = (int64_t)sub * EPL;
+    const int head = (int)(eoff >> 5);
+    float q[EPL];
+    {
+        const uint4* qp = (const uint4*)((const T*)p.q + row * p.q_stride + eoff);
+        Elem<T>::unpack(qp[0], qp[1], q);
+    }
+    float bias[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[head * 4 + i];
+    const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+
+    const uint32_t* erow = p.ell + row * (int64_t)p.ell_w;
+    float m = -INFINITY, z = 0.f;
+    float acc[EPL];
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+    for (int c0 = 0; c0 < p.ell_w; c0 += CH) {
+        const uint4 e4 = *(const uint4*)(erow + c0);
+        const uint32_t ent[CH] = { e4.x, e4.y, e4.z, e4.w };
+        if (ent[0] == DG4_ELL_PAD) break;         // the same for all lanes of the row
+        uint4 ka[CH], kb[CH], va[CH], vb[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (ent[j] != DG4_ELL_PAD) {
+                const uint32_t rel = ent[j] >> 30;
+                const int64_t idx = ent[j] & 0x3FFFFFFFu;
+                const T* kr = rel == 0 ? (const T*)p.k_self + row * p.self_stride : (const T*)p.k_src + idx * p.src_stride;
+                const T* vr = rel == 0 ? (const T*)p.v_self + row * p.self_stride : (const T*)p.v_src + idx * p.src_stride;
+                const uint4* kp = (const uint4*)(kr + eoff);
+                const uint4* vp = (const uint4*)(vr + eoff);
+                ka[j] = kp[0]; kb[j] = kp[1]; va[j] = vp[0]; vb[j] = vp[1];
+            } else {
+                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j]; va[j] = ka[j]; vb[j] = ka[j];
+            }
+        }
+        float sc[CH];
+        float cm = m;
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            float k[EPL];
+            Elem<T>::unpack(ka[j], kb[j], k);
+            float dot = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
+            dot = Elem<T>::head_sum(dot);
+            const uint32_t rel = ent[j] >> 30;
+            const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+            sc[j] = ent[j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
+            cm = fmaxf(cm, sc[j]);
+        }
+        const float corr = __expf(m - cm);        // 0 on the first chunk (m = -inf, cm finite)
+        z *= corr;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] *= corr;
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            float v[EPL];
+            Elem<T>::unpack(va[j], vb[j], v);
+            const float pj = __expf(sc[j] - cm);  // 0 for padding
+            z += pj;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(pj, v[i], acc[i]);
+        }
+        m = cm;
+    }
+    const float rz = 1.0f / z;
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] *= rz;
+    uint4 oa, ob;
+    Elem<T>::pack(acc, oa, ob);
+    uint4* op = (uint4*)((T*)p.a + row * p.a_stride + eoff);
+    op[0] = oa; op[1] = ob;
+}
+
 template <typename T, int D>
 int launch_attn_w(const dg4_attn_args& a, hipStream_t s)
 {
@@ -145,7 +236,10 @@ int launch_attn_w(const dg4_attn_args& a, hipStream_t s)
     case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), dim3(grid), dim3(256), 0, s, a); break;
     case 8: hipLaunchKernelGGL((attn_kernel<T, D, 8>), dim3(grid), dim3(256), 0, s, a); break;
     case 16: hipLaunchKernelGGL((attn_kernel<T, D, 16>), dim3(grid), dim3(256), 0, s, a); break;
-    default: return hipErrorInvalidValue;
+    default:
+        if (a.ell_w < 4 || a.ell_w % 4) return hipErrorInvalidValue;
+        hipLaunchKernelGGL((attn_wide_kernel<T, D>), dim3(grid), dim3(256), 0, s, a);
+        break;
     }
     return hipGetLastError();
 }

@@ -28,6 +28,11 @@ pytestmark = pytest.mark.gpu
     ("medium", 12_000, 2, 1, 16, {}),
     ("large", 12_000, 2, 1, 128, dict(ffn=True)),          # pairs of tiles, feed-forward sub-block
     ("large", 12_000, 2, 1, 128, dict(per_level=True)),
+    ("tiny", None, 8, 6, 128, {}),                         # the paper's depth, stride and mini-batch size
+    ("small", 8_000, 8, 6, 128, {}),
+    ("medium", 12_000, 8, 6, 128, {}),
+    ("medium", 6_000, 8, 6, 64, dict(n_layers=2)),
+    ("large", 12_000, 5, 3, 16, dict(ffn=True)),
 ])
 def test_partitioned_layer(name, n_and, k, delta, batch, kw):
     print(f"partitioned layer {name} n_and={n_and} k={k} delta={delta} B={batch} {kw}", flush=True)
@@ -66,3 +71,55 @@ def test_partitioned_layer(name, n_and, k, delta, batch, kw):
         assert cut > 50
         whole = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype, w1=w1, w2=w2)
         assert row_rel_err(H, whole).max() > 10 * TOL[c.dtype]
+
+
+@pytest.mark.parametrize("name,n_and,hops,dtype,d", [
+    ("tiny", None, 4, "f32", 128), ("tiny", None, 8, "f32", 128), ("small", 8_000, 8, "f32", 128),
+    ("medium", 10_000, 8, "bf16", 256), ("stress", 5_000, 6, "bf16", 256), ("tiny", None, 8, "bf16", 128),
+])
+def test_attention_over_deep_cones(name, n_and, hops, dtype, d):
+    """dg4_sparse_attn_fwd on whole cones of more than three hops (rows of up to 2^(k+1)-1 sources)."""
+    print(f"sparse_attn deep {name} n_and={n_and} hops={hops} {dtype} d={d}", flush=True)
+    w = synth.make(name, n_and=n_and, features=False)
+    n, heads, bf = w.cfg.n_nodes, d // 32, dtype == "bf16"
+    g = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint)
+    og = oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint)
+    longest = int(np.diff(og.nbr_ptr).max())
+    assert longest > 16
+    Q, K, V = (synth.normal(33, s, (n, d), 1.5, bf) for s in (4, 5, 6))
+    bias = synth.normal(33, 102, (heads, 4))
+    cfg = dg4.LayerConfig(d, heads, hops, 1, dtype)
+    A = torch.full((n, d), 3.0, dtype=tdtype(dtype), device="cuda")
+    lo, hi = 3, n - 5
+    dg4.dg4_sparse_attn_fwd(cfg, g, to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype), to_dev(bias, "f32"),
+                            A, row_begin=lo, row_end=hi)
+    torch.cuda.synchronize()
+    got = to_np(A)
+    ref = oracle.sparse_attn(og, heads, Q, K, V, bias, lo, hi)
+    assert (got[:lo] == 3.0).all() and (got[hi:] == 3.0).all()
+    err = row_rel_err(got[lo:hi], ref[lo:hi])
+    print(f"  longest row {longest}, max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= (TOL[dtype] if bf else 5e-6), err.max()
+
+
+@pytest.mark.parametrize("name,n_and,hops,kw", [
+    ("tiny", None, 8, {}), ("small", 6_000, 5, {}), ("medium", 10_000, 8, {}), ("stress", 3_000, 4, dict(bounded_kv=True)),
+])
+def test_layer_over_deep_cones(name, n_and, hops, kw):
+    print(f"layer deep {name} n_and={n_and} hops={hops} {kw}", flush=True)
+    base = synth.CONFIGS[name]
+    c = synth.Config(**{**base.__dict__, "hops": hops, **({"n_and": n_and} if n_and else {})})
+    w = synth.make(c)
+    n = c.n_nodes
+    cfg = cfg_of(c, **kw)
+    g = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint)
+    og = oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint)
+    H = torch.full((n, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+    dg4.dg4_layer_fwd(cfg, g, to_dev(w.x, c.dtype), device_weights(w, c.dtype), H)
+    torch.cuda.synchronize()
+    H = to_np(H)
+    assert not np.isnan(H).any()
+    ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
+    err = row_rel_err(H, ref)
+    print(f"  max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype], err.max()

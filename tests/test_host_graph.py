@@ -41,6 +41,7 @@ def test_hand_graphs(gr):
 
 
 @pytest.mark.parametrize("name,n_and,hops", [("tiny", None, 1), ("tiny", None, 2), ("tiny", None, 3),
+                                             ("tiny", None, 4), ("tiny", None, 8), ("small", 3000, 6), ("stress", 2000, 8),
                                               ("small", None, 2), ("medium", 50_000, 2),
                                               ("large", 60_000, 2), ("stress", 60_000, 3)])
 def test_tables_bit_exact_against_oracle(name, n_and, hops):
@@ -160,7 +161,7 @@ def test_bad_hint_hops_and_empty():
     with pytest.raises(dg4.DG4Error) as e:
         dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2, level_hint=[0, 1, 2])
     assert e.value.name == "EHINT"
-    for hops in (0, 4):
+    for hops in (0, 9):
         with pytest.raises(dg4.DG4Error) as e:
             dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], hops)
         assert e.value.name == "EUNSUPPORTED"

@@ -45,7 +45,7 @@ def test_hand_worked_cases(case):
 
 @pytest.mark.parametrize("seed,k,delta,batch,cap", [
     (1, 3, 2, 1, 0), (2, 3, 2, 4, 0), (3, 3, 1, 3, 0), (4, 2, 1, 128, 0), (7, 3, 2, 3, 30), (9, 3, 2, 2, -1),
-    (10, 3, 2, 128, -1), (11, 3, 1, 5, -1),
+    (10, 3, 2, 128, -1), (11, 3, 1, 5, -1), (12, 8, 6, 128, 0), (13, 8, 6, 4, -1), (14, 5, 3, 16, 40), (15, 8, 7, 1, 0),
 ])
 def test_small_graphs_bit_for_bit(seed, k, delta, batch, cap):
     n, src, dst, inv, hint = irregular(seed, n_and=300, window=24, cap=cap)
@@ -53,9 +53,10 @@ def test_small_graphs_bit_for_bit(seed, k, delta, batch, cap):
     same_partition(g, *oracle_run(n, src, dst, inv, k, delta, batch, hint))
 
 
-@pytest.mark.parametrize("cfg,k,delta,batch", [("tiny", 3, 2, 128), ("small", 3, 2, 128), ("medium", 2, 1, 16)])
+@pytest.mark.parametrize("cfg,k,delta,batch", [("tiny", 3, 2, 128), ("small", 3, 2, 128), ("medium", 2, 1, 16),
+                                               ("tiny", 8, 6, 128), ("stress", 8, 6, 128)])
 def test_configs_bit_for_bit(cfg, k, delta, batch):
-    w = synth.make(cfg, n_and=20000 if cfg != "tiny" else None, features=False)
+    w = synth.make(cfg, n_and=None if cfg == "tiny" else 3000 if k > 3 else 20000, features=False)
     n, src, dst, inv = w.cfg.n_nodes, w.edge_src, w.edge_dst, w.edge_inv
     g = dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch, level_hint=w.level_hint)
     og, cones, rows, stage = oracle_run(n, src, dst, inv, k, delta, batch, w.level_hint)
@@ -77,7 +78,7 @@ def test_arguments():
             dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch)
         assert e.value.name == "EINVAL"
     with pytest.raises(dg4.DG4Error) as e:
-        dg4.dg4_build_partitioned(n, src, dst, inv, 4, 2, 8)
+        dg4.dg4_build_partitioned(n, src, dst, inv, 9, 2, 8)
     assert e.value.name == "EUNSUPPORTED"
     plain = dg4.dg4_build_levels(n, src, dst, inv, 3)
     with pytest.raises(dg4.DG4Error):

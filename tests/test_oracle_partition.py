@@ -116,7 +116,10 @@ def test_against_brute_force_with_sets_and_dense_masks(seed, k, delta, batch, ma
     w1 = [synth.normal(seed, 200 + 2 * l, (d, 4 * d), d ** -0.5) for l in range(layers)] if ffn else None
     w2 = [synth.normal(seed, 201 + 2 * l, (4 * d, d), (4 * d) ** -0.5) for l in range(layers)] if ffn else None
     cones = oracle.partition(g, src, delta)
-    H, rows, stage, work = oracle.partitioned_fwd(g, cones, batch, x, wqkv, wo, rb, 2, mark=mark, w1=w1, w2=w2)
+    H, rows, stage, work = oracle.partitioned_fwd(g, cones, batch, x, wqkv, wo, rb, 2, mark=mark, w1=w1, w2=w2, memo=False)
+    H2, rows2, stage2, work2 = oracle.partitioned_fwd(g, cones, batch, x, wqkv, wo, rb, 2, mark=mark, w1=w1, w2=w2, memo=True)
+    assert (H == H2).all() and (stage == stage2).all() and work == work2       # the K|V cache changes no bit
+    assert all((a == b).all() for a, b in zip(rows, rows2))
     ref, masks, ref_work = dense_partitioned(n, src, dst, inv, g.level.tolist(), k, delta, batch, x, wqkv, wo, rb, 2,
                                              mark=mark, w1=w1, w2=w2)
     # Algorithm 1: the same lists
