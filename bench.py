@@ -50,10 +50,11 @@ def algorithmic_bytes(g, cfg, levels=None):
     else:
         n_rows = n
     distinct = len(np.unique(dl * n + src))
-    ell_row = 4 * (1 << (g.hops + 1))
-    per_gate = (R + R + 2 * R + ell_row) * cfg.n_layers
-    compulsory = n_rows * per_gate + distinct * 2 * R * cfg.n_layers
-    gathered = n_rows * per_gate + len(src) * 2 * R * cfg.n_layers
+    # neighbour rows: fixed width up to three hops, else the entries themselves
+    ell_bytes = n_rows * 4 * (1 << (g.hops + 1)) if g.hops <= 3 else 4 * (len(src) + n_rows)
+    per_gate = (R + R + 2 * R) * cfg.n_layers
+    compulsory = n_rows * per_gate + ell_bytes * cfg.n_layers + distinct * 2 * R * cfg.n_layers
+    gathered = n_rows * per_gate + ell_bytes * cfg.n_layers + len(src) * 2 * R * cfg.n_layers
     return compulsory, gathered
 
 
@@ -72,6 +73,11 @@ def main():
     ap.add_argument("--ffn", action="store_true",
                     help="time the layer WITH its feed-forward sub-block (not the headline configuration; "
                          "the roofline object then prices the step's matrix products against the MFMA peak)")
+    ap.add_argument("--partition", default=None, metavar="K,STRIDE,BATCH",
+                    help="time the layer under the general partition and updating strategy (cones of depth K "
+                         "collected every STRIDE levels, mini-batches of BATCH cones) instead of the headline sweep")
+    ap.add_argument("--no-partition-point", action="store_true",
+                    help="skip the extra measurement of the partitioned layer (medium graph, k=8, stride 6, 128 cones)")
     ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
@@ -102,15 +108,21 @@ def main():
     w = synth.make(args.workload, n_and=args.n_and)
     c = w.cfg
     t_gen = time.perf_counter() - t0
+    part = [int(t) for t in args.partition.split(",")] if args.partition else None
+    if part:
+        c = synth.Config(**{**c.__dict__, "hops": part[0]})
     t0 = time.perf_counter()
-    g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
+    if part:
+        g = dg4.dg4_build_partitioned(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, part[0], part[1], part[2], w.level_hint)
+    else:
+        g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, c.hops, w.level_hint)
     t_build = time.perf_counter() - t0
     # the same analysis on the GPU, edge list resident in device memory (second call timed: the first pays
     # for module loading)
     e_dev = [torch.from_numpy(a).cuda() for a in (w.edge_src, w.edge_dst, w.edge_inv)]
     h_dev = torch.from_numpy(w.level_hint).cuda() if w.level_hint is not None else None
     t_build_dev = None
-    for _ in range(2):
+    for _ in range(2 if c.hops <= 3 else 0):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         g_dev = dg4.dg4_build_levels_device(c.n_nodes, *e_dev, c.hops, h_dev)
@@ -177,13 +189,17 @@ def main():
                      "kernel": "sweep_kernel (persistent level sweep)" if len(sweep_ms) == args.steps
                                else "dg4_layer_fwd (all launches of one step)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": TRAFFIC_BYTES.get(c.name),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None if part else TRAFFIC_BYTES.get(c.name),
                      "algorithmic_bytes": compulsory, "gathered_bytes": gathered,
                      "kernel_ms": ms_kernel, "step_ms_device": ms_dev,
                      "step_achieved": compulsory / (ms_dev * 1e-3) / 1e9},
-        "setup_s": {"generate": t_gen, "dg4_build_levels": t_build, "dg4_build_levels_device": t_build_dev,
-                    "upload": t_upload},
+        "setup_s": {"generate": t_gen, "dg4_build_partitioned" if part else "dg4_build_levels": t_build,
+                    "dg4_build_levels_device": t_build_dev, "upload": t_upload},
     }
+    if part:
+        out["config"]["workload"] += f", partition: stride {part[1]}, mini-batches of {part[2]} cones, marks"
+        out["config"]["cones"] = int(len(g.array("cone_root")))
+        out["config"]["mini_batches"] = int(g.array("stage").max()) + 1 if g.n else 0
     if args.ffn:
         # With the feed-forward sub-block the step is bound by its matrix products and by the weight
         # stream that feeds them, not by HBM: per gate and layer 2*d*3d (Q|K|V of x) + 2*d*d (Wo) +
@@ -200,7 +216,7 @@ def main():
 
     # For information: the same step with the tiles dealt strictly level by level (the order of the
     # level hint) instead of the library's default dependency-driven order. Same results, bit for bit.
-    if len(sweep_ms) == args.steps and not args.no_level_order and not args.ffn:
+    if len(sweep_ms) == args.steps and not args.no_level_order and not args.ffn and not part:
         os.environ["DG4_SWEEP_LEVEL_ORDER"] = "1"
         for _ in range(args.warmup):
             dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
@@ -222,7 +238,7 @@ def main():
 
     # The two non-recurrent calls over all rows at once, as pure-kernel roofline points
     # (bf16 MFMA peak 2.5 PFLOP/s dense; both are HBM-bound at this size).
-    if not args.no_kernel_points and not args.ffn:
+    if not args.no_kernel_points and not args.ffn and not part:
         def timed(fn, reps=5):
             for _ in range(2):
                 fn()
@@ -281,7 +297,43 @@ def main():
                             "gates_per_s": n_gates * layers / (ms_l * 1e-3)}
         del Q, K, V, A, fwsl
 
-    if not args.no_cpu_baseline:
+    # The layer under the paper's general partition and updating strategy (Algorithms 1 and 2 with the
+    # paper's k = 8, stride 6, mini-batches of 128 cones, marks) on the 200K-gate graph: every gate is
+    # computed once, over the part of its 8-hop cone that its first mini-batch shows.
+    if not args.no_partition_point and not args.ffn and not part and args.workload == "large" and args.n_and is None:
+        pw = synth.make("medium")
+        pc = pw.cfg
+        t0 = time.perf_counter()
+        pg = dg4.dg4_build_partitioned(pc.n_nodes, pw.edge_src, pw.edge_dst, pw.edge_inv, 8, 6, 128, pw.level_hint)
+        t_part = time.perf_counter() - t0
+        pcfg = dg4.LayerConfig(pc.hidden, pc.heads, 8, 1, pc.dtype)
+        PX = torch.from_numpy(pw.x).cuda().to(td).contiguous()
+        PW = [(torch.from_numpy(pw.wqkv[0]).cuda().to(td).contiguous(), torch.from_numpy(pw.wo[0]).cuda().to(td).contiguous(),
+               torch.from_numpy(pw.rel_bias[0]).cuda().contiguous())]
+        PH = torch.empty_like(PX)
+        pws = torch.empty(dg4.dg4_layer_workspace_bytes(pcfg, pg), dtype=torch.uint8, device="cuda")
+        for _ in range(2):
+            dg4.dg4_layer_fwd(pcfg, pg, PX, PW, PH, workspace=pws)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(3):
+            dg4.dg4_layer_fwd(pcfg, pg, PX, PW, PH, workspace=pws)
+        b.record()
+        torch.cuda.synchronize()
+        ms_part = a.elapsed_time(b) / 3
+        pcomp, pgath = algorithmic_bytes(pg, pcfg)
+        out["partition"] = {"workload": f"medium: {pc.n_pi} PIs + {pc.n_and} ANDs, {pg.n_levels} levels, 8-hop cones, "
+                                        "stride 6, mini-batches of 128 cones, marks",
+                            "step_ms_device": ms_part, "edges_per_s": pg.nnz / (ms_part * 1e-3),
+                            "gates_per_s": pg.n / (ms_part * 1e-3), "gates": pg.n, "neighbour_edges": pg.nnz,
+                            "cones": int(len(pg.array("cone_root"))), "mini_batches": int(pg.array("stage").max()) + 1,
+                            "dg4_build_partitioned_s": t_part,
+                            "gathered_GBps": pgath / (ms_part * 1e-3) / 1e9,
+                            "compulsory_GBps": pcomp / (ms_part * 1e-3) / 1e9}
+        del PX, PH, pws, pg
+
+    if not args.no_cpu_baseline and not part:
         import oracle
         # bounded sample: the same sweep over the lowest levels holding about --cpu-gates gates
         lp = g.array("level_ptr")

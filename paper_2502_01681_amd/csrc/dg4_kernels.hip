@@ -134,87 +134,118 @@ __global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
     op[0] = oa; op[1] = ob;
 }
 
-// The same for rows of any width (cones deeper than three hops, up to 2^(k+1)-1 sources): the row is
-// walked four entries at a time with a running maximum, denominator and weighted sum (the softmax is
-// unchanged by the rescaling). Rows are padded at the end only, to a multiple of four entries.
-template <typename T, int D>
+// The same for rows of any width (cones deeper than three hops, up to 2^(k+1)-1 sources). S lane
+// groups share a row: group `part` walks the chunks of four entries part, part + S, ... with a
+// running maximum, denominator and weighted sum (the softmax is unchanged by the rescaling), and
+// the S partial results are merged through LDS by the first group. Long rows of few gates per
+// level thus keep many loads in flight. Rows are padded at the end only, to a multiple of four.
+template <typename T, int D, int S>
 __global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
 {
     constexpr int EPL = Elem<T>::EPL;
-    constexpr int LPR = D / EPL;
-    constexpr int RPW = 64 / LPR;
+    constexpr int LPR = D / EPL;              // lanes per lane group
+    constexpr int G = 256 / LPR;              // lane groups per workgroup
+    constexpr int RPB = G / S;                // rows per workgroup
     constexpr int CH = 4;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int sub = lane % LPR;
-    const int64_t row = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
-    if (row >= p.row_end) return;             // whole lane groups leave together
+    static_assert(G % S == 0, "lane groups per row must divide the workgroup");
+    __shared__ float part_m[S > 1 ? 256 : 1], part_z[S > 1 ? 256 : 1], part_acc[S > 1 ? 256 * EPL : 1];
+    const int group = threadIdx.x / LPR;
+    const int sub = threadIdx.x % LPR;
+    const int part = group % S;
+    const int64_t row = p.row_begin + (int64_t)blockIdx.x * RPB + group / S;
+    const bool active = row < p.row_end;
 
     const int64_t eoff = (int64_t)sub * EPL;
     const int head = (int)(eoff >> 5);
-    float q[EPL];
-    {
-        const uint4* qp = (const uint4*)((const T*)p.q + row * p.q_stride + eoff);
-        Elem<T>::unpack(qp[0], qp[1], q);
-    }
-    float bias[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[head * 4 + i];
-    const float scale = 0.17677669529663687f;     // 1/sqrt(32)
-
-    const uint32_t* erow = p.ell + row * (int64_t)p.ell_w;
     float m = -INFINITY, z = 0.f;
     float acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-    for (int c0 = 0; c0 < p.ell_w; c0 += CH) {
-        const uint4 e4 = *(const uint4*)(erow + c0);
-        const uint32_t ent[CH] = { e4.x, e4.y, e4.z, e4.w };
-        if (ent[0] == DG4_ELL_PAD) break;         // the same for all lanes of the row
-        uint4 ka[CH], kb[CH], va[CH], vb[CH];
+    if (active) {
+        float q[EPL];
+        {
+            const uint4* qp = (const uint4*)((const T*)p.q + row * p.q_stride + eoff);
+            Elem<T>::unpack(qp[0], qp[1], q);
+        }
+        float bias[4];
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            if (ent[j] != DG4_ELL_PAD) {
-                const uint32_t rel = ent[j] >> 30;
-                const int64_t idx = ent[j] & 0x3FFFFFFFu;
-                const T* kr = rel == 0 ? (const T*)p.k_self + row * p.self_stride : (const T*)p.k_src + idx * p.src_stride;
-                const T* vr = rel == 0 ? (const T*)p.v_self + row * p.self_stride : (const T*)p.v_src + idx * p.src_stride;
-                const uint4* kp = (const uint4*)(kr + eoff);
-                const uint4* vp = (const uint4*)(vr + eoff);
-                ka[j] = kp[0]; kb[j] = kp[1]; va[j] = vp[0]; vb[j] = vp[1];
-            } else {
-                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j]; va[j] = ka[j]; vb[j] = ka[j];
+        for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[head * 4 + i];
+        const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+        const uint32_t* erow = p.ell + row * (int64_t)p.ell_w;
+        for (int c0 = part * CH; c0 < p.ell_w; c0 += S * CH) {
+            const uint4 e4 = *(const uint4*)(erow + c0);
+            const uint32_t ent[CH] = { e4.x, e4.y, e4.z, e4.w };
+            if (ent[0] == DG4_ELL_PAD) break;         // the same for all lanes of the group
+            uint4 ka[CH], kb[CH], va[CH], vb[CH];
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                if (ent[j] != DG4_ELL_PAD) {
+                    const uint32_t rel = ent[j] >> 30;
+                    const int64_t idx = ent[j] & 0x3FFFFFFFu;
+                    const T* kr = rel == 0 ? (const T*)p.k_self + row * p.self_stride : (const T*)p.k_src + idx * p.src_stride;
+                    const T* vr = rel == 0 ? (const T*)p.v_self + row * p.self_stride : (const T*)p.v_src + idx * p.src_stride;
+                    const uint4* kp = (const uint4*)(kr + eoff);
+                    const uint4* vp = (const uint4*)(vr + eoff);
+                    ka[j] = kp[0]; kb[j] = kp[1]; va[j] = vp[0]; vb[j] = vp[1];
+                } else {
+                    ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j]; va[j] = ka[j]; vb[j] = ka[j];
+                }
             }
+            float sc[CH];
+            float cm = m;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                float k[EPL];
+                Elem<T>::unpack(ka[j], kb[j], k);
+                float dot = 0.f;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
+                dot = Elem<T>::head_sum(dot);
+                const uint32_t rel = ent[j] >> 30;
+                const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+                sc[j] = ent[j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
+                cm = fmaxf(cm, sc[j]);
+            }
+            const float corr = __expf(m - cm);        // 0 on the first chunk (m = -inf, cm finite)
+            z *= corr;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] *= corr;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                float v[EPL];
+                Elem<T>::unpack(va[j], vb[j], v);
+                const float pj = __expf(sc[j] - cm);  // 0 for padding
+                z += pj;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) acc[i] = fmaf(pj, v[i], acc[i]);
+            }
+            m = cm;
         }
-        float sc[CH];
-        float cm = m;
+    }
+    if (S > 1) {
+        part_m[threadIdx.x] = m; part_z[threadIdx.x] = z;
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            float k[EPL];
-            Elem<T>::unpack(ka[j], kb[j], k);
-            float dot = 0.f;
+        for (int i = 0; i < EPL; ++i) part_acc[i * 256 + threadIdx.x] = acc[i];
+        __syncthreads();
+        if (!active || part != 0) return;
+        // group 0 of the row holds the row's first chunk, so its maximum is finite
+        float mm = m;
 #pragma unroll
-            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
-            dot = Elem<T>::head_sum(dot);
-            const uint32_t rel = ent[j] >> 30;
-            const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
-            sc[j] = ent[j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
-            cm = fmaxf(cm, sc[j]);
+        for (int s = 1; s < S; ++s) mm = fmaxf(mm, part_m[threadIdx.x + s * LPR]);
+        const float c0 = __expf(m - mm);
+        z *= c0;
+#pragma unroll
+        for (int i = 0; i < EPL; ++i) acc[i] *= c0;
+#pragma unroll
+        for (int s = 1; s < S; ++s) {
+            const int t = threadIdx.x + s * LPR;
+            const float cs = __expf(part_m[t] - mm);  // 0 for a part that saw no entry
+            z = fmaf(part_z[t], cs, z);
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(part_acc[i * 256 + t], cs, acc[i]);
         }
-        const float corr = __expf(m - cm);        // 0 on the first chunk (m = -inf, cm finite)
-        z *= corr;
-#pragma unroll
-        for (int i = 0; i < EPL; ++i) acc[i] *= corr;
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            float v[EPL];
-            Elem<T>::unpack(va[j], vb[j], v);
-            const float pj = __expf(sc[j] - cm);  // 0 for padding
-            z += pj;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(pj, v[i], acc[i]);
-        }
-        m = cm;
+    } else if (!active) {
+        return;
     }
     const float rz = 1.0f / z;
 #pragma unroll
@@ -236,10 +267,17 @@ int launch_attn_w(const dg4_attn_args& a, hipStream_t s)
     case 4: hipLaunchKernelGGL((attn_kernel<T, D, 4>), dim3(grid), dim3(256), 0, s, a); break;
     case 8: hipLaunchKernelGGL((attn_kernel<T, D, 8>), dim3(grid), dim3(256), 0, s, a); break;
     case 16: hipLaunchKernelGGL((attn_kernel<T, D, 16>), dim3(grid), dim3(256), 0, s, a); break;
-    default:
+    default: {
+        // the split depends on the table's width alone, so a row's result does not depend on the
+        // range of rows a call covers
         if (a.ell_w < 4 || a.ell_w % 4) return hipErrorInvalidValue;
-        hipLaunchKernelGGL((attn_wide_kernel<T, D>), dim3(grid), dim3(256), 0, s, a);
+        constexpr int G = 256 / (D / Elem<T>::EPL);
+        if (a.ell_w > 64)
+            hipLaunchKernelGGL((attn_wide_kernel<T, D, G>), dim3((unsigned)rows), dim3(256), 0, s, a);
+        else
+            hipLaunchKernelGGL((attn_wide_kernel<T, D, 4>), dim3((unsigned)((rows + G / 4 - 1) / (G / 4))), dim3(256), 0, s, a);
         break;
+    }
     }
     return hipGetLastError();
 }
@@ -450,6 +488,21 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     uint4 ring[RING];
 #pragma unroll
     for (int j = 0; j < RING; ++j) ring[j] = wp[j * 64];
+    // the residual does not wait for the product: fetched now, added after it
+    const int col0 = wave * NTW * 32 + m;
+    int64_t orow[16];
+    bool ok[16];
+    float res[NTW][16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int row = 8 * (i / 4) + 4 * kg + (i % 4);
+        const int64_t r = r0 + row;
+        ok[i] = r < p.row_end;
+        orow[i] = ok[i] ? r : p.row_end - 1;
+        const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[orow[i]] : orow[i];
+#pragma unroll
+        for (int nt = 0; nt < NTW; ++nt) res[nt][i] = Elem<T>::load1(p.resid, rr * p.resid_stride + col0 + nt * 32);
+    }
     f32x16 acc[NTW];
 #pragma unroll
     for (int j = 0; j < NTW * KC; ++j) {
@@ -462,21 +515,14 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         if (j + RING < NTW * KC) ring[j % RING] = wp[(j + RING) * 64];
     }
     // residual, then LayerNorm over each row (no affine, biased variance), in two passes
-    const int col0 = wave * NTW * 32 + m;
-    int64_t orow[16];
-    bool ok[16];
     float mean[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int row = 8 * (i / 4) + 4 * kg + (i % 4);
-        const int64_t r = r0 + row;
-        ok[i] = r < p.row_end;
-        orow[i] = ok[i] ? r : p.row_end - 1;
-        const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[orow[i]] : orow[i];
         float s1 = 0.f;
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
-            acc[nt][i] += Elem<T>::load1(p.resid, rr * p.resid_stride + col0 + nt * 32);
+            acc[nt][i] += res[nt][i];
             s1 += acc[nt][i];
         }
         s1 = sum_over_32_lanes(s1);
