@@ -331,7 +331,30 @@ def main():
                             "dg4_build_partitioned_s": t_part,
                             "gathered_GBps": pgath / (ms_part * 1e-3) / 1e9,
                             "compulsory_GBps": pcomp / (ms_part * 1e-3) / 1e9}
-        del PX, PH, pws, pg
+        # The ablation without marks (every mini-batch recomputes its gates; one copy per mini-batch
+        # and gate), against the same partition with marks. At k = 8 this graph would have 66 copies
+        # per gate, so the pair is timed at k = 3, stride 2, mini-batches of 128 cones.
+        def layer_ms(graph, cfg_, X_, reps):
+            H_ = torch.empty_like(X_)
+            ws_ = torch.empty(dg4.dg4_layer_workspace_bytes(cfg_, graph), dtype=torch.uint8, device="cuda")
+            dg4.dg4_layer_fwd(cfg_, graph, X_, PW, H_, workspace=ws_)
+            torch.cuda.synchronize()
+            a.record()
+            for _ in range(reps):
+                dg4.dg4_layer_fwd(cfg_, graph, X_, PW, H_, workspace=ws_)
+            b.record()
+            torch.cuda.synchronize()
+            return a.elapsed_time(b) / reps
+        acfg = dg4.LayerConfig(pc.hidden, pc.heads, 3, 1, pc.dtype)
+        mg = dg4.dg4_build_partitioned(pc.n_nodes, pw.edge_src, pw.edge_dst, pw.edge_inv, 3, 2, 128, pw.level_hint)
+        ug = dg4.dg4_build_partitioned(pc.n_nodes, pw.edge_src, pw.edge_dst, pw.edge_inv, 3, 2, 128, pw.level_hint, marks=False)
+        UX = PX[torch.from_numpy(ug.array("copy_of").astype(np.int64)).cuda()].contiguous()
+        ms_m, ms_u = layer_ms(mg, acfg, PX, 3), layer_ms(ug, acfg, UX, 3)
+        out["partition"]["marks_ablation"] = {"workload": "medium, 3-hop cones, stride 2, mini-batches of 128 cones",
+                                              "with_marks": {"step_ms_device": ms_m, "gate_computations": mg.n, "neighbour_edges": mg.nnz},
+                                              "without_marks": {"step_ms_device": ms_u, "gate_computations": ug.n, "neighbour_edges": ug.nnz},
+                                              "work_ratio": ug.n / mg.n, "time_ratio": ms_u / ms_m}
+        del PX, PH, pws, pg, UX, ug, mg
 
     if not args.no_cpu_baseline and not part:
         import oracle

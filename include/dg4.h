@@ -123,13 +123,20 @@ int dg4_build_levels_device(int64_t n_nodes, int64_t n_edges,
  * below it, the embeddings are those of one sweep in level order over these rows: the returned graph
  * is used with every other call exactly like one from dg4_build_levels (rows are subsets of that
  * call's rows, same order and codes), and its nnz counts the kept entries.
- * HOST call, host pointers. Errors as dg4_build_levels; EINVAL if stride < 1, stride >= hops or
- * batch_cones < 1.
+ * marks = 0 is the ablation without marks (Section 4.4): every mini-batch recomputes all the gates
+ * of its cones from their initial features and reads nothing from earlier mini-batches; the last
+ * result of a gate stands. The returned graph then has one node per (mini-batch, gate of it), a COPY,
+ * numbered mini-batch after mini-batch and by ascending gate id inside one; dg4_graph_info gives the
+ * number of copies as n_nodes. The caller runs the other calls on the copies: features X'[c] =
+ * X[DG4_COPY_OF[c]], and the embedding of gate v is H'[DG4_LAST_COPY[v]]. The number of copies over
+ * the number of gates is the work the marks save.
+ * HOST call, host pointers. Errors as dg4_build_levels; EINVAL if stride < 1, stride >= hops,
+ * batch_cones < 1 or marks not 0 / 1; EUNSUPPORTED if there would be 2^30 copies or more.
  */
 int dg4_build_partitioned(int64_t n_nodes, int64_t n_edges,
                           const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,
                           int32_t hops, const int32_t* level_hint /* nullable */,
-                          int32_t stride, int32_t batch_cones,
+                          int32_t stride, int32_t batch_cones, int32_t marks,
                           dg4_graph** out);
 
 /* Tables of a graph, borrowed host pointers valid until dg4_graph_free. */
@@ -159,7 +166,11 @@ typedef enum {
     DG4_CONE_ROOT = 12,        /* int32 [n_cones]      roots, list after list                */
     DG4_CONE_GROUP_LEVEL = 13, /* int32 [n_lists]      level of each list, ascending         */
     DG4_CONE_GROUP_PTR = 14,   /* int64 [n_lists + 1]  first cone of each list               */
-    DG4_STAGE = 15             /* int32 [n_nodes]                                            */
+    DG4_STAGE = 15,            /* int32 [n_nodes]      (marks = 1 only)                      */
+    /* marks = 0 only: the gate each copy stands for, and each gate's copy in the last mini-batch
+     * that holds it. */
+    DG4_COPY_OF = 16,          /* int32 [n_copies]                                           */
+    DG4_LAST_COPY = 17         /* int32 [n_gates]                                            */
 } dg4_array;
 
 int dg4_graph_array(const dg4_graph* g, int which, const void** host_ptr, int64_t* count);

@@ -24,7 +24,7 @@ ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.in
           "out_and": (8, np.int32), "out_not": (9, np.int32),
           "pair_order": (10, np.int32), "pair_tile_ptr": (11, np.int64),
           "cone_root": (12, np.int32), "cone_group_level": (13, np.int32), "cone_group_ptr": (14, np.int64),
-          "stage": (15, np.int32)}
+          "stage": (15, np.int32), "copy_of": (16, np.int32), "last_copy": (17, np.int32)}
 STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
           -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP"}
 
@@ -81,7 +81,7 @@ def lib():
         L.dg4_build_levels.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, ctypes.POINTER(_P)]
         L.dg4_graph_array.restype = ctypes.c_int
         L.dg4_build_partitioned.restype = ctypes.c_int
-        L.dg4_build_partitioned.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, _I32, _I32, ctypes.POINTER(_P)]
+        L.dg4_build_partitioned.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, _I32, _I32, _I32, ctypes.POINTER(_P)]
         L.dg4_build_levels_device.restype = ctypes.c_int
         L.dg4_build_levels_device.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, _P, ctypes.POINTER(_P)]
         L.dg4_graph_array.argtypes = [_P, ctypes.c_int, ctypes.POINTER(_P), ctypes.POINTER(_I64)]
@@ -175,7 +175,8 @@ def dg4_build_levels(n_nodes, edge_src, edge_dst, edge_inv, hops, level_hint=Non
     return Graph(out.value)
 
 
-def dg4_build_partitioned(n_nodes, edge_src, edge_dst, edge_inv, hops, stride, batch_cones, level_hint=None) -> Graph:
+def dg4_build_partitioned(n_nodes, edge_src, edge_dst, edge_inv, hops, stride, batch_cones, level_hint=None,
+                          marks=True) -> Graph:
     src = np.ascontiguousarray(edge_src, dtype=np.int32)
     dst = np.ascontiguousarray(edge_dst, dtype=np.int32)
     inv = np.ascontiguousarray(edge_inv, dtype=np.uint8)
@@ -187,7 +188,7 @@ def dg4_build_partitioned(n_nodes, edge_src, edge_dst, edge_inv, hops, stride, b
     out = _P()
     rc = lib().dg4_build_partitioned(n_nodes, len(src), src.ctypes.data, dst.ctypes.data, inv.ctypes.data, hops,
                                      hint.ctypes.data if hint is not None else None, stride, batch_cones,
-                                     ctypes.byref(out))
+                                     int(marks), ctypes.byref(out))
     _check(rc, "dg4_build_partitioned")
     return Graph(out.value)
 

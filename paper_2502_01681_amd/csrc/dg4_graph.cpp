@@ -178,7 +178,9 @@ void deep_cones(dg4_graph* g, const Fanins& f)
 // no cone, each part by ascending id); a gate is computed by the smallest number among the cones
 // that hold it, and keeps the entries of its cone row that lie in one of that mini-batch's cones
 // together with it. Rows of g hold cone_hops(v), ascending id, on entry.
-void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, int32_t batch)
+// Algorithm 1's lists (g->cone_root, cone_group_level, cone_group_ptr) and the running number of the
+// mini-batch of every root (-1 for gates that root no cone). Returns the number of mini-batches.
+int32_t collect_cones(dg4_graph* g, const Fanins& f, int32_t stride, int32_t batch, std::vector<int32_t>& root_stage)
 {
     const int64_t n = g->n;
     const int32_t k = g->hops;
@@ -197,7 +199,7 @@ void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, i
     for (int64_t v = 0; v < n; ++v)
         if (!covered[v]) kind[v] = LEFT;
     // the lists, and the mini-batch number of every root
-    std::vector<int32_t> root_stage((size_t)n, -1);
+    root_stage.assign((size_t)n, -1);
     int32_t stage = 0;
     for (int32_t l = 0; l <= g->max_level; ++l) {
         const size_t first_cone = g->cone_root.size();
@@ -212,6 +214,28 @@ void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, i
         stage += (int32_t)((cones + (size_t)batch - 1) / (size_t)batch);
     }
     g->cone_group_ptr.push_back((int64_t)g->cone_root.size());
+    g->stride = stride; g->batch_cones = batch;
+    return stage;
+}
+
+// marks[j] = 1 for the entries j of row(v) that also lie in row(r) (two rows of ascending ids)
+inline void mark_common(const dg4_graph* g, int32_t v, int32_t r, uint8_t* marks)
+{
+    int64_t a = g->nbr_ptr[v], b = g->nbr_ptr[r];
+    const int64_t a0 = a, a1 = g->nbr_ptr[v + 1], b1 = g->nbr_ptr[r + 1];
+    while (a < a1 && b < b1) {
+        const int32_t x = g->nbr_idx[a], y = g->nbr_idx[b];
+        if (x == y) { marks[a - a0] = 1; ++a; ++b; }
+        else if (x < y) ++a;
+        else ++b;
+    }
+}
+
+void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, int32_t batch)
+{
+    const int64_t n = g->n;
+    std::vector<int32_t> root_stage;
+    collect_cones(g, f, stride, batch, root_stage);
     // the mini-batch that computes a gate: the first one that holds it
     g->stage.assign((size_t)n, INT32_MAX);
     for (const int32_t r : g->cone_root)
@@ -225,15 +249,7 @@ void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, i
         const int64_t r0 = g->nbr_ptr[r], r1 = g->nbr_ptr[r + 1];
         for (int64_t j = r0; j < r1; ++j) {
             const int32_t v = g->nbr_idx[j];
-            if (g->stage[(size_t)v] != root_stage[(size_t)r]) continue;
-            int64_t a = g->nbr_ptr[v], b = r0;                // two ascending rows
-            const int64_t a1 = g->nbr_ptr[v + 1];
-            while (a < a1 && b < r1) {
-                const int32_t x = g->nbr_idx[a], y = g->nbr_idx[b];
-                if (x == y) { keep[(size_t)a] = 1; ++a; ++b; }
-                else if (x < y) ++a;
-                else ++b;
-            }
+            if (g->stage[(size_t)v] == root_stage[(size_t)r]) mark_common(g, v, r, &keep[(size_t)g->nbr_ptr[v]]);
         }
     }
     int64_t out = 0;
@@ -245,12 +261,98 @@ void restrict_rows_to_partition(dg4_graph* g, const Fanins& f, int32_t stride, i
     }
     g->nbr_ptr[n] = out; g->nnz = out;
     g->nbr_idx.resize((size_t)out); g->nbr_rel.resize((size_t)out);
-    g->fanin = f.src;
-    g->stride = stride; g->batch_cones = batch;
+}
+
+// (level, id) order of g->level by a counting sort: level_ptr, order, pos
+void sort_by_level(dg4_graph* g)
+{
+    const int64_t n = g->n;
+    g->max_level = 0;
+    for (int64_t v = 0; v < n; ++v) g->max_level = std::max(g->max_level, g->level[v]);
+    g->level_ptr.assign((size_t)g->max_level + 2, 0);
+    for (int64_t v = 0; v < n; ++v) ++g->level_ptr[(size_t)g->level[v] + 1];
+    for (int32_t l = 0; l <= g->max_level; ++l) g->level_ptr[l + 1] += g->level_ptr[l];
+    g->order.resize((size_t)n);
+    g->pos.resize((size_t)n);
+    std::vector<int64_t> cur(g->level_ptr.begin(), g->level_ptr.end() - 1);
+    for (int64_t v = 0; v < n; ++v) {
+        const int64_t p = cur[g->level[v]]++;
+        g->order[p] = (int32_t)v; g->pos[v] = (int32_t)p;
+    }
+}
+
+// The ablation without marks (Section 4.4): every mini-batch recomputes all the gates of its cones
+// from their initial features, reading nothing from earlier mini-batches, and the last result of a
+// gate stands. As a graph: one COPY of a gate per mini-batch that holds it (numbered mini-batch
+// after mini-batch, inside one by ascending gate id), whose row holds the copies, in the same
+// mini-batch, of the sources that the mini-batch's cones show together with it. g holds the whole
+// cone rows of the circuit on entry and the expanded graph on return.
+int expand_without_marks(dg4_graph* g, const Fanins& f, int32_t stride, int32_t batch)
+{
+    const int64_t n = g->n;
+    std::vector<int32_t> root_stage;
+    const int32_t stages = collect_cones(g, f, stride, batch, root_stage);
+    std::vector<int32_t> copy_of, level2, out_and2, out_not2, idx2;
+    std::vector<uint8_t> rel2;
+    std::vector<int64_t> ptr2(1, 0);
+    std::vector<int32_t> last_copy((size_t)n, -1), slot((size_t)n, -1);
+    std::vector<int32_t> members;
+    std::vector<int64_t> off;                 // start of each member's flags
+    std::vector<uint8_t> keep;
+    size_t c0 = 0;                            // first cone of the mini-batch
+    for (int32_t b = 0; b < stages; ++b) {
+        size_t c1 = c0;
+        while (c1 < g->cone_root.size() && root_stage[(size_t)g->cone_root[c1]] == b) ++c1;
+        members.clear();
+        for (size_t c = c0; c < c1; ++c) {
+            const int32_t r = g->cone_root[c];
+            members.insert(members.end(), g->nbr_idx.begin() + g->nbr_ptr[r], g->nbr_idx.begin() + g->nbr_ptr[r + 1]);
+        }
+        std::sort(members.begin(), members.end());
+        members.erase(std::unique(members.begin(), members.end()), members.end());
+        const int64_t first = (int64_t)copy_of.size();
+        if (first + (int64_t)members.size() >= (int64_t)0x3FFFFFFF) return DG4_EUNSUPPORTED;
+        off.assign(members.size() + 1, 0);
+        for (size_t i = 0; i < members.size(); ++i) {
+            const int32_t v = members[i];
+            slot[(size_t)v] = (int32_t)i;
+            off[i + 1] = off[i] + (g->nbr_ptr[v + 1] - g->nbr_ptr[v]);
+        }
+        keep.assign((size_t)off.back(), 0);
+        for (size_t c = c0; c < c1; ++c) {
+            const int32_t r = g->cone_root[c];
+            for (int64_t j = g->nbr_ptr[r]; j < g->nbr_ptr[r + 1]; ++j) {
+                const int32_t v = g->nbr_idx[j];
+                mark_common(g, v, r, &keep[(size_t)off[(size_t)slot[(size_t)v]]]);
+            }
+        }
+        for (size_t i = 0; i < members.size(); ++i) {
+            const int32_t v = members[i];
+            copy_of.push_back(v);
+            level2.push_back(g->level[v]);
+            out_and2.push_back(g->out_and[v]); out_not2.push_back(g->out_not[v]);
+            last_copy[(size_t)v] = (int32_t)(first + (int64_t)i);
+            for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                if (keep[(size_t)(off[i] + j - g->nbr_ptr[v])]) {
+                    idx2.push_back((int32_t)(first + slot[(size_t)g->nbr_idx[j]]));
+                    rel2.push_back(g->nbr_rel[j]);
+                }
+            ptr2.push_back((int64_t)idx2.size());
+        }
+        c0 = c1;
+    }
+    g->n = (int64_t)copy_of.size();
+    g->nnz = (int64_t)idx2.size();
+    g->level.swap(level2); g->out_and.swap(out_and2); g->out_not.swap(out_not2);
+    g->nbr_ptr.swap(ptr2); g->nbr_idx.swap(idx2); g->nbr_rel.swap(rel2);
+    g->copy_of.swap(copy_of); g->last_copy.swap(last_copy);
+    g->marks = false;
+    sort_by_level(g);
+    return DG4_OK;
 }
 
 int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei, int32_t hops,
-                const int32_t* level_hint, int32_t stride, int32_t batch, dg4_graph** out);
+                const int32_t* level_hint, int32_t stride, int32_t batch, bool marks, dg4_graph** out);
 
 }  // namespace
 
@@ -258,23 +360,23 @@ extern "C" int dg4_build_levels(int64_t n, int64_t e, const int32_t* es, const i
                                 const uint8_t* ei, int32_t hops, const int32_t* level_hint,
                                 dg4_graph** out)
 {
-    return build_graph(n, e, es, ed, ei, hops, level_hint, 0, 0, out);
+    return build_graph(n, e, es, ed, ei, hops, level_hint, 0, 0, true, out);
 }
 
 extern "C" int dg4_build_partitioned(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
                                      const uint8_t* ei, int32_t hops, const int32_t* level_hint,
-                                     int32_t stride, int32_t batch_cones, dg4_graph** out)
+                                     int32_t stride, int32_t batch_cones, int32_t marks, dg4_graph** out)
 {
     if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
-    if (stride < 1 || stride >= hops || batch_cones < 1) return DG4_EINVAL;
-    return build_graph(n, e, es, ed, ei, hops, level_hint, stride, batch_cones, out);
+    if (stride < 1 || stride >= hops || batch_cones < 1 || (marks != 0 && marks != 1)) return DG4_EINVAL;
+    return build_graph(n, e, es, ed, ei, hops, level_hint, stride, batch_cones, marks != 0, out);
 }
 
 namespace {
 
-// stride == 0: plain cone rows; else the rows of the partitioned update
+// stride == 0: plain cone rows; else the rows of the partitioned update (without marks: of its copies)
 int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei, int32_t hops,
-                const int32_t* level_hint, int32_t stride, int32_t batch, dg4_graph** out)
+                const int32_t* level_hint, int32_t stride, int32_t batch, bool marks, dg4_graph** out)
 {
     if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
     if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
@@ -350,7 +452,11 @@ int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, cons
             }
             for (int64_t v = 0; v < n; ++v) g->out_not[v] += inverter[v];
         }
-        if (stride > 0) restrict_rows_to_partition(g, f, stride, batch);
+        if (stride > 0 && marks) restrict_rows_to_partition(g, f, stride, batch);
+        if (stride > 0 && !marks) {
+            rc = expand_without_marks(g, f, stride, batch);
+            if (rc != DG4_OK) return rc;
+        }
         *out = guard.release();
         return DG4_OK;
     } catch (const std::bad_alloc&) {
@@ -403,10 +509,17 @@ extern "C" int dg4_graph_array(const dg4_graph* g, int which, const void** host_
     case DG4_CONE_GROUP_PTR:
     case DG4_STAGE:
         if (g->stride == 0) return DG4_EINVAL;
+        if (which == DG4_STAGE && !g->marks) return DG4_EINVAL;                  // graphs without marks have copies instead
         if (which == DG4_CONE_ROOT) { *host_ptr = g->cone_root.data(); *count = (int64_t)g->cone_root.size(); }
         else if (which == DG4_CONE_GROUP_LEVEL) { *host_ptr = g->cone_group_level.data(); *count = (int64_t)g->cone_group_level.size(); }
         else if (which == DG4_CONE_GROUP_PTR) { *host_ptr = g->cone_group_ptr.data(); *count = (int64_t)g->cone_group_ptr.size(); }
         else { *host_ptr = g->stage.data(); *count = g->n; }
+        break;
+    case DG4_COPY_OF:
+    case DG4_LAST_COPY:
+        if (g->stride == 0 || g->marks) return DG4_EINVAL;
+        if (which == DG4_COPY_OF) { *host_ptr = g->copy_of.data(); *count = (int64_t)g->copy_of.size(); }
+        else { *host_ptr = g->last_copy.data(); *count = (int64_t)g->last_copy.size(); }
         break;
     default: return DG4_EINVAL;
     }
@@ -438,17 +551,12 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
     try {
         std::vector<int64_t> fo_ptr((size_t)g->n + 1, 0);
         std::vector<int32_t> remaining((size_t)g->n, 0);
-        // direct fanins: the entries with codes 1 and 2 of a whole cone row; a row cut by the
-        // partition may lack one (while keeping a source behind it), so those graphs carry the
-        // fanin table itself
+        // what a gate waits for: its direct fanins (codes 1 and 2; everything else in a whole cone
+        // row lies behind them). A row cut by the partition may lack a fanin while keeping a source
+        // behind it, so there every source of the row counts.
         auto for_each_fanin = [&](int64_t v, auto&& fn) {
-            if (!g->fanin.empty()) {
-                for (int i = 0; i < 2; ++i)
-                    if (g->fanin[2 * (size_t)v + i] >= 0) fn(g->fanin[2 * (size_t)v + i]);
-            } else {
-                for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
-                    if (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2) fn(g->nbr_idx[j]);
-            }
+            for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j)
+                if (g->stride > 0 ? g->nbr_rel[j] != 0 : (g->nbr_rel[j] == 1 || g->nbr_rel[j] == 2)) fn(g->nbr_idx[j]);
         };
         for (int64_t v = 0; v < g->n; ++v)
             for_each_fanin(v, [&](int32_t u) { ++fo_ptr[(size_t)u + 1]; ++remaining[v]; });

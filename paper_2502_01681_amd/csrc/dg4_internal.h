@@ -30,12 +30,13 @@ struct dg4_graph {
     int32_t* d_struct = nullptr;                 // device [n][3]: level, OutAND, OutNOT (on first dg4_struct_encode)
     std::vector<int32_t> nbr_idx;
     std::vector<uint8_t> nbr_rel;
-    // Partitioned graphs (dg4_build_partitioned): rows may lack a direct fanin, so the fanin table
-    // is kept for the schedulers ([2n], -1 = none); Algorithm 1's lists; the mini-batch of each gate.
+    // Partitioned graphs (dg4_build_partitioned): Algorithm 1's lists; with marks the mini-batch of
+    // each gate; without marks the nodes are copies: the gate each stands for, each gate's last copy.
     int32_t stride = 0, batch_cones = 0;
-    std::vector<int32_t> fanin;
+    bool marks = true;
     std::vector<int32_t> cone_root, cone_group_level, stage;
     std::vector<int64_t> cone_group_ptr;
+    std::vector<int32_t> copy_of, last_copy;
 
     // device mirror (one device), created once under `mu`
     std::mutex mu;

@@ -123,3 +123,51 @@ def test_layer_over_deep_cones(name, n_and, hops, kw):
     err = row_rel_err(H, ref)
     print(f"  max rel err {err.max():.3e}", flush=True)
     assert err.max() <= TOL[c.dtype], err.max()
+
+
+@pytest.mark.parametrize("name,n_and,k,delta,batch,kw", [
+    ("tiny", None, 3, 2, 16, {}),
+    ("tiny", None, 8, 6, 128, dict(n_layers=2)),
+    ("small", 6_000, 3, 2, 128, {}),
+    ("medium", 8_000, 8, 6, 128, {}),
+    ("large", 10_000, 2, 1, 64, {}),                       # copies through the persistent sweep
+    ("large", 10_000, 2, 1, 64, dict(ffn=True)),
+    ("stress", 8_000, 3, 2, 128, dict(n_layers=1)),
+])
+def test_partitioned_layer_without_marks(name, n_and, k, delta, batch, kw):
+    """The ablation of Section 4.4: every mini-batch recomputes its gates from scratch; the library
+    runs it as a sweep over one copy per (mini-batch, gate)."""
+    print(f"partitioned layer without marks {name} n_and={n_and} k={k} delta={delta} B={batch} {kw}", flush=True)
+    base = synth.CONFIGS[name]
+    over = {key: v for key, v in kw.items() if key in ("n_layers",)}
+    c = synth.Config(**{**base.__dict__, **over, "hops": k, **({"n_and": n_and} if n_and else {})})
+    w = synth.make(c)
+    n = c.n_nodes
+    ffn = kw.get("ffn", False)
+    w1, w2 = synth.ffn_weights(c) if ffn else (None, None)
+    cfg = cfg_of(c, ffn=ffn)
+    g = dg4.dg4_build_partitioned(n, w.edge_src, w.edge_dst, w.edge_inv, k, delta, batch, level_hint=w.level_hint,
+                                  marks=False)
+    og = oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, k, w.level_hint)
+    cones = oracle.partition(og, w.edge_src, delta)
+    ref, _, _, work = oracle.partitioned_fwd(og, cones, batch, w.x, w.wqkv, w.wo, w.rel_bias, c.heads,
+                                             store=c.dtype, w1=w1, w2=w2, mark=False)
+    assert g.n == work and work > n
+    copy_of = torch.from_numpy(g.array("copy_of").astype(np.int64)).cuda()
+    last_copy = torch.from_numpy(g.array("last_copy").astype(np.int64)).cuda()
+    X = to_dev(w.x, c.dtype)[copy_of].contiguous()
+    W = device_weights(w, c.dtype)
+    if ffn:
+        W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(W)]
+    Hc = torch.full((g.n, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+    dg4.dg4_layer_fwd(cfg, g, X, W, Hc)
+    torch.cuda.synchronize()
+    assert not torch.isnan(Hc.float()).any()
+    H = to_np(Hc[last_copy])
+    err = row_rel_err(H, ref)
+    print(f"  {work} copies of {n} gates, max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype], err.max()
+    # and the marks matter: with them the embeddings differ
+    marked, _, _, _ = oracle.partitioned_fwd(og, cones, batch, w.x, w.wqkv, w.wo, w.rel_bias, c.heads,
+                                             store=c.dtype, w1=w1, w2=w2)
+    assert row_rel_err(H, marked).max() > 10 * TOL[c.dtype]

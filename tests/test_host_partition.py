@@ -90,7 +90,7 @@ def test_arguments():
 @pytest.mark.parametrize("which", ["flow", "pair"])
 def test_processing_orders_put_every_source_in_an_earlier_tile(which):
     """Rows cut by the partition may keep a distant source while losing the fanin in between: the
-    orders must still come from the circuit's real edges."""
+    orders must wait for every source of a row, not only for the direct fanins."""
     n, src, dst, inv, hint = irregular(9, n_and=3000, window=48, cap=-1)
     g = dg4.dg4_build_partitioned(n, src, dst, inv, 3, 2, 8, level_hint=hint)
     order, tile_ptr = g.array(which + "_order"), g.array(which + "_tile_ptr")
@@ -109,5 +109,53 @@ def test_processing_orders_put_every_source_in_an_earlier_tile(which):
             assert u == v or tile_of[u] < tile_of[v]
         lost += any(u not in row for u in fanins.get(v, [])) and (rel[ptr[v]:ptr[v + 1]] == 3).any()
     assert lost > 20            # the case this test is about does occur
-    for s, t in zip(src.tolist(), dst.tolist()):
-        assert tile_of[s] < tile_of[t]
+
+
+def members_of_batches(cones, batch):
+    out = []
+    for i in range(len(cones.group_level)):
+        for b in range(cones.group_ptr[i], cones.group_ptr[i + 1], batch):
+            cs = range(b, min(b + batch, cones.group_ptr[i + 1]))
+            out.append((sorted(set(v for c in cs for v in cones.cone(c).tolist())), [set(cones.cone(c).tolist()) for c in cs]))
+    return out
+
+
+@pytest.mark.parametrize("seed,k,delta,batch,cap", [
+    (1, 3, 2, 1, 0), (2, 3, 2, 4, 0), (5, 2, 1, 16, 0), (9, 3, 2, 2, -1), (12, 8, 6, 128, 0), (13, 5, 3, 3, -1),
+])
+def test_without_marks_one_copy_per_mini_batch_and_gate(seed, k, delta, batch, cap):
+    n, src, dst, inv, hint = irregular(seed, n_and=150, window=16, cap=cap)
+    g = dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch, level_hint=hint, marks=False)
+    og = oracle.build_levels(n, src, dst, inv, k, level_hint=hint)
+    cones = oracle.partition(og, src, delta)
+    x, wqkv, wo, rb = problem(n, d=4, heads=1)
+    _, rows, last_stage, work = oracle.partitioned_fwd(og, cones, batch, x, wqkv, wo, rb, 1, mark=False)
+    assert g.n == work and (g.array("cone_root") == cones.cone_root).all()
+    copy_of, last_copy = g.array("copy_of"), g.array("last_copy")
+    ptr, idx, rel, level = g.array("nbr_ptr"), g.array("nbr_idx"), g.array("nbr_rel"), g.array("level")
+    assert (level == og.level[copy_of]).all()
+    full = {v: dict(zip(og.nbr_idx[og.nbr_ptr[v]:og.nbr_ptr[v + 1]].tolist(), og.nbr_rel[og.nbr_ptr[v]:og.nbr_ptr[v + 1]].tolist()))
+            for v in range(n)}
+    c = 0
+    for members, cone_sets in members_of_batches(cones, batch):
+        first = c
+        assert copy_of[c:c + len(members)].tolist() == members
+        for v in members:
+            want = sorted(u for u in full[v] if any(u in cs and v in cs for cs in cone_sets))
+            got = idx[ptr[c]:ptr[c + 1]]
+            assert ((got >= first) & (got < first + len(members))).all()          # copies of the same mini-batch
+            assert copy_of[got].tolist() == want
+            assert rel[ptr[c]:ptr[c + 1]].tolist() == [full[v][u] for u in want]
+            c += 1
+    assert c == g.n
+    # the copy that stands: the one of the last mini-batch holding the gate, with the row the oracle used last
+    for v in range(n):
+        cp = last_copy[v]
+        assert copy_of[cp] == v and not (copy_of[cp + 1:] == v).any()
+        assert copy_of[idx[ptr[cp]:ptr[cp + 1]]].tolist() == rows[1][rows[0][v]:rows[0][v + 1]].tolist()
+    with pytest.raises(dg4.DG4Error):
+        g.array("stage")
+    marked = dg4.dg4_build_partitioned(n, src, dst, inv, k, delta, batch, level_hint=hint)
+    with pytest.raises(dg4.DG4Error):
+        marked.array("copy_of")
+    assert g.n > marked.n
