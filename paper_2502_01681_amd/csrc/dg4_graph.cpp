@@ -680,6 +680,9 @@ int dg4_graph_ensure_device(dg4_graph* g)
         w = std::max(w, (int)((longest + 3) / 4 * 4));
     }
     const bool with_flow = g->hops <= 2;       // the persistent sweep's tables
+    // two tables of rows x w entries are staged in host memory and copied: refuse what cannot fit
+    // (a graph of copies without marks at k = 8 can have tens of millions of rows 512 wide)
+    if (((size_t)g->n + DG4_TILE_ROWS) * (size_t)w * sizeof(uint32_t) > ((size_t)16 << 30)) return DG4_ENOMEM;
     // one tile of padding: the sweep kernel fetches descriptors of 16 positions at a time
     const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
     try {

@@ -147,3 +147,47 @@ def test_bounded_wait_aborts_instead_of_hanging(monkeypatch):
     Hn = to_np(H)
     ref = oracle.layer_nodes(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, Hn, nodes, store=c.dtype)
     assert row_rel_err(Hn[nodes], ref).max() <= TOL[c.dtype]
+
+
+@pytest.mark.timeout(500)
+def test_full_size_partitioned_k8():
+    """The layer under the general partition and updating strategy (Sections 3.3 and 3.4) in the
+    configuration bench.py times: the 200K-gate graph, cones of depth 8 every 6 levels, mini-batches
+    of 128 cones, marks. Lists, mini-batch numbers and rows against the oracle's literal run of the
+    two algorithms (on 4-wide features: the rows do not depend on them); sampled gates recomputed
+    by the oracle over those rows from the GPU's own source embeddings."""
+    print("full size medium, partition 8/6/128: generating", flush=True)
+    w = synth.make("medium")
+    c = synth.Config(**{**w.cfg.__dict__, "hops": 8})
+    n = c.n_nodes
+    cfg = cfg_of(c)
+    g = dg4.dg4_build_partitioned(n, w.edge_src, w.edge_dst, w.edge_inv, 8, 6, 128, level_hint=w.level_hint)
+    print(f"  {n} gates, {g.n_levels} levels, nnz {g.nnz}", flush=True)
+    X = to_dev(w.x, c.dtype)
+    W = device_weights(w, c.dtype)
+    H = torch.full((n, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+    dg4.dg4_layer_fwd(cfg, g, X, W, H)
+    torch.cuda.synchronize()
+    print("  sweep done", flush=True)
+    Hn = to_np(H)
+    assert not np.isnan(Hn).any()
+    assert np.abs(Hn.mean(axis=1)).max() < 2e-2 and np.abs(Hn.var(axis=1) - 1).max() < 5e-2
+    og = oracle.build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, 8, w.level_hint)
+    print("  oracle cones done", flush=True)
+    cones = oracle.partition(og, w.edge_src, 6)
+    x4 = np.zeros((n, 4), dtype=np.float32); x4[:, 0] = 1.0
+    zero = [np.zeros((4, 12), np.float32)], [np.zeros((4, 4), np.float32)], [np.zeros((1, 4), np.float32)]
+    _, rows, stage, work = oracle.partitioned_fwd(og, cones, 128, x4, *zero, 1)
+    assert work == n
+    assert (g.array("cone_root") == cones.cone_root).all() and (g.array("cone_group_ptr") == cones.group_ptr).all()
+    assert (g.array("stage") == stage).all()
+    for name, ref in zip(("nbr_ptr", "nbr_idx", "nbr_rel"), rows):
+        assert (g.array(name) == ref).all(), name
+    print("  tables equal", flush=True)
+    cut = oracle.Graph(n, og.level, og.order, og.level_ptr, rows[0], rows[1], rows[2], 8)
+    rng = np.random.default_rng(2)
+    nodes = np.unique(np.concatenate([rng.choice(n, size=500, replace=False), og.order[-50:], og.order[:50]]))
+    ref = oracle.layer_nodes(cut, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, Hn, nodes, store=c.dtype)
+    err = row_rel_err(Hn[nodes], ref)
+    print(f"  sampled {len(nodes)} gates: max rel err {err.max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype]
