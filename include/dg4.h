@@ -49,7 +49,10 @@ typedef enum {
 /* cfg->flags */
 #define DG4_NO_EPILOGUE 1u  /* H = A*Wo without residual and LayerNorm (kernel tests)      */
 #define DG4_PER_LEVEL   2u  /* dg4_layer_fwd: launch level by level instead of the single  */
-                            /* persistent dataflow kernel (same results; for comparison)   */
+                            /* persistent dataflow kernel (same results; for comparison).  */
+                            /* Level-by-level sweeps over ALL levels of a graph built with */
+                            /* a level_hint deeper than Eq. 1 go through the Eq. 1 levels  */
+                            /* (fewer rounds, same bits; host-built graphs only)           */
 #define DG4_BOUNDED_KV  4u  /* dg4_layer_fwd: keep no K|V store of finished gates. The K|V  */
                             /* rows of a level's distinct sources are projected from Hout   */
                             /* when the level is processed, so the workspace holds one      */

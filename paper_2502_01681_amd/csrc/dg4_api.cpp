@@ -55,6 +55,7 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     const size_t L = (size_t)c->n_layers;
     int64_t mr = 1;
     for (size_t l = 0; l + 1 < g->level_ptr.size(); ++l) mr = std::max(mr, g->level_ptr[l + 1] - g->level_ptr[l]);
+    for (size_t l = 0; l + 1 < g->eq1_level_ptr.size(); ++l) mr = std::max(mr, g->eq1_level_ptr[l + 1] - g->eq1_level_ptr[l]);
     p.max_rows = mr;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
@@ -371,11 +372,27 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         return DG4_OK;
     }
 
+    // A sweep over ALL levels of a graph whose levelling (a caller's hint) is deeper than Eq. 1 goes
+    // through the Eq. 1 levels instead: as many rounds of launches as the circuit is deep. Same
+    // embeddings (every source of a gate lies on a lower Eq. 1 level too); rows of the internal
+    // buffers are then positions in that order. DG4_SWEEP_LEVEL_ORDER=1 keeps the caller's levels.
+    const bool compact = whole_range && !bounded && !g->eq1_level_ptr.empty() && !getenv("DG4_SWEEP_LEVEL_ORDER");
+    if (compact) {
+        rc = dg4_graph_ensure_eq1(g);
+        if (rc != DG4_OK) return rc;
+    }
+    const std::vector<int64_t>& lptr = compact ? g->eq1_level_ptr : g->level_ptr;
+    const int32_t* d_order = compact ? g->d_order_eq1 : g->d_order;
+    const uint32_t* d_ell_pos = compact ? g->d_ell_eq1 : g->d_ell_pos;
+    const int32_t lev_first = compact ? 0 : level_begin;
+    const int32_t lev_end = compact ? (int32_t)lptr.size() - 1 : level_end;
+    const int32_t lev_count = compact ? (int32_t)lptr.size() - 1 : n_levels;
+
     // layer 0 projections of x for every gate of the swept levels, in one pass (level by level
     // further down if nothing of the size of the graph may be kept)
     if (!bounded) {
         dg4_gemm_args a{};
-        a.a = X; a.a_stride = d; a.a_gather = g->d_order;
+        a.a = X; a.a_stride = d; a.a_gather = d_order;
         a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
         char* base = ws + pl.qkv_self;
         a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
@@ -384,8 +401,8 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         HIPCHK(dg4_launch_gemm(dt, d, a, s));
     }
 
-    for (int32_t lev = level_begin; lev < level_end; ++lev) {
-        const int64_t p0 = g->level_ptr[lev], p1 = g->level_ptr[lev + 1];
+    for (int32_t lev = lev_first; lev < lev_end; ++lev) {
+        const int64_t p0 = lptr[lev], p1 = lptr[lev + 1];
         if (p1 == p0) continue;
         if (bounded) {
             // K | V (every layer) of this level's distinct sources, from their final embeddings
@@ -416,7 +433,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             char* kvb = ws + pl.kv + (size_t)l * pl.kv_rows * 2 * d * es;
             t.k_src = kvb; t.v_src = kvb + (size_t)d * es; t.src_stride = 2 * d;
             t.rel_bias = (const float*)W[WS * l + 2];
-            t.ell = bounded ? g->d_ell_front : g->d_ell_pos; t.ell_w = g->ell_w;
+            t.ell = bounded ? g->d_ell_front : d_ell_pos; t.ell_w = g->ell_w;
             t.a = local(pl.abuf, p0, d); t.a_stride = d;
             t.row_begin = p0; t.row_end = p1;
             HIPCHK(dg4_launch_attn(dt, d, t, s));
@@ -428,13 +445,13 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             o.w_packed = at(pl.wo[l]); o.n_cols = d;
             o.row_begin = p0; o.row_end = p1;
             o.epilogue = epi ? 1 : 0; o.ln_eps = cfg->ln_eps;
-            if (l == 0) { o.resid = X; o.resid_stride = d; o.resid_gather = g->d_order; }
+            if (l == 0) { o.resid = X; o.resid_stride = d; o.resid_gather = d_order; }
             else { o.resid = local((l & 1) ? pl.s1 : pl.s0, p0, d); o.resid_stride = d; }
             void* next = local(((l + 1) & 1) ? pl.s1 : pl.s0, p0, d);
             if (ffn) {
                 o.out[0] = local(pl.h1, p0, d); o.out_stride = d;
             } else if (last) {
-                o.out[0] = Hout; o.out_stride = d; o.out_scatter = g->d_order;
+                o.out[0] = Hout; o.out_stride = d; o.out_scatter = d_order;
                 if (!bounded) { o.out2 = at(pl.hpos); o.out2_stride = d; }
             } else {
                 o.out[0] = next; o.out_stride = d;
@@ -446,7 +463,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
                 f.w1_packed = at(pl.w1[l]); f.w2_packed = at(pl.w2[l]);
                 f.row_begin = p0; f.row_end = p1; f.ln_eps = cfg->ln_eps;
                 if (last) {
-                    f.out = Hout; f.out_stride = d; f.out_scatter = g->d_order;
+                    f.out = Hout; f.out_stride = d; f.out_scatter = d_order;
                     if (!bounded) { f.out2 = at(pl.hpos); f.out2_stride = d; }
                 } else {
                     f.out = next; f.out_stride = d;
@@ -466,7 +483,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             }
         }
         // publish K/V of the level's final embeddings for every layer
-        if (lev + 1 < n_levels && !bounded) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
+        if (lev + 1 < lev_count && !bounded) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
     }
     return DG4_OK;
 }

@@ -345,6 +345,11 @@ int expand_without_marks(dg4_graph* g, const Fanins& f, int32_t stride, int32_t 
     g->nnz = (int64_t)idx2.size();
     g->level.swap(level2); g->out_and.swap(out_and2); g->out_not.swap(out_not2);
     g->nbr_ptr.swap(ptr2); g->nbr_idx.swap(idx2); g->nbr_rel.swap(rel2);
+    if (!g->eq1_level.empty()) {
+        std::vector<int32_t> e2(copy_of.size());
+        for (size_t c = 0; c < copy_of.size(); ++c) e2[c] = g->eq1_level[(size_t)copy_of[c]];
+        g->eq1_level.swap(e2);
+    }
     g->copy_of.swap(copy_of); g->last_copy.swap(last_copy);
     g->marks = false;
     sort_by_level(g);
@@ -393,6 +398,7 @@ int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, cons
         if (level_hint) {
             rc = check_hint(n, f, level_hint);
             if (rc != DG4_OK) return rc;
+            g->eq1_level = g->level;
             g->level.assign(level_hint, level_hint + n);
         }
         // (level, id) order by a counting sort
@@ -456,6 +462,18 @@ int build_graph(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, cons
         if (stride > 0 && !marks) {
             rc = expand_without_marks(g, f, stride, batch);
             if (rc != DG4_OK) return rc;
+        }
+        // the shallower Eq. 1 levelling, if the caller's is deeper
+        if (!g->eq1_level.empty()) {
+            int32_t deepest = 0;
+            for (const int32_t l : g->eq1_level) deepest = std::max(deepest, l);
+            if (deepest < g->max_level) {
+                g->eq1_level_ptr.assign((size_t)deepest + 2, 0);
+                for (const int32_t l : g->eq1_level) ++g->eq1_level_ptr[(size_t)l + 1];
+                for (int32_t l = 0; l <= deepest; ++l) g->eq1_level_ptr[l + 1] += g->eq1_level_ptr[l];
+            } else {
+                g->eq1_level.clear();
+            }
         }
         *out = guard.release();
         return DG4_OK;
@@ -804,6 +822,43 @@ int dg4_graph_ensure_device(dg4_graph* g)
     return DG4_OK;
 }
 
+// Device tables of the (Eq. 1 level, id) order, see dg4_graph::eq1_level_ptr.
+int dg4_graph_ensure_eq1(dg4_graph* g)
+{
+    std::lock_guard<std::mutex> lock(g->mu);
+    if (g->d_ell_eq1) return DG4_OK;
+    if (!g->on_device || g->eq1_level_ptr.empty()) return DG4_EINVAL;
+    const int w = g->ell_w;
+    const size_t rows = (size_t)g->n + DG4_TILE_ROWS;
+    try {
+        std::vector<int32_t> order(rows, 0), pos((size_t)g->n, 0);
+        std::vector<int64_t> cur(g->eq1_level_ptr.begin(), g->eq1_level_ptr.end() - 1);
+        for (int64_t v = 0; v < g->n; ++v) {
+            const int64_t p = cur[(size_t)g->eq1_level[v]]++;
+            order[(size_t)p] = (int32_t)v; pos[(size_t)v] = (int32_t)p;
+        }
+        std::vector<uint32_t> ell(rows * w, DG4_ELL_PAD);
+        for (int64_t v = 0; v < g->n; ++v) {
+            const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
+            uint32_t* r = &ell[(size_t)pos[v] * w];
+            for (int64_t j = 0; j < cnt; ++j)
+                r[j] = ((uint32_t)g->nbr_rel[lo + j] << 30) | (uint32_t)pos[g->nbr_idx[lo + j]];
+        }
+        uint32_t* d_ell = nullptr; int32_t* d_order = nullptr;
+        if (hipMalloc((void**)&d_ell, rows * w * sizeof(uint32_t)) != hipSuccess) return DG4_ENOMEM;
+        if (hipMalloc((void**)&d_order, rows * sizeof(int32_t)) != hipSuccess) { (void)hipFree(d_ell); return DG4_ENOMEM; }
+        if (hipMemcpy(d_ell, ell.data(), rows * w * sizeof(uint32_t), hipMemcpyHostToDevice) != hipSuccess ||
+            hipMemcpy(d_order, order.data(), rows * sizeof(int32_t), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(d_ell); (void)hipFree(d_order);
+            return DG4_EHIP;
+        }
+        g->d_order_eq1 = d_order; g->d_ell_eq1 = d_ell;
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
+    return DG4_OK;
+}
+
 // level, OutAND, OutNOT of every node as one device table [n][3] for dg4_struct_encode
 int dg4_graph_ensure_struct(dg4_graph* g)
 {
@@ -908,5 +963,7 @@ extern "C" void dg4_graph_free(dg4_graph* g)
     if (g->d_pair_ell) (void)hipFree(g->d_pair_ell);
     if (g->d_pair_order) (void)hipFree(g->d_pair_order);
     if (g->d_pair_tiles) (void)hipFree(g->d_pair_tiles);
+    if (g->d_order_eq1) (void)hipFree(g->d_order_eq1);
+    if (g->d_ell_eq1) (void)hipFree(g->d_ell_eq1);
     delete g;
 }

@@ -37,6 +37,14 @@ struct dg4_graph {
     std::vector<int32_t> cone_root, cone_group_level, stage;
     std::vector<int64_t> cone_group_ptr;
     std::vector<int32_t> copy_of, last_copy;
+    // Graphs built with a caller's levelling that is deeper than Eq. 1: the Eq. 1 levels and the
+    // tables of a (Eq. 1 level, id) order, for level-by-level sweeps over ALL levels, which then
+    // take as many rounds of launches as the circuit is deep, not as the levelling is. Host part at
+    // build time, device tables on first use.
+    std::vector<int32_t> eq1_level;
+    std::vector<int64_t> eq1_level_ptr;      // empty: no such order
+    int32_t* d_order_eq1 = nullptr;          // [n] position -> node id
+    uint32_t* d_ell_eq1 = nullptr;           // [n, ell_w] rows and entries by position in that order
 
     // device mirror (one device), created once under `mu`
     std::mutex mu;
@@ -83,6 +91,7 @@ int dg4_pair_schedule(dg4_graph* g);   // caller holds g->mu
 int dg4_graph_ensure_frontier(dg4_graph* g);           // after dg4_graph_ensure_device
 int dg4_graph_ensure_struct(dg4_graph* g);
 int dg4_graph_ensure_pairs(dg4_graph* g);              // after dg4_graph_ensure_device
+int dg4_graph_ensure_eq1(dg4_graph* g);                // after dg4_graph_ensure_device; needs eq1_level_ptr
 
 // ---- structural encoding (dg4_kernels.hip) ----
 int dg4_launch_struct_encode(int dtype, int hidden, const void* x, const int32_t* feat, const float* emb, void* out,

@@ -152,6 +152,24 @@ def test_dataflow_and_level_ordered_tiles_agree(monkeypatch):
     assert not torch.isnan(H_flow.float()).any()
 
 
+@pytest.mark.parametrize("name,n_and", [("stress", 30_000), ("large", 30_000)])
+def test_level_by_level_sweeps_through_eq1_levels_or_the_hint_agree(name, n_and, monkeypatch):
+    # level-by-level launches over ALL levels of a graph with a deeper levelling than Eq. 1 go
+    # through the Eq. 1 levels (far fewer rounds of launches); forced through the caller's levels
+    # they must give the same bits
+    print(f"layer_fwd per level: Eq. 1 levels vs hint {name}", flush=True)
+    w = synth.make(name, n_and=n_and)
+    cfg = cfg_of(w.cfg, per_level=True)
+    g, og = graphs(w, hint=True)
+    assert g.n_levels > 3 * (int(oracle.levels(w.cfg.n_nodes, w.edge_src, w.edge_dst).max()) + 1)
+    H_eq1 = run_layer(w, cfg, g)
+    monkeypatch.setenv("DG4_SWEEP_LEVEL_ORDER", "1")
+    H_hint = run_layer(w, cfg, g)
+    monkeypatch.delenv("DG4_SWEEP_LEVEL_ORDER")
+    assert not torch.isnan(H_eq1.float()).any()
+    assert torch.equal(H_eq1, H_hint)
+
+
 @pytest.mark.parametrize("name,n_and,kw", [("stress", 30_000, {}), ("large", 30_000, {}),
                                            ("tiny", None, dict(n_layers=2)), ("small", None, {})])
 def test_bounded_kv_sweep(name, n_and, kw):
