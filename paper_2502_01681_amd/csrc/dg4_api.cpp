@@ -55,7 +55,8 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     const size_t L = (size_t)c->n_layers;
     int64_t mr = 1;
     for (size_t l = 0; l + 1 < g->level_ptr.size(); ++l) mr = std::max(mr, g->level_ptr[l + 1] - g->level_ptr[l]);
-    for (size_t l = 0; l + 1 < g->eq1_level_ptr.size(); ++l) mr = std::max(mr, g->eq1_level_ptr[l + 1] - g->eq1_level_ptr[l]);
+    if (!(c->flags & DG4_BOUNDED_KV))        // sweeps with the K|V store may run through the Eq. 1 levels
+        for (size_t l = 0; l + 1 < g->eq1_level_ptr.size(); ++l) mr = std::max(mr, g->eq1_level_ptr[l + 1] - g->eq1_level_ptr[l]);
     p.max_rows = mr;
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align256(off + bytes); return o; };
