@@ -388,6 +388,8 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     const int32_t lev_first = compact ? 0 : level_begin;
     const int32_t lev_end = compact ? (int32_t)lptr.size() - 1 : level_end;
     const int32_t lev_count = compact ? (int32_t)lptr.size() - 1 : n_levels;
+    // one layer without feed-forward sub-block: the output projection's launch also projects K | V
+    const bool fuse_kv = L == 1 && !ffn && !bounded && epi && dg4_gemm_fuses_kv(dt, d);
 
     // layer 0 projections of x for every gate of the swept levels, in one pass (level by level
     // further down if nothing of the size of the graph may be kept)
@@ -454,6 +456,9 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             } else if (last) {
                 o.out[0] = Hout; o.out_stride = d; o.out_scatter = d_order;
                 if (!bounded) { o.out2 = at(pl.hpos); o.out2_stride = d; }
+                if (fuse_kv && lev + 1 < lev_count) {        // K | V of the level's gates in the same launch
+                    o.kv_w_packed = at(pl.wkv_all); o.kv_out = ws + pl.kv; o.kv_stride = 2 * d;
+                }
             } else {
                 o.out[0] = next; o.out_stride = d;
             }
@@ -484,7 +489,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             }
         }
         // publish K/V of the level's final embeddings for every layer
-        if (lev + 1 < lev_count && !bounded) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
+        if (lev + 1 < lev_count && !bounded && !fuse_kv) HIPCHK(kv_project(at(pl.hpos), d, nullptr, p0, p1));
     }
     return DG4_OK;
 }

@@ -129,8 +129,13 @@ struct dg4_gemm_args {
     void* out2; int64_t out2_stride;        // nullable second copy, indexed by r
     float ln_eps;
     int split;                              // set by the launcher: waves of a workgroup share rows and split the columns
+    // Optional second product behind the epilogue (shapes for which dg4_gemm_fuses_kv() holds):
+    // [K | V] = y * kv_w_packed (packed [hidden, 2*hidden]) for the normalised rows y, row r to
+    // kv_out + r*kv_stride. The same bits as a separate launch over the stored rows.
+    const void* kv_w_packed; void* kv_out; int64_t kv_stride;
 };
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s);
+bool dg4_gemm_fuses_kv(int dtype, int hidden);
 
 // Feed-forward sub-block: out = LN(h + max(h W1, 0) W2) for rows [row_begin, row_end).
 struct dg4_ffn_args {

@@ -460,7 +460,10 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
 // gemm_kernel<.., LN = true> for launches with few rows: the four waves of a workgroup share 32 rows
 // and take a quarter of the D output columns each (four times as many compute units at work, a
 // quarter of the weight stream per wave); the LayerNorm sums are completed through LDS.
-template <typename T, int D>
+// KV: the normalised rows also go, rounded to T, through LDS into a second product with the packed
+// [D, 2D] weight p.kv_w_packed, each wave taking a quarter of its 2D columns (the K | V rows of the
+// gates of a one-layer sweep, otherwise a launch of their own).
+template <typename T, int D, bool KV>
 __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
 {
     constexpr int E = 16 / sizeof(T);
@@ -470,6 +473,8 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     constexpr int GROUP = KC > RING ? KC : RING;
     static_assert((NTW * KC) % GROUP == 0, "whole groups per wave");
     __shared__ float part[2][4][32];
+    constexpr int YS = D + E;                     // row stride of the staged rows: 16 bytes of padding
+    __shared__ __attribute__((aligned(16))) T ybuf[KV ? 32 * YS : 1];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int m = lane & 31, kg = lane >> 5;
@@ -551,6 +556,36 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
             const float y = (acc[nt][i] - mean[i]) * rstd;
             Elem<T>::store1(p.out[0], orr * p.out_stride + col0 + nt * 32, y);
             if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col0 + nt * 32, y);
+            if constexpr (KV) Elem<T>::store1(ybuf, (int64_t)row * YS + col0 + nt * 32, y);
+        }
+    }
+    if constexpr (KV) {
+        __syncthreads();
+        // rows past the end were skipped above: their staged rows are never stored below either
+        uint4 a2[KC];
+#pragma unroll
+        for (int c = 0; c < KC; ++c) a2[c] = *(const uint4*)&ybuf[m * YS + (2 * c + kg) * E];
+        constexpr int NTW2 = 2 * D / 32 / 4;      // column tiles of K | V per wave
+        static_assert((NTW2 * KC) % GROUP == 0, "whole groups per wave");
+        const uint4* wp2 = (const uint4*)p.kv_w_packed + (int64_t)wave * NTW2 * KC * 64 + lane;
+#pragma unroll
+        for (int j = 0; j < RING; ++j) ring[j] = wp2[j * 64];
+        f32x16 kv;
+#pragma unroll
+        for (int j = 0; j < NTW2 * KC; ++j) {
+            const int c = j % KC, nt = j / KC;
+            if (c == 0) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) kv[i] = 0.f;
+            }
+            Mma<T>::run(a2[c], ring[j % RING], kv);
+            if (j + RING < NTW2 * KC) ring[j % RING] = wp2[(j + RING) * 64];
+            if (c == KC - 1) {
+                const int col = (wave * NTW2 + nt) * 32 + m;
+#pragma unroll
+                for (int i = 0; i < 16; ++i)
+                    if (ok[i]) Elem<T>::store1(p.kv_out, orow[i] * p.kv_stride + col, kv[i]);
+            }
         }
     }
 }
@@ -572,10 +607,15 @@ int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
         // (always the same kernel for a given shape, whatever the number of rows: the two sum the
         // LayerNorm statistics in different orders, and the embeddings must not depend on how the
         // rows were cut into launches)
-        if constexpr (can_split)
-            hipLaunchKernelGGL((gemm_ln_split_kernel<T, D>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
-        else
+        if constexpr (can_split) {
+            if (a.kv_out)
+                hipLaunchKernelGGL((gemm_ln_split_kernel<T, D, true>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
+            else
+                hipLaunchKernelGGL((gemm_ln_split_kernel<T, D, false>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
+        } else {
+            if (a.kv_out) return hipErrorInvalidValue;
             hipLaunchKernelGGL((gemm_kernel<T, D, true>), dim3(grid), dim3(256), 0, s, a);
+        }
     } else {
         if (a.out2 && a.n_cols != D) return hipErrorInvalidValue;
         dg4_gemm_args b = a;
@@ -1016,6 +1056,14 @@ int dg4_launch_struct_encode(int dtype, int hidden, const void* x, const int32_t
     if (dtype == DG4_F32)
         return hidden == 128 ? launch_struct_encode_t<float, 128>(x, feat, emb, out, n, s) : launch_struct_encode_t<float, 256>(x, feat, emb, out, n, s);
     return hidden == 128 ? launch_struct_encode_t<uint16_t, 128>(x, feat, emb, out, n, s) : launch_struct_encode_t<uint16_t, 256>(x, feat, emb, out, n, s);
+}
+
+// shapes whose epilogue kernel can carry the K | V product (gemm_ln_split_kernel)
+bool dg4_gemm_fuses_kv(int dtype, int hidden)
+{
+    const int e = dtype == DG4_F32 ? 4 : 8;
+    const int kc = hidden / (2 * e), group = kc > 16 ? kc : 16;
+    return (hidden / 32) % 4 == 0 && ((hidden / 32 / 4) * kc) % group == 0;
 }
 
 int dg4_launch_attn(int dtype, int hidden, const dg4_attn_args& a, hipStream_t s)
