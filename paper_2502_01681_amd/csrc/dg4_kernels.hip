@@ -135,7 +135,7 @@ __global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
 }
 
 // The same for rows of any width (cones deeper than three hops, up to 2^(k+1)-1 sources). S lane
-// groups share a row: group `part` walks the chunks of four entries part, part + S, ... with a
+// groups share a row: group `part` walks the chunks of CH entries part, part + S, ... with a
 // running maximum, denominator and weighted sum (the softmax is unchanged by the rescaling), and
 // the S partial results are merged through LDS by the first group. Long rows of few gates per
 // level thus keep many loads in flight. Rows are padded at the end only, to a multiple of four.
@@ -146,7 +146,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
     constexpr int LPR = D / EPL;              // lanes per lane group
     constexpr int G = 256 / LPR;              // lane groups per workgroup
     constexpr int RPB = G / S;                // rows per workgroup
-    constexpr int CH = 4;
+    constexpr int CH = S == G ? 8 : 4;        // sources per step (a whole workgroup per row: few steps, more loads in flight)
     static_assert(G % S == 0, "lane groups per row must divide the workgroup");
     __shared__ float part_m[S > 1 ? 256 : 1], part_z[S > 1 ? 256 : 1], part_acc[S > 1 ? 256 * EPL : 1];
     const int group = threadIdx.x / LPR;
@@ -173,8 +173,13 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
         const float scale = 0.17677669529663687f;     // 1/sqrt(32)
         const uint32_t* erow = p.ell + row * (int64_t)p.ell_w;
         for (int c0 = part * CH; c0 < p.ell_w; c0 += S * CH) {
-            const uint4 e4 = *(const uint4*)(erow + c0);
-            const uint32_t ent[CH] = { e4.x, e4.y, e4.z, e4.w };
+            uint32_t ent[CH];
+#pragma unroll
+            for (int q = 0; q < CH; q += 4) {
+                // (the table's width is a multiple of four, not of eight: the second half may lie past the row)
+                const uint4 e4 = c0 + q < p.ell_w ? *(const uint4*)(erow + c0 + q) : make_uint4(DG4_ELL_PAD, DG4_ELL_PAD, DG4_ELL_PAD, DG4_ELL_PAD);
+                ent[q] = e4.x; ent[q + 1] = e4.y; ent[q + 2] = e4.z; ent[q + 3] = e4.w;
+            }
             if (ent[0] == DG4_ELL_PAD) break;         // the same for all lanes of the group
             uint4 ka[CH], kb[CH], va[CH], vb[CH];
 #pragma unroll
