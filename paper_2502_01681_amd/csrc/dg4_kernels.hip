@@ -503,6 +503,7 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     int64_t orow[16];
     bool ok[16];
     float res[NTW][16];
+    int32_t oidx[16];                             // where the row goes in out[0], if scattered
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int row = 8 * (i / 4) + 4 * kg + (i % 4);
@@ -510,6 +511,7 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         ok[i] = r < p.row_end;
         orow[i] = ok[i] ? r : p.row_end - 1;
         const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[orow[i]] : orow[i];
+        oidx[i] = p.out_scatter ? p.out_scatter[orow[i]] : (int32_t)0;
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) res[nt][i] = Elem<T>::load1(p.resid, rr * p.resid_stride + col0 + nt * 32);
     }
@@ -523,6 +525,12 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         }
         Mma<T>::run(a[c], ring[j % RING], acc[nt]);
         if (j + RING < NTW * KC) ring[j % RING] = wp[(j + RING) * 64];
+    }
+    constexpr int NTW2 = 2 * D / 32 / 4;          // column tiles of K | V per wave
+    const uint4* wp2 = (const uint4*)p.kv_w_packed + (int64_t)wave * NTW2 * KC * 64 + lane;
+    if constexpr (KV) {                           // the second product's first fragments, under the LayerNorm
+#pragma unroll
+        for (int j = 0; j < RING; ++j) ring[j] = wp2[j * 64];
     }
     // residual, then LayerNorm over each row (no affine, biased variance), in two passes
     float mean[16];
@@ -555,7 +563,7 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         if (!ok[i]) continue;
         const int row = 8 * (i / 4) + 4 * kg + (i % 4);
         const float rstd = rsqrtf((part[1][0][row] + part[1][1][row] + part[1][2][row] + part[1][3][row]) * (1.0f / D) + p.ln_eps);
-        const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
+        const int64_t orr = p.out_scatter ? (int64_t)oidx[i] : orow[i];
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
             const float y = (acc[nt][i] - mean[i]) * rstd;
@@ -570,11 +578,7 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         uint4 a2[KC];
 #pragma unroll
         for (int c = 0; c < KC; ++c) a2[c] = *(const uint4*)&ybuf[m * YS + (2 * c + kg) * E];
-        constexpr int NTW2 = 2 * D / 32 / 4;      // column tiles of K | V per wave
         static_assert((NTW2 * KC) % GROUP == 0, "whole groups per wave");
-        const uint4* wp2 = (const uint4*)p.kv_w_packed + (int64_t)wave * NTW2 * KC * 64 + lane;
-#pragma unroll
-        for (int j = 0; j < RING; ++j) ring[j] = wp2[j * 64];
         f32x16 kv;
 #pragma unroll
         for (int j = 0; j < NTW2 * KC; ++j) {
