@@ -159,3 +159,27 @@ def test_without_marks_one_copy_per_mini_batch_and_gate(seed, k, delta, batch, c
     with pytest.raises(dg4.DG4Error):
         marked.array("copy_of")
     assert g.n > marked.n
+
+
+def test_degenerate_circuits():
+    # nothing at all; primary inputs only (each is read by nothing: one cone per input, in the list of level 0)
+    for marks in (True, False):
+        empty = dg4.dg4_build_partitioned(0, [], [], [], 3, 2, 8, marks=marks)
+        assert empty.n == 0 and empty.array("cone_root").size == 0 and empty.array("cone_group_ptr").tolist() == [0]
+        g = dg4.dg4_build_partitioned(5, [], [], [], 8, 6, 2, marks=marks)
+        assert g.n == 5 and g.array("cone_root").tolist() == [0, 1, 2, 3, 4]
+        assert g.array("cone_group_level").tolist() == [0] and g.array("cone_group_ptr").tolist() == [0, 5]
+        assert g.array("nbr_idx").tolist() == [0, 1, 2, 3, 4] and g.array("nbr_rel").tolist() == [0] * 5
+        if marks:
+            assert g.array("stage").tolist() == [0, 0, 1, 1, 2]
+        else:
+            assert g.array("copy_of").tolist() == [0, 1, 2, 3, 4] and g.array("last_copy").tolist() == [0, 1, 2, 3, 4]
+    og = oracle.build_levels(5, [], [], [], 8)
+    cones = oracle.partition(og, [], 6)
+    assert cones.cone_root.tolist() == [0, 1, 2, 3, 4] and cones.group_level.tolist() == [0]
+    # a single AND: level 1 < k, so its cone comes from the "read by nothing" rule and covers the inputs
+    g = dg4.dg4_build_partitioned(3, [0, 1], [2, 2], [0, 1], 3, 2, 4)
+    assert g.array("cone_root").tolist() == [2] and g.array("cone_group_level").tolist() == [1]
+    assert g.array("stage").tolist() == [0, 0, 0] and g.nnz == 5
+    og = oracle.build_levels(3, [0, 1], [2, 2], [0, 1], 3)
+    assert oracle.partition(og, [0, 1], 2).cone_root.tolist() == [2]
