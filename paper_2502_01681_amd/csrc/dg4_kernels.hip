@@ -794,14 +794,17 @@ __global__ __launch_bounds__(256) void ffn_kernel(dg4_ffn_args p)
 // ------------------------------------------------- feed-forward, many rows at once (bf16, d = 256)
 //
 // dg4_ffn_fwd over a whole matrix is bound by how often the megabyte of W1 | W2 has to come from
-// the L2 cache: ffn_kernel above reads it once per 32 rows. Here a workgroup takes 96 rows, keeps
+// the L2 cache: ffn_kernel above reads it once per 32 rows. Here a workgroup takes 64 rows, keeps
 // them in LDS, and streams the weights once for all of them: one contiguous stream per wave, in
 // four passes of 256 hidden units. Per pass a wave forms the activations of its 64 hidden units
-// for all 96 rows (transposed, W1 piece as the A operand), rectifies and writes them to LDS,
+// for all 64 rows (transposed, W1 piece as the A operand), rectifies and writes them to LDS,
 // and after a barrier adds the pass's part of ITS 64 output columns for all rows (the output
-// accumulators, 96 registers, stay put over the passes). Residual + LayerNorm from registers with
+// accumulators, 64 registers, stay put over the passes). Residual + LayerNorm from registers with
 // the row sums completed through LDS; the result leaves through LDS as whole 16-byte pieces.
-constexpr int FB_ROWS = 96, FB_RT = 3, FB_STRIDE = 264, FB_PASSES = 4, FB_FRAGS = 64, FB_RING = 16;
+// Two workgroups share a compute unit (70 KB of LDS and at most 256 registers each), so that one
+// computes while the other waits at a barrier or for its rows: measured 1.18 ms for 1M rows, against
+// 1.32 ms with 96 rows and one workgroup per compute unit (a third less weight traffic, no overlap).
+constexpr int FB_ROWS = 64, FB_RT = 2, FB_STRIDE = 264, FB_PASSES = 4, FB_FRAGS = 64, FB_RING = 8;
 constexpr int FB_SMEM = 2 * FB_ROWS * FB_STRIDE * 2 + 2 * 4 * FB_ROWS * 4;
 
 // Stream order, 16-byte units: (((w*4 + pass)*64 + j)*64 + lane), lane = 32*kg + m.
@@ -839,7 +842,7 @@ __device__ __forceinline__ void lds_barrier()      // LDS traffic only: the weig
     __asm__ volatile("" ::: "memory");
 }
 
-__global__ __launch_bounds__(256) void ffn_bulk_kernel(dg4_ffn_args p)
+__global__ __launch_bounds__(256, 2) void ffn_bulk_kernel(dg4_ffn_args p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char fb_smem[];
     uint16_t (*sH)[FB_STRIDE] = (uint16_t (*)[FB_STRIDE])fb_smem;
