@@ -263,6 +263,12 @@ int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begi
  * and W holds 5*n_layers pointers: Wqkv_l, Wo_l, rel_bias_l, W1_l [hidden,4*hidden],
  * W2_l [4*hidden,hidden].
  * The workspace contents are scratch; nothing persists between calls.
+ * On a graph from dg4_build_partitioned the same sweep realises Algorithm 2 in general (the rows
+ * of the graph are what each gate's first mini-batch shows of its cone).
+ * The order in which a sweep over ALL levels visits the gates is the library's (dependency-driven
+ * tiles in the persistent kernel, Eq. 1 levels in level-by-level launches) and does not change a
+ * bit of the result; the environment variable DG4_SWEEP_LEVEL_ORDER=1 forces the graph's own levels
+ * (for comparisons).
  */
 int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const void* const* W,
                   int32_t level_begin, int32_t level_end, void* Hout,
