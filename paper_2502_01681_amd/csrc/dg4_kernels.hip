@@ -478,8 +478,14 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     constexpr int GROUP = KC > RING ? KC : RING;
     static_assert((NTW * KC) % GROUP == 0, "whole groups per wave");
     __shared__ float part[2][4][32];
-    constexpr int YS = D + E;                     // row stride of the staged rows: 16 bytes of padding
-    __shared__ __attribute__((aligned(16))) T ybuf[KV ? 32 * YS : 1];
+    // The 32 rows of the workgroup pass through LDS twice, as whole 16-byte pieces on the global
+    // side: first the residual rows (in), then the normalised rows (out, and the operand of the K | V
+    // product). Element-wise traffic of the accumulator layout (2 or 4 bytes per lane and access)
+    // stays inside LDS.
+    constexpr int YS = D + E;                     // row stride: 16 bytes of padding
+    constexpr int CPR = D / E;                    // 16-byte pieces per row
+    constexpr int PPT = 32 * CPR / 256;           // pieces per thread
+    __shared__ __attribute__((aligned(16))) T ybuf[32 * YS];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int m = lane & 31, kg = lane >> 5;
@@ -498,22 +504,17 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     uint4 ring[RING];
 #pragma unroll
     for (int j = 0; j < RING; ++j) ring[j] = wp[j * 64];
-    // the residual does not wait for the product: fetched now, added after it
-    const int col0 = wave * NTW * 32 + m;
-    int64_t orow[16];
-    bool ok[16];
-    float res[NTW][16];
-    int32_t oidx[16];                             // where the row goes in out[0], if scattered
+    // this thread's pieces of the rows: the residual now, where the results go later
+    uint4 rpiece[PPT];
+    int64_t pidx[PPT];                            // row of out[0] for the piece (-1: past the end)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int row = 8 * (i / 4) + 4 * kg + (i % 4);
+    for (int q = 0; q < PPT; ++q) {
+        const int piece = (int)threadIdx.x + 256 * q, row = piece / CPR, c = piece % CPR;
         const int64_t r = r0 + row;
-        ok[i] = r < p.row_end;
-        orow[i] = ok[i] ? r : p.row_end - 1;
-        const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[orow[i]] : orow[i];
-        oidx[i] = p.out_scatter ? p.out_scatter[orow[i]] : (int32_t)0;
-#pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) res[nt][i] = Elem<T>::load1(p.resid, rr * p.resid_stride + col0 + nt * 32);
+        const int64_t rc = r < p.row_end ? r : p.row_end - 1;
+        const int64_t rr = p.resid_gather ? (int64_t)p.resid_gather[rc] : rc;
+        pidx[q] = r < p.row_end ? (p.out_scatter ? (int64_t)p.out_scatter[rc] : rc) : -1;
+        rpiece[q] = *((const uint4*)((const T*)p.resid + rr * p.resid_stride) + c);
     }
     f32x16 acc[NTW];
 #pragma unroll
@@ -532,7 +533,14 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
 #pragma unroll
         for (int j = 0; j < RING; ++j) ring[j] = wp2[j * 64];
     }
+#pragma unroll
+    for (int q = 0; q < PPT; ++q) {
+        const int piece = (int)threadIdx.x + 256 * q;
+        *(uint4*)&ybuf[(piece / CPR) * YS + (piece % CPR) * E] = rpiece[q];
+    }
+    __syncthreads();
     // residual, then LayerNorm over each row (no affine, biased variance), in two passes
+    const int col0 = wave * NTW * 32 + m;
     float mean[16];
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
@@ -540,13 +548,13 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         float s1 = 0.f;
 #pragma unroll
         for (int nt = 0; nt < NTW; ++nt) {
-            acc[nt][i] += res[nt][i];
+            acc[nt][i] += Elem<T>::load1(ybuf, (int64_t)row * YS + col0 + nt * 32);
             s1 += acc[nt][i];
         }
         s1 = sum_over_32_lanes(s1);
         if (m == 0) part[0][wave][row] = s1;
     }
-    __syncthreads();
+    __syncthreads();                              // (also: every wave has taken its residual values)
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int row = 8 * (i / 4) + 4 * kg + (i % 4);
@@ -560,21 +568,32 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     __syncthreads();
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        if (!ok[i]) continue;
         const int row = 8 * (i / 4) + 4 * kg + (i % 4);
         const float rstd = rsqrtf((part[1][0][row] + part[1][1][row] + part[1][2][row] + part[1][3][row]) * (1.0f / D) + p.ln_eps);
-        const int64_t orr = p.out_scatter ? (int64_t)oidx[i] : orow[i];
 #pragma unroll
-        for (int nt = 0; nt < NTW; ++nt) {
-            const float y = (acc[nt][i] - mean[i]) * rstd;
-            Elem<T>::store1(p.out[0], orr * p.out_stride + col0 + nt * 32, y);
-            if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col0 + nt * 32, y);
-            if constexpr (KV) Elem<T>::store1(ybuf, (int64_t)row * YS + col0 + nt * 32, y);
-        }
+        for (int nt = 0; nt < NTW; ++nt)
+            Elem<T>::store1(ybuf, (int64_t)row * YS + col0 + nt * 32, (acc[nt][i] - mean[i]) * rstd);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int q = 0; q < PPT; ++q) {
+        if (pidx[q] < 0) continue;
+        const int piece = (int)threadIdx.x + 256 * q, row = piece / CPR, c = piece % CPR;
+        const uint4 v = *(const uint4*)&ybuf[row * YS + c * E];
+        *((uint4*)((T*)p.out[0] + pidx[q] * p.out_stride) + c) = v;
+        if (p.out2) *((uint4*)((T*)p.out2 + (r0 + row) * p.out2_stride) + c) = v;
+    }
+    // rows this lane's accumulator elements belong to (for the K | V rows below)
+    int64_t orow[16];
+    bool ok[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t r = r0 + 8 * (i / 4) + 4 * kg + (i % 4);
+        ok[i] = r < p.row_end;
+        orow[i] = ok[i] ? r : p.row_end - 1;
     }
     if constexpr (KV) {
-        __syncthreads();
-        // rows past the end were skipped above: their staged rows are never stored below either
+        // (rows past the end hold the last row's values: computed, never stored)
         uint4 a2[KC];
 #pragma unroll
         for (int c = 0; c < KC; ++c) a2[c] = *(const uint4*)&ybuf[m * YS + (2 * c + kg) * E];
