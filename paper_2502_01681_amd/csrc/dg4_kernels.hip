@@ -486,6 +486,9 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     constexpr int CPR = D / E;                    // 16-byte pieces per row
     constexpr int PPT = 32 * CPR / 256;           // pieces per thread
     __shared__ __attribute__((aligned(16))) T ybuf[32 * YS];
+    constexpr int TS = 32 + E;                    // row stride of a staged 32x32 tile
+    constexpr int TPR = 32 / E;                   // 16-byte pieces per row of a tile
+    __shared__ __attribute__((aligned(16))) T tile[KV ? 4 : 1][KV ? 32 * TS : 1];
     const int lane = threadIdx.x & 63;
     const int wave = threadIdx.x >> 6;
     const int m = lane & 31, kg = lane >> 5;
@@ -583,15 +586,6 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
         *((uint4*)((T*)p.out[0] + pidx[q] * p.out_stride) + c) = v;
         if (p.out2) *((uint4*)((T*)p.out2 + (r0 + row) * p.out2_stride) + c) = v;
     }
-    // rows this lane's accumulator elements belong to (for the K | V rows below)
-    int64_t orow[16];
-    bool ok[16];
-#pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int64_t r = r0 + 8 * (i / 4) + 4 * kg + (i % 4);
-        ok[i] = r < p.row_end;
-        orow[i] = ok[i] ? r : p.row_end - 1;
-    }
     if constexpr (KV) {
         // (rows past the end hold the last row's values: computed, never stored)
         uint4 a2[KC];
@@ -609,10 +603,19 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
             Mma<T>::run(a2[c], ring[j % RING], kv);
             if (j + RING < NTW2 * KC) ring[j % RING] = wp2[(j + RING) * 64];
             if (c == KC - 1) {
-                const int col = (wave * NTW2 + nt) * 32 + m;
+                // the 32x32 tile leaves through this wave's own corner of LDS, as 16-byte pieces
+                // (LDS operations of a wave complete in order: no barrier)
 #pragma unroll
                 for (int i = 0; i < 16; ++i)
-                    if (ok[i]) Elem<T>::store1(p.kv_out, orow[i] * p.kv_stride + col, kv[i]);
+                    Elem<T>::store1(tile[wave], (int64_t)(8 * (i / 4) + 4 * kg + (i % 4)) * TS + m, kv[i]);
+                const int col = (wave * NTW2 + nt) * 32;
+#pragma unroll
+                for (int q = 0; q < 32 * TPR / 64; ++q) {
+                    const int piece = lane + 64 * q, row = piece / TPR, cc = piece % TPR;
+                    const uint4 v = *(const uint4*)&tile[wave][row * TS + cc * E];
+                    if (r0 + row < p.row_end)
+                        *(uint4*)((T*)p.kv_out + (r0 + row) * p.kv_stride + col + cc * E) = v;
+                }
             }
         }
     }
