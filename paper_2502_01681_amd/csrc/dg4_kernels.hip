@@ -354,6 +354,9 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
     // of the columns each, which puts four times as many compute units to work.
     const bool split = !LN && p.split != 0;
     const int64_t r0 = p.row_begin + (split ? (int64_t)blockIdx.x : (int64_t)blockIdx.x * 4 + wave) * 32;
+    constexpr int TS = 32 + E;                    // row stride of a staged 32x32 tile
+    constexpr int TPR = 32 / E;                   // 16-byte pieces per row of a tile
+    __shared__ __attribute__((aligned(16))) T tile[LN ? 1 : 4][LN ? 1 : 32 * TS];
     if (r0 >= p.row_end) return;
 
     uint4 a[KC];
@@ -406,15 +409,23 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
                 Mma<T>::run(a[c], ring[j % RING], acc);
                 if (f0 + j + RING < total) ring[j % RING] = wp[(f0 + j + RING) * 64 + lane];
                 if (c == KC - 1) {
-                    const int col = (int)(f0 / KC + j / KC) * 32 + m;
-                    void* base = p.out[col / D];
-                    const int cc = col % D;
+                    // the 32x32 tile leaves through this wave's own corner of LDS, as 16-byte pieces
+                    // of rows (LDS operations of a wave complete in order: no barrier)
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) {
-                        if (!ok[i]) continue;
-                        const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[orow[i]] : orow[i];
-                        Elem<T>::store1(base, orr * p.out_stride + cc, acc[i]);
-                        if (p.out2) Elem<T>::store1(p.out2, orow[i] * p.out2_stride + col, acc[i]);
+                    for (int i = 0; i < 16; ++i)
+                        Elem<T>::store1(tile[wave], (int64_t)(8 * (i / 4) + 4 * kg + (i % 4)) * TS + m, acc[i]);
+                    const int col = (int)(f0 / KC + j / KC) * 32;
+                    T* base = (T*)p.out[col / D] + col % D;
+#pragma unroll
+                    for (int q = 0; q < 32 * TPR / 64; ++q) {
+                        const int piece = lane + 64 * q, row = piece / TPR, cc = piece % TPR;
+                        const uint4 v = *(const uint4*)&tile[wave][row * TS + cc * E];
+                        const int64_t r = r0 + row;
+                        if (r < p.row_end) {
+                            const int64_t orr = p.out_scatter ? (int64_t)p.out_scatter[r] : r;
+                            *(uint4*)(base + orr * p.out_stride + cc * E) = v;
+                            if (p.out2) *(uint4*)((T*)p.out2 + r * p.out2_stride + col + cc * E) = v;
+                        }
                     }
                 }
             }
