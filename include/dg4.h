@@ -14,6 +14,8 @@
  *     on the first device call that uses the graph or in dg4_graph_upload.
  *   - rows of X, H, Q, K, V, A are indexed by ORIGINAL node id, row-major,
  *     `hidden` elements each, element type cfg->dtype (float or bfloat16).
+ *     Device tensors and weight matrices start on a 16-byte boundary (EINVAL
+ *     otherwise): rows are read and written as 16-byte pieces.
  *   - device calls are asynchronous on `stream` (a hipStream_t, may be NULL
  *     for the default stream) and touch no other stream.
  *   - a dg4_graph is immutable after construction; concurrent calls may share it.

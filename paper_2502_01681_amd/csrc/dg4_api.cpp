@@ -98,6 +98,9 @@ SweepEvents& sweep_events() { static SweepEvents e; return e; }
 
 #define HIPCHK(expr) do { if ((expr) != (int)hipSuccess) return DG4_EHIP; } while (0)
 
+// rows are read and written as 16-byte pieces
+template <typename... P> bool aligned16(P... ptrs) { return (((uintptr_t)ptrs | ...) & 15) == 0; }
+
 }  // namespace
 
 extern "C" const char* dg4_strerror(int status)
@@ -153,6 +156,7 @@ extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row
     int rc = check_cfg(cfg, false);
     if (rc != DG4_OK) return rc;
     if (!S || !Wqkv || !Q || !K || !V || row_begin < 0 || row_end < row_begin) return DG4_EINVAL;
+    if (!aligned16(S, Wqkv, Q, K, V)) return DG4_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < dg4_proj_workspace_bytes(cfg)) return DG4_EWORKSPACE;
     if (row_end == row_begin) return DG4_OK;
     hipStream_t s = (hipStream_t)stream;
@@ -184,6 +188,7 @@ extern "C" int dg4_ffn_fwd(const dg4_layer_cfg* cfg, const void* S, int64_t row_
     int rc = check_cfg(cfg, false);
     if (rc != DG4_OK) return rc;
     if (!S || !W1 || !W2 || !Out || row_begin < 0 || row_end < row_begin) return DG4_EINVAL;
+    if (!aligned16(S, W1, W2, Out)) return DG4_EINVAL;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < dg4_ffn_workspace_bytes(cfg)) return DG4_EWORKSPACE;
     if (row_end == row_begin) return DG4_OK;
     hipStream_t s = (hipStream_t)stream;
@@ -220,7 +225,7 @@ extern "C" int dg4_struct_encode(const dg4_layer_cfg* cfg, dg4_graph* g, const v
 {
     int rc = check_cfg(cfg, false);
     if (rc != DG4_OK) return rc;
-    if (!g || !X || !emb || !Xout) return DG4_EINVAL;
+    if (!g || !X || !emb || !Xout || !aligned16(X, emb, Xout)) return DG4_EINVAL;
     if (g->n == 0) return DG4_OK;
     rc = dg4_graph_ensure_struct(g);
     if (rc != DG4_OK) return rc;
@@ -234,7 +239,7 @@ extern "C" int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64
 {
     int rc = check_cfg(cfg, false);
     if (rc != DG4_OK) return rc;
-    if (!g || !Q || !K || !V || !rel_bias || !A) return DG4_EINVAL;
+    if (!g || !Q || !K || !V || !rel_bias || !A || !aligned16(Q, K, V, A)) return DG4_EINVAL;
     if (g->hops != cfg->hops || row_begin < 0 || row_end < row_begin || row_end > g->n) return DG4_EINVAL;
     if (row_end == row_begin) return DG4_OK;
     rc = dg4_graph_ensure_device(g);
@@ -258,7 +263,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
 {
     int rc = check_cfg(cfg, true);
     if (rc != DG4_OK) return rc;
-    if (!g || !X || !W || !Hout) return DG4_EINVAL;
+    if (!g || !X || !W || !Hout || !aligned16(X, Hout)) return DG4_EINVAL;
     if (g->hops != cfg->hops) return DG4_EINVAL;
     const int32_t n_levels = g->max_level + 1;
     if (level_begin < 0 || level_end < level_begin || level_end > n_levels) return DG4_EINVAL;

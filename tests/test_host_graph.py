@@ -181,3 +181,24 @@ def test_config_errors_without_a_device():
             dg4.dg4_layer_workspace_bytes(dg4.LayerConfig(**kw), g)
     assert dg4.dg4_layer_workspace_bytes(dg4.LayerConfig(128, 4, 2, 1, "f32"), g) > 0
     assert dg4.dg4_proj_workspace_bytes(dg4.LayerConfig(256, 8, 2, 1, "bf16")) == 256 * 768 * 2
+
+
+def test_misaligned_tensors_are_refused_before_any_device_work():
+    # rows travel as 16-byte pieces: a tensor that does not start on a 16-byte boundary is an
+    # argument error, found before anything is queued (so this needs no GPU: the addresses are never used)
+    L = dg4.lib()
+    cfg = dg4.LayerConfig(128, 4, 2, 1, "f32").c()
+    ok, odd = 0x10000, 0x10008
+    P = ctypes.c_void_p
+    rc = L.dg4_qkv_proj(ctypes.byref(cfg), P(odd), 0, 4, P(ok), P(ok), P(ok), P(ok), P(ok), 1 << 20, None)
+    assert rc == -1
+    rc = L.dg4_qkv_proj(ctypes.byref(cfg), P(ok), 0, 4, P(ok), P(ok), P(odd), P(ok), P(ok), 1 << 20, None)
+    assert rc == -1
+    rc = L.dg4_ffn_fwd(ctypes.byref(cfg), P(ok), 0, 4, P(ok), P(ok), P(odd), P(ok), 1 << 20, None)
+    assert rc == -1
+    g = dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2)
+    rc = L.dg4_sparse_attn_fwd(ctypes.byref(cfg), g.handle, 0, 3, P(ok), P(odd), P(ok), P(ok), P(ok), None)
+    assert rc == -1
+    W = (P * 3)(P(ok), P(ok), P(ok))
+    rc = L.dg4_layer_fwd(ctypes.byref(cfg), g.handle, P(ok), W, 0, 1, P(odd), P(ok), 1 << 30, None)
+    assert rc == -1
