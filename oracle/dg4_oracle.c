@@ -610,6 +610,8 @@ void orc_cones_copy(const orc_cones* c, int32_t* group_level, int64_t* group_ptr
     memcpy(cone_node, c->cone_node, sizeof(int32_t) * (size_t)c->n_entries);
 }
 
+/* (qsort takes no context argument: the levels go through this file-scope pointer, so one call of
+ * orc_partitioned_fwd at a time) */
 static const int32_t* sort_level;
 static int by_level_then_id(const void* a, const void* b)
 {
