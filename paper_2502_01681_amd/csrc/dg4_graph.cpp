@@ -5,6 +5,7 @@
 #include <cstring>
 #include <new>
 #include <queue>
+#include <thread>
 
 #include "dg4_internal.h"
 
@@ -143,31 +144,62 @@ void cone_step(int64_t n, const Fanins& f, const ConeTable& prev, ConeTable& nex
 void deep_cones(dg4_graph* g, const Fanins& f)
 {
     const int64_t n = g->n;
-    std::vector<int32_t> seen((size_t)n, -1);
-    std::vector<std::pair<int32_t, uint8_t>> row;       // (id, code)
-    std::vector<int32_t> frontier, next;
-    g->nbr_ptr.assign((size_t)n + 1, 0);
-    g->nbr_idx.clear(); g->nbr_rel.clear();
-    for (int64_t v = 0; v < n; ++v) {
-        row.clear(); frontier.clear();
-        row.emplace_back((int32_t)v, (uint8_t)0);
-        seen[v] = (int32_t)v;
-        frontier.push_back((int32_t)v);
-        for (int hop = 1; hop <= g->hops && !frontier.empty(); ++hop) {
-            next.clear();
-            for (const int32_t w : frontier)
-                for (int i = 0; i < 2; ++i) {
-                    const int32_t u = f.src[2 * (size_t)w + i];
-                    if (u < 0 || seen[u] == (int32_t)v) continue;
-                    seen[u] = (int32_t)v;
-                    row.emplace_back(u, hop == 1 ? (uint8_t)(1 + f.inv[2 * (size_t)w + i]) : (uint8_t)3);
-                    next.push_back(u);
+    // contiguous ranges of gates, one per host thread; the pieces are joined in order
+    const int64_t want = std::max<int64_t>(1, std::min<int64_t>(16, (int64_t)std::thread::hardware_concurrency()));
+    const int n_parts = (int)std::max<int64_t>(1, std::min<int64_t>(want, n / 4096));
+    struct Part { std::vector<int32_t> idx; std::vector<uint8_t> rel; std::vector<int32_t> cnt; bool failed = false; };
+    std::vector<Part> parts((size_t)n_parts);
+    auto work = [&](int t) {
+        Part& out = parts[(size_t)t];
+        try {
+            const int64_t v0 = n * t / n_parts, v1 = n * (t + 1) / n_parts;
+            std::vector<int32_t> seen((size_t)n, -1);
+            std::vector<std::pair<int32_t, uint8_t>> row;       // (id, code)
+            std::vector<int32_t> frontier, next;
+            out.cnt.reserve((size_t)(v1 - v0));
+            for (int64_t v = v0; v < v1; ++v) {
+                row.clear(); frontier.clear();
+                row.emplace_back((int32_t)v, (uint8_t)0);
+                seen[v] = (int32_t)v;
+                frontier.push_back((int32_t)v);
+                for (int hop = 1; hop <= g->hops && !frontier.empty(); ++hop) {
+                    next.clear();
+                    for (const int32_t w : frontier)
+                        for (int i = 0; i < 2; ++i) {
+                            const int32_t u = f.src[2 * (size_t)w + i];
+                            if (u < 0 || seen[u] == (int32_t)v) continue;
+                            seen[u] = (int32_t)v;
+                            row.emplace_back(u, hop == 1 ? (uint8_t)(1 + f.inv[2 * (size_t)w + i]) : (uint8_t)3);
+                            next.push_back(u);
+                        }
+                    frontier.swap(next);
                 }
-            frontier.swap(next);
+                std::sort(row.begin(), row.end());
+                for (const auto& r : row) { out.idx.push_back(r.first); out.rel.push_back(r.second); }
+                out.cnt.push_back((int32_t)row.size());
+            }
+        } catch (...) {
+            out.failed = true;
         }
-        std::sort(row.begin(), row.end());
-        for (const auto& r : row) { g->nbr_idx.push_back(r.first); g->nbr_rel.push_back(r.second); }
-        g->nbr_ptr[v + 1] = (int64_t)g->nbr_idx.size();
+    };
+    {
+        std::vector<std::thread> threads;
+        for (int t = 1; t < n_parts; ++t) threads.emplace_back(work, t);
+        work(0);
+        for (auto& th : threads) th.join();
+    }
+    for (const Part& part : parts)
+        if (part.failed) throw std::bad_alloc();
+    g->nbr_ptr.assign((size_t)n + 1, 0);
+    size_t total = 0;
+    for (const Part& part : parts) total += part.idx.size();
+    g->nbr_idx.clear(); g->nbr_rel.clear();
+    g->nbr_idx.reserve(total); g->nbr_rel.reserve(total);
+    int64_t v = 0;
+    for (const Part& part : parts) {
+        g->nbr_idx.insert(g->nbr_idx.end(), part.idx.begin(), part.idx.end());
+        g->nbr_rel.insert(g->nbr_rel.end(), part.rel.begin(), part.rel.end());
+        for (const int32_t c : part.cnt) { g->nbr_ptr[(size_t)v + 1] = g->nbr_ptr[(size_t)v] + c; ++v; }
     }
     g->nnz = (int64_t)g->nbr_idx.size();
 }
