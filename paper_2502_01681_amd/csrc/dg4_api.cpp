@@ -444,7 +444,11 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             t.ell = bounded ? g->d_ell_front : d_ell_pos; t.ell_w = g->ell_w;
             t.a = local(pl.abuf, p0, d); t.a_stride = d;
             t.row_begin = p0; t.row_end = p1;
-            HIPCHK(dg4_launch_attn(dt, d, t, s));
+            // narrow rows, a level of few gates (bound by the latency of its launches): the attention
+            // runs inside the output projection's launch. The same arithmetic either way, so the
+            // choice by the size of the level does not show in the result.
+            const bool fuse_att = epi && g->ell_w <= 16 && p1 - p0 <= 4096 && dg4_gemm_fuses_kv(dt, d);
+            if (!fuse_att) HIPCHK(dg4_launch_attn(dt, d, t, s));
 
             // s_{l+1} = LN(s_l + a Wo_l), then (DG4_FFN) s_{l+1} <- LN(s_{l+1} + relu(s_{l+1} W1_l) W2_l);
             // the last layer's result is H
@@ -467,7 +471,8 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             } else {
                 o.out[0] = next; o.out_stride = d;
             }
-            HIPCHK(dg4_launch_gemm(dt, d, o, s));
+            if (fuse_att) HIPCHK(dg4_launch_attn_gemm(dt, d, t, o, s));
+            else HIPCHK(dg4_launch_gemm(dt, d, o, s));
             if (ffn) {
                 dg4_ffn_args f{};
                 f.h = local(pl.h1, p0, d); f.h_stride = d;

@@ -136,6 +136,7 @@ struct dg4_gemm_args {
 };
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s);
 bool dg4_gemm_fuses_kv(int dtype, int hidden);
+int dg4_launch_attn_gemm(int dtype, int hidden, const dg4_attn_args& att, const dg4_gemm_args& a, hipStream_t s);
 
 // Feed-forward sub-block: out = LN(h + max(h W1, 0) W2) for rows [row_begin, row_end).
 struct dg4_ffn_args {

@@ -22,21 +22,14 @@ namespace {
 
 // ------------------------------------------------------------------ attention
 
-// One destination row per group of LPR lanes; every lane owns 32 contiguous
-// bytes of each 512-byte (or 256 / 1024-byte) row it touches.
+// The attention of one destination row, by a group of LPR = D / EPL lanes of which this lane is
+// number `sub`: every lane owns 32 contiguous bytes of each 512-byte (or 256 / 1024-byte) row it
+// touches and ends with its EPL elements of the row's result.
 template <typename T, int D, int W>
-__global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
+__device__ __forceinline__ void attend_row(const dg4_attn_args& p, int64_t row, int sub, float (&acc)[Elem<T>::EPL])
 {
     constexpr int EPL = Elem<T>::EPL;
-    constexpr int LPR = D / EPL;              // lanes per row
-    constexpr int RPW = 64 / LPR;             // rows per wave
     constexpr int CH = W < 8 ? W : 8;         // neighbour rows in flight per pass
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int sub = lane % LPR;
-    const int64_t row = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
-    if (row >= p.row_end) return;             // whole lane groups leave together
-
     const int64_t eoff = (int64_t)sub * EPL;  // element offset of this lane inside a row
     const int head = (int)(eoff >> 5);
 
@@ -104,7 +97,6 @@ __global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
     const float rz = 1.0f / z;
 
     // pass 2: aggregation
-    float acc[EPL];
 #pragma unroll
     for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
 #pragma unroll
@@ -128,9 +120,25 @@ __global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
             for (int i = 0; i < EPL; ++i) acc[i] = fmaf(al, v[i], acc[i]);
         }
     }
+}
+
+// One destination row per group of LPR lanes.
+template <typename T, int D, int W>
+__global__ __launch_bounds__(256) void attn_kernel(dg4_attn_args p)
+{
+    constexpr int EPL = Elem<T>::EPL;
+    constexpr int LPR = D / EPL;              // lanes per row
+    constexpr int RPW = 64 / LPR;             // rows per wave
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int sub = lane % LPR;
+    const int64_t row = p.row_begin + ((int64_t)blockIdx.x * 4 + wave) * RPW + lane / LPR;
+    if (row >= p.row_end) return;             // whole lane groups leave together
+    float acc[EPL];
+    attend_row<T, D, W>(p, row, sub, acc);
     uint4 oa, ob;
     Elem<T>::pack(acc, oa, ob);
-    uint4* op = (uint4*)((T*)p.a + row * p.a_stride + eoff);
+    uint4* op = (uint4*)((T*)p.a + row * p.a_stride + (int64_t)sub * EPL);
     op[0] = oa; op[1] = ob;
 }
 
@@ -479,8 +487,11 @@ __global__ __launch_bounds__(256) void gemm_kernel(dg4_gemm_args p)
 // KV: the normalised rows also go, rounded to T, through LDS into a second product with the packed
 // [D, 2D] weight p.kv_w_packed, each wave taking a quarter of its 2D columns (the K | V rows of the
 // gates of a one-layer sweep, otherwise a launch of their own).
-template <typename T, int D, bool KV>
-__global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
+// AW > 0: the rows' operand is not read from memory but computed here, the attention of the 32
+// rows over neighbour rows of width AW (attend_row, two or four rows per lane group, through LDS
+// into the operand layout): attention, output projection, LayerNorm and K | V in one launch.
+template <typename T, int D, bool KV, int AW>
+__global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p, dg4_attn_args t)
 {
     constexpr int E = 16 / sizeof(T);
     constexpr int KC = D / (2 * E);
@@ -506,7 +517,7 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     const int64_t r0 = p.row_begin + (int64_t)blockIdx.x * 32;
 
     uint4 a[KC];
-    {
+    if constexpr (AW == 0) {
         int64_t r = r0 + m;
         if (r >= p.row_end) r = p.row_end - 1;          // clamp: loads stay in bounds, stores are masked
         const int64_t ar = p.a_gather ? (int64_t)p.a_gather[r] : r;
@@ -518,6 +529,25 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
     uint4 ring[RING];
 #pragma unroll
     for (int j = 0; j < RING; ++j) ring[j] = wp[j * 64];
+    if constexpr (AW > 0) {
+        constexpr int EPL = Elem<T>::EPL, LPR = D / EPL, G = 256 / LPR;
+        const int group = (int)threadIdx.x / LPR, sub = (int)threadIdx.x % LPR;
+#pragma unroll 1
+        for (int rr = group; rr < 32; rr += G) {
+            int64_t row = r0 + rr;
+            if (row >= p.row_end) row = p.row_end - 1;  // computed again, never stored
+            float av[EPL];
+            attend_row<T, D, AW>(t, row, sub, av);
+            uint4 oa, ob;
+            Elem<T>::pack(av, oa, ob);
+            uint4* op = (uint4*)&ybuf[rr * YS + sub * EPL];
+            op[0] = oa; op[1] = ob;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < KC; ++c) a[c] = *(const uint4*)&ybuf[m * YS + (2 * c + kg) * E];
+        __syncthreads();                          // the space is used again for the residual rows
+    }
     // this thread's pieces of the rows: the residual now, where the results go later
     uint4 rpiece[PPT];
     int64_t pidx[PPT];                            // row of out[0] for the piece (-1: past the end)
@@ -633,7 +663,7 @@ __global__ __launch_bounds__(256) void gemm_ln_split_kernel(dg4_gemm_args p)
 }
 
 template <typename T, int D>
-int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
+int launch_gemm_t(const dg4_gemm_args& a, const dg4_attn_args* att, hipStream_t s)
 {
     const int64_t rows = a.row_end - a.row_begin;
     if (rows <= 0) return hipSuccess;
@@ -650,12 +680,31 @@ int launch_gemm_t(const dg4_gemm_args& a, hipStream_t s)
         // LayerNorm statistics in different orders, and the embeddings must not depend on how the
         // rows were cut into launches)
         if constexpr (can_split) {
-            if (a.kv_out)
-                hipLaunchKernelGGL((gemm_ln_split_kernel<T, D, true>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
-            else
-                hipLaunchKernelGGL((gemm_ln_split_kernel<T, D, false>), dim3((unsigned)((rows + 31) / 32)), dim3(256), 0, s, a);
+            const dim3 g32((unsigned)((rows + 31) / 32));
+            const dg4_attn_args none{};
+            const int aw = att ? att->ell_w : 0;
+            if (att && (att->row_begin != a.row_begin || att->row_end != a.row_end)) return hipErrorInvalidValue;
+#define DG4_LAUNCH_LN(KV_, AW_) hipLaunchKernelGGL((gemm_ln_split_kernel<T, D, KV_, AW_>), g32, dim3(256), 0, s, a, att ? *att : none)
+            if (a.kv_out) {
+                switch (aw) {
+                case 0: DG4_LAUNCH_LN(true, 0); break;
+                case 4: DG4_LAUNCH_LN(true, 4); break;
+                case 8: DG4_LAUNCH_LN(true, 8); break;
+                case 16: DG4_LAUNCH_LN(true, 16); break;
+                default: return hipErrorInvalidValue;
+                }
+            } else {
+                switch (aw) {
+                case 0: DG4_LAUNCH_LN(false, 0); break;
+                case 4: DG4_LAUNCH_LN(false, 4); break;
+                case 8: DG4_LAUNCH_LN(false, 8); break;
+                case 16: DG4_LAUNCH_LN(false, 16); break;
+                default: return hipErrorInvalidValue;
+                }
+            }
+#undef DG4_LAUNCH_LN
         } else {
-            if (a.kv_out) return hipErrorInvalidValue;
+            if (a.kv_out || att) return hipErrorInvalidValue;
             hipLaunchKernelGGL((gemm_kernel<T, D, true>), dim3(grid), dim3(256), 0, s, a);
         }
     } else {
@@ -1167,6 +1216,16 @@ int dg4_launch_ffn(int dtype, int hidden, const dg4_ffn_args& a, hipStream_t s)
 
 int dg4_launch_gemm(int dtype, int hidden, const dg4_gemm_args& a, hipStream_t s)
 {
-    if (dtype == DG4_F32) return hidden == 128 ? launch_gemm_t<float, 128>(a, s) : launch_gemm_t<float, 256>(a, s);
-    return hidden == 128 ? launch_gemm_t<bf16_t, 128>(a, s) : launch_gemm_t<bf16_t, 256>(a, s);
+    if (dtype == DG4_F32) return hidden == 128 ? launch_gemm_t<float, 128>(a, nullptr, s) : launch_gemm_t<float, 256>(a, nullptr, s);
+    return hidden == 128 ? launch_gemm_t<bf16_t, 128>(a, nullptr, s) : launch_gemm_t<bf16_t, 256>(a, nullptr, s);
+}
+
+// The epilogue product with its rows' operand computed in the same launch: the attention `att`
+// (same row range, neighbour rows of width 4, 8 or 16) instead of a.a. Shapes for which
+// dg4_gemm_fuses_kv() holds.
+int dg4_launch_attn_gemm(int dtype, int hidden, const dg4_attn_args& att, const dg4_gemm_args& a, hipStream_t s)
+{
+    if (!a.epilogue) return hipErrorInvalidValue;
+    if (dtype == DG4_F32) return hidden == 128 ? launch_gemm_t<float, 128>(a, &att, s) : launch_gemm_t<float, 256>(a, &att, s);
+    return hidden == 128 ? launch_gemm_t<bf16_t, 128>(a, &att, s) : launch_gemm_t<bf16_t, 256>(a, &att, s);
 }
