@@ -6,7 +6,10 @@ AIG: projections, per-edge scores, segmented softmax, aggregation, output
 projection + LayerNorm, swept over all of its about 1000 levels. Inputs are
 resident in HBM before the timed region; graph analysis (host) and uploads are
 reported separately and excluded. Prints ONE JSON line. `--ffn` times the layer with its
-feed-forward sub-block instead (not the headline configuration).
+feed-forward sub-block instead (not the headline configuration); `--partition K,STRIDE,BATCH`
+times the layer under the paper's general graph partition and updating strategy. The default
+run also carries kernel points, the feed-forward layer and a partition point (`partition`:
+200K-gate graph, k = 8, stride 6, mini-batches of 128 cones; marks against no marks at k = 3).
 """
 from __future__ import annotations
 
