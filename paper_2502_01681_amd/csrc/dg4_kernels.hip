@@ -180,14 +180,17 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
         for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[head * 4 + i];
         const float scale = 0.17677669529663687f;     // 1/sqrt(32)
         const uint32_t* erow = p.ell + row * (int64_t)p.ell_w;
-        for (int c0 = part * CH; c0 < p.ell_w; c0 += S * CH) {
-            uint32_t ent[CH];
+        // the CH entries at c0 (padding past the table: its width is a multiple of four, not of eight)
+        auto entries = [&](int c0, uint32_t (&e)[CH]) __attribute__((always_inline)) {
 #pragma unroll
             for (int q = 0; q < CH; q += 4) {
-                // (the table's width is a multiple of four, not of eight: the second half may lie past the row)
                 const uint4 e4 = c0 + q < p.ell_w ? *(const uint4*)(erow + c0 + q) : make_uint4(DG4_ELL_PAD, DG4_ELL_PAD, DG4_ELL_PAD, DG4_ELL_PAD);
-                ent[q] = e4.x; ent[q + 1] = e4.y; ent[q + 2] = e4.z; ent[q + 3] = e4.w;
+                e[q] = e4.x; e[q + 1] = e4.y; e[q + 2] = e4.z; e[q + 3] = e4.w;
             }
+        };
+        uint32_t ent[CH], ahead[CH];
+        entries(part * CH, ent);
+        for (int c0 = part * CH; c0 < p.ell_w; c0 += S * CH) {
             if (ent[0] == DG4_ELL_PAD) break;         // the same for all lanes of the group
             uint4 ka[CH], kb[CH], va[CH], vb[CH];
 #pragma unroll
@@ -204,6 +207,7 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
                     ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j]; va[j] = ka[j]; vb[j] = ka[j];
                 }
             }
+            entries(c0 + S * CH, ahead);              // the next step's entries travel with this step's rows
             float sc[CH];
             float cm = m;
 #pragma unroll
@@ -233,6 +237,8 @@ __global__ __launch_bounds__(256) void attn_wide_kernel(const dg4_attn_args p)
                 for (int i = 0; i < EPL; ++i) acc[i] = fmaf(pj, v[i], acc[i]);
             }
             m = cm;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) ent[j] = ahead[j];
         }
     }
     if (S > 1) {
