@@ -221,6 +221,20 @@ int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int
                  void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * dg4_qkv_proj for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc. Same arguments, meaning and results (bit for bit)
+ * as dg4_qkv_proj, but no workspace: the packed copy of the weight goes into a device array inside
+ * the library, dg4_static_scratch_bytes() = 512 KB per GPU, held until the process ends. The call
+ * allocates and frees nothing. EWORKSPACE if the packed weight does not fit (fp32 with hidden 256:
+ * 768 KB), before anything is queued. Every call on a GPU shares that GPU's array, so two calls that
+ * overlap in time on one GPU (different streams or threads) race; calls on one stream are safe, each
+ * rewrites what it reads.
+ */
+int64_t dg4_static_scratch_bytes(void);
+int dg4_qkv_proj_static(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                        const void* Wqkv, void* Q, void* K, void* V, void* stream);
+
+/*
  * The position-wise feed-forward sub-block that follows the attention sub-block in the
  * transformer layer (Section 3.5: the attention module is replaced, the rest of the transformer
  * structure is kept), for rows [row_begin, row_end) of S:

@@ -8,5 +8,6 @@ from .binding import (DG4Error, Graph, LayerConfig, dg4_build_levels, dg4_build_
                       dg4_build_partitioned, dg4_layer_fwd,
                       dg4_layer_profile, dg4_sweep_elapsed_ms,
                       dg4_layer_workspace_bytes, dg4_proj_workspace_bytes, dg4_qkv_proj,
+                      dg4_qkv_proj_static, dg4_static_scratch_bytes,
                       dg4_ffn_fwd, dg4_ffn_workspace_bytes,
                       dg4_sparse_attn_fwd, dg4_struct_encode, lib, library_path)

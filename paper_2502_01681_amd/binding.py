@@ -102,6 +102,10 @@ def lib():
         L.dg4_layer_workspace_bytes.argtypes = [ctypes.POINTER(_Cfg), _P]
         L.dg4_qkv_proj.restype = ctypes.c_int
         L.dg4_qkv_proj.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P, _I64, _P]
+        L.dg4_qkv_proj_static.restype = ctypes.c_int
+        L.dg4_qkv_proj_static.argtypes = [ctypes.POINTER(_Cfg), _P, _I64, _I64, _P, _P, _P, _P, _P]
+        L.dg4_static_scratch_bytes.restype = _I64
+        L.dg4_static_scratch_bytes.argtypes = []
         L.dg4_struct_encode.restype = ctypes.c_int
         L.dg4_struct_encode.argtypes = [ctypes.POINTER(_Cfg), _P, _P, _P, _P, _P]
         L.dg4_sparse_attn_fwd.restype = ctypes.c_int
@@ -257,6 +261,19 @@ def dg4_qkv_proj(cfg: LayerConfig, S, Wqkv, Q, K, V, row_begin=0, row_end=None, 
     rc = lib().dg4_qkv_proj(ctypes.byref(c), S.data_ptr(), row_begin, row_end, Wqkv.data_ptr(),
                             Q.data_ptr(), K.data_ptr(), V.data_ptr(), ws.data_ptr(), ws.numel(), _stream())
     _check(rc, "dg4_qkv_proj")
+
+
+def dg4_static_scratch_bytes() -> int:
+    return int(lib().dg4_static_scratch_bytes())
+
+
+def dg4_qkv_proj_static(cfg: LayerConfig, S, Wqkv, Q, K, V, row_begin=0, row_end=None):
+    """dg4_qkv_proj without a workspace: the library's own device array takes the packed weight."""
+    row_end = S.shape[0] if row_end is None else row_end
+    c = cfg.c()
+    rc = lib().dg4_qkv_proj_static(ctypes.byref(c), S.data_ptr(), row_begin, row_end, Wqkv.data_ptr(),
+                                   Q.data_ptr(), K.data_ptr(), V.data_ptr(), _stream())
+    _check(rc, "dg4_qkv_proj_static")
 
 
 def dg4_ffn_fwd(cfg: LayerConfig, S, W1, W2, Out, row_begin=0, row_end=None, workspace=None):

@@ -149,36 +149,52 @@ extern "C" int64_t dg4_layer_workspace_bytes(const dg4_layer_cfg* cfg, const dg4
     return (int64_t)plan_layer(cfg, g).total;
 }
 
-extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
-                            const void* Wqkv, void* Q, void* K, void* V,
-                            void* workspace, int64_t workspace_bytes, void* stream)
+// Argument checks of dg4_qkv_proj that do not concern the workspace (shared with dg4_qkv_proj_static).
+int dg4_qkv_proj_check(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                       const void* Wqkv, const void* Q, const void* K, const void* V)
 {
-    int rc = check_cfg(cfg, false);
+    const int rc = check_cfg(cfg, false);
     if (rc != DG4_OK) return rc;
     if (!S || !Wqkv || !Q || !K || !V || row_begin < 0 || row_end < row_begin) return DG4_EINVAL;
     if (!aligned16(S, Wqkv, Q, K, V)) return DG4_EINVAL;
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < dg4_proj_workspace_bytes(cfg)) return DG4_EWORKSPACE;
+    return DG4_OK;
+}
+
+// The launches of dg4_qkv_proj: `packed` (dg4_proj_workspace_bytes, 256-byte aligned) takes the weight
+// in matrix-core operand order. Allocates nothing.
+int dg4_qkv_proj_run(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                     const void* Wqkv, void* Q, void* K, void* V, void* packed, hipStream_t s)
+{
     if (row_end == row_begin) return DG4_OK;
-    hipStream_t s = (hipStream_t)stream;
     const int d = cfg->hidden;
     if (cfg->dtype == DG4_BF16 && d == 256) {
-        HIPCHK(dg4_launch_pack_w32(Wqkv, 3 * d, workspace, s));
+        HIPCHK(dg4_launch_pack_w32(Wqkv, 3 * d, packed, s));
         dg4_bulk_args b{};
         b.src = (const uint16_t*)S;
-        b.w_packed = workspace; b.n_cols = 3 * d;
+        b.w_packed = packed; b.n_cols = 3 * d;
         b.out[0] = (uint16_t*)Q; b.out[1] = (uint16_t*)K; b.out[2] = (uint16_t*)V; b.out_stride = d;
         b.row_begin = row_begin; b.row_end = row_end;
         HIPCHK(dg4_launch_bulk_proj(b, s));
         return DG4_OK;
     }
-    HIPCHK(dg4_launch_pack_w(cfg->dtype, Wqkv, 3 * d, 0, 3 * d, d, workspace, s));
+    HIPCHK(dg4_launch_pack_w(cfg->dtype, Wqkv, 3 * d, 0, 3 * d, d, packed, s));
     dg4_gemm_args a{};
     a.a = S; a.a_stride = d;
-    a.w_packed = workspace; a.n_cols = 3 * d;
+    a.w_packed = packed; a.n_cols = 3 * d;
     a.out[0] = Q; a.out[1] = K; a.out[2] = V; a.out_stride = d;
     a.row_begin = row_begin; a.row_end = row_end;
     HIPCHK(dg4_launch_gemm(cfg->dtype, d, a, s));
     return DG4_OK;
+}
+
+extern "C" int dg4_qkv_proj(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                            const void* Wqkv, void* Q, void* K, void* V,
+                            void* workspace, int64_t workspace_bytes, void* stream)
+{
+    const int rc = dg4_qkv_proj_check(cfg, S, row_begin, row_end, Wqkv, Q, K, V);
+    if (rc != DG4_OK) return rc;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < dg4_proj_workspace_bytes(cfg)) return DG4_EWORKSPACE;
+    return dg4_qkv_proj_run(cfg, S, row_begin, row_end, Wqkv, Q, K, V, workspace, (hipStream_t)stream);
 }
 
 extern "C" int dg4_ffn_fwd(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,

@@ -85,6 +85,14 @@ struct dg4_graph {
     int64_t n_pair_tiles = 0;
 };
 
+// dg4_qkv_proj in two parts (dg4_api.cpp): the argument checks that do not concern the workspace, and
+// the launches, which allocate nothing; shared with dg4_qkv_proj_static.
+#define DG4_STATIC_SCRATCH_BYTES (512 * 1024)
+int dg4_qkv_proj_check(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                       const void* Wqkv, const void* Q, const void* K, const void* V);
+int dg4_qkv_proj_run(const dg4_layer_cfg* cfg, const void* S, int64_t row_begin, int64_t row_end,
+                     const void* Wqkv, void* Q, void* K, void* V, void* packed, hipStream_t s);
+
 int dg4_graph_ensure_device(dg4_graph* g);
 int dg4_flow_schedule(dg4_graph* g);   // caller holds g->mu
 int dg4_pair_schedule(dg4_graph* g);   // caller holds g->mu
