@@ -42,10 +42,12 @@ typedef enum {
     DG4_EFANIN = -3,        /* in-degree above 2, or the same (src,dst) pair twice         */
     DG4_ECYCLE = -4,        /* the edge list is not a DAG (self loops included)            */
     DG4_EHINT = -5,         /* level_hint is not a topological levelling with PIs at 0     */
-    DG4_EUNSUPPORTED = -6,  /* head dim != 32, hidden not 128/256, hops not 1..8, layers>8 */
+    DG4_EUNSUPPORTED = -6,  /* head dim != 32, hidden not 128/256, hops not 1..8, layers>16 */
     DG4_ENOMEM = -7,        /* host or device allocation failed                            */
     DG4_EWORKSPACE = -8,    /* workspace missing, misaligned (256 B) or too small          */
-    DG4_EHIP = -9           /* a HIP runtime call failed                                   */
+    DG4_EHIP = -9,          /* a HIP runtime call failed                                   */
+    DG4_EABORTED = -10      /* dg4_layer_status: the last persistent sweep gave up on a    */
+                            /* dependency wait; Hout is incomplete                         */
 } dg4_status;
 
 /* cfg->flags */
@@ -66,15 +68,32 @@ typedef enum {
                             /* transformer structure around the attention):                  */
                             /* s <- LayerNorm(s + max(s W1, 0) W2).                          */
                             /* Not together with DG4_NO_EPILOGUE                             */
+#define DG4_LEVEL_ORDER 16u /* dg4_layer_fwd: a sweep over ALL levels follows the graph's own  */
+                            /* levels (the caller's level_hint, if one was given) instead of  */
+                            /* the library's dependency-driven order. Same results bit for    */
+                            /* bit; for comparisons of schedules                              */
+#define DG4_PROFILE     32u /* dg4_layer_fwd: the specialised persistent kernel accumulates    */
+                            /* per-phase timers, read back by dg4_layer_profile                */
+#define DG4_TIME_SWEEP  64u /* dg4_layer_fwd: bracket the persistent kernel with two events on  */
+                            /* the caller's stream, read back by dg4_sweep_elapsed_ms           */
+#define DG4_WEIGHTS_PACKED 128u /* dg4_layer_fwd: the caller vouches that W holds the same      */
+                            /* values as in its previous completed call with the same cfg       */
+                            /* (apart from this flag), graph, level range and workspace, and    */
+                            /* that nothing else wrote to the workspace since: the copies of    */
+                            /* the weights in matrix-core operand order that call left in the   */
+                            /* workspace are used again instead of being rebuilt                */
 
 typedef struct {
     int32_t hidden;         /* d: 128 or 256                                               */
     int32_t heads;          /* d / 32                                                      */
     int32_t hops;           /* k of cone_k, must equal the graph's                         */
-    int32_t n_layers;       /* 1..8 stacked layers (dg4_layer_fwd only)                    */
+    int32_t n_layers;       /* 1..16 stacked layers (dg4_layer_fwd only; the paper uses 12) */
     int32_t dtype;          /* dg4_dtype of X, H, Q, K, V, A and of the weight matrices    */
     uint32_t flags;
     float ln_eps;           /* LayerNorm epsilon, e.g. 1e-5                                */
+    uint32_t spin_limit;    /* persistent sweeps: polls of a "published" flag before a tile */
+                            /* gives up and the sweep aborts (dg4_layer_status); 0 = the     */
+                            /* default of 2^22 (seconds). Tests of the abort path use 1      */
 } dg4_layer_cfg;
 
 /*
@@ -278,24 +297,36 @@ int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begi
  *   s_{l+1} <- LayerNorm(s_{l+1} + max(s_{l+1} W1_l, 0) W2_l)   (as in dg4_ffn_fwd),
  * and W holds 5*n_layers pointers: Wqkv_l, Wo_l, rel_bias_l, W1_l [hidden,4*hidden],
  * W2_l [4*hidden,hidden].
- * The workspace contents are scratch; nothing persists between calls.
+ * The workspace contents are scratch; nothing a caller may rely on persists between calls, except
+ * under DG4_WEIGHTS_PACKED.
  * On a graph from dg4_build_partitioned the same sweep realises Algorithm 2 in general (the rows
  * of the graph are what each gate's first mini-batch shows of its cone).
  * The order in which a sweep over ALL levels visits the gates is the library's (dependency-driven
- * tiles in the persistent kernel, Eq. 1 levels in level-by-level launches) and does not change a
- * bit of the result; the environment variable DG4_SWEEP_LEVEL_ORDER=1 forces the graph's own levels
- * (for comparisons).
+ * tiles in the persistent kernels, Eq. 1 levels in level-by-level launches) and does not change a
+ * bit of the result; DG4_LEVEL_ORDER forces the graph's own levels (for comparisons).
+ * Persistent sweeps (everything but DG4_PER_LEVEL, DG4_BOUNDED_KV, rows wider than 16 entries and
+ * some combinations with DG4_FFN) hand tiles of gates to resident workgroups, which wait for the
+ * tiles their gates read from. Should such a wait exceed cfg->spin_limit polls (it cannot, unless
+ * the device is taken away from the kernel), the sweep stops, Hout is left incomplete, and the
+ * call has long returned DG4_OK: dg4_layer_status tells.
  */
 int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void* X, const void* const* W,
                   int32_t level_begin, int32_t level_end, void* Hout,
                   void* workspace, int64_t workspace_bytes, void* stream);
 
 /*
+ * Whether the last dg4_layer_fwd on `workspace` (same cfg and graph) ran to completion. Synchronous:
+ * the caller has synchronised the stream; four bytes are copied from the workspace. DG4_OK, or
+ * DG4_EABORTED if a persistent sweep gave up on a dependency wait (Hout is then incomplete).
+ */
+int dg4_layer_status(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace);
+
+/*
  * Tracing aid for the persistent sweep kernel of dg4_layer_fwd. Synchronous:
  * copies from `workspace` (as left by the last dg4_layer_fwd with the same cfg
  * and graph, after the caller synchronised the stream) the abort flag of the
  * kernel's bounded dependency wait (0 = the sweep ran to completion) and, if
- * the environment variable DG4_SWEEP_PROFILE was set during that call, eight
+ * DG4_PROFILE was set in that call's cfg->flags, eight
  * per-phase timers in 10 ns ticks summed over workgroups: tiles with a late source (a count), dependency
  * wait, attention, output projection, LayerNorm, K|V projection, publish, feed-forward sub-block.
  */
@@ -304,9 +335,9 @@ int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* 
 
 /*
  * Tracing aid: device time in milliseconds of the persistent sweep kernel of the most recent
- * dg4_layer_fwd that ran it while the environment variable DG4_SWEEP_EVENTS was set (two
- * events recorded on the caller's stream around that one kernel). Waits for the kernel.
- * EINVAL if no such call has been made.
+ * dg4_layer_fwd (of any thread) that ran one with DG4_TIME_SWEEP in cfg->flags (two events recorded
+ * on the caller's stream around that one kernel). Waits for the kernel. EINVAL if no such call
+ * has been made.
  */
 int dg4_sweep_elapsed_ms(float* ms);
 

@@ -18,6 +18,10 @@ DG4_NO_EPILOGUE = 1
 DG4_PER_LEVEL = 2
 DG4_BOUNDED_KV = 4
 DG4_FFN = 8
+DG4_LEVEL_ORDER = 16
+DG4_PROFILE = 32
+DG4_TIME_SWEEP = 64
+DG4_WEIGHTS_PACKED = 128
 ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.int64),
           "nbr_ptr": (3, np.int64), "nbr_idx": (4, np.int32), "nbr_rel": (5, np.uint8),
           "flow_order": (6, np.int32), "flow_tile_ptr": (7, np.int64),
@@ -26,7 +30,7 @@ ARRAYS = {"level": (0, np.int32), "order": (1, np.int32), "level_ptr": (2, np.in
           "cone_root": (12, np.int32), "cone_group_level": (13, np.int32), "cone_group_ptr": (14, np.int64),
           "stage": (15, np.int32), "copy_of": (16, np.int32), "last_copy": (17, np.int32)}
 STATUS = {0: "OK", -1: "EINVAL", -2: "ERANGE", -3: "EFANIN", -4: "ECYCLE", -5: "EHINT",
-          -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP"}
+          -6: "EUNSUPPORTED", -7: "ENOMEM", -8: "EWORKSPACE", -9: "EHIP", -10: "EABORTED"}
 
 
 class DG4Error(RuntimeError):
@@ -38,7 +42,8 @@ class DG4Error(RuntimeError):
 
 class _Cfg(ctypes.Structure):
     _fields_ = [("hidden", _I32), ("heads", _I32), ("hops", _I32), ("n_layers", _I32),
-                ("dtype", _I32), ("flags", ctypes.c_uint32), ("ln_eps", ctypes.c_float)]
+                ("dtype", _I32), ("flags", ctypes.c_uint32), ("ln_eps", ctypes.c_float),
+                ("spin_limit", ctypes.c_uint32)]
 
 
 @dataclass
@@ -53,12 +58,20 @@ class LayerConfig:
     per_level: bool = False      # launch level by level instead of the persistent sweep kernel
     bounded_kv: bool = False     # no K|V store: one level's frontier is projected when the level is processed
     ffn: bool = False            # every layer ends with the feed-forward sub-block (weights W1, W2 per layer)
+    level_order: bool = False    # whole-graph sweeps follow the graph's own levels, not the dependency-driven order
+    profile: bool = False        # phase timers of the specialised persistent kernel (dg4_layer_profile)
+    time_sweep: bool = False     # events around the persistent kernel (dg4_sweep_elapsed_ms)
+    weights_packed: bool = False # reuse the packed weights the previous call left in the workspace
+    spin_limit: int = 0          # polls before a persistent sweep gives up on a dependency (0: default)
 
     def c(self) -> _Cfg:
         return _Cfg(self.hidden, self.heads, self.hops, self.n_layers,
                     DG4_F32 if self.dtype == "f32" else DG4_BF16,
                     (0 if self.epilogue else DG4_NO_EPILOGUE) | (DG4_PER_LEVEL if self.per_level else 0) |
-                    (DG4_BOUNDED_KV if self.bounded_kv else 0) | (DG4_FFN if self.ffn else 0), self.ln_eps)
+                    (DG4_BOUNDED_KV if self.bounded_kv else 0) | (DG4_FFN if self.ffn else 0) |
+                    (DG4_LEVEL_ORDER if self.level_order else 0) | (DG4_PROFILE if self.profile else 0) |
+                    (DG4_TIME_SWEEP if self.time_sweep else 0) | (DG4_WEIGHTS_PACKED if self.weights_packed else 0),
+                    self.ln_eps, self.spin_limit)
 
 
 _lib = None
@@ -114,6 +127,8 @@ def lib():
         L.dg4_layer_fwd.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(_P), _I32, _I32, _P, _P, _I64, _P]
         L.dg4_sweep_elapsed_ms.restype = ctypes.c_int
         L.dg4_sweep_elapsed_ms.argtypes = [ctypes.POINTER(ctypes.c_float)]
+        L.dg4_layer_status.restype = ctypes.c_int
+        L.dg4_layer_status.argtypes = [ctypes.POINTER(_Cfg), _P, _P]
         L.dg4_layer_profile.restype = ctypes.c_int
         L.dg4_layer_profile.argtypes = [ctypes.POINTER(_Cfg), _P, _P, ctypes.POINTER(ctypes.c_uint64),
                                         ctypes.POINTER(ctypes.c_uint32)]
@@ -316,6 +331,15 @@ def dg4_layer_fwd(cfg: LayerConfig, g: Graph, X, weights, Hout, level_begin=0, l
     return ws
 
 
+def dg4_layer_status(cfg: LayerConfig, g: Graph, workspace, check=True) -> int:
+    """Status of the last dg4_layer_fwd on `workspace` (synchronise first): 0, or raises / returns EABORTED."""
+    c = cfg.c()
+    rc = int(lib().dg4_layer_status(ctypes.byref(c), g.handle, workspace.data_ptr()))
+    if check:
+        _check(rc, "dg4_layer_status")
+    return rc
+
+
 def dg4_layer_profile(cfg: LayerConfig, g: Graph, workspace):
     """(aborted, ticks[8]) left in `workspace` by the last persistent sweep (synchronise first)."""
     ticks = (ctypes.c_uint64 * 8)()
@@ -327,7 +351,7 @@ def dg4_layer_profile(cfg: LayerConfig, g: Graph, workspace):
 
 
 def dg4_sweep_elapsed_ms() -> float:
-    """Device time of the last persistent sweep kernel launched with DG4_SWEEP_EVENTS set."""
+    """Device time of the last persistent sweep kernel launched with cfg.time_sweep."""
     ms = ctypes.c_float()
     _check(lib().dg4_sweep_elapsed_ms(ctypes.byref(ms)), "dg4_sweep_elapsed_ms")
     return float(ms.value)

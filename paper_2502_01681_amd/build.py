@@ -10,7 +10,7 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdg4.so")
 OBJ = os.path.join(HERE, "_build")
-SOURCES = ["dg4_graph.cpp", "dg4_graph_gpu.hip", "dg4_api.cpp", "dg4_kernels.hip", "dg4_sweep.hip",
+SOURCES = ["dg4_graph.cpp", "dg4_graph_gpu.hip", "dg4_api.cpp", "dg4_kernels.hip", "dg4_sweep.hip", "dg4_flow.hip",
            "dg4_static.hip"]
 HEADERS = [os.path.join(CSRC, "dg4_internal.h"), os.path.join(CSRC, "dg4_device.h"), os.path.join(ROOT, "include", "dg4.h")]
 

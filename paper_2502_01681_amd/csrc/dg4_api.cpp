@@ -16,7 +16,8 @@ int check_cfg(const dg4_layer_cfg* c, bool need_layers)
 {
     if (!c) return DG4_EINVAL;
     if (c->dtype != DG4_F32 && c->dtype != DG4_BF16) return DG4_EINVAL;
-    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL | DG4_BOUNDED_KV | DG4_FFN)) return DG4_EINVAL;
+    if (c->flags & ~(uint32_t)(DG4_NO_EPILOGUE | DG4_PER_LEVEL | DG4_BOUNDED_KV | DG4_FFN | DG4_LEVEL_ORDER | DG4_PROFILE |
+                               DG4_TIME_SWEEP | DG4_WEIGHTS_PACKED)) return DG4_EINVAL;
     if ((c->flags & DG4_FFN) && (c->flags & DG4_NO_EPILOGUE)) return DG4_EINVAL;
     if (c->hidden != 128 && c->hidden != 256) return DG4_EUNSUPPORTED;
     if (c->heads <= 0 || c->heads * 32 != c->hidden) return DG4_EUNSUPPORTED;
@@ -42,8 +43,9 @@ struct LayerPlan {
     size_t wo_t, wkv_t;  // persistent sweep: weights in its A-operand order (layer 0)
     size_t ffn_t;        // persistent sweep: W1 | W2 in its streaming order (DG4_FFN)
     size_t park;         // persistent sweep: rows parked between the two tiles of a pair (DG4_FFN)
+    size_t bias_all;     // [n_layers][heads, 4] float: the relation biases of every layer, contiguous
     size_t flags;        // [n] uint32 "rows published"
-    size_t ctrl;         // abort flag, phase timers
+    size_t ctrl;         // abort word, ticket counter, phase timers
     size_t total;
     int64_t max_rows;
 };
@@ -79,21 +81,19 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     p.wkv_t = take(d * 2 * d * es);
     p.ffn_t = take(ffn ? 2 * d * 4 * d * es : 0);
     p.park = take(ffn ? (size_t)DG4_MAX_SWEEP_GROUPS * DG4_TILE_ROWS * d * es : 0);
+    p.bias_all = take(L * (size_t)c->heads * 4 * sizeof(float));
     p.flags = take(n * sizeof(uint32_t));
     p.ctrl = take(256);
     p.total = off;
     return p;
 }
 
-// Tunables of the persistent sweep, overridable from the environment for experiments.
-uint32_t dg4_sweep_spin_limit()
-{
-    const char* e = getenv("DG4_SWEEP_SPIN_LIMIT");
-    return e ? (uint32_t)strtoul(e, nullptr, 10) : (1u << 22);
-}
-// Optional timing of the persistent sweep kernel alone (tracing aid): two events on the
-// caller's stream around its launch, read back by dg4_sweep_elapsed_ms.
-struct SweepEvents { hipEvent_t a = nullptr, b = nullptr; bool armed = false; };
+// polls of a flag before a persistent sweep gives up (cfg->spin_limit = 0: this default)
+constexpr uint32_t DEFAULT_SPIN_LIMIT = 1u << 22;
+// Optional timing of the persistent sweep kernel alone (DG4_TIME_SWEEP, a tracing aid): two events on
+// the caller's stream around its launch, read back by dg4_sweep_elapsed_ms. One pair per process,
+// guarded by a mutex; the figure is that of the most recent such call, whichever thread made it.
+struct SweepEvents { std::mutex mu; hipEvent_t a = nullptr, b = nullptr; bool armed = false; };
 SweepEvents& sweep_events() { static SweepEvents e; return e; }
 
 #define HIPCHK(expr) do { if ((expr) != (int)hipSuccess) return DG4_EHIP; } while (0)
@@ -116,6 +116,7 @@ extern "C" const char* dg4_strerror(int status)
     case DG4_ENOMEM: return "out of memory";
     case DG4_EWORKSPACE: return "workspace missing, misaligned or too small";
     case DG4_EHIP: return "HIP runtime error";
+    case DG4_EABORTED: return "persistent sweep gave up on a dependency wait";
     default: return "unknown status";
     }
 }
@@ -308,14 +309,33 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // base pointer of a per-level buffer such that row p (a position) lands at local row p - p0
     auto local = [&](size_t off, int64_t p0, int64_t stride) { return (void*)(ws + off - p0 * stride * es); };
 
-    for (int l = 0; l < L; ++l) {
-        HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
-        HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 1], d, 0, d, d, at(pl.wo[l]), s));
-        // K | V columns of layer l go to column tiles [l*2d/32, (l+1)*2d/32) of wkv_all
-        HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
-        if (ffn) {
-            HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 3], 4 * d, 0, 4 * d, d, at(pl.w1[l]), s));
-            HIPCHK(dg4_launch_pack_w2(dt, W[WS * l + 4], d, at(pl.w2[l]), s));
+    // Which path: the kernel specialised for bf16 / hidden 256 / one layer / cones of two hops (weights
+    // resident in registers), the persistent dataflow kernel for the other shapes and any number of
+    // layers, or level-by-level launches (DG4_PER_LEVEL, DG4_BOUNDED_KV, the feed-forward sub-block
+    // outside the specialised shape, neighbour rows wider than 16 entries, partial sweeps with the
+    // feed-forward sub-block).
+    const bool whole_range = level_begin == 0 && level_end == (int32_t)g->max_level + 1;
+    const bool forced_levels = (cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) != 0;
+    const bool resident = dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops <= 2 && !forced_levels && (!ffn || whole_range);
+    const bool flow = !resident && !forced_levels && !ffn && dg4_flow_supports(dt, d, g->ell_w);
+    // a caller that has not changed the weights since its last call with this configuration, graph
+    // and workspace vouches for the packed copies that call left behind
+    const bool pack = !(cfg->flags & DG4_WEIGHTS_PACKED);
+    const uint32_t spin_limit = cfg->spin_limit ? cfg->spin_limit : DEFAULT_SPIN_LIMIT;
+
+    if (pack) {
+        for (int l = 0; l < L; ++l) {
+            if (!resident) {
+                if (l > 0 || !flow || dt != DG4_BF16) HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
+                HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 1], d, 0, d, d, at(pl.wo[l]), s));
+            }
+            // K | V columns of layer l go to column tiles [l*2d/32, (l+1)*2d/32) of wkv_all
+            if (!resident || level_begin > 0)
+                HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
+            if (ffn && !resident) {
+                HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 3], 4 * d, 0, 4 * d, d, at(pl.w1[l]), s));
+                HIPCHK(dg4_launch_pack_w2(dt, W[WS * l + 4], d, at(pl.w2[l]), s));
+            }
         }
     }
     const int64_t P0 = g->level_ptr[level_begin], P1 = g->level_ptr[level_end];
@@ -336,21 +356,35 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // K/V of gates finished before this call (resume): from the caller's H
     if (P0 > 0 && !bounded) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
+    // optional timing of the persistent kernel alone
+    const bool timed = (cfg->flags & DG4_TIME_SWEEP) != 0 && (resident || flow);
+    auto bracket = [&](auto&& launch) -> int {
+        if (!timed) return launch();
+        SweepEvents& ev = sweep_events();
+        std::lock_guard<std::mutex> lock(ev.mu);
+        if (!ev.a && (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess)) return (int)hipErrorUnknown;
+        if (hipEventRecord(ev.a, s) != hipSuccess) return (int)hipErrorUnknown;
+        const int rc2 = launch();
+        if (rc2 != (int)hipSuccess) return rc2;
+        if (hipEventRecord(ev.b, s) != hipSuccess) return (int)hipErrorUnknown;
+        ev.armed = true;
+        return (int)hipSuccess;
+    };
+
     // One persistent dataflow kernel for the whole range of levels (with the feed-forward sub-block:
     // whole-graph sweeps only, partial ones run level by level)
-    const bool whole_range = level_begin == 0 && level_end == (int32_t)g->max_level + 1;
-    if (dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops <= 2 && !(cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) &&
-        (!ffn || whole_range)) {
+    if (resident) {
         // A sweep over all levels runs in the dependency-driven tile order, a partial one (resume)
-        // level by level; rows of the internal buffers are positions in the order in use.
-        const bool whole = whole_range && (ffn || !getenv("DG4_SWEEP_LEVEL_ORDER"));
+        // or one with DG4_LEVEL_ORDER level by level; rows of the internal buffers are positions in
+        // the order in use.
+        const bool whole = whole_range && (ffn || !(cfg->flags & DG4_LEVEL_ORDER));
         if (ffn) {
             rc = dg4_graph_ensure_pairs(g);
             if (rc != DG4_OK) return rc;
         }
         const int32_t* order_in_use = ffn ? g->d_pair_order : whole ? g->d_flow_order : g->d_order;
         {   // Q | K | V of x for every gate of the swept levels, rows in processing order
-            HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, at(pl.wqkv[0]), s));
+            if (pack) HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, at(pl.wqkv[0]), s));
             dg4_bulk_args b{};
             b.src = (const uint16_t*)X; b.gather = order_in_use;
             b.w_packed = at(pl.wqkv[0]); b.n_cols = 3 * d;
@@ -359,8 +393,10 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             b.row_begin = P0; b.row_end = P1;
             HIPCHK(dg4_launch_bulk_proj(b, s));
         }
-        HIPCHK(dg4_launch_pack_wt(W[1], d, 0, 4, 4, at(pl.wo_t), s));
-        HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, d, 8, 4, at(pl.wkv_t), s));
+        if (pack) {
+            HIPCHK(dg4_launch_pack_wt(W[1], d, 0, 4, 4, at(pl.wo_t), s));
+            HIPCHK(dg4_launch_pack_wt(W[0], 3 * d, d, 8, 4, at(pl.wkv_t), s));
+        }
         dg4_sweep_args a{};
         a.tiles = ffn ? g->d_pair_tiles : whole ? g->d_flow_tiles : g->d_tiles;
         a.tile_begin = whole ? 0 : g->level_tile_ptr[level_begin];
@@ -374,31 +410,83 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.wo_packed = at(pl.wo_t); a.wkv_packed = at(pl.wkv_t);
         a.rel_bias = (const float*)W[2];
         if (ffn) {
-            HIPCHK(dg4_launch_pack_ffn(W[3], W[4], at(pl.ffn_t), s));
+            if (pack) HIPCHK(dg4_launch_pack_ffn(W[3], W[4], at(pl.ffn_t), s));
             a.ffn_packed = at(pl.ffn_t);
             a.park = (uint16_t*)at(pl.park);
         }
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
         a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.eager_publish = whole ? 0 : 1;
-        a.spin_limit = dg4_sweep_spin_limit();
-        a.prof = getenv("DG4_SWEEP_PROFILE") ? (uint64_t*)((char*)at(pl.ctrl) + 64) : nullptr;
-        SweepEvents& ev = sweep_events();
-        const bool timed = getenv("DG4_SWEEP_EVENTS") != nullptr;
-        if (timed && !ev.a) {
-            if (hipEventCreate(&ev.a) != hipSuccess || hipEventCreate(&ev.b) != hipSuccess) return DG4_EHIP;
-        }
-        HIPCHK(dg4_launch_sweep_init(a, g->n, P0, s));
-        if (timed) HIPCHK(hipEventRecord(ev.a, s));
-        HIPCHK(dg4_launch_sweep(a, s));
-        if (timed) { HIPCHK(hipEventRecord(ev.b, s)); ev.armed = true; }
+        a.spin_limit = spin_limit;
+        a.prof = (cfg->flags & DG4_PROFILE) ? (uint64_t*)((char*)at(pl.ctrl) + 64) : nullptr;
+        HIPCHK(dg4_launch_sweep_init(a.flags, a.ctrl, g->n, P0, s));
+        HIPCHK(bracket([&]() { return dg4_launch_sweep(a, s); }));
         return DG4_OK;
     }
+
+    if (flow) {
+        // tiles of up to 32 mutually independent gates: the pairs of the dependency-driven order for a
+        // sweep over all levels, runs inside a level otherwise
+        const bool whole = whole_range && !(cfg->flags & DG4_LEVEL_ORDER);
+        if (whole) {
+            rc = dg4_graph_ensure_pairs(g);
+            if (rc != DG4_OK) return rc;
+        }
+        const int32_t* order_in_use = whole ? g->d_pair_order : g->d_order;
+        if (dt == DG4_BF16) {       // (hidden 256: the bulk projection kernel and its weight order)
+            if (pack) HIPCHK(dg4_launch_pack_w32(W[0], 3 * d, at(pl.wqkv[0]), s));
+            dg4_bulk_args b{};
+            b.src = (const uint16_t*)X; b.gather = order_in_use;
+            b.w_packed = at(pl.wqkv[0]); b.n_cols = 3 * d;
+            uint16_t* base = (uint16_t*)at(pl.qkv_self);
+            b.out[0] = base; b.out[1] = base + d; b.out[2] = base + 2 * d; b.out_stride = 3 * d;
+            b.row_begin = P0; b.row_end = P1;
+            HIPCHK(dg4_launch_bulk_proj(b, s));
+        } else {
+            dg4_gemm_args a{};
+            a.a = X; a.a_stride = d; a.a_gather = order_in_use;
+            a.w_packed = at(pl.wqkv[0]); a.n_cols = 3 * d;
+            char* base = ws + pl.qkv_self;
+            a.out[0] = base; a.out[1] = base + (size_t)d * es; a.out[2] = base + (size_t)2 * d * es;
+            a.out_stride = 3 * d;
+            a.row_begin = P0; a.row_end = P1;
+            HIPCHK(dg4_launch_gemm(dt, d, a, s));
+        }
+        if (pack)
+            for (int l = 0; l < L; ++l)
+                if (hipMemcpyAsync(ws + pl.bias_all + (size_t)l * cfg->heads * 4 * sizeof(float), W[WS * l + 2],
+                                   (size_t)cfg->heads * 4 * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess) return DG4_EHIP;
+        dg4_flow_args a{};
+        if (whole) {
+            a.tiles = g->d_pair_tiles; a.pairs = 1; a.tile_begin = 0; a.n_tiles = g->n_pair_tiles / 2;
+            a.ell = g->d_pair_ell;
+        } else {
+            a.tiles = g->d_tiles32; a.pairs = 0; a.tile_begin = g->level_tile32_ptr[level_begin];
+            a.n_tiles = g->level_tile32_ptr[level_end] - a.tile_begin;
+            a.ell = g->d_ell_pos;
+        }
+        a.ell_w = g->ell_w;
+        a.order = order_in_use;
+        a.x = X; a.qkv_self = at(pl.qkv_self);
+        a.kv = at(pl.kv); a.kv_layer_stride = (int64_t)pl.kv_rows * 2 * d;
+        a.h_out = Hout;
+        a.wqkv_packed = at(pl.wqkv[0]); a.wo_packed = at(pl.wo[0]);
+        a.w_layer_stride = L > 1 ? (int64_t)(pl.wqkv[1] - pl.wqkv[0]) : 0;
+        a.wkv_packed = at(pl.wkv_all);
+        a.rel_bias = (const float*)at(pl.bias_all);
+        a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
+        a.n_layers = L; a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.project_kv = 1;
+        a.spin_limit = spin_limit;
+        HIPCHK(dg4_launch_sweep_init(a.flags, a.ctrl, g->n, P0, s));
+        HIPCHK(bracket([&]() { return dg4_launch_flow(dt, d, a, s); }));
+        return DG4_OK;
+    }
+    HIPCHK(dg4_launch_sweep_init((uint32_t*)at(pl.flags), (uint32_t*)at(pl.ctrl), 0, 0, s));   // the status words only
 
     // A sweep over ALL levels of a graph whose levelling (a caller's hint) is deeper than Eq. 1 goes
     // through the Eq. 1 levels instead: as many rounds of launches as the circuit is deep. Same
     // embeddings (every source of a gate lies on a lower Eq. 1 level too); rows of the internal
-    // buffers are then positions in that order. DG4_SWEEP_LEVEL_ORDER=1 keeps the caller's levels.
-    const bool compact = whole_range && !bounded && !g->eq1_level_ptr.empty() && !getenv("DG4_SWEEP_LEVEL_ORDER");
+    // buffers are then positions in that order. DG4_LEVEL_ORDER keeps the caller's levels.
+    const bool compact = whole_range && !bounded && !g->eq1_level_ptr.empty() && !(cfg->flags & DG4_LEVEL_ORDER);
     if (compact) {
         rc = dg4_graph_ensure_eq1(g);
         if (rc != DG4_OK) return rc;
@@ -520,6 +608,17 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     return DG4_OK;
 }
 
+extern "C" int dg4_layer_status(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace)
+{
+    const int rc = check_cfg(cfg, true);
+    if (rc != DG4_OK) return rc;
+    if (!g || !workspace) return DG4_EINVAL;
+    const LayerPlan pl = plan_layer(cfg, g);
+    uint32_t ctrl[4];
+    if (hipMemcpy(ctrl, (const char*)workspace + pl.ctrl, sizeof(ctrl), hipMemcpyDeviceToHost) != hipSuccess) return DG4_EHIP;
+    return ctrl[1] ? DG4_EABORTED : DG4_OK;
+}
+
 extern "C" int dg4_layer_profile(const dg4_layer_cfg* cfg, const dg4_graph* g, const void* workspace,
                                  uint64_t* ticks8, uint32_t* aborted)
 {
@@ -538,6 +637,7 @@ extern "C" int dg4_sweep_elapsed_ms(float* ms)
 {
     SweepEvents& ev = sweep_events();
     if (!ms) return DG4_EINVAL;
+    std::lock_guard<std::mutex> lock(ev.mu);
     if (!ev.armed) return DG4_EINVAL;
     if (hipEventSynchronize(ev.b) != hipSuccess) return DG4_EHIP;
     if (hipEventElapsedTime(ms, ev.a, ev.b) != hipSuccess) return DG4_EHIP;

@@ -789,6 +789,14 @@ int dg4_graph_ensure_device(dg4_graph* g)
                 tiles.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(DG4_TILE_ROWS, g->level_ptr[l + 1] - p0)));
         }
         g->level_tile_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
+        std::vector<uint2> tiles32;
+        g->level_tile32_ptr.assign((size_t)g->max_level + 2, 0);
+        for (int32_t l = 0; l <= g->max_level; ++l) {
+            g->level_tile32_ptr[l] = (int64_t)tiles32.size();
+            for (int64_t p0 = g->level_ptr[l]; p0 < g->level_ptr[l + 1]; p0 += 32)
+                tiles32.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(32, g->level_ptr[l + 1] - p0)));
+        }
+        g->level_tile32_ptr[(size_t)g->max_level + 1] = (int64_t)tiles32.size();
         // Dataflow order for whole-graph sweeps (dg4_flow_schedule)
         std::vector<int32_t> flow;
         std::vector<uint2> flow_tiles;
@@ -822,7 +830,8 @@ int dg4_graph_ensure_device(dg4_graph* g)
             if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
             if (g->d_order) (void)hipFree(g->d_order);
             if (g->d_tiles) (void)hipFree(g->d_tiles);
-            g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr;
+            if (g->d_tiles32) (void)hipFree(g->d_tiles32);
+            g->d_ell_id = g->d_ell_pos = nullptr; g->d_order = nullptr; g->d_tiles = nullptr; g->d_tiles32 = nullptr;
             return rc;
         };
         if (hipMalloc((void**)&g->d_ell_id, bytes) != hipSuccess) return fail(DG4_ENOMEM);
@@ -831,6 +840,10 @@ int dg4_graph_ensure_device(dg4_graph* g)
         if (hipMalloc((void**)&g->d_tiles, std::max<size_t>(tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
         if (!tiles.empty() &&
             hipMemcpy(g->d_tiles, tiles.data(), tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess)
+            return fail(DG4_EHIP);
+        if (hipMalloc((void**)&g->d_tiles32, std::max<size_t>(tiles32.size(), 1) * sizeof(uint2)) != hipSuccess) return fail(DG4_ENOMEM);
+        if (!tiles32.empty() &&
+            hipMemcpy(g->d_tiles32, tiles32.data(), tiles32.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess)
             return fail(DG4_EHIP);
         if (hipMemcpy(g->d_ell_id, by_id.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
         if (hipMemcpy(g->d_ell_pos, by_pos.data(), bytes, hipMemcpyHostToDevice) != hipSuccess) return fail(DG4_EHIP);
@@ -986,6 +999,7 @@ extern "C" void dg4_graph_free(dg4_graph* g)
     if (g->d_ell_pos) (void)hipFree(g->d_ell_pos);
     if (g->d_order) (void)hipFree(g->d_order);
     if (g->d_tiles) (void)hipFree(g->d_tiles);
+    if (g->d_tiles32) (void)hipFree(g->d_tiles32);
     if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
     if (g->d_flow_order) (void)hipFree(g->d_flow_order);
     if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);

@@ -15,7 +15,7 @@
 // (relation code << 30 | index), padded with DG4_ELL_PAD. Width = 2^(hops+1), at least 8:
 // one more than the largest cone (Section 3.2), so a row always ends in a pad.
 #define DG4_ELL_PAD 0xFFFFFFFFu
-#define DG4_MAX_LAYERS 8
+#define DG4_MAX_LAYERS 16        // the paper stacks 12 (Section 4.1)
 #define DG4_TILE_ROWS 16          // gates per tile of the persistent sweep
 #define DG4_MAX_SWEEP_GROUPS 1024 // most workgroups the persistent sweep is launched with (one per compute unit)
 
@@ -57,6 +57,9 @@ struct dg4_graph {
     // tiles of the persistent sweep: runs of <= DG4_TILE_ROWS positions inside one level
     std::vector<int64_t> level_tile_ptr;   // [n_levels + 1] first tile of each level
     uint2* d_tiles = nullptr;        // [n_tiles] (first position, rows)
+    // the same with runs of <= 32 positions (the persistent kernel for every shape)
+    std::vector<int64_t> level_tile32_ptr;
+    uint2* d_tiles32 = nullptr;
     // A second processing order for sweeps over ALL levels: tiles filled by list scheduling over
     // the real dependencies (a gate goes as early as its sources allow, sources long finished
     // first), not level by level. Host copy (node ids in processing order, first position of
@@ -186,8 +189,31 @@ struct dg4_sweep_args {
 };
 int dg4_launch_pack_wt(const void* w, int ld, int col0, int ntw, int waves, void* packed, hipStream_t s);
 int dg4_launch_pack_ffn(const void* w1, const void* w2, void* packed, hipStream_t s);   // [256,1024], [1024,256] bf16
-int dg4_launch_sweep_init(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, hipStream_t s);
+// flags[i] = i < done_below for i < n_flags; the control words (abort, ticket counter, timers) = 0
+int dg4_launch_sweep_init(uint32_t* flags, uint32_t* ctrl, int64_t n_flags, int64_t done_below, hipStream_t s);
 int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s);
+
+// ---- persistent dataflow sweep for every shape and any number of layers (dg4_flow.hip) ----
+struct dg4_flow_args {
+    const uint2* tiles; int64_t tile_begin; int64_t n_tiles;   // tile t is tiles[tile_begin + t] = (first position, rows <= 32) ...
+    int pairs;                             // ... or (pairs != 0) entries 2t and 2t+1 of the table together
+    const uint32_t* ell; int ell_w;        // neighbour rows by position
+    const int32_t* order;                  // position -> node id
+    const void* x;                         // [n, d] by node id
+    const void* qkv_self;                  // [n, 3d] by position: Q | K | V of x (layer 0)
+    void* kv; int64_t kv_layer_stride;     // [layers][n, 2d] by position: K | V of the final embeddings; elements between layers
+    void* h_out;                           // [n, d] by node id
+    const void* wqkv_packed; const void* wo_packed; int64_t w_layer_stride;   // dg4_launch_pack_w order; bytes from a layer's to the next's
+    const void* wkv_packed;                // [d, layers*2d] packed: K | V columns of every layer
+    const float* rel_bias;                 // [layers][heads, 4]
+    uint32_t* flags;                       // [n] by position: 1 = rows published
+    uint32_t* ctrl;                        // [1] abort word, [2] ticket counter
+    int n_layers;
+    float ln_eps; int epilogue; int project_kv;
+    uint32_t spin_limit;
+};
+bool dg4_flow_supports(int dtype, int hidden, int ell_w);
+int dg4_launch_flow(int dtype, int hidden, const dg4_flow_args& a, hipStream_t s);
 
 // ---- bulk projection on the matrix cores (dg4_sweep.hip): bf16, hidden 256 ----
 struct dg4_bulk_args {

@@ -17,110 +17,11 @@
 
 #include "dg4_device.h"
 #include "dg4_internal.h"
+#include "dg4_rowops.h"
 
 namespace {
 
 // ------------------------------------------------------------------ attention
-
-// The attention of one destination row, by a group of LPR = D / EPL lanes of which this lane is
-// number `sub`: every lane owns 32 contiguous bytes of each 512-byte (or 256 / 1024-byte) row it
-// touches and ends with its EPL elements of the row's result.
-template <typename T, int D, int W>
-__device__ __forceinline__ void attend_row(const dg4_attn_args& p, int64_t row, int sub, float (&acc)[Elem<T>::EPL])
-{
-    constexpr int EPL = Elem<T>::EPL;
-    constexpr int CH = W < 8 ? W : 8;         // neighbour rows in flight per pass
-    const int64_t eoff = (int64_t)sub * EPL;  // element offset of this lane inside a row
-    const int head = (int)(eoff >> 5);
-
-    uint32_t ent[W];
-    {
-        const uint4* e4 = (const uint4*)(p.ell + row * W);
-#pragma unroll
-        for (int i = 0; i < W / 4; ++i) {
-            const uint4 t = e4[i];
-            ent[4 * i] = t.x; ent[4 * i + 1] = t.y; ent[4 * i + 2] = t.z; ent[4 * i + 3] = t.w;
-        }
-    }
-    float q[EPL];
-    {
-        const uint4* qp = (const uint4*)((const T*)p.q + row * p.q_stride + eoff);
-        Elem<T>::unpack(qp[0], qp[1], q);
-    }
-    float bias[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) bias[i] = p.rel_bias[head * 4 + i];
-
-    auto src_row = [&](const void* self_base, const void* src_base, uint32_t e) -> const uint4* {
-        const uint32_t rel = e >> 30;
-        const int64_t idx = e & 0x3FFFFFFFu;
-        const T* r = rel == 0 ? (const T*)self_base + row * p.self_stride
-                              : (const T*)src_base + idx * p.src_stride;
-        return (const uint4*)(r + eoff);
-    };
-
-    // pass 1: scores
-    float s[W];
-    const float scale = 0.17677669529663687f;     // 1/sqrt(32)
-#pragma unroll
-    for (int c0 = 0; c0 < W; c0 += CH) {
-        uint4 ka[CH], kb[CH];
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            if (ent[c0 + j] != DG4_ELL_PAD) {
-                const uint4* kp = src_row(p.k_self, p.k_src, ent[c0 + j]);
-                ka[j] = kp[0]; kb[j] = kp[1];
-            } else {
-                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            float k[EPL];
-            Elem<T>::unpack(ka[j], kb[j], k);
-            float dot = 0.f;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
-            dot = Elem<T>::head_sum(dot);
-            const uint32_t rel = ent[c0 + j] >> 30;
-            const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
-            s[c0 + j] = ent[c0 + j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
-        }
-    }
-    // softmax over the row, in this lane (all lanes of a head hold the same s)
-    float mx = s[0];
-#pragma unroll
-    for (int j = 1; j < W; ++j) mx = fmaxf(mx, s[j]);
-    float z = 0.f;
-#pragma unroll
-    for (int j = 0; j < W; ++j) { s[j] = __expf(s[j] - mx); z += s[j]; }
-    const float rz = 1.0f / z;
-
-    // pass 2: aggregation
-#pragma unroll
-    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
-#pragma unroll
-    for (int c0 = 0; c0 < W; c0 += CH) {
-        uint4 va[CH], vb[CH];
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            if (ent[c0 + j] != DG4_ELL_PAD) {
-                const uint4* vp = src_row(p.v_self, p.v_src, ent[c0 + j]);
-                va[j] = vp[0]; vb[j] = vp[1];
-            } else {
-                va[j] = make_uint4(0, 0, 0, 0); vb[j] = va[j];
-            }
-        }
-#pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            float v[EPL];
-            Elem<T>::unpack(va[j], vb[j], v);
-            const float al = s[c0 + j] * rz;
-#pragma unroll
-            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(al, v[i], acc[i]);
-        }
-    }
-}
 
 // One destination row per group of LPR lanes.
 template <typename T, int D, int W>
@@ -325,30 +226,6 @@ __global__ void pack_w_kernel(const T* w, int ld, int col0, int n_cols, int k_di
 }
 
 // ----------------------------------------------------------------------- GEMM
-
-template <typename T> struct Mma;
-template <> struct Mma<bf16_t> {
-    __device__ static void run(const uint4& a, const uint4& b, f32x16& c)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    }
-};
-template <> struct Mma<float> {
-    __device__ static void run(const uint4& a, const uint4& b, f32x16& c)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
-    }
-};
-
-__device__ __forceinline__ float sum_over_32_lanes(float v)
-{
-    v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4);
-    v += __shfl_xor(v, 8); v += __shfl_xor(v, 16);
-    return v;
-}
 
 // One wave = 32 rows x all output columns. The wave keeps its 32 x D slice of
 // the A operand in registers and streams the packed weight tiles.

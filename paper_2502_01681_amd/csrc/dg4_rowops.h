@@ -1,0 +1,158 @@
+// Per-row device functions shared by the level-by-level kernels and the persistent dataflow kernel:
+// the attention of one destination row, the matrix-core product step, a row sum. One definition, so
+// that a gate's arithmetic is the same whichever kernel computes it.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "dg4_device.h"
+#include "dg4_internal.h"
+
+namespace {
+
+// The attention of one destination row (Section 3.5), by a group of LPR = D / EPL lanes of which this
+// lane is number `sub`: every lane owns 32 contiguous bytes of each 512-byte (or 256 / 1024-byte) row
+// it touches and ends with its EPL elements of the row's result. `ent`: the packed neighbour row;
+// q_row, k_self, v_self: the destination's own rows (any address space); sources at k_src / v_src +
+// index * src_stride elements; rel_bias [heads, 4].
+template <typename T, int D, int W>
+__device__ __forceinline__ void attend_core(const uint32_t (&ent)[W], const T* q_row, const T* k_self, const T* v_self,
+                                            const T* k_src, const T* v_src, int64_t src_stride, const float* rel_bias,
+                                            int sub, float (&acc)[Elem<T>::EPL])
+{
+    constexpr int EPL = Elem<T>::EPL;
+    constexpr int CH = W < 8 ? W : 8;         // neighbour rows in flight per pass
+    const int64_t eoff = (int64_t)sub * EPL;  // element offset of this lane inside a row
+    const int head = (int)(eoff >> 5);
+
+    float q[EPL];
+    {
+        const uint4* qp = (const uint4*)(q_row + eoff);
+        Elem<T>::unpack(qp[0], qp[1], q);
+    }
+    float bias[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) bias[i] = rel_bias[head * 4 + i];
+
+    auto src_row = [&](const T* self_row, const T* src_base, uint32_t e) -> const uint4* {
+        const uint32_t rel = e >> 30;
+        const int64_t idx = e & 0x3FFFFFFFu;
+        const T* r = rel == 0 ? self_row : src_base + idx * src_stride;
+        return (const uint4*)(r + eoff);
+    };
+
+    // pass 1: scores
+    float s[W];
+    const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+#pragma unroll
+    for (int c0 = 0; c0 < W; c0 += CH) {
+        uint4 ka[CH], kb[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (ent[c0 + j] != DG4_ELL_PAD) {
+                const uint4* kp = src_row(k_self, k_src, ent[c0 + j]);
+                ka[j] = kp[0]; kb[j] = kp[1];
+            } else {
+                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            float k[EPL];
+            Elem<T>::unpack(ka[j], kb[j], k);
+            float dot = 0.f;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
+            dot = Elem<T>::head_sum(dot);
+            const uint32_t rel = ent[c0 + j] >> 30;
+            const float b = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+            s[c0 + j] = ent[c0 + j] != DG4_ELL_PAD ? fmaf(dot, scale, b) : -INFINITY;
+        }
+    }
+    // softmax over the row, in this lane (all lanes of a head hold the same s)
+    float mx = s[0];
+#pragma unroll
+    for (int j = 1; j < W; ++j) mx = fmaxf(mx, s[j]);
+    float z = 0.f;
+#pragma unroll
+    for (int j = 0; j < W; ++j) { s[j] = __expf(s[j] - mx); z += s[j]; }
+    const float rz = 1.0f / z;
+
+    // pass 2: aggregation
+#pragma unroll
+    for (int i = 0; i < EPL; ++i) acc[i] = 0.f;
+#pragma unroll
+    for (int c0 = 0; c0 < W; c0 += CH) {
+        uint4 va[CH], vb[CH];
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            if (ent[c0 + j] != DG4_ELL_PAD) {
+                const uint4* vp = src_row(v_self, v_src, ent[c0 + j]);
+                va[j] = vp[0]; vb[j] = vp[1];
+            } else {
+                va[j] = make_uint4(0, 0, 0, 0); vb[j] = va[j];
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            float v[EPL];
+            Elem<T>::unpack(va[j], vb[j], v);
+            const float al = s[c0 + j] * rz;
+#pragma unroll
+            for (int i = 0; i < EPL; ++i) acc[i] = fmaf(al, v[i], acc[i]);
+        }
+    }
+}
+
+// the packed neighbour row `row` of a table of width W
+template <int W>
+__device__ __forceinline__ void load_entries(const uint32_t* ell, int64_t row, uint32_t (&ent)[W])
+{
+    const uint4* e4 = (const uint4*)(ell + row * W);
+#pragma unroll
+    for (int i = 0; i < W / 4; ++i) {
+        const uint4 t = e4[i];
+        ent[4 * i] = t.x; ent[4 * i + 1] = t.y; ent[4 * i + 2] = t.z; ent[4 * i + 3] = t.w;
+    }
+}
+
+// attend_core on the tensors of a launch: destination row `row` of p
+template <typename T, int D, int W>
+__device__ __forceinline__ void attend_row(const dg4_attn_args& p, int64_t row, int sub, float (&acc)[Elem<T>::EPL])
+{
+    uint32_t ent[W];
+    load_entries<W>(p.ell, row, ent);
+    attend_core<T, D, W>(ent, (const T*)p.q + row * p.q_stride, (const T*)p.k_self + row * p.self_stride,
+                         (const T*)p.v_self + row * p.self_stride, (const T*)p.k_src, (const T*)p.v_src, p.src_stride,
+                         p.rel_bias, sub, acc);
+}
+
+// One step of a 32-row product on the matrix cores: 16 bytes of A (rows) and of B (packed weight)
+// per lane; accumulator element i of lane (m = lane % 32, kg = lane / 32) is row 8*(i/4) + 4*kg + i%4,
+// column m of the 32x32 tile.
+template <typename T> struct Mma;
+template <> struct Mma<bf16_t> {
+    __device__ static void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+    }
+};
+template <> struct Mma<float> {
+    __device__ static void run(const uint4& a, const uint4& b, f32x16& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), c, 0, 0, 0);
+    }
+};
+
+__device__ __forceinline__ float sum_over_32_lanes(float v)
+{
+    v += __shfl_xor(v, 1); v += __shfl_xor(v, 2); v += __shfl_xor(v, 4);
+    v += __shfl_xor(v, 8); v += __shfl_xor(v, 16);
+    return v;
+}
+
+}  // namespace

@@ -1044,10 +1044,10 @@ int dg4_launch_pack_ffn(const void* w1, const void* w2, void* packed, hipStream_
     return hipGetLastError();
 }
 
-int dg4_launch_sweep_init(const dg4_sweep_args& a, int64_t n_flags, int64_t done_below, hipStream_t s)
+int dg4_launch_sweep_init(uint32_t* flags, uint32_t* ctrl, int64_t n_flags, int64_t done_below, hipStream_t s)
 {
     hipLaunchKernelGGL(sweep_init_kernel, dim3((unsigned)((std::max<int64_t>(n_flags, 64) + 255) / 256)), dim3(256), 0, s,
-                       a.flags, n_flags, done_below, a.ctrl);
+                       flags, n_flags, done_below, ctrl);
     return hipGetLastError();
 }
 

@@ -26,6 +26,13 @@ def row_rel_err(got: np.ndarray, ref: np.ndarray) -> np.ndarray:
     return num / np.maximum(den, 1e-30)
 
 
+def elem_err(got: np.ndarray, ref: np.ndarray) -> np.ndarray:
+    """Element-wise error |got - ref| / max(|ref|, RMS of the reference row): one badly wrong element of a
+    row shows here even when the row's norm hides it."""
+    rms = np.sqrt((ref * ref).mean(axis=1, keepdims=True))
+    return np.abs(got.astype(np.float64) - ref) / np.maximum(np.maximum(np.abs(ref), rms), 1e-30)
+
+
 def device_weights(w, dtype):
     return [(to_dev(w.wqkv[l], dtype), to_dev(w.wo[l], dtype), to_dev(w.rel_bias[l], "f32"))
             for l in range(len(w.wqkv))]

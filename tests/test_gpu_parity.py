@@ -80,8 +80,9 @@ def run_layer(w, cfg, g, level_begin=0, level_end=None, H0=None):
     X = to_dev(w.x, dtype)
     W = device_weights(w, dtype)
     H = torch.full((w.cfg.n_nodes, cfg.hidden), float("nan"), dtype=tdtype(dtype), device="cuda") if H0 is None else H0
-    dg4.dg4_layer_fwd(cfg, g, X, W, H, level_begin, level_end)
+    ws = dg4.dg4_layer_fwd(cfg, g, X, W, H, level_begin, level_end)
     torch.cuda.synchronize()
+    dg4.dg4_layer_status(cfg, g, ws)                    # raises if a persistent sweep gave up
     return H
 
 
@@ -136,7 +137,7 @@ def test_layer_fwd_schedule_split_and_determinism():
     assert torch.equal(H2, Hh)                          # resumed sweep = whole sweep
 
 
-def test_dataflow_and_level_ordered_tiles_agree(monkeypatch):
+def test_dataflow_and_level_ordered_tiles_agree():
     # a whole-graph sweep runs in the dependency-driven tile order; the same sweep with the tiles
     # dealt level by level must not change a bit (nor does the per-level launch path change more
     # than rounding)
@@ -145,15 +146,13 @@ def test_dataflow_and_level_ordered_tiles_agree(monkeypatch):
     cfg = cfg_of(w.cfg)
     g, _ = graphs(w, hint=True)
     H_flow = run_layer(w, cfg, g)
-    monkeypatch.setenv("DG4_SWEEP_LEVEL_ORDER", "1")
-    H_level = run_layer(w, cfg, g)
-    monkeypatch.delenv("DG4_SWEEP_LEVEL_ORDER")
+    H_level = run_layer(w, cfg_of(w.cfg, level_order=True), g)
     assert torch.equal(H_flow, H_level)
     assert not torch.isnan(H_flow.float()).any()
 
 
 @pytest.mark.parametrize("name,n_and", [("stress", 30_000), ("large", 30_000)])
-def test_level_by_level_sweeps_through_eq1_levels_or_the_hint_agree(name, n_and, monkeypatch):
+def test_level_by_level_sweeps_through_eq1_levels_or_the_hint_agree(name, n_and):
     # level-by-level launches over ALL levels of a graph with a deeper levelling than Eq. 1 go
     # through the Eq. 1 levels (far fewer rounds of launches); forced through the caller's levels
     # they must give the same bits
@@ -163,9 +162,7 @@ def test_level_by_level_sweeps_through_eq1_levels_or_the_hint_agree(name, n_and,
     g, og = graphs(w, hint=True)
     assert g.n_levels > 3 * (int(oracle.levels(w.cfg.n_nodes, w.edge_src, w.edge_dst).max()) + 1)
     H_eq1 = run_layer(w, cfg, g)
-    monkeypatch.setenv("DG4_SWEEP_LEVEL_ORDER", "1")
-    H_hint = run_layer(w, cfg, g)
-    monkeypatch.delenv("DG4_SWEEP_LEVEL_ORDER")
+    H_hint = run_layer(w, cfg_of(w.cfg, per_level=True, level_order=True), g)
     assert not torch.isnan(H_eq1.float()).any()
     assert torch.equal(H_eq1, H_hint)
 
@@ -347,8 +344,7 @@ def test_small_graphs_through_the_persistent_kernel(n_pi, n_and, ffn):
     Hd = torch.full((n, c.hidden), float("nan"), dtype=torch.bfloat16, device="cuda")
     dg4.dg4_layer_fwd(cfg, g, to_dev(x, "bf16"), W, Hd, workspace=ws)
     torch.cuda.synchronize()
-    aborted, _ = dg4.dg4_layer_profile(cfg, g, ws)
-    assert aborted == 0
+    dg4.dg4_layer_status(cfg, g, ws)
     H = to_np(Hd)
     assert not np.isnan(H).any()
     ref = oracle.layer_fwd(og, x, wqkv, wo, rb, c.heads, store="bf16", w1=w1, w2=w2)

@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "dg4.h")).read()
     names = set(re.findall(r"^(?:int|int64_t|void|const char\*)\s+(dg4_[a-z_]+)\s*\(", hdr, flags=re.M))
-    assert len(names) == 20
+    assert len(names) == 21
     assert {"dg4_build_levels", "dg4_qkv_proj", "dg4_sparse_attn_fwd", "dg4_layer_fwd", "dg4_struct_encode"} <= names
     L = ctypes.CDLL(dg4.library_path()) if os.path.exists(dg4.library_path()) else dg4.lib()
     for n in sorted(names):
@@ -173,7 +173,7 @@ def test_bad_hint_hops_and_empty():
 
 def test_config_errors_without_a_device():
     g = dg4.dg4_build_levels(3, [0, 1], [2, 2], [0, 0], 2)
-    for bad in (dict(hidden=64, heads=2), dict(hidden=128, heads=8), dict(hidden=128, heads=4, n_layers=9),
+    for bad in (dict(hidden=64, heads=2), dict(hidden=128, heads=8), dict(hidden=128, heads=4, n_layers=17),
                 dict(hidden=128, heads=4, hops=3)):
         kw = dict(hidden=128, heads=4, hops=2, n_layers=1, dtype="f32")
         kw.update(bad)
