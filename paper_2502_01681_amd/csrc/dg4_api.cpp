@@ -33,6 +33,7 @@ struct LayerPlan {
     size_t w1[DG4_MAX_LAYERS], w2[DG4_MAX_LAYERS];   // feed-forward weights, packed (DG4_FFN)
     size_t h1;           // [max_level_rows, d] state after the attention sub-block (DG4_FFN)
     size_t wkv_all;      // packed [d, n_layers*2d]: K|V columns of every layer
+    size_t wkv_a;        // the same in the order of the persistent kernel for every shape
     size_t qkv_self;     // [n, 3d]  Q | K | V of x, level-sorted rows (layer 0)
     size_t kv;           // [n_layers, kv_rows, 2d]  K | V of the final embeddings, level-sorted
     size_t kv_rows;
@@ -66,6 +67,7 @@ LayerPlan plan_layer(const dg4_layer_cfg* c, const dg4_graph* g)
     const bool ffn = (c->flags & DG4_FFN) != 0;
     for (size_t l = 0; l < L; ++l) { p.w1[l] = take(ffn ? d * 4 * d * es : 0); p.w2[l] = take(ffn ? 4 * d * d * es : 0); }
     p.wkv_all = take(d * 2 * d * L * es);
+    p.wkv_a = take(d * 2 * d * L * es);
     p.qkv_self = take((c->flags & DG4_BOUNDED_KV) ? 0 : n * 3 * d * es);
     // K | V rows: of every finished gate, or (DG4_BOUNDED_KV) of one level's frontier only
     const bool bounded = (c->flags & DG4_BOUNDED_KV) != 0;
@@ -325,12 +327,18 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
 
     if (pack) {
         for (int l = 0; l < L; ++l) {
-            if (!resident) {
-                if (l > 0 || !flow || dt != DG4_BF16) HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
+            if (flow) {
+                // layer 0's Q | K | V weight serves the bulk projection of x (packed further down for bf16)
+                if (l > 0) HIPCHK(dg4_launch_pack_wa(dt, d, W[WS * l], 3 * d, 0, 3 * d, at(pl.wqkv[l]), s));
+                else if (dt != DG4_BF16) HIPCHK(dg4_launch_pack_w(dt, W[0], 3 * d, 0, 3 * d, d, at(pl.wqkv[0]), s));
+                HIPCHK(dg4_launch_pack_wa(dt, d, W[WS * l + 1], d, 0, d, at(pl.wo[l]), s));
+                HIPCHK(dg4_launch_pack_wa(dt, d, W[WS * l], 3 * d, d, 2 * d, ws + pl.wkv_a + (size_t)l * 2 * d * d * es, s));
+            } else if (!resident) {
+                HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 1], d, 0, d, d, at(pl.wo[l]), s));
             }
             // K | V columns of layer l go to column tiles [l*2d/32, (l+1)*2d/32) of wkv_all
-            if (!resident || level_begin > 0)
+            if ((!resident && !flow) || (resident && level_begin > 0))
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
             if (ffn && !resident) {
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 3], 4 * d, 0, 4 * d, d, at(pl.w1[l]), s));
@@ -353,8 +361,9 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         return dg4_launch_gemm(dt, d, a, s);
     };
 
-    // K/V of gates finished before this call (resume): from the caller's H
-    if (P0 > 0 && !bounded) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
+    // K/V of gates finished before this call (resume): from the caller's H (the persistent kernel for
+    // every shape does that itself, with its own arithmetic)
+    if (P0 > 0 && !bounded && !flow) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
     // optional timing of the persistent kernel alone
     const bool timed = (cfg->flags & DG4_TIME_SWEEP) != 0 && (resident || flow);
@@ -457,7 +466,13 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
                                    (size_t)cfg->heads * 4 * sizeof(float), hipMemcpyDeviceToDevice, s) != hipSuccess) return DG4_EHIP;
         dg4_flow_args a{};
         if (whole) {
-            a.tiles = g->d_pair_tiles; a.pairs = 1; a.tile_begin = 0; a.n_tiles = g->n_pair_tiles / 2;
+            // Tiles of 32 gates (two of the table's tiles of 16, which never depend on each other) share a
+            // pass over the weights; on a deep, narrow circuit, where a level is a handful of tiles and
+            // most compute units idle, tiles of 16 halve the matrix-core time on the dependency chain.
+            const int64_t depth = g->eq1_level_ptr.empty() ? (int64_t)g->max_level + 1 : (int64_t)g->eq1_level_ptr.size() - 1;
+            const bool narrow = g->n / std::max<int64_t>(depth, 1) < 4096;
+            a.tiles = g->d_pair_tiles; a.pairs = narrow ? 0 : 1; a.tile_begin = 0;
+            a.n_tiles = narrow ? g->n_pair_tiles : g->n_pair_tiles / 2;
             a.ell = g->d_pair_ell;
         } else {
             a.tiles = g->d_tiles32; a.pairs = 0; a.tile_begin = g->level_tile32_ptr[level_begin];
@@ -465,18 +480,20 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             a.ell = g->d_ell_pos;
         }
         a.ell_w = g->ell_w;
+        a.pre_rows = P0; a.n_pre = (P0 + 31) / 32;
         a.order = order_in_use;
         a.x = X; a.qkv_self = at(pl.qkv_self);
         a.kv = at(pl.kv); a.kv_layer_stride = (int64_t)pl.kv_rows * 2 * d;
         a.h_out = Hout;
         a.wqkv_packed = at(pl.wqkv[0]); a.wo_packed = at(pl.wo[0]);
         a.w_layer_stride = L > 1 ? (int64_t)(pl.wqkv[1] - pl.wqkv[0]) : 0;
-        a.wkv_packed = at(pl.wkv_all);
+        a.wkv_packed = at(pl.wkv_a);
         a.rel_bias = (const float*)at(pl.bias_all);
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
         a.n_layers = L; a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.project_kv = 1;
         a.spin_limit = spin_limit;
-        HIPCHK(dg4_launch_sweep_init(a.flags, a.ctrl, g->n, P0, s));
+        a.prof = (cfg->flags & DG4_PROFILE) ? (uint64_t*)((char*)at(pl.ctrl) + 64) : nullptr;
+        HIPCHK(dg4_launch_sweep_init(a.flags, a.ctrl, g->n, 0, s));
         HIPCHK(bracket([&]() { return dg4_launch_flow(dt, d, a, s); }));
         return DG4_OK;
     }

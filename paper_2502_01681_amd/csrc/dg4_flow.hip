@@ -1,5 +1,6 @@
-// The level sweep as one persistent dataflow kernel, for every shape: fp32 or bf16, hidden 128 or 256,
-// cones of up to three hops (neighbour rows of 8 or 16 entries), any number of stacked layers.
+// The level sweep as one persistent dataflow kernel, for every shape: fp32 with hidden 128 or bf16 with
+// hidden 256 (rows of 512 bytes either way), cones of up to three hops (neighbour rows of 8 or 16
+// entries), any number of stacked layers.
 //
 // The updating strategy (paper Section 3.4, Algorithm 2) requires that a gate reads the FINAL
 // embeddings of its cone sources and is itself computed once; with several layers a gate runs all
@@ -10,24 +11,28 @@
 // workgroups the device keeps resident. A bounded spin count turns any violation into an abort word
 // instead of a hang.
 //
-// Per tile: wait for the "published" flags of the sources of its gates; then per layer the attention
-// over the cone rows (lanes split the feature dimension, attend_core), the output projection with
-// residual + LayerNorm on the matrix cores (the four waves split the columns, the packed weight
-// streams from the L2 cache through a ring of fragments), and the Q | K | V projection of the new
-// state for the next layer, into LDS; after the last layer the embeddings go out and K | V of every
-// layer are projected from them into the store of finished gates, followed by a device-scope
-// release and the flags. The arithmetic of a row is, operation for operation, that of the
-// level-by-level kernels (attn_kernel, gemm_ln_split_kernel, gemm_kernel): same bits.
+// Per tile (eight waves): wait for the "published" flags of the sources of its gates; then per layer
+// the attention over the cone rows (16 lanes per gate split the feature dimension, attend_core), the
+// output projection on the matrix cores, residual + LayerNorm, and the Q | K | V projection of the
+// new state for the next layer, into LDS; after the last layer the embeddings go out and K | V of
+// every layer are projected from them into the store of finished gates. Projections run on blocks of
+// 16 gates with the WEIGHT as the A operand of a 16x16 product and the gates as B: a lane ends up
+// with 16 contiguous bytes of ONE gate's row, so residual, LayerNorm and the stores need no
+// transposition, and a tile of at most 16 gates costs half the matrix-core time of a full one (what
+// counts on deep, narrow circuits, where a level is one or two tiles). The packed weights stream
+// from the L2 cache through a ring of fragments in registers that is refilled one group of columns
+// ahead, across phase boundaries: the first fragments of the next product travel during the
+// LayerNorm, those of the next tile's first product during the last stores. A gate's arithmetic does
+// not depend on which tile or block it falls into: any schedule gives the same bits.
 //
-// Visibility between compute units follows the memory model as the compiler implements it for
-// gfx950: a writer's rows are ordinary stores followed by a release fence at agent scope (every
-// thread, for its own stores), a workgroup barrier, and release stores of the flags; a reader polls
-// the flags with agent-scope atomic loads and issues an acquire fence at agent scope before the
-// first load of a source row. No row is read before its flag has been seen.
+// Visibility between compute units: a K | V row is written exactly once per sweep, with agent-scope
+// (write-through) stores, and its flag is raised, again at agent scope, only after the writing
+// threads have waited for those stores to complete (s_waitcnt vmcnt(0), then a workgroup barrier).
+// A reader polls the flag with agent-scope loads, which are served past its own L1 and L2, and
+// reads the row only after it has seen the flag. No row is ever read before it is written, not
+// even speculatively, so no cache on the reader's side can hold an older copy of its lines.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-
-#include <type_traits>
 
 #include "dg4_device.h"
 #include "dg4_internal.h"
@@ -35,321 +40,471 @@
 
 namespace {
 
-constexpr int FT = 32;                    // gates per tile
+constexpr int FT = 32;                    // gates per tile (two blocks of 16)
+constexpr int FLOW_THREADS = 512;
 
-// compile-time loop: f(integral_constant<int, I>) for I = 0 .. N-1
-template <int I, int N, typename F>
-__device__ __forceinline__ void static_for(F&& f)
-{
-    if constexpr (I < N) {
-        f(std::integral_constant<int, I>{});
-        static_for<I + 1, N>(f);
+// One fragment of packed weight (16 bytes per lane: 16 output columns x 32 bytes of the input
+// dimension) against a block of 16 gates: c[i] of lane (n = lane % 16, g = lane / 16) is gate n,
+// output column 4*g + i of the fragment's 16.
+template <typename T> struct Blk;
+template <> struct Blk<bf16_t> {
+    __device__ static __forceinline__ void run(const uint4& w, const uint4& r, f32x4& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, w), __builtin_bit_cast(bf16x8, r), c, 0, 0, 0);
     }
-}
-
-template <typename T, int D>
-struct FlowShape {
-    static constexpr int E = 16 / (int)sizeof(T);     // elements per 16 bytes
-    static constexpr int KC = D / (2 * E);            // k-chunks of a product (16 for both supported shapes... checked below)
-    static constexpr int YS = D + E;                  // row stride of a staged row (16 bytes of padding)
-    static constexpr int QS = 3 * D + E;              // row stride of the staged Q | K | V rows
-    static constexpr int TS = 32 + E;                 // row stride of a staged 32x32 output tile
-    static constexpr int CPR = D / E;                 // 16-byte pieces per row
-    static constexpr int TPR = 32 / E;                // 16-byte pieces per row of a 32x32 tile
-    static constexpr int RING = 16;
-    static constexpr size_t row_buf = (size_t)FT * YS * sizeof(T);
-    static constexpr size_t tile_buf = (size_t)4 * 32 * TS * sizeof(T);
-    static constexpr size_t part_buf = 2 * 4 * 32 * sizeof(float);
-    static constexpr size_t ctl_buf = 16;
-    static constexpr size_t qkv_buf = (size_t)FT * QS * sizeof(T);
-    static constexpr size_t smem(bool multi) { return 2 * row_buf + tile_buf + part_buf + ctl_buf + (multi ? qkv_buf : 0); }
+};
+template <> struct Blk<float> {
+    __device__ static __forceinline__ void run(const uint4& w, const uint4& r, f32x4& c)
+    {
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(w.x), __uint_as_float(r.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(w.y), __uint_as_float(r.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(w.z), __uint_as_float(r.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(__uint_as_float(w.w), __uint_as_float(r.w), c, 0, 0, 0);
+    }
 };
 
-// rows [32] x packed weight columns: the fragments of `n_tiles` column tiles, KC each, starting at
-// column tile `first_tile` of the stream wp (already offset by the lane), through a ring of KC
-// fragments requested one tile ahead. emit(column tile, accumulator) is called per finished tile.
-template <typename T, int KC, typename F>
-__device__ __forceinline__ void stream_product(const uint4 (&a)[KC], const uint4* wp, int first_tile, int n_tiles, F&& emit)
-{
-    static_assert(KC == 16, "the ring is one column tile deep");
-    uint4 ring[KC];
-    const uint4* w = wp + (int64_t)first_tile * KC * 64;
-#pragma unroll
-    for (int c = 0; c < KC; ++c) ring[c] = w[c * 64];
-#pragma unroll 1
-    for (int t = 0; t < n_tiles; ++t) {
-        f32x16 acc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-        const bool more = t + 1 < n_tiles;
-        const uint4* wn = w + (int64_t)(t + 1) * KC * 64;
-#pragma unroll
-        for (int c = 0; c < KC; ++c) {
-            Mma<T>::run(a[c], ring[c], acc);
-            if (more) ring[c] = wn[c * 64];
-        }
-        emit(first_tile + t, acc);
+// 16 bytes <-> the lane's contiguous columns (4 floats or 8 bfloat16)
+template <typename T> struct Piece;
+template <> struct Piece<float> {
+    static constexpr int N = 4;
+    __device__ static __forceinline__ void unpack(const uint4& v, float* f)
+    {
+        f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
     }
-}
-// the same for a number of tiles known at compile time: emit(index 0 .. NT-1 as a constant, accumulator)
-template <typename T, int KC, int NT, typename F>
-__device__ __forceinline__ void stream_product_fixed(const uint4 (&a)[KC], const uint4* wp, int first_tile, F&& emit)
+    __device__ static __forceinline__ uint4 pack(const float* f)
+    {
+        return make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
+    }
+};
+template <> struct Piece<bf16_t> {
+    static constexpr int N = 8;
+    __device__ static __forceinline__ void unpack(const uint4& v, float* f)
+    {
+        const uint32_t w[4] = { v.x, v.y, v.z, v.w };
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = bf16_lo(w[i]); f[2 * i + 1] = bf16_hi(w[i]); }
+    }
+    __device__ static __forceinline__ uint4 pack(const float* f)
+    {
+        return make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
+    }
+};
+
+// Weights in the order the kernel streams them, 16-byte units. Columns come in GROUPS of gt tiles of
+// 16 (one group = what one wave computes at a time: 16*gt consecutive columns), each tile in 8 steps
+// of 32 bytes of the input dimension. Unit (((group*gt + nt)*8 + s)*64 + lane), lane = 16*kq + m,
+// holds input rows k = s*4E + kq*E .. +E-1 (E = 16 / sizeof(T)) of column
+//   col0 + group*16*gt + (m/4)*4*gt + nt*4 + m%4,
+// so that accumulator register i of lane (n, g) of tile nt is column group*16*gt + g*4*gt + nt*4 + i:
+// the lane owns 4*gt consecutive columns (16 bytes) of gate n.
+template <typename T>
+__global__ void pack_wa_kernel(const T* w, int ld, int col0, int n_cols, int gt, T* packed)
 {
-    static_assert(KC == 16, "the ring is one column tile deep");
-    uint4 ring[KC];
-    const uint4* w = wp + (int64_t)first_tile * KC * 64;
+    constexpr int E = 16 / (int)sizeof(T);
+    const int64_t unit = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    const int64_t units = (int64_t)(n_cols / 16) * 8 * 64;
+    if (unit >= units) return;
+    const int lane = (int)(unit & 63);
+    const int s = (int)((unit >> 6) & 7);
+    const int tile = (int)(unit >> 9);
+    const int nt = tile % gt, group = tile / gt;
+    const int m = lane & 15, kq = lane >> 4;
+    const int col = col0 + group * 16 * gt + (m >> 2) * 4 * gt + nt * 4 + (m & 3);
+    const int k0 = s * 4 * E + kq * E;
 #pragma unroll
-    for (int c = 0; c < KC; ++c) ring[c] = w[c * 64];
-    static_for<0, NT>([&](auto I) __attribute__((always_inline)) {
-        constexpr int t = I.value;
-        f32x16 acc;
-#pragma unroll
-        for (int i = 0; i < 16; ++i) acc[i] = 0.f;
-#pragma unroll
-        for (int c = 0; c < KC; ++c) {
-            Mma<T>::run(a[c], ring[c], acc);
-            if (t + 1 < NT) ring[c] = w[((t + 1) * KC + c) * 64];
-        }
-        emit(I, acc);
-    });
+    for (int j = 0; j < E; ++j) packed[unit * E + j] = w[(int64_t)(k0 + j) * ld + col];
 }
 
-template <typename T, int D, int AW>
-__global__ __launch_bounds__(256) void flow_kernel(dg4_flow_args p)
+// x summed over the four 16-lane rows of a wave (lanes with equal lane % 16), in every lane
+__device__ __forceinline__ float sum_lane_rows(float x)
 {
-    using S = FlowShape<T, D>;
-    constexpr int E = S::E, KC = S::KC, YS = S::YS, QS = S::QS, TS = S::TS, CPR = S::CPR, TPR = S::TPR;
+    const uint32_t u = __float_as_uint(x);
+    const auto a = __builtin_amdgcn_permlane16_swap(u, u, false, false);      // rows (0,1) and (2,3) exchanged
+    const uint32_t v = __float_as_uint(__uint_as_float(a[0]) + __uint_as_float(a[1]));
+    const auto b = __builtin_amdgcn_permlane32_swap(v, v, false, false);      // halves exchanged
+    return __uint_as_float(b[0]) + __uint_as_float(b[1]);
+}
+
+template <typename T, int AW, bool TIMERS>
+__global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
+{
+    constexpr int D = 512 / (int)sizeof(T);       // 128 (fp32) or 256 (bf16): a row is 512 bytes
+    constexpr int E = 16 / (int)sizeof(T);
     constexpr int EPL = Elem<T>::EPL, LPR = D / EPL;
-    static_assert(LPR == 16 && AW <= LPR, "one lane per neighbour entry while waiting");
-    static_assert(KC == 16, "fp32 with hidden 128 or bf16 with hidden 256");
-    constexpr int NTW = D / 32 / 4;               // column tiles of the output projection per wave
-    constexpr int PPT = FT * CPR / 256;           // 16-byte pieces of the tile's rows per thread
+    static_assert(LPR == 16 && AW <= LPR, "16 lanes per gate in the attention, one per neighbour entry while waiting");
+    constexpr int GT = D / 16 / 8;                // 16-column tiles per group (1 or 2): a wave's share of D columns
+    constexpr int CW = 4 * GT;                    // consecutive columns a lane owns (16 bytes)
+    static_assert(CW == Piece<T>::N, "a lane's columns are one 16-byte piece");
+    constexpr int RING = 8 * GT;                  // fragments of one group
+    constexpr int YS = D + E;                     // row stride in LDS (16 bytes of padding)
+    constexpr int QS = 3 * D + E;
+    constexpr int CPR = D / E;                    // 16-byte pieces per row (32)
+    constexpr int PPT = FT * CPR / FLOW_THREADS;  // pieces of the tile's rows per thread (2)
+    constexpr int GROUP_UNITS = RING * 64;        // 16-byte units per group in the packed stream
 
     extern __shared__ __attribute__((aligned(16))) unsigned char flow_smem[];
+    constexpr size_t ROW_BUF = (size_t)FT * YS * sizeof(T);
     T* buf0 = (T*)flow_smem;
-    T* buf1 = (T*)(flow_smem + S::row_buf);
-    T* stage = (T*)(flow_smem + 2 * S::row_buf);                       // [4][32 * TS]
-    float (*part)[4][32] = (float (*)[4][32])(flow_smem + 2 * S::row_buf + S::tile_buf);
-    int* ctl = (int*)(flow_smem + 2 * S::row_buf + S::tile_buf + S::part_buf);     // [0] ticket, [1] abort
-    T* qkvbuf = (T*)(flow_smem + 2 * S::row_buf + S::tile_buf + S::part_buf + S::ctl_buf);
+    T* buf1 = (T*)(flow_smem + ROW_BUF);
+    float (*part)[8][FT] = (float (*)[8][FT])(flow_smem + 2 * ROW_BUF);             // [2][wave][row]
+    // two tile descriptors {kind, first position, rows, -} (this tile's and the next one's), then the abort word
+    int* ctl = (int*)(flow_smem + 2 * ROW_BUF + 2 * 8 * FT * sizeof(float));
+    T* qkvbuf = (T*)(flow_smem + 2 * ROW_BUF + 2 * 8 * FT * sizeof(float) + 64);    // [FT][QS], sweeps of several layers
 
     const int tid = threadIdx.x;
-    const int lane = tid & 63, wave = tid >> 6;
-    const int m = lane & 31, kg = lane >> 5;
-    const int group = tid / LPR, sub = tid % LPR;  // attention role: rows `group` and `group + 16` of the tile
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int n = lane & 15, g = lane >> 4;       // projection role: gate n of a block, columns wave*16*GT + g*CW .. +CW-1 of a group
+    const int cbase = wave * 16 * GT + g * CW;
+    const int arow = tid >> 4, sub = tid & 15;    // attention role: gate `arow` of the tile, 32 bytes `sub` of its rows
     const int L = p.n_layers;
 
-    if (tid == 0) ctl[1] = 0;
-    for (;;) {
-        if (tid == 0) ctl[0] = (int)__hip_atomic_fetch_add(&p.ctrl[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __syncthreads();                          // (also: the previous tile is done with every buffer)
-        const int64_t t = ctl[0];
-        if (t >= p.n_tiles || ctl[1]) break;
-        int64_t p0;
-        int rows;
-        if (p.pairs) {
-            const uint2 ta = p.tiles[p.tile_begin + 2 * t], tb = p.tiles[p.tile_begin + 2 * t + 1];
-            p0 = ta.x; rows = (int)(ta.y + tb.y);
-        } else {
-            const uint2 ta = p.tiles[p.tile_begin + t];
-            p0 = ta.x; rows = (int)ta.y;
+    // optional phase timers (thread 0, constant-rate clock, 10 ns ticks, summed over workgroups):
+    // ticket, wait, attention, output projection + LayerNorm, next layer's Q|K|V, rows out + K|V, publish
+    uint64_t prof[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    uint64_t tick = 0;
+    if (TIMERS && tid == 0) tick = wall_clock64();
+    auto lap = [&](int phase) __attribute__((always_inline)) {
+        if (TIMERS && tid == 0) { const uint64_t now = wall_clock64(); prof[phase] += now - tick; tick = now; }
+    };
+
+    // The ring: the next eight fragments of the packed weight stream this wave multiplies, refilled
+    // eight fragments ahead as they are used up, across the end of a group into the group that follows.
+    uint4 ring[8];
+    const uint4* ring_src;                        // the group whose first fragments the ring holds
+    auto group_ptr = [&](const void* packed, int group) __attribute__((always_inline)) {
+        return (const uint4*)packed + (int64_t)group * GROUP_UNITS + lane;
+    };
+    auto fill_ring = [&](const uint4* src) __attribute__((always_inline)) {
+        ring_src = src;
+#pragma unroll
+        for (int f = 0; f < 8; ++f) ring[f] = src[f * 64];
+    };
+    // acc[block][tile] = (the group in the ring) x b; `next`: the group that follows it
+    auto run_group = [&](const uint4 (&b)[2][8], bool two, const uint4* next, f32x4 (&acc)[2][GT]) __attribute__((always_inline)) {
+        const uint4* cur = ring_src;
+#pragma unroll
+        for (int nt = 0; nt < GT; ++nt) {
+            acc[0][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            acc[1][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
         }
-        // rows past the end of a ragged tile repeat its last gate: computed, never stored
+#pragma unroll
+        for (int f = 0; f < RING; ++f) {
+            const int nt = f / 8, s = f % 8;
+            const uint4 frag = ring[s];
+            Blk<T>::run(frag, b[0][s], acc[0][nt]);
+            if (two) Blk<T>::run(frag, b[1][s], acc[1][nt]);
+            ring[s] = f + 8 < RING ? cur[(f + 8) * 64] : next[(f + 8 - RING) * 64];
+        }
+        ring_src = next;
+    };
+    // the B operands: this lane's 16 bytes per step of the rows of both blocks (the second block's
+    // are read, and never used, when the tile has no second block)
+    auto load_rows = [&](const T* buf, uint4 (&b)[2][8]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            b[0][s] = *(const uint4*)((const unsigned char*)buf + (size_t)n * (YS * sizeof(T)) + s * 64 + g * 16);
+            b[1][s] = *(const uint4*)((const unsigned char*)buf + (size_t)(16 + n) * (YS * sizeof(T)) + s * 64 + g * 16);
+        }
+    };
+    // the lane's CW values of group-local columns from an accumulator
+    auto cols_of = [&](const f32x4 (&a)[GT], float* t) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nt = 0; nt < GT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) t[nt * 4 + i] = a[nt][i];
+    };
+
+    // Tickets, by thread 0. Tickets below n_pre stand for the gates finished before this call (a
+    // resumed sweep), 32 positions each: nothing is computed for them but K | V of every layer, from
+    // the caller's embeddings, with the arithmetic of a gate computed here. The ticket of the next
+    // tile is drawn at the top of a tile and its descriptor lands in LDS in the middle of it.
+    const int64_t total = p.n_pre + p.n_tiles;
+    auto describe = [&](int64_t t, int slot) __attribute__((always_inline)) {      // kind: 0 no tile left, 1 tile, 2 finished gates, 3 empty
+        int kind = 0, p0 = 0, rows = 0;
+        if (t < p.n_pre) {
+            kind = 2; p0 = (int)(t * FT); rows = (int)(p.pre_rows - p0 < FT ? p.pre_rows - p0 : FT);
+        } else if (t < total) {
+            if (p.pairs) {
+                const uint2 ta = p.tiles[p.tile_begin + 2 * (t - p.n_pre)], tb = p.tiles[p.tile_begin + 2 * (t - p.n_pre) + 1];
+                p0 = (int)ta.x; rows = (int)(ta.y + tb.y);
+            } else {
+                const uint2 ta = p.tiles[p.tile_begin + (t - p.n_pre)];
+                p0 = (int)ta.x; rows = (int)ta.y;
+            }
+            kind = rows > 0 ? 1 : 3;
+        }
+        ctl[4 * slot] = kind; ctl[4 * slot + 1] = p0; ctl[4 * slot + 2] = rows;
+    };
+    if (tid == 0) {
+        ctl[8] = 0;
+        describe((int64_t)__hip_atomic_fetch_add(&p.ctrl[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0);
+    }
+    fill_ring(group_ptr(p.wo_packed, wave));      // layer 0's output projection, this wave's columns
+    // the neighbour row of this lane group's gate in the NEXT tile, requested in the middle of a tile
+    uint32_t ent_n[AW], watch_n = DG4_ELL_PAD;
+#pragma unroll
+    for (int j = 0; j < AW; ++j) ent_n[j] = DG4_ELL_PAD;
+    bool have_next = false;                       // ent_n / watch_n hold the row of this tile (workgroup-uniform)
+    for (int it = 0;; ++it) {
+        __syncthreads();                          // the descriptor; the previous tile is done with every buffer
+        const int kind = ctl[4 * (it & 1)];
+        if (kind == 0 || ctl[8]) break;
+        const int64_t p0 = ctl[4 * (it & 1) + 1];
+        const int rows = ctl[4 * (it & 1) + 2];
+        const bool pre = kind == 2;
+        // the next tile's ticket travels during this tile
+        int64_t t_next = 0;
+        if (tid == 0) t_next = (int64_t)__hip_atomic_fetch_add(&p.ctrl[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (kind != 1) {
+            if (tid == 0) describe(t_next, (it + 1) & 1);
+            have_next = false;
+            if (kind == 3) continue;              // an empty tile of the table
+        }
+        const bool two = rows > 16;               // a second block of 16 gates
+        const int live = two ? FT : 16;           // rows that are computed (past `rows`: the last gate again, never stored)
         auto pos_of = [&](int r) { return p0 + (r < rows ? r : rows - 1); };
+        lap(0);
 
         T* resid = buf0;                          // the running state s_l
         T* ybuf = buf1;                           // attention output, then the normalised rows
 
         // s_0 = X rows of the tile's gates, as 16-byte pieces
-        int64_t pidx[PPT];                        // node id of the piece's row (-1: past the end)
+        int64_t pidx[PPT];                        // node id of the piece's row (-1: not stored)
 #pragma unroll
         for (int q = 0; q < PPT; ++q) {
-            const int piece = tid + 256 * q, row = piece / CPR, c = piece % CPR;
-            const int64_t id = p.order[pos_of(row)];
-            pidx[q] = row < rows ? id : -1;
-            *(uint4*)&resid[row * YS + c * E] = *((const uint4*)((const T*)p.x + id * D) + c);
+            const int piece = tid + FLOW_THREADS * q, row = piece / CPR, c = piece % CPR;
+            pidx[q] = -1;
+            if (row < live) {
+                const int64_t id = p.order[pos_of(row)];
+                if (row < rows && !pre) pidx[q] = id;
+                if (pre) *(uint4*)&ybuf[row * YS + c * E] = *((const uint4*)((const T*)p.h_out + id * D) + c);
+                else *(uint4*)&resid[row * YS + c * E] = *((const uint4*)((const T*)p.x + id * D) + c);
+            }
         }
 
-        // ---- the sources of this wave's eight gates must be published: lane `sub` of a gate's
-        // group watches entry `sub` of the gate's row
-        {
-            const int64_t ra = pos_of(group), rb = pos_of(group + 16);
-            const uint32_t ea = sub < AW ? p.ell[ra * AW + sub] : DG4_ELL_PAD;
-            const uint32_t eb = sub < AW ? p.ell[rb * AW + sub] : DG4_ELL_PAD;
-            const bool wa = ea != DG4_ELL_PAD && (ea >> 30) != 0, wb = eb != DG4_ELL_PAD && (eb >> 30) != 0;
-            const uint32_t* fa = p.flags + (wa ? (ea & 0x3FFFFFFFu) : 0u);
-            const uint32_t* fb = p.flags + (wb ? (eb & 0x3FFFFFFFu) : 0u);
+        // ---- the sources of this lane group's gate must be published: lane `sub` watches entry `sub` of its row
+        const bool attends = arow < live && !pre; // (whole waves: 4 gates per wave)
+        const int64_t apos = pos_of(arow);
+        uint32_t ent[AW];
+        if (attends) {
+            uint32_t e;
+            if (have_next) {
+#pragma unroll
+                for (int j = 0; j < AW; ++j) ent[j] = ent_n[j];
+                e = watch_n;
+            } else {
+                load_entries<AW>(p.ell, apos, ent);
+                e = sub < AW ? p.ell[apos * AW + sub] : DG4_ELL_PAD;
+            }
+            const bool watch = e != DG4_ELL_PAD && (e >> 30) != 0;
+            const uint32_t* f = p.flags + (watch ? (e & 0x3FFFFFFFu) : 0u);
             uint32_t spins = 0;
             for (;;) {
-                const bool ok = (!wa || __hip_atomic_load(fa, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u) &&
-                                (!wb || __hip_atomic_load(fb, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u);
+                const bool ok = !watch || __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
                 if (__ballot(!ok) == 0) break;
-                __builtin_amdgcn_s_sleep(2);
+                __builtin_amdgcn_s_sleep(1);
                 if (++spins > p.spin_limit ||
                     ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
                     // give up: the tile is computed from whatever is there (every access stays in
                     // bounds), nothing of it is published, and the workgroup leaves after it
                     if (lane == 0) {
                         __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ctl[1] = 1;
+                        ctl[8] = 1;
                     }
                     break;
                 }
             }
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+            // (the flag loads above are the only ordering needed, see the head of the file; the fence
+            // keeps the compiler from moving row loads above them)
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        } else {
+#pragma unroll
+            for (int j = 0; j < AW; ++j) ent[j] = DG4_ELL_PAD;
         }
+        if (TIMERS) __syncthreads();
+        lap(1);
 
-        for (int l = 0; l < L; ++l) {
+        uint4 b[2][8];
+        f32x4 acc[2][GT];
+        if (pre) {
+            fill_ring(group_ptr(p.wkv_packed, wave));     // (the ring held the first product of a tile that is computed)
+            __syncthreads();
+            load_rows(ybuf, b);
+        }
+        for (int l = 0; l < (pre ? 0 : L); ++l) {
             const bool last = l == L - 1;
             // ---- attention of layer l: the gate's own Q, K, V from the projection of x (layer 0) or
             // from LDS (its running state, projected at the end of the previous layer); sources from
             // the store of finished gates, layer l
-            {
+            if (attends) {
                 const T* kvl = (const T*)p.kv + (int64_t)l * p.kv_layer_stride;
-                const float* bias = p.rel_bias + l * (D / 32) * 4;
-#pragma unroll 1
-                for (int rr = group; rr < FT; rr += 256 / LPR) {
-                    const int64_t pos = pos_of(rr);
-                    uint32_t ent[AW];
-                    load_entries<AW>(p.ell, pos, ent);
-                    const T* qrow = l == 0 ? (const T*)p.qkv_self + pos * (3 * D) : qkvbuf + (rr < rows ? rr : rows - 1) * QS;
-                    float av[EPL];
-                    attend_core<T, D, AW>(ent, qrow, qrow + D, qrow + 2 * D, kvl, kvl + D, 2 * D, bias, sub, av);
-                    uint4 oa, ob;
-                    Elem<T>::pack(av, oa, ob);
-                    uint4* op = (uint4*)&ybuf[rr * YS + sub * EPL];
-                    op[0] = oa; op[1] = ob;
-                }
+                const T* qrow = l == 0 ? (const T*)p.qkv_self + apos * (3 * D) : qkvbuf + arow * QS;
+                float av[EPL];
+                attend_core<T, D, AW, 8, AW == 8>(ent, qrow, qrow + D, qrow + 2 * D, kvl, kvl + D, 2 * D,
+                                          p.rel_bias + l * (D / 32) * 4, sub, av);
+                uint4 oa, ob;
+                Elem<T>::pack(av, oa, ob);
+                uint4* op = (uint4*)&ybuf[arow * YS + sub * EPL];
+                op[0] = oa; op[1] = ob;
             }
             __syncthreads();
-            // ---- s_{l+1} = LN(s_l + a Wo_l): wave w takes columns [w*NTW*32, (w+1)*NTW*32)
-            uint4 a[KC];
+            lap(2);
+            // ---- s_{l+1} = LN(s_l + a Wo_l): this lane ends with columns cbase .. cbase+CW-1 of gates n and 16+n
+            load_rows(ybuf, b);
+            // (the ring then takes the first group of the product that follows the LayerNorm)
+            const void* after = last ? p.wkv_packed : (const void*)((const char*)p.wqkv_packed + (int64_t)(l + 1) * p.w_layer_stride);
+            run_group(b, two, group_ptr(after, wave), acc);
+            if (l == 0 && tid == 0) describe(t_next, (it + 1) & 1);       // (the ticket has had the attention to arrive)
+            float tv[2][CW];
 #pragma unroll
-            for (int c = 0; c < KC; ++c) a[c] = *(const uint4*)&ybuf[m * YS + (2 * c + kg) * E];
-            f32x16 acc[NTW];
-            {
-                const uint4* wp = (const uint4*)((const char*)p.wo_packed + (int64_t)l * p.w_layer_stride) + lane;
-                stream_product_fixed<T, KC, NTW>(a, wp, wave * NTW, [&](auto NT, const f32x16& v) __attribute__((always_inline)) {
-                    acc[NT.value] = v;
-                });
+            for (int nb = 0; nb < 2; ++nb) {
+                cols_of(acc[nb], tv[nb]);
+                if (p.epilogue && (nb == 0 || two)) {
+                    float r[CW];
+                    Piece<T>::unpack(*(const uint4*)&resid[(16 * nb + n) * YS + cbase], r);
+#pragma unroll
+                    for (int i = 0; i < CW; ++i) tv[nb][i] += r[i];
+                }
             }
-            __syncthreads();                      // every wave holds its operand: ybuf may be written
-            const int col0 = wave * NTW * 32 + m;
+            __syncthreads();                      // every wave holds its operands: ybuf may be written
             if (p.epilogue) {
-                float mean[16];
+                // LayerNorm over each gate's row (no affine, biased variance), two passes: the lane's
+                // columns, the wave's 16*GT columns across its four lane rows, the eight waves through LDS
+                float mean[2];
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = 8 * (i / 4) + 4 * kg + (i % 4);
+                for (int nb = 0; nb < 2; ++nb) {
                     float s1 = 0.f;
 #pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) {
-                        acc[nt][i] += Elem<T>::load1(resid, (int64_t)row * YS + col0 + nt * 32);
-                        s1 += acc[nt][i];
-                    }
-                    s1 = sum_over_32_lanes(s1);
-                    if (m == 0) part[0][wave][row] = s1;
+                    for (int i = 0; i < CW; ++i) s1 += tv[nb][i];
+                    s1 = sum_lane_rows(s1);
+                    if (g == 0) part[0][wave][16 * nb + n] = s1;
                 }
                 __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = 8 * (i / 4) + 4 * kg + (i % 4);
-                    mean[i] = (part[0][0][row] + part[0][1][row] + part[0][2][row] + part[0][3][row]) * (1.0f / D);
+                for (int nb = 0; nb < 2; ++nb) {
+                    float a1 = 0.f;
+#pragma unroll
+                    for (int w2 = 0; w2 < 8; ++w2) a1 += part[0][w2][16 * nb + n];
+                    mean[nb] = a1 * (1.0f / D);
                     float s2 = 0.f;
 #pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) { const float t2 = acc[nt][i] - mean[i]; s2 = fmaf(t2, t2, s2); }
-                    s2 = sum_over_32_lanes(s2);
-                    if (m == 0) part[1][wave][row] = s2;
+                    for (int i = 0; i < CW; ++i) { const float d2 = tv[nb][i] - mean[nb]; s2 = fmaf(d2, d2, s2); }
+                    s2 = sum_lane_rows(s2);
+                    if (g == 0) part[1][wave][16 * nb + n] = s2;
                 }
                 __syncthreads();
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = 8 * (i / 4) + 4 * kg + (i % 4);
-                    const float rstd = rsqrtf((part[1][0][row] + part[1][1][row] + part[1][2][row] + part[1][3][row]) * (1.0f / D) + p.ln_eps);
+                for (int nb = 0; nb < 2; ++nb) {
+                    float a2 = 0.f;
 #pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt)
-                        Elem<T>::store1(ybuf, (int64_t)row * YS + col0 + nt * 32, (acc[nt][i] - mean[i]) * rstd);
-                }
-            } else {
+                    for (int w2 = 0; w2 < 8; ++w2) a2 += part[1][w2][16 * nb + n];
+                    const float rstd = rsqrtf(a2 * (1.0f / D) + p.ln_eps);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    const int row = 8 * (i / 4) + 4 * kg + (i % 4);
-#pragma unroll
-                    for (int nt = 0; nt < NTW; ++nt) Elem<T>::store1(ybuf, (int64_t)row * YS + col0 + nt * 32, acc[nt][i]);
+                    for (int i = 0; i < CW; ++i) tv[nb][i] = (tv[nb][i] - mean[nb]) * rstd;
                 }
             }
-            __syncthreads();                      // ybuf = s_{l+1}, rounded to T
-#pragma unroll
-            for (int c = 0; c < KC; ++c) a[c] = *(const uint4*)&ybuf[m * YS + (2 * c + kg) * E];
+            *(uint4*)&ybuf[n * YS + cbase] = Piece<T>::pack(tv[0]);
+            if (two) *(uint4*)&ybuf[(16 + n) * YS + cbase] = Piece<T>::pack(tv[1]);
+            __syncthreads();                      // ybuf = s_{l+1}, rounded to T; the next tile's descriptor
+            lap(3);
+            load_rows(ybuf, b);
+            if (l == 0) {
+                // the neighbour row this lane group will need at the top of the next tile
+                const int nslot = 4 * ((it + 1) & 1);
+                have_next = ctl[nslot] == 1;
+                if (have_next) {
+                    const int nrows = ctl[nslot + 2];
+                    if (arow < (nrows > 16 ? FT : 16)) {
+                        const int64_t npos = (int64_t)ctl[nslot + 1] + (arow < nrows ? arow : nrows - 1);
+                        load_entries<AW>(p.ell, npos, ent_n);
+                        watch_n = sub < AW ? p.ell[npos * AW + sub] : DG4_ELL_PAD;
+                    }
+                }
+            }
 
             if (!last) {
-                // ---- Q | K | V of the new state for the next layer, into LDS: wave w takes a quarter of the 3D columns
-                constexpr int NTQ = 3 * D / 32 / 4;
-                const uint4* wp = (const uint4*)((const char*)p.wqkv_packed + (int64_t)(l + 1) * p.w_layer_stride) + lane;
-                stream_product_fixed<T, KC, NTQ>(a, wp, wave * NTQ, [&](auto NT, const f32x16& v) __attribute__((always_inline)) {
-                    const int ct = wave * NTQ + NT.value;
+                // ---- Q | K | V of the new state for the next layer, into LDS: groups wave, 8 + wave, 16 + wave
+                // of the 3D columns are this wave's columns of Q, of K and of V
+                const void* wq = (const char*)p.wqkv_packed + (int64_t)(l + 1) * p.w_layer_stride;
+                const void* wo_next = (const char*)p.wo_packed + (int64_t)(l + 1) * p.w_layer_stride;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i)
-                        Elem<T>::store1(qkvbuf, (int64_t)(8 * (i / 4) + 4 * kg + (i % 4)) * QS + ct * 32 + m, v[i]);
-                });
+                for (int part3 = 0; part3 < 3; ++part3) {
+                    run_group(b, two, part3 < 2 ? group_ptr(wq, 8 * (part3 + 1) + wave) : group_ptr(wo_next, wave), acc);
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) {
+                        if (nb == 1 && !two) continue;
+                        float v[CW];
+                        cols_of(acc[nb], v);
+                        *(uint4*)&qkvbuf[(16 * nb + n) * QS + part3 * D + cbase] = Piece<T>::pack(v);
+                    }
+                }
                 // the new state is the next layer's residual; the old one's space takes the next attention output
                 T* tmp = resid; resid = ybuf; ybuf = tmp;
                 __syncthreads();
+                lap(4);
                 continue;
             }
-
-            // ---- the embeddings of the tile's gates go out, by node id
+        }
+        // ---- the embeddings of the tile's gates go out, by node id
 #pragma unroll
-            for (int q = 0; q < PPT; ++q) {
-                if (pidx[q] < 0) continue;
-                const int piece = tid + 256 * q, row = piece / CPR, c = piece % CPR;
-                *((uint4*)((T*)p.h_out + pidx[q] * D) + c) = *(const uint4*)&ybuf[row * YS + c * E];
-            }
-            // ---- K | V of every layer from the final embeddings: wave w takes a quarter of the 2D*L columns
-            if (p.project_kv) {
-                const int ntk = 2 * D / 32 * L / 4;
-                const uint4* wp = (const uint4*)p.wkv_packed + lane;
-                T* st = stage + wave * 32 * TS;
-                stream_product<T, KC>(a, wp, wave * ntk, ntk, [&](int ct, const f32x16& v) {
-                    // the 32x32 tile leaves through this wave's own corner of LDS, as 16-byte pieces of
-                    // rows (LDS operations of a wave complete in order: no barrier)
+        for (int q = 0; q < PPT; ++q) {
+            if (pidx[q] < 0) continue;
+            const int piece = tid + FLOW_THREADS * q, row = piece / CPR, c = piece % CPR;
+            *((uint4*)((T*)p.h_out + pidx[q] * D) + c) = *(const uint4*)&ybuf[row * YS + c * E];
+        }
+        // ---- K | V of every layer from the final embeddings: per layer, groups wave (K) and 8 + wave (V)
+        // of its 2D columns; written through to device memory (agent scope), 16 bytes per lane
+        for (int j = 0; j < 2 * L; ++j) {
+            const int nj = j + 1;
+            const uint4* next = nj < 2 * L ? group_ptr(p.wkv_packed, (nj >> 1) * 16 + (nj & 1) * 8 + wave)
+                                           : group_ptr(p.wo_packed, wave);      // the next tile's first product
+            run_group(b, two, next, acc);
+            T* base = (T*)p.kv + (int64_t)(j >> 1) * p.kv_layer_stride + (j & 1) * D + cbase;
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) Elem<T>::store1(st, (int64_t)(8 * (i / 4) + 4 * kg + (i % 4)) * TS + m, v[i]);
-                    const int col = ct * 32;
-                    T* base = (T*)p.kv + (int64_t)(col / (2 * D)) * p.kv_layer_stride + col % (2 * D);
-#pragma unroll
-                    for (int q = 0; q < 32 * TPR / 64; ++q) {
-                        const int piece = lane + 64 * q, row = piece / TPR, cc = piece % TPR;
-                        const uint4 val = *(const uint4*)&st[row * TS + cc * E];
-                        if (row < rows) *(uint4*)(base + (p0 + row) * (2 * D) + cc * E) = val;
-                    }
-                });
+            for (int nb = 0; nb < 2; ++nb) {
+                const int row = 16 * nb + n;
+                if (row >= rows) continue;
+                float v[CW];
+                cols_of(acc[nb], v);
+                const uint4 val = Piece<T>::pack(v);
+                uint64_t* gp = (uint64_t*)(base + (p0 + row) * (2 * D));
+                __hip_atomic_store(gp, (uint64_t)val.x | ((uint64_t)val.y << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                __hip_atomic_store(gp + 1, (uint64_t)val.z | ((uint64_t)val.w << 32), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
         }
-        // ---- publish: every thread's rows are written through before the flags go up
-        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+        lap(5);
+        // ---- publish: every thread's row stores have completed (the ring's loads with them) before the flags go up
+        __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+        __asm__ volatile("" ::: "memory");
         __syncthreads();
-        if (ctl[1]) break;                        // an aborted tile publishes nothing
-        if (tid < rows) __hip_atomic_store(&p.flags[p0 + tid], 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+        if (ctl[8]) break;                        // an aborted tile publishes nothing
+        if (tid < rows) __hip_atomic_store(&p.flags[p0 + tid], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        lap(6);
     }
+    if (TIMERS && tid == 0)
+        for (int i = 0; i < 8; ++i) atomicAdd((unsigned long long*)&p.prof[i], (unsigned long long)prof[i]);
 }
 
-template <typename T, int D>
+template <typename T>
 int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
 {
-    using S = FlowShape<T, D>;
+    constexpr int D = 512 / (int)sizeof(T), E = 16 / (int)sizeof(T);
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
-    const size_t smem = S::smem(a.n_layers > 1);
-    void (*kern)(dg4_flow_args) = a.ell_w == 8 ? flow_kernel<T, D, 8> : a.ell_w == 16 ? flow_kernel<T, D, 16> : nullptr;
+    const size_t smem = 2 * (size_t)FT * (D + E) * sizeof(T) + 2 * 8 * FT * sizeof(float) + 64 +
+                        (a.n_layers > 1 ? (size_t)FT * (3 * D + E) * sizeof(T) : 0);
+    void (*kern)(dg4_flow_args) = nullptr;
+    if (a.ell_w == 8) kern = a.prof ? flow_kernel<T, 8, true> : flow_kernel<T, 8, false>;
+    else if (a.ell_w == 16) kern = a.prof ? flow_kernel<T, 16, true> : flow_kernel<T, 16, false>;
     if (!kern) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
-    // as many workgroups as stay resident (tiles are handed out by tickets, so fewer resident ones
-    // only cost speed): two per compute unit when the LDS allows it
-    const int per_cu = smem * 2 <= 160 * 1024 ? 2 : 1;
-    const int64_t grid = std::min<int64_t>((int64_t)cus * per_cu, a.n_tiles);
-    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(256), smem, s, a);
+    // one workgroup of eight waves per compute unit (tiles are handed out by tickets, so fewer
+    // resident ones would only cost speed)
+    const int64_t grid = std::min<int64_t>((int64_t)cus, a.n_tiles + a.n_pre);
+    hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FLOW_THREADS), smem, s, a);
     return hipGetLastError();
 }
 
@@ -360,9 +515,24 @@ bool dg4_flow_supports(int dtype, int hidden, int ell_w)
     return ((dtype == DG4_F32 && hidden == 128) || (dtype == DG4_BF16 && hidden == 256)) && (ell_w == 8 || ell_w == 16);
 }
 
+// `packed` takes columns [col0, col0 + n_cols) of the row-major weight w (row stride ld, hidden rows)
+// in the streaming order of the kernel above; n_cols a multiple of 16 * (hidden / 128)
+int dg4_launch_pack_wa(int dtype, int hidden, const void* w, int ld, int col0, int n_cols, void* packed, hipStream_t s)
+{
+    const int gt = hidden / 16 / 8;
+    if (gt < 1 || n_cols % (16 * gt)) return hipErrorInvalidValue;
+    const int64_t units = (int64_t)(n_cols / 16) * 8 * 64;
+    const unsigned grid = (unsigned)((units + 255) / 256);
+    if (dtype == DG4_F32)
+        hipLaunchKernelGGL(pack_wa_kernel<float>, dim3(grid), dim3(256), 0, s, (const float*)w, ld, col0, n_cols, gt, (float*)packed);
+    else
+        hipLaunchKernelGGL(pack_wa_kernel<uint16_t>, dim3(grid), dim3(256), 0, s, (const uint16_t*)w, ld, col0, n_cols, gt, (uint16_t*)packed);
+    return hipGetLastError();
+}
+
 int dg4_launch_flow(int dtype, int hidden, const dg4_flow_args& a, hipStream_t s)
 {
     if (a.n_tiles <= 0) return hipSuccess;
-    if (!dg4_flow_supports(dtype, hidden, a.ell_w) || a.n_layers < 1) return hipErrorInvalidValue;
-    return dtype == DG4_F32 ? launch_flow_t<float, 128>(a, s) : launch_flow_t<bf16_t, 256>(a, s);
+    if (!dg4_flow_supports(dtype, hidden, a.ell_w) || a.n_layers < 1 || a.n_pre * FT < a.pre_rows) return hipErrorInvalidValue;
+    return dtype == DG4_F32 ? launch_flow_t<float>(a, s) : launch_flow_t<bf16_t>(a, s);
 }

@@ -197,22 +197,25 @@ int dg4_launch_sweep(const dg4_sweep_args& a, hipStream_t s);
 struct dg4_flow_args {
     const uint2* tiles; int64_t tile_begin; int64_t n_tiles;   // tile t is tiles[tile_begin + t] = (first position, rows <= 32) ...
     int pairs;                             // ... or (pairs != 0) entries 2t and 2t+1 of the table together
+    int64_t n_pre; int64_t pre_rows;       // resumed sweeps: positions [0, pre_rows) are finished gates whose K | V come from h_out first, in n_pre = ceil(pre_rows / 32) extra tiles
     const uint32_t* ell; int ell_w;        // neighbour rows by position
     const int32_t* order;                  // position -> node id
     const void* x;                         // [n, d] by node id
     const void* qkv_self;                  // [n, 3d] by position: Q | K | V of x (layer 0)
     void* kv; int64_t kv_layer_stride;     // [layers][n, 2d] by position: K | V of the final embeddings; elements between layers
     void* h_out;                           // [n, d] by node id
-    const void* wqkv_packed; const void* wo_packed; int64_t w_layer_stride;   // dg4_launch_pack_w order; bytes from a layer's to the next's
-    const void* wkv_packed;                // [d, layers*2d] packed: K | V columns of every layer
+    const void* wqkv_packed; const void* wo_packed; int64_t w_layer_stride;   // dg4_launch_pack_wa order; bytes from a layer's to the next's
+    const void* wkv_packed;                // [layers][d, 2d] in dg4_launch_pack_wa order: K | V columns of every layer
     const float* rel_bias;                 // [layers][heads, 4]
     uint32_t* flags;                       // [n] by position: 1 = rows published
     uint32_t* ctrl;                        // [1] abort word, [2] ticket counter
+    uint64_t* prof;                        // nullable: 8 phase timers (10 ns ticks, summed over workgroups)
     int n_layers;
     float ln_eps; int epilogue; int project_kv;
     uint32_t spin_limit;
 };
 bool dg4_flow_supports(int dtype, int hidden, int ell_w);
+int dg4_launch_pack_wa(int dtype, int hidden, const void* w, int ld, int col0, int n_cols, void* packed, hipStream_t s);
 int dg4_launch_flow(int dtype, int hidden, const dg4_flow_args& a, hipStream_t s);
 
 // ---- bulk projection on the matrix cores (dg4_sweep.hip): bf16, hidden 256 ----

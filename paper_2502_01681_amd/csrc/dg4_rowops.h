@@ -15,14 +15,16 @@ namespace {
 // lane is number `sub`: every lane owns 32 contiguous bytes of each 512-byte (or 256 / 1024-byte) row
 // it touches and ends with its EPL elements of the row's result. `ent`: the packed neighbour row;
 // q_row, k_self, v_self: the destination's own rows (any address space); sources at k_src / v_src +
-// index * src_stride elements; rel_bias [heads, 4].
-template <typename T, int D, int W>
+// index * src_stride elements; rel_bias [heads, 4]. CH: neighbour rows requested together (a matter of
+// latency against registers only: the arithmetic of a row does not depend on it). V_EARLY (needs CH == W):
+// the V rows are requested together with the K rows, before the scores are formed.
+template <typename T, int D, int W, int CH = (W < 8 ? W : 8), bool V_EARLY = false>
 __device__ __forceinline__ void attend_core(const uint32_t (&ent)[W], const T* q_row, const T* k_self, const T* v_self,
                                             const T* k_src, const T* v_src, int64_t src_stride, const float* rel_bias,
                                             int sub, float (&acc)[Elem<T>::EPL])
 {
     constexpr int EPL = Elem<T>::EPL;
-    constexpr int CH = W < 8 ? W : 8;         // neighbour rows in flight per pass
+    static_assert(W % CH == 0, "whole passes");
     const int64_t eoff = (int64_t)sub * EPL;  // element offset of this lane inside a row
     const int head = (int)(eoff >> 5);
 
@@ -42,6 +44,8 @@ __device__ __forceinline__ void attend_core(const uint32_t (&ent)[W], const T* q
         return (const uint4*)(r + eoff);
     };
 
+    static_assert(!V_EARLY || CH == W, "all rows at once");
+    uint4 va0[V_EARLY ? W : 1], vb0[V_EARLY ? W : 1];
     // pass 1: scores
     float s[W];
     const float scale = 0.17677669529663687f;     // 1/sqrt(32)
@@ -55,6 +59,17 @@ __device__ __forceinline__ void attend_core(const uint32_t (&ent)[W], const T* q
                 ka[j] = kp[0]; kb[j] = kp[1];
             } else {
                 ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j];
+            }
+        }
+        if constexpr (V_EARLY) {
+#pragma unroll
+            for (int j = 0; j < W; ++j) {
+                if (ent[j] != DG4_ELL_PAD) {
+                    const uint4* vp = src_row(v_self, v_src, ent[j]);
+                    va0[j] = vp[0]; vb0[j] = vp[1];
+                } else {
+                    va0[j] = make_uint4(0, 0, 0, 0); vb0[j] = va0[j];
+                }
             }
         }
 #pragma unroll
@@ -87,7 +102,9 @@ __device__ __forceinline__ void attend_core(const uint32_t (&ent)[W], const T* q
         uint4 va[CH], vb[CH];
 #pragma unroll
         for (int j = 0; j < CH; ++j) {
-            if (ent[c0 + j] != DG4_ELL_PAD) {
+            if constexpr (V_EARLY) {
+                va[j] = va0[j]; vb[j] = vb0[j];
+            } else if (ent[c0 + j] != DG4_ELL_PAD) {
                 const uint4* vp = src_row(v_self, v_src, ent[c0 + j]);
                 va[j] = vp[0]; vb[j] = vp[1];
             } else {

@@ -1,5 +1,6 @@
 """The persistent dataflow kernel for every shape (fp32 / hidden 128, bf16 / hidden 256, cones of up to
-three hops, any number of layers) against the oracle and, bit for bit, against level-by-level launches.
+three hops, any number of layers) against the oracle, against level-by-level launches (other kernels,
+another summation order: equal up to rounding) and, bit for bit, against itself under other schedules.
 """
 import numpy as np
 import pytest
@@ -52,8 +53,8 @@ def test_flow_kernel_against_oracle_and_level_by_level(name, n_and, over):
     g, og = graphs(w)
     H = run(w, cfg_of(c), g, poison=True)
     assert not torch.isnan(H.float()).any()                      # every gate written
-    H_pl = run(w, cfg_of(c, per_level=True), g)
-    assert torch.equal(H, H_pl)                                  # the same arithmetic per gate: the same bits
+    H_pl = to_np(run(w, cfg_of(c, per_level=True), g))
+    assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= TOL[c.dtype]      # other kernels: equal up to rounding
     ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
     Hn = to_np(H)
     err = row_rel_err(Hn, ref)
@@ -70,7 +71,8 @@ def test_flow_kernel_without_epilogue():
     H = run(w, cfg, g)
     ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, w.cfg.heads, store="f32", epilogue=False)
     assert row_rel_err(to_np(H), ref).max() <= TOL["f32"]
-    assert torch.equal(H, run(w, cfg_of(w.cfg, epilogue=False, per_level=True), g))
+    H_pl = to_np(run(w, cfg_of(w.cfg, epilogue=False, per_level=True), g))
+    assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= TOL["f32"]
 
 
 @pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {})])
