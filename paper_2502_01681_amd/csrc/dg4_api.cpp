@@ -365,8 +365,13 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // every shape does that itself, with its own arithmetic)
     if (P0 > 0 && !bounded && !flow) HIPCHK(kv_project(Hout, d, g->d_order, 0, P0));
 
-    // optional timing of the persistent kernel alone
+    // optional timing of the persistent kernel alone (a call that runs none leaves nothing to read back)
     const bool timed = (cfg->flags & DG4_TIME_SWEEP) != 0 && (resident || flow);
+    if ((cfg->flags & DG4_TIME_SWEEP) && !timed) {
+        SweepEvents& ev = sweep_events();
+        std::lock_guard<std::mutex> lock(ev.mu);
+        ev.armed = false;
+    }
     auto bracket = [&](auto&& launch) -> int {
         if (!timed) return launch();
         SweepEvents& ev = sweep_events();

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include <memory>
+#include <type_traits>
 #include <mutex>
 #include <vector>
 
@@ -229,3 +230,15 @@ struct dg4_bulk_args {
 };
 int dg4_launch_pack_w32(const void* w, int ld, void* packed, hipStream_t s);   // [256, 768] weights, row stride ld
 int dg4_launch_bulk_proj(const dg4_bulk_args& a, hipStream_t s);
+
+// Every kernel takes its argument block by value: plain data of pointer alignment, well inside the
+// kernel-argument segment (4 KB), value-initialised by every caller before the fields are set.
+#define DG4_CHECK_KERNEL_ARGS(S) \
+    static_assert(std::is_trivially_copyable<S>::value && std::is_standard_layout<S>::value && alignof(S) == 8 && sizeof(S) <= 1024, #S)
+DG4_CHECK_KERNEL_ARGS(dg4_attn_args);
+DG4_CHECK_KERNEL_ARGS(dg4_gemm_args);
+DG4_CHECK_KERNEL_ARGS(dg4_ffn_args);
+DG4_CHECK_KERNEL_ARGS(dg4_sweep_args);
+DG4_CHECK_KERNEL_ARGS(dg4_flow_args);
+DG4_CHECK_KERNEL_ARGS(dg4_bulk_args);
+#undef DG4_CHECK_KERNEL_ARGS

@@ -12,7 +12,7 @@ import torch
 import dg4_synth as synth
 import oracle
 import paper_2502_01681_amd as dg4
-from gpu_utils import TOL, cfg_of, device_weights, row_rel_err, tdtype, to_dev, to_np
+from gpu_utils import TOL, cfg_of, device_weights, elem_err, row_rel_err, tdtype, to_dev, to_np
 
 pytestmark = pytest.mark.gpu
 
@@ -53,6 +53,15 @@ def test_full_size_sampled(name, samples):
     dg4.dg4_layer_fwd(cfg, g, X, W, H2, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(H, H2)
+    if c.n_layers == 1:
+        # end to end: the oracle's own sweep over the whole circuit, every gate and every element
+        # (one layer: seconds of oracle time even for a million gates)
+        full = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
+        err, el = row_rel_err(Hn, full), elem_err(Hn, full)
+        print(f"  end to end, all {c.n_nodes} gates: max rel err {err.max():.3e} (p99.9 {np.quantile(err, 0.999):.3e}), "
+              f"max element err {el.max():.3e}", flush=True)
+        assert err.max() <= TOL[c.dtype]
+        assert el.max() <= 4 * TOL[c.dtype]
 
 
 @pytest.mark.parametrize("name", ["medium", "large"])
