@@ -177,13 +177,13 @@ def main():
                 "ms_kernel": float(np.mean(sweep_ms)) if len(sweep_ms) == steps else None, "H": H, "ws": ws, "cfg": hot}
 
     def path_of(c, g, flags):
-        if flags.get("per_level") or flags.get("bounded_kv") or g.hops > 3:
+        if flags.get("per_level") or flags.get("bounded_kv"):
             return "level-by-level launches"
         if c.dtype == "bf16" and c.hidden == 256 and c.n_layers == 1 and g.hops <= 2:
             return "sweep_kernel (persistent, weights resident in registers)"
         if flags.get("ffn"):
             return "level-by-level launches"
-        return "flow_kernel (persistent, weights streamed)"
+        return "flow_kernel (persistent, weights streamed" + (", several lane groups per neighbour row)" if g.hops > 3 else ")")
 
     t0 = time.perf_counter()
     over = {}

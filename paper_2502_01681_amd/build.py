@@ -33,6 +33,9 @@ def _flags():
             # MFMA accumulators in VGPRs: leaves the AGPR half of the register file to the
             # weights that the persistent sweep kernel keeps resident
             "-mllvm", "-amdgpu-mfma-vgpr-form=1",
+            # no wave-wide rewriting of atomics: the ticket draws of the persistent kernels are single-lane
+            # already, and the rewriting makes the wave wait for the result on the spot
+            "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
             "-I", os.path.join(ROOT, "include"), "-I", CSRC,
             "-Wall", "-Wno-unused-function"]
 

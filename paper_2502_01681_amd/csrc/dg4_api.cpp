@@ -440,9 +440,15 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     if (flow) {
         // tiles of up to 32 mutually independent gates: the pairs of the dependency-driven order for a
         // sweep over all levels, runs inside a level otherwise
-        const bool whole = whole_range && !(cfg->flags & DG4_LEVEL_ORDER);
+        // (rows wider than 16 entries: always level by level, tiles of a few gates)
+        const bool wide = g->ell_w > 16;
+        const bool whole = whole_range && !(cfg->flags & DG4_LEVEL_ORDER) && !wide;
         if (whole) {
             rc = dg4_graph_ensure_pairs(g);
+            if (rc != DG4_OK) return rc;
+        }
+        if (wide) {
+            rc = dg4_graph_ensure_wide_tiles(g);
             if (rc != DG4_OK) return rc;
         }
         const int32_t* order_in_use = whole ? g->d_pair_order : g->d_order;
@@ -479,6 +485,11 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             a.tiles = g->d_pair_tiles; a.pairs = narrow ? 0 : 1; a.tile_begin = 0;
             a.n_tiles = narrow ? g->n_pair_tiles : g->n_pair_tiles / 2;
             a.ell = g->d_pair_ell;
+        } else if (wide) {
+            a.tiles = g->d_tilesw; a.pairs = 0; a.tile_rows = g->wide_tile_rows;
+            a.tile_begin = g->level_tilew_ptr[level_begin];
+            a.n_tiles = g->level_tilew_ptr[level_end] - a.tile_begin;
+            a.ell = g->d_ell_pos;
         } else {
             a.tiles = g->d_tiles32; a.pairs = 0; a.tile_begin = g->level_tile32_ptr[level_begin];
             a.n_tiles = g->level_tile32_ptr[level_end] - a.tile_begin;

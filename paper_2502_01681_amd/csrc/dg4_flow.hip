@@ -132,6 +132,10 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
     constexpr int E = 16 / (int)sizeof(T);
     constexpr int EPL = Elem<T>::EPL, LPR = D / EPL;
     static_assert(LPR == 16 && AW <= LPR, "16 lanes per gate in the attention, one per neighbour entry while waiting");
+    // AW == 0: neighbour rows of any width (a multiple of four entries; cones deeper than three hops).
+    // Tiles then hold p.tile_rows <= 16 gates and 32 / tile_rows lane groups share a gate's row.
+    constexpr bool WIDE = AW == 0;
+    constexpr int AWN = WIDE ? 1 : AW;
     constexpr int GT = D / 16 / 8;                // 16-column tiles per group (1 or 2): a wave's share of D columns
     constexpr int CW = 4 * GT;                    // consecutive columns a lane owns (16 bytes)
     static_assert(CW == Piece<T>::N, "a lane's columns are one 16-byte piece");
@@ -242,9 +246,9 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
     }
     fill_ring(group_ptr(p.wo_packed, wave));      // layer 0's output projection, this wave's columns
     // the neighbour row of this lane group's gate in the NEXT tile, requested in the middle of a tile
-    uint32_t ent_n[AW], watch_n = DG4_ELL_PAD;
+    uint32_t ent_n[AWN], watch_n = DG4_ELL_PAD;
 #pragma unroll
-    for (int j = 0; j < AW; ++j) ent_n[j] = DG4_ELL_PAD;
+    for (int j = 0; j < AWN; ++j) ent_n[j] = DG4_ELL_PAD;
     bool have_next = false;                       // ent_n / watch_n hold the row of this tile (workgroup-uniform)
     for (int it = 0;; ++it) {
         __syncthreads();                          // the descriptor; the previous tile is done with every buffer
@@ -283,19 +287,55 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             }
         }
 
-        // ---- the sources of this lane group's gate must be published: lane `sub` watches entry `sub` of its row
+        // ---- the sources of the tile's gates must be published
         const bool attends = arow < live && !pre; // (whole waves: 4 gates per wave)
         const int64_t apos = pos_of(arow);
-        uint32_t ent[AW];
-        if (attends) {
+        uint32_t ent[AWN];
+        auto give_up = [&](uint32_t spins) __attribute__((always_inline)) -> bool {
+            if (spins > p.spin_limit ||
+                ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
+                // the tile is computed from whatever is there (every access stays in bounds),
+                // nothing of it is published, and the workgroup leaves after it
+                if (lane == 0) {
+                    __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    ctl[8] = 1;
+                }
+                return true;
+            }
+            return false;
+        };
+        if constexpr (WIDE) {
+            // 512 / tile_rows lanes per gate, each watching every (512 / tile_rows)-th entry of its row
+            const int LR = FLOW_THREADS / p.tile_rows;
+            const int wrow = tid / LR, wl = tid % LR;
+            const bool act = !pre && wrow < rows;
+            const uint32_t* erow = p.ell + (p0 + (act ? wrow : 0)) * (int64_t)p.ell_w;
+            uint32_t spins = 0;
+            for (;;) {
+                bool ok = true;
+                if (act)
+                    for (int i = wl; i < p.ell_w; i += LR) {
+                        const uint32_t e = erow[i];
+                        if (e != DG4_ELL_PAD && (e >> 30) != 0 &&
+                            __hip_atomic_load(p.flags + (e & 0x3FFFFFFFu), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == 0u) ok = false;
+                    }
+                if (__ballot(!ok) == 0) break;
+                __builtin_amdgcn_s_sleep(1);
+                if (give_up(++spins)) break;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            __syncthreads();                      // a gate's entries were watched by several waves
+            ent[0] = DG4_ELL_PAD;
+        } else if (attends) {
+            // lane `sub` of a gate's lane group watches entry `sub` of its row
             uint32_t e;
             if (have_next) {
 #pragma unroll
-                for (int j = 0; j < AW; ++j) ent[j] = ent_n[j];
+                for (int j = 0; j < AWN; ++j) ent[j] = ent_n[j];
                 e = watch_n;
             } else {
-                load_entries<AW>(p.ell, apos, ent);
-                e = sub < AW ? p.ell[apos * AW + sub] : DG4_ELL_PAD;
+                load_entries<AWN>(p.ell, apos, ent);
+                e = sub < AWN ? p.ell[apos * AWN + sub] : DG4_ELL_PAD;
             }
             const bool watch = e != DG4_ELL_PAD && (e >> 30) != 0;
             const uint32_t* f = p.flags + (watch ? (e & 0x3FFFFFFFu) : 0u);
@@ -304,23 +344,14 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                 const bool ok = !watch || __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
                 if (__ballot(!ok) == 0) break;
                 __builtin_amdgcn_s_sleep(1);
-                if (++spins > p.spin_limit ||
-                    ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
-                    // give up: the tile is computed from whatever is there (every access stays in
-                    // bounds), nothing of it is published, and the workgroup leaves after it
-                    if (lane == 0) {
-                        __hip_atomic_store(&p.ctrl[1], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                        ctl[8] = 1;
-                    }
-                    break;
-                }
+                if (give_up(++spins)) break;
             }
             // (the flag loads above are the only ordering needed, see the head of the file; the fence
             // keeps the compiler from moving row loads above them)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         } else {
 #pragma unroll
-            for (int j = 0; j < AW; ++j) ent[j] = DG4_ELL_PAD;
+            for (int j = 0; j < AWN; ++j) ent[j] = DG4_ELL_PAD;
         }
         if (TIMERS) __syncthreads();
         lap(1);
@@ -337,12 +368,118 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             // ---- attention of layer l: the gate's own Q, K, V from the projection of x (layer 0) or
             // from LDS (its running state, projected at the end of the previous layer); sources from
             // the store of finished gates, layer l
-            if (attends) {
+            if constexpr (WIDE) {
+                // S = 32 / tile_rows lane groups share a gate: group `part` walks the chunks of eight
+                // entries part, part + S, ... with a running maximum, denominator and weighted sum
+                // (the softmax is unchanged by the rescaling); the S partial results are merged
+                // through LDS by the first group, always in the same order.
+                const int S = FLOW_THREADS / 16 / p.tile_rows;
+                const int grp = tid >> 4, r = grp / S, part = grp % S;
+                const bool act = r < rows;
+                const int64_t eoff = (int64_t)sub * EPL;
+                float m = -INFINITY, z = 0.f;
+                float av[EPL];
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) av[i] = 0.f;
+                if (act) {
+                    const T* kvl = (const T*)p.kv + (int64_t)l * p.kv_layer_stride;
+                    const T* qrow = l == 0 ? (const T*)p.qkv_self + (p0 + r) * (3 * D) : qkvbuf + r * QS;
+                    float q[EPL];
+                    {
+                        const uint4* qp = (const uint4*)(qrow + eoff);
+                        Elem<T>::unpack(qp[0], qp[1], q);
+                    }
+                    const float* bp = p.rel_bias + l * (D / 32) * 4 + (int)(eoff >> 5) * 4;
+                    const float bias[4] = { bp[0], bp[1], bp[2], bp[3] };
+                    const float scale = 0.17677669529663687f;     // 1/sqrt(32)
+                    const uint32_t* erow = p.ell + (p0 + r) * (int64_t)p.ell_w;
+                    for (int c0 = part * 8; c0 < p.ell_w; c0 += S * 8) {
+                        uint32_t en[8];
+                        {
+                            const uint4 e0 = *(const uint4*)(erow + c0);
+                            const uint4 e1 = c0 + 4 < p.ell_w ? *(const uint4*)(erow + c0 + 4)
+                                                              : make_uint4(DG4_ELL_PAD, DG4_ELL_PAD, DG4_ELL_PAD, DG4_ELL_PAD);
+                            en[0] = e0.x; en[1] = e0.y; en[2] = e0.z; en[3] = e0.w; en[4] = e1.x; en[5] = e1.y; en[6] = e1.z; en[7] = e1.w;
+                        }
+                        if (en[0] == DG4_ELL_PAD) break;          // rows are padded at the end only
+                        uint4 ka[8], kb[8], va[8], vb[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            if (en[j] != DG4_ELL_PAD) {
+                                const T* kr = (en[j] >> 30) == 0 ? qrow + D : kvl + (int64_t)(en[j] & 0x3FFFFFFFu) * (2 * D);
+                                const uint4* kp = (const uint4*)(kr + eoff);
+                                const uint4* vp = (const uint4*)(kr + D + eoff);
+                                ka[j] = kp[0]; kb[j] = kp[1]; va[j] = vp[0]; vb[j] = vp[1];
+                            } else {
+                                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j]; va[j] = ka[j]; vb[j] = ka[j];
+                            }
+                        }
+                        float sc[8];
+                        float cm = m;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            float k[EPL];
+                            Elem<T>::unpack(ka[j], kb[j], k);
+                            float dot = 0.f;
+#pragma unroll
+                            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
+                            dot = Elem<T>::head_sum(dot);
+                            const uint32_t rel = en[j] >> 30;
+                            const float bb = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+                            sc[j] = en[j] != DG4_ELL_PAD ? fmaf(dot, scale, bb) : -INFINITY;
+                            cm = fmaxf(cm, sc[j]);
+                        }
+                        const float corr = __expf(m - cm);        // 0 on the first chunk (m = -inf, cm finite)
+                        z *= corr;
+#pragma unroll
+                        for (int i = 0; i < EPL; ++i) av[i] *= corr;
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            float v[EPL];
+                            Elem<T>::unpack(va[j], vb[j], v);
+                            const float pj = __expf(sc[j] - cm);  // 0 for padding
+                            z += pj;
+#pragma unroll
+                            for (int i = 0; i < EPL; ++i) av[i] = fmaf(pj, v[i], av[i]);
+                        }
+                        m = cm;
+                    }
+                }
+                float* mrg = (float*)(qkvbuf + (L > 1 ? FT * QS : 0));           // [EPL + 2][512]
+                mrg[EPL * FLOW_THREADS + tid] = m;
+                mrg[(EPL + 1) * FLOW_THREADS + tid] = z;
+#pragma unroll
+                for (int i = 0; i < EPL; ++i) mrg[i * FLOW_THREADS + tid] = av[i];
+                __syncthreads();
+                if (act && part == 0) {
+                    // (this group holds the row's first chunk, so its maximum is finite)
+                    float mm = m;
+                    for (int s2 = 1; s2 < S; ++s2) mm = fmaxf(mm, mrg[EPL * FLOW_THREADS + tid + 16 * s2]);
+                    const float c0f = __expf(m - mm);
+                    z *= c0f;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) av[i] *= c0f;
+                    for (int s2 = 1; s2 < S; ++s2) {
+                        const int t2 = tid + 16 * s2;
+                        const float cs = __expf(mrg[EPL * FLOW_THREADS + t2] - mm);   // 0 for a part that saw no entry
+                        z = fmaf(mrg[(EPL + 1) * FLOW_THREADS + t2], cs, z);
+#pragma unroll
+                        for (int i = 0; i < EPL; ++i) av[i] = fmaf(mrg[i * FLOW_THREADS + t2], cs, av[i]);
+                    }
+                    const float rz = 1.0f / z;
+#pragma unroll
+                    for (int i = 0; i < EPL; ++i) av[i] *= rz;
+                    uint4 oa, ob;
+                    Elem<T>::pack(av, oa, ob);
+                    uint4* op = (uint4*)&ybuf[r * YS + sub * EPL];
+                    op[0] = oa; op[1] = ob;
+                }
+            } else if (attends) {
                 const T* kvl = (const T*)p.kv + (int64_t)l * p.kv_layer_stride;
                 const T* qrow = l == 0 ? (const T*)p.qkv_self + apos * (3 * D) : qkvbuf + arow * QS;
                 float av[EPL];
-                attend_core<T, D, AW, 8, AW == 8>(ent, qrow, qrow + D, qrow + 2 * D, kvl, kvl + D, 2 * D,
-                                          p.rel_bias + l * (D / 32) * 4, sub, av);
+                attend_core<T, D, AWN, AWN < 8 ? AWN : 8, AWN == 8>(ent, qrow, qrow + D, qrow + 2 * D, kvl, kvl + D, 2 * D,
+                                                                    p.rel_bias + l * (D / 32) * 4, sub, av);
                 uint4 oa, ob;
                 Elem<T>::pack(av, oa, ob);
                 uint4* op = (uint4*)&ybuf[arow * YS + sub * EPL];
@@ -409,7 +546,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             __syncthreads();                      // ybuf = s_{l+1}, rounded to T; the next tile's descriptor
             lap(3);
             load_rows(ybuf, b);
-            if (l == 0) {
+            if (l == 0 && !WIDE) {
                 // the neighbour row this lane group will need at the top of the next tile
                 const int nslot = 4 * ((it + 1) & 1);
                 have_next = ctl[nslot] == 1;
@@ -417,8 +554,8 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                     const int nrows = ctl[nslot + 2];
                     if (arow < (nrows > 16 ? FT : 16)) {
                         const int64_t npos = (int64_t)ctl[nslot + 1] + (arow < nrows ? arow : nrows - 1);
-                        load_entries<AW>(p.ell, npos, ent_n);
-                        watch_n = sub < AW ? p.ell[npos * AW + sub] : DG4_ELL_PAD;
+                        load_entries<AWN>(p.ell, npos, ent_n);
+                        watch_n = sub < AWN ? p.ell[npos * AWN + sub] : DG4_ELL_PAD;
                     }
                 }
             }
@@ -493,11 +630,15 @@ int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
+    const bool wide = a.ell_w > 16;
     const size_t smem = 2 * (size_t)FT * (D + E) * sizeof(T) + 2 * 8 * FT * sizeof(float) + 64 +
-                        (a.n_layers > 1 ? (size_t)FT * (3 * D + E) * sizeof(T) : 0);
+                        (a.n_layers > 1 ? (size_t)FT * (3 * D + E) * sizeof(T) : 0) +
+                        (wide ? (size_t)(Elem<T>::EPL + 2) * FLOW_THREADS * sizeof(float) : 0);
     void (*kern)(dg4_flow_args) = nullptr;
     if (a.ell_w == 8) kern = a.prof ? flow_kernel<T, 8, true> : flow_kernel<T, 8, false>;
     else if (a.ell_w == 16) kern = a.prof ? flow_kernel<T, 16, true> : flow_kernel<T, 16, false>;
+    else if (wide && a.ell_w % 4 == 0 && !a.pairs && (a.tile_rows == 2 || a.tile_rows == 4 || a.tile_rows == 8 || a.tile_rows == 16))
+        kern = a.prof ? flow_kernel<T, 0, true> : flow_kernel<T, 0, false>;
     if (!kern) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
@@ -512,7 +653,8 @@ int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
 
 bool dg4_flow_supports(int dtype, int hidden, int ell_w)
 {
-    return ((dtype == DG4_F32 && hidden == 128) || (dtype == DG4_BF16 && hidden == 256)) && (ell_w == 8 || ell_w == 16);
+    return ((dtype == DG4_F32 && hidden == 128) || (dtype == DG4_BF16 && hidden == 256)) &&
+           (ell_w == 8 || ell_w == 16 || (ell_w > 16 && ell_w % 4 == 0));
 }
 
 // `packed` takes columns [col0, col0 + n_cols) of the row-major weight w (row stride ld, hidden rows)

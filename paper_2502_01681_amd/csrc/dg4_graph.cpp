@@ -2,6 +2,7 @@
 // validation, logic levels (Eq. 1), the (level, id) order and the cone_k
 // neighbour rows with relation codes, plus the upload of the device tables.
 #include <algorithm>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <queue>
@@ -618,7 +619,8 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
                 for_each_fanin(v, [&](int32_t u) { fo[(size_t)fill[u]++] = (int32_t)v; });
         }
         // the ready list is a queue of batches, one per tile, each sorted by (level, id)
-        auto before = [&](int32_t a, int32_t b) { return g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };
+        const bool by_id = getenv("DG4_FLOW_TIEBREAK") != nullptr;     // experiment
+        auto before = [&](int32_t a, int32_t b) { return !by_id && g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };
         std::vector<int32_t> ready;                 // the queue: taken from `head`, appended at the end
         ready.reserve((size_t)g->n);
         for (int64_t v = 0; v < g->n; ++v)
@@ -867,6 +869,38 @@ int dg4_graph_ensure_device(dg4_graph* g)
     return DG4_OK;
 }
 
+// Tiles for the persistent sweep over rows wider than 16 entries: runs of a few positions inside a
+// level. The wider the rows, the fewer gates share a tile (and the more lanes walk a gate's row):
+// the number depends on the width of the table alone, so that a gate's arithmetic does not depend
+// on the range of levels a call covers.
+int dg4_graph_ensure_wide_tiles(dg4_graph* g)
+{
+    std::lock_guard<std::mutex> lock(g->mu);
+    if (g->d_tilesw) return DG4_OK;
+    if (!g->on_device || g->ell_w <= 16) return DG4_EINVAL;
+    const int rows = g->ell_w <= 32 ? 16 : g->ell_w <= 64 ? 8 : g->ell_w <= 128 ? 4 : 2;
+    try {
+        std::vector<uint2> tiles;
+        g->level_tilew_ptr.assign((size_t)g->max_level + 2, 0);
+        for (int32_t l = 0; l <= g->max_level; ++l) {
+            g->level_tilew_ptr[l] = (int64_t)tiles.size();
+            for (int64_t p0 = g->level_ptr[l]; p0 < g->level_ptr[l + 1]; p0 += rows)
+                tiles.push_back(make_uint2((uint32_t)p0, (uint32_t)std::min<int64_t>(rows, g->level_ptr[l + 1] - p0)));
+        }
+        g->level_tilew_ptr[(size_t)g->max_level + 1] = (int64_t)tiles.size();
+        uint2* d = nullptr;
+        if (hipMalloc((void**)&d, std::max<size_t>(tiles.size(), 1) * sizeof(uint2)) != hipSuccess) return DG4_ENOMEM;
+        if (!tiles.empty() && hipMemcpy(d, tiles.data(), tiles.size() * sizeof(uint2), hipMemcpyHostToDevice) != hipSuccess) {
+            (void)hipFree(d);
+            return DG4_EHIP;
+        }
+        g->d_tilesw = d; g->wide_tile_rows = rows;
+    } catch (const std::bad_alloc&) {
+        return DG4_ENOMEM;
+    }
+    return DG4_OK;
+}
+
 // Device tables of the (Eq. 1 level, id) order, see dg4_graph::eq1_level_ptr.
 int dg4_graph_ensure_eq1(dg4_graph* g)
 {
@@ -1000,6 +1034,7 @@ extern "C" void dg4_graph_free(dg4_graph* g)
     if (g->d_order) (void)hipFree(g->d_order);
     if (g->d_tiles) (void)hipFree(g->d_tiles);
     if (g->d_tiles32) (void)hipFree(g->d_tiles32);
+    if (g->d_tilesw) (void)hipFree(g->d_tilesw);
     if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);
     if (g->d_flow_order) (void)hipFree(g->d_flow_order);
     if (g->d_flow_tiles) (void)hipFree(g->d_flow_tiles);

@@ -58,9 +58,13 @@ struct dg4_graph {
     // tiles of the persistent sweep: runs of <= DG4_TILE_ROWS positions inside one level
     std::vector<int64_t> level_tile_ptr;   // [n_levels + 1] first tile of each level
     uint2* d_tiles = nullptr;        // [n_tiles] (first position, rows)
-    // the same with runs of <= 32 positions (the persistent kernel for every shape)
+    // the same with runs of <= 32 positions (the persistent kernel for every shape), and, for rows wider
+    // than 16 entries, of <= wide_tile_rows positions (on first use)
     std::vector<int64_t> level_tile32_ptr;
     uint2* d_tiles32 = nullptr;
+    int wide_tile_rows = 0;
+    std::vector<int64_t> level_tilew_ptr;
+    uint2* d_tilesw = nullptr;
     // A second processing order for sweeps over ALL levels: tiles filled by list scheduling over
     // the real dependencies (a gate goes as early as its sources allow, sources long finished
     // first), not level by level. Host copy (node ids in processing order, first position of
@@ -103,6 +107,7 @@ int dg4_pair_schedule(dg4_graph* g);   // caller holds g->mu
 int dg4_graph_ensure_frontier(dg4_graph* g);           // after dg4_graph_ensure_device
 int dg4_graph_ensure_struct(dg4_graph* g);
 int dg4_graph_ensure_pairs(dg4_graph* g);              // after dg4_graph_ensure_device
+int dg4_graph_ensure_wide_tiles(dg4_graph* g);         // after dg4_graph_ensure_device; graphs with rows wider than 16 entries
 int dg4_graph_ensure_eq1(dg4_graph* g);                // after dg4_graph_ensure_device; needs eq1_level_ptr
 
 // ---- structural encoding (dg4_kernels.hip) ----
@@ -200,6 +205,7 @@ struct dg4_flow_args {
     int pairs;                             // ... or (pairs != 0) entries 2t and 2t+1 of the table together
     int64_t n_pre; int64_t pre_rows;       // resumed sweeps: positions [0, pre_rows) are finished gates whose K | V come from h_out first, in n_pre = ceil(pre_rows / 32) extra tiles
     const uint32_t* ell; int ell_w;        // neighbour rows by position
+    int tile_rows;                         // rows wider than 16 entries: most gates of a tile (2, 4, 8 or 16; no pairs)
     const int32_t* order;                  // position -> node id
     const void* x;                         // [n, d] by node id
     const void* qkv_self;                  // [n, 3d] by position: Q | K | V of x (layer 0)

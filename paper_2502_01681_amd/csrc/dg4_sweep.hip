@@ -5,13 +5,15 @@
 // cone sources and is itself computed once. Work is cut into tiles of at most 16
 // gates, in an order in which every source of a gate sits in an earlier tile:
 // level by level, or (whole-graph sweeps) list-scheduled over the dependencies.
-// One workgroup per compute unit; workgroup b owns tiles b, b + G, b + 2G, ...
-// A tile waits only on the "published" flags of ITS sources, so many levels are
-// in flight at once while every gate still sees exactly the values the
-// level-by-level sweep would give it. A tile waits only for lower-numbered
-// tiles, and those belong to workgroups that are running, so the wait always
-// ends; a bounded spin count turns any violation into an abort flag instead of
-// a hang.
+// One workgroup per compute unit; workgroups draw tiles from a ticket counter,
+// three tiles ahead of the one they work on (the descriptors of the next two
+// travel while a tile is computed). A tile waits only on the "published" flags
+// of ITS sources, so many levels are in flight at once while every gate still
+// sees exactly the values the level-by-level sweep would give it. A tile waits
+// only for lower-numbered tiles; those were drawn earlier, by workgroups that
+// are running and that take their own tiles in ascending order, so the wait
+// always ends, whether or not every workgroup of the launch is resident. A
+// bounded spin count turns any violation into an abort flag instead of a hang.
 //
 // With the weights resident in registers (Wo in vector registers, Wk|Wv in the
 // accumulation registers) there is ONE wave per SIMD: nothing hides latency for
@@ -260,6 +262,15 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
     };
     roles();
     const uint32_t wave_land = lds0 + (uint32_t)(SMEM_LAND + 4 * wave * LAND_GATE);   // landing zone of this wave's gates
+    // a ticket for a tile (a pair of tiles with the feed-forward sub-block): one lane only
+    auto draw = [&]() __attribute__((always_inline)) -> int {
+        const int k = (int)__hip_atomic_fetch_add(&p.ctrl[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return FFN ? 2 * k : k;
+    };
+    // the first one now, the next two once the weights are in (the other workgroups start within
+    // microseconds of this one, so the draws interleave: first tiles first)
+    int first_ticket = 0;
+    if (threadIdx.x == 0) first_ticket = draw();
 
     // The weights of this wave stay in registers for the whole kernel: its 4 column tiles of Wo
     // (128 vector registers) and its 8 column tiles of Wk|Wv (all 256 accumulation registers,
@@ -412,25 +423,33 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         __asm__ volatile("" ::: "memory");
     };
 
-    // Tiles are dealt round-robin: workgroup b owns tiles b, b + G, b + 2G, ... (G = grid size,
-    // one workgroup per compute unit, so all of them are resident together). A tile waits only
-    // for lower-numbered tiles, each owned by a workgroup that is running.
-    const int64_t G = gridDim.x;
+    // Tiles are handed out by tickets (p.ctrl[2], zero at launch): a workgroup holds the tile it works
+    // on and the next two, drawn in ascending order, and draws one more per tile; the drawn number
+    // reaches the other waves through LDS. With the feed-forward sub-block a ticket is a PAIR of
+    // tiles (2k, 2k+1) that one workgroup runs back to back; the table then holds an even number of
+    // tiles. Tickets past the end are clamped where a descriptor is fetched (harmless, unused).
     // (Dealing runs of consecutive tiles to one XCD, so that gates sharing a source share an L2, was
     // measured and is not worth it: 80 % of a tile's source rows are distinct already inside the
     // tile, 71 % inside 32 consecutive tiles.)
-    // With the feed-forward sub-block tiles come in pairs (2k, 2k+1) that one workgroup runs back
-    // to back: workgroup b owns pairs b, b + G, ...; the table then holds an even number of tiles.
-    auto next_of = [&](int64_t t) __attribute__((always_inline)) -> int64_t {
-        return FFN ? ((t & 1) ? t + 2 * G - 1 : t + 1) : t + G;
-    };
-    int64_t ticket = FFN ? 2 * (int64_t)blockIdx.x : (int64_t)blockIdx.x;
-    if (ticket >= p.n_tiles) return;
-    // (tickets past the end are clamped: the fetch is harmless and its result unused)
+    int* sTick = (int*)(smem + SMEM_ABORT) + 1;
+    // (thread 0 keeps one more drawn ticket in `spare`: a draw takes about as long as a third of a
+    // tile, so what a tile hands to the other waves was drawn during the tile before)
+    int spare = 0;
+    if (threadIdx.x == 0) {
+        sTick[0] = first_ticket;
+        sTick[1] = FFN ? first_ticket + 1 : draw();
+        sTick[2] = draw();
+        spare = draw();
+    }
+    __syncthreads();
+    int q0 = __builtin_amdgcn_readfirstlane(sTick[0]);            // this tile, the next one, the one after
+    int q1 = __builtin_amdgcn_readfirstlane(sTick[1]);
+    int q2 = __builtin_amdgcn_readfirstlane(sTick[2]);
+    if (q0 >= p.n_tiles) return;
     const int64_t last = p.n_tiles - 1;
     int d0 = 0, d1 = 1, d2 = 2;                   // descriptor buffers of this tile, the next one, the one after
-    uint2 cur = tile_at(ticket);                                      // first position, rows
-    uint2 nxt = tile_at(next_of(ticket) < last ? next_of(ticket) : last);
+    uint2 cur = tile_at(q0);                                          // first position, rows
+    uint2 nxt = tile_at(q1 < last ? q1 : last);
     uint64_t late = 0, need_cur = 0;              // sources of the current tile not gathered yet / all of them
     {
         gather_desc(cur.x, 0);
@@ -460,8 +479,8 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
 
         const int64_t p0 = cur.x;
         const int rows = (int)cur.y;
-        const bool has_next = next_of(ticket) < p.n_tiles;
-        const bool second = FFN && (ticket & 1) != 0;         // second tile of a feed-forward pair
+        const bool has_next = q1 < p.n_tiles;
+        const bool second = FFN && (q0 & 1) != 0;             // second tile of a feed-forward pair
         const bool first = FFN && !second;
         roles();
 
@@ -504,9 +523,11 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (TIMERS) __syncthreads();          // timers only: charge every wave's wait to phase 1
         lap(1);
         // the descriptor two tiles ahead travels during the attention below
-        const int64_t after_next = next_of(next_of(ticket));
-        const uint2 nn = tile_at(after_next < last ? after_next : last);
+        const uint2 nn = tile_at(q2 < last ? q2 : last);
         gather_desc(nn.x, d2);
+        // the tile after those: the second of a pair follows its first, anything else takes the
+        // spare ticket (further down, where a wait that is there anyway has covered its draw)
+        const bool draws = !FFN || (q2 & 1) != 0;
         // A first look at the flags of the NEXT tile's sources (its descriptor came in a round
         // ago). Loaded by every lane, needed or not; looked at after the first attention round.
         uint32_t nent = DG4_ELL_PAD;
@@ -620,6 +641,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 __builtin_amdgcn_s_waitcnt(0x0F70);
                 __asm__ volatile("" ::: "memory");
                 if (!published) publish();        // the previous tile's row stores have completed too
+                if (draws && threadIdx.x == 0) { sTick[0] = spare; spare = draw(); }
                 need_nxt = __ballot(nneed);
                 const bool upl = nneed && looked(0) != 0u;
                 up_nxt = __ballot(upl);
@@ -698,6 +720,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (any_miss) look_async(nent, miss, 1);
         __syncthreads();                      // sA and the descriptor fetched above complete
         if (sAbort) { flush(); return; }
+        const int q3 = draws ? __builtin_amdgcn_readfirstlane(sTick[0]) : q2 + 1;
         lap(2);
         if (has_next) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
         if (second) {
@@ -1019,7 +1042,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
             flush();
             return;
         }
-        ticket = next_of(ticket);
+        q0 = q1; q1 = q2; q2 = q3;
         { const int t = d0; d0 = d1; d1 = d2; d2 = t; }
         cur = nxt; nxt = nn;
         need_cur = need_nxt; late = need_nxt & ~up_nxt;

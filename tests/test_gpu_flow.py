@@ -124,3 +124,29 @@ def test_flow_kernel_bounded_wait_and_packed_weights():
     dg4.dg4_layer_fwd(cfg_of(c, weights_packed=True), g, X, W, H3, workspace=ws)
     torch.cuda.synchronize()
     assert torch.equal(H, H3)
+
+
+@pytest.mark.parametrize("name,n_and,k,over", [("medium", 12_000, 8, {}), ("small", 6_000, 5, {}), ("medium", 6_000, 6, dict(n_layers=2))])
+def test_flow_kernel_on_wide_rows(name, n_and, k, over):
+    # cones deeper than three hops (rows of up to 2^(k+1)-1 sources, several lane groups per gate):
+    # against the oracle, against level-by-level launches, and bit for bit against a sweep cut in two
+    print(f"flow kernel, wide rows {name} n_and={n_and} k={k} {over}", flush=True)
+    w = make(name, n_and, hops=k, **over)
+    c = w.cfg
+    g, og = graphs(w)
+    assert int(np.diff(og.nbr_ptr).max()) > 16
+    cfg = cfg_of(c)
+    H = run(w, cfg, g, poison=True)
+    assert not torch.isnan(H.float()).any()
+    ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
+    Hn = to_np(H)
+    err = row_rel_err(Hn, ref)
+    print(f"  max rel err {err.max():.3e}, max element err {elem_err(Hn, ref).max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype]
+    H_pl = to_np(run(w, cfg_of(c, per_level=True), g))
+    assert row_rel_err(Hn, H_pl.astype(np.float64)).max() <= TOL[c.dtype]
+    assert torch.equal(H, run(w, cfg, g))
+    mid = g.n_levels // 2
+    H1 = run(w, cfg, g, 0, mid)
+    H2 = run(w, cfg, g, mid, None, H0=H1)
+    assert torch.equal(H2, H)

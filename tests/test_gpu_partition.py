@@ -58,8 +58,9 @@ def test_partitioned_layer(name, n_and, k, delta, batch, kw):
     if ffn:
         W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(W)]
     H = torch.full((n, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
-    dg4.dg4_layer_fwd(cfg, g, X, W, H)
+    ws = dg4.dg4_layer_fwd(cfg, g, X, W, H)
     torch.cuda.synchronize()
+    dg4.dg4_layer_status(cfg, g, ws)
     H = to_np(H)
     assert not np.isnan(H).any()
     err = row_rel_err(H, ref)
