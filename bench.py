@@ -92,6 +92,8 @@ def main():
                          "collected every STRIDE levels, mini-batches of BATCH cones) instead of the headline sweep")
     ap.add_argument("--no-partition-point", action="store_true",
                     help="skip the extra measurement of the partitioned layer (medium graph, k=8, stride 6, 128 cones)")
+    ap.add_argument("--level-order", action="store_true",
+                    help="the timed sweep follows the graph's own (assigned) levels (DG4_LEVEL_ORDER) and is priced on them")
     ap.add_argument("--per-level", action="store_true", help="force level-by-level launches (DG4_PER_LEVEL)")
     ap.add_argument("--bounded-kv", action="store_true", help="no K|V store (DG4_BOUNDED_KV)")
     ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
@@ -222,7 +224,7 @@ def main():
     torch.cuda.synchronize()
     t_upload = time.perf_counter() - t0
 
-    flags = dict(ffn=args.ffn, per_level=args.per_level, bounded_kv=args.bounded_kv)
+    flags = dict(ffn=args.ffn, per_level=args.per_level, bounded_kv=args.bounded_kv, level_order=args.level_order)
     r = time_layer(c, g, X, W, args.steps, args.warmup, **flags)
     ms_step, ms_dev = r["ms_wall"], r["ms_dev"]
     ms_kernel = r["ms_kernel"] if r["ms_kernel"] is not None else ms_dev
@@ -232,7 +234,7 @@ def main():
     layers = c.n_layers
     lev_eq1 = eq1_levels(w, c, g)
     depth_eq1 = int(lev_eq1.max()) + 1 if n_gates else 0
-    sched_level = g.array("level") if args.bounded_kv else lev_eq1       # (bounded sweeps go through the graph's own levels)
+    sched_level = g.array("level") if args.bounded_kv or args.level_order else lev_eq1       # (bounded sweeps go through the graph's own levels)
     compulsory, gathered = algorithmic_bytes(g, cfg, sched_level)
     comp_hint, _ = algorithmic_bytes(g, cfg, g.array("level"))
     # The persistent kernel performs every algorithmic transfer of the step itself (residual row in, H
@@ -256,7 +258,7 @@ def main():
                    "gates": n_gates, "neighbour_edges": nnz, "aig_edges": int(len(w.edge_src)),
                    "levels": g.n_levels, "eq1_depth": depth_eq1, "path": path_of(c, g, flags)},
         "roofline": {"bound": "hbm",
-                     "kernel": f"{kernel_name} (persistent level sweep, dependency-driven tile order)" if persistent
+                     "kernel": f"{kernel_name} (persistent level sweep, " + ("tiles by assigned level)" if args.level_order else "dependency-driven tile order)") if persistent
                                else "dg4_layer_fwd (all launches of one step)",
                      "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS,
@@ -293,12 +295,12 @@ def main():
     del r
 
     headline = args.workload == "large" and args.n_and is None and args.layers is None and not part and not args.ffn \
-        and not args.per_level and not args.bounded_kv
+        and not args.per_level and not args.bounded_kv and not args.level_order
 
     # For information: the same step with the tiles dealt strictly level by level (the graph's own,
     # assigned levels) instead of the library's dependency-driven order. Same results, bit for bit.
     # Priced on the assigned levels: that schedule cannot share a source between two of them.
-    if persistent and not args.no_level_order and not args.ffn and not part:
+    if persistent and not args.no_level_order and not args.level_order and not args.ffn and not part:
         lo = time_layer(c, g, X, W, args.steps, args.warmup, level_order=True)
         k = lo["ms_kernel"] if lo["ms_kernel"] is not None else lo["ms_dev"]
         out["level_order_tiles"] = {"step_ms_device": lo["ms_dev"], "kernel_ms": k,

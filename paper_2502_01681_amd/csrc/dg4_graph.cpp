@@ -619,8 +619,7 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
                 for_each_fanin(v, [&](int32_t u) { fo[(size_t)fill[u]++] = (int32_t)v; });
         }
         // the ready list is a queue of batches, one per tile, each sorted by (level, id)
-        const bool by_id = getenv("DG4_FLOW_TIEBREAK") != nullptr;     // experiment
-        auto before = [&](int32_t a, int32_t b) { return !by_id && g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };
+        auto before = [&](int32_t a, int32_t b) { return g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };
         std::vector<int32_t> ready;                 // the queue: taken from `head`, appended at the end
         ready.reserve((size_t)g->n);
         for (int64_t v = 0; v < g->n; ++v)
