@@ -211,7 +211,7 @@ def main():
     e_dev = [torch.from_numpy(a).cuda() for a in (w.edge_src, w.edge_dst, w.edge_inv)]
     h_dev = torch.from_numpy(w.level_hint).cuda() if w.level_hint is not None else None
     t_build_dev = None
-    for _ in range(2 if c.hops <= 3 else 0):
+    for _ in range(0 if part else 2):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         g_dev = dg4.dg4_build_levels_device(c.n_nodes, *e_dev, c.hops, h_dev)

@@ -122,12 +122,13 @@ int dg4_build_levels(int64_t n_nodes, int64_t n_edges,
  * the GPU, for an edge list that is already in DEVICE memory: edge_src, edge_dst, edge_inv and
  * level_hint (nullable) are device pointers. Levels are found in rounds over the fanin table (a gate
  * is finished one round after its fanins), the (level, id) order by a stable sort, each cone row by a
- * backward search from its gate. Every table of the resulting graph equals the host call's bit for
+ * backward search from its gate (up to three hops) or, for deeper cones, one hop at a time as a
+ * merge of the fanins' rows (about 9 bytes per neighbour entry of temporary memory then). Every table of the resulting graph equals the host call's bit for
  * bit. Synchronous: waits on `stream`; temporary device memory (about 160 bytes per node and 5 per neighbour entry) is
  * allocated and released inside the call, and the tables are copied to host memory, where the graph
  * object keeps them. Errors as dg4_build_levels; if an edge list has defects of several kinds, the
  * kind reported may differ from the host call's (which reports the first in edge order), and an
- * invalid hint on a cyclic graph gives EHINT. Also EHIP. hops above 3: EUNSUPPORTED (host call only).
+ * invalid hint on a cyclic graph gives EHINT. Also EHIP.
  */
 int dg4_build_levels_device(int64_t n_nodes, int64_t n_edges,
                             const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,

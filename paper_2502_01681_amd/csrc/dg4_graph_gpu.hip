@@ -145,6 +145,53 @@ __global__ void cone_kernel(int64_t n, int hops, const int32_t* fin, const uint8
     cnt[v] = c;
 }
 
+// Cones deeper than three hops, one hop at a time: cone_j(v) = {v} u cone_{j-1}(f0) u cone_{j-1}(f1) over
+// the fanins f0, f1 of v, as a merge of id-sorted rows (a gate with no fanin keeps {v}). One thread
+// per gate walks the two rows and its own id in step; FILL = false counts the distinct ids, FILL =
+// true writes them (ascending) and, if rel is given, their relation codes: 0 the gate itself, 1 / 2 a
+// direct fanin (plain / inverted: the shortest path decides, Section 3.5), 3 anything further.
+// prev_ptr == nullptr stands for the rows of zero hops ({u} for every u).
+template <bool FILL>
+__global__ void cone_merge_kernel(int64_t n, const int32_t* fin, const uint8_t* finv, const int32_t* deg,
+                                  const int64_t* prev_ptr, const int32_t* prev_idx,
+                                  int64_t* cnt, const int64_t* ptr, int32_t* idx, uint8_t* rel)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    const int d = deg[v];
+    const int32_t f0 = d > 0 ? fin[2 * v] : -1, f1 = d > 1 ? fin[2 * v + 1] : -1;
+    int64_t a = 0, a1 = 0, b = 0, b1 = 0;          // [a, a1) and [b, b1): the rows of f0 and f1
+    int32_t self0 = f0, self1 = f1;                // (zero hops: the row of u is u itself)
+    if (prev_ptr) {
+        if (f0 >= 0) { a = prev_ptr[f0]; a1 = prev_ptr[f0 + 1]; }
+        if (f1 >= 0) { b = prev_ptr[f1]; b1 = prev_ptr[f1 + 1]; }
+    } else {
+        a1 = f0 >= 0 ? 1 : 0; b1 = f1 >= 0 ? 1 : 0;
+    }
+    auto at_a = [&](int64_t i) { return prev_ptr ? prev_idx[i] : self0; };
+    auto at_b = [&](int64_t i) { return prev_ptr ? prev_idx[i] : self1; };
+    bool self_left = true;
+    int64_t out = FILL ? ptr[v] : 0, count = 0;
+    const int32_t none = 0x7FFFFFFF;
+    int32_t xa = a < a1 ? at_a(a) : none, xb = b < b1 ? at_b(b) : none;
+    for (;;) {
+        const int32_t xs = self_left ? (int32_t)v : none;
+        int32_t m = xa < xb ? xa : xb;
+        m = xs < m ? xs : m;
+        if (m == none) break;
+        if (FILL) {
+            idx[out] = m;
+            if (rel) rel[out] = m == (int32_t)v ? 0 : m == f0 ? (uint8_t)(1 + finv[2 * v]) : m == f1 ? (uint8_t)(1 + finv[2 * v + 1]) : (uint8_t)3;
+            ++out;
+        }
+        ++count;
+        if (xa == m) { ++a; xa = a < a1 ? at_a(a) : none; }
+        if (xb == m) { ++b; xb = b < b1 ? at_b(b) : none; }
+        if (xs == m) self_left = false;
+    }
+    if (!FILL) cnt[v] = count;
+}
+
 __global__ void compact_kernel(int64_t n, const int32_t* row_id, const uint8_t* row_rel, const int64_t* nbr_ptr,
                                int32_t* nbr_idx, uint8_t* nbr_rel)
 {
@@ -212,7 +259,7 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
                                        void* stream, dg4_graph** out)
 {
     if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
-    if (hops < 1 || hops > 3) return DG4_EUNSUPPORTED;
+    if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
     if (n >= (int64_t)0x3FFFFFFF) return DG4_EUNSUPPORTED;
     hipStream_t s = (hipStream_t)stream;
     try {
@@ -288,23 +335,54 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
         hipLaunchKernelGGL(level_ptr_kernel, dim3(blocks_for(n_ptr)), dim3(256), 0, s, n, sorted_level, n_ptr, level_ptr);
 
         // cones
-        GPU_ALLOC(row_id, int32_t, (size_t)n * MAXW, false);
-        GPU_ALLOC(row_rel, uint8_t, (size_t)n * MAXW, false);
         GPU_ALLOC(cnt, int64_t, (size_t)n + 1, true);
         GPU_ALLOC(nbr_ptr, int64_t, (size_t)n + 1, false);
-        hipLaunchKernelGGL(cone_kernel, dim3(nb), dim3(256), 0, s, n, (int)hops, fin, finv, deg, row_id, row_rel, cnt);
         size_t scan_bytes = 0;
         GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(nullptr, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
         GPU_ALLOC(scan_tmp, unsigned char, scan_bytes, false);
-        GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
         int64_t nnz = 0;
-        GPU_CHECK(hipMemcpyAsync(&nnz, nbr_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
-        GPU_CHECK(hipStreamSynchronize(s));
+        int32_t* nbr_idx = nullptr;
+        uint8_t* nbr_rel = nullptr;
+        if (hops <= 3) {
+            GPU_ALLOC(row_id, int32_t, (size_t)n * MAXW, false);
+            GPU_ALLOC(row_rel, uint8_t, (size_t)n * MAXW, false);
+            hipLaunchKernelGGL(cone_kernel, dim3(nb), dim3(256), 0, s, n, (int)hops, fin, finv, deg, row_id, row_rel, cnt);
+            GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
+            GPU_CHECK(hipMemcpyAsync(&nnz, nbr_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+            GPU_CHECK(hipStreamSynchronize(s));
+            if (!arena.reserve((size_t)nnz * 5 + 1024)) return DG4_ENOMEM;
+            nbr_idx = arena.get<int32_t>((size_t)nnz, false, s);
+            nbr_rel = arena.get<uint8_t>((size_t)nnz, false, s);
+            if (!nbr_idx || !nbr_rel) return DG4_ENOMEM;
+            hipLaunchKernelGGL(compact_kernel, dim3(nb), dim3(256), 0, s, n, row_id, row_rel, nbr_ptr, nbr_idx, nbr_rel);
+        } else {
+            // one hop at a time, rows of hop j from those of hop j - 1 (count, scan, fill); the row
+            // pointers of two consecutive hops alternate between two buffers
+            GPU_ALLOC(ptr_b, int64_t, (size_t)n + 1, false);
+            int64_t* ptr_cur = nbr_ptr;
+            int64_t* ptr_prev = nullptr;
+            int32_t* idx_prev = nullptr;
+            for (int32_t j = 1; j <= hops; ++j) {
+                hipLaunchKernelGGL(cone_merge_kernel<false>, dim3(nb), dim3(256), 0, s, n, fin, finv, deg,
+                                   (const int64_t*)ptr_prev, (const int32_t*)idx_prev, cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (uint8_t*)nullptr);
+                GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, ptr_cur, (int)(n + 1), s));
+                GPU_CHECK(hipMemcpyAsync(&nnz, ptr_cur + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+                GPU_CHECK(hipStreamSynchronize(s));
+                const bool final_hop = j == hops;
+                if (!arena.reserve((size_t)nnz * (final_hop ? 5 : 4) + 1024)) return DG4_ENOMEM;
+                int32_t* idx_cur = arena.get<int32_t>((size_t)nnz, false, s);
+                uint8_t* rel_cur = final_hop ? arena.get<uint8_t>((size_t)nnz, false, s) : nullptr;
+                if (!idx_cur || (final_hop && !rel_cur)) return DG4_ENOMEM;
+                hipLaunchKernelGGL(cone_merge_kernel<true>, dim3(nb), dim3(256), 0, s, n, fin, finv, deg,
+                                   (const int64_t*)ptr_prev, (const int32_t*)idx_prev, (int64_t*)nullptr, (const int64_t*)ptr_cur, idx_cur, rel_cur);
+                nbr_idx = idx_cur; nbr_rel = rel_cur;
+                ptr_prev = ptr_cur; idx_prev = idx_cur;
+                ptr_cur = ptr_cur == nbr_ptr ? ptr_b : nbr_ptr;
+            }
+            if (ptr_prev != nbr_ptr)             // the last hop's pointers, where the copies below expect them
+                GPU_CHECK(hipMemcpyAsync(nbr_ptr, ptr_prev, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
+        }
         g->nnz = nnz;
-        if (!arena.reserve((size_t)nnz * 5 + 1024)) return DG4_ENOMEM;
-        GPU_ALLOC(nbr_idx, int32_t, (size_t)nnz, false);
-        GPU_ALLOC(nbr_rel, uint8_t, (size_t)nnz, false);
-        hipLaunchKernelGGL(compact_kernel, dim3(nb), dim3(256), 0, s, n, row_id, row_rel, nbr_ptr, nbr_idx, nbr_rel);
 
         // fanout counts of the structural encoding
         GPU_ALLOC(out_and, int32_t, (size_t)n, true);
