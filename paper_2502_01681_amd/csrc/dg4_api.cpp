@@ -319,7 +319,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     const bool whole_range = level_begin == 0 && level_end == (int32_t)g->max_level + 1;
     const bool forced_levels = (cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) != 0;
     const bool resident = dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops <= 2 && !forced_levels && (!ffn || whole_range);
-    const bool flow = !resident && !forced_levels && !ffn && dg4_flow_supports(dt, d, g->ell_w);
+    const bool flow = !resident && !forced_levels && dg4_flow_supports(dt, d, g->ell_w) && (!ffn || g->ell_w <= 16);
     // a caller that has not changed the weights since its last call with this configuration, graph
     // and workspace vouches for the packed copies that call left behind
     const bool pack = !(cfg->flags & DG4_WEIGHTS_PACKED);
@@ -333,6 +333,12 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
                 else if (dt != DG4_BF16) HIPCHK(dg4_launch_pack_w(dt, W[0], 3 * d, 0, 3 * d, d, at(pl.wqkv[0]), s));
                 HIPCHK(dg4_launch_pack_wa(dt, d, W[WS * l + 1], d, 0, d, at(pl.wo[l]), s));
                 HIPCHK(dg4_launch_pack_wa(dt, d, W[WS * l], 3 * d, d, 2 * d, ws + pl.wkv_a + (size_t)l * 2 * d * d * es, s));
+                if (ffn) {      // W1 whole; W2 as four blocks of d input rows
+                    HIPCHK(dg4_launch_pack_wa(dt, d, W[WS * l + 3], 4 * d, 0, 4 * d, at(pl.w1[l]), s));
+                    for (int c4 = 0; c4 < 4; ++c4)
+                        HIPCHK(dg4_launch_pack_wa(dt, d, (const char*)W[WS * l + 4] + (size_t)c4 * d * d * es, d, 0, d,
+                                                  ws + pl.w2[l] + (size_t)c4 * d * d * es, s));
+                }
             } else if (!resident) {
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, 0, 3 * d, d, at(pl.wqkv[l]), s));
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 1], d, 0, d, d, at(pl.wo[l]), s));
@@ -340,7 +346,7 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             // K | V columns of layer l go to column tiles [l*2d/32, (l+1)*2d/32) of wkv_all
             if ((!resident && !flow) || (resident && level_begin > 0))
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l], 3 * d, d, 2 * d, d, ws + pl.wkv_all + (size_t)l * 2 * d * d * es, s));
-            if (ffn && !resident) {
+            if (ffn && !resident && !flow) {
                 HIPCHK(dg4_launch_pack_w(dt, W[WS * l + 3], 4 * d, 0, 4 * d, d, at(pl.w1[l]), s));
                 HIPCHK(dg4_launch_pack_w2(dt, W[WS * l + 4], d, at(pl.w2[l]), s));
             }
@@ -504,6 +510,10 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
         a.wqkv_packed = at(pl.wqkv[0]); a.wo_packed = at(pl.wo[0]);
         a.w_layer_stride = L > 1 ? (int64_t)(pl.wqkv[1] - pl.wqkv[0]) : 0;
         a.wkv_packed = at(pl.wkv_a);
+        if (ffn) {
+            a.ffn = 1; a.w1_packed = at(pl.w1[0]); a.w2_packed = at(pl.w2[0]);
+            a.ffn_layer_stride = L > 1 ? (int64_t)(pl.w1[1] - pl.w1[0]) : 0;
+        }
         a.rel_bias = (const float*)at(pl.bias_all);
         a.flags = (uint32_t*)at(pl.flags); a.ctrl = (uint32_t*)at(pl.ctrl);
         a.n_layers = L; a.ln_eps = cfg->ln_eps; a.epilogue = epi ? 1 : 0; a.project_kv = 1;

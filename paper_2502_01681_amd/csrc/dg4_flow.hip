@@ -198,12 +198,14 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
         for (int f = 0; f < 8; ++f) ring[f] = src[f * 64];
     };
     // acc[block][tile] = (the group in the ring) x b; `next`: the group that follows it
-    auto run_group = [&](const uint4 (&b)[2][8], bool two, const uint4* next, f32x4 (&acc)[2][GT]) __attribute__((always_inline)) {
+    auto run_group = [&](const uint4 (&b)[2][8], bool two, const uint4* next, f32x4 (&acc)[2][GT], bool add = false) __attribute__((always_inline)) {
         const uint4* cur = ring_src;
+        if (!add) {
 #pragma unroll
-        for (int nt = 0; nt < GT; ++nt) {
-            acc[0][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
-            acc[1][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            for (int nt = 0; nt < GT; ++nt) {
+                acc[0][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+                acc[1][nt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+            }
         }
 #pragma unroll
         for (int f = 0; f < RING; ++f) {
@@ -217,12 +219,55 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
     };
     // the B operands: this lane's 16 bytes per step of the rows of both blocks (the second block's
     // are read, and never used, when the tile has no second block)
-    auto load_rows = [&](const T* buf, uint4 (&b)[2][8]) __attribute__((always_inline)) {
+    auto load_rows = [&](const T* buf, uint4 (&b)[2][8], int stride = (512 + 16) / (int)sizeof(T)) __attribute__((always_inline)) {
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            b[0][s] = *(const uint4*)((const unsigned char*)buf + (size_t)n * (YS * sizeof(T)) + s * 64 + g * 16);
-            b[1][s] = *(const uint4*)((const unsigned char*)buf + (size_t)(16 + n) * (YS * sizeof(T)) + s * 64 + g * 16);
+            b[0][s] = *(const uint4*)((const unsigned char*)buf + (size_t)n * (stride * sizeof(T)) + s * 64 + g * 16);
+            b[1][s] = *(const uint4*)((const unsigned char*)buf + (size_t)(16 + n) * (stride * sizeof(T)) + s * 64 + g * 16);
         }
+    };
+    // LayerNorm over each gate's row (no affine, biased variance), two passes: the lane's columns, the
+    // wave's 16*GT columns across its four lane rows, the eight waves through LDS; then the rows go,
+    // rounded to T, to dst. Barriers inside: every wave has read what it needed of dst before.
+    auto normalise_to = [&](float (&tv)[2][CW], bool two, bool norm, T* dst) __attribute__((always_inline)) {
+        __syncthreads();                          // every wave holds its operands: dst may be written
+        if (norm) {
+            float mean[2];
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                float s1 = 0.f;
+#pragma unroll
+                for (int i = 0; i < CW; ++i) s1 += tv[nb][i];
+                s1 = sum_lane_rows(s1);
+                if (g == 0) part[0][wave][16 * nb + n] = s1;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                float a1 = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < 8; ++w2) a1 += part[0][w2][16 * nb + n];
+                mean[nb] = a1 * (1.0f / D);
+                float s2 = 0.f;
+#pragma unroll
+                for (int i = 0; i < CW; ++i) { const float d2 = tv[nb][i] - mean[nb]; s2 = fmaf(d2, d2, s2); }
+                s2 = sum_lane_rows(s2);
+                if (g == 0) part[1][wave][16 * nb + n] = s2;
+            }
+            __syncthreads();
+#pragma unroll
+            for (int nb = 0; nb < 2; ++nb) {
+                float a2 = 0.f;
+#pragma unroll
+                for (int w2 = 0; w2 < 8; ++w2) a2 += part[1][w2][16 * nb + n];
+                const float rstd = rsqrtf(a2 * (1.0f / D) + p.ln_eps);
+#pragma unroll
+                for (int i = 0; i < CW; ++i) tv[nb][i] = (tv[nb][i] - mean[nb]) * rstd;
+            }
+        }
+        *(uint4*)&dst[n * YS + cbase] = Piece<T>::pack(tv[0]);
+        if (two) *(uint4*)&dst[(16 + n) * YS + cbase] = Piece<T>::pack(tv[1]);
+        __syncthreads();                          // dst complete
     };
     // the lane's CW values of group-local columns from an accumulator
     auto cols_of = [&](const f32x4 (&a)[GT], float* t) __attribute__((always_inline)) {
@@ -504,7 +549,9 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             load_rows(ybuf, b);
             // (the ring then takes the first group of the product that follows the LayerNorm)
             const void* after = last ? p.wkv_packed : (const void*)((const char*)p.wqkv_packed + (int64_t)(l + 1) * p.w_layer_stride);
-            run_group(b, two, group_ptr(after, wave), acc);
+            const void* w1l = (const char*)p.w1_packed + (int64_t)l * p.ffn_layer_stride;
+            const void* w2l = (const char*)p.w2_packed + (int64_t)l * p.ffn_layer_stride;
+            run_group(b, two, p.ffn ? group_ptr(w1l, wave) : group_ptr(after, wave), acc);
             if (l == 0 && tid == 0) describe(t_next, (it + 1) & 1);       // (the ticket has had the attention to arrive)
             float tv[2][CW];
 #pragma unroll
@@ -517,46 +564,47 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                     for (int i = 0; i < CW; ++i) tv[nb][i] += r[i];
                 }
             }
-            __syncthreads();                      // every wave holds its operands: ybuf may be written
-            if (p.epilogue) {
-                // LayerNorm over each gate's row (no affine, biased variance), two passes: the lane's
-                // columns, the wave's 16*GT columns across its four lane rows, the eight waves through LDS
-                float mean[2];
+            normalise_to(tv, two, p.epilogue != 0, ybuf);         // ybuf = LN(s_l + a Wo_l), rounded to T (and the next tile's descriptor is in LDS)
+            if (p.ffn) {
+                // ---- the feed-forward sub-block (Section 3.5 keeps the transformer structure around the
+                // attention): s_{l+1} = LN(h + max(h W1, 0) W2), h = ybuf. The 4D activations of the
+                // tile go to LDS rounded to T (slab `sl` of D hidden units: this wave's columns of it),
+                // the second product runs over them in four steps of D, accumulating.
+                constexpr int US = 4 * D + E;
+                T* ubuf = (T*)((unsigned char*)(qkvbuf + (L > 1 ? FT * QS : 0)));
+                load_rows(ybuf, b);
+#pragma unroll 1
+                for (int sl = 0; sl < 4; ++sl) {
+                    run_group(b, two, sl < 3 ? group_ptr(w1l, 8 * (sl + 1) + wave) : group_ptr(w2l, wave), acc);
+#pragma unroll
+                    for (int nb = 0; nb < 2; ++nb) {
+                        if (nb == 1 && !two) continue;
+                        float v[CW];
+                        cols_of(acc[nb], v);
+#pragma unroll
+                        for (int i = 0; i < CW; ++i) v[i] = fmaxf(v[i], 0.f);
+                        *(uint4*)&ubuf[(16 * nb + n) * US + sl * D + cbase] = Piece<T>::pack(v);
+                    }
+                }
+                __syncthreads();                  // the activations of every wave
+#pragma unroll 1
+                for (int c4 = 0; c4 < 4; ++c4) {
+                    load_rows(ubuf + c4 * D, b, US);
+                    run_group(b, two, c4 < 3 ? group_ptr(w2l, 8 * (c4 + 1) + wave) : group_ptr(after, wave), acc, c4 > 0);
+                }
 #pragma unroll
                 for (int nb = 0; nb < 2; ++nb) {
-                    float s1 = 0.f;
+                    cols_of(acc[nb], tv[nb]);
+                    if (nb == 0 || two) {
+                        float r[CW];
+                        Piece<T>::unpack(*(const uint4*)&ybuf[(16 * nb + n) * YS + cbase], r);
 #pragma unroll
-                    for (int i = 0; i < CW; ++i) s1 += tv[nb][i];
-                    s1 = sum_lane_rows(s1);
-                    if (g == 0) part[0][wave][16 * nb + n] = s1;
+                        for (int i = 0; i < CW; ++i) tv[nb][i] += r[i];
+                    }
                 }
-                __syncthreads();
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    float a1 = 0.f;
-#pragma unroll
-                    for (int w2 = 0; w2 < 8; ++w2) a1 += part[0][w2][16 * nb + n];
-                    mean[nb] = a1 * (1.0f / D);
-                    float s2 = 0.f;
-#pragma unroll
-                    for (int i = 0; i < CW; ++i) { const float d2 = tv[nb][i] - mean[nb]; s2 = fmaf(d2, d2, s2); }
-                    s2 = sum_lane_rows(s2);
-                    if (g == 0) part[1][wave][16 * nb + n] = s2;
-                }
-                __syncthreads();
-#pragma unroll
-                for (int nb = 0; nb < 2; ++nb) {
-                    float a2 = 0.f;
-#pragma unroll
-                    for (int w2 = 0; w2 < 8; ++w2) a2 += part[1][w2][16 * nb + n];
-                    const float rstd = rsqrtf(a2 * (1.0f / D) + p.ln_eps);
-#pragma unroll
-                    for (int i = 0; i < CW; ++i) tv[nb][i] = (tv[nb][i] - mean[nb]) * rstd;
-                }
+                normalise_to(tv, two, true, ybuf);
+                lap(7);
             }
-            *(uint4*)&ybuf[n * YS + cbase] = Piece<T>::pack(tv[0]);
-            if (two) *(uint4*)&ybuf[(16 + n) * YS + cbase] = Piece<T>::pack(tv[1]);
-            __syncthreads();                      // ybuf = s_{l+1}, rounded to T; the next tile's descriptor
             lap(3);
             load_rows(ybuf, b);
             if (l == 0 && !WIDE) {
@@ -643,7 +691,9 @@ int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
     const bool wide = a.ell_w > 16;
     const size_t smem = 2 * (size_t)FT * (D + E) * sizeof(T) + 2 * 8 * FT * sizeof(float) + 64 +
                         (a.n_layers > 1 ? (size_t)FT * (3 * D + E) * sizeof(T) : 0) +
-                        (wide ? (size_t)(Elem<T>::EPL + 2) * FLOW_THREADS * sizeof(float) : 0);
+                        (wide ? (size_t)(Elem<T>::EPL + 2) * FLOW_THREADS * sizeof(float) : 0) +
+                        (a.ffn ? (size_t)FT * (4 * D + E) * sizeof(T) : 0);
+    if (a.ffn && (wide || !a.w1_packed || !a.w2_packed)) return hipErrorInvalidValue;
     void (*kern)(dg4_flow_args) = nullptr;
     if (a.ell_w == 8) kern = a.prof ? flow_kernel<T, 8, true> : flow_kernel<T, 8, false>;
     else if (a.ell_w == 16) kern = a.prof ? flow_kernel<T, 16, true> : flow_kernel<T, 16, false>;

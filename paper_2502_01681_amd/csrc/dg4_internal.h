@@ -213,6 +213,10 @@ struct dg4_flow_args {
     void* h_out;                           // [n, d] by node id
     const void* wqkv_packed; const void* wo_packed; int64_t w_layer_stride;   // dg4_launch_pack_wa order; bytes from a layer's to the next's
     const void* wkv_packed;                // [layers][d, 2d] in dg4_launch_pack_wa order: K | V columns of every layer
+    int ffn;                               // the feed-forward sub-block after every attention sub-block (rows of at most 16 entries)
+    const void* w1_packed;                 // per layer W1 [d, 4d] in dg4_launch_pack_wa order ...
+    const void* w2_packed;                 // ... and W2 [4d, d] as four [d, d] blocks of d input rows each, same order
+    int64_t ffn_layer_stride;              // bytes from a layer's W1 (W2) to the next's
     const float* rel_bias;                 // [layers][heads, 4]
     uint32_t* flags;                       // [n] by position: 1 = rows published
     uint32_t* ctrl;                        // [1] abort word, [2] ticket counter

@@ -150,3 +150,41 @@ def test_flow_kernel_on_wide_rows(name, n_and, k, over):
     H1 = run(w, cfg, g, 0, mid)
     H2 = run(w, cfg, g, mid, None, H0=H1)
     assert torch.equal(H2, H)
+
+
+@pytest.mark.parametrize("name,n_and,over", [("tiny", None, {}), ("small", 3000, dict(n_layers=12)), ("stress", 8000, {}),
+                                             ("medium", 8000, dict(n_layers=2))])
+def test_flow_kernel_with_feed_forward(name, n_and, over):
+    # the whole transformer block per layer (attention sub-block, then LN(h + relu(h W1) W2)), up to the
+    # paper's twelve layers, in one persistent launch
+    print(f"flow kernel + feed-forward {name} n_and={n_and} {over}", flush=True)
+    w = make(name, n_and, **over)
+    c = w.cfg
+    w1, w2 = synth.ffn_weights(c)
+    g, og = graphs(w)
+
+    def go(cfg, level_begin=0, level_end=None, H0=None):
+        X = to_dev(w.x, c.dtype)
+        W = [lw + (to_dev(w1[l], c.dtype), to_dev(w2[l], c.dtype)) for l, lw in enumerate(device_weights(w, c.dtype))]
+        H = torch.full((c.n_nodes, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda") if H0 is None else H0
+        ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        dg4.dg4_layer_fwd(cfg, g, X, W, H, level_begin, level_end, workspace=ws)
+        torch.cuda.synchronize()
+        dg4.dg4_layer_status(cfg, g, ws)
+        return H
+
+    cfg = cfg_of(c, ffn=True)
+    H = go(cfg)
+    Hn = to_np(H)
+    assert not np.isnan(Hn).any()
+    ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype, w1=w1, w2=w2)
+    err = row_rel_err(Hn, ref)
+    print(f"  max rel err {err.max():.3e}, max element err {elem_err(Hn, ref).max():.3e}", flush=True)
+    assert err.max() <= TOL[c.dtype]
+    H_pl = to_np(go(cfg_of(c, ffn=True, per_level=True)))
+    assert row_rel_err(Hn, H_pl.astype(np.float64)).max() <= TOL[c.dtype]
+    assert torch.equal(H, go(cfg_of(c, ffn=True, level_order=True)))
+    mid = g.n_levels // 2
+    H2 = go(cfg, mid, None, H0=go(cfg, 0, mid))
+    assert torch.equal(H2, H)
