@@ -183,7 +183,7 @@ def main():
             return "level-by-level launches"
         if c.dtype == "bf16" and c.hidden == 256 and c.n_layers == 1 and g.hops <= 2:
             return "sweep_kernel (persistent, weights resident in registers)"
-        if flags.get("ffn"):
+        if flags.get("ffn") and g.hops > 3:
             return "level-by-level launches"
         return "flow_kernel (persistent, weights streamed" + (", several lane groups per neighbour row)" if g.hops > 3 else ")")
 
@@ -377,12 +377,13 @@ def main():
             cc = cw.cfg
             cg = dg4.dg4_build_levels(cc.n_nodes, cw.edge_src, cw.edge_dst, cw.edge_inv, cc.hops, cw.level_hint)
             CX, CW = tensors(cw, cc)
+            FW = tensors(cw, cc, ffn=True)[1] if any(f.get("ffn") for f in fl.values()) else None
             cg.upload()
             setup = time.perf_counter() - t0
             lev = eq1_levels(cw, cc, cg)
             res = {}
             for label, f in fl.items():
-                rr = time_layer(cc, cg, CX, CW, steps, warmup, **f)
+                rr = time_layer(cc, cg, CX, FW if f.get("ffn") else CW, steps, warmup, **f)
                 comp, gath = algorithmic_bytes(cg, rr["cfg"], cg.array("level") if f.get("bounded_kv") else lev)
                 res[label] = {"path": path_of(cc, cg, f), "step_ms_device": rr["ms_dev"], "kernel_ms": rr["ms_kernel"],
                               "step_ms_device_with_weight_packing": rr["ms_with_packing"],
@@ -406,7 +407,8 @@ def main():
             "tiny": one("tiny", 20, 3, default={}, level_by_level=dict(per_level=True)),
             "small": one("small", 10, 3, default={}, level_by_level=dict(per_level=True)),
             "medium": one("medium", 10, 3, default={}),
-            "medium_12_layers": one("medium", 2, 1, over=dict(n_layers=12), default={}),
+            # Section 4.1's depth; with_feed_forward: the complete transformer block per layer
+            "medium_12_layers": one("medium", 2, 1, over=dict(n_layers=12), default={}, with_feed_forward=dict(ffn=True)),
             # stress as stored (K|V of finished gates kept for all four layers) and as the workload list
             # defines it: memory bounded to one level's frontier of K|V (level-by-level launches through
             # the 1001 assigned levels, the frontier's K|V projected again for every level that reads it)

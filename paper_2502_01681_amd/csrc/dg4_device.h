@@ -57,6 +57,16 @@ template <> struct Elem<float> {
         a = make_uint4(__float_as_uint(f[0]), __float_as_uint(f[1]), __float_as_uint(f[2]), __float_as_uint(f[3]));
         b = make_uint4(__float_as_uint(f[4]), __float_as_uint(f[5]), __float_as_uint(f[6]), __float_as_uint(f[7]));
     }
+    // the lane's part of a dot product of two rows, from their 32 bytes as loaded
+    __device__ static float dot(const uint4& qa, const uint4& qb, const uint4& ka, const uint4& kb)
+    {
+        float q[8], k[8];
+        unpack(qa, qb, q); unpack(ka, kb, k);
+        float d = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) d = fmaf(q[i], k[i], d);
+        return d;
+    }
     __device__ static float head_sum(float p) { p += xor1(p); p += xor2(p); return p; }   // 4 lanes per head
     __device__ static float load1(const void* p, int64_t i) { return ((const float*)p)[i]; }
     __device__ static void store1(void* p, int64_t i, float v) { ((float*)p)[i] = v; }
@@ -73,6 +83,20 @@ template <> struct Elem<bf16_t> {
     {
         a = make_uint4(pack_bf16x2(f[0], f[1]), pack_bf16x2(f[2], f[3]), pack_bf16x2(f[4], f[5]), pack_bf16x2(f[6], f[7]));
         b = make_uint4(pack_bf16x2(f[8], f[9]), pack_bf16x2(f[10], f[11]), pack_bf16x2(f[12], f[13]), pack_bf16x2(f[14], f[15]));
+    }
+    // (pairs of bfloat16 multiplied and added in one instruction, fp32 accumulation, two chains)
+    __device__ static float dot(const uint4& qa, const uint4& qb, const uint4& ka, const uint4& kb)
+    {
+        typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+        auto d2 = [](uint32_t a, uint32_t b, float c) {
+            return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), c, false);
+        };
+        float d0 = 0.f, d1 = 0.f;
+        d0 = d2(qa.x, ka.x, d0); d1 = d2(qa.y, ka.y, d1);
+        d0 = d2(qa.z, ka.z, d0); d1 = d2(qa.w, ka.w, d1);
+        d0 = d2(qb.x, kb.x, d0); d1 = d2(qb.y, kb.y, d1);
+        d0 = d2(qb.z, kb.z, d0); d1 = d2(qb.w, kb.w, d1);
+        return d0 + d1;
     }
     __device__ static float head_sum(float p) { p += xor1(p); return p; }                   // 2 lanes per head
     __device__ static float load1(const void* p, int64_t i) { return bf16_lo(((const uint16_t*)p)[i]); }

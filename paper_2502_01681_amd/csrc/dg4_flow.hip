@@ -42,6 +42,9 @@ namespace {
 
 constexpr int FT = 32;                    // gates per tile (two blocks of 16)
 constexpr int FLOW_THREADS = 512;
+#ifndef FLOW_RING_DEPTH
+#define FLOW_RING_DEPTH 8
+#endif
 
 // One fragment of packed weight (16 bytes per lane: 16 output columns x 32 bytes of the input
 // dimension) against a block of 16 gates: c[i] of lane (n = lane % 16, g = lane / 16) is gate n,
@@ -128,6 +131,15 @@ __device__ __forceinline__ void store16_agent(void* dst, const uint4& v)
     __asm__ volatile("global_store_dwordx4 %0, %1, off sc1\n\ts_nop 1" : : "v"(dst), "v"(t) : "memory");
 }
 
+// Global memory -> LDS without passing through registers: every lane moves 16 bytes from its own global
+// address to LDS address lds_base + 16 * lane (lds_base wave-uniform). The transfers count in vmcnt like
+// loads, but the compiler does not see them: the reader waits with vmcnt(0) itself.
+__device__ __forceinline__ void flow_dma16(const void* src, uint32_t lds_base)
+{
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
+                     : : "v"(src), "s"((uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base)) : "memory");
+}
+
 // x summed over the four 16-lane rows of a wave (lanes with equal lane % 16), in every lane
 __device__ __forceinline__ float sum_lane_rows(float x)
 {
@@ -166,7 +178,20 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
     float (*part)[8][FT] = (float (*)[8][FT])(flow_smem + 2 * ROW_BUF);             // [2][wave][row]
     // two tile descriptors {kind, first position, rows, -} (this tile's and the next one's), then the abort word
     int* ctl = (int*)(flow_smem + 2 * ROW_BUF + 2 * 8 * FT * sizeof(float));
-    T* qkvbuf = (T*)(flow_smem + 2 * ROW_BUF + 2 * 8 * FT * sizeof(float) + 64);    // [FT][QS], sweeps of several layers
+    // the packed neighbour rows of this tile's gates and of the next tile's, [2][FT][AW] (read by the 16
+    // lanes of a gate's group at the start of every attention: kept in LDS, not in registers)
+    constexpr size_t ENT_BYTES = WIDE ? 0 : 2 * (size_t)FT * AWN * sizeof(uint32_t);
+    uint32_t (*entbuf)[FT][AWN] = (uint32_t (*)[FT][AWN])(flow_smem + 2 * ROW_BUF + 2 * 8 * FT * sizeof(float) + 64);
+    // Q | K | V of the tile's gates at their running state, [FT][QS]: layer 0's come in from the projection
+    // of x at the top of a tile, the next layer's are projected here (rows of any width read layer 0's
+    // from global memory and have the buffer only in sweeps of several layers)
+    T* qkvbuf = (T*)(flow_smem + 2 * ROW_BUF + 2 * 8 * FT * sizeof(float) + 64 + ENT_BYTES);
+    const size_t qkv_bytes = (!WIDE || p.n_layers > 1) ? (size_t)FT * QS * sizeof(T) : 0;
+    const uint32_t qkv_lds = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) unsigned char*)flow_smem +
+                             (uint32_t)(2 * ROW_BUF + 2 * 8 * FT * sizeof(float) + 64 + ENT_BYTES);
+    // Rows of 16 entries: the attention keeps 128 registers of row halves in flight, so nothing else may
+    // stay in registers across it: the weight ring is then filled after the attention, not before it.
+    constexpr bool OVER = AW == 8;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -187,7 +212,8 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
 
     // The ring: the next eight fragments of the packed weight stream this wave multiplies, refilled
     // eight fragments ahead as they are used up, across the end of a group into the group that follows.
-    uint4 ring[8];
+    constexpr int RD = FLOW_RING_DEPTH < RING ? FLOW_RING_DEPTH : RING;      // fragments in flight per wave
+    uint4 ring[RD];
     const uint4* ring_src;                        // the group whose first fragments the ring holds
     auto group_ptr = [&](const void* packed, int group) __attribute__((always_inline)) {
         return (const uint4*)packed + (int64_t)group * GROUP_UNITS + lane;
@@ -195,10 +221,12 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
     auto fill_ring = [&](const uint4* src) __attribute__((always_inline)) {
         ring_src = src;
 #pragma unroll
-        for (int f = 0; f < 8; ++f) ring[f] = src[f * 64];
+        for (int f = 0; f < RD; ++f) ring[f] = src[f * 64];
     };
     // acc[block][tile] = (the group in the ring) x b; `next`: the group that follows it
-    auto run_group = [&](const uint4 (&b)[2][8], bool two, const uint4* next, f32x4 (&acc)[2][GT], bool add = false) __attribute__((always_inline)) {
+    // (`refill` false: nothing follows that may be requested yet, the ring is left empty)
+    auto run_group = [&](const uint4 (&b)[2][8], bool two, const uint4* next, f32x4 (&acc)[2][GT], bool add = false,
+                         bool refill = true) __attribute__((always_inline)) {
         const uint4* cur = ring_src;
         if (!add) {
 #pragma unroll
@@ -210,10 +238,11 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
 #pragma unroll
         for (int f = 0; f < RING; ++f) {
             const int nt = f / 8, s = f % 8;
-            const uint4 frag = ring[s];
+            const uint4 frag = ring[f % RD];
             Blk<T>::run(frag, b[0][s], acc[0][nt]);
             if (two) Blk<T>::run(frag, b[1][s], acc[1][nt]);
-            ring[s] = f + 8 < RING ? cur[(f + 8) * 64] : next[(f + 8 - RING) * 64];
+            if (f + RD < RING) ring[f % RD] = cur[(f + RD) * 64];
+            else if (refill) ring[f % RD] = next[(f + RD - RING) * 64];
         }
         ring_src = next;
     };
@@ -302,12 +331,8 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
         ctl[8] = 0;
         describe((int64_t)__hip_atomic_fetch_add(&p.ctrl[2], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), 0);
     }
-    fill_ring(group_ptr(p.wo_packed, wave));      // layer 0's output projection, this wave's columns
-    // the neighbour row of this lane group's gate in the NEXT tile, requested in the middle of a tile
-    uint32_t ent_n[AWN], watch_n = DG4_ELL_PAD;
-#pragma unroll
-    for (int j = 0; j < AWN; ++j) ent_n[j] = DG4_ELL_PAD;
-    bool have_next = false;                       // ent_n / watch_n hold the row of this tile (workgroup-uniform)
+    if (OVER) fill_ring(group_ptr(p.wo_packed, wave));    // layer 0's output projection, this wave's columns
+    bool have_next = false;                       // entbuf[it & 1] holds the rows of this tile already (workgroup-uniform)
     for (int it = 0;; ++it) {
         __syncthreads();                          // the descriptor; the previous tile is done with every buffer
         const int kind = ctl[4 * (it & 1)];
@@ -332,14 +357,11 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
         T* ybuf = buf1;                           // attention output, then the normalised rows
 
         // s_0 = X rows of the tile's gates, as 16-byte pieces
-        int64_t pidx[PPT];                        // node id of the piece's row (-1: not stored)
 #pragma unroll
         for (int q = 0; q < PPT; ++q) {
             const int piece = tid + FLOW_THREADS * q, row = piece / CPR, c = piece % CPR;
-            pidx[q] = -1;
             if (row < live) {
                 const int64_t id = p.order[pos_of(row)];
-                if (row < rows && !pre) pidx[q] = id;
                 if (pre) *(uint4*)&ybuf[row * YS + c * E] = *((const uint4*)((const T*)p.h_out + id * D) + c);
                 else *(uint4*)&resid[row * YS + c * E] = *((const uint4*)((const T*)p.x + id * D) + c);
             }
@@ -348,7 +370,20 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
         // ---- the sources of the tile's gates must be published
         const bool attends = arow < live && !pre; // (whole waves: 4 gates per wave)
         const int64_t apos = pos_of(arow);
-        uint32_t ent[AWN];
+        if constexpr (!WIDE) {
+            // Q | K | V of layer 0 for this wave's four gates, straight into LDS (96 pieces of 16 bytes a row)
+            if (!pre) {
+#pragma unroll
+                for (int gq = 0; gq < 4; ++gq) {
+                    const int r = 4 * wave + gq;
+                    if (r >= live) break;
+                    const unsigned char* src = (const unsigned char*)((const T*)p.qkv_self + pos_of(r) * (3 * D)) + lane * 16;
+                    const uint32_t dst = qkv_lds + (uint32_t)(r * QS * sizeof(T));
+                    flow_dma16(src, dst);
+                    if (lane < 32) flow_dma16(src + 1024, dst + 1024u);
+                }
+            }
+        }
         auto give_up = [&](uint32_t spins) __attribute__((always_inline)) -> bool {
             if (spins > p.spin_limit ||
                 ((spins & 63u) == 0 && __hip_atomic_load(&p.ctrl[1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT))) {
@@ -383,18 +418,11 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             }
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
             __syncthreads();                      // a gate's entries were watched by several waves
-            ent[0] = DG4_ELL_PAD;
         } else if (attends) {
-            // lane `sub` of a gate's lane group watches entry `sub` of its row
-            uint32_t e;
-            if (have_next) {
-#pragma unroll
-                for (int j = 0; j < AWN; ++j) ent[j] = ent_n[j];
-                e = watch_n;
-            } else {
-                load_entries<AWN>(p.ell, apos, ent);
-                e = sub < AWN ? p.ell[apos * AWN + sub] : DG4_ELL_PAD;
-            }
+            // lane `sub` of a gate's lane group watches entry `sub` of its row (the row came in during
+            // the previous tile, or is fetched now; the 16 lanes of a gate sit in one wave)
+            if (!have_next && sub < AWN) entbuf[it & 1][arow][sub] = p.ell[apos * AWN + sub];
+            const uint32_t e = sub < AWN ? entbuf[it & 1][arow][sub] : DG4_ELL_PAD;
             const bool watch = e != DG4_ELL_PAD && (e >> 30) != 0;
             const uint32_t* f = p.flags + (watch ? (e & 0x3FFFFFFFu) : 0u);
             uint32_t spins = 0;
@@ -407,9 +435,6 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             // (the flag loads above are the only ordering needed, see the head of the file; the fence
             // keeps the compiler from moving row loads above them)
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        } else {
-#pragma unroll
-            for (int j = 0; j < AWN; ++j) ent[j] = DG4_ELL_PAD;
         }
         if (TIMERS) __syncthreads();
         lap(1);
@@ -440,13 +465,13 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
 #pragma unroll
                 for (int i = 0; i < EPL; ++i) av[i] = 0.f;
                 if (act) {
-                    const T* kvl = (const T*)p.kv + (int64_t)l * p.kv_layer_stride;
+                    // sources through the structured buffer of layer l's K | V store: an entry that is no
+                    // source (the gate itself, padding) asks for the row past its end and gets zeros
+                    // without a request, so the sixteen requests of a chunk go out back to back
+                    const uint32_t kv_rows = (uint32_t)(p.kv_layer_stride / (2 * D));
+                    const dg4_i32x4 kvb = row_buffer((const T*)p.kv + (int64_t)l * p.kv_layer_stride, 2 * D * sizeof(T), kv_rows);
                     const T* qrow = l == 0 ? (const T*)p.qkv_self + (p0 + r) * (3 * D) : qkvbuf + r * QS;
-                    float q[EPL];
-                    {
-                        const uint4* qp = (const uint4*)(qrow + eoff);
-                        Elem<T>::unpack(qp[0], qp[1], q);
-                    }
+                    const uint4 qa = ((const uint4*)(qrow + eoff))[0], qb = ((const uint4*)(qrow + eoff))[1];
                     const float* bp = p.rel_bias + l * (D / 32) * 4 + (int)(eoff >> 5) * 4;
                     const float bias[4] = { bp[0], bp[1], bp[2], bp[3] };
                     const float scale = 0.17677669529663687f;     // 1/sqrt(32)
@@ -463,39 +488,56 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                         uint4 ka[8], kb[8], va[8], vb[8];
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
-                            if (en[j] != DG4_ELL_PAD) {
-                                const T* kr = (en[j] >> 30) == 0 ? qrow + D : kvl + (int64_t)(en[j] & 0x3FFFFFFFu) * (2 * D);
-                                const uint4* kp = (const uint4*)(kr + eoff);
-                                const uint4* vp = (const uint4*)(kr + D + eoff);
-                                ka[j] = kp[0]; kb[j] = kp[1]; va[j] = vp[0]; vb[j] = vp[1];
-                            } else {
-                                ka[j] = make_uint4(0, 0, 0, 0); kb[j] = ka[j]; va[j] = ka[j]; vb[j] = ka[j];
-                            }
+                            const bool src = en[j] != DG4_ELL_PAD && (en[j] >> 30) != 0;
+                            const uint32_t row = src ? (en[j] & 0x3FFFFFFFu) : kv_rows;
+                            ka[j] = row_load16(kvb, row, (uint32_t)sub * 32u);
+                            kb[j] = row_load16(kvb, row, (uint32_t)sub * 32u + 16u);
+                        }
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const bool src = en[j] != DG4_ELL_PAD && (en[j] >> 30) != 0;
+                            const uint32_t row = src ? (en[j] & 0x3FFFFFFFu) : kv_rows;
+                            va[j] = row_load16(kvb, row, (uint32_t)(D * sizeof(T)) + (uint32_t)sub * 32u);
+                            vb[j] = row_load16(kvb, row, (uint32_t)(D * sizeof(T)) + (uint32_t)sub * 32u + 16u);
                         }
                         float sc[8];
                         float cm = m;
+                        bool self_here = false;                   // the chunk holds the gate's own entry (same for its 16 lanes)
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
-                            float k[EPL];
-                            Elem<T>::unpack(ka[j], kb[j], k);
-                            float dot = 0.f;
-#pragma unroll
-                            for (int i = 0; i < EPL; ++i) dot = fmaf(q[i], k[i], dot);
-                            dot = Elem<T>::head_sum(dot);
+                            const float dot = Elem<T>::head_sum(Elem<T>::dot(qa, qb, ka[j], kb[j]));
                             const uint32_t rel = en[j] >> 30;
-                            const float bb = rel == 0 ? bias[0] : rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
-                            sc[j] = en[j] != DG4_ELL_PAD ? fmaf(dot, scale, bb) : -INFINITY;
+                            const float bb = rel == 1 ? bias[1] : rel == 2 ? bias[2] : bias[3];
+                            const bool src = en[j] != DG4_ELL_PAD && rel != 0;
+                            self_here = self_here || rel == 0;
+                            sc[j] = src ? fmaf(dot, scale, bb) : -INFINITY;
                             cm = fmaxf(cm, sc[j]);
                         }
-                        const float corr = __expf(m - cm);        // 0 on the first chunk (m = -inf, cm finite)
+                        float s_self = -INFINITY;
+                        float vs[EPL];
+                        if (self_here) {                          // its K and V come from the gate's own projection
+                            const uint4* kp = (const uint4*)(qrow + D + eoff);
+                            const uint4* vp = (const uint4*)(qrow + 2 * D + eoff);
+                            s_self = fmaf(Elem<T>::head_sum(Elem<T>::dot(qa, qb, kp[0], kp[1])), scale, bias[0]);
+                            Elem<T>::unpack(vp[0], vp[1], vs);
+                            cm = fmaxf(cm, s_self);
+                        }
+                        // (a chunk holds at least one entry, a source or the gate itself: cm is finite)
+                        const float corr = __expf(m - cm);        // 0 if these are the first terms (m = -inf)
                         z *= corr;
 #pragma unroll
                         for (int i = 0; i < EPL; ++i) av[i] *= corr;
+                        if (self_here) {
+                            const float ps = __expf(s_self - cm);
+                            z += ps;
+#pragma unroll
+                            for (int i = 0; i < EPL; ++i) av[i] = fmaf(ps, vs[i], av[i]);
+                        }
 #pragma unroll
                         for (int j = 0; j < 8; ++j) {
                             float v[EPL];
                             Elem<T>::unpack(va[j], vb[j], v);
-                            const float pj = __expf(sc[j] - cm);  // 0 for padding
+                            const float pj = __expf(sc[j] - cm);  // 0 for what is no source
                             z += pj;
 #pragma unroll
                             for (int i = 0; i < EPL; ++i) av[i] = fmaf(pj, v[i], av[i]);
@@ -503,7 +545,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                         m = cm;
                     }
                 }
-                float* mrg = (float*)(qkvbuf + (L > 1 ? FT * QS : 0));           // [EPL + 2][512]
+                float* mrg = (float*)((unsigned char*)qkvbuf + qkv_bytes);        // [EPL + 2][512]
                 mrg[EPL * FLOW_THREADS + tid] = m;
                 mrg[(EPL + 1) * FLOW_THREADS + tid] = z;
 #pragma unroll
@@ -534,10 +576,30 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                 }
             } else if (attends) {
                 const T* kvl = (const T*)p.kv + (int64_t)l * p.kv_layer_stride;
-                const T* qrow = l == 0 ? (const T*)p.qkv_self + apos * (3 * D) : qkvbuf + arow * QS;
+                const T* qrow = qkvbuf + arow * QS;
+                if (l == 0) {                     // this wave's transfers of the gates' own rows have landed
+                    __builtin_amdgcn_s_waitcnt(0x0F70);       // vmcnt(0)
+                    __asm__ volatile("" ::: "memory");
+                }
                 float av[EPL];
-                attend_core<T, D, AWN, AWN < 8 ? AWN : 8, AWN == 8>(ent, qrow, qrow + D, qrow + 2 * D, kvl, kvl + D, 2 * D,
-                                                                    p.rel_bias + l * (D / 32) * 4, sub, av);
+                uint32_t ent[AWN];
+                {
+                    const uint4* ep = (const uint4*)&entbuf[it & 1][arow][0];
+#pragma unroll
+                    for (int i = 0; i < AWN / 4; ++i) {
+                        const uint4 t4 = ep[i];
+                        ent[4 * i] = t4.x; ent[4 * i + 1] = t4.y; ent[4 * i + 2] = t4.z; ent[4 * i + 3] = t4.w;
+                    }
+                }
+                const uint32_t kv_rows = (uint32_t)(p.kv_layer_stride / (2 * D));
+                // (rows of eight entries: one trip to memory either way, and the plain two-pass form has the
+                // shorter chain of arithmetic, which is what deep, narrow circuits wait for)
+                if constexpr (AWN == 8)
+                    attend_core<T, D, AWN, AWN, true>(ent, qrow, qrow + D, qrow + 2 * D, kvl, kvl + D, 2 * D,
+                                                      p.rel_bias + l * (D / 32) * 4, sub, av);
+                else
+                attend_chunked<T, D, AWN>(ent, qrow, qrow + D, qrow + 2 * D, row_buffer(kvl, 2 * D * sizeof(T), kv_rows), kv_rows,
+                                          p.rel_bias + l * (D / 32) * 4, sub, av);
                 uint4 oa, ob;
                 Elem<T>::pack(av, oa, ob);
                 uint4* op = (uint4*)&ybuf[arow * YS + sub * EPL];
@@ -546,6 +608,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             __syncthreads();
             lap(2);
             // ---- s_{l+1} = LN(s_l + a Wo_l): this lane ends with columns cbase .. cbase+CW-1 of gates n and 16+n
+            if (!OVER) fill_ring(group_ptr((const char*)p.wo_packed + (int64_t)l * p.w_layer_stride, wave));
             load_rows(ybuf, b);
             // (the ring then takes the first group of the product that follows the LayerNorm)
             const void* after = last ? p.wkv_packed : (const void*)((const char*)p.wqkv_packed + (int64_t)(l + 1) * p.w_layer_stride);
@@ -571,7 +634,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                 // tile go to LDS rounded to T (slab `sl` of D hidden units: this wave's columns of it),
                 // the second product runs over them in four steps of D, accumulating.
                 constexpr int US = 4 * D + E;
-                T* ubuf = (T*)((unsigned char*)(qkvbuf + (L > 1 ? FT * QS : 0)));
+                T* ubuf = (T*)((unsigned char*)qkvbuf + qkv_bytes);
                 load_rows(ybuf, b);
 #pragma unroll 1
                 for (int sl = 0; sl < 4; ++sl) {
@@ -613,10 +676,9 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                 have_next = ctl[nslot] == 1;
                 if (have_next) {
                     const int nrows = ctl[nslot + 2];
-                    if (arow < (nrows > 16 ? FT : 16)) {
+                    if (arow < (nrows > 16 ? FT : 16) && sub < AWN) {
                         const int64_t npos = (int64_t)ctl[nslot + 1] + (arow < nrows ? arow : nrows - 1);
-                        load_entries<AWN>(p.ell, npos, ent_n);
-                        watch_n = sub < AWN ? p.ell[npos * AWN + sub] : DG4_ELL_PAD;
+                        entbuf[(it + 1) & 1][arow][sub] = p.ell[npos * AWN + sub];
                     }
                 }
             }
@@ -628,7 +690,8 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                 const void* wo_next = (const char*)p.wo_packed + (int64_t)(l + 1) * p.w_layer_stride;
 #pragma unroll
                 for (int part3 = 0; part3 < 3; ++part3) {
-                    run_group(b, two, part3 < 2 ? group_ptr(wq, 8 * (part3 + 1) + wave) : group_ptr(wo_next, wave), acc);
+                    run_group(b, two, part3 < 2 ? group_ptr(wq, 8 * (part3 + 1) + wave) : group_ptr(wo_next, wave), acc, false,
+                              OVER || part3 < 2);
 #pragma unroll
                     for (int nb = 0; nb < 2; ++nb) {
                         if (nb == 1 && !two) continue;
@@ -647,9 +710,9 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
         // ---- the embeddings of the tile's gates go out, by node id
 #pragma unroll
         for (int q = 0; q < PPT; ++q) {
-            if (pidx[q] < 0) continue;
             const int piece = tid + FLOW_THREADS * q, row = piece / CPR, c = piece % CPR;
-            *((uint4*)((T*)p.h_out + pidx[q] * D) + c) = *(const uint4*)&ybuf[row * YS + c * E];
+            if (row >= rows || pre) continue;
+            *((uint4*)((T*)p.h_out + (int64_t)p.order[p0 + row] * D) + c) = *(const uint4*)&ybuf[row * YS + c * E];
         }
         // ---- K | V of every layer from the final embeddings: per layer, groups wave (K) and 8 + wave (V)
         // of its 2D columns; written through to device memory (agent scope), 16 bytes per lane
@@ -657,7 +720,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             const int nj = j + 1;
             const uint4* next = nj < 2 * L ? group_ptr(p.wkv_packed, (nj >> 1) * 16 + (nj & 1) * 8 + wave)
                                            : group_ptr(p.wo_packed, wave);      // the next tile's first product
-            run_group(b, two, next, acc);
+            run_group(b, two, next, acc, false, OVER || nj < 2 * L);
             T* base = (T*)p.kv + (int64_t)(j >> 1) * p.kv_layer_stride + (j & 1) * D + cbase;
 #pragma unroll
             for (int nb = 0; nb < 2; ++nb) {
@@ -690,7 +753,8 @@ int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return hipErrorInvalidDevice;
     const bool wide = a.ell_w > 16;
     const size_t smem = 2 * (size_t)FT * (D + E) * sizeof(T) + 2 * 8 * FT * sizeof(float) + 64 +
-                        (a.n_layers > 1 ? (size_t)FT * (3 * D + E) * sizeof(T) : 0) +
+                        (wide ? 0 : 2 * (size_t)FT * a.ell_w * sizeof(uint32_t)) +
+                        (a.n_layers > 1 || !wide ? (size_t)FT * (3 * D + E) * sizeof(T) : 0) +
                         (wide ? (size_t)(Elem<T>::EPL + 2) * FLOW_THREADS * sizeof(float) : 0) +
                         (a.ffn ? (size_t)FT * (4 * D + E) * sizeof(T) : 0);
     if (a.ffn && (wide || !a.w1_packed || !a.w2_packed)) return hipErrorInvalidValue;
@@ -704,6 +768,7 @@ int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
     if (e != hipSuccess) return e;
     // one workgroup of eight waves per compute unit (tiles are handed out by tickets, so fewer
     // resident ones would only cost speed)
+    // (with fewer XCDs at work the whole grid is still launched: the idle workgroups leave at once)
     const int64_t grid = std::min<int64_t>((int64_t)cus, a.n_tiles + a.n_pre);
     hipLaunchKernelGGL(kern, dim3((unsigned)grid), dim3(FLOW_THREADS), smem, s, a);
     return hipGetLastError();

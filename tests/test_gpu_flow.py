@@ -54,7 +54,8 @@ def test_flow_kernel_against_oracle_and_level_by_level(name, n_and, over):
     H = run(w, cfg_of(c), g, poison=True)
     assert not torch.isnan(H.float()).any()                      # every gate written
     H_pl = to_np(run(w, cfg_of(c, per_level=True), g))
-    assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= TOL[c.dtype]      # other kernels: equal up to rounding
+    # other kernels, another summation order: each within TOL of the oracle, so within 2 TOL of each other
+    assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= 2 * TOL[c.dtype]
     ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, c.heads, store=c.dtype)
     Hn = to_np(H)
     err = row_rel_err(Hn, ref)
@@ -72,7 +73,7 @@ def test_flow_kernel_without_epilogue():
     ref = oracle.layer_fwd(og, w.x, w.wqkv, w.wo, w.rel_bias, w.cfg.heads, store="f32", epilogue=False)
     assert row_rel_err(to_np(H), ref).max() <= TOL["f32"]
     H_pl = to_np(run(w, cfg_of(w.cfg, epilogue=False, per_level=True), g))
-    assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= TOL["f32"]
+    assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= 2 * TOL["f32"]
 
 
 @pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {})])
@@ -144,7 +145,7 @@ def test_flow_kernel_on_wide_rows(name, n_and, k, over):
     print(f"  max rel err {err.max():.3e}, max element err {elem_err(Hn, ref).max():.3e}", flush=True)
     assert err.max() <= TOL[c.dtype]
     H_pl = to_np(run(w, cfg_of(c, per_level=True), g))
-    assert row_rel_err(Hn, H_pl.astype(np.float64)).max() <= TOL[c.dtype]
+    assert row_rel_err(Hn, H_pl.astype(np.float64)).max() <= 2 * TOL[c.dtype]
     assert torch.equal(H, run(w, cfg, g))
     mid = g.n_levels // 2
     H1 = run(w, cfg, g, 0, mid)
@@ -183,7 +184,7 @@ def test_flow_kernel_with_feed_forward(name, n_and, over):
     print(f"  max rel err {err.max():.3e}, max element err {elem_err(Hn, ref).max():.3e}", flush=True)
     assert err.max() <= TOL[c.dtype]
     H_pl = to_np(go(cfg_of(c, ffn=True, per_level=True)))
-    assert row_rel_err(Hn, H_pl.astype(np.float64)).max() <= TOL[c.dtype]
+    assert row_rel_err(Hn, H_pl.astype(np.float64)).max() <= 2 * TOL[c.dtype]
     assert torch.equal(H, go(cfg_of(c, ffn=True, level_order=True)))
     mid = g.n_levels // 2
     H2 = go(cfg, mid, None, H0=go(cfg, 0, mid))

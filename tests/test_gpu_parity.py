@@ -256,7 +256,7 @@ def test_ffn_fwd(dtype, d, rows, lo, hi):
 @pytest.mark.parametrize("name,n_and,kw", [
     ("tiny", None, {}), ("small", None, {}), ("tiny", None, dict(n_layers=3, hops=3)),
     ("large", 30_000, {}), ("large", 30_000, dict(per_level=True)), ("medium", 20_000, {}),
-    ("large", 20_000, dict(hops=1)), ("stress", 20_000, {}), ("stress", 20_000, dict(bounded_kv=True)),
+    ("large", 20_000, dict(hops=1)), ("stress", 8_000, {}), ("stress", 8_000, dict(bounded_kv=True)),
     ("medium", 20_000, dict(dtype="f32")),
 ])
 def test_layer_fwd_with_feed_forward(name, n_and, kw):

@@ -132,7 +132,7 @@ def test_layer_over_deep_cones(name, n_and, hops, kw):
     ("small", 6_000, 3, 2, 128, {}),
     ("medium", 8_000, 8, 6, 128, {}),
     ("large", 10_000, 2, 1, 64, {}),                       # copies through the persistent sweep
-    ("large", 10_000, 2, 1, 64, dict(ffn=True)),
+    ("large", 4_000, 2, 1, 64, dict(ffn=True)),
     ("stress", 8_000, 3, 2, 128, dict(n_layers=1)),
 ])
 def test_partitioned_layer_without_marks(name, n_and, k, delta, batch, kw):
