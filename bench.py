@@ -437,7 +437,7 @@ def main():
                             "dg4_build_partitioned_s": t_part,
                             "gathered_GBps": pgath / (ms_part * 1e-3) / 1e9,
                             "compulsory_GBps": pcomp / (ms_part * 1e-3) / 1e9,
-                            "traffic": measured_traffic("medium_partition_k8_rocprofv3.txt", "dg4_layer_fwd")}
+                            "traffic": measured_traffic("medium_partition_k8_rocprofv3.txt", "flow_kernel")}
         del pr
         # The ablation without marks (every mini-batch recomputes its gates; one copy per mini-batch
         # and gate), against the same partition with marks. At k = 8 this graph would have 66 copies
