@@ -137,7 +137,7 @@ __device__ __forceinline__ void store16_agent(void* dst, const uint4& v)
 __device__ __forceinline__ void flow_dma16(const void* src, uint32_t lds_base)
 {
     __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off"
-                     : : "v"(src), "s"((uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base)) : "memory");
+                     : : "v"(src), "s"((uint32_t)__builtin_amdgcn_readfirstlane((int)lds_base)) : "memory", "m0");
 }
 
 // x summed over the four 16-lane rows of a wave (lanes with equal lane % 16), in every lane

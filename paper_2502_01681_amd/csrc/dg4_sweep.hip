@@ -95,17 +95,17 @@ __device__ __forceinline__ const void* uniform_ptr(const void* q)
 }
 __device__ __forceinline__ void dma16(const void* src, uint32_t lds_base)
 {
-    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform32(lds_base)) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(uniform32(lds_base)) : "memory", "m0");
 }
 // same with a wave-uniform 64-bit base and a per-lane 32-bit byte offset
 __device__ __forceinline__ void dma16_row(const void* base, uint32_t lane_off, uint32_t lds_base)
 {
-    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory", "m0");
 }
 // one 32-bit word per lane, read at device scope (served by the L2, never by this unit's L1)
 __device__ __forceinline__ void dma4_fresh(const void* base, uint32_t lane_off, uint32_t lds_base)
 {
-    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 sc1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dword %0, %1 sc1" : : "v"(lane_off), "s"(uniform_ptr(base)), "s"(uniform32(lds_base)) : "memory", "m0");
 }
 
 // Packed order for weights used as the A operand of a 16x16x32 MFMA, in
@@ -135,7 +135,7 @@ __global__ void pack_wt_kernel(const uint16_t* w, int ld, int col0, int ntw, int
 // unit wrote earlier in the kernel: never served from a line its L1 may still hold)
 __device__ __forceinline__ void dma16_fresh(const void* src, uint32_t lds_base)
 {
-    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc1" : : "v"(src), "s"(uniform32(lds_base)) : "memory");
+    __asm__ volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off sc1" : : "v"(src), "s"(uniform32(lds_base)) : "memory", "m0");
 }
 
 // The feed-forward weights in the order the sweep streams them (16-byte units). A tile's
