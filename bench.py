@@ -211,10 +211,13 @@ def main():
     e_dev = [torch.from_numpy(a).cuda() for a in (w.edge_src, w.edge_dst, w.edge_inv)]
     h_dev = torch.from_numpy(w.level_hint).cuda() if w.level_hint is not None else None
     t_build_dev = None
-    for _ in range(0 if part else 2):
+    for _ in range(2):
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        g_dev = dg4.dg4_build_levels_device(c.n_nodes, *e_dev, c.hops, h_dev)
+        if part:
+            g_dev = dg4.dg4_build_partitioned_device(c.n_nodes, *e_dev, part[0], part[1], part[2], h_dev)
+        else:
+            g_dev = dg4.dg4_build_levels_device(c.n_nodes, *e_dev, c.hops, h_dev)
         t_build_dev = time.perf_counter() - t0
         del g_dev
     del e_dev, h_dev
@@ -272,7 +275,7 @@ def main():
                      "step_achieved": compulsory / (ms_dev * 1e-3) / 1e9,
                      "step_frac": compulsory / (ms_dev * 1e-3) / 1e9 / HBM_PEAK_GBPS},
         "setup_s": {"generate": t_gen, "dg4_build_partitioned" if part else "dg4_build_levels": t_build,
-                    "dg4_build_levels_device": t_build_dev, "upload": t_upload},
+                    "dg4_build_partitioned_device" if part else "dg4_build_levels_device": t_build_dev, "upload": t_upload},
     }
     if part:
         out["config"]["workload"] += f", partition: stride {part[1]}, mini-batches of {part[2]} cones, marks"
@@ -424,6 +427,16 @@ def main():
         t0 = time.perf_counter()
         pg = dg4.dg4_build_partitioned(pc.n_nodes, pw.edge_src, pw.edge_dst, pw.edge_inv, 8, 6, 128, pw.level_hint)
         t_part = time.perf_counter() - t0
+        # the same analysis on the GPU (edge list resident in device memory; second call timed)
+        pe_dev = [torch.from_numpy(a).cuda() for a in (pw.edge_src, pw.edge_dst, pw.edge_inv)]
+        ph_dev = torch.from_numpy(pw.level_hint).cuda() if pw.level_hint is not None else None
+        for _ in range(2):
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            pg_dev = dg4.dg4_build_partitioned_device(pc.n_nodes, *pe_dev, 8, 6, 128, ph_dev)
+            t_part_dev = time.perf_counter() - t0
+            del pg_dev
+        del pe_dev, ph_dev
         PX, PW = tensors(pw, pc)
         pr = time_layer(pc, pg, PX, PW, 3, 2)
         ms_part = pr["ms_dev"]
@@ -434,7 +447,7 @@ def main():
                             "step_ms_device": ms_part, "edges_per_s": pg.nnz / (ms_part * 1e-3),
                             "gates_per_s": pg.n / (ms_part * 1e-3), "gates": pg.n, "neighbour_edges": pg.nnz,
                             "cones": int(len(pg.array("cone_root"))), "mini_batches": int(pg.array("stage").max()) + 1,
-                            "dg4_build_partitioned_s": t_part,
+                            "dg4_build_partitioned_s": t_part, "dg4_build_partitioned_device_s": t_part_dev,
                             "gathered_GBps": pgath / (ms_part * 1e-3) / 1e9,
                             "compulsory_GBps": pcomp / (ms_part * 1e-3) / 1e9,
                             "traffic": measured_traffic("medium_partition_k8_rocprofv3.txt", "flow_kernel")}

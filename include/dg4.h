@@ -164,6 +164,25 @@ int dg4_build_partitioned(int64_t n_nodes, int64_t n_edges,
                           int32_t stride, int32_t batch_cones, int32_t marks,
                           dg4_graph** out);
 
+/*
+ * dg4_build_partitioned with marks (Section 3.3, Algorithm 1; Section 3.4, Algorithm 2) on the GPU, for
+ * an edge list in DEVICE memory (edge_src, edge_dst, edge_inv, level_hint: device pointers), on top of
+ * dg4_build_levels_device: the kinds of roots, the members their cones cover and the left-over roots
+ * per gate; the lists by a stable sort of the (level, id) order on (level, kind); the first mini-batch
+ * of every gate by a minimum over the cones that hold it; the kept entries by merging a gate's row
+ * with the rows of its mini-batch's roots (a wave per cone), then a compaction. Only the running
+ * mini-batch numbers of the cones (one pass over the sorted roots) are formed on the host. Every
+ * table, DG4_CONE_* and DG4_STAGE included, equals the host call's bit for bit. Synchronous on
+ * `stream`; temporary device memory as dg4_build_levels_device plus about 22 bytes per node and one
+ * byte per neighbour entry of the unrestricted cones. The ablation without marks is a host call only.
+ * Errors as dg4_build_partitioned and dg4_build_levels_device.
+ */
+int dg4_build_partitioned_device(int64_t n_nodes, int64_t n_edges,
+                                 const int32_t* edge_src, const int32_t* edge_dst, const uint8_t* edge_inv,
+                                 int32_t hops, const int32_t* level_hint /* nullable */,
+                                 int32_t stride, int32_t batch_cones,
+                                 void* stream, dg4_graph** out);
+
 /* Tables of a graph, borrowed host pointers valid until dg4_graph_free. */
 typedef enum {
     DG4_LEVEL = 0,      /* int32  [n_nodes]                                    */

@@ -97,6 +97,8 @@ def lib():
         L.dg4_build_partitioned.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, _I32, _I32, _I32, ctypes.POINTER(_P)]
         L.dg4_build_levels_device.restype = ctypes.c_int
         L.dg4_build_levels_device.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, _P, ctypes.POINTER(_P)]
+        L.dg4_build_partitioned_device.restype = ctypes.c_int
+        L.dg4_build_partitioned_device.argtypes = [_I64, _I64, _P, _P, _P, _I32, _P, _I32, _I32, _P, ctypes.POINTER(_P)]
         L.dg4_graph_array.argtypes = [_P, ctypes.c_int, ctypes.POINTER(_P), ctypes.POINTER(_I64)]
         L.dg4_graph_info.restype = ctypes.c_int
         L.dg4_graph_info.argtypes = [_P, ctypes.POINTER(_I64), ctypes.POINTER(_I64), ctypes.POINTER(_I64),
@@ -231,6 +233,27 @@ def dg4_build_levels_device(n_nodes, edge_src, edge_dst, edge_inv, hops, level_h
                                        level_hint.data_ptr() if level_hint is not None else None,
                                        _stream(), ctypes.byref(out))
     _check(rc, "dg4_build_levels_device")
+    return Graph(out.value)
+
+
+def dg4_build_partitioned_device(n_nodes, edge_src, edge_dst, edge_inv, hops, stride, batch_cones, level_hint=None) -> Graph:
+    """dg4_build_partitioned (with marks) on the GPU: the edge list and the hint are device tensors."""
+    import torch
+    assert edge_src.dtype == torch.int32 and edge_dst.dtype == torch.int32 and edge_inv.dtype == torch.uint8
+    assert edge_src.is_cuda and edge_dst.is_cuda and edge_inv.is_cuda
+    assert edge_src.is_contiguous() and edge_dst.is_contiguous() and edge_inv.is_contiguous()
+    if not (edge_src.numel() == edge_dst.numel() == edge_inv.numel()):
+        raise DG4Error(-1, "dg4_build_partitioned_device")
+    if level_hint is not None:
+        assert level_hint.dtype == torch.int32 and level_hint.is_cuda and level_hint.is_contiguous()
+        if level_hint.numel() != n_nodes:
+            raise DG4Error(-1, "dg4_build_partitioned_device")
+    out = _P()
+    rc = lib().dg4_build_partitioned_device(n_nodes, edge_src.numel(), edge_src.data_ptr(), edge_dst.data_ptr(),
+                                            edge_inv.data_ptr(), hops,
+                                            level_hint.data_ptr() if level_hint is not None else None,
+                                            stride, batch_cones, _stream(), ctypes.byref(out))
+    _check(rc, "dg4_build_partitioned_device")
     return Graph(out.value)
 
 

@@ -221,6 +221,114 @@ __global__ void add_inverter_kernel(int64_t n, int32_t* out_not, const uint8_t* 
     if (v < n) out_not[v] += inverter[v];
 }
 
+// ---- partition and updating strategy (Algorithms 1 and 2 with marks) on the device.
+// Kinds of cone roots, as in the host analysis: 0 a gate on a stride level (level >= k and (level - k)
+// a multiple of the stride), 1 a gate nobody reads, 2 a gate that no cone of the first two kinds
+// holds (it roots its own cone); PART_NONE: not a root.
+constexpr uint8_t PART_NONE = 255;
+
+__global__ void part_read_kernel(int64_t n, const int32_t* fin, const int32_t* deg, uint8_t* is_read)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    for (int i = 0; i < deg[v]; ++i) is_read[fin[2 * v + i]] = 1;       // (every writer stores the same byte)
+}
+
+__global__ void part_kind_kernel(int64_t n, int32_t k, int32_t stride, const int32_t* level, const uint8_t* is_read, uint8_t* kind)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v >= n) return;
+    const int32_t l = level[v];
+    kind[v] = l >= k && (l - k) % stride == 0 ? (uint8_t)0 : !is_read[v] ? (uint8_t)1 : PART_NONE;
+}
+
+// one wave per gate: the members of the cones rooted so far are covered
+__global__ void part_cover_kernel(int64_t n, const uint8_t* kind, const int64_t* nbr_ptr, const int32_t* nbr_idx, uint8_t* covered)
+{
+    const int64_t v = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (v >= n || kind[v] == PART_NONE) return;
+    for (int64_t j = nbr_ptr[v] + lane; j < nbr_ptr[v + 1]; j += 64) covered[nbr_idx[j]] = 1;
+}
+
+// sort key of position q of the (level, id) order: roots by (level, kind), everything else behind them
+__global__ void part_key_kernel(int64_t n, const int32_t* order, const int32_t* level, uint8_t* kind, const uint8_t* covered,
+                                uint32_t none_key, uint32_t* key, unsigned long long* n_roots)
+{
+    const int64_t q = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (q >= n) return;
+    const int32_t v = order[q];
+    uint8_t kd = kind[v];
+    if (kd == PART_NONE && !covered[v]) { kd = 2; kind[v] = 2; }
+    key[q] = kd == PART_NONE ? none_key : ((uint32_t)level[v] << 2) | kd;
+    if (kd != PART_NONE) atomicAdd(n_roots, 1ull);
+}
+
+__global__ void part_fill_stage_kernel(int64_t n, int32_t* stage)
+{
+    const int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < n) stage[v] = INT32_MAX;
+}
+
+// one wave per cone: a gate is computed by the first mini-batch that holds it
+__global__ void part_stage_kernel(int64_t n_cones, const int32_t* cone_root, const int32_t* cone_stage,
+                                  const int64_t* nbr_ptr, const int32_t* nbr_idx, int32_t* stage)
+{
+    const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (c >= n_cones) return;
+    const int32_t r = cone_root[c];
+    const int32_t st = cone_stage[c];
+    for (int64_t j = nbr_ptr[r] + lane; j < nbr_ptr[r + 1]; j += 64) atomicMin(&stage[nbr_idx[j]], st);
+}
+
+// one wave per cone, a lane per member v computed in the cone's mini-batch: the entries of row(v) that
+// also lie in row(root) are kept (two rows of ascending ids, merged; every writer stores the same byte)
+__global__ void part_keep_kernel(int64_t n_cones, const int32_t* cone_root, const int32_t* cone_stage, const int32_t* stage,
+                                 const int64_t* nbr_ptr, const int32_t* nbr_idx, uint8_t* keep)
+{
+    const int64_t c = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (c >= n_cones) return;
+    const int32_t r = cone_root[c];
+    const int32_t st = cone_stage[c];
+    const int64_t r0 = nbr_ptr[r], r1 = nbr_ptr[r + 1];
+    for (int64_t j = r0 + lane; j < r1; j += 64) {
+        const int32_t v = nbr_idx[j];
+        if (stage[v] != st) continue;
+        int64_t a = nbr_ptr[v], b = r0;
+        const int64_t a1 = nbr_ptr[v + 1];
+        while (a < a1 && b < r1) {
+            const int32_t x = nbr_idx[a], y = nbr_idx[b];
+            if (x == y) { keep[a] = 1; ++a; ++b; }
+            else if (x < y) ++a;
+            else ++b;
+        }
+    }
+}
+
+// one wave per gate: kept entries counted, then (FILL) written in order behind new_ptr[v]
+template <bool FILL>
+__global__ void part_compact_kernel(int64_t n, const int64_t* nbr_ptr, const int32_t* nbr_idx, const uint8_t* nbr_rel, const uint8_t* keep,
+                                    int64_t* cnt, const int64_t* new_ptr, int32_t* new_idx, uint8_t* new_rel)
+{
+    const int64_t v = ((int64_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    if (v >= n) return;
+    int64_t out = FILL ? new_ptr[v] : 0;
+    for (int64_t j0 = nbr_ptr[v]; j0 < nbr_ptr[v + 1]; j0 += 64) {
+        const int64_t j = j0 + lane;
+        const bool k = j < nbr_ptr[v + 1] && keep[j] != 0;
+        const unsigned long long m = __ballot(k);
+        if (FILL && k) {
+            const int64_t o = out + __popcll(m & ((1ull << lane) - 1ull));
+            new_idx[o] = nbr_idx[j]; new_rel[o] = nbr_rel[j];
+        }
+        out += __popcll(m);
+    }
+    if (!FILL && lane == 0) cnt[v] = out;
+}
+
 // Device memory of one call: carved out of at most two allocations (the tables sized by the node
 // count, then those sized by the number of neighbour entries), released when the call returns.
 struct Arena {
@@ -252,11 +360,9 @@ inline unsigned blocks_for(int64_t items) { return (unsigned)((items + 255) / 25
 #define GPU_CHECK(expr) do { if ((expr) != hipSuccess) return DG4_EHIP; } while (0)
 #define GPU_ALLOC(var, T, count, zero) T* var = arena.get<T>((count), (zero), s); if (!var) return DG4_ENOMEM
 
-}  // namespace
-
-extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
-                                       const uint8_t* ei, int32_t hops, const int32_t* level_hint,
-                                       void* stream, dg4_graph** out)
+// stride == 0: plain cone rows; else the rows of the partitioned update with marks
+int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, const uint8_t* ei, int32_t hops,
+                 const int32_t* level_hint, int32_t stride, int32_t batch, void* stream, dg4_graph** out)
 {
     if (!out || n < 0 || e < 0 || (e > 0 && (!es || !ed || !ei))) return DG4_EINVAL;
     if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
@@ -382,6 +488,81 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
             if (ptr_prev != nbr_ptr)             // the last hop's pointers, where the copies below expect them
                 GPU_CHECK(hipMemcpyAsync(nbr_ptr, ptr_prev, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
         }
+        // ---- partition and updating strategy: roots, mini-batch numbers, rows restricted to the cones
+        // a gate shares with the mini-batch that computes it (the host analysis, step by step)
+        int32_t* stage = nullptr;
+        if (stride > 0) {
+            GPU_ALLOC(is_read, uint8_t, (size_t)n, true);
+            GPU_ALLOC(kind, uint8_t, (size_t)n, false);
+            GPU_ALLOC(covered, uint8_t, (size_t)n, true);
+            GPU_ALLOC(pkey, uint32_t, (size_t)n, false);
+            GPU_ALLOC(pkey_sorted, uint32_t, (size_t)n, false);
+            GPU_ALLOC(roots_sorted, int32_t, (size_t)n, false);
+            GPU_ALLOC(n_roots_d, unsigned long long, 1, true);
+            const unsigned nb_wave = blocks_for(n * 64);
+            hipLaunchKernelGGL(part_read_kernel, dim3(nb), dim3(256), 0, s, n, fin, deg, is_read);
+            hipLaunchKernelGGL(part_kind_kernel, dim3(nb), dim3(256), 0, s, n, hops, stride, level, is_read, kind);
+            hipLaunchKernelGGL(part_cover_kernel, dim3(nb_wave), dim3(256), 0, s, n, kind, nbr_ptr, nbr_idx, covered);
+            const uint32_t none_key = ((uint32_t)h_max + 1u) << 2;
+            hipLaunchKernelGGL(part_key_kernel, dim3(nb), dim3(256), 0, s, n, order, level, kind, covered, none_key, pkey, n_roots_d);
+            int key_bits = 1;
+            while (key_bits < 32 && (none_key >> key_bits) != 0) ++key_bits;
+            size_t psort_bytes = 0;
+            GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(nullptr, psort_bytes, pkey, pkey_sorted, order, roots_sorted, (int)n, 0, key_bits, s));
+            GPU_ALLOC(psort_tmp, unsigned char, psort_bytes, false);
+            GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(psort_tmp, psort_bytes, pkey, pkey_sorted, order, roots_sorted, (int)n, 0, key_bits, s));
+            unsigned long long n_roots = 0;
+            GPU_CHECK(hipMemcpyAsync(&n_roots, n_roots_d, sizeof(n_roots), hipMemcpyDeviceToHost, s));
+            GPU_CHECK(hipStreamSynchronize(s));
+            // the lists (one per level that has roots) and the running number of every cone's mini-batch
+            std::vector<uint32_t> keys((size_t)n_roots);
+            g->cone_root.resize((size_t)n_roots);
+            GPU_CHECK(hipMemcpyAsync(keys.data(), pkey_sorted, (size_t)n_roots * 4, hipMemcpyDeviceToHost, s));
+            GPU_CHECK(hipMemcpyAsync(g->cone_root.data(), roots_sorted, (size_t)n_roots * 4, hipMemcpyDeviceToHost, s));
+            GPU_CHECK(hipStreamSynchronize(s));
+            std::vector<int32_t> cone_stage((size_t)n_roots);
+            int32_t next_stage = 0;
+            for (size_t c = 0; c < (size_t)n_roots;) {
+                const uint32_t l = keys[c] >> 2;
+                size_t c1 = c;
+                while (c1 < (size_t)n_roots && (keys[c1] >> 2) == l) ++c1;
+                g->cone_group_level.push_back((int32_t)l);
+                g->cone_group_ptr.push_back((int64_t)c);
+                for (size_t i = c; i < c1; ++i) cone_stage[i] = next_stage + (int32_t)((i - c) / (size_t)batch);
+                next_stage += (int32_t)((c1 - c + (size_t)batch - 1) / (size_t)batch);
+                c = c1;
+            }
+            g->cone_group_ptr.push_back((int64_t)n_roots);
+            g->stride = stride; g->batch_cones = batch;
+            GPU_ALLOC(cone_stage_d, int32_t, (size_t)n_roots, false);
+            GPU_CHECK(hipMemcpyAsync(cone_stage_d, cone_stage.data(), (size_t)n_roots * 4, hipMemcpyHostToDevice, s));
+            stage = arena.get<int32_t>((size_t)n, false, s);
+            if (!stage) return DG4_ENOMEM;
+            hipLaunchKernelGGL(part_fill_stage_kernel, dim3(nb), dim3(256), 0, s, n, stage);
+            const unsigned cb_wave = blocks_for((int64_t)n_roots * 64);
+            if (n_roots)
+                hipLaunchKernelGGL(part_stage_kernel, dim3(cb_wave), dim3(256), 0, s, (int64_t)n_roots, roots_sorted, cone_stage_d, nbr_ptr, nbr_idx, stage);
+            if (!arena.reserve((size_t)nnz + 1024)) return DG4_ENOMEM;
+            uint8_t* keep = arena.get<uint8_t>((size_t)nnz, true, s);
+            if (!keep) return DG4_ENOMEM;
+            if (n_roots)
+                hipLaunchKernelGGL(part_keep_kernel, dim3(cb_wave), dim3(256), 0, s, (int64_t)n_roots, roots_sorted, cone_stage_d, stage, nbr_ptr, nbr_idx, keep);
+            GPU_ALLOC(part_ptr, int64_t, (size_t)n + 1, false);
+            hipLaunchKernelGGL(part_compact_kernel<false>, dim3(nb_wave), dim3(256), 0, s, n, nbr_ptr, nbr_idx, nbr_rel, keep,
+                               cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (uint8_t*)nullptr);
+            GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, part_ptr, (int)(n + 1), s));
+            int64_t nnz2 = 0;
+            GPU_CHECK(hipMemcpyAsync(&nnz2, part_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
+            GPU_CHECK(hipStreamSynchronize(s));        // (the stream's copy of cone_stage has been consumed too)
+            if (!arena.reserve((size_t)nnz2 * 5 + 1024)) return DG4_ENOMEM;
+            int32_t* idx2 = arena.get<int32_t>((size_t)nnz2, false, s);
+            uint8_t* rel2 = arena.get<uint8_t>((size_t)nnz2, false, s);
+            if (!idx2 || !rel2) return DG4_ENOMEM;
+            hipLaunchKernelGGL(part_compact_kernel<true>, dim3(nb_wave), dim3(256), 0, s, n, nbr_ptr, nbr_idx, nbr_rel, keep,
+                               (int64_t*)nullptr, (const int64_t*)part_ptr, idx2, rel2);
+            GPU_CHECK(hipMemcpyAsync(nbr_ptr, part_ptr, ((size_t)n + 1) * sizeof(int64_t), hipMemcpyDeviceToDevice, s));
+            nbr_idx = idx2; nbr_rel = rel2; nnz = nnz2;
+        }
         g->nnz = nnz;
 
         // fanout counts of the structural encoding
@@ -405,6 +586,10 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
         GPU_CHECK(hipMemcpyAsync(g->nbr_rel.data(), nbr_rel, (size_t)nnz, hipMemcpyDeviceToHost, s));
         GPU_CHECK(hipMemcpyAsync(g->out_and.data(), out_and, (size_t)n * 4, hipMemcpyDeviceToHost, s));
         GPU_CHECK(hipMemcpyAsync(g->out_not.data(), out_not, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        if (stage) {
+            g->stage.resize((size_t)n);
+            GPU_CHECK(hipMemcpyAsync(g->stage.data(), stage, (size_t)n * 4, hipMemcpyDeviceToHost, s));
+        }
         GPU_CHECK(hipStreamSynchronize(s));
         for (int64_t p = 0; p < n; ++p) g->pos[(size_t)g->order[(size_t)p]] = (int32_t)p;
         *out = g.release();
@@ -414,4 +599,22 @@ extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, 
     } catch (...) {
         return DG4_EINVAL;
     }
+}
+
+}  // namespace
+
+extern "C" int dg4_build_levels_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
+                                       const uint8_t* ei, int32_t hops, const int32_t* level_hint,
+                                       void* stream, dg4_graph** out)
+{
+    return build_device(n, e, es, ed, ei, hops, level_hint, 0, 0, stream, out);
+}
+
+extern "C" int dg4_build_partitioned_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed,
+                                            const uint8_t* ei, int32_t hops, const int32_t* level_hint,
+                                            int32_t stride, int32_t batch_cones, void* stream, dg4_graph** out)
+{
+    if (hops < 1 || hops > DG4_MAX_HOPS) return DG4_EUNSUPPORTED;
+    if (stride < 1 || stride >= hops || batch_cones < 1) return DG4_EINVAL;
+    return build_device(n, e, es, ed, ei, hops, level_hint, stride, batch_cones, stream, out);
 }

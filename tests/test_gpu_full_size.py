@@ -188,6 +188,13 @@ def test_full_size_partitioned_k8():
     for name, ref in zip(("nbr_ptr", "nbr_idx", "nbr_rel"), rows):
         assert (g.array(name) == ref).all(), name
     print("  tables equal", flush=True)
+    # the same partition analysed on the GPU: every table again, bit for bit
+    gd = dg4.dg4_build_partitioned_device(n, *(torch.from_numpy(a).cuda() for a in (w.edge_src, w.edge_dst, w.edge_inv)), 8, 6, 128,
+                                          None if w.level_hint is None else torch.from_numpy(w.level_hint).cuda())
+    for name in ("level", "order", "level_ptr", "nbr_ptr", "nbr_idx", "nbr_rel", "stage", "cone_root", "cone_group_level", "cone_group_ptr"):
+        assert np.array_equal(gd.array(name), g.array(name)), name
+    del gd
+    print("  device analysis equal", flush=True)
     cut = oracle.Graph(n, og.level, og.order, og.level_ptr, rows[0], rows[1], rows[2], 8)
     rng = np.random.default_rng(2)
     nodes = np.unique(np.concatenate([rng.choice(n, size=500, replace=False), og.order[-50:], og.order[:50]]))

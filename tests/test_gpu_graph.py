@@ -129,3 +129,53 @@ def test_full_size_and_the_sweep_on_a_device_built_graph():
     dg4.dg4_layer_fwd(cfg, gh, X, W, H2)
     torch.cuda.synchronize()
     assert torch.equal(H1, H2)
+
+
+# ---- dg4_build_partitioned_device: Algorithm 1's lists, the mini-batch of every gate and the restricted rows
+
+PART_TABLES = TABLES + ("cone_root", "cone_group_level", "cone_group_ptr", "stage", "out_and", "out_not")
+
+
+def partition_on_gpu(n, src, dst, inv, k, delta, batch, hint=None):
+    return dg4.dg4_build_partitioned_device(n, dev(src, np.int32), dev(dst, np.int32), dev(inv, np.uint8), k, delta, batch,
+                                            None if hint is None else dev(hint, np.int32))
+
+
+@pytest.mark.parametrize("seed,k,delta,batch,cap", [
+    (1, 3, 2, 1, 0), (2, 3, 2, 4, 0), (3, 3, 1, 3, 0), (4, 2, 1, 128, 0), (7, 3, 2, 3, 30), (9, 3, 2, 2, -1),
+    (12, 8, 6, 128, 0), (13, 8, 6, 4, -1), (14, 5, 3, 16, 40), (15, 8, 7, 1, 0),
+])
+def test_partition_on_device_small_graphs_against_the_oracle(seed, k, delta, batch, cap):
+    from test_host_partition import oracle_run, same_partition
+    from test_oracle_partition import irregular
+    print(f"device partition seed={seed} k={k} stride={delta} batch={batch} cap={cap}", flush=True)
+    n, src, dst, inv, hint = irregular(seed, n_and=300, window=24, cap=cap)
+    g = partition_on_gpu(n, src, dst, inv, k, delta, batch, hint)
+    same_partition(g, *oracle_run(n, src, dst, inv, k, delta, batch, hint))       # Algorithms 1 and 2 run literally
+
+
+@pytest.mark.parametrize("name,n_and,k,delta,batch,hint", [
+    ("tiny", None, 3, 2, 128, False), ("small", None, 3, 2, 128, False), ("medium", 30_000, 2, 1, 16, False),
+    ("tiny", None, 8, 6, 128, False), ("stress", 20_000, 8, 6, 128, True), ("medium", 40_000, 8, 6, 128, False),
+    ("large", 50_000, 5, 3, 64, True),
+])
+def test_partition_on_device_matches_the_host_call(name, n_and, k, delta, batch, hint):
+    print(f"device partition {name} n_and={n_and} k={k} stride={delta} batch={batch} hint={hint}", flush=True)
+    w = synth.make(name, n_and=n_and, features=False)
+    n = w.cfg.n_nodes
+    h = w.level_hint if hint else None
+    g = partition_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, k, delta, batch, h)
+    gh = dg4.dg4_build_partitioned(n, w.edge_src, w.edge_dst, w.edge_inv, k, delta, batch, level_hint=h)
+    assert g.n == gh.n and g.nnz == gh.nnz and g.n_levels == gh.n_levels
+    for a in PART_TABLES:
+        assert np.array_equal(g.array(a), gh.array(a)), a
+
+
+def test_partition_on_device_rejects_what_the_host_call_rejects():
+    w = synth.make("tiny", features=False)
+    n = w.cfg.n_nodes
+    for k, delta, batch in ((3, 3, 4), (3, 0, 4), (3, 2, 0)):
+        with pytest.raises(dg4.DG4Error):
+            partition_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, k, delta, batch)
+    with pytest.raises(dg4.DG4Error):
+        partition_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, 9, 6, 4)

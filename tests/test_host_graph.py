@@ -18,7 +18,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def test_library_exports_every_declared_symbol():
     hdr = open(os.path.join(ROOT, "include", "dg4.h")).read()
     names = set(re.findall(r"^(?:int|int64_t|void|const char\*)\s+(dg4_[a-z_]+)\s*\(", hdr, flags=re.M))
-    assert len(names) == 21
+    assert len(names) == 22
     assert {"dg4_build_levels", "dg4_qkv_proj", "dg4_sparse_attn_fwd", "dg4_layer_fwd", "dg4_struct_encode"} <= names
     L = ctypes.CDLL(dg4.library_path()) if os.path.exists(dg4.library_path()) else dg4.lib()
     for n in sorted(names):
