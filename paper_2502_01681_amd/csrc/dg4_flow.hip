@@ -1,6 +1,7 @@
 // The level sweep as one persistent dataflow kernel, for every shape: fp32 with hidden 128 or bf16 with
 // hidden 256 (rows of 512 bytes either way), cones of up to three hops (neighbour rows of 8 or 16
-// entries), any number of stacked layers.
+// entries) or deeper ones (rows of any width, several lane groups per gate), 1 to 16 stacked layers,
+// with or without the feed-forward sub-block.
 //
 // The updating strategy (paper Section 3.4, Algorithm 2) requires that a gate reads the FINAL
 // embeddings of its cone sources and is itself computed once; with several layers a gate runs all
@@ -12,10 +13,12 @@
 // instead of a hang.
 //
 // Per tile (eight waves): wait for the "published" flags of the sources of its gates; then per layer
-// the attention over the cone rows (16 lanes per gate split the feature dimension, attend_core), the
-// output projection on the matrix cores, residual + LayerNorm, and the Q | K | V projection of the
-// new state for the next layer, into LDS; after the last layer the embeddings go out and K | V of
-// every layer are projected from them into the store of finished gates. Projections run on blocks of
+// the attention over the cone rows (16 lanes per gate split the feature dimension; sources are read
+// through a structured buffer over the layer's K | V store, so that an entry that is no source costs
+// neither a branch nor a request and a lane has 32 row halves in flight; the gate's own rows and its
+// neighbour row sit in LDS), the output projection on the matrix cores, residual + LayerNorm, and the
+// Q | K | V projection of the new state for the next layer, into LDS; after the last layer the
+// embeddings go out and K | V of every layer are projected from them into the store of finished gates. Projections run on blocks of
 // 16 gates with the WEIGHT as the A operand of a 16x16 product and the gates as B: a lane ends up
 // with 16 contiguous bytes of ONE gate's row, so residual, LayerNorm and the stores need no
 // transposition, and a tile of at most 16 gates costs half the matrix-core time of a full one (what
