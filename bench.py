@@ -467,6 +467,22 @@ def main():
                                               "without_marks": {"step_ms_device": ms_u, "gate_computations": ug.n, "neighbour_edges": ug.nnz},
                                               "work_ratio": ug.n / mg.n, "time_ratio": ms_u / ms_m}
         del PX, pg, UX, ug, mg, rm, ru
+        # The same ablation at the paper's own k = 8, stride 6, mini-batches of 128 cones, on a circuit of the same
+        # shape with a tenth of the gates (on the full one the copies' tables alone would take tens of GB).
+        kc = synth.Config(**{**pc.__dict__, "n_and": 20_000, "hops": 8})
+        kw = synth.make(kc)
+        KX, KW = tensors(kw, kc)
+        mg = dg4.dg4_build_partitioned(kc.n_nodes, kw.edge_src, kw.edge_dst, kw.edge_inv, 8, 6, 128, kw.level_hint)
+        ug = dg4.dg4_build_partitioned(kc.n_nodes, kw.edge_src, kw.edge_dst, kw.edge_inv, 8, 6, 128, kw.level_hint, marks=False)
+        UX = KX[torch.from_numpy(ug.array("copy_of").astype(np.int64)).cuda()].contiguous()
+        rm, ru = time_layer(kc, mg, KX, KW, 3, 2), time_layer(kc, ug, UX, KW, 3, 2)
+        out["partition"]["marks_ablation_k8"] = {
+            "workload": f"medium-shaped, {kc.n_pi} PIs + {kc.n_and} ANDs, 8-hop cones, stride 6, mini-batches of 128 cones",
+            "path": path_of(kc, mg, {}),
+            "with_marks": {"step_ms_device": rm["ms_dev"], "gate_computations": mg.n, "neighbour_edges": mg.nnz},
+            "without_marks": {"step_ms_device": ru["ms_dev"], "gate_computations": ug.n, "neighbour_edges": ug.nnz},
+            "work_ratio": ug.n / mg.n, "time_ratio": ru["ms_dev"] / rm["ms_dev"]}
+        del KX, UX, ug, mg, rm, ru
 
     if not args.no_cpu_baseline and not part:
         import oracle
