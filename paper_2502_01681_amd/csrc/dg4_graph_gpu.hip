@@ -373,6 +373,7 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
         g->n = n; g->e = e; g->hops = hops;
         if (n == 0) {
             g->level_ptr.assign(2, 0); g->nbr_ptr.assign(1, 0);
+            if (stride > 0) { g->cone_group_ptr.assign(1, 0); g->stride = stride; g->batch_cones = batch; }
             *out = g.release();
             return DG4_OK;
         }

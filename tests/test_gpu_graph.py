@@ -179,3 +179,10 @@ def test_partition_on_device_rejects_what_the_host_call_rejects():
             partition_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, k, delta, batch)
     with pytest.raises(dg4.DG4Error):
         partition_on_gpu(n, w.edge_src, w.edge_dst, w.edge_inv, 9, 6, 4)
+    # an empty circuit and one of primary inputs only: the host call's tables
+    none = np.empty(0, np.int32)
+    for n_pi in (0, 5):
+        g = partition_on_gpu(n_pi, none, none, np.empty(0, np.uint8), 3, 2, 4)
+        gh = dg4.dg4_build_partitioned(n_pi, none, none, np.empty(0, np.uint8), 3, 2, 4)
+        for a in ("nbr_ptr", "nbr_idx", "cone_root", "cone_group_level", "cone_group_ptr") + (("stage",) if n_pi else ()):
+            assert np.array_equal(g.array(a), gh.array(a)), (n_pi, a)
