@@ -46,8 +46,8 @@
  *       inverted edge into an AND], OutAND(v) = #non-inverted edges into ANDs. Each
  *       Emb is a linear layer on a scalar, s*w + b; the encoding is added to the
  *       initial embedding.
- *   R16 "the original transformer structure" (Section 3.5) read as the post-norm encoder
- *       block: after the attention sub-block h = LN(s + a Wo) comes the position-wise
+ *   R16 Section 3.5 swaps the attention module for a GAT module and keeps the rest of the
+ *       transformer layer as it is; read as the post-norm encoder block: after the attention sub-block h = LN(s + a Wo) comes the position-wise
  *       feed-forward sub-block s' = LN(h + max(h W1, 0) W2), W1 [d, 4d], W2 [4d, d],
  *       rectifier, no biases (R10), LayerNorm as in R7. Optional: a layer without
  *       W1 / W2 is the attention sub-block alone.

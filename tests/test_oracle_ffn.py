@@ -1,5 +1,5 @@
-"""Pins of the oracle's feed-forward sub-block (the post-norm encoder block read out of
-Section 3.5's "original transformer structure": s' = LN(h + relu(h W1) W2) after the
+"""Pins of the oracle's feed-forward sub-block (the post-norm encoder block that Section 3.5's
+unchanged rest of the transformer layer is read as: s' = LN(h + relu(h W1) W2) after the
 attention sub-block).
 
 Pinned by mathematics, as the paper prints no value: the dense brute force (library
