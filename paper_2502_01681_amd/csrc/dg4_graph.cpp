@@ -618,6 +618,39 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
             for (int64_t v = 0; v < g->n; ++v)
                 for_each_fanin(v, [&](int32_t u) { fo[(size_t)fill[u]++] = (int32_t)v; });
         }
+        // Gates per tile. A tile is published as a whole and waits for the sources of all its gates, so on a
+        // deep, narrow circuit (few gates per dependency level, most compute units idle) small tiles shorten
+        // the chain from level to level: a gate then waits for its own sources and little else (medium, 264
+        // gates per level, through the register-resident kernel: 6.05 ms with tiles of 16, 5.47 with 4, 4.86
+        // with 2, 4.95 with 1). Wide circuits keep 16: there the number of tiles is what costs. The width is
+        // gates over the depth of the dependencies scheduled here (one pass in topological order).
+        int cap_rows = DG4_TILE_ROWS;
+        {
+            std::vector<int32_t> rem(remaining), depth_of((size_t)g->n, 0), queue;
+            queue.reserve((size_t)g->n);
+            for (int64_t v = 0; v < g->n; ++v)
+                if (rem[v] == 0) queue.push_back((int32_t)v);
+            int32_t deepest = 0;
+            for (size_t i = 0; i < queue.size(); ++i) {
+                const int32_t v = queue[i];
+                deepest = std::max(deepest, depth_of[v]);
+                for (int64_t j = fo_ptr[v]; j < fo_ptr[v + 1]; ++j) {
+                    const int32_t u = fo[(size_t)j];
+                    depth_of[u] = std::max(depth_of[u], depth_of[v] + 1);
+                    if (--rem[u] == 0) queue.push_back(u);
+                }
+            }
+            const int64_t width = g->n / ((int64_t)deepest + 1);
+            if (pairs) {
+                // (the dataflow kernel for the other shapes, which takes the tiles of this table one by one on
+                // narrow circuits, has the larger fixed cost per tile: 8 gates there, e.g. 105 -> 99 ms for
+                // twelve layers on medium; a level of a handful of gates is best left in one tile)
+                if (width >= 64 && width <= 8 * DG4_SCHED_TILES_PER_LEVEL) cap_rows = 8;
+            } else {
+                cap_rows = 2;
+                while (cap_rows < DG4_TILE_ROWS && width > (int64_t)cap_rows * DG4_SCHED_TILES_PER_LEVEL) cap_rows *= 2;
+            }
+        }
         // the ready list is a queue of batches, one per tile, each sorted by (level, id)
         auto before = [&](int32_t a, int32_t b) { return g->level[a] != g->level[b] ? g->level[a] < g->level[b] : a < b; };
         std::vector<int32_t> ready;                 // the queue: taken from `head`, appended at the end
@@ -631,8 +664,8 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
         int64_t q = 0;
         while (head < ready.size()) {
             const int64_t first = q;
-            for (int k = 0; k < (pairs ? 2 : 1) * DG4_TILE_ROWS && head < ready.size(); ++k) flow[(size_t)q++] = ready[head++];
-            if (pairs) tile_ptr.push_back(std::min<int64_t>(first + DG4_TILE_ROWS, q));
+            for (int k = 0; k < (pairs ? 2 : 1) * cap_rows && head < ready.size(); ++k) flow[(size_t)q++] = ready[head++];
+            if (pairs) tile_ptr.push_back(std::min<int64_t>(first + cap_rows, q));
             tile_ptr.push_back(q);
             const size_t fresh = ready.size();      // eligible from the next tile on
             for (int64_t p = first; p < q; ++p) {

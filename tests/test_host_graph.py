@@ -67,7 +67,8 @@ def test_dataflow_order_is_a_valid_schedule(name, n_and, hops, hint):
     assert sorted(order.tolist()) == list(range(n))
     assert tp[0] == 0 and tp[-1] == n
     rows = np.diff(tp)
-    assert rows.min() >= 1 and rows.max() <= 16
+    cap = int(rows.max())                                  # the tile size the scheduler chose for this circuit
+    assert rows.min() >= 1 and cap in (2, 4, 8, 16)
     tile_of = np.empty(n, dtype=np.int64)
     tile_of[order] = np.repeat(np.arange(len(rows)), rows)
     ptr, idx = g.array("nbr_ptr"), g.array("nbr_idx")
@@ -76,10 +77,22 @@ def test_dataflow_order_is_a_valid_schedule(name, n_and, hops, hint):
     assert (tile_of[idx[other]] < tile_of[dst[other]]).all()
     # a primary input has no source: all of them fit into the leading tiles, which are full
     n_pi = int((np.diff(ptr) == 1).sum())
-    assert (rows[: n_pi // 16] == 16).all()
+    assert (rows[: n_pi // cap] == cap).all()
     # the same graph gives the same order again
     g2 = dg4.dg4_build_levels(n, w.edge_src, w.edge_dst, w.edge_inv, hops, w.level_hint if hint else None)
     assert (g2.array("flow_order") == order).all()
+
+
+def test_tile_size_follows_the_width_of_the_circuit():
+    # deep and narrow (a few hundred gates per dependency level): small tiles, so that a gate waits for its
+    # own sources and little else; wide: full tiles of 16 (pairs: 8 and 16)
+    deep = synth.make("medium", n_and=100_000, features=False)
+    wide = synth.make("large", n_and=200_000, features=False)
+    sizes = {}
+    for tag, w in (("deep", deep), ("wide", wide)):
+        g = dg4.dg4_build_levels(w.cfg.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, 2, w.level_hint)
+        sizes[tag] = (int(np.diff(g.array("flow_tile_ptr")).max()), int(np.diff(g.array("pair_tile_ptr")).max()))
+    assert sizes["deep"] == (2, 8) and sizes["wide"] == (16, 16), sizes
 
 
 @pytest.mark.parametrize("name,n_and,hint", [("tiny", None, False), ("medium", 30_000, False), ("large", 40_000, True)])
@@ -93,9 +106,10 @@ def test_pair_order_is_a_valid_schedule(name, n_and, hint):
     assert sorted(order.tolist()) == list(range(n))
     assert tp[0] == 0 and tp[-1] == n and (len(tp) - 1) % 2 == 0
     rows = np.diff(tp)
-    assert rows.min() >= 0 and rows.max() <= 16
+    cap = int(rows.max())
+    assert rows.min() >= 0 and cap in (8, 16)
     assert (rows[0::2] >= 1).all()                         # only a second tile may be empty ...
-    assert (rows[1::2][rows[0::2] < 16] == 0).all()        # ... and is, unless the first one is full
+    assert (rows[1::2][rows[0::2] < cap] == 0).all()       # ... and is, unless the first one is full
     pair_of = np.empty(n, dtype=np.int64)
     pair_of[order] = np.repeat(np.arange(len(rows)), rows) // 2
     ptr, idx = g.array("nbr_ptr"), g.array("nbr_idx")
