@@ -622,8 +622,10 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
         // deep, narrow circuit (few gates per dependency level, most compute units idle) small tiles shorten
         // the chain from level to level: a gate then waits for its own sources and little else (medium, 264
         // gates per level, through the register-resident kernel: 6.05 ms with tiles of 16, 5.47 with 4, 4.86
-        // with 2, 4.95 with 1). Wide circuits keep 16: there the number of tiles is what costs. The width is
-        // gates over the depth of the dependencies scheduled here (one pass in topological order).
+        // with 2, 4.95 with 1). Wide circuits keep 16: there the number of tiles is what costs. Best measured
+        // sizes: 2 at 264 and 515 gates per level, 4 at 966, 8 at 1718, 16 at 3092: about one tile per compute
+        // unit and level. The width is gates over the depth of the dependencies scheduled here (one pass in
+        // topological order).
         int cap_rows = DG4_TILE_ROWS;
         {
             std::vector<int32_t> rem(remaining), depth_of((size_t)g->n, 0), queue;
@@ -645,7 +647,7 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
                 // (the dataflow kernel for the other shapes, which takes the tiles of this table one by one on
                 // narrow circuits, has the larger fixed cost per tile: 8 gates there, e.g. 105 -> 99 ms for
                 // twelve layers on medium; a level of a handful of gates is best left in one tile)
-                if (width >= 64 && width <= 8 * DG4_SCHED_TILES_PER_LEVEL) cap_rows = 8;
+                if (width >= 64 && width <= 1536) cap_rows = 8;
             } else {
                 cap_rows = 2;
                 while (cap_rows < DG4_TILE_ROWS && width > (int64_t)cap_rows * DG4_SCHED_TILES_PER_LEVEL) cap_rows *= 2;

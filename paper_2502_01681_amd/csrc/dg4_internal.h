@@ -16,8 +16,9 @@
 // (relation code << 30 | index), padded with DG4_ELL_PAD. Width = 2^(hops+1), at least 8:
 // one more than the largest cone (Section 3.2), so a row always ends in a pad.
 #define DG4_ELL_PAD 0xFFFFFFFFu
-// tiles of one dependency level that the schedules aim to stay below (three quarters of the 256 compute units)
-#define DG4_SCHED_TILES_PER_LEVEL 192
+// tiles of one dependency level that the schedule of the register-resident kernel aims to stay below (1.25 x the 256
+// compute units: measured on circuits of 264 ... 3092 gates per level)
+#define DG4_SCHED_TILES_PER_LEVEL 320
 #define DG4_MAX_LAYERS 16        // the paper stacks 12 (Section 4.1)
 #define DG4_TILE_ROWS 16          // gates per tile of the persistent sweep
 #define DG4_MAX_SWEEP_GROUPS 1024 // most workgroups the persistent sweep is launched with (one per compute unit)
