@@ -646,8 +646,9 @@ static int flow_schedule(const dg4_graph* g, bool pairs, std::vector<int32_t>& o
             if (pairs) {
                 // (the dataflow kernel for the other shapes, which takes the tiles of this table one by one on
                 // narrow circuits, has the larger fixed cost per tile: 8 gates there, e.g. 105 -> 99 ms for
-                // twelve layers on medium; a level of a handful of gates is best left in one tile)
-                if (width >= 64 && width <= 1536) cap_rows = 8;
+                // twelve layers on medium; a level of a handful of gates is best left in one tile; three-hop
+                // cones, one layer: 8 is best or within 4 % of it from 264 to 1718 gates per level, 16 at 3092)
+                if (width >= 64 && width <= 2560) cap_rows = 8;
             } else {
                 cap_rows = 2;
                 while (cap_rows < DG4_TILE_ROWS && width > (int64_t)cap_rows * DG4_SCHED_TILES_PER_LEVEL) cap_rows *= 2;
