@@ -480,6 +480,9 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         const int64_t p0 = cur.x;
         const int rows = (int)cur.y;
         const bool has_next = q1 < p.n_tiles;
+        // (a wave none of whose four gates exists in the next tile, as on the small tiles of narrow circuits,
+        // has no rows to request for it)
+        const bool wave_gathers = has_next && 4 * wave < (int)nxt.y;
         const bool second = FFN && (q0 & 1) != 0;             // second tile of a feed-forward pair
         const bool first = FFN && !second;
         roles();
@@ -701,7 +704,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                 // (the gathers are spread out: a wave that issues more transfers than the memory
                 // pipeline takes stalls until they have drained. Slots 0 .. 2 go here, 3 .. 5 below,
                 // around the output projection)
-                if (has_next) {
+                if (wave_gathers) {
                     if (r == 0) issue_slots<0, 1>(src_lo, src_hi, lane16, wave_land);
                     else if (r == 1) issue_slots<1, 3>(src_lo, src_hi, lane16, wave_land);
                 }
@@ -722,7 +725,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
         if (sAbort) { flush(); return; }
         const int q3 = draws ? __builtin_amdgcn_readfirstlane(sTick[0]) : q2 + 1;
         lap(2);
-        if (has_next) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
+        if (wave_gathers) issue_slots<3, 5>(keep_lo, keep_hi, lane16, wave_land);
         if (second) {
             // the rows the first tile of the pair parked in global memory come back into the places
             // of the gates' own K|V, which the attention has finished with (512 bytes a gate, each
@@ -754,7 +757,7 @@ __global__ __launch_bounds__(256, 1) void sweep_kernel(dg4_sweep_args p)
                     acc[nt] = mfma16(nt == 3 && ks == 7 ? *sWoF : __builtin_bit_cast(uint4, wo_r[nt][ks]), b,
                                      ks == 0 ? (f32x4){0.f, 0.f, 0.f, 0.f} : acc[nt]);
             }
-                if (has_next) issue_slots<5, 6>(keep_lo, keep_hi, lane16, wave_land);
+                if (wave_gathers) issue_slots<5, 6>(keep_lo, keep_hi, lane16, wave_land);
             float x[16];
             {
                 const uint4* xp = (const uint4*)(sLand + n * LAND_GATE + LAND_X + c0 * 2);
