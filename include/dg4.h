@@ -192,17 +192,18 @@ typedef enum {
     DG4_NBR_IDX = 4,    /* int32  [nnz]                                        */
     DG4_NBR_REL = 5,    /* uint8  [nnz]                                        */
     /* The order in which a sweep over ALL levels processes the gates on the device: tiles of at
-     * most 16 gates, each gate after every gate of its neighbour row (list scheduling over the
-     * real dependencies; the level only breaks ties). For inspection and tests; the embeddings do
-     * not depend on it. Built on first request. */
+     * most 16 gates (2, 4 or 8 on circuits with few gates per dependency level, where small tiles
+     * shorten the chain from level to level), each gate after every gate of its neighbour row
+     * (list scheduling over the real dependencies; the level only breaks ties). For inspection
+     * and tests; the embeddings do not depend on it. Built on first request. */
     DG4_FLOW_ORDER = 6,     /* int32 [n_nodes]     node ids in processing order          */
     DG4_FLOW_TILE_PTR = 7,  /* int64 [n_tiles + 1] first position of each tile           */
     /* Fanout counts of the structural encoding (Section 3.5, Eq. 2), see dg4_struct_encode. */
     DG4_OUT_AND = 8,        /* int32 [n_nodes]                                           */
     DG4_OUT_NOT = 9,        /* int32 [n_nodes]                                           */
-    /* The processing order of sweeps with DG4_FFN: tiles 2k and 2k+1 form a pair without
-     * dependencies between them (the second may be empty). Built on first request. For inspection
-     * and tests. */
+    /* The processing order of sweeps with DG4_FFN and of the streaming dataflow kernel: tiles 2k and
+     * 2k+1 (at most 16 gates each; 8 on narrow circuits) form a pair without dependencies between
+     * them (the second may be empty). Built on first request. For inspection and tests. */
     DG4_PAIR_ORDER = 10,    /* int32 [n_nodes]                                           */
     DG4_PAIR_TILE_PTR = 11, /* int64 [n_tiles + 1], n_tiles even                         */
     /* Graphs from dg4_build_partitioned only (EINVAL otherwise): Algorithm 1's lists and the
