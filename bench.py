@@ -183,7 +183,7 @@ def main():
             return "level-by-level launches"
         if c.dtype == "bf16" and c.hidden == 256 and c.n_layers == 1 and g.hops <= 2:
             return "sweep_kernel (persistent, weights resident in registers)"
-        if (flags.get("ffn") and g.hops > 3) or g.n * 1024 > 0xFFFFFFFF:      # (K|V stores of 4 GB or more per layer)
+        if flags.get("ffn") and g.hops > 3:
             return "level-by-level launches"
         return "flow_kernel (persistent, weights streamed" + (", several lane groups per neighbour row)" if g.hops > 3 else ")")
 

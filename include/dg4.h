@@ -325,9 +325,8 @@ int dg4_sparse_attn_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, int64_t row_begi
  * The order in which a sweep over ALL levels visits the gates is the library's (dependency-driven
  * tiles in the persistent kernels, Eq. 1 levels in level-by-level launches) and does not change a
  * bit of the result; DG4_LEVEL_ORDER forces the graph's own levels (for comparisons).
- * Persistent sweeps (everything but DG4_PER_LEVEL, DG4_BOUNDED_KV, DG4_FFN on rows wider than 16
- * entries, and graphs whose K|V store reaches 4 GB per layer, i.e. about 4.19 million gates, which
- * run level by level) hand tiles of gates to resident workgroups, which wait for the
+ * Persistent sweeps (everything but DG4_PER_LEVEL, DG4_BOUNDED_KV and DG4_FFN on rows wider than 16
+ * entries, which run level by level) hand tiles of gates to resident workgroups, which wait for the
  * tiles their gates read from. Should such a wait exceed cfg->spin_limit polls (it cannot, unless
  * the device is taken away from the kernel), the sweep stops, Hout is left incomplete, and the
  * call has long returned DG4_OK: dg4_layer_status tells.

@@ -314,13 +314,11 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
     // Which path: the kernel specialised for bf16 / hidden 256 / one layer / cones of two hops (weights
     // resident in registers), the persistent dataflow kernel for the other shapes and any number of
     // layers, or level-by-level launches (DG4_PER_LEVEL, DG4_BOUNDED_KV, the feed-forward sub-block
-    // on neighbour rows wider than 16 entries, and K|V stores of 4 GB or more per layer: the dataflow
-    // kernel reads a layer's store through a structured buffer, whose offsets are 32 bits wide).
+    // on neighbour rows wider than 16 entries).
     const bool whole_range = level_begin == 0 && level_end == (int32_t)g->max_level + 1;
     const bool forced_levels = (cfg->flags & (DG4_PER_LEVEL | DG4_BOUNDED_KV)) != 0;
     const bool resident = dt == DG4_BF16 && d == 256 && L == 1 && cfg->hops <= 2 && !forced_levels && (!ffn || whole_range);
-    const bool kv_fits = (uint64_t)pl.kv_rows * 2u * (uint64_t)d * (uint64_t)es <= 0xFFFFFFFFull;
-    const bool flow = !resident && !forced_levels && kv_fits && dg4_flow_supports(dt, d, g->ell_w) && (!ffn || g->ell_w <= 16);
+    const bool flow = !resident && !forced_levels && dg4_flow_supports(dt, d, g->ell_w) && (!ffn || g->ell_w <= 16);
     // a caller that has not changed the weights since its last call with this configuration, graph
     // and workspace vouches for the packed copies that call left behind
     const bool pack = !(cfg->flags & DG4_WEIGHTS_PACKED);

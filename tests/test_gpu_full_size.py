@@ -202,3 +202,30 @@ def test_full_size_partitioned_k8():
     err = row_rel_err(Hn[nodes], ref)
     print(f"  sampled {len(nodes)} gates: max rel err {err.max():.3e}", flush=True)
     assert err.max() <= TOL[c.dtype]
+
+
+def test_kv_store_past_4_gb():
+    """The dataflow kernel reads a layer's K|V store through a structured buffer (row index x 1 KB): 4.3 M gates
+    put the last rows past the 4 GB mark. Against level-by-level launches (plain 64-bit pointers), on the device."""
+    c = synth.Config(**{**synth.CONFIGS["stress"].__dict__, "n_and": 4_300_000, "hops": 1, "n_layers": 2})
+    print("K|V store past 4 GB: generating", flush=True)
+    w = synth.make(c)
+    g = dg4.dg4_build_levels(c.n_nodes, w.edge_src, w.edge_dst, w.edge_inv, 1, w.level_hint)
+    assert g.n * 1024 > 2 ** 32
+    X, W = to_dev(w.x, c.dtype), device_weights(w, c.dtype)
+    outs = []
+    for per_level in (False, True):
+        cfg = cfg_of(c, per_level=per_level)
+        H = torch.full((c.n_nodes, c.hidden), float("nan"), dtype=tdtype(c.dtype), device="cuda")
+        ws = torch.empty(dg4.dg4_layer_workspace_bytes(cfg, g), dtype=torch.uint8, device="cuda")
+        ws.fill_(0xFF)
+        dg4.dg4_layer_fwd(cfg, g, X, W, H, workspace=ws)
+        torch.cuda.synchronize()
+        dg4.dg4_layer_status(cfg, g, ws)
+        outs.append(H.float())
+        del ws
+        print("  done", "level by level" if per_level else "persistent", flush=True)
+    assert not torch.isnan(outs[0]).any()
+    err = (outs[0] - outs[1]).norm(dim=1) / outs[1].norm(dim=1).clamp_min(1e-30)
+    print(f"  max rel err {float(err.max()):.3e}", flush=True)
+    assert float(err.max()) <= 2 * TOL[c.dtype]
