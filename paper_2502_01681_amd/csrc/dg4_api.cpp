@@ -489,19 +489,20 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             const bool narrow = g->n / std::max<int64_t>(depth, 1) < 4096;
             a.tiles = g->d_pair_tiles; a.pairs = narrow ? 0 : 1; a.tile_begin = 0;
             a.n_tiles = narrow ? g->n_pair_tiles : g->n_pair_tiles / 2;
+            a.tile_cap = narrow ? 16 : 32;
             a.ell = g->d_pair_ell;
         } else if (wide) {
-            a.tiles = g->d_tilesw; a.pairs = 0; a.tile_rows = g->wide_tile_rows;
+            a.tiles = g->d_tilesw; a.pairs = 0; a.tile_rows = g->wide_tile_rows; a.tile_cap = 16;
             a.tile_begin = g->level_tilew_ptr[level_begin];
             a.n_tiles = g->level_tilew_ptr[level_end] - a.tile_begin;
             a.ell = g->d_ell_pos;
         } else {
-            a.tiles = g->d_tiles32; a.pairs = 0; a.tile_begin = g->level_tile32_ptr[level_begin];
+            a.tiles = g->d_tiles32; a.pairs = 0; a.tile_begin = g->level_tile32_ptr[level_begin]; a.tile_cap = 32;
             a.n_tiles = g->level_tile32_ptr[level_end] - a.tile_begin;
             a.ell = g->d_ell_pos;
         }
         a.ell_w = g->ell_w;
-        a.pre_rows = P0; a.n_pre = (P0 + 31) / 32;
+        a.pre_rows = P0; a.n_pre = (P0 + a.tile_cap - 1) / a.tile_cap;
         a.order = order_in_use;
         a.x = X; a.qkv_self = at(pl.qkv_self);
         a.kv = at(pl.kv); a.kv_layer_stride = (int64_t)pl.kv_rows * 2 * d;

@@ -153,7 +153,7 @@ __device__ __forceinline__ float sum_lane_rows(float x)
     return __uint_as_float(b[0]) + __uint_as_float(b[1]);
 }
 
-template <typename T, int AW, bool TIMERS>
+template <typename T, int AW, bool TIMERS, bool TWO>
 __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
 {
     constexpr int D = 512 / (int)sizeof(T);       // 128 (fp32) or 256 (bf16): a row is 512 bytes
@@ -194,7 +194,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                              (uint32_t)(2 * ROW_BUF + 2 * 8 * FT * sizeof(float) + 64 + ENT_BYTES);
     // Rows of 16 entries: the attention keeps 128 registers of row halves in flight, so nothing else may
     // stay in registers across it: the weight ring is then filled after the attention, not before it.
-    constexpr bool OVER = AW == 8;
+    constexpr bool OVER = AW == 8 && TWO;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -215,7 +215,10 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
 
     // The ring: the next eight fragments of the packed weight stream this wave multiplies, refilled
     // eight fragments ahead as they are used up, across the end of a group into the group that follows.
-    constexpr int RD = FLOW_RING_DEPTH < RING ? FLOW_RING_DEPTH : RING;      // fragments in flight per wave
+    // (TWO = false: every tile of the launch is a single block of at most 16 gates, as on narrow circuits and for
+    // rows of any width; the registers of the second block's operands then go to a ring twice as deep)
+    constexpr int RD_WANT = TWO ? FLOW_RING_DEPTH : 2 * FLOW_RING_DEPTH;
+    constexpr int RD = RD_WANT < RING ? RD_WANT : RING;                      // fragments in flight per wave
     uint4 ring[RD];
     const uint4* ring_src;                        // the group whose first fragments the ring holds
     auto group_ptr = [&](const void* packed, int group) __attribute__((always_inline)) {
@@ -310,14 +313,15 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
     };
 
     // Tickets, by thread 0. Tickets below n_pre stand for the gates finished before this call (a
-    // resumed sweep), 32 positions each: nothing is computed for them but K | V of every layer, from
+    // resumed sweep), 32 positions each (16 in launches whose tiles hold one block): nothing is computed for them but K | V of every layer, from
     // the caller's embeddings, with the arithmetic of a gate computed here. The ticket of the next
     // tile is drawn at the top of a tile and its descriptor lands in LDS in the middle of it.
     const int64_t total = p.n_pre + p.n_tiles;
     auto describe = [&](int64_t t, int slot) __attribute__((always_inline)) {      // kind: 0 no tile left, 1 tile, 2 finished gates, 3 empty
         int kind = 0, p0 = 0, rows = 0;
         if (t < p.n_pre) {
-            kind = 2; p0 = (int)(t * FT); rows = (int)(p.pre_rows - p0 < FT ? p.pre_rows - p0 : FT);
+            constexpr int PRE = TWO ? FT : 16;      // positions per ticket: what a tile of this launch can hold
+            kind = 2; p0 = (int)(t * PRE); rows = (int)(p.pre_rows - p0 < PRE ? p.pre_rows - p0 : PRE);
         } else if (t < total) {
             if (p.pairs) {
                 const uint2 ta = p.tiles[p.tile_begin + 2 * (t - p.n_pre)], tb = p.tiles[p.tile_begin + 2 * (t - p.n_pre) + 1];
@@ -351,7 +355,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             have_next = false;
             if (kind == 3) continue;              // an empty tile of the table
         }
-        const bool two = rows > 16;               // a second block of 16 gates
+        const bool two = TWO && rows > 16;        // a second block of 16 gates
         const int live = two ? FT : 16;           // rows that are computed (past `rows`: the last gate again, never stored)
         auto pos_of = [&](int r) { return p0 + (r < rows ? r : rows - 1); };
         lap(0);
@@ -762,10 +766,16 @@ int launch_flow_t(const dg4_flow_args& a, hipStream_t s)
                         (a.ffn ? (size_t)FT * (4 * D + E) * sizeof(T) : 0);
     if (a.ffn && (wide || !a.w1_packed || !a.w2_packed)) return hipErrorInvalidValue;
     void (*kern)(dg4_flow_args) = nullptr;
-    if (a.ell_w == 8) kern = a.prof ? flow_kernel<T, 8, true> : flow_kernel<T, 8, false>;
-    else if (a.ell_w == 16) kern = a.prof ? flow_kernel<T, 16, true> : flow_kernel<T, 16, false>;
+    // tiles of 32 gates: whole sweeps that take the pair table two tiles at a time, and sweeps over a range of levels
+    if (a.tile_cap != 16 && a.tile_cap != 32) return hipErrorInvalidValue;
+    const bool two = a.tile_cap == 32;
+    if (wide && two) return hipErrorInvalidValue;
+    if (a.ell_w == 8) kern = two ? (a.prof ? flow_kernel<T, 8, true, true> : flow_kernel<T, 8, false, true>)
+                                 : (a.prof ? flow_kernel<T, 8, true, false> : flow_kernel<T, 8, false, false>);
+    else if (a.ell_w == 16) kern = two ? (a.prof ? flow_kernel<T, 16, true, true> : flow_kernel<T, 16, false, true>)
+                                       : (a.prof ? flow_kernel<T, 16, true, false> : flow_kernel<T, 16, false, false>);
     else if (wide && a.ell_w % 4 == 0 && !a.pairs && (a.tile_rows == 2 || a.tile_rows == 4 || a.tile_rows == 8 || a.tile_rows == 16))
-        kern = a.prof ? flow_kernel<T, 0, true> : flow_kernel<T, 0, false>;
+        kern = a.prof ? flow_kernel<T, 0, true, false> : flow_kernel<T, 0, false, false>;
     if (!kern) return hipErrorInvalidValue;
     hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem);
     if (e != hipSuccess) return e;
@@ -803,6 +813,6 @@ int dg4_launch_pack_wa(int dtype, int hidden, const void* w, int ld, int col0, i
 int dg4_launch_flow(int dtype, int hidden, const dg4_flow_args& a, hipStream_t s)
 {
     if (a.n_tiles <= 0) return hipSuccess;
-    if (!dg4_flow_supports(dtype, hidden, a.ell_w) || a.n_layers < 1 || a.n_pre * FT < a.pre_rows) return hipErrorInvalidValue;
+    if (!dg4_flow_supports(dtype, hidden, a.ell_w) || a.n_layers < 1 || a.n_pre * a.tile_cap < a.pre_rows) return hipErrorInvalidValue;
     return dtype == DG4_F32 ? launch_flow_t<float>(a, s) : launch_flow_t<bf16_t>(a, s);
 }

@@ -209,6 +209,7 @@ struct dg4_flow_args {
     int64_t n_pre; int64_t pre_rows;       // resumed sweeps: positions [0, pre_rows) are finished gates whose K | V come from h_out first, in n_pre = ceil(pre_rows / 32) extra tiles
     const uint32_t* ell; int ell_w;        // neighbour rows by position
     int tile_rows;                         // rows wider than 16 entries: most gates of a tile (2, 4, 8 or 16; no pairs)
+    int tile_cap;                          // most gates of any tile of this launch: 16 (one block) or 32
     const int32_t* order;                  // position -> node id
     const void* x;                         // [n, d] by node id
     const void* qkv_self;                  // [n, 3d] by position: Q | K | V of x (layer 0)
