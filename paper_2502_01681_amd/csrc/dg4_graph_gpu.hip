@@ -1,11 +1,10 @@
 // Graph analysis of paper Section 3.2 on the device, behind dg4_build_levels_device: validation,
 // fanin table, logic levels (Eq. 1) by rounds over the fanin table, the (level, id) order by a
-// stable radix sort, cone_k rows with relation codes by a per-gate backward search, and the fanout
+// stable radix sort (this file's own, like its prefix sum), cone_k rows with relation codes by a per-gate backward search, and the fanout
 // counts of Eq. 2. Integer work throughout: every table equals the host builder's bit for bit
 // (nothing here depends on the order in which atomics land: the fanin slot a source takes is not
 // observable in any output).
 #include <hip/hip_runtime.h>
-#include <hipcub/hipcub.hpp>
 #include <stdint.h>
 
 #include <algorithm>
@@ -329,6 +328,169 @@ __global__ void part_compact_kernel(int64_t n, const int64_t* nbr_ptr, const int
     if (!FILL && lane == 0) cnt[v] = out;
 }
 
+// ---- two primitives of this file's own: an exclusive prefix sum of 64-bit counts, and a stable
+// sort of (32-bit key, 32-bit value) pairs by the key's low bits, least significant digit first.
+// Both are deterministic: no result depends on the order in which workgroups run.
+constexpr int SCAN_ITEMS = 8, SCAN_CHUNK = 256 * SCAN_ITEMS;      // consecutive items per thread, per workgroup
+constexpr int RADIX_BITS = 8, RADIX = 1 << RADIX_BITS;
+constexpr int SORT_ROUNDS = 16, SORT_CHUNK = 256 * SORT_ROUNDS;   // items per workgroup, 256 at a time
+
+// exclusive prefix of v over the 256 threads of a workgroup (in thread order) and the workgroup's total
+__device__ __forceinline__ int64_t block_exclusive(int64_t v, int64_t* total)
+{
+    __shared__ int64_t wave_sum[4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int64_t incl = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int64_t up = __shfl_up(incl, d);
+        if (lane >= d) incl += up;
+    }
+    __syncthreads();                              // (the array may still be read from an earlier call)
+    if (lane == 63) wave_sum[wave] = incl;
+    __syncthreads();
+    int64_t before = 0, all = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) { if (w < wave) before += wave_sum[w]; all += wave_sum[w]; }
+    *total = all;
+    return before + incl - v;
+}
+
+__global__ __launch_bounds__(256) void scan_sums_kernel(const int64_t* in, int64_t n, int64_t* sums)
+{
+    const int64_t i0 = (int64_t)blockIdx.x * SCAN_CHUNK + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int64_t v = 0;
+    for (int k = 0; k < SCAN_ITEMS; ++k) if (i0 + k < n) v += in[i0 + k];
+    int64_t total;
+    (void)block_exclusive(v, &total);
+    if (threadIdx.x == 0) sums[blockIdx.x] = total;
+}
+
+// the chunk sums become chunk offsets, in place: one workgroup walks them 256 at a time
+__global__ __launch_bounds__(256) void scan_top_kernel(int64_t* sums, int64_t chunks)
+{
+    int64_t carry = 0;
+    for (int64_t c0 = 0; c0 < chunks; c0 += 256) {
+        const int64_t c = c0 + threadIdx.x;
+        const int64_t v = c < chunks ? sums[c] : 0;
+        int64_t total;
+        const int64_t ex = block_exclusive(v, &total);
+        if (c < chunks) sums[c] = carry + ex;
+        carry += total;
+    }
+}
+
+__global__ __launch_bounds__(256) void scan_apply_kernel(const int64_t* in, int64_t n, const int64_t* sums, int64_t* out)
+{
+    const int64_t i0 = (int64_t)blockIdx.x * SCAN_CHUNK + (int64_t)threadIdx.x * SCAN_ITEMS;
+    int64_t item[SCAN_ITEMS];
+    int64_t v = 0;
+    for (int k = 0; k < SCAN_ITEMS; ++k) { item[k] = i0 + k < n ? in[i0 + k] : 0; v += item[k]; }
+    int64_t total;
+    int64_t run = sums[blockIdx.x] + block_exclusive(v, &total);
+    for (int k = 0; k < SCAN_ITEMS; ++k) {
+        if (i0 + k < n) out[i0 + k] = run;
+        run += item[k];
+    }
+}
+
+inline size_t scan_chunks(int64_t n) { return (size_t)((n + SCAN_CHUNK - 1) / SCAN_CHUNK); }
+// out[i] = in[0] + ... + in[i-1]; sums: scan_chunks(n) words of scratch; in and out may be the same array
+inline void exclusive_sum(const int64_t* in, int64_t* out, int64_t n, int64_t* sums, hipStream_t s)
+{
+    if (n <= 0) return;
+    const unsigned chunks = (unsigned)scan_chunks(n);
+    hipLaunchKernelGGL(scan_sums_kernel, dim3(chunks), dim3(256), 0, s, in, n, sums);
+    hipLaunchKernelGGL(scan_top_kernel, dim3(1), dim3(256), 0, s, sums, (int64_t)chunks);
+    hipLaunchKernelGGL(scan_apply_kernel, dim3(chunks), dim3(256), 0, s, in, n, (const int64_t*)sums, out);
+}
+
+// One digit of the sort. Workgroup b owns items b * SORT_CHUNK ..; hist[digit * chunks + b] counts its
+// items per digit, so that the exclusive sum over the whole table is, for every (digit, workgroup), where
+// that workgroup's first item with that digit goes: all smaller digits first, then the same digit in
+// earlier workgroups.
+__global__ __launch_bounds__(256) void sort_count_kernel(const uint32_t* keys, int64_t n, int shift, int64_t chunks, int64_t* hist)
+{
+    __shared__ unsigned cnt[RADIX];
+    cnt[threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t i0 = (int64_t)blockIdx.x * SORT_CHUNK;
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const int64_t i = i0 + r * 256 + threadIdx.x;
+        if (i < n) atomicAdd(&cnt[(keys[i] >> shift) & (RADIX - 1)], 1u);
+    }
+    __syncthreads();
+    hist[(int64_t)threadIdx.x * chunks + blockIdx.x] = cnt[threadIdx.x];
+}
+
+// Items leave in their order within the workgroup: 256 at a time, an item's place among the equal
+// digits of its round is the number of such items in lower waves plus those in lower lanes of its own.
+__global__ __launch_bounds__(256) void sort_move_kernel(const uint32_t* keys, const int32_t* vals, int64_t n, int shift, int64_t chunks,
+                                                        const int64_t* offs, uint32_t* keys_out, int32_t* vals_out)
+{
+    __shared__ int64_t next[RADIX];               // where the workgroup's next item of a digit goes
+    __shared__ unsigned in_wave[4][RADIX];        // this round's items per wave and digit
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    next[threadIdx.x] = offs[(int64_t)threadIdx.x * chunks + blockIdx.x];
+#pragma unroll
+    for (int w = 0; w < 4; ++w) in_wave[w][threadIdx.x] = 0;
+    __syncthreads();
+    const int64_t i0 = (int64_t)blockIdx.x * SORT_CHUNK;
+    for (int r = 0; r < SORT_ROUNDS; ++r) {
+        const int64_t i = i0 + r * 256 + threadIdx.x;
+        const bool valid = i < n;
+        const uint32_t key = valid ? keys[i] : 0u;
+        const int32_t val = valid ? vals[i] : 0;
+        const uint32_t d = (key >> shift) & (RADIX - 1);
+        unsigned long long peers = __ballot(valid);           // the lanes of this wave with the same digit
+#pragma unroll
+        for (int b = 0; b < RADIX_BITS; ++b) {
+            const bool set = ((d >> b) & 1u) != 0;
+            const unsigned long long m = __ballot(set);
+            peers &= set ? m : ~m;
+        }
+        const unsigned long long lower = peers & ((1ull << lane) - 1ull);
+        if (valid && lower == 0) in_wave[wave][d] = (unsigned)__popcll(peers);
+        __syncthreads();
+        if (valid) {
+            int64_t pos = next[d] + __popcll(lower);
+            for (int w = 0; w < wave; ++w) pos += in_wave[w][d];
+            keys_out[pos] = key; vals_out[pos] = val;
+        }
+        __syncthreads();
+        unsigned moved = 0;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) { moved += in_wave[w][threadIdx.x]; in_wave[w][threadIdx.x] = 0; }
+        next[threadIdx.x] += moved;
+        __syncthreads();
+    }
+}
+
+inline size_t sort_chunks(int64_t n) { return (size_t)((n + SORT_CHUNK - 1) / SORT_CHUNK); }
+inline size_t sort_hist_words(int64_t n) { return sort_chunks(n) * RADIX; }
+// (keys_out, vals_out) = (keys, vals) in ascending order of the keys' low `bits` bits, equal keys in their
+// input order; the inputs are left as they are. tmp_keys / tmp_vals: n words each (used for more than one
+// digit); hist: sort_hist_words(n) words; sums: scan_chunks(sort_hist_words(n)) words.
+inline void sort_pairs(const uint32_t* keys, const int32_t* vals, uint32_t* keys_out, int32_t* vals_out, int64_t n, int bits,
+                       uint32_t* tmp_keys, int32_t* tmp_vals, int64_t* hist, int64_t* sums, hipStream_t s)
+{
+    if (n <= 0) return;
+    const int passes = (bits + RADIX_BITS - 1) / RADIX_BITS;
+    const int64_t chunks = (int64_t)sort_chunks(n);
+    const uint32_t* src_k = keys;
+    const int32_t* src_v = vals;
+    for (int k = 0; k < passes; ++k) {
+        const bool to_out = ((passes - 1 - k) & 1) == 0;      // the last digit lands in the output arrays
+        uint32_t* dst_k = to_out ? keys_out : tmp_keys;
+        int32_t* dst_v = to_out ? vals_out : tmp_vals;
+        hipLaunchKernelGGL(sort_count_kernel, dim3((unsigned)chunks), dim3(256), 0, s, src_k, n, k * RADIX_BITS, chunks, hist);
+        exclusive_sum(hist, hist, chunks * RADIX, sums, s);
+        hipLaunchKernelGGL(sort_move_kernel, dim3((unsigned)chunks), dim3(256), 0, s, src_k, src_v, n, k * RADIX_BITS, chunks,
+                           (const int64_t*)hist, dst_k, dst_v);
+        src_k = dst_k; src_v = dst_v;
+    }
+}
+
 // Device memory of one call: carved out of at most two allocations (the tables sized by the node
 // count, then those sized by the number of neighbour entries), released when the call returns.
 struct Arena {
@@ -433,10 +595,11 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
         g->max_level = h_max;
         int bits = 1;
         while (bits < 31 && (h_max >> bits) != 0) ++bits;
-        size_t sort_bytes = 0;
-        GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(nullptr, sort_bytes, level, sorted_level, ids, order, (int)n, 0, bits, s));
-        GPU_ALLOC(sort_tmp, unsigned char, sort_bytes, false);
-        GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(sort_tmp, sort_bytes, level, sorted_level, ids, order, (int)n, 0, bits, s));
+        GPU_ALLOC(sort_keys, uint32_t, (size_t)n, false);
+        GPU_ALLOC(sort_vals, int32_t, (size_t)n, false);
+        GPU_ALLOC(sort_hist, int64_t, sort_hist_words(n), false);
+        GPU_ALLOC(scan_sums, int64_t, scan_chunks(std::max<int64_t>(n + 1, (int64_t)sort_hist_words(n))), false);
+        sort_pairs((const uint32_t*)level, ids, (uint32_t*)sorted_level, order, n, bits, sort_keys, sort_vals, sort_hist, scan_sums, s);
         const int32_t n_ptr = h_max + 2;
         GPU_ALLOC(level_ptr, int64_t, (size_t)n_ptr, false);
         hipLaunchKernelGGL(level_ptr_kernel, dim3(blocks_for(n_ptr)), dim3(256), 0, s, n, sorted_level, n_ptr, level_ptr);
@@ -444,9 +607,6 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
         // cones
         GPU_ALLOC(cnt, int64_t, (size_t)n + 1, true);
         GPU_ALLOC(nbr_ptr, int64_t, (size_t)n + 1, false);
-        size_t scan_bytes = 0;
-        GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(nullptr, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
-        GPU_ALLOC(scan_tmp, unsigned char, scan_bytes, false);
         int64_t nnz = 0;
         int32_t* nbr_idx = nullptr;
         uint8_t* nbr_rel = nullptr;
@@ -454,7 +614,7 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
             GPU_ALLOC(row_id, int32_t, (size_t)n * MAXW, false);
             GPU_ALLOC(row_rel, uint8_t, (size_t)n * MAXW, false);
             hipLaunchKernelGGL(cone_kernel, dim3(nb), dim3(256), 0, s, n, (int)hops, fin, finv, deg, row_id, row_rel, cnt);
-            GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, nbr_ptr, (int)(n + 1), s));
+            exclusive_sum(cnt, nbr_ptr, n + 1, scan_sums, s);
             GPU_CHECK(hipMemcpyAsync(&nnz, nbr_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
             GPU_CHECK(hipStreamSynchronize(s));
             if (!arena.reserve((size_t)nnz * 5 + 1024)) return DG4_ENOMEM;
@@ -472,7 +632,7 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
             for (int32_t j = 1; j <= hops; ++j) {
                 hipLaunchKernelGGL(cone_merge_kernel<false>, dim3(nb), dim3(256), 0, s, n, fin, finv, deg,
                                    (const int64_t*)ptr_prev, (const int32_t*)idx_prev, cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (uint8_t*)nullptr);
-                GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, ptr_cur, (int)(n + 1), s));
+                exclusive_sum(cnt, ptr_cur, n + 1, scan_sums, s);
                 GPU_CHECK(hipMemcpyAsync(&nnz, ptr_cur + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
                 GPU_CHECK(hipStreamSynchronize(s));
                 const bool final_hop = j == hops;
@@ -508,10 +668,7 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
             hipLaunchKernelGGL(part_key_kernel, dim3(nb), dim3(256), 0, s, n, order, level, kind, covered, none_key, pkey, n_roots_d);
             int key_bits = 1;
             while (key_bits < 32 && (none_key >> key_bits) != 0) ++key_bits;
-            size_t psort_bytes = 0;
-            GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(nullptr, psort_bytes, pkey, pkey_sorted, order, roots_sorted, (int)n, 0, key_bits, s));
-            GPU_ALLOC(psort_tmp, unsigned char, psort_bytes, false);
-            GPU_CHECK(hipcub::DeviceRadixSort::SortPairs(psort_tmp, psort_bytes, pkey, pkey_sorted, order, roots_sorted, (int)n, 0, key_bits, s));
+            sort_pairs(pkey, order, pkey_sorted, roots_sorted, n, key_bits, sort_keys, sort_vals, sort_hist, scan_sums, s);
             unsigned long long n_roots = 0;
             GPU_CHECK(hipMemcpyAsync(&n_roots, n_roots_d, sizeof(n_roots), hipMemcpyDeviceToHost, s));
             GPU_CHECK(hipStreamSynchronize(s));
@@ -551,7 +708,7 @@ int build_device(int64_t n, int64_t e, const int32_t* es, const int32_t* ed, con
             GPU_ALLOC(part_ptr, int64_t, (size_t)n + 1, false);
             hipLaunchKernelGGL(part_compact_kernel<false>, dim3(nb_wave), dim3(256), 0, s, n, nbr_ptr, nbr_idx, nbr_rel, keep,
                                cnt, (const int64_t*)nullptr, (int32_t*)nullptr, (uint8_t*)nullptr);
-            GPU_CHECK(hipcub::DeviceScan::ExclusiveSum(scan_tmp, scan_bytes, cnt, part_ptr, (int)(n + 1), s));
+            exclusive_sum(cnt, part_ptr, n + 1, scan_sums, s);
             int64_t nnz2 = 0;
             GPU_CHECK(hipMemcpyAsync(&nnz2, part_ptr + n, sizeof(int64_t), hipMemcpyDeviceToHost, s));
             GPU_CHECK(hipStreamSynchronize(s));        // (the stream's copy of cone_stage has been consumed too)

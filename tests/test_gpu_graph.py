@@ -67,6 +67,22 @@ def test_shuffled_edges_relabelled_nodes_and_not_nodes():
     assert np.array_equal(g.array("out_and"), oa) and np.array_equal(g.array("out_not"), on)
 
 
+def test_order_of_a_graph_with_more_than_65536_levels():
+    # three digits of the library's radix sort: a chain of 70,000 buffers among 30,000 loose inputs, ids
+    # shuffled, levels given as a hint (Eq. 1 by rounds would take 70,000 of them)
+    chain, loose = 70_000, 30_000
+    n = chain + 1 + loose
+    rng = np.random.default_rng(11)
+    perm = rng.permutation(n).astype(np.int32)
+    src, dst = perm[np.arange(chain)], perm[np.arange(1, chain + 1)]
+    inv = (np.arange(chain) % 2).astype(np.uint8)
+    hint = np.zeros(n, dtype=np.int32)
+    hint[perm[np.arange(chain + 1)]] = np.arange(chain + 1)
+    g = build_on_gpu(n, src, dst, inv, 2, hint)
+    same_as_oracle(g, oracle.build_levels(n, src, dst, inv, 2, hint))
+    assert g.n_levels == chain + 1
+
+
 def test_deep_chain_and_hand_graph():
     # a chain of 3000 buffers: 3001 levels, one gate each (many rounds of Eq. 1)
     n = 3001
