@@ -6,6 +6,7 @@
 #include <cstring>
 #include <new>
 #include <queue>
+#include <system_error>
 #include <thread>
 
 #include "dg4_internal.h"
@@ -779,8 +780,17 @@ int dg4_graph_ensure_device(dg4_graph* g)
         // that gates whose sources are old share tiles and only the last tiles of a level wait on
         // the levels just before. (The published `order` table keeps (level, id); results do not
         // depend on this.)
+        // (three independent derivations, on three threads: the level-sorted tables, the table by node id,
+        // the dependency-driven schedule with its table)
         std::vector<int32_t> sweep(rows, 0);
-        {
+        std::vector<uint32_t> by_id, by_pos, by_flow;
+        std::vector<int32_t> flow;
+        std::vector<uint2> flow_tiles;
+        int rc_job[3] = {DG4_OK, DG4_OK, DG4_OK};
+        auto guarded = [&](int slot, auto&& body) {
+            try { body(); } catch (const std::bad_alloc&) { rc_job[slot] = DG4_ENOMEM; }
+        };
+        auto job_levels = [&]() { guarded(0, [&]() {
             std::vector<int32_t> min_reader((size_t)g->n, INT32_MAX);
             for (int64_t v = 0; v < g->n; ++v)
                 for (int64_t j = g->nbr_ptr[v]; j < g->nbr_ptr[v + 1]; ++j) {
@@ -803,21 +813,26 @@ int dg4_graph_ensure_device(dg4_graph* g)
                                  [&](int32_t a, int32_t b) { return key[a] < key[b]; });
                 for (int64_t q = lo; q < hi; ++q) g->pos[sweep[q]] = (int32_t)q;   // sources of higher levels see these
             }
-        }
-        g->sweep_order.assign(sweep.begin(), sweep.begin() + g->n);
-        std::vector<uint32_t> by_id(rows * w, DG4_ELL_PAD), by_pos(rows * w, DG4_ELL_PAD);
-        for (int64_t v = 0; v < g->n; ++v) {
-            const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
-            uint32_t* rid = &by_id[(size_t)v * w];
-            uint32_t* rpos = &by_pos[(size_t)g->pos[v] * w];
-            for (int64_t j = 0; j < cnt; ++j) {
-                const uint32_t rel = g->nbr_rel[lo + j];
-                rid[j] = (rel << 30) | (uint32_t)g->nbr_idx[lo + j];
-                rpos[j] = (rel << 30) | (uint32_t)g->pos[g->nbr_idx[lo + j]];
+            g->sweep_order.assign(sweep.begin(), sweep.begin() + g->n);
+            by_pos.assign(rows * w, DG4_ELL_PAD);
+            for (int64_t v = 0; v < g->n; ++v) {
+                const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
+                uint32_t* rpos = &by_pos[(size_t)g->pos[v] * w];
+                for (int64_t j = 0; j < cnt; ++j)
+                    rpos[j] = ((uint32_t)g->nbr_rel[lo + j] << 30) | (uint32_t)g->pos[g->nbr_idx[lo + j]];
             }
-            // entries stay in ascending-id order in both tables, so the summation
-            // order of a gate's sources does not depend on the schedule
-        }
+        }); };
+        // entries stay in ascending-id order in every table, so the summation order of a gate's sources
+        // does not depend on the schedule
+        auto job_id = [&]() { guarded(1, [&]() {
+            by_id.assign(rows * w, DG4_ELL_PAD);
+            for (int64_t v = 0; v < g->n; ++v) {
+                const int64_t lo = g->nbr_ptr[v], cnt = g->nbr_ptr[v + 1] - lo;
+                uint32_t* rid = &by_id[(size_t)v * w];
+                for (int64_t j = 0; j < cnt; ++j)
+                    rid[j] = ((uint32_t)g->nbr_rel[lo + j] << 30) | (uint32_t)g->nbr_idx[lo + j];
+            }
+        }); };
         std::vector<uint2> tiles;
         g->level_tile_ptr.assign((size_t)g->max_level + 2, 0);
         for (int32_t l = 0; l <= g->max_level; ++l) {
@@ -835,12 +850,10 @@ int dg4_graph_ensure_device(dg4_graph* g)
         }
         g->level_tile32_ptr[(size_t)g->max_level + 1] = (int64_t)tiles32.size();
         // Dataflow order for whole-graph sweeps (dg4_flow_schedule)
-        std::vector<int32_t> flow;
-        std::vector<uint2> flow_tiles;
-        std::vector<uint32_t> by_flow;
-        if (with_flow) {
+        auto job_flow = [&]() { guarded(2, [&]() {
+            if (!with_flow) return;
             const int rc = dg4_flow_schedule(g);
-            if (rc != DG4_OK) return rc;
+            if (rc != DG4_OK) { rc_job[2] = rc; return; }
             flow.assign(rows, 0);
             std::copy(g->flow_order.begin(), g->flow_order.end(), flow.begin());
             flow_tiles.resize(g->flow_tile_ptr.size() - 1);
@@ -856,7 +869,21 @@ int dg4_graph_ensure_device(dg4_graph* g)
                     r[j] = ((uint32_t)g->nbr_rel[lo + j] << 30) | (uint32_t)fpos[g->nbr_idx[lo + j]];
             }
             g->n_flow_tiles = (int64_t)flow_tiles.size();
+        }); };
+        {
+            std::vector<std::thread> helpers;
+            try {
+                helpers.emplace_back(job_id);
+                helpers.emplace_back(job_flow);
+            } catch (const std::system_error&) {}      // no thread to be had: the jobs run here
+            job_levels();
+            const size_t started = helpers.size();
+            for (std::thread& t : helpers) t.join();
+            if (started < 1) job_id();
+            if (started < 2) job_flow();
         }
+        for (int rc : rc_job)
+            if (rc != DG4_OK) return rc;
         const size_t bytes = rows * w * sizeof(uint32_t);
         auto fail = [&](int rc) {
             if (g->d_flow_ell) (void)hipFree(g->d_flow_ell);

@@ -76,7 +76,7 @@ def test_flow_kernel_without_epilogue():
     assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= 2 * TOL["f32"]
 
 
-@pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {})])
+@pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {}), ("medium", 12_000, dict(n_layers=2))])
 def test_flow_kernel_schedules_and_resume(name, n_and, over):
     # dependency-driven tiles, the graph's own levels, Eq. 1 levels or a caller's deeper levelling,
     # a sweep cut in two: never a different bit
