@@ -96,7 +96,7 @@ def main():
                     help="the timed sweep follows the graph's own (assigned) levels (DG4_LEVEL_ORDER) and is priced on them")
     ap.add_argument("--per-level", action="store_true", help="force level-by-level launches (DG4_PER_LEVEL)")
     ap.add_argument("--bounded-kv", action="store_true", help="no K|V store (DG4_BOUNDED_KV)")
-    ap.add_argument("--cpu-gates", type=int, default=400_000, help="gates in the oracle's timed sample")
+    ap.add_argument("--cpu-gates", type=int, default=800_000, help="gates in the oracle's timed sample")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="only run a plain 1 GiB device copy (reference point for rocprofv3 byte counters)")
     args = ap.parse_args()
