@@ -490,6 +490,9 @@ extern "C" int dg4_layer_fwd(const dg4_layer_cfg* cfg, dg4_graph* g, const void*
             a.tiles = g->d_pair_tiles; a.pairs = narrow ? 0 : 1; a.tile_begin = 0;
             a.n_tiles = narrow ? g->n_pair_tiles : g->n_pair_tiles / 2;
             a.tile_cap = narrow ? 16 : 32;
+            // (there the chain from level to level is what counts: with several layers a reader starts on K | V
+            // of the first layer while its sources still project the later ones)
+            a.layer_flags = narrow && L > 1 ? 1 : 0;
             a.ell = g->d_pair_ell;
         } else if (wide) {
             a.tiles = g->d_tilesw; a.pairs = 0; a.tile_rows = g->wide_tile_rows; a.tile_cap = 16;

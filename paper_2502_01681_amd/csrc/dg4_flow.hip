@@ -30,9 +30,11 @@
 //
 // Visibility between compute units: a K | V row is written exactly once per sweep, with agent-scope
 // (write-through) stores, and its flag is raised, again at agent scope, only after the writing
-// threads have waited for those stores to complete (s_waitcnt vmcnt(0), then a workgroup barrier).
+// threads have waited for those stores to complete (s_waitcnt, then a workgroup barrier). The flag
+// of a gate counts the layers whose rows are in the store: it goes up once, to the number of layers,
+// or (deep, narrow circuits) layer by layer while the later layers are still being projected.
 // A reader polls the flag with agent-scope loads, which are served past its own L1 and L2, and
-// reads the row only after it has seen the flag. No row is ever read before it is written, not
+// reads a row only after it has seen the flag cover that row's layer. No row is ever read before it is written, not
 // even speculatively, so no cache on the reader's side can hold an older copy of its lines.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -404,6 +406,28 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             }
             return false;
         };
+        // A flag counts the layers whose K | V of its gate are in the store (all of them at once, or one
+        // by one: see the end of the tile). The lanes of a wave wait until every source they watch shows
+        // at least `need`; the result is the smallest count seen, at most the number of layers: what the
+        // wave need not ask about again.
+        auto await = [&](uint32_t e, int need) __attribute__((always_inline)) -> int {
+            const bool watch = e != DG4_ELL_PAD && (e >> 30) != 0;
+            const uint32_t* f = p.flags + (watch ? (e & 0x3FFFFFFFu) : 0u);
+            uint32_t spins = 0, seen;
+            for (;;) {
+                seen = watch ? __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0xFFFFFFFFu;
+                if (__ballot(seen < (uint32_t)need) == 0) break;
+                __builtin_amdgcn_s_sleep(1);
+                if (give_up(++spins)) break;
+            }
+            // (the flag loads above are the only ordering needed, see the head of the file; the fence
+            // keeps the compiler from moving row loads above them)
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            int known = need;
+            while (known < L && __ballot(seen < (uint32_t)(known + 1)) == 0) ++known;
+            return known;
+        };
+        int have = L;                             // (this wave's sources; only rows of at most 16 entries are followed layer by layer)
         if constexpr (WIDE) {
             // 512 / tile_rows lanes per gate, each watching every (512 / tile_rows)-th entry of its row
             const int LR = FLOW_THREADS / p.tile_rows;
@@ -430,18 +454,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
             // the previous tile, or is fetched now; the 16 lanes of a gate sit in one wave)
             if (!have_next && sub < AWN) entbuf[it & 1][arow][sub] = p.ell[apos * AWN + sub];
             const uint32_t e = sub < AWN ? entbuf[it & 1][arow][sub] : DG4_ELL_PAD;
-            const bool watch = e != DG4_ELL_PAD && (e >> 30) != 0;
-            const uint32_t* f = p.flags + (watch ? (e & 0x3FFFFFFFu) : 0u);
-            uint32_t spins = 0;
-            for (;;) {
-                const bool ok = !watch || __hip_atomic_load(f, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0u;
-                if (__ballot(!ok) == 0) break;
-                __builtin_amdgcn_s_sleep(1);
-                if (give_up(++spins)) break;
-            }
-            // (the flag loads above are the only ordering needed, see the head of the file; the fence
-            // keeps the compiler from moving row loads above them)
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            have = await(e, 1);
         }
         if (TIMERS) __syncthreads();
         lap(1);
@@ -582,6 +595,8 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                     op[0] = oa; op[1] = ob;
                 }
             } else if (attends) {
+                // the sources' K | V of this layer (published layer by layer on deep, narrow circuits)
+                if (have < l + 1) have = await(sub < AWN ? entbuf[it & 1][arow][sub] : DG4_ELL_PAD, l + 1);
                 const T* kvl = (const T*)p.kv + (int64_t)l * p.kv_layer_stride;
                 const T* qrow = qkvbuf + arow * QS;
                 if (l == 0) {                     // this wave's transfers of the gates' own rows have landed
@@ -737,6 +752,18 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
                 cols_of(acc[nb], v);
                 store16_agent(base + (p0 + row) * (2 * D), Piece<T>::pack(v));
             }
+            // Layer by layer (deep, narrow circuits with several layers: a reader can run its first layers while
+            // this tile still projects K | V for the later ones): once K of layer j/2 has been issued, V of the
+            // layer before is a whole group behind. Loads and stores of a wave complete in order, and since
+            // those V stores the wave has issued this group's RING fragment loads and at least one store: with
+            // at most RING operations outstanding they are written through.
+            if (p.layer_flags && (j & 1) == 0 && j >= 2) {
+                __builtin_amdgcn_s_waitcnt(RING == 16 ? 0x4F70 : 0x0F78);        // vmcnt(16) / vmcnt(8)
+                __asm__ volatile("" ::: "memory");
+                __syncthreads();
+                if (!ctl[8] && tid < rows)
+                    __hip_atomic_store(&p.flags[p0 + tid], (uint32_t)(j >> 1), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
         }
         lap(5);
         // ---- publish: every thread's row stores have completed (the ring's loads with them) before the flags go up
@@ -744,7 +771,7 @@ __global__ __launch_bounds__(FLOW_THREADS) void flow_kernel(dg4_flow_args p)
         __asm__ volatile("" ::: "memory");
         __syncthreads();
         if (ctl[8]) break;                        // an aborted tile publishes nothing
-        if (tid < rows) __hip_atomic_store(&p.flags[p0 + tid], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tid < rows) __hip_atomic_store(&p.flags[p0 + tid], (uint32_t)L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         lap(6);
     }
     if (TIMERS && tid == 0)

@@ -210,6 +210,7 @@ struct dg4_flow_args {
     const uint32_t* ell; int ell_w;        // neighbour rows by position
     int tile_rows;                         // rows wider than 16 entries: most gates of a tile (2, 4, 8 or 16; no pairs)
     int tile_cap;                          // most gates of any tile of this launch: 16 (one block) or 32
+    int layer_flags;                       // a gate's flag goes up layer by layer (its count of stored layers), not once at the end
     const int32_t* order;                  // position -> node id
     const void* x;                         // [n, d] by node id
     const void* qkv_self;                  // [n, 3d] by position: Q | K | V of x (layer 0)
