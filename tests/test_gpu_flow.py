@@ -76,10 +76,11 @@ def test_flow_kernel_without_epilogue():
     assert row_rel_err(to_np(H), H_pl.astype(np.float64)).max() <= 2 * TOL["f32"]
 
 
-@pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {}), ("medium", 12_000, dict(n_layers=2))])
+@pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {}), ("medium", 12_000, dict(n_layers=2)),
+                                                ("small", 4_000, dict(n_layers=4))])
 def test_flow_kernel_schedules_and_resume(name, n_and, over):
-    # dependency-driven tiles, the graph's own levels, Eq. 1 levels or a caller's deeper levelling,
-    # a sweep cut in two: never a different bit
+    # dependency-driven tiles (on narrow circuits with several layers: flags that go up layer by layer), the
+    # graph's own levels, Eq. 1 levels or a caller's deeper levelling, a sweep cut in two: never a different bit
     print(f"flow kernel schedules {name}", flush=True)
     w = make(name, n_and, **over)
     c = w.cfg
