@@ -45,6 +45,9 @@ def run(w, cfg, g, level_begin=0, level_end=None, H0=None, poison=False):
     ("tiny", None, dict(n_layers=3)), ("small", 3000, dict(n_layers=12)),
     ("stress", 30_000, {}), ("stress", 20_000, dict(n_layers=1)), ("medium", 20_000, dict(n_layers=2)),
     ("medium", 10_000, dict(hops=3)), ("stress", 3_000, dict(dtype="f32", hidden=128, heads=4)),
+    # wide, shallow circuits (Eq. 1 depth 4: more than 4096 gates per level): tiles of 32 gates, two of the table's at a time
+    ("stress", 20_000, dict(level_cap=3)), ("stress", 20_000, dict(level_cap=3, hops=2, n_layers=2)),
+    ("stress", 20_000, dict(level_cap=3, dtype="f32", hidden=128, heads=4, n_layers=2)), ("stress", 17_001, dict(level_cap=2, n_layers=1)),
 ])
 def test_flow_kernel_against_oracle_and_level_by_level(name, n_and, over):
     print(f"flow kernel {name} n_and={n_and} {over}", flush=True)
@@ -77,7 +80,7 @@ def test_flow_kernel_without_epilogue():
 
 
 @pytest.mark.parametrize("name,n_and,over", [("small", None, {}), ("stress", 20_000, {}), ("medium", 12_000, dict(n_layers=2)),
-                                                ("small", 4_000, dict(n_layers=4))])
+                                                ("small", 4_000, dict(n_layers=4)), ("stress", 20_000, dict(level_cap=3))])
 def test_flow_kernel_schedules_and_resume(name, n_and, over):
     # dependency-driven tiles (on narrow circuits with several layers: flags that go up layer by layer), the
     # graph's own levels, Eq. 1 levels or a caller's deeper levelling, a sweep cut in two: never a different bit
