@@ -452,6 +452,14 @@ def main():
                             "compulsory_GBps": pcomp / (ms_part * 1e-3) / 1e9,
                             "traffic": measured_traffic("medium_partition_k8_rocprofv3.txt", "flow_kernel")}
         del pr
+        # ... and under the paper's transformer depth as well (Section 4.1: twelve layers): its own configuration
+        pc12 = synth.Config(**{**pc.__dict__, "n_layers": 12})
+        pw12 = synth.make(pc12)                      # (same seed: the same circuit, weights for twelve layers)
+        PX12, PW12 = tensors(pw12, pc12)
+        pr12 = time_layer(pc12, pg, PX12, PW12, 2, 1)
+        out["partition"]["with_12_layers"] = {"step_ms_device": pr12["ms_dev"], "path": path_of(pc12, pg, {}),
+                                              "edges_per_s": pg.nnz * 12 / (pr12["ms_dev"] * 1e-3)}
+        del pw12, PX12, PW12, pr12
         # The ablation without marks (every mini-batch recomputes its gates; one copy per mini-batch
         # and gate), against the same partition with marks. At k = 8 this graph would have 66 copies
         # per gate, so the pair is timed at k = 3, stride 2, mini-batches of 128 cones.
