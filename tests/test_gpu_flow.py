@@ -101,11 +101,13 @@ def test_flow_kernel_schedules_and_resume(name, n_and, over):
     assert torch.equal(H2, H)
 
 
-def test_flow_kernel_bounded_wait_and_packed_weights():
-    # A spin limit of one makes a tile give up on the first unpublished source: the sweep must return,
-    # report it, publish nothing of the abandoned tile, and a normal run afterwards is correct. Then
+@pytest.mark.parametrize("n_layers", [1, 3])
+def test_flow_kernel_bounded_wait_and_packed_weights(n_layers):
+    # A spin limit of one makes a tile give up on the first unpublished source (with several layers on this
+    # narrow circuit: also on a source whose later layers are not in the store yet): the sweep must return,
+    # report it, publish nothing more of the abandoned tile, and a normal run afterwards is correct. Then
     # the packed weights of that run serve a third one.
-    w = make("small")
+    w = make("small", n_layers=n_layers)
     c = w.cfg
     g, og = graphs(w)
     X, W = to_dev(w.x, c.dtype), device_weights(w, c.dtype)
